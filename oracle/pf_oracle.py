@@ -1,0 +1,275 @@
+"""TEST INFRASTRUCTURE -- the unfused fp64 CPU evaluator of a chain of memory-intensive operators.
+
+`evaluate(spec, inputs)` walks the chain operator by operator; every operator is one call into the plain C
+routines of pf_oracle.c and materialises one complete float64 tensor (the unfused program whose
+intermediates the fused kernels keep on chip: paper section 5.1, gOperator merging).  Nothing here is
+shared with the HIP library, and nothing in the product may import this package: only tests, the smoke
+check and the benchmark's CPU-baseline leg do.
+
+`build()` compiles pf_oracle.c with gcc into oracle/libpf_oracle.so (plain C, -O2, OpenMP for the
+row/group loops so the same code can be timed on one core and on all cores).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pf_oracle.c")
+_LIB = os.path.join(_HERE, "libpf_oracle.so")
+_lib = None
+
+_BINARY = {"add": 0, "sub": 1, "mul": 2, "div": 3, "max": 4, "min": 5}
+_UNARY = {"scale": 0, "addc": 1, "neg": 2, "relu": 3, "sigmoid": 4, "silu": 5, "gelu_erf": 6, "tanh": 7,
+          "exp": 8, "rsqrt": 9}
+_REDUCE = {"reduce_sum": 0, "reduce_max": 1, "reduce_mean": 2}
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle.  Returns the path of the shared library."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        i64 = ctypes.c_int64
+        lib.orc_set_threads.argtypes = [ctypes.c_int]
+        lib.orc_max_threads.argtypes = []
+        lib.orc_ew_binary.argtypes = [ctypes.c_int, dp, i64, dp, i64, dp]
+        lib.orc_ew_unary.argtypes = [ctypes.c_int, dp, i64, ctypes.c_double, dp]
+        lib.orc_causal_mask.argtypes = [dp, i64, i64, i64, dp]
+        lib.orc_reduce_last.argtypes = [ctypes.c_int, dp, i64, i64, dp]
+        lib.orc_row_broadcast_binary.argtypes = [ctypes.c_int, dp, i64, i64, dp, dp]
+        lib.orc_softmax_last.argtypes = [dp, i64, i64, dp]
+        lib.orc_layernorm_last.argtypes = [dp, i64, i64, dp, dp, ctypes.c_double, dp]
+        lib.orc_rmsnorm_last.argtypes = [dp, i64, i64, dp, ctypes.c_double, dp]
+        lib.orc_groupnorm_nhwc.argtypes = [dp, i64, i64, i64, i64, dp, dp, ctypes.c_double, dp]
+        lib.orc_permute_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(i64),
+                                          ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def set_threads(n: int) -> int:
+    return _load().orc_set_threads(int(n))
+
+
+def max_threads() -> int:
+    return _load().orc_max_threads()
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"oracle: {what} failed with code {rc}")
+
+
+def _is_trailing(small: Sequence[int], big: Sequence[int]) -> bool:
+    small = tuple(small)
+    while small and small[0] == 1:
+        small = small[1:]
+    return len(small) <= len(big) and tuple(big[len(big) - len(small):]) == small
+
+
+# ---- one function per operator ---------------------------------------------------------------
+
+def ew_binary(name: str, a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    a, b = _f64(a), _f64(b)
+    if a.size >= b.size:
+        if not _is_trailing(b.shape, a.shape):
+            raise ValueError(f"oracle: cannot broadcast {b.shape} over {a.shape}")
+        shape = a.shape
+    else:
+        if not _is_trailing(a.shape, b.shape):
+            raise ValueError(f"oracle: cannot broadcast {a.shape} over {b.shape}")
+        shape = b.shape
+    out = np.empty(shape, dtype=np.float64)
+    _check(_load().orc_ew_binary(_BINARY[name], _p(a), a.size, _p(b), b.size, _p(out)), name)
+    return out
+
+
+def ew_unary(name: str, x: np.ndarray, alpha: float = 0.0) -> np.ndarray:
+    x = _f64(x)
+    out = np.empty_like(x)
+    _check(_load().orc_ew_unary(_UNARY[name], _p(x), x.size, float(alpha), _p(out)), name)
+    return out
+
+
+def silu_decomposed(x: np.ndarray) -> np.ndarray:
+    """SiLU as the two basic operators it is split into: a sigmoid, then a multiply (section 6)."""
+    return ew_binary("mul", x, ew_unary("sigmoid", x))
+
+
+def causal_mask(x: np.ndarray) -> np.ndarray:
+    x = _f64(x)
+    if x.ndim < 2:
+        raise ValueError("oracle: causal_mask needs rank >= 2")
+    si, sj = x.shape[-2], x.shape[-1]
+    outer = x.size // (si * sj)
+    out = np.empty_like(x)
+    _check(_load().orc_causal_mask(_p(x), outer, si, sj, _p(out)), "causal_mask")
+    return out
+
+
+def reduce_last(name: str, x: np.ndarray) -> np.ndarray:
+    x = _f64(x)
+    n = x.shape[-1]
+    rows = x.size // n
+    out = np.empty(x.shape[:-1] + (1,), dtype=np.float64)
+    _check(_load().orc_reduce_last(_REDUCE[name], _p(x), rows, n, _p(out)), name)
+    return out
+
+
+def softmax(x: np.ndarray) -> np.ndarray:
+    x = _f64(x)
+    n = x.shape[-1]
+    out = np.empty_like(x)
+    _check(_load().orc_softmax_last(_p(x), x.size // n, n, _p(out)), "softmax")
+    return out
+
+
+def layernorm(x: np.ndarray, gamma, beta, eps: float) -> np.ndarray:
+    x = _f64(x)
+    n = x.shape[-1]
+    g = None if gamma is None else _f64(gamma).reshape(-1)
+    b = None if beta is None else _f64(beta).reshape(-1)
+    for v in (g, b):
+        if v is not None and v.size != n:
+            raise ValueError("oracle: layernorm parameter size")
+    out = np.empty_like(x)
+    _check(_load().orc_layernorm_last(_p(x), x.size // n, n, None if g is None else _p(g),
+                                      None if b is None else _p(b), float(eps), _p(out)), "layernorm")
+    return out
+
+
+def rmsnorm(x: np.ndarray, gamma, eps: float) -> np.ndarray:
+    x = _f64(x)
+    n = x.shape[-1]
+    g = None if gamma is None else _f64(gamma).reshape(-1)
+    if g is not None and g.size != n:
+        raise ValueError("oracle: rmsnorm parameter size")
+    out = np.empty_like(x)
+    _check(_load().orc_rmsnorm_last(_p(x), x.size // n, n, None if g is None else _p(g), float(eps),
+                                    _p(out)), "rmsnorm")
+    return out
+
+
+def groupnorm_nhwc(x: np.ndarray, gamma, beta, groups: int, eps: float) -> np.ndarray:
+    """x is channels-last: [N, spatial..., C]."""
+    x = _f64(x)
+    if x.ndim < 2:
+        raise ValueError("oracle: groupnorm needs rank >= 2")
+    nb, c = x.shape[0], x.shape[-1]
+    hw = x.size // (nb * c)
+    g = None if gamma is None else _f64(gamma).reshape(-1)
+    b = None if beta is None else _f64(beta).reshape(-1)
+    for v in (g, b):
+        if v is not None and v.size != c:
+            raise ValueError("oracle: groupnorm parameter size")
+    out = np.empty_like(x)
+    _check(_load().orc_groupnorm_nhwc(_p(x), nb, hw, c, int(groups), None if g is None else _p(g),
+                                      None if b is None else _p(b), float(eps), _p(out)), "groupnorm")
+    return out
+
+
+def permute(x: np.ndarray, perm: Sequence[int]) -> np.ndarray:
+    """Works on any fixed-size dtype; the elements are moved as raw bytes."""
+    x = np.ascontiguousarray(x)
+    rank = x.ndim
+    if len(perm) != rank:
+        raise ValueError("oracle: permutation rank")
+    shape = (ctypes.c_int64 * rank)(*x.shape)
+    pm = (ctypes.c_int32 * rank)(*[int(p) for p in perm])
+    out = np.empty(tuple(x.shape[p] for p in perm), dtype=x.dtype)
+    _check(_load().orc_permute_bytes(x.ctypes.data, rank, shape, pm, x.dtype.itemsize, out.ctypes.data),
+           "permute")
+    return out
+
+
+def reshape(x: np.ndarray, shape: Sequence[int]) -> np.ndarray:
+    x = np.ascontiguousarray(x)
+    if int(np.prod(shape, dtype=np.int64)) != x.size:
+        raise ValueError("oracle: reshape size")
+    return x.reshape(tuple(int(s) for s in shape)).copy()
+
+
+# ---- the chain walker ------------------------------------------------------------------------
+
+def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
+    name = op.name
+    a = [vals[s] for s in op.src]
+    if name in _BINARY:
+        return ew_binary(name, a[0], a[1])
+    if name in ("scale", "addc"):
+        return ew_unary(name, a[0], op.f[0])
+    if name in _UNARY:
+        return ew_unary(name, a[0])
+    if name == "causal_mask":
+        return causal_mask(a[0])
+    if name in _REDUCE:
+        return reduce_last(name, a[0])
+    if name == "softmax":
+        return softmax(a[0])
+    if name == "layernorm":
+        return layernorm(a[0], a[1], a[2], op.f[0])
+    if name == "rmsnorm":
+        return rmsnorm(a[0], a[1], op.f[0])
+    if name == "groupnorm":
+        return groupnorm_nhwc(a[0], a[1], a[2], op.i[0], op.f[0])
+    if name == "permute":
+        return permute(a[0], op.i)
+    if name == "reshape":
+        return reshape(a[0], op.i)
+    raise KeyError(f"oracle: unknown op {name}")
+
+
+def evaluate(spec, inputs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Evaluate the chain on float64 inputs.  Returns every value (inputs first, then one per op)."""
+    if len(inputs) != len(spec.inputs):
+        raise ValueError("oracle: wrong number of inputs")
+    vals: List[np.ndarray] = []
+    for (_, shape), t in zip(spec.inputs, inputs):
+        arr = _f64(t)
+        if tuple(arr.shape) != tuple(shape):
+            raise ValueError(f"oracle: input shape {arr.shape} != declared {shape}")
+        vals.append(arr)
+    for op in spec.ops:
+        vals.append(_eval_op(op, vals))
+    return vals
+
+
+def evaluate_outputs(spec, inputs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    vals = evaluate(spec, inputs)
+    return [vals[v] for v, _ in spec.outputs]
+
+
+def evaluate_layout_bits(spec, inputs_bits: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Chains made only of permute / reshape, evaluated on raw bit patterns (unsigned integer arrays)."""
+    vals = [np.ascontiguousarray(t) for t in inputs_bits]
+    for op in spec.ops:
+        if op.name == "permute":
+            vals.append(permute(vals[op.src[0]], op.i))
+        elif op.name == "reshape":
+            vals.append(reshape(vals[op.src[0]], op.i))
+        else:
+            raise ValueError("oracle: evaluate_layout_bits accepts only permute and reshape")
+    return [vals[v] for v, _ in spec.outputs]

@@ -1,0 +1,384 @@
+"""Pins for the CPU oracle: closed forms, invariants, brute-force tiny cases, hand-expanded fixtures and
+library routines.  None of the expected values comes from the oracle itself or from the HIP path.
+
+What the method computes is the unfused operator-by-operator result (paper section 5.1: merging removes
+data movement only; section 5.2: rewriting never changes the program's meaning); the paper gives no
+operator formulas or worked examples, so the pins are the operators' textbook definitions.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pf_oracle as orc
+import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def load_fixture(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, _, rest = line.partition(":")
+            out[key.strip()] = np.array([float(v) for v in rest.split()], dtype=np.float64)
+    return out
+
+
+# ---------------- hand-expanded fixtures ----------------
+
+def test_fixture_layernorm_2x4():
+    fx = load_fixture("layernorm_2x4.txt")
+    x = fx["x"].reshape(2, 4)
+    plain = orc.layernorm(x, None, None, fx["eps"][0])
+    np.testing.assert_allclose(plain.ravel(), fx["normalised"], rtol=0, atol=1e-15)
+    y = orc.layernorm(x, fx["gamma"], fx["beta"], fx["eps"][0])
+    np.testing.assert_allclose(y.ravel(), fx["y"], rtol=0, atol=2e-15)
+
+
+def test_fixture_causal_softmax_3x3():
+    fx = load_fixture("causal_softmax_3x3.txt")
+    spec = wl.ChainSpec(inputs=[("f32", (1, 3, 3))])
+    v = spec.op("scale", 0, f=[fx["scale"][0]])
+    v = spec.op("causal_mask", v)
+    v = spec.op("softmax", v)
+    spec.out(v, "f32")
+    (y,) = orc.evaluate_outputs(spec, [fx["x"].reshape(1, 3, 3)])
+    np.testing.assert_allclose(y.ravel(), fx["y"], rtol=0, atol=1e-15)
+    # masked entries are exactly zero, not merely small
+    assert y[0, 0, 1] == 0.0 and y[0, 0, 2] == 0.0 and y[0, 1, 2] == 0.0
+
+
+def test_fixture_groupnorm_tiny():
+    fx = load_fixture("groupnorm_1x2x2x4_g2.txt")
+    x = fx["x"].reshape(1, 2, 2, 4)
+    plain = orc.groupnorm_nhwc(x, None, None, int(fx["groups"][0]), fx["eps"][0])
+    np.testing.assert_allclose(plain.ravel(), fx["normalised"], rtol=0, atol=2e-15)
+    y = orc.groupnorm_nhwc(x, fx["gamma"], fx["beta"], int(fx["groups"][0]), fx["eps"][0])
+    np.testing.assert_allclose(y.ravel(), fx["y"], rtol=0, atol=4e-15)
+
+
+def test_fixture_permute_iota():
+    fx = load_fixture("permute_2x3x2x2.txt")
+    shape = tuple(int(v) for v in fx["shape"])
+    perm = [int(v) for v in fx["perm"]]
+    x = np.arange(int(np.prod(shape)), dtype=np.float64).reshape(shape)
+    out = orc.permute(x, perm)
+    assert out.shape == (2, 2, 3, 2)
+    np.testing.assert_array_equal(out.ravel(), fx["out"])
+
+
+def test_fixture_activation_points():
+    fx = load_fixture("gelu_silu_points.txt")
+    for name in ("sigmoid", "silu", "gelu_erf", "tanh"):
+        got = orc.ew_unary(name, fx["x"])
+        np.testing.assert_allclose(got, fx[name], rtol=4e-16, atol=1e-16, err_msg=name)
+
+
+# ---------------- element-wise and broadcast ----------------
+
+def test_binary_operand_order_and_broadcast_direction():
+    a = np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]])
+    v = np.array([10.0, 20.0, 40.0])
+    np.testing.assert_array_equal(orc.ew_binary("sub", a, v), [[-9, -18, -37], [-6, -15, -34]])
+    np.testing.assert_array_equal(orc.ew_binary("sub", v, a), [[9, 18, 37], [6, 15, 34]])
+    np.testing.assert_array_equal(orc.ew_binary("div", v, a), [[10, 10, 40 / 3], [2.5, 4, 40 / 6]])
+    np.testing.assert_array_equal(orc.ew_binary("div", a, v), [[0.1, 0.1, 3 / 40], [0.4, 0.25, 6 / 40]])
+    np.testing.assert_array_equal(orc.ew_binary("max", a, v * 0 + 3.5), [[3.5, 3.5, 3.5], [4, 5, 6]])
+    np.testing.assert_array_equal(orc.ew_binary("min", a, v * 0 + 3.5), [[1, 2, 3], [3.5, 3.5, 3.5]])
+    np.testing.assert_array_equal(orc.ew_binary("mul", a, v), [[10, 40, 120], [40, 100, 240]])
+    np.testing.assert_array_equal(orc.ew_binary("add", a, v), [[11, 22, 43], [14, 25, 46]])
+
+
+def test_broadcast_is_over_leading_dims_only():
+    a = np.zeros((2, 3, 4))
+    tail = np.arange(12.0).reshape(3, 4)
+    out = orc.ew_binary("add", a, tail)
+    for b in range(2):
+        np.testing.assert_array_equal(out[b], tail)
+    with pytest.raises(ValueError):
+        orc.ew_binary("add", a, np.zeros((2, 3)))      # [2,3] is not a trailing shape of [2,3,4]
+    with pytest.raises(ValueError):
+        orc.ew_binary("add", a, np.zeros((3,)))
+
+
+def test_binary_matches_numpy_on_random():
+    g = np.random.default_rng(7)
+    a = g.standard_normal((5, 6, 7))
+    b = g.standard_normal((6, 7)) + 3.0
+    for name, fn in (("add", np.add), ("sub", np.subtract), ("mul", np.multiply), ("div", np.divide),
+                     ("max", np.maximum), ("min", np.minimum)):
+        np.testing.assert_array_equal(orc.ew_binary(name, a, b), fn(a, b), err_msg=name)
+        np.testing.assert_array_equal(orc.ew_binary(name, b, a), fn(b, a), err_msg=name + " swapped")
+
+
+def test_unary_simple_ops():
+    x = np.array([-2.0, -0.0, 0.5, 4.0])
+    np.testing.assert_array_equal(orc.ew_unary("scale", x, -3.0), [6.0, 0.0, -1.5, -12.0])
+    np.testing.assert_array_equal(orc.ew_unary("addc", x, 1.25), [-0.75, 1.25, 1.75, 5.25])
+    np.testing.assert_array_equal(orc.ew_unary("neg", x), [2.0, 0.0, -0.5, -4.0])
+    np.testing.assert_array_equal(orc.ew_unary("relu", x), [0.0, 0.0, 0.5, 4.0])
+    np.testing.assert_allclose(orc.ew_unary("rsqrt", np.array([4.0, 0.25, 16.0])), [0.5, 2.0, 0.25], rtol=0,
+                               atol=0)
+    np.testing.assert_allclose(orc.ew_unary("exp", np.array([0.0, 1.0, -1.0])), [1.0, math.e, 1 / math.e],
+                               rtol=1e-16)
+
+
+def test_activation_identities():
+    x = np.linspace(-6, 6, 97)
+    gelu = orc.ew_unary("gelu_erf", x)
+    silu = orc.ew_unary("silu", x)
+    np.testing.assert_allclose(gelu - orc.ew_unary("gelu_erf", -x), x, atol=1e-15)     # odd part is x/2 * 2
+    np.testing.assert_allclose(silu - orc.ew_unary("silu", -x), x, atol=1e-15)
+    assert orc.ew_unary("gelu_erf", np.zeros(1))[0] == 0.0 and orc.ew_unary("silu", np.zeros(1))[0] == 0.0
+    sig = orc.ew_unary("sigmoid", x)
+    np.testing.assert_allclose(sig + orc.ew_unary("sigmoid", -x), 1.0, atol=1e-15)
+    np.testing.assert_allclose(orc.ew_unary("tanh", x), 2 * orc.ew_unary("sigmoid", 2 * x) - 1, atol=1e-15)
+    # composite == decomposition into sigmoid and multiply (section 6)
+    np.testing.assert_allclose(orc.silu_decomposed(x), silu, rtol=0, atol=0)
+
+
+def test_activations_match_torch_float64():
+    g = np.random.default_rng(11)
+    x = 3 * g.standard_normal(1000)
+    t = torch.from_numpy(x)
+    np.testing.assert_allclose(orc.ew_unary("gelu_erf", x), torch.nn.functional.gelu(t).numpy(), atol=1e-15)
+    np.testing.assert_allclose(orc.ew_unary("silu", x), torch.nn.functional.silu(t).numpy(), atol=1e-15)
+    np.testing.assert_allclose(orc.ew_unary("sigmoid", x), torch.sigmoid(t).numpy(), atol=1e-15)
+
+
+# ---------------- causal mask ----------------
+
+def test_causal_mask_brute_force():
+    g = np.random.default_rng(3)
+    x = g.standard_normal((2, 3, 4, 6))
+    y = orc.causal_mask(x)
+    for idx in np.ndindex(*x.shape):
+        i, j = idx[-2], idx[-1]
+        if j > i:
+            assert y[idx] == -np.inf
+        else:
+            assert y[idx] == x[idx]
+
+
+# ---------------- reductions ----------------
+
+def test_reduce_last():
+    x = np.array([[1.0, 5.0, -2.0, 0.0], [7.0, 7.0, 7.0, 7.0], [-1.0, -3.0, -2.0, -8.0]])
+    np.testing.assert_array_equal(orc.reduce_last("reduce_sum", x), [[4.0], [28.0], [-14.0]])
+    np.testing.assert_array_equal(orc.reduce_last("reduce_max", x), [[5.0], [7.0], [-1.0]])
+    np.testing.assert_array_equal(orc.reduce_last("reduce_mean", x), [[1.0], [7.0], [-3.5]])
+    g = np.random.default_rng(5)
+    y = g.standard_normal((3, 4, 33))
+    np.testing.assert_allclose(orc.reduce_last("reduce_sum", y)[..., 0], y.sum(-1), atol=1e-13)
+    np.testing.assert_array_equal(orc.reduce_last("reduce_max", y)[..., 0], y.max(-1))
+
+
+# ---------------- softmax ----------------
+
+def test_softmax_closed_forms():
+    n = 9
+    x = np.log(np.arange(1, n + 1, dtype=np.float64))[None, :]
+    np.testing.assert_allclose(orc.softmax(x)[0], np.arange(1, n + 1) / (n * (n + 1) / 2), atol=1e-15)
+    # constant row under a causal mask: row i is 1/(i+1) on j <= i
+    s = 7
+    y = orc.softmax(orc.causal_mask(np.full((1, s, s), 3.25)))
+    for i in range(s):
+        np.testing.assert_allclose(y[0, i, : i + 1], 1.0 / (i + 1), atol=1e-16)
+        assert np.all(y[0, i, i + 1:] == 0.0)
+    assert y[0, 0, 0] == 1.0
+
+
+def test_softmax_invariants():
+    g = np.random.default_rng(21)
+    x = 4 * g.standard_normal((6, 5, 40))
+    y = orc.softmax(x)
+    assert np.all(y >= 0) and np.all(y <= 1)
+    np.testing.assert_allclose(y.sum(-1), 1.0, atol=1e-12)
+    np.testing.assert_allclose(orc.softmax(x + 123.5), y, atol=1e-13)            # shift invariance
+    np.testing.assert_allclose(y, torch.softmax(torch.from_numpy(x), -1).numpy(), atol=1e-15)
+    # ratios are exp of differences
+    np.testing.assert_allclose(y[..., 3] / y[..., 7], np.exp(x[..., 3] - x[..., 7]), rtol=1e-12)
+
+
+def test_softmax_fully_masked_row_is_nan():
+    y = orc.softmax(np.full((1, 4), -np.inf))
+    assert np.all(np.isnan(y))
+
+
+def test_softmax_large_values_do_not_overflow():
+    y = orc.softmax(np.array([[1000.0, 1000.0, -1000.0]]))
+    np.testing.assert_allclose(y[0], [0.5, 0.5, 0.0], atol=1e-300)
+
+
+# ---------------- LayerNorm / RMSNorm ----------------
+
+def test_layernorm_closed_forms():
+    n = 12
+    x = np.arange(n, dtype=np.float64)[None, :]
+    eps = 0.5
+    var = (n * n - 1) / 12.0
+    want = (x[0] - (n - 1) / 2.0) / math.sqrt(var + eps)
+    np.testing.assert_allclose(orc.layernorm(x, None, None, eps)[0], want, atol=1e-15)
+
+
+def test_layernorm_invariants():
+    g = np.random.default_rng(31)
+    x = 2 * g.standard_normal((17, 96)) + 5.0
+    eps = 1e-5
+    y = orc.layernorm(x, None, None, eps)
+    np.testing.assert_allclose(y.mean(-1), 0.0, atol=1e-12)
+    var = x.var(-1)                                        # numpy: biased
+    np.testing.assert_allclose(y.var(-1), var / (var + eps), rtol=1e-12)     # exactly sigma^2/(sigma^2+eps)
+    np.testing.assert_allclose(orc.layernorm(x + 77.0, None, None, eps), y, atol=1e-12)
+    gamma = g.standard_normal(96)
+    beta = g.standard_normal(96)
+    np.testing.assert_allclose(orc.layernorm(x, gamma, beta, eps), y * gamma + beta, atol=1e-14)
+    t = torch.nn.functional.layer_norm(torch.from_numpy(x), (96,), torch.from_numpy(gamma),
+                                       torch.from_numpy(beta), eps)
+    np.testing.assert_allclose(orc.layernorm(x, gamma, beta, eps), t.numpy(), atol=1e-13)
+
+
+def test_layernorm_uses_biased_variance():
+    x = np.array([[0.0, 2.0]])                            # mean 1, biased var 1, unbiased var 2
+    np.testing.assert_allclose(orc.layernorm(x, None, None, 0.0)[0], [-1.0, 1.0], atol=1e-16)
+
+
+def test_rmsnorm():
+    x = np.array([[3.0, -4.0, 0.0, 0.0]])                 # mean square 25/4
+    np.testing.assert_allclose(orc.rmsnorm(x, None, 0.0)[0], [1.2, -1.6, 0.0, 0.0], atol=1e-16)
+    np.testing.assert_allclose(orc.rmsnorm(x, np.array([1.0, 2.0, 3.0, 4.0]), 0.0)[0], [1.2, -3.2, 0, 0],
+                               atol=1e-16)
+    g = np.random.default_rng(41)
+    z = g.standard_normal((9, 64))
+    z -= z.mean(-1, keepdims=True)                         # zero-mean rows: RMSNorm == LayerNorm (beta = 0)
+    gamma = g.standard_normal(64)
+    np.testing.assert_allclose(orc.rmsnorm(z, gamma, 1e-6), orc.layernorm(z, gamma, None, 1e-6), atol=1e-13)
+    eps = 0.25
+    w = g.standard_normal((4, 10))
+    np.testing.assert_allclose(orc.rmsnorm(w, None, eps), w / np.sqrt((w * w).mean(-1, keepdims=True) + eps),
+                               atol=1e-15)
+
+
+# ---------------- GroupNorm ----------------
+
+def test_groupnorm_one_group_is_layernorm_of_flattened_sample():
+    g = np.random.default_rng(51)
+    x = g.standard_normal((3, 4, 5, 6)) + 2.0
+    y = orc.groupnorm_nhwc(x, None, None, 1, 1e-5)
+    want = orc.layernorm(x.reshape(3, -1), None, None, 1e-5).reshape(x.shape)
+    np.testing.assert_allclose(y, want, atol=1e-13)
+
+
+def test_groupnorm_two_independent_paths_and_torch():
+    g = np.random.default_rng(52)
+    n, h, w, c, groups = 2, 3, 5, 12, 3
+    x = g.standard_normal((n, h, w, c)) + g.uniform(-2, 2, c)
+    gamma, beta = g.standard_normal(c), g.standard_normal(c)
+    eps = 1e-5
+    y = orc.groupnorm_nhwc(x, gamma, beta, groups, eps)
+    # path 2: to channels-first, contiguous groups normalised as rows, back to channels-last
+    xc = orc.permute(x, [0, 3, 1, 2])                                      # [n, c, h, w]
+    rows = xc.reshape(n * groups, (c // groups) * h * w)
+    norm = orc.layernorm(rows, None, None, eps).reshape(n, c, h, w)
+    norm = norm * gamma[None, :, None, None] + beta[None, :, None, None]
+    want = orc.permute(norm, [0, 2, 3, 1])
+    np.testing.assert_allclose(y, want, atol=1e-13)
+    t = torch.nn.functional.group_norm(torch.from_numpy(x).permute(0, 3, 1, 2), groups,
+                                       torch.from_numpy(gamma), torch.from_numpy(beta), eps)
+    np.testing.assert_allclose(y, t.permute(0, 2, 3, 1).numpy(), atol=1e-13)
+
+
+def test_groupnorm_invariants():
+    g = np.random.default_rng(53)
+    n, hw, c, groups = 2, 7, 8, 4
+    x = g.standard_normal((n, hw, c)) * 3 + 1
+    eps = 1e-3
+    y = orc.groupnorm_nhwc(x, None, None, groups, eps)
+    yy = y.reshape(n, hw, groups, c // groups)
+    xx = x.reshape(n, hw, groups, c // groups)
+    np.testing.assert_allclose(yy.mean(axis=(1, 3)), 0.0, atol=1e-13)
+    var = xx.var(axis=(1, 3))
+    np.testing.assert_allclose(yy.var(axis=(1, 3)), var / (var + eps), rtol=1e-12)
+
+
+# ---------------- permute / reshape ----------------
+
+def test_permute_matches_numpy_and_inverse_is_identity():
+    g = np.random.default_rng(61)
+    x = g.standard_normal((2, 3, 4, 5, 6))
+    for perm in ([0, 1, 2, 3, 4], [4, 3, 2, 1, 0], [0, 2, 1, 4, 3], [3, 0, 4, 1, 2]):
+        y = orc.permute(x, perm)
+        np.testing.assert_array_equal(y, np.transpose(x, perm))
+        inv = np.argsort(perm)
+        np.testing.assert_array_equal(orc.permute(y, inv), x)
+
+
+def test_permute_raw_bits_exact():
+    g = np.random.default_rng(62)
+    bits = g.integers(0, 1 << 16, size=(3, 4, 5, 2), dtype=np.uint16)       # includes NaN / inf patterns
+    out = orc.permute(bits, [0, 2, 1, 3])
+    assert out.dtype == np.uint16
+    np.testing.assert_array_equal(out, np.transpose(bits, [0, 2, 1, 3]))
+    bits32 = g.integers(0, 1 << 32, size=(4, 6), dtype=np.uint32)
+    np.testing.assert_array_equal(orc.permute(bits32, [1, 0]), bits32.T)
+
+
+def test_elementwise_commutes_with_permute():
+    # moving element-wise work across a layout change must not change a single bit (section 5.1, swapping)
+    g = np.random.default_rng(63)
+    x = g.standard_normal((3, 4, 5))
+    a = orc.ew_unary("gelu_erf", orc.permute(x, [2, 0, 1]))
+    b = orc.permute(orc.ew_unary("gelu_erf", x), [2, 0, 1])
+    np.testing.assert_array_equal(a, b)
+
+
+# ---------------- chain walker ----------------
+
+def test_chain_walker_composite_equals_primitives():
+    # softmax written with the composite op and with reduce / broadcast primitives evaluated by hand
+    g = np.random.default_rng(71)
+    x = g.standard_normal((4, 10))
+    m = orc.reduce_last("reduce_max", x)
+    e = orc.ew_unary("exp", x - m)
+    want = e / orc.reduce_last("reduce_sum", e)
+    np.testing.assert_allclose(orc.softmax(x), want, rtol=0, atol=0)
+
+
+def test_chain_walker_c1_against_numpy_formula():
+    spec, ins = wl.c1_bias_res_layernorm_gelu(rows=5, n=24)
+    x, res, bias, gamma, beta = [wl.widen(t) for t in ins]
+    (y,) = orc.evaluate_outputs(spec, [x, res, bias, gamma, beta])
+    z = (x + res) + bias
+    mu = z.mean(-1, keepdims=True)
+    var = ((z - mu) ** 2).mean(-1, keepdims=True)
+    ln = (z - mu) / np.sqrt(var + 1e-5) * gamma + beta
+    want = np.array([[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row] for row in ln])
+    np.testing.assert_allclose(y, want, atol=1e-14)
+
+
+def test_chain_walker_c4_and_c5_shapes():
+    spec, ins = wl.c4_bias_scale_permute(b=2, s=3, h=2, d=8)
+    (y,) = orc.evaluate_outputs(spec, [wl.widen(t) for t in ins])
+    q, bias = [wl.widen(t) for t in ins]
+    assert y.shape == (2, 2, 3, 8)
+    np.testing.assert_array_equal(y, np.transpose((q + bias) * 0.125, (0, 2, 1, 3)))
+    spec, ins = wl.c5_groupnorm_silu(n=1, h=2, w=2, ch=8, groups=2)
+    (y,) = orc.evaluate_outputs(spec, [wl.widen(t) for t in ins])
+    assert y.shape == (1, 2, 2, 8)
+
+
+def test_thread_count_does_not_change_results():
+    spec, ins = wl.c3_bias_res_layernorm(rows=64, n=128)
+    wide = [wl.widen(t) for t in ins]
+    orc.set_threads(1)
+    (a,) = orc.evaluate_outputs(spec, wide)
+    orc.set_threads(4)
+    (b,) = orc.evaluate_outputs(spec, wide)
+    orc.set_threads(orc.max_threads())
+    np.testing.assert_array_equal(a, b)

@@ -1,0 +1,202 @@
+"""Chain descriptions and seeded synthetic inputs shared by the tests, the benchmark and the smoke check.
+
+This module holds *no arithmetic of the method*: it only says which operators a chain consists of
+(names, operand ids, attributes), draws the random input tensors and quantises them to their storage
+dtype.  The CPU oracle and the HIP library each interpret a :class:`ChainSpec` with code of their own.
+
+Chain vocabulary: the four basic operator kinds a memory-intensive subgraph is split into
+(element-wise, broadcast, reduce, transpose; paper section 6, "GIR-Graph generation"), with the
+composite operators (softmax, the normalisations, SiLU, GELU) kept as named ops as well, so a chain can
+be written either way.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+import torch
+
+DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+# op name -> number of operands.  Binary element-wise ops broadcast a lower-rank operand over the
+# leading dimensions of the other one (its shape must equal the trailing dimensions).
+OP_ARITY: Dict[str, int] = {
+    "add": 2, "sub": 2, "mul": 2, "div": 2, "max": 2, "min": 2,
+    "scale": 1, "addc": 1, "neg": 1, "relu": 1, "sigmoid": 1, "silu": 1, "gelu_erf": 1,
+    "tanh": 1, "exp": 1, "rsqrt": 1,
+    "causal_mask": 1,
+    "reduce_sum": 1, "reduce_max": 1, "reduce_mean": 1,
+    "softmax": 1, "layernorm": 3, "rmsnorm": 2, "groupnorm": 3,
+    "permute": 1, "reshape": 1,
+}
+
+
+@dataclass
+class OpSpec:
+    name: str
+    src: Tuple[int, ...]               # value ids: 0..n_inputs-1 are inputs, n_inputs+k is the result of op k
+    f: Tuple[float, ...] = ()          # float attributes (scale factor, constant, eps)
+    i: Tuple[int, ...] = ()            # integer attributes (permutation, new shape, group count)
+
+
+@dataclass
+class ChainSpec:
+    inputs: List[Tuple[str, Tuple[int, ...]]]          # (dtype name, shape) per input, contiguous row-major
+    ops: List[OpSpec] = field(default_factory=list)
+    outputs: List[Tuple[int, str]] = field(default_factory=list)   # (value id, dtype name)
+
+    # small builder helpers (bookkeeping only)
+    def op(self, name: str, *src: int, f: Sequence[float] = (), i: Sequence[int] = ()) -> int:
+        if name not in OP_ARITY:
+            raise KeyError(name)
+        self.ops.append(OpSpec(name, tuple(int(s) for s in src), tuple(float(x) for x in f),
+                               tuple(int(x) for x in i)))
+        return len(self.inputs) + len(self.ops) - 1
+
+    def out(self, value: int, dtype: str) -> None:
+        self.outputs.append((int(value), dtype))
+
+
+def quantise(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """fp32 numpy array -> contiguous CPU torch tensor in the storage dtype (round to nearest even)."""
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(DTYPES[dtype]).contiguous()
+
+
+def widen(t: torch.Tensor) -> np.ndarray:
+    """Storage-dtype tensor (CPU) -> float64 numpy array holding exactly the same values."""
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def raw_bits(t: torch.Tensor) -> np.ndarray:
+    """Bit pattern of a tensor as an unsigned integer array of the same shape (for layout-only checks)."""
+    t = t.detach().cpu().contiguous()
+    view = {2: torch.int16, 4: torch.int32}[t.element_size()]
+    udt = {2: np.uint16, 4: np.uint32}[t.element_size()]
+    return t.view(view).numpy().view(udt)
+
+
+BASE_SEED = 20230704
+
+
+def _rng(k: int, salt: int = 0) -> np.random.Generator:
+    return np.random.default_rng(BASE_SEED + k + 1000 * salt)
+
+
+# ---------------------------------------------------------------------------------------------
+# The five benchmark chains.  Every builder takes the sizes as arguments so the parity tests can run
+# the same chain at sizes the oracle finishes in seconds; the defaults are the full sizes.
+# Tensors are drawn in the order they are listed, as fp32, then cast to the storage dtype.
+# ---------------------------------------------------------------------------------------------
+
+def c1_bias_res_layernorm_gelu(rows: int = 256, n: int = 768, dtype: str = "f32", eps: float = 1e-5,
+                               salt: int = 0):
+    """x + res + bias -> LayerNorm(gamma, beta) -> GELU(erf); x, res [rows, n]; bias, gamma, beta [n]."""
+    g = _rng(1, salt)
+    x = g.standard_normal((rows, n), dtype=np.float32)
+    res = g.standard_normal((rows, n), dtype=np.float32)
+    bias = g.standard_normal(n, dtype=np.float32)
+    gamma = 1.0 + 0.1 * g.standard_normal(n, dtype=np.float32)
+    beta = g.standard_normal(n, dtype=np.float32)
+    c = ChainSpec(inputs=[(dtype, (rows, n)), (dtype, (rows, n)), (dtype, (n,)), (dtype, (n,)), (dtype, (n,))])
+    v = c.op("add", 0, 1)
+    v = c.op("add", v, 2)
+    v = c.op("layernorm", v, 3, 4, f=[eps])
+    v = c.op("gelu_erf", v)
+    c.out(v, dtype)
+    return c, [quantise(t, dtype) for t in (x, res, bias, gamma, beta)]
+
+
+def c2_causal_softmax(b: int = 8, h: int = 12, s: int = 512, dtype: str = "f16", scale: float = 0.125,
+                      sigma: float = 2.0, salt: int = 0, s_k: int | None = None):
+    """scores * scale -> causal mask (j > i -> -inf) -> softmax over the last dim; scores [b, h, s, s_k]."""
+    s_k = s if s_k is None else s_k
+    g = _rng(2, salt)
+    scores = sigma * g.standard_normal((b, h, s, s_k), dtype=np.float32)
+    c = ChainSpec(inputs=[(dtype, (b, h, s, s_k))])
+    v = c.op("scale", 0, f=[scale])
+    v = c.op("causal_mask", v)
+    v = c.op("softmax", v)
+    c.out(v, dtype)
+    return c, [quantise(scores, dtype)]
+
+
+def c3_bias_res_layernorm(rows: int = 16384, n: int = 1024, dtype: str = "f16", eps: float = 1e-5,
+                          salt: int = 0):
+    """x + bias + res -> LayerNorm(gamma, beta); x, res [rows, n]; bias, gamma, beta [n]."""
+    g = _rng(3, salt)
+    x = g.standard_normal((rows, n), dtype=np.float32)
+    res = g.standard_normal((rows, n), dtype=np.float32)
+    bias = g.standard_normal(n, dtype=np.float32)
+    gamma = 1.0 + 0.1 * g.standard_normal(n, dtype=np.float32)
+    beta = g.standard_normal(n, dtype=np.float32)
+    c = ChainSpec(inputs=[(dtype, (rows, n)), (dtype, (rows, n)), (dtype, (n,)), (dtype, (n,)), (dtype, (n,))])
+    v = c.op("add", 0, 2)
+    v = c.op("add", v, 1)
+    v = c.op("layernorm", v, 3, 4, f=[eps])
+    c.out(v, dtype)
+    return c, [quantise(t, dtype) for t in (x, res, bias, gamma, beta)]
+
+
+def c4_bias_scale_permute(b: int = 32, s: int = 512, h: int = 16, d: int = 64, dtype: str = "bf16",
+                          scale: float = 0.125, salt: int = 0):
+    """(Q + bias[h, d]) * scale -> permute [b, s, h, d] -> [b, h, s, d]."""
+    g = _rng(4, salt)
+    q = g.uniform(-1.0, 1.0, (b, s, h, d)).astype(np.float32)
+    bias = g.uniform(-1.0, 1.0, (h, d)).astype(np.float32)
+    c = ChainSpec(inputs=[(dtype, (b, s, h, d)), (dtype, (h, d))])
+    v = c.op("add", 0, 1)
+    v = c.op("scale", v, f=[scale])
+    v = c.op("permute", v, i=[0, 2, 1, 3])
+    c.out(v, dtype)
+    return c, [quantise(q, dtype), quantise(bias, dtype)]
+
+
+def c5_groupnorm_silu(n: int = 16, h: int = 64, w: int = 64, ch: int = 512, groups: int = 32,
+                      dtype: str = "f16", eps: float = 1e-5, salt: int = 0):
+    """GroupNorm(groups, affine) -> SiLU on NHWC x [n, h, w, ch]; gamma, beta [ch]."""
+    g = _rng(5, salt)
+    x = g.standard_normal((n, h, w, ch), dtype=np.float32)
+    off = g.uniform(-2.0, 2.0, ch).astype(np.float32)
+    x = x + off            # one offset per channel, shared over n, h, w
+    gamma = 1.0 + 0.1 * g.standard_normal(ch, dtype=np.float32)
+    beta = g.standard_normal(ch, dtype=np.float32)
+    c = ChainSpec(inputs=[(dtype, (n, h, w, ch)), (dtype, (ch,)), (dtype, (ch,))])
+    v = c.op("groupnorm", 0, 1, 2, f=[eps], i=[groups])
+    v = c.op("silu", v)
+    c.out(v, dtype)
+    return c, [quantise(t, dtype) for t in (x, gamma, beta)]
+
+
+CONFIGS = {
+    "C1": c1_bias_res_layernorm_gelu,
+    "C2": c2_causal_softmax,
+    "C3": c3_bias_res_layernorm,
+    "C4": c4_bias_scale_permute,
+    "C5": c5_groupnorm_silu,
+}
+
+
+def compulsory_bytes(spec: ChainSpec, out_shapes: Sequence[Sequence[int]]) -> int:
+    """Every input once plus every output once, in bytes."""
+    size = {"f32": 4, "f16": 2, "bf16": 2}
+    total = 0
+    for dt, shape in spec.inputs:
+        total += size[dt] * int(np.prod(shape, dtype=np.int64))
+    for (_, dt), shape in zip(spec.outputs, out_shapes):
+        total += size[dt] * int(np.prod(shape, dtype=np.int64))
+    return total
+
+
+def random_tensor(shape, dtype: str, seed: int, dist: str = "normal", scale: float = 1.0) -> torch.Tensor:
+    """Generic seeded tensor for the shape-sweep tests."""
+    g = np.random.default_rng(BASE_SEED * 7 + seed)
+    if dist == "normal":
+        x = scale * g.standard_normal(shape, dtype=np.float32)
+    elif dist == "uniform":
+        x = g.uniform(-scale, scale, shape).astype(np.float32)
+    elif dist == "positive":
+        x = g.uniform(0.25 * scale, scale, shape).astype(np.float32)
+    else:
+        raise ValueError(dist)
+    return quantise(x, dtype)
