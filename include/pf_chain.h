@@ -1,0 +1,209 @@
+/*
+ * pf_chain.h -- C ABI of the fused-chain executor for AMD Instinct MI355X (gfx950).
+ *
+ * The library runs one already-isolated subgraph of memory-intensive operators (a "chain") as a single
+ * HIP kernel: every input is read from HBM once, every output is written once, all intermediates live in
+ * registers and LDS.  This is the run-time half of the method of arXiv 2307.04995: what its optimised
+ * GIR-Graph does on the device after synchronisation insertion, gOperator merging and swapping have
+ * removed the DRAM round trips between operators (sections 4 and 5.1).  The search and the code
+ * generator of the paper are not part of this library; a chain is mapped onto one of a few hand-written
+ * kernel families instead.
+ *
+ * All functions are thread-safe with respect to distinct plans.  No function throws or aborts; every
+ * failure is a pf_status and a thread-local detail string (pf_last_error).  "Device pointer" always
+ * means memory of the plan's device; "host pointer" means ordinary process memory.
+ */
+#ifndef PF_CHAIN_H
+#define PF_CHAIN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PF_CHAIN_VERSION 1u
+#define PF_MAX_RANK 6
+#define PF_MAX_INPUTS 8
+#define PF_MAX_OPS 32
+#define PF_MAX_OUTPUTS 2
+
+typedef enum {
+    PF_OK = 0,
+    PF_ERR_INVALID_ARG = 1, /* null pointer, bad struct_size/version, value id out of range, bad attribute */
+    PF_ERR_SHAPE = 2,       /* shapes do not fit the operator (broadcast, parameter length, permutation)   */
+    PF_ERR_DTYPE = 3,       /* unknown dtype, or a dtype mix the kernels do not implement                  */
+    PF_ERR_UNSUPPORTED = 4, /* valid chain that fits no kernel family; there is no unfused fallback        */
+    PF_ERR_ALIGNMENT = 5,   /* pointer not 16-byte aligned, or innermost extent not a multiple of 16 bytes */
+    PF_ERR_ALIAS = 6,       /* an output overlaps an input in a family that cannot run in place            */
+    PF_ERR_NOMEM = 7,       /* host or device allocation failed                                            */
+    PF_ERR_HIP = 8          /* a HIP runtime call failed; pf_last_error holds hipGetErrorString            */
+} pf_status;
+
+typedef enum { PF_F32 = 0, PF_F16 = 1, PF_BF16 = 2 } pf_dtype;
+
+/*
+ * The fixed operator set: the four basic operator kinds a memory-intensive subgraph is split into
+ * (element-wise, broadcast, reduce, transpose: section 6, "GIR-Graph generation"), plus the usual
+ * composites, which the library treats as one reduce-then-broadcast step.
+ *
+ * Element-wise binary operators take two values; if their shapes differ, the lower-rank one must equal
+ * the trailing dimensions of the other and is broadcast over the leading ones.  Operand order is kept
+ * (SUB = src0 - src1, DIV = src0 / src1).  MAX, MIN and RELU return NaN when an operand is NaN.
+ * All arithmetic is done in fp32 whatever the storage type; results are rounded to the output type once,
+ * on the final store (round to nearest even).
+ */
+typedef enum {
+    /* element-wise, two operands */
+    PF_ADD = 0, PF_SUB = 1, PF_MUL = 2, PF_DIV = 3, PF_MAX = 4, PF_MIN = 5,
+    /* element-wise, one operand */
+    PF_SCALE = 6,       /* x * f[0]                                   */
+    PF_ADDC = 7,        /* x + f[0]                                   */
+    PF_NEG = 8,
+    PF_RELU = 9,
+    PF_SIGMOID = 10,    /* 1 / (1 + exp(-x))                          */
+    PF_SILU = 11,       /* x * sigmoid(x)   (section 6: sigmoid, then multiply) */
+    PF_GELU_ERF = 12,   /* x/2 * (1 + erf(x / sqrt 2))                */
+    PF_TANH = 13,
+    PF_EXP = 14,
+    PF_RSQRT = 15,      /* 1 / sqrt(x)                                */
+    PF_CAUSAL_MASK = 16,/* last two dims (i, j): j > i -> -inf, else x; the mask is implicit, never stored */
+    /* reduce over the last dimension, result keeps that dimension with extent 1 */
+    PF_REDUCE_SUM = 17, PF_REDUCE_MAX = 18, PF_REDUCE_MEAN = 19,
+    /* reduce-then-broadcast composites over the last dimension */
+    PF_SOFTMAX = 20,    /* exp(x - max) / sum exp(x - max); exp(-inf) = 0; an all -inf row gives NaN        */
+    PF_LAYERNORM = 21,  /* src = x, gamma, beta; f[0] = eps; biased variance; (x-mu)/sqrt(var+eps)*g+b      */
+    PF_RMSNORM = 22,    /* src = x, gamma;       f[0] = eps; x / sqrt(mean(x^2)+eps) * gamma                */
+    PF_GROUPNORM = 23,  /* channels-last x [N, spatial.., C]; src = x, gamma, beta; i[0] = groups; f[0]=eps */
+    /* layout */
+    PF_PERMUTE = 24,    /* i[0..rank-1] = perm; output dim k is input dim perm[k]                           */
+    PF_RESHAPE = 25,    /* i[0..n_i-1] = new shape with the same element count; contiguous data is
+                           reinterpreted, nothing moves                                                     */
+    PF_OP_COUNT_ = 26
+} pf_op;
+
+/* A contiguous row-major tensor. */
+typedef struct {
+    int32_t dtype; /* pf_dtype */
+    int32_t rank;  /* 1..PF_MAX_RANK */
+    int64_t shape[PF_MAX_RANK];
+} pf_tensor_desc;
+
+/*
+ * One operator.  Value ids: 0..n_inputs-1 are the chain's inputs, n_inputs+k is the result of ops[k];
+ * an operator may only use ids smaller than its own.
+ */
+typedef struct {
+    int32_t op;     /* pf_op */
+    int32_t n_src;  /* must equal the operator's arity */
+    int32_t src[3];
+    float f[2];
+    int64_t i[PF_MAX_RANK];
+    int32_t n_i;    /* number of meaningful entries of i (rank for PERMUTE / RESHAPE, 1 for GROUPNORM)      */
+} pf_op_desc;
+
+/*
+ * The chain: plain data, owned by the caller, copied by pf_chain_plan.  struct_size must be
+ * sizeof(pf_chain_desc) and version PF_CHAIN_VERSION.
+ */
+typedef struct {
+    uint32_t struct_size, version;
+    int32_t n_inputs;
+    pf_tensor_desc inputs[PF_MAX_INPUTS];
+    int32_t n_ops;
+    pf_op_desc ops[PF_MAX_OPS];
+    int32_t n_outputs;                   /* 1..PF_MAX_OUTPUTS */
+    int32_t out_value[PF_MAX_OUTPUTS];   /* value id of each output (must be an operator result) */
+    int32_t out_dtype[PF_MAX_OUTPUTS];   /* pf_dtype each output is stored in */
+} pf_chain_desc;
+
+/* Kernel family a plan was mapped to.  Families follow the widest synchronisation scope the chain needs
+ * (section 5.1, synchronisation insertion: lane / parallel unit / block / device). */
+typedef enum {
+    PF_FAMILY_ELEMENTWISE = 0, /* lane scope only: values never leave their register                        */
+    PF_FAMILY_ROW = 1,         /* row reduction then broadcast: wave shuffle, LDS when a row spans waves     */
+    PF_FAMILY_GROUP = 2,       /* GroupNorm: a group spans workgroups, partial statistics cross the device   */
+    PF_FAMILY_TRANSPOSE = 3    /* layout change staged through an LDS tile                                   */
+} pf_family;
+
+typedef struct {
+    int32_t family;   /* pf_family */
+    int32_t variant;  /* family-specific: see the PF_VARIANT_* constants */
+    uint32_t grid[3], block[3];
+    uint32_t lds_bytes;
+    uint64_t workspace_bytes;          /* device memory the plan owns */
+    uint64_t compulsory_read_bytes;    /* every input once */
+    uint64_t compulsory_write_bytes;   /* every output once */
+    int32_t n_launches;                /* kernels enqueued per pf_chain_run */
+    int32_t n_micro_ops;               /* element-wise steps the kernel executes per element */
+    int32_t spec_id;                   /* > 0: a statically specialised kernel was chosen; 0: the generic one */
+    int32_t vectors_per_lane;          /* 16-byte vectors each lane keeps in registers */
+} pf_plan_info;
+
+#define PF_VARIANT_EW_FLAT 0          /* element-wise: one 16-byte vector per lane per step                  */
+#define PF_VARIANT_ROW_WAVE 0         /* row family: one 64-lane wave owns a row                             */
+#define PF_VARIANT_ROW_BLOCK 1        /* row family: one workgroup owns a row                                */
+#define PF_VARIANT_GROUP_TWO_PASS 0   /* group family: statistics pass, then normalise pass (re-reads x)     */
+#define PF_VARIANT_GROUP_RESIDENT 1   /* group family: x held in registers across a device-scope exchange    */
+#define PF_VARIANT_T_ROWS 0           /* transpose family: innermost dim kept, 16-byte vectors re-addressed  */
+#define PF_VARIANT_T_LDS_ROWS 1       /* transpose family: innermost dim kept, LDS tile makes both sides long*/
+#define PF_VARIANT_T_LDS_TILE 2       /* transpose family: innermost dim changes, padded LDS tile transposed */
+
+typedef struct pf_plan_s pf_plan; /* opaque plan object, owned by the library */
+
+/*
+ * Check a chain description on the host (no GPU needed): structure, value ids, arities, attributes,
+ * shape compatibility of every operator.  Returns PF_OK or the first problem found.
+ */
+pf_status pf_chain_validate(const pf_chain_desc *desc);
+
+/*
+ * Shape and (for inputs) dtype of any value of the chain (host only).  `value` is a value id.  For
+ * operator results the dtype field is PF_F32, the type intermediates are computed in.  `out` is written
+ * only on success.
+ */
+pf_status pf_chain_infer_shape(const pf_chain_desc *desc, int32_t value, pf_tensor_desc *out);
+
+/*
+ * Map the chain onto a kernel family and fix launch geometry (section 6: the parallelism and tile size of
+ * a GIR template are parameters chosen before code is produced; here they are chosen once per plan).
+ * `device` is a HIP device ordinal.  May allocate plan-owned device workspace; launches no kernel.
+ * On success *out is a new plan the caller must release with pf_chain_plan_destroy.
+ * The environment variable PF_FORCE_VARIANT=<int> overrides the variant choice where that variant is
+ * legal for the chain (for A/B measurements); PF_LOG=1 prints the decision to stderr.
+ */
+pf_status pf_chain_plan(const pf_chain_desc *desc, int32_t device, pf_plan **out);
+
+/* Same as pf_chain_plan but with an explicit variant (-1 = choose automatically). */
+pf_status pf_chain_plan_variant(const pf_chain_desc *desc, int32_t device, int32_t variant, pf_plan **out);
+
+pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
+
+/*
+ * Enqueue the fused kernel on `stream` (a hipStream_t, passed as void*; NULL = the default stream) and
+ * return without waiting.  inputs[k] / outputs[k] are device pointers to contiguous tensors of exactly
+ * the shapes and dtypes of the description, 16-byte aligned, owned by the caller and not retained.
+ * No allocation, no host synchronisation, no host work proportional to tensor size.
+ * An output may be the same buffer as an input of identical shape and dtype in the element-wise, row and
+ * group families (each element is read before it is written by the same lane); the transpose family
+ * returns PF_ERR_ALIAS for any overlap.  A plan with workspace (group family) must not run on two streams
+ * at the same time.
+ */
+pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *const *outputs, void *stream);
+
+void pf_chain_plan_destroy(pf_plan *plan);
+
+const char *pf_status_str(pf_status s);
+const char *pf_last_error(void); /* thread-local, valid until the next failing call on this thread */
+
+/*
+ * Measurement aid, not part of a chain: a plain 16-byte-per-lane device copy of `bytes` bytes
+ * (multiple of 16) from src to dst on `stream`, used to calibrate achievable HBM bandwidth and the
+ * hardware traffic counters against a transfer of known size.
+ */
+pf_status pf_copy_probe(const void *src, void *dst, uint64_t bytes, int32_t variant, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PF_CHAIN_H */

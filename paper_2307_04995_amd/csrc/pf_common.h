@@ -1,0 +1,144 @@
+// Structures shared by the host planner and the device kernels of the fused-chain library.
+//
+// A planned chain reaches the device as
+//   * up to PF_DEV_MAX_FULL "full" operands: tensors with the shape of the value being computed, each read
+//     from HBM exactly once as 16-byte vectors (the DRAM -> register data-movement step of the chain);
+//   * up to PF_DEV_MAX_VEC "vec" operands: lower-rank tensors broadcast over the leading dimensions
+//     (bias, gamma, beta); they are a few KB and served from cache after first touch;
+//   * two micro-programs (prologue, epilogue) of element-wise steps on an accumulator held in registers;
+//   * one core step between them (nothing, a row reduction + broadcast, a group normalisation, a
+//     permutation).
+// The micro-programs are what is left of the chain's element-wise operators after the planner has applied
+// by hand the two merging rules of the paper (section 5.1): every write-then-read pair between operators
+// collapsed into a register, every repeated read of an input served by the same load.
+#pragma once
+#include <stdint.h>
+
+#define PF_DEV_MAX_FULL 3
+#define PF_DEV_MAX_VEC 4
+#define PF_DEV_MAX_UOPS 24
+#define PF_DEV_MAX_TMP 2
+#define PF_DEV_MAX_OUT 2
+#define PF_DEV_MAX_RANK 6
+
+namespace pf {
+
+// micro-op codes: acc = f(acc, operand) unless noted
+enum UopCode : uint8_t {
+    U_MOV = 0,     // acc = operand
+    U_ADD, U_SUB,  // acc - operand
+    U_RSUB,        // operand - acc
+    U_MUL, U_DIV,  // acc / operand
+    U_RDIV,        // operand / acc
+    U_MAX, U_MIN,
+    U_NEG, U_RELU, U_SIGMOID, U_SILU, U_GELU_ERF, U_TANH, U_EXP, U_RSQRT,
+    U_MASK_CAUSAL, // acc = (col > row % ival) ? -inf : acc ; ival = extent of the second-to-last dim
+    U_SAVE,        // tmp[slot] = acc
+    U_STORE,       // write acc to output[slot] at the current position (secondary outputs)
+    U_COUNT_
+};
+
+enum OperandKind : uint8_t { K_NONE = 0, K_IMM = 1, K_FULL = 2, K_VEC = 3, K_TMP = 4 };
+
+struct Uop {
+    uint8_t code;  // UopCode
+    uint8_t kind;  // OperandKind
+    uint8_t slot;  // full / vec / tmp / output slot
+    uint8_t pad;
+    union {
+        float imm;
+        int32_t ival;
+    };
+};
+
+struct Program {
+    int32_t n;
+    Uop u[PF_DEV_MAX_UOPS];
+};
+
+enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+
+// A broadcast operand with `numel` elements laid over a value whose innermost extent is n_inner:
+//   numel >= n_inner (numel = m * n_inner): element (row, col) reads vec[(row % m) * n_inner + col]
+//   numel <  n_inner (n_inner % numel == 0): reads vec[col % numel]; numel == 1 is a scalar.
+struct VecArg {
+    const void* ptr;
+    uint32_t numel;
+    uint32_t period_rows;  // m above (1 when numel <= n_inner)
+    int32_t dtype;         // DType of the storage; may differ from the chain's main dtype only as f32
+    int32_t pad;
+};
+
+enum CoreKind : int32_t {
+    CORE_NONE = 0,
+    CORE_SOFTMAX = 1,
+    CORE_LAYERNORM = 2,
+    CORE_RMSNORM = 3,
+    CORE_REDUCE_SUM = 4,
+    CORE_REDUCE_MAX = 5,
+    CORE_REDUCE_MEAN = 6,
+    CORE_GROUPNORM = 7,
+    CORE_PERMUTE = 8
+};
+
+// Arguments common to all families.
+struct ChainArgs {
+    const void* full[PF_DEV_MAX_FULL];
+    VecArg vec[PF_DEV_MAX_VEC];
+    void* out[PF_DEV_MAX_OUT];
+    int32_t n_full, n_vec;
+    int32_t core;            // CoreKind
+    int32_t core_vec[2];     // vec slots of gamma / beta (-1 = absent)
+    float eps;
+    uint32_t n_inner;        // innermost extent (elements) of the value the programs run on
+    uint32_t mask_si;        // > 0: the prologue masks columns > row % mask_si and loads may skip them
+    uint64_t rows;           // number of rows (product of the other extents)
+    Program pro, epi;
+};
+
+// Row family geometry.
+struct RowGeom {
+    uint32_t waves_per_row;  // 1 = a wave owns a row; > 1 = a workgroup of that many waves owns a row
+    uint32_t rows_per_block; // wave variant: waves (= rows) per workgroup
+};
+
+// Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every
+// 32-bit n (multiply-high, one correction add, two shifts).  Built on the host by make_fastdiv().
+struct FastDiv {
+    uint32_t m, s1, s2, d;
+};
+
+// Group family (channels-last GroupNorm) geometry.
+struct GroupGeom {
+    uint32_t samples, hw, channels, groups;
+    uint32_t cv;                 // 16-byte vectors per position (channels / VEC)
+    uint32_t vpg;                // vectors per group (power of two)
+    uint32_t log2_vpg;
+    uint32_t pos_per_step;       // positions a workgroup covers per step (blockDim / cv)
+    uint32_t pos_per_block;      // positions one workgroup owns
+    uint32_t blocks_per_sample;
+    float* ws_partial;           // [samples][blocks_per_sample][groups][4] = (count, mean, M2, -)
+    uint32_t* ws_counter;        // [samples] arrival counters (resident variant)
+    uint32_t epoch;              // launch number; the counters reach epoch * blocks_per_sample
+    uint32_t spin_limit;         // resident variant: bounded wait, then the error flag is raised
+    uint32_t* ws_error;          // resident variant: set to 1 if a wait ran out
+    FastDiv div_cv;
+};
+
+// Transpose family geometry.  The iteration space lists the merged dims from outermost to innermost in
+// the order of the side that is walked contiguously; both sides' strides are given per iteration dim.
+struct PermGeom {
+    int32_t rank;                               // iteration dims used (<= PF_DEV_MAX_RANK)
+    uint32_t extent[PF_DEV_MAX_RANK];           // extents, innermost counted in 16-byte vectors
+    uint32_t in_stride[PF_DEV_MAX_RANK];        // input stride in elements of each iteration dim
+    uint32_t out_stride[PF_DEV_MAX_RANK];       // output stride in elements
+    FastDiv div[PF_DEV_MAX_RANK];
+    uint32_t in_n_inner, out_n_inner;           // innermost extents (elements) of the two layouts
+    FastDiv div_in_inner, div_out_inner;
+    uint32_t total_vecs;
+    uint32_t epi_full_mask, epi_vec_mask;       // operands addressed in the output layout
+    // LDS-staged variant (innermost dim kept): a workgroup moves a [tile_a x tile_b] block of inner rows
+    uint32_t tile_a, tile_b;
+};
+
+}  // namespace pf

@@ -1,0 +1,458 @@
+// Device-side building blocks shared by every kernel family (gfx950, wave64).
+//
+//   * 16-byte vector loads/stores and storage <-> fp32 conversion (the DRAM <-> register data-movement
+//     steps of a chain; each lane moves 16 contiguous bytes, a wave 1 KB: the paper's rule that a parallel
+//     unit reads n x lanes contiguous elements as n elements per lane at lane stride, section 7);
+//   * wave-scope all-reduce built on DPP lane permutations (the "parallel unit" synchronisation scope of
+//     section 5.1: the exchange stays in registers);
+//   * the micro-op interpreter that runs the element-wise part of a chain on a register accumulator
+//     (lane scope: read pattern == write pattern, nothing moves).
+//
+// All control flow inside the interpreter depends only on kernel arguments, so it is wave-uniform and
+// costs scalar branches, not divergence.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "pf_common.h"
+
+namespace pf {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+#define PF_DEVICE __device__ __forceinline__
+
+// ---------------------------------------------------------------------------------------------
+// storage types
+// ---------------------------------------------------------------------------------------------
+template <int DT>
+struct Storage;
+
+template <>
+struct Storage<DT_F32> {
+    static constexpr int VEC = 4;      // elements per 16-byte vector
+    static constexpr int ESIZE = 4;
+    static constexpr bool PRECISE = true;  // fp32 results are held to 1e-5: use correctly rounded math
+    static PF_DEVICE void unpack(u32x4 raw, float* out) {
+        f32x4 v = __builtin_bit_cast(f32x4, raw);
+        out[0] = v[0]; out[1] = v[1]; out[2] = v[2]; out[3] = v[3];
+    }
+    static PF_DEVICE u32x4 pack(const float* in) {
+        f32x4 v = {in[0], in[1], in[2], in[3]};
+        return __builtin_bit_cast(u32x4, v);
+    }
+    static PF_DEVICE u32x4 splat(const void* p) {
+        uint32_t b = *reinterpret_cast<const uint32_t*>(p);
+        return u32x4{b, b, b, b};
+    }
+};
+
+template <>
+struct Storage<DT_F16> {
+    static constexpr int VEC = 8;
+    static constexpr int ESIZE = 2;
+    static constexpr bool PRECISE = false;
+    static PF_DEVICE void unpack(u32x4 raw, float* out) {
+        f16x8 h = __builtin_bit_cast(f16x8, raw);
+        f32x8 v = __builtin_convertvector(h, f32x8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = v[i];
+    }
+    static PF_DEVICE u32x4 pack(const float* in) {
+        f32x8 v = {in[0], in[1], in[2], in[3], in[4], in[5], in[6], in[7]};
+        f16x8 h = __builtin_convertvector(v, f16x8);  // round to nearest even
+        return __builtin_bit_cast(u32x4, h);
+    }
+    static PF_DEVICE u32x4 splat(const void* p) {
+        uint32_t b = *reinterpret_cast<const uint16_t*>(p);
+        b |= b << 16;
+        return u32x4{b, b, b, b};
+    }
+};
+
+template <>
+struct Storage<DT_BF16> {
+    static constexpr int VEC = 8;
+    static constexpr int ESIZE = 2;
+    static constexpr bool PRECISE = false;
+    static PF_DEVICE void unpack(u32x4 raw, float* out) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __builtin_bit_cast(float, raw[i] << 16);
+            out[2 * i + 1] = __builtin_bit_cast(float, raw[i] & 0xffff0000u);
+        }
+    }
+    static PF_DEVICE u32x4 pack(const float* in) {
+        f32x8 v = {in[0], in[1], in[2], in[3], in[4], in[5], in[6], in[7]};
+        bf16x8 h = __builtin_convertvector(v, bf16x8);  // round to nearest even
+        return __builtin_bit_cast(u32x4, h);
+    }
+    static PF_DEVICE u32x4 splat(const void* p) {
+        uint32_t b = *reinterpret_cast<const uint16_t*>(p);
+        b |= b << 16;
+        return u32x4{b, b, b, b};
+    }
+};
+
+// Streamed data is touched once: mark it non-temporal so it does not displace the broadcast operands.
+PF_DEVICE u32x4 load_stream(const void* base, uint64_t byte_off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off));
+}
+PF_DEVICE void store_stream(void* base, uint64_t byte_off, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<char*>(base) + byte_off));
+}
+PF_DEVICE u32x4 load_cached(const void* base, uint64_t byte_off) {
+    return *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off);
+}
+
+PF_DEVICE uint32_t fast_div(uint32_t n, const FastDiv& f) {
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
+// ---------------------------------------------------------------------------------------------
+// wave-scope all-reduce (64 lanes) on DPP permutations; every lane ends with the same bits
+// ---------------------------------------------------------------------------------------------
+template <int CTRL>
+PF_DEVICE float dpp_move(float v) {
+    int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+    return __builtin_bit_cast(float, r);
+}
+PF_DEVICE float read_lane(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+struct OpSum {
+    static PF_DEVICE float apply(float a, float b) { return a + b; }
+};
+struct OpMax {
+    // NaN-propagating is not needed here: a NaN element poisons the row through the later arithmetic
+    static PF_DEVICE float apply(float a, float b) { return fmaxf(a, b); }
+};
+
+template <class Op>
+PF_DEVICE float wave_allreduce(float v) {
+    v = Op::apply(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = Op::apply(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = Op::apply(v, dpp_move<0x141>(v));  // row_half_mirror: 8-lane halves exchanged
+    v = Op::apply(v, dpp_move<0x140>(v));  // row_mirror: every lane of a 16-lane row holds the row result
+    const float r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    return Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
+}
+
+// all-reduce over groups of 2^LOG2 adjacent lanes (LOG2 <= 4), result in every lane of the group
+template <class Op, int LOG2>
+PF_DEVICE float subrow_allreduce(float v) {
+    if (LOG2 >= 1) v = Op::apply(v, dpp_move<0xB1>(v));
+    if (LOG2 >= 2) v = Op::apply(v, dpp_move<0x4E>(v));
+    if (LOG2 >= 3) v = Op::apply(v, dpp_move<0x141>(v));
+    if (LOG2 >= 4) v = Op::apply(v, dpp_move<0x140>(v));
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// element-wise math
+// ---------------------------------------------------------------------------------------------
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <bool PRECISE>
+PF_DEVICE float pf_exp(float x) {
+    if (PRECISE) return expf(x);
+    return __builtin_amdgcn_exp2f(x * kLog2e);
+}
+template <bool PRECISE>
+PF_DEVICE float pf_rcp(float x) {
+    if (PRECISE) return 1.0f / x;
+    return __builtin_amdgcn_rcpf(x);
+}
+template <bool PRECISE>
+PF_DEVICE float pf_div(float a, float b) {
+    if (PRECISE) return a / b;
+    return a * __builtin_amdgcn_rcpf(b);
+}
+template <bool PRECISE>
+PF_DEVICE float pf_rsqrt(float x) {
+    if (PRECISE) return 1.0f / sqrtf(x);
+    return __builtin_amdgcn_rsqf(x);
+}
+template <bool PRECISE>
+PF_DEVICE float pf_sigmoid(float x) {
+    return pf_rcp<PRECISE>(1.0f + pf_exp<PRECISE>(-x));
+}
+template <bool PRECISE>
+PF_DEVICE float pf_tanh(float x) {
+    if (PRECISE) return tanhf(x);
+    return 2.0f * pf_sigmoid<false>(2.0f * x) - 1.0f;
+}
+PF_DEVICE float pf_gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+PF_DEVICE float pf_max_nan(float a, float b) {
+    float r = fmaxf(a, b);
+    return (a != a || b != b) ? __builtin_nanf("") : r;
+}
+PF_DEVICE float pf_min_nan(float a, float b) {
+    float r = fminf(a, b);
+    return (a != a || b != b) ? __builtin_nanf("") : r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// chain specifications: how a kernel learns what the chain looks like
+// ---------------------------------------------------------------------------------------------
+// A kernel is instantiated once per "spec".  The generic spec reads operand counts and the micro-programs
+// from the kernel arguments at run time (wave-uniform scalar loads and branches).  A static spec fixes
+// the structure (operand counts, step codes, operand kinds and slots) at compile time, so the interpreter
+// loop unrolls and the switches fold away; immediates (scale factors, eps, mask extent) stay run-time
+// values in both cases.  This mirrors the paper's GIR templates (section 6): a graph structure chosen
+// ahead of time, with parameters filled in per use.
+
+struct UopC {
+    uint8_t code, kind, slot;
+};
+
+// run-time program list
+struct DynList {
+    static constexpr bool kDynamic = true;
+    static constexpr int n = 0;
+    static constexpr UopC at(int) { return UopC{0, 0, 0}; }
+};
+
+template <class L>
+struct ProgView {
+    const Program& p;
+    PF_DEVICE int n() const { return L::kDynamic ? p.n : L::n; }
+    PF_DEVICE int code(int i) const { return L::kDynamic ? p.u[i].code : L::at(i).code; }
+    PF_DEVICE int kind(int i) const { return L::kDynamic ? p.u[i].kind : L::at(i).kind; }
+    PF_DEVICE int slot(int i) const { return L::kDynamic ? p.u[i].slot : L::at(i).slot; }
+    PF_DEVICE float imm(int i) const { return p.u[i].imm; }
+    PF_DEVICE int32_t ival(int i) const { return p.u[i].ival; }
+};
+
+struct GenericSpec {
+    static constexpr bool kStatic = false;
+    static constexpr int NF = 3, NV = 4, NT = PF_DEV_MAX_TMP;
+    using Pro = DynList;
+    using Epi = DynList;
+    static PF_DEVICE int n_full(const ChainArgs& a) { return a.n_full; }
+    static PF_DEVICE int n_vec(const ChainArgs& a) { return a.n_vec; }
+    static PF_DEVICE int core(const ChainArgs& a) { return a.core; }
+    static PF_DEVICE int gamma(const ChainArgs& a) { return a.core_vec[0]; }
+    static PF_DEVICE int beta(const ChainArgs& a) { return a.core_vec[1]; }
+};
+
+template <int NF_, int NV_, int NT_, int CORE_, int GAMMA_, int BETA_, class ProL, class EpiL>
+struct StaticSpec {
+    static constexpr bool kStatic = true;
+    static constexpr int NF = NF_, NV = NV_, NT = NT_;
+    using Pro = ProL;
+    using Epi = EpiL;
+    static PF_DEVICE int n_full(const ChainArgs&) { return NF_; }
+    static PF_DEVICE int n_vec(const ChainArgs&) { return NV_; }
+    static PF_DEVICE int core(const ChainArgs&) { return CORE_; }
+    static PF_DEVICE int gamma(const ChainArgs&) { return GAMMA_; }
+    static PF_DEVICE int beta(const ChainArgs&) { return BETA_; }
+};
+
+constexpr int at_least_1(int n) { return n < 1 ? 1 : n; }
+
+// ---------------------------------------------------------------------------------------------
+// per-lane state: K 16-byte vectors of every operand, an fp32 accumulator, temporaries
+// ---------------------------------------------------------------------------------------------
+template <int DT, int K, class Spec>
+struct LaneState {
+    static constexpr int VEC = Storage<DT>::VEC;
+    static constexpr int E = K * VEC;
+    u32x4 fraw[at_least_1(Spec::NF)][K];
+    u32x4 vraw[at_least_1(Spec::NV)][K];
+    float acc[E];
+    float tmp[at_least_1(Spec::NT)][E];
+    uint32_t row[K];  // row (index over all but the innermost dim) of vector k
+    uint32_t col[K];  // column of the first element of vector k
+};
+
+// Where a broadcast operand's 16-byte vector for position (row, col) starts, in elements.
+PF_DEVICE uint32_t vec_offset(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner) {
+    if (va.numel >= n_inner) {
+        const uint32_t r = (va.period_rows == 1) ? 0u : row % va.period_rows;
+        return r * n_inner + col;
+    }
+    return col % va.numel;
+}
+
+template <int DT>
+PF_DEVICE u32x4 load_vec_operand(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner) {
+    if (va.numel == 1) return Storage<DT>::splat(va.ptr);
+    const uint32_t off = vec_offset(va, row, col, n_inner);
+    return load_cached(va.ptr, (uint64_t)off * Storage<DT>::ESIZE);
+}
+
+template <int DT, int K>
+PF_DEVICE void unpack_slot(const u32x4 (&raw)[K], float* out) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) Storage<DT>::unpack(raw[k], out + k * Storage<DT>::VEC);
+}
+
+// Fetch an operand by slot; the unrolled compare chain keeps every register index static.
+template <int DT, int K, class Spec>
+PF_DEVICE void fetch_full(const LaneState<DT, K, Spec>& s, int slot, float* b) {
+#pragma unroll
+    for (int f = 0; f < Spec::NF; ++f)
+        if (slot == f) unpack_slot<DT, K>(s.fraw[f], b);
+}
+template <int DT, int K, class Spec>
+PF_DEVICE void fetch_vec(const LaneState<DT, K, Spec>& s, int slot, float* b) {
+#pragma unroll
+    for (int v = 0; v < Spec::NV; ++v)
+        if (slot == v) unpack_slot<DT, K>(s.vraw[v], b);
+}
+
+// Secondary-output hook: the families that support U_STORE pass a functor; others pass NoStore.
+struct NoStore {
+    template <int DT, int K, class Spec>
+    PF_DEVICE void operator()(int, const LaneState<DT, K, Spec>&) const {}
+};
+
+template <int DT, int K, class Spec>
+PF_DEVICE void apply_uop(int code, int slot, int32_t ival, LaneState<DT, K, Spec>& s, const float* b) {
+    constexpr int E = LaneState<DT, K, Spec>::E;
+    constexpr int VEC = LaneState<DT, K, Spec>::VEC;
+    constexpr bool PR = Storage<DT>::PRECISE;
+    switch (code) {
+        case U_MOV:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = b[e];
+            break;
+        case U_ADD:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] + b[e];
+            break;
+        case U_SUB:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] - b[e];
+            break;
+        case U_RSUB:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = b[e] - s.acc[e];
+            break;
+        case U_MUL:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] * b[e];
+            break;
+        case U_DIV:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_div<PR>(s.acc[e], b[e]);
+            break;
+        case U_RDIV:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_div<PR>(b[e], s.acc[e]);
+            break;
+        case U_MAX:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_max_nan(s.acc[e], b[e]);
+            break;
+        case U_MIN:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_min_nan(s.acc[e], b[e]);
+            break;
+        case U_NEG:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = -s.acc[e];
+            break;
+        case U_RELU:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_max_nan(s.acc[e], 0.0f);
+            break;
+        case U_SIGMOID:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_sigmoid<PR>(s.acc[e]);
+            break;
+        case U_SILU:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] * pf_sigmoid<PR>(s.acc[e]);
+            break;
+        case U_GELU_ERF:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_gelu_erf(s.acc[e]);
+            break;
+        case U_TANH:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_tanh<PR>(s.acc[e]);
+            break;
+        case U_EXP:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_exp<PR>(s.acc[e]);
+            break;
+        case U_RSQRT:
+#pragma unroll
+            for (int e = 0; e < E; ++e) s.acc[e] = pf_rsqrt<PR>(s.acc[e]);
+            break;
+        case U_MASK_CAUSAL: {
+            const uint32_t si = (uint32_t)ival;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t i_row = s.row[k] % si;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    s.acc[k * VEC + e] = (s.col[k] + e > i_row) ? -__builtin_inff() : s.acc[k * VEC + e];
+            }
+            break;
+        }
+        case U_SAVE:
+#pragma unroll
+            for (int t = 0; t < Spec::NT; ++t)
+                if (slot == t) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) s.tmp[t][e] = s.acc[e];
+                }
+            break;
+        default: break;
+    }
+}
+
+// One step of the interpreter.
+template <int DT, int K, class Spec, class L, class StoreFn>
+PF_DEVICE void run_step(const ProgView<L>& pv, int i, LaneState<DT, K, Spec>& s, const StoreFn& store_fn) {
+    constexpr int E = LaneState<DT, K, Spec>::E;
+    const int kind = pv.kind(i), code = pv.code(i), slot = pv.slot(i);
+    float b[E];
+    switch (kind) {
+        case K_IMM: {
+            const float imm = pv.imm(i);
+#pragma unroll
+            for (int e = 0; e < E; ++e) b[e] = imm;
+            break;
+        }
+        case K_FULL: fetch_full<DT, K, Spec>(s, slot, b); break;
+        case K_VEC: fetch_vec<DT, K, Spec>(s, slot, b); break;
+        case K_TMP:
+#pragma unroll
+            for (int t = 0; t < Spec::NT; ++t)
+                if (slot == t) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) b[e] = s.tmp[t][e];
+                }
+            break;
+        default:
+#pragma unroll
+            for (int e = 0; e < E; ++e) b[e] = 0.0f;
+            break;
+    }
+    if (code == U_STORE) store_fn(slot, s);
+    else apply_uop<DT, K, Spec>(code, slot, pv.ival(i), s, b);
+}
+
+// The micro-op interpreter.  With a static list the loop bound and every code / kind / slot are compile
+// time constants: the loop unrolls and only the selected arithmetic remains.
+template <int DT, int K, class Spec, class L, class StoreFn>
+PF_DEVICE void run_program(const ProgView<L> pv, LaneState<DT, K, Spec>& s, const StoreFn& store_fn) {
+    if (L::kDynamic) {
+        const int n = pv.n();
+        for (int i = 0; i < n; ++i) run_step<DT, K, Spec, L, StoreFn>(pv, i, s, store_fn);
+    } else {
+#pragma unroll
+        for (int i = 0; i < L::n; ++i) run_step<DT, K, Spec, L, StoreFn>(pv, i, s, store_fn);
+    }
+}
+
+}  // namespace pf

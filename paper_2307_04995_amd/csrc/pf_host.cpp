@@ -1,0 +1,1260 @@
+// Host side of the fused-chain library: description checking, shape inference, lowering of a chain to
+// micro-programs, kernel-family choice, launch geometry, and the C ABI of include/pf_chain.h.
+//
+// Lowering applies, once and by hand, what the paper's rewriting does on a merged GIR-Graph (section 5):
+//   * every value produced by one element-wise operator and consumed by the next stays in a register
+//     (write-then-read merging; lane-scope synchronisation is a no-op);
+//   * an input used by several operators is loaded once (read-after-read merging);
+//   * element-wise operators are moved across the layout change so they run where the data already is
+//     (gOperator swapping): the prologue of a permutation runs on the input layout, its epilogue on the
+//     output layout;
+//   * the one remaining exchange (row reduction, group statistics, tile transpose) decides the kernel
+//     family by its synchronisation scope.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pf_chain.h"
+#include "pf_common.h"
+#include "pf_launch.h"
+#include "pf_specs.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+pf_status fail(pf_status s, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return s;
+}
+
+enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE };
+
+struct OpTraits {
+    OpClass cls;
+    int arity;
+    const char* name;
+};
+
+const OpTraits kOps[PF_OP_COUNT_] = {
+    {OC_BINARY, 2, "add"},      {OC_BINARY, 2, "sub"},      {OC_BINARY, 2, "mul"},      {OC_BINARY, 2, "div"},
+    {OC_BINARY, 2, "max"},      {OC_BINARY, 2, "min"},      {OC_UNARY, 1, "scale"},     {OC_UNARY, 1, "addc"},
+    {OC_UNARY, 1, "neg"},       {OC_UNARY, 1, "relu"},      {OC_UNARY, 1, "sigmoid"},   {OC_UNARY, 1, "silu"},
+    {OC_UNARY, 1, "gelu_erf"},  {OC_UNARY, 1, "tanh"},      {OC_UNARY, 1, "exp"},       {OC_UNARY, 1, "rsqrt"},
+    {OC_MASK, 1, "causal_mask"}, {OC_REDUCE, 1, "reduce_sum"}, {OC_REDUCE, 1, "reduce_max"}, {OC_REDUCE, 1, "reduce_mean"},
+    {OC_SOFTMAX, 1, "softmax"}, {OC_LAYERNORM, 3, "layernorm"}, {OC_RMSNORM, 2, "rmsnorm"}, {OC_GROUPNORM, 3, "groupnorm"},
+    {OC_PERMUTE, 1, "permute"}, {OC_RESHAPE, 1, "reshape"},
+};
+
+bool is_elementwise(OpClass c) { return c == OC_BINARY || c == OC_UNARY || c == OC_MASK; }
+
+typedef std::vector<int64_t> Shape;
+
+int64_t numel(const Shape& s) {
+    int64_t n = 1;
+    for (int64_t d : s) n *= d;
+    return n;
+}
+
+// lower-rank operand equals the trailing dims of the other (leading extents of 1 are ignored)
+bool is_trailing(const Shape& small_in, const Shape& big) {
+    size_t lead = 0;
+    while (lead + 1 < small_in.size() && small_in[lead] == 1) ++lead;
+    Shape small(small_in.begin() + lead, small_in.end());
+    if (small.size() > big.size()) return false;
+    return std::equal(small.begin(), small.end(), big.end() - small.size());
+}
+
+int dtype_size(int dt) { return dt == PF_F32 ? 4 : 2; }
+
+struct Checked {
+    std::vector<Shape> shape;  // per value id
+};
+
+// Full structural + shape check.  Fills per-value shapes.
+pf_status check_desc(const pf_chain_desc* d, Checked* out) {
+    if (!d) return fail(PF_ERR_INVALID_ARG, "desc is null");
+    if (d->struct_size != sizeof(pf_chain_desc))
+        return fail(PF_ERR_INVALID_ARG, "struct_size %u != %zu", d->struct_size, sizeof(pf_chain_desc));
+    if (d->version != PF_CHAIN_VERSION) return fail(PF_ERR_INVALID_ARG, "version %u unsupported", d->version);
+    if (d->n_inputs < 1 || d->n_inputs > PF_MAX_INPUTS) return fail(PF_ERR_INVALID_ARG, "n_inputs %d out of range", d->n_inputs);
+    if (d->n_ops < 1 || d->n_ops > PF_MAX_OPS) return fail(PF_ERR_INVALID_ARG, "n_ops %d out of range", d->n_ops);
+    if (d->n_outputs < 1 || d->n_outputs > PF_MAX_OUTPUTS) return fail(PF_ERR_INVALID_ARG, "n_outputs %d out of range", d->n_outputs);
+    std::vector<Shape>& sh = out->shape;
+    sh.clear();
+    for (int k = 0; k < d->n_inputs; ++k) {
+        const pf_tensor_desc& t = d->inputs[k];
+        if (t.dtype < PF_F32 || t.dtype > PF_BF16) return fail(PF_ERR_DTYPE, "input %d: unknown dtype %d", k, t.dtype);
+        if (t.rank < 1 || t.rank > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "input %d: rank %d out of range", k, t.rank);
+        Shape s(t.shape, t.shape + t.rank);
+        for (int64_t e : s)
+            if (e <= 0) return fail(PF_ERR_SHAPE, "input %d: non-positive extent", k);
+        sh.push_back(s);
+    }
+    for (int k = 0; k < d->n_ops; ++k) {
+        const pf_op_desc& o = d->ops[k];
+        const int id = d->n_inputs + k;
+        if (o.op < 0 || o.op >= PF_OP_COUNT_) return fail(PF_ERR_INVALID_ARG, "op %d: unknown operator %d", k, o.op);
+        const OpTraits& tr = kOps[o.op];
+        if (o.n_src != tr.arity) return fail(PF_ERR_INVALID_ARG, "op %d (%s): n_src %d, expected %d", k, tr.name, o.n_src, tr.arity);
+        for (int s = 0; s < o.n_src; ++s)
+            if (o.src[s] < 0 || o.src[s] >= id) return fail(PF_ERR_INVALID_ARG, "op %d (%s): operand id %d out of range", k, tr.name, o.src[s]);
+        const Shape& a = sh[o.src[0]];
+        Shape r;
+        switch (tr.cls) {
+            case OC_BINARY: {
+                const Shape& b = sh[o.src[1]];
+                if (a == b) r = a;
+                else if (numel(a) >= numel(b) && is_trailing(b, a)) r = a;
+                else if (numel(b) > numel(a) && is_trailing(a, b)) r = b;
+                else return fail(PF_ERR_SHAPE, "op %d (%s): operand shapes do not broadcast", k, tr.name);
+                break;
+            }
+            case OC_UNARY:
+                if ((o.op == PF_SCALE || o.op == PF_ADDC) && !std::isfinite(o.f[0]))
+                    return fail(PF_ERR_INVALID_ARG, "op %d (%s): constant is not finite", k, tr.name);
+                r = a;
+                break;
+            case OC_MASK:
+                if (a.size() < 2) return fail(PF_ERR_SHAPE, "op %d (causal_mask): rank < 2", k);
+                r = a;
+                break;
+            case OC_REDUCE:
+                r = a;
+                r.back() = 1;
+                break;
+            case OC_SOFTMAX: r = a; break;
+            case OC_LAYERNORM:
+            case OC_RMSNORM:
+            case OC_GROUPNORM: {
+                if (!(o.f[0] >= 0.0f) || !std::isfinite(o.f[0])) return fail(PF_ERR_INVALID_ARG, "op %d (%s): eps must be finite and >= 0", k, tr.name);
+                if (tr.cls == OC_GROUPNORM) {
+                    if (a.size() < 2) return fail(PF_ERR_SHAPE, "op %d (groupnorm): rank < 2", k);
+                    if (o.n_i != 1 || o.i[0] < 1 || a.back() % o.i[0] != 0)
+                        return fail(PF_ERR_INVALID_ARG, "op %d (groupnorm): groups must divide the channel count", k);
+                }
+                for (int s = 1; s < o.n_src; ++s) {
+                    const Shape& p = sh[o.src[s]];
+                    if (p.size() != 1 || p[0] != a.back())
+                        return fail(PF_ERR_SHAPE, "op %d (%s): parameter %d must have shape [%lld]", k, tr.name, s, (long long)a.back());
+                }
+                r = a;
+                break;
+            }
+            case OC_PERMUTE: {
+                const int rank = (int)a.size();
+                if (o.n_i != rank) return fail(PF_ERR_INVALID_ARG, "op %d (permute): n_i %d != rank %d", k, o.n_i, rank);
+                bool seen[PF_MAX_RANK] = {false};
+                r.resize(rank);
+                for (int q = 0; q < rank; ++q) {
+                    const int64_t p = o.i[q];
+                    if (p < 0 || p >= rank || seen[p]) return fail(PF_ERR_INVALID_ARG, "op %d (permute): not a permutation", k);
+                    seen[p] = true;
+                    r[q] = a[p];
+                }
+                break;
+            }
+            case OC_RESHAPE: {
+                if (o.n_i < 1 || o.n_i > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "op %d (reshape): n_i out of range", k);
+                r.assign(o.i, o.i + o.n_i);
+                for (int64_t e : r)
+                    if (e <= 0) return fail(PF_ERR_SHAPE, "op %d (reshape): non-positive extent", k);
+                if (numel(r) != numel(a)) return fail(PF_ERR_SHAPE, "op %d (reshape): element count changes", k);
+                break;
+            }
+        }
+        sh.push_back(r);
+    }
+    for (int k = 0; k < d->n_outputs; ++k) {
+        if (d->out_value[k] < d->n_inputs || d->out_value[k] >= d->n_inputs + d->n_ops)
+            return fail(PF_ERR_INVALID_ARG, "output %d: value id %d is not an operator result", k, d->out_value[k]);
+        if (d->out_dtype[k] < PF_F32 || d->out_dtype[k] > PF_BF16) return fail(PF_ERR_DTYPE, "output %d: unknown dtype", k);
+        for (int j = 0; j < k; ++j)
+            if (d->out_value[j] == d->out_value[k]) return fail(PF_ERR_INVALID_ARG, "outputs %d and %d name the same value", j, k);
+    }
+    return PF_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// lowering
+// ---------------------------------------------------------------------------------------------
+struct Lowered {
+    int main_dtype = PF_F32;
+    int core_op = -1;         // index into desc->ops, -1 = none
+    int core = pf::CORE_NONE;
+    float eps = 0.0f;
+    int n_full = 0, n_vec = 0, n_tmp = 0;
+    int full_input[PF_DEV_MAX_FULL];  // chain input index per full slot
+    bool full_is_epi[PF_DEV_MAX_FULL];
+    int vec_input[PF_DEV_MAX_VEC];
+    bool vec_is_epi[PF_DEV_MAX_VEC];
+    int core_vec[2] = {-1, -1};
+    pf::Program pro, epi;
+    uint32_t mask_si = 0;     // load skipping allowed for a causal mask of this extent
+    int out_slot_to_user[PF_MAX_OUTPUTS];  // args.out[slot] <- user outputs[...]
+    int n_out = 1;
+    Shape pre_shape;          // shape of the value entering the core (or the final value if no core)
+    Shape post_shape;         // shape of the value leaving the core
+    int64_t groups = 0;
+    int perm[PF_MAX_RANK];
+};
+
+struct Lowerer {
+    const pf_chain_desc* d;
+    const Checked* c;
+    Lowered* L;
+    std::vector<int> alias;      // value id -> root value id (reshape chains collapse)
+    std::vector<int> uses;       // remaining uses per root value
+    enum LocKind { LOC_NONE, LOC_ACC, LOC_TMP, LOC_FULL, LOC_VEC };
+    struct Loc {
+        LocKind kind = LOC_NONE;
+        int slot = -1;
+    };
+    std::vector<Loc> loc;
+    bool tmp_busy[PF_DEV_MAX_TMP] = {false, false};
+    int acc_val = -1;
+    pf::Program* prog = nullptr;
+    bool in_epi = false;
+    int64_t region_numel = 0;
+    pf_status status = PF_OK;
+
+    int root(int v) const { return alias[v]; }
+
+    bool emit(uint8_t code, uint8_t kind, uint8_t slot, float imm = 0.0f, int32_t ival = 0, bool use_ival = false) {
+        if (prog->n >= PF_DEV_MAX_UOPS) {
+            status = fail(PF_ERR_UNSUPPORTED, "chain needs more than %d element-wise steps", PF_DEV_MAX_UOPS);
+            return false;
+        }
+        pf::Uop& u = prog->u[prog->n++];
+        u.code = code;
+        u.kind = kind;
+        u.slot = slot;
+        u.pad = 0;
+        if (use_ival) u.ival = ival;
+        else u.imm = imm;
+        return true;
+    }
+
+    // location of a raw input operand (assigning a slot on first use)
+    bool input_loc(int v, Loc* out) {
+        if (loc[v].kind == LOC_FULL || loc[v].kind == LOC_VEC) {
+            // an input used on both sides of a layout change would need two layouts
+            const bool was_epi = loc[v].kind == LOC_FULL ? L->full_is_epi[loc[v].slot] : L->vec_is_epi[loc[v].slot];
+            if (was_epi != in_epi && L->core == pf::CORE_PERMUTE) {
+                status = fail(PF_ERR_UNSUPPORTED, "input %d is used before and after the permutation", v);
+                return false;
+            }
+            *out = loc[v];
+            return true;
+        }
+        const int64_t n = numel(c->shape[v]);
+        if (d->inputs[v].dtype != L->main_dtype) {
+            status = fail(PF_ERR_DTYPE, "input %d: dtype differs from the chain's main dtype", v);
+            return false;
+        }
+        if (n == region_numel) {
+            if (L->n_full >= PF_DEV_MAX_FULL) {
+                status = fail(PF_ERR_UNSUPPORTED, "more than %d full-shape inputs", PF_DEV_MAX_FULL);
+                return false;
+            }
+            L->full_input[L->n_full] = v;
+            L->full_is_epi[L->n_full] = in_epi;
+            loc[v].kind = LOC_FULL;
+            loc[v].slot = L->n_full++;
+        } else {
+            if (L->n_vec >= PF_DEV_MAX_VEC) {
+                status = fail(PF_ERR_UNSUPPORTED, "more than %d broadcast inputs", PF_DEV_MAX_VEC);
+                return false;
+            }
+            L->vec_input[L->n_vec] = v;
+            L->vec_is_epi[L->n_vec] = in_epi;
+            loc[v].kind = LOC_VEC;
+            loc[v].slot = L->n_vec++;
+        }
+        *out = loc[v];
+        return true;
+    }
+
+    bool operand_of(int v, uint8_t* kind, uint8_t* slot) {
+        Loc l;
+        if (v < d->n_inputs) {
+            if (!input_loc(v, &l)) return false;
+        } else {
+            l = loc[v];
+        }
+        switch (l.kind) {
+            case LOC_FULL: *kind = pf::K_FULL; break;
+            case LOC_VEC: *kind = pf::K_VEC; break;
+            case LOC_TMP: *kind = pf::K_TMP; break;
+            default:
+                status = fail(PF_ERR_UNSUPPORTED, "value %d is not available where it is used (crosses the core step?)", v);
+                return false;
+        }
+        *slot = (uint8_t)l.slot;
+        return true;
+    }
+
+    // keep the accumulator's value if something still needs it
+    bool spill_acc_if_live(int consumed_now) {
+        if (acc_val < 0) return true;
+        if (uses[acc_val] - consumed_now <= 0) return true;
+        if (loc[acc_val].kind == LOC_TMP) return true;
+        for (int t = 0; t < PF_DEV_MAX_TMP; ++t)
+            if (!tmp_busy[t]) {
+                tmp_busy[t] = true;
+                if (t + 1 > L->n_tmp) L->n_tmp = t + 1;
+                if (!emit(pf::U_SAVE, pf::K_NONE, (uint8_t)t)) return false;
+                loc[acc_val].kind = LOC_TMP;
+                loc[acc_val].slot = t;
+                return true;
+            }
+        status = fail(PF_ERR_UNSUPPORTED, "chain keeps more than %d intermediate values alive", PF_DEV_MAX_TMP);
+        return false;
+    }
+
+    void consume(int v) {
+        if (--uses[v] == 0 && loc[v].kind == LOC_TMP) {
+            tmp_busy[loc[v].slot] = false;
+            loc[v].kind = LOC_NONE;
+        }
+    }
+
+    bool load_acc(int v) {
+        if (acc_val == v) return true;
+        if (!spill_acc_if_live(0)) return false;
+        uint8_t kind, slot;
+        if (!operand_of(v, &kind, &slot)) return false;
+        if (!emit(pf::U_MOV, kind, slot)) return false;
+        if (acc_val >= 0 && loc[acc_val].kind == LOC_ACC) loc[acc_val].kind = LOC_NONE;
+        acc_val = v;
+        return true;
+    }
+
+    void set_acc(int v) {
+        if (acc_val >= 0 && loc[acc_val].kind == LOC_ACC) loc[acc_val].kind = LOC_NONE;
+        acc_val = v;
+        if (loc[v].kind == LOC_NONE) loc[v].kind = LOC_ACC;
+    }
+
+    // secondary outputs: store a value the moment it sits in the accumulator
+    bool maybe_store_output(int v) {
+        if (v == final_value) return true;  // the kernel's last store writes it
+        for (int o = 0; o < d->n_outputs; ++o) {
+            if (root(d->out_value[o]) != v) continue;
+            L->out_slot_to_user[1] = o;
+            L->n_out = 2;
+            if (!emit(pf::U_STORE, pf::K_NONE, 1)) return false;
+            consume(v);
+        }
+        return true;
+    }
+
+    int final_value = -1;
+
+    bool lower_elementwise_op(int k) {
+        const pf_op_desc& o = d->ops[k];
+        const int id = d->n_inputs + k;
+        const OpTraits& tr = kOps[o.op];
+        if (tr.cls == OC_RESHAPE) return true;  // alias only
+        if (tr.cls == OC_UNARY || tr.cls == OC_MASK) {
+            const int a = root(o.src[0]);
+            if (!load_acc(a)) return false;
+            if (!spill_acc_if_live(1)) return false;
+            consume(a);
+            bool ok = true;
+            switch (o.op) {
+                case PF_SCALE: ok = emit(pf::U_MUL, pf::K_IMM, 0, o.f[0]); break;
+                case PF_ADDC: ok = emit(pf::U_ADD, pf::K_IMM, 0, o.f[0]); break;
+                case PF_NEG: ok = emit(pf::U_NEG, pf::K_NONE, 0); break;
+                case PF_RELU: ok = emit(pf::U_RELU, pf::K_NONE, 0); break;
+                case PF_SIGMOID: ok = emit(pf::U_SIGMOID, pf::K_NONE, 0); break;
+                case PF_SILU: ok = emit(pf::U_SILU, pf::K_NONE, 0); break;
+                case PF_GELU_ERF: ok = emit(pf::U_GELU_ERF, pf::K_NONE, 0); break;
+                case PF_TANH: ok = emit(pf::U_TANH, pf::K_NONE, 0); break;
+                case PF_EXP: ok = emit(pf::U_EXP, pf::K_NONE, 0); break;
+                case PF_RSQRT: ok = emit(pf::U_RSQRT, pf::K_NONE, 0); break;
+                case PF_CAUSAL_MASK: {
+                    const Shape& s = c->shape[o.src[0]];
+                    const int64_t si = s[s.size() - 2], sj = s.back();
+                    if (sj != region_inner) {
+                        status = fail(PF_ERR_UNSUPPORTED, "causal_mask: the masked value's last extent differs from the kernel's row length");
+                        return false;
+                    }
+                    if (si > 0x7fffffffLL) {
+                        status = fail(PF_ERR_UNSUPPORTED, "causal_mask: extent too large");
+                        return false;
+                    }
+                    ok = emit(pf::U_MASK_CAUSAL, pf::K_NONE, 0, 0.0f, (int32_t)si, true);
+                    break;
+                }
+                default: ok = false; break;
+            }
+            if (!ok) return false;
+            set_acc(id);
+            return maybe_store_output(id);
+        }
+        // binary
+        const int a = root(o.src[0]), b = root(o.src[1]);
+        static const uint8_t fwd[6] = {pf::U_ADD, pf::U_SUB, pf::U_MUL, pf::U_DIV, pf::U_MAX, pf::U_MIN};
+        static const uint8_t rev[6] = {pf::U_ADD, pf::U_RSUB, pf::U_MUL, pf::U_RDIV, pf::U_MAX, pf::U_MIN};
+        uint8_t code, kind, slot;
+        if (a == b) {
+            if (!load_acc(a)) return false;
+            // the same value on both sides: park a copy in a temporary
+            if (loc[a].kind != LOC_TMP && !spill_acc_if_live(0)) return false;  // uses[a] >= 2: this saves it
+            if (loc[a].kind != LOC_TMP) {
+                status = fail(PF_ERR_UNSUPPORTED, "internal: operand used twice could not be parked");
+                return false;
+            }
+            kind = pf::K_TMP;
+            slot = (uint8_t)loc[a].slot;
+            code = fwd[o.op];
+            if (!emit(code, kind, slot)) return false;
+            consume(a);
+            consume(a);
+        } else {
+            int in_acc, other;
+            bool reversed;
+            if (acc_val == a) { in_acc = a; other = b; reversed = false; }
+            else if (acc_val == b) { in_acc = b; other = a; reversed = true; }
+            else {
+                // prefer loading a computed / full-shape value into the accumulator
+                const bool a_small = a < d->n_inputs && numel(c->shape[a]) != region_numel;
+                if (a_small && !(b < d->n_inputs && numel(c->shape[b]) != region_numel)) { in_acc = b; other = a; reversed = true; }
+                else { in_acc = a; other = b; reversed = false; }
+                if (!load_acc(in_acc)) return false;
+            }
+            if (!spill_acc_if_live(1)) return false;
+            if (!operand_of(other, &kind, &slot)) return false;
+            code = reversed ? rev[o.op] : fwd[o.op];
+            if (!emit(code, kind, slot)) return false;
+            consume(in_acc);
+            consume(other);
+        }
+        set_acc(id);
+        return maybe_store_output(id);
+    }
+
+    int64_t region_inner = 0;
+};
+
+// value ids of chain inputs never reach zero uses through consume() bookkeeping problems: inputs keep
+// LOC_FULL / LOC_VEC for the whole region, so only computed values matter for temporaries.
+
+pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
+    const int n_in = d->n_inputs, n_val = d->n_inputs + d->n_ops;
+    // the core: first operator that is neither element-wise nor a reshape
+    L->core_op = -1;
+    for (int k = 0; k < d->n_ops; ++k) {
+        const OpClass cls = kOps[d->ops[k].op].cls;
+        if (!is_elementwise(cls) && cls != OC_RESHAPE) {
+            if (L->core_op >= 0)
+                return fail(PF_ERR_UNSUPPORTED, "op %d (%s): a chain may hold one reduce / normalise / permute step", k, kOps[d->ops[k].op].name);
+            L->core_op = k;
+        }
+    }
+    Lowerer lw;
+    lw.d = d;
+    lw.c = &c;
+    lw.L = L;
+    lw.alias.resize(n_val);
+    for (int v = 0; v < n_val; ++v) lw.alias[v] = v;
+    for (int k = 0; k < d->n_ops; ++k)
+        if (kOps[d->ops[k].op].cls == OC_RESHAPE) lw.alias[n_in + k] = lw.alias[d->ops[k].src[0]];
+    lw.uses.assign(n_val, 0);
+    for (int k = 0; k < d->n_ops; ++k) {
+        if (kOps[d->ops[k].op].cls == OC_RESHAPE) continue;
+        for (int s = 0; s < d->ops[k].n_src; ++s) lw.uses[lw.root(d->ops[k].src[s])]++;
+    }
+    for (int o = 0; o < d->n_outputs; ++o) lw.uses[lw.root(d->out_value[o])]++;
+    lw.loc.assign(n_val, Lowerer::Loc());
+
+    // the chain's final value: the last operator's result; it must be an output
+    int last_op = d->n_ops - 1;
+    lw.final_value = lw.root(n_in + last_op);
+    bool final_is_output = false;
+    for (int o = 0; o < d->n_outputs; ++o)
+        if (lw.root(d->out_value[o]) == lw.final_value) {
+            final_is_output = true;
+            L->out_slot_to_user[0] = o;
+        }
+    if (!final_is_output) return fail(PF_ERR_UNSUPPORTED, "the last operator's result must be an output");
+    if (lw.final_value < n_in) return fail(PF_ERR_UNSUPPORTED, "the chain computes nothing (only reshapes of an input)");
+    L->n_out = 1;
+    L->out_slot_to_user[1] = -1;
+
+    // main dtype: that of the primary output; every tensor the kernels touch must share it
+    L->main_dtype = d->out_dtype[L->out_slot_to_user[0]];
+    for (int o = 0; o < d->n_outputs; ++o)
+        if (d->out_dtype[o] != L->main_dtype) return fail(PF_ERR_DTYPE, "outputs of different dtypes are not implemented");
+
+    memset(&L->pro, 0, sizeof(L->pro));
+    memset(&L->epi, 0, sizeof(L->epi));
+
+    const int core_k = L->core_op;
+    const int pro_end = core_k >= 0 ? core_k : d->n_ops;
+    // shape entering the core (or leaving the chain when there is none)
+    int pre_value;
+    if (core_k >= 0) pre_value = d->ops[core_k].src[0];
+    else pre_value = n_in + d->n_ops - 1;
+    L->pre_shape = c.shape[pre_value];
+    L->post_shape = core_k >= 0 ? c.shape[n_in + core_k] : L->pre_shape;
+
+    if (core_k >= 0) {
+        const pf_op_desc& o = d->ops[core_k];
+        switch (o.op) {
+            case PF_SOFTMAX: L->core = pf::CORE_SOFTMAX; break;
+            case PF_LAYERNORM: L->core = pf::CORE_LAYERNORM; break;
+            case PF_RMSNORM: L->core = pf::CORE_RMSNORM; break;
+            case PF_GROUPNORM: L->core = pf::CORE_GROUPNORM; L->groups = o.i[0]; break;
+            case PF_REDUCE_SUM: L->core = pf::CORE_REDUCE_SUM; break;
+            case PF_REDUCE_MAX: L->core = pf::CORE_REDUCE_MAX; break;
+            case PF_REDUCE_MEAN: L->core = pf::CORE_REDUCE_MEAN; break;
+            case PF_PERMUTE:
+                L->core = pf::CORE_PERMUTE;
+                for (int q = 0; q < o.n_i; ++q) L->perm[q] = (int)o.i[q];
+                break;
+            default: return fail(PF_ERR_UNSUPPORTED, "unexpected core operator");
+        }
+        L->eps = o.f[0];
+    }
+
+    // ---- prologue
+    lw.prog = &L->pro;
+    lw.in_epi = false;
+    lw.region_numel = numel(L->pre_shape);
+    lw.region_inner = L->pre_shape.back();
+    for (int k = 0; k < pro_end; ++k)
+        if (!lw.lower_elementwise_op(k)) return lw.status;
+    if (core_k >= 0) {
+        const int src = lw.root(d->ops[core_k].src[0]);
+        if (!lw.load_acc(src)) return lw.status;
+        if (!lw.spill_acc_if_live(1)) return lw.status;
+        lw.consume(src);
+        // temporaries do not survive the core step
+        for (int t = 0; t < PF_DEV_MAX_TMP; ++t)
+            if (lw.tmp_busy[t]) return fail(PF_ERR_UNSUPPORTED, "a value computed before the core step is used after it");
+        // affine parameters
+        const pf_op_desc& o = d->ops[core_k];
+        for (int s = 1; s < o.n_src; ++s) {
+            const int p = lw.root(o.src[s]);
+            if (p >= n_in) return fail(PF_ERR_UNSUPPORTED, "normalisation parameters must be chain inputs");
+            Lowerer::Loc l;
+            if (!lw.input_loc(p, &l)) return lw.status;
+            if (l.kind != Lowerer::LOC_VEC) return fail(PF_ERR_UNSUPPORTED, "normalisation parameter has the full shape");
+            L->core_vec[s - 1] = l.slot;
+            lw.consume(p);
+        }
+        // ---- epilogue
+        const int core_val = n_in + core_k;
+        lw.acc_val = -1;
+        lw.set_acc(core_val);
+        lw.prog = &L->epi;
+        lw.in_epi = true;
+        lw.region_numel = numel(L->post_shape);
+        lw.region_inner = L->post_shape.back();
+        if (!lw.maybe_store_output(core_val)) return lw.status;
+        for (int k = core_k + 1; k < d->n_ops; ++k)
+            if (!lw.lower_elementwise_op(k)) return lw.status;
+    }
+    if (lw.acc_val != lw.final_value) return fail(PF_ERR_UNSUPPORTED, "internal: final value is not in the accumulator");
+    // every declared output must have been reached
+    for (int o = 0; o < d->n_outputs; ++o) {
+        if (o == L->out_slot_to_user[0]) continue;
+        if (L->n_out < 2 || L->out_slot_to_user[1] != o) return fail(PF_ERR_UNSUPPORTED, "output %d cannot be produced by this chain shape", o);
+    }
+
+    // causal-mask load skipping: legal when the masked value depends on loaded data only through steps
+    // that come before the mask and nothing computed before the mask is kept
+    L->mask_si = 0;
+    if (L->core == pf::CORE_SOFTMAX || L->core == pf::CORE_NONE) {
+        int mask_at = -1;
+        for (int i = 0; i < L->pro.n; ++i)
+            if (L->pro.u[i].code == pf::U_MASK_CAUSAL) mask_at = i;
+        if (mask_at >= 0) {
+            bool ok = true;
+            for (int i = 0; i < L->pro.n; ++i) {
+                const pf::Uop& u = L->pro.u[i];
+                if (u.code == pf::U_SAVE || u.code == pf::U_STORE) ok = false;
+                if (i > mask_at && (u.kind == pf::K_FULL || u.kind == pf::K_TMP)) ok = false;
+                if (i > mask_at && u.code == pf::U_MOV) ok = false;
+            }
+            if (ok && L->core == pf::CORE_SOFTMAX) L->mask_si = (uint32_t)L->pro.u[mask_at].ival;
+        }
+    }
+    return PF_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// spec catalogue (host view)
+// ---------------------------------------------------------------------------------------------
+struct SpecTable {
+    std::vector<pf::SpecDesc> row, group, perm;
+    SpecTable() {
+#define PF_ADD_SPEC(vec, id_, nf_, nv_, nt_, core_, gamma_, beta_, pro_, epi_)              \
+    {                                                                                       \
+        pf::SpecDesc s;                                                                     \
+        memset(&s, 0, sizeof(s));                                                           \
+        s.id = id_; s.nf = nf_; s.nv = nv_; s.nt = nt_; s.core = pf::core_;                 \
+        s.gamma = gamma_; s.beta = beta_;                                                   \
+        const uint32_t p[] = {0u, pro_};                                                    \
+        const uint32_t e[] = {0u, epi_};                                                    \
+        s.n_pro = (int)(sizeof(p) / sizeof(p[0])) - 1;                                      \
+        s.n_epi = (int)(sizeof(e) / sizeof(e[0])) - 1;                                      \
+        for (int i = 0; i < s.n_pro; ++i) s.pro[i] = p[i + 1];                              \
+        for (int i = 0; i < s.n_epi; ++i) s.epi[i] = e[i + 1];                              \
+        vec.push_back(s);                                                                   \
+    }
+#define PF_ROW_X(id, nf, nv, nt, core, gamma, beta, pro, epi) PF_ADD_SPEC(row, id, nf, nv, nt, core, gamma, beta, PF_L(pro), PF_L(epi))
+        PF_ROW_SPECS(PF_ROW_X)
+#define PF_GROUP_X(id, nf, nv, nt, core, gamma, beta, pro, epi) PF_ADD_SPEC(group, id, nf, nv, nt, core, gamma, beta, PF_L(pro), PF_L(epi))
+        PF_GROUP_SPECS(PF_GROUP_X)
+#define PF_PERM_X(id, nf, nv, nt, core, gamma, beta, pro, epi) PF_ADD_SPEC(perm, id, nf, nv, nt, core, gamma, beta, PF_L(pro), PF_L(epi))
+        PF_PERM_SPECS(PF_PERM_X)
+    }
+};
+
+const SpecTable& spec_table() {
+    static const SpecTable t;
+    return t;
+}
+
+bool list_equal(const pf::Program& p, const uint32_t* list, int n) {
+    if (p.n != n) return false;
+    for (int i = 0; i < n; ++i) {
+        const uint32_t packed = (uint32_t)p.u[i].code | ((uint32_t)p.u[i].kind << 8) | ((uint32_t)p.u[i].slot << 16);
+        if (packed != list[i]) return false;
+    }
+    return true;
+}
+
+int match_spec(const std::vector<pf::SpecDesc>& table, const Lowered& L) {
+    if (L.n_out != 1) return 0;
+    for (const pf::SpecDesc& s : table) {
+        if (s.nf != L.n_full || s.nv != L.n_vec || s.nt != L.n_tmp || s.core != L.core) continue;
+        if (s.gamma != L.core_vec[0] || s.beta != L.core_vec[1]) continue;
+        if (!list_equal(L.pro, s.pro, s.n_pro) || !list_equal(L.epi, s.epi, s.n_epi)) continue;
+        return s.id;
+    }
+    return 0;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// the plan
+// ---------------------------------------------------------------------------------------------
+struct pf_plan_s {
+    pf_chain_desc desc;
+    Lowered low;
+    int device = 0;
+    int family = 0, variant = 0;
+    int spec_id = 0;          // 0 = generic interpreter
+    int k = 1;                // 16-byte vectors per lane
+    bool reduce_only = false;
+    pf::ChainArgs args;       // pointers are filled per run
+    pf::RowGeom row;
+    pf::GroupGeom group;
+    pf::PermGeom permg;
+    uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
+    dim3 grid, block;
+    dim3 grid2, block2;       // second launch (two-pass group variant)
+    uint32_t lds_bytes = 0;
+    void* workspace = nullptr;
+    uint64_t workspace_bytes = 0;
+    uint64_t in_bytes[PF_MAX_INPUTS];
+    uint64_t out_bytes[PF_MAX_OUTPUTS];
+    Shape out_shape[PF_MAX_OUTPUTS];
+    int n_launches = 1;
+    mutable uint32_t epoch = 0;
+};
+
+namespace {
+
+int env_int(const char* name, int dflt) {
+    const char* s = getenv(name);
+    if (!s || !*s) return dflt;
+    return atoi(s);
+}
+
+pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    for (int v = 0; v < L.n_vec; ++v) {
+        const int in = L.vec_input[v];
+        const int64_t n = numel(c.shape[in]);
+        const int64_t inner = (L.vec_is_epi[v] ? L.post_shape : L.pre_shape).back();
+        pf::VecArg& va = p->args.vec[v];
+        va.ptr = nullptr;
+        va.dtype = L.main_dtype;
+        va.pad = 0;
+        if (n > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d too large", in);
+        va.numel = (uint32_t)n;
+        va.period_rows = 1;
+        if (n == 1) continue;
+        if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "broadcast input %d: size is not a multiple of 16 bytes", in);
+        if (n >= inner) {
+            if (n % inner != 0) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d does not tile the kernel's rows", in);
+            va.period_rows = (uint32_t)(n / inner);
+        } else if (inner % n != 0) {
+            return fail(PF_ERR_UNSUPPORTED, "broadcast input %d does not tile the kernel's rows", in);
+        }
+    }
+    return PF_OK;
+}
+
+pf_status plan_row(pf_plan_s* p, int forced_variant) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const int64_t n = L.pre_shape.back();
+    const int64_t rows = numel(L.pre_shape) / n;
+    if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "row length %lld is not a multiple of 16 bytes", (long long)n);
+    if (rows > 0xffffffffLL || n > 0x7fffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the row family");
+    const int64_t vpr = n / vec;
+    // candidates (waves per row, vectors per lane); prefer little idle lanes, small workgroups, a single wave
+    int best_wpr = 0, best_k = 0;
+    long best_score = -1;
+    const int ks[3] = {1, 2, 4};
+    for (int ki = 0; ki < 3; ++ki) {
+        const int k = ks[ki];
+        const int64_t wpr = (vpr + 64 * k - 1) / (64 * k);
+        if (wpr > 16) continue;
+        if (forced_variant == PF_VARIANT_ROW_WAVE && wpr != 1) continue;
+        if (forced_variant == PF_VARIANT_ROW_BLOCK && wpr == 1) continue;
+        const double waste = 1.0 - (double)vpr / (double)(wpr * 64 * k);
+        long score = (waste > 0.26 ? 4000 : (waste > 0.13 ? 2000 : 0)) + (wpr > 4 ? 1000 : 0) + (wpr > 1 ? 100 : 0) + k;
+        if (best_score < 0 || score < best_score) {
+            best_score = score;
+            best_wpr = (int)wpr;
+            best_k = k;
+        }
+    }
+    if (best_score < 0) {
+        if (forced_variant >= 0) return fail(PF_ERR_UNSUPPORTED, "variant %d is not possible for row length %lld", forced_variant, (long long)n);
+        return fail(PF_ERR_UNSUPPORTED, "row length %lld exceeds what one workgroup keeps in registers", (long long)n);
+    }
+    p->family = PF_FAMILY_ROW;
+    p->variant = best_wpr == 1 ? PF_VARIANT_ROW_WAVE : PF_VARIANT_ROW_BLOCK;
+    p->k = best_k;
+    p->row.waves_per_row = (uint32_t)best_wpr;
+    p->row.rows_per_block = best_wpr >= 4 ? 1u : (uint32_t)(4 / best_wpr);
+    p->block = dim3(64u * best_wpr * p->row.rows_per_block);
+    p->grid = dim3((uint32_t)((rows + p->row.rows_per_block - 1) / p->row.rows_per_block));
+    p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
+    p->reduce_only = L.core == pf::CORE_REDUCE_SUM || L.core == pf::CORE_REDUCE_MAX || L.core == pf::CORE_REDUCE_MEAN;
+    if (p->reduce_only) {
+        // the epilogue runs on one value per row: no tensor operands there
+        for (int i = 0; i < L.epi.n; ++i)
+            if (L.epi.u[i].kind != pf::K_NONE && L.epi.u[i].kind != pf::K_IMM)
+                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
+        for (int i = 0; i < L.epi.n; ++i)
+            if (L.epi.u[i].code == pf::U_MASK_CAUSAL || L.epi.u[i].code == pf::U_STORE)
+                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
+        if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "a keep-dim reduction has one output");
+    }
+    p->args.n_inner = (uint32_t)n;
+    p->args.rows = (uint64_t)rows;
+    p->spec_id = 0;
+    if (!p->reduce_only && env_int("PF_NO_STATIC", 0) == 0) {
+        const int id = match_spec(spec_table().row, L);
+        if (id && pf::row_static_available(id, p->k, p->block.x)) p->spec_id = id;
+    }
+    return PF_OK;
+}
+
+pf_status plan_ew(pf_plan_s* p) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const int64_t n = L.pre_shape.back();
+    const int64_t total = numel(L.pre_shape);
+    if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost extent %lld is not a multiple of 16 bytes", (long long)n);
+    const int64_t total_vecs = total / vec;
+    if (total_vecs > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the element-wise family");
+    p->family = PF_FAMILY_ELEMENTWISE;
+    p->variant = PF_VARIANT_EW_FLAT;
+    p->k = 1;
+    p->ew_total_vecs = (uint32_t)total_vecs;
+    p->ew_vecs_per_row = (uint32_t)(n / vec);
+    p->block = dim3(256);
+    p->grid = dim3((uint32_t)((total_vecs + 256 * p->k - 1) / (256 * p->k)));
+    p->args.n_inner = (uint32_t)n;
+    p->args.rows = (uint64_t)(total / n);
+    return PF_OK;
+}
+
+}  // namespace
+
+namespace {
+
+pf::FastDiv make_fastdiv(uint32_t d) {
+    pf::FastDiv f;
+    f.d = d;
+    if (d <= 1) {
+        f.m = 0; f.s1 = 0; f.s2 = 0;
+        return f;
+    }
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    f.m = (uint32_t)((((1ull << 32) * ((1ull << l) - d)) / d) + 1);
+    f.s1 = 1;
+    f.s2 = l - 1;
+    return f;
+}
+
+// ---- transpose family
+pf_status plan_perm(pf_plan_s* p, int forced_variant) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const Shape& in = L.pre_shape;
+    const int rank = (int)in.size();
+    if (numel(in) > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the transpose family");
+    for (int i = 0; i < L.pro.n; ++i)
+        if (L.pro.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the transpose family");
+    for (int i = 0; i < L.epi.n; ++i)
+        if (L.epi.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the transpose family");
+    // input strides
+    std::vector<int64_t> istr(rank);
+    int64_t acc = 1;
+    for (int k = rank - 1; k >= 0; --k) { istr[k] = acc; acc *= in[k]; }
+    // output dims in order, dropping extent-1 dims and merging dims that stay adjacent
+    struct Dim { int64_t extent, in_stride; };
+    std::vector<Dim> od;
+    for (int q = 0; q < rank; ++q) {
+        const int src = L.perm[q];
+        if (in[src] == 1) continue;
+        if (!od.empty() && od.back().in_stride == in[src] * istr[src]) {
+            od.back().extent *= in[src];
+            od.back().in_stride = istr[src];
+        } else {
+            od.push_back(Dim{in[src], istr[src]});
+        }
+    }
+    if (od.empty()) od.push_back(Dim{1, 1});
+    const int m = (int)od.size();
+    if (od.back().in_stride != 1)
+        return fail(PF_ERR_UNSUPPORTED, "permutations that change the innermost dimension are not implemented yet");
+    const int64_t inner = od.back().extent;
+    if ((inner * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost run of %lld elements is not a multiple of 16 bytes", (long long)inner);
+    // the vectors of broadcast operands must not straddle rows of either layout
+    if ((L.pre_shape.back() * es) % 16 != 0 || (L.post_shape.back() * es) % 16 != 0)
+        return fail(PF_ERR_ALIGNMENT, "innermost extent is not a multiple of 16 bytes");
+    pf::PermGeom& g = p->permg;
+    memset(&g, 0, sizeof(g));
+    g.in_n_inner = (uint32_t)L.pre_shape.back();
+    g.out_n_inner = (uint32_t)L.post_shape.back();
+    g.div_in_inner = make_fastdiv(g.in_n_inner);
+    g.div_out_inner = make_fastdiv(g.out_n_inner);
+    g.total_vecs = (uint32_t)(numel(in) / vec);
+    for (int f = 0; f < L.n_full; ++f) if (L.full_is_epi[f]) g.epi_full_mask |= 1u << f;
+    for (int v = 0; v < L.n_vec; ++v) if (L.vec_is_epi[v]) g.epi_vec_mask |= 1u << v;
+    // output strides of the merged dims
+    std::vector<int64_t> ostr(m);
+    acc = 1;
+    for (int q = m - 1; q >= 0; --q) { ostr[q] = acc; acc *= od[q].extent; }
+    p->family = PF_FAMILY_TRANSPOSE;
+    p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().perm, L);
+    // LDS-staged variant: [batch, A, B, inner] -> [batch, B, A, inner]
+    bool lds_ok = false;
+    uint32_t ta = 0, tb = 0;
+    int ia = -1, ib = -1;  // output positions of B (first) and A (second): out = [batch?, B, A, inner]
+    if (m == 3 || m == 4) {
+        ib = m - 3;
+        ia = m - 2;
+        const Dim& B = od[ib];
+        const Dim& A = od[ia];
+        // in the input A is outside B: stride(A) == extent(B) * stride(B), stride(B) == inner
+        const bool pattern = B.in_stride == inner && A.in_stride == B.extent * inner && (m == 3 || od[0].in_stride == A.extent * A.in_stride);
+        if (pattern) {
+            const int64_t inner_v = inner / vec;
+            // tile: tb inner rows of B per input run, ta of A per output run; keep the tile near 32 KB
+            for (int64_t cand_b = std::min<int64_t>(B.extent, 32); cand_b >= 1 && !lds_ok; --cand_b) {
+                if (B.extent % cand_b != 0) continue;
+                for (int64_t cand_a = 32; cand_a >= 2; --cand_a) {
+                    if (A.extent % cand_a != 0) continue;
+                    const int64_t bytes = cand_a * (cand_b * inner_v + 1) * 16;
+                    if (bytes > 48 * 1024 || cand_a * cand_b * inner_v < 256) continue;
+                    ta = (uint32_t)cand_a; tb = (uint32_t)cand_b; lds_ok = true;
+                    break;
+                }
+            }
+        }
+    }
+    int variant = forced_variant >= 0 ? forced_variant : PF_VARIANT_T_ROWS;
+    if (variant == PF_VARIANT_T_LDS_ROWS && !lds_ok)
+        return fail(PF_ERR_UNSUPPORTED, "the LDS-staged variant needs a [.., A, B, inner] -> [.., B, A, inner] permutation with tileable extents");
+    if (variant != PF_VARIANT_T_ROWS && variant != PF_VARIANT_T_LDS_ROWS)
+        return fail(PF_ERR_UNSUPPORTED, "variant %d is not implemented for this permutation", variant);
+    p->variant = variant;
+    if (variant == PF_VARIANT_T_LDS_ROWS) {
+        const Dim& B = od[ib];
+        const Dim& A = od[ia];
+        const int64_t batch = m == 4 ? od[0].extent : 1;
+        g.rank = 4;
+        g.extent[0] = (uint32_t)batch;
+        g.extent[1] = (uint32_t)(A.extent / ta);
+        g.extent[2] = (uint32_t)(B.extent / tb);
+        g.extent[3] = (uint32_t)(inner / vec);
+        g.in_stride[0] = m == 4 ? (uint32_t)od[0].in_stride : 0u;
+        g.in_stride[1] = (uint32_t)A.in_stride;
+        g.in_stride[2] = (uint32_t)B.in_stride;
+        g.in_stride[3] = 1;
+        g.out_stride[0] = m == 4 ? (uint32_t)ostr[0] : 0u;
+        g.out_stride[1] = (uint32_t)ostr[ia];
+        g.out_stride[2] = (uint32_t)ostr[ib];
+        g.out_stride[3] = 1;
+        g.tile_a = ta;
+        g.tile_b = tb;
+        p->k = 1;
+        p->block = dim3(256);
+        p->grid = dim3((uint32_t)(batch * (A.extent / ta) * (B.extent / tb)));
+        p->lds_bytes = (uint32_t)(ta * (tb * (inner / vec) + 1) * 16);
+    } else {
+        if (m > PF_DEV_MAX_RANK) return fail(PF_ERR_UNSUPPORTED, "too many dimensions");
+        g.rank = m;
+        for (int q = 0; q < m; ++q) {
+            g.extent[q] = (uint32_t)(q == m - 1 ? od[q].extent / vec : od[q].extent);
+            g.in_stride[q] = (uint32_t)od[q].in_stride;
+            g.out_stride[q] = (uint32_t)ostr[q];
+            g.div[q] = make_fastdiv(g.extent[q]);
+        }
+        p->k = g.total_vecs >= 65536u ? 2 : 1;
+        p->block = dim3(256);
+        p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
+        p->lds_bytes = 0;
+    }
+    p->args.n_inner = g.in_n_inner;
+    p->args.rows = (uint64_t)(numel(in) / g.in_n_inner);
+    return PF_OK;
+}
+
+// ---- group family
+pf_status plan_group(pf_plan_s* p, int forced_variant) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const Shape& sh = L.pre_shape;
+    const int64_t samples = sh[0], C = sh.back();
+    const int64_t hw = numel(sh) / (samples * C);
+    const int64_t G = L.groups;
+    if ((C * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)C);
+    const int64_t cpg = C / G;
+    if (cpg % vec != 0) return fail(PF_ERR_UNSUPPORTED, "channels per group (%lld) must be a multiple of %d", (long long)cpg, vec);
+    const int64_t vpg = cpg / vec, cv = C / vec;
+    if ((vpg & (vpg - 1)) != 0 || vpg > 64) return fail(PF_ERR_UNSUPPORTED, "channels per group / %d must be a power of two <= 64", vec);
+    if (cv > 1024) return fail(PF_ERR_UNSUPPORTED, "more than %d channels", 1024 * vec);
+    if (samples * hw > 0xffffffffLL || samples > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
+    for (int v = 0; v < L.n_vec; ++v)
+        if (p->args.vec[v].numel > (uint32_t)C && p->args.vec[v].numel != 1)
+            ;  // per-position broadcast operands are fine in the two-pass variant
+    for (int i = 0; i < L.pro.n; ++i)
+        if (L.pro.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the group family");
+    for (int i = 0; i < L.epi.n; ++i)
+        if (L.epi.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the group family");
+    pf::GroupGeom& g = p->group;
+    memset(&g, 0, sizeof(g));
+    g.samples = (uint32_t)samples;
+    g.hw = (uint32_t)hw;
+    g.channels = (uint32_t)C;
+    g.groups = (uint32_t)G;
+    g.cv = (uint32_t)cv;
+    g.vpg = (uint32_t)vpg;
+    g.log2_vpg = 0;
+    while ((1u << g.log2_vpg) < g.vpg) ++g.log2_vpg;
+    g.div_cv = make_fastdiv(g.cv);
+    g.spin_limit = 1u << 22;
+    p->family = PF_FAMILY_GROUP;
+    p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().group, L);
+
+    hipDeviceProp_t prop;
+    if (hipSetDevice(p->device) != hipSuccess || hipGetDeviceProperties(&prop, p->device) != hipSuccess)
+        return fail(PF_ERR_HIP, "cannot query device %d (the group family needs the device at plan time)", p->device);
+    const int n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    const uint32_t threads = 1024;
+    g.pos_per_step = threads / g.cv;
+
+    // resident variant: catalogue entry, one full operand, per-channel broadcast operands only
+    bool resident_ok = p->spec_id != 0 && L.n_full == 1;
+    for (int v = 0; v < L.n_vec; ++v)
+        if (p->args.vec[v].numel > (uint32_t)C) resident_ok = false;
+    int nv = 0;
+    uint32_t res_bps = 0, res_grid = 0;
+    if (resident_ok) {
+        // largest slice per workgroup that still gives every compute unit work
+        const int cands[3] = {16, 8, 4};
+        for (int ci = 0; ci < 3 && nv == 0; ++ci) {
+            const uint32_t ppb = cands[ci] * g.pos_per_step;
+            const uint32_t bps = (uint32_t)((hw + ppb - 1) / ppb);
+            const uint64_t tiles = (uint64_t)bps * samples;
+            if (bps * g.groups > 2048u) continue;
+            if (tiles >= (uint64_t)n_cu || ci == 2) {
+                const int per_cu = pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, cands[ci], (int)threads);
+                if (per_cu < 1) continue;
+                uint64_t cap = (uint64_t)per_cu * n_cu;
+                uint64_t grid = std::min<uint64_t>(tiles, cap);
+                grid = grid / bps * bps;  // whole samples per round, so every wait is for co-resident workgroups
+                if (grid < bps) continue;
+                nv = cands[ci];
+                res_bps = bps;
+                res_grid = (uint32_t)grid;
+            }
+        }
+        if (nv == 0) resident_ok = false;
+    }
+    int variant = forced_variant >= 0 ? forced_variant : (resident_ok ? PF_VARIANT_GROUP_RESIDENT : PF_VARIANT_GROUP_TWO_PASS);
+    if (variant == PF_VARIANT_GROUP_RESIDENT && !resident_ok)
+        return fail(PF_ERR_UNSUPPORTED, "the register-resident variant is not available for this chain or shape");
+    if (variant != PF_VARIANT_GROUP_RESIDENT && variant != PF_VARIANT_GROUP_TWO_PASS)
+        return fail(PF_ERR_UNSUPPORTED, "unknown group variant %d", variant);
+    p->variant = variant;
+    p->block = dim3(threads);
+    if (variant == PF_VARIANT_GROUP_RESIDENT) {
+        g.pos_per_block = nv * g.pos_per_step;
+        g.blocks_per_sample = res_bps;
+        p->k = nv;
+        p->grid = dim3(res_grid);
+        p->n_launches = 1;
+    } else {
+        // enough workgroups to fill the device, whole steps of two positions-steps per iteration
+        const uint32_t step = g.pos_per_step * 2u;
+        uint32_t want_bps = (uint32_t)std::max<int64_t>(1, (4 * n_cu + samples - 1) / samples);
+        uint32_t ppb = (uint32_t)((hw + want_bps - 1) / want_bps);
+        ppb = (ppb + step - 1) / step * step;
+        uint32_t bps = (uint32_t)((hw + ppb - 1) / ppb);
+        while (bps * g.groups > 2048u) {
+            ppb *= 2;
+            bps = (uint32_t)((hw + ppb - 1) / ppb);
+        }
+        g.pos_per_block = ppb;
+        g.blocks_per_sample = bps;
+        p->k = 2;
+        p->grid = dim3(bps, (uint32_t)samples);
+        p->grid2 = p->grid;
+        p->block2 = p->block;
+        p->n_launches = 2;
+    }
+    p->lds_bytes = 2048 * 3 * 4 + 1024 * 2 * 4;
+    // workspace: partials, arrival counters, error word
+    const uint64_t part_bytes = (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
+    const uint64_t cnt_bytes = ((uint64_t)samples * sizeof(uint32_t) + 255) / 256 * 256;
+    p->workspace_bytes = part_bytes + cnt_bytes + 256;
+    if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
+    if (hipMemset(p->workspace, 0, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
+    g.ws_partial = static_cast<float*>(p->workspace);
+    g.ws_counter = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
+    g.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes + cnt_bytes);
+    p->args.n_inner = (uint32_t)C;
+    p->args.rows = (uint64_t)(samples * hw);
+    return PF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pf_status pf_chain_validate(const pf_chain_desc* desc) {
+    Checked c;
+    return check_desc(desc, &c);
+}
+
+pf_status pf_chain_infer_shape(const pf_chain_desc* desc, int32_t value, pf_tensor_desc* out) {
+    Checked c;
+    pf_status s = check_desc(desc, &c);
+    if (s != PF_OK) return s;
+    if (!out) return fail(PF_ERR_INVALID_ARG, "out is null");
+    if (value < 0 || value >= (int32_t)c.shape.size()) return fail(PF_ERR_INVALID_ARG, "value id %d out of range", value);
+    const Shape& sh = c.shape[value];
+    if (sh.size() > PF_MAX_RANK) return fail(PF_ERR_SHAPE, "rank exceeds PF_MAX_RANK");
+    pf_tensor_desc t;
+    memset(&t, 0, sizeof(t));
+    t.dtype = value < desc->n_inputs ? desc->inputs[value].dtype : PF_F32;
+    t.rank = (int32_t)sh.size();
+    for (size_t i = 0; i < sh.size(); ++i) t.shape[i] = sh[i];
+    *out = t;
+    return PF_OK;
+}
+
+pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out) {
+    if (!out) return fail(PF_ERR_INVALID_ARG, "out is null");
+    Checked c;
+    pf_status s = check_desc(desc, &c);
+    if (s != PF_OK) return s;
+    pf_plan_s* p = new (std::nothrow) pf_plan_s();
+    if (!p) return fail(PF_ERR_NOMEM, "out of host memory");
+    p->desc = *desc;
+    p->device = device;
+    memset(&p->args, 0, sizeof(p->args));
+    memset(&p->row, 0, sizeof(p->row));
+    memset(&p->group, 0, sizeof(p->group));
+    memset(&p->permg, 0, sizeof(p->permg));
+    s = lower_chain(desc, c, &p->low);
+    if (s == PF_OK) {
+        const Lowered& L = p->low;
+        p->args.n_full = L.n_full;
+        p->args.n_vec = L.n_vec;
+        p->args.core = L.core;
+        p->args.core_vec[0] = L.core_vec[0];
+        p->args.core_vec[1] = L.core_vec[1];
+        p->args.eps = L.eps;
+        p->args.mask_si = L.mask_si;
+        p->args.pro = L.pro;
+        p->args.epi = L.epi;
+        s = fill_vec_args(p, c);
+    }
+    if (s == PF_OK) {
+        switch (p->low.core) {
+            case pf::CORE_NONE: s = plan_ew(p); break;
+            case pf::CORE_GROUPNORM: s = plan_group(p, variant); break;
+            case pf::CORE_PERMUTE: s = plan_perm(p, variant); break;
+            default: s = plan_row(p, variant); break;
+        }
+    }
+    if (s == PF_OK) {
+        for (int k = 0; k < desc->n_inputs; ++k) p->in_bytes[k] = (uint64_t)numel(c.shape[k]) * dtype_size(desc->inputs[k].dtype);
+        for (int o = 0; o < desc->n_outputs; ++o) {
+            p->out_shape[o] = c.shape[desc->out_value[o]];
+            p->out_bytes[o] = (uint64_t)numel(p->out_shape[o]) * dtype_size(desc->out_dtype[o]);
+        }
+        if (env_int("PF_LOG", 0))
+            fprintf(stderr, "[pf_chain] family=%d variant=%d spec=%d k=%d grid=%u block=%u uops=%d+%d full=%d vec=%d tmp=%d mask_si=%u\n",
+                    p->family, p->variant, p->spec_id, p->k, p->grid.x, p->block.x, p->low.pro.n, p->low.epi.n, p->low.n_full,
+                    p->low.n_vec, p->low.n_tmp, p->low.mask_si);
+        *out = p;
+        return PF_OK;
+    }
+    pf_chain_plan_destroy(p);
+    return s;
+}
+
+pf_status pf_chain_plan(const pf_chain_desc* desc, int32_t device, pf_plan** out) {
+    return pf_chain_plan_variant(desc, device, env_int("PF_FORCE_VARIANT", -1), out);
+}
+
+pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
+    if (!plan || !info) return fail(PF_ERR_INVALID_ARG, "null argument");
+    memset(info, 0, sizeof(*info));
+    info->family = plan->family;
+    info->variant = plan->variant;
+    info->grid[0] = plan->grid.x; info->grid[1] = plan->grid.y; info->grid[2] = plan->grid.z;
+    info->block[0] = plan->block.x; info->block[1] = plan->block.y; info->block[2] = plan->block.z;
+    info->lds_bytes = plan->lds_bytes;
+    info->workspace_bytes = plan->workspace_bytes;
+    for (int k = 0; k < plan->desc.n_inputs; ++k) info->compulsory_read_bytes += plan->in_bytes[k];
+    for (int o = 0; o < plan->desc.n_outputs; ++o) info->compulsory_write_bytes += plan->out_bytes[o];
+    info->n_launches = plan->n_launches;
+    info->n_micro_ops = plan->low.pro.n + plan->low.epi.n;
+    info->spec_id = plan->spec_id;
+    info->vectors_per_lane = plan->k;
+    return PF_OK;
+}
+
+pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* const* outputs, void* stream) {
+    if (!plan || !inputs || !outputs) return fail(PF_ERR_INVALID_ARG, "null argument");
+    const pf_chain_desc& d = plan->desc;
+    for (int k = 0; k < d.n_inputs; ++k) {
+        if (!inputs[k]) return fail(PF_ERR_INVALID_ARG, "input %d is null", k);
+        if ((uintptr_t)inputs[k] % 16 != 0) return fail(PF_ERR_ALIGNMENT, "input %d is not 16-byte aligned", k);
+    }
+    for (int o = 0; o < d.n_outputs; ++o) {
+        if (!outputs[o]) return fail(PF_ERR_INVALID_ARG, "output %d is null", o);
+        if ((uintptr_t)outputs[o] % 16 != 0) return fail(PF_ERR_ALIGNMENT, "output %d is not 16-byte aligned", o);
+        const uintptr_t ob = (uintptr_t)outputs[o], oe = ob + plan->out_bytes[o];
+        for (int k = 0; k < d.n_inputs; ++k) {
+            const uintptr_t ib = (uintptr_t)inputs[k], ie = ib + plan->in_bytes[k];
+            if (ob < ie && ib < oe) {
+                const bool same = ob == ib && plan->out_bytes[o] == plan->in_bytes[k];
+                if (!same || plan->family == PF_FAMILY_TRANSPOSE)
+                    return fail(PF_ERR_ALIAS, "output %d overlaps input %d", o, k);
+            }
+        }
+        for (int j = 0; j < o; ++j) {
+            const uintptr_t jb = (uintptr_t)outputs[j], je = jb + plan->out_bytes[j];
+            if (ob < je && jb < oe) return fail(PF_ERR_ALIAS, "outputs %d and %d overlap", j, o);
+        }
+    }
+    pf::ChainArgs a = plan->args;
+    const Lowered& L = plan->low;
+    for (int f = 0; f < L.n_full; ++f) a.full[f] = inputs[L.full_input[f]];
+    for (int v = 0; v < L.n_vec; ++v) a.vec[v].ptr = inputs[L.vec_input[v]];
+    for (int s = 0; s < L.n_out; ++s) a.out[s] = outputs[L.out_slot_to_user[s]];
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    switch (plan->family) {
+        case PF_FAMILY_ROW:
+            if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
+            else e = pf::launch_row_generic(L.main_dtype, a, plan->row, plan->k, plan->reduce_only, plan->grid, plan->block, st);
+            break;
+        case PF_FAMILY_ELEMENTWISE:
+            e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->grid, st);
+            break;
+        case PF_FAMILY_GROUP: {
+            pf::GroupGeom g = plan->group;
+            g.epoch = ++plan->epoch;
+            if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
+                e = pf::launch_group_stats(plan->spec_id, L.main_dtype, a, g, plan->grid, plan->block, st);
+                if (e == hipSuccess) e = pf::launch_group_apply(plan->spec_id, L.main_dtype, a, g, plan->grid2, plan->block2, st);
+            } else {
+                e = pf::launch_group_resident(plan->spec_id, L.main_dtype, a, g, plan->k, g.samples * g.blocks_per_sample, plan->grid,
+                                              plan->block, st);
+            }
+            break;
+        }
+        case PF_FAMILY_TRANSPOSE:
+            e = pf::launch_perm(plan->spec_id, L.main_dtype, a, plan->permg, plan->variant, plan->k, plan->grid, plan->block,
+                                plan->lds_bytes, st);
+            break;
+        default: return fail(PF_ERR_INVALID_ARG, "corrupt plan");
+    }
+    if (e != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return PF_OK;
+}
+
+void pf_chain_plan_destroy(pf_plan* plan) {
+    if (!plan) return;
+    if (plan->workspace) (void)hipFree(plan->workspace);
+    delete plan;
+}
+
+const char* pf_status_str(pf_status s) {
+    switch (s) {
+        case PF_OK: return "PF_OK";
+        case PF_ERR_INVALID_ARG: return "PF_ERR_INVALID_ARG";
+        case PF_ERR_SHAPE: return "PF_ERR_SHAPE";
+        case PF_ERR_DTYPE: return "PF_ERR_DTYPE";
+        case PF_ERR_UNSUPPORTED: return "PF_ERR_UNSUPPORTED";
+        case PF_ERR_ALIGNMENT: return "PF_ERR_ALIGNMENT";
+        case PF_ERR_ALIAS: return "PF_ERR_ALIAS";
+        case PF_ERR_NOMEM: return "PF_ERR_NOMEM";
+        case PF_ERR_HIP: return "PF_ERR_HIP";
+        default: return "PF_ERR_UNKNOWN";
+    }
+}
+
+const char* pf_last_error(void) { return g_last_error.c_str(); }
+
+pf_status pf_copy_probe(const void* src, void* dst, uint64_t bytes, int32_t variant, void* stream) {
+    if (!src || !dst) return fail(PF_ERR_INVALID_ARG, "null argument");
+    if (bytes % 16 != 0 || (uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0)
+        return fail(PF_ERR_ALIGNMENT, "copy probe needs 16-byte aligned pointers and size");
+    hipError_t e = pf::launch_copy_probe(src, dst, bytes, variant, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(PF_ERR_HIP, "copy probe launch failed: %s", hipGetErrorString(e));
+    return PF_OK;
+}
+
+}  // extern "C"

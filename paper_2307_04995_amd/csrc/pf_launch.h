@@ -1,0 +1,27 @@
+// Host-callable launchers of the kernel families (implemented in the .hip files).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "pf_common.h"
+
+namespace pf {
+
+hipError_t launch_row_generic(int dtype, const ChainArgs& a, const RowGeom& g, int k, bool reduce_only, dim3 grid,
+                              dim3 block, hipStream_t st);
+bool row_static_available(int spec_id, int k, unsigned block_threads);
+hipError_t launch_row_static(int spec_id, int dtype, const ChainArgs& a, const RowGeom& g, int k, dim3 grid, dim3 block,
+                             hipStream_t st);
+hipError_t launch_ew(int dtype, const ChainArgs& a, uint32_t total_vecs, uint32_t vecs_per_row, int k, dim3 grid,
+                     hipStream_t st);
+hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+                       dim3 block, uint32_t lds, hipStream_t st);
+hipError_t launch_group_stats(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, dim3 grid, dim3 block,
+                              hipStream_t st);
+hipError_t launch_group_apply(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, dim3 grid, dim3 block,
+                              hipStream_t st);
+hipError_t launch_group_resident(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, dim3 grid,
+                                 dim3 block, hipStream_t st);
+int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads);
+hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int variant, hipStream_t st);
+
+}  // namespace pf

@@ -1,0 +1,263 @@
+// Transpose family: prologue -> permutation of dimensions -> epilogue in one kernel.
+//
+// A layout change is a synchronisation step whose read and write slice patterns differ (paper section 4,
+// synchronisation gOperators).  Element-wise steps commute with it (section 5.1, gOperator swapping), so
+// the prologue runs on values addressed in the input layout, the epilogue on values addressed in the
+// output layout, and the permuted tensor itself never exists in HBM twice.
+//
+// Variants for permutations that keep the innermost dimension (every 16-byte vector moves intact):
+//   T_ROWS      each lane re-addresses its vector: one side of the transfer is contiguous per wave, the
+//               other side is contiguous in runs of the innermost extent;
+//   T_LDS_ROWS  a workgroup stages a [tile_a x tile_b] block of innermost rows in LDS between a read phase
+//               and a write phase, so both sides are walked in long contiguous runs.
+#include "pf_device.hpp"
+#include "pf_launch.h"
+#include "pf_row_kernels.hpp"
+#include "pf_specs.h"
+
+namespace pf {
+
+struct NoStoreT {
+    template <int DT, int K, class Spec>
+    PF_DEVICE void operator()(int, const LaneState<DT, K, Spec>&) const {}
+};
+
+// Split a vector index of the iteration space into element offsets on both sides.
+PF_DEVICE void perm_offsets(const PermGeom& g, uint32_t v, uint32_t vec, uint32_t* in_off, uint32_t* out_off) {
+    uint32_t io = 0, oo = 0, rem = v;
+#pragma unroll
+    for (int q = PF_DEV_MAX_RANK - 1; q >= 0; --q) {
+        if (q < g.rank) {
+            const uint32_t quo = (q == 0) ? 0u : fast_div(rem, g.div[q]);
+            const uint32_t idx = (q == 0) ? rem : rem - quo * g.extent[q];
+            const uint32_t scale = (q == g.rank - 1) ? vec : 1u;
+            io += idx * scale * g.in_stride[q];
+            oo += idx * scale * g.out_stride[q];
+            rem = quo;
+        }
+    }
+    *in_off = io;
+    *out_off = oo;
+}
+
+template <int DT, int K, class Spec>
+PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneState<DT, K, Spec>& s, const uint32_t* in_off,
+                                  const uint32_t* out_off, const bool* valid) {
+    using S = Storage<DT>;
+#pragma unroll
+    for (int f = 0; f < Spec::NF; ++f) {
+        if (f < Spec::n_full(a)) {
+            const bool epi = (g.epi_full_mask >> f) & 1u;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
+                if (valid[k]) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)(epi ? out_off[k] : in_off[k]) * S::ESIZE);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < Spec::NV; ++v) {
+        if (v < Spec::n_vec(a)) {
+            const bool epi = (g.epi_vec_mask >> v) & 1u;
+            const uint32_t inner = epi ? g.out_n_inner : g.in_n_inner;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
+                if (valid[k]) {
+                    const uint32_t off = epi ? out_off[k] : in_off[k];
+                    const uint32_t row = fast_div(off, epi ? g.div_out_inner : g.div_in_inner);
+                    s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, off - row * inner, inner);
+                }
+            }
+        }
+    }
+}
+
+template <int DT, int K, class Spec>
+PF_DEVICE void set_positions(LaneState<DT, K, Spec>& s, const uint32_t* off, const FastDiv& d, uint32_t inner) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        s.row[k] = fast_div(off[k], d);
+        s.col[k] = off[k] - s.row[k] * inner;
+    }
+}
+
+template <int DT, int K, class Spec>
+__global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    LaneState<DT, K, Spec> s;
+    uint32_t in_off[K], out_off[K];
+    bool valid[K];
+    const uint32_t base = blockIdx.x * (256u * K) + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t v = base + 256u * k;
+        valid[k] = v < g.total_vecs;
+        perm_offsets(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
+    }
+    perm_load_operands<DT, K, Spec>(a, g, s, in_off, out_off, valid);
+    set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
+    run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+    set_positions<DT, K, Spec>(s, out_off, g.div_out_inner, g.out_n_inner);
+    run_program<DT, K, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, S::pack(s.acc + k * VEC));
+}
+
+// LDS-staged variant for permutations that keep the innermost dimension and swap two outer dims A and B
+// (input order ... A, B, inner; output order ... B, A, inner).  A workgroup owns a tile of tile_a x tile_b
+// inner rows: it reads tile_a runs of tile_b * inner contiguous elements, runs the prologue, parks the
+// fp32 -> storage converted vectors in LDS, and after one barrier writes tile_b runs of tile_a * inner
+// contiguous elements, running the epilogue on the way out.  LDS traffic is 16 bytes per lane both ways
+// with consecutive lanes on consecutive 16-byte slots in the write phase and a stride of whole inner rows
+// in the read phase; a one-vector pad per staged row keeps the read phase off a single bank group.
+template <int DT, class Spec>
+__global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    extern __shared__ u32x4 tile[];
+    // iteration dims: [rank-3] = outer (merged batch), [rank-2]... are described by the host as:
+    //   extent[0] = batch, extent[1] = A tiles, extent[2] = B tiles; inner vectors = extent[3]
+    const uint32_t inner_v = g.extent[3];
+    const uint32_t ta = g.tile_a, tb = g.tile_b;
+    uint32_t blk = blockIdx.x;
+    const uint32_t bt = blk % g.extent[2];
+    blk /= g.extent[2];
+    const uint32_t at = blk % g.extent[1];
+    const uint32_t batch = blk / g.extent[1];
+    // element offsets of the tile origin on both sides
+    const uint32_t in_base = batch * g.in_stride[0] + at * ta * g.in_stride[1] + bt * tb * g.in_stride[2];
+    const uint32_t out_base = batch * g.out_stride[0] + at * ta * g.out_stride[1] + bt * tb * g.out_stride[2];
+    const uint32_t row_v = tb * inner_v;           // vectors per staged input run
+    const uint32_t pitch = row_v + 1u;             // padded LDS pitch in vectors
+    const uint32_t tile_v = ta * row_v;
+    LaneState<DT, 1, Spec> s;
+    // ---- read phase: input-contiguous
+    for (uint32_t v = threadIdx.x; v < tile_v; v += 256u) {
+        const uint32_t ai = v / row_v, r = v - ai * row_v;  // r = bi * inner_v + iv
+        const uint32_t in_off = in_base + ai * g.in_stride[1] + r * VEC;   // B and inner are contiguous in the input
+        const uint32_t bi = r / inner_v, iv = r - bi * inner_v;
+        const uint32_t out_off = out_base + bi * g.out_stride[2] + ai * g.out_stride[1] + iv * VEC;
+        const bool valid = true;
+        perm_load_operands<DT, 1, Spec>(a, g, s, &in_off, &out_off, &valid);
+        set_positions<DT, 1, Spec>(s, &in_off, g.div_in_inner, g.in_n_inner);
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+        set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+        tile[ai * pitch + r] = S::pack(s.acc);
+    }
+    __syncthreads();
+    // ---- write phase: output-contiguous (for each b: ta runs of inner)
+    const uint32_t orow_v = ta * inner_v;
+    for (uint32_t v = threadIdx.x; v < tile_v; v += 256u) {
+        const uint32_t bi = v / orow_v, r = v - bi * orow_v;  // r = ai * inner_v + iv
+        const uint32_t ai = r / inner_v, iv = r - ai * inner_v;
+        const uint32_t out_off = out_base + bi * g.out_stride[2] + r * VEC;  // A and inner are contiguous in the output
+        store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, tile[ai * pitch + bi * inner_v + iv]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int ID>
+struct PermSpecOf;
+#define PF_DEF_SPEC(id, nf, nv, nt, core, gamma, beta, pro, epi)                                              \
+    template <>                                                                                                \
+    struct PermSpecOf<id> {                                                                                    \
+        using type = StaticSpec<nf, nv, nt, core, gamma, beta, StaticList<pro>, StaticList<epi>>;              \
+    };
+PF_PERM_SPECS(PF_DEF_SPEC)
+#undef PF_DEF_SPEC
+template <>
+struct PermSpecOf<0> {
+    using type = GenericSpec;
+};
+
+template <int ID, int DT>
+static hipError_t launch_perm_spec_dt(const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid, dim3 block,
+                                      uint32_t lds, hipStream_t st) {
+    using Spec = typename PermSpecOf<ID>::type;
+    if (variant == 1) {
+        hipLaunchKernelGGL((perm_lds_rows_kernel<DT, Spec>), grid, block, lds, st, a, g);
+    } else if (k == 2) {
+        hipLaunchKernelGGL((perm_rows_kernel<DT, 2, Spec>), grid, block, 0, st, a, g);
+    } else {
+        hipLaunchKernelGGL((perm_rows_kernel<DT, 1, Spec>), grid, block, 0, st, a, g);
+    }
+    return hipGetLastError();
+}
+
+template <int ID>
+static hipError_t launch_perm_spec(int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+                                   dim3 block, uint32_t lds, hipStream_t st) {
+    switch (dtype) {
+        case DT_F32: return launch_perm_spec_dt<ID, DT_F32>(a, g, variant, k, grid, block, lds, st);
+        case DT_F16: return launch_perm_spec_dt<ID, DT_F16>(a, g, variant, k, grid, block, lds, st);
+        case DT_BF16: return launch_perm_spec_dt<ID, DT_BF16>(a, g, variant, k, grid, block, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+                       dim3 block, uint32_t lds, hipStream_t st) {
+    switch (spec_id) {
+        case 0: return launch_perm_spec<0>(dtype, a, g, variant, k, grid, block, lds, st);
+#define PF_CASE(id, ...) \
+    case id: return launch_perm_spec<id>(dtype, a, g, variant, k, grid, block, lds, st);
+            PF_PERM_SPECS(PF_CASE)
+#undef PF_CASE
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// copy probe: the plain streaming copy every chain is measured against
+// ---------------------------------------------------------------------------------------------
+template <int K, bool NT>
+__global__ void __launch_bounds__(256) copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n_vec) {
+    const uint64_t base = (uint64_t)blockIdx.x * (256u * K) + threadIdx.x;
+    u32x4 r[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t v = base + 256u * k;
+        r[k] = u32x4{0u, 0u, 0u, 0u};
+        if (v < n_vec) r[k] = NT ? __builtin_nontemporal_load(src + v) : src[v];
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t v = base + 256u * k;
+        if (v < n_vec) {
+            if (NT) __builtin_nontemporal_store(r[k], dst + v);
+            else dst[v] = r[k];
+        }
+    }
+}
+
+hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int variant, hipStream_t st) {
+    const uint64_t n_vec = bytes / 16;
+    if (n_vec == 0) return hipSuccess;
+    const u32x4* s = static_cast<const u32x4*>(src);
+    u32x4* d = static_cast<u32x4*>(dst);
+    // variant = unroll (1, 2, 4, 8) + 16 for plain (temporal) accesses
+    const bool nt = (variant & 16) == 0;
+    const int k = variant & 15;
+    const uint64_t per_block = 256ull * (uint64_t)(k ? k : 1);
+    const uint64_t blocks = (n_vec + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    dim3 grid((uint32_t)blocks), block(256);
+#define PF_COPY(KK)                                                                                   \
+    if (nt) hipLaunchKernelGGL((copy_probe_kernel<KK, true>), grid, block, 0, st, s, d, n_vec);       \
+    else hipLaunchKernelGGL((copy_probe_kernel<KK, false>), grid, block, 0, st, s, d, n_vec);
+    switch (k) {
+        case 1: PF_COPY(1) break;
+        case 2: PF_COPY(2) break;
+        case 4: PF_COPY(4) break;
+        case 8: PF_COPY(8) break;
+        default: return hipErrorInvalidValue;
+    }
+#undef PF_COPY
+    return hipGetLastError();
+}
+
+}  // namespace pf

@@ -1,0 +1,224 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, validates descriptions,
+infers shapes and maps chains to kernel families.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import workloads as wl
+from paper_2307_04995_amd import binding as pf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pf_chain.h")).read()
+    declared = set(re.findall(r"^\s*(?:pf_status|void|const char \*)\s*\*?(pf_[a-z_]+)\s*\(", header, flags=re.M))
+    assert {"pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
+            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_destroy", "pf_status_str", "pf_last_error",
+            "pf_copy_probe"} <= declared
+    lib = ctypes.CDLL(pf.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in pf_chain.h but not exported"
+    assert set(pf.EXPORTS) == declared
+
+
+def test_struct_layout_matches_header_constants():
+    d = pf.make_desc(wl.c3_bias_res_layernorm(rows=8, n=64)[0])
+    assert d.struct_size == ctypes.sizeof(pf.pf_chain_desc)
+    assert pf.pf_chain_validate(d) == pf.PF_OK
+    d.struct_size += 4
+    assert pf.pf_chain_validate(d) == pf.PF_ERR_INVALID_ARG
+    assert "struct_size" in pf.pf_last_error()
+
+
+def test_status_strings():
+    assert pf.pf_status_str(pf.PF_OK) == "PF_OK"
+    assert pf.pf_status_str(pf.PF_ERR_ALIAS) == "PF_ERR_ALIAS"
+    assert pf.pf_status_str(99) == "PF_ERR_UNKNOWN"
+
+
+def _plan_info(spec, variant=None):
+    plan = pf.Plan(spec, 0, variant)
+    info = plan.info()
+    shapes = plan.output_shapes()
+    plan.close()
+    return info, shapes
+
+
+def test_benchmark_chains_map_to_their_families():
+    info, shapes = _plan_info(wl.c1_bias_res_layernorm_gelu()[0])
+    assert (info.family, info.variant, info.n_launches) == (pf.PF_FAMILY_ROW, pf.PF_VARIANT_ROW_BLOCK, 1)
+    assert info.spec_id > 0 and list(info.block)[0] == 192 and list(info.grid)[0] == 256
+    assert info.compulsory_read_bytes + info.compulsory_write_bytes == 2368512
+    assert shapes == [(256, 768)]
+
+    info, shapes = _plan_info(wl.c2_causal_softmax(b=8, h=12, s=512)[0].__class__(
+        inputs=[("f16", (8, 12, 512, 512))], ops=wl.c2_causal_softmax(b=1, h=1, s=8)[0].ops,
+        outputs=wl.c2_causal_softmax(b=1, h=1, s=8)[0].outputs))
+    assert (info.family, info.variant) == (pf.PF_FAMILY_ROW, pf.PF_VARIANT_ROW_WAVE)
+    assert info.spec_id > 0 and info.vectors_per_lane == 1
+    assert info.compulsory_read_bytes + info.compulsory_write_bytes == 100663296
+
+    spec = wl.ChainSpec(inputs=[("f16", (16384, 1024)), ("f16", (16384, 1024)), ("f16", (1024,)), ("f16", (1024,)),
+                                ("f16", (1024,))])
+    v = spec.op("add", 0, 2)
+    v = spec.op("add", v, 1)
+    v = spec.op("layernorm", v, 3, 4, f=[1e-5])
+    spec.out(v, "f16")
+    info, _ = _plan_info(spec)
+    assert (info.family, info.variant, info.vectors_per_lane) == (pf.PF_FAMILY_ROW, pf.PF_VARIANT_ROW_WAVE, 2)
+    assert info.compulsory_read_bytes + info.compulsory_write_bytes == 100669440
+
+    spec = wl.ChainSpec(inputs=[("bf16", (32, 512, 16, 64)), ("bf16", (16, 64))])
+    v = spec.op("add", 0, 1)
+    v = spec.op("scale", v, f=[0.125])
+    v = spec.op("permute", v, i=[0, 2, 1, 3])
+    spec.out(v, "bf16")
+    info, shapes = _plan_info(spec)
+    assert info.family == pf.PF_FAMILY_TRANSPOSE and info.spec_id > 0
+    assert shapes == [(32, 16, 512, 64)]
+    assert info.compulsory_read_bytes + info.compulsory_write_bytes == 67110912
+    info, _ = _plan_info(spec, variant=pf.PF_VARIANT_T_LDS_ROWS)
+    assert info.variant == pf.PF_VARIANT_T_LDS_ROWS and 0 < info.lds_bytes <= 48 * 1024
+
+
+def test_generic_chain_uses_interpreter():
+    spec = wl.ChainSpec(inputs=[("f32", (10, 256)), ("f32", (256,))])
+    v = spec.op("tanh", 0)
+    v = spec.op("mul", v, 1)
+    v = spec.op("softmax", v)
+    v = spec.op("relu", v)
+    spec.out(v, "f32")
+    info, _ = _plan_info(spec)
+    assert info.family == pf.PF_FAMILY_ROW and info.spec_id == 0 and info.n_micro_ops == 4
+
+
+def test_infer_shape():
+    spec, _ = wl.c4_bias_scale_permute(b=2, s=3, h=4, d=8)
+    d = pf.make_desc(spec)
+    st, t = pf.pf_chain_infer_shape(d, 4)          # the permute result
+    assert st == pf.PF_OK and [t.shape[k] for k in range(t.rank)] == [2, 4, 3, 8]
+    st, t = pf.pf_chain_infer_shape(d, 1)          # bias input
+    assert st == pf.PF_OK and t.dtype == pf.PF_BF16 and t.rank == 2
+    st, t = pf.pf_chain_infer_shape(d, 9)
+    assert st == pf.PF_ERR_INVALID_ARG and t is None
+    red = wl.ChainSpec(inputs=[("f32", (3, 5, 8))])
+    red.out(red.op("reduce_max", 0), "f32")
+    st, t = pf.pf_chain_infer_shape(pf.make_desc(red), 1)
+    assert [t.shape[k] for k in range(t.rank)] == [3, 5, 1]
+
+
+def _status_of(spec):
+    return pf.pf_chain_validate(pf.make_desc(spec))
+
+
+def test_validation_errors():
+    s = wl.ChainSpec(inputs=[("f32", (4, 8)), ("f32", (4,))])
+    s.out(s.op("add", 0, 1), "f32")                      # [4] is not a trailing shape of [4, 8]
+    assert _status_of(s) == pf.PF_ERR_SHAPE
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8))])
+    s.ops.append(wl.OpSpec("add", (0,)))                 # wrong arity
+    s.out(1, "f32")
+    assert _status_of(s) == pf.PF_ERR_INVALID_ARG
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8))])
+    s.ops.append(wl.OpSpec("relu", (3,)))                # operand id in the future
+    s.out(1, "f32")
+    assert _status_of(s) == pf.PF_ERR_INVALID_ARG
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8))])
+    s.out(s.op("permute", 0, i=[0, 0]), "f32")
+    assert _status_of(s) == pf.PF_ERR_INVALID_ARG
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8)), ("f32", (4,)), ("f32", (8,))])
+    s.out(s.op("layernorm", 0, 1, 2, f=[1e-5]), "f32")   # gamma has the wrong length
+    assert _status_of(s) == pf.PF_ERR_SHAPE
+
+    s = wl.ChainSpec(inputs=[("f32", (2, 4, 12)), ("f32", (12,)), ("f32", (12,))])
+    s.out(s.op("groupnorm", 0, 1, 2, f=[1e-5], i=[5]), "f32")   # 5 does not divide 12
+    assert _status_of(s) == pf.PF_ERR_INVALID_ARG
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8))])
+    s.out(s.op("reshape", 0, i=[5, 8]), "f32")
+    assert _status_of(s) == pf.PF_ERR_SHAPE
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 8))])
+    s.op("relu", 0)
+    s.out(0, "f32")                                      # an input is not an output
+    assert _status_of(s) == pf.PF_ERR_INVALID_ARG
+
+    s = wl.ChainSpec(inputs=[("f32", (8,))])
+    s.out(s.op("causal_mask", 0), "f32")
+    assert _status_of(s) == pf.PF_ERR_SHAPE
+
+    d = pf.make_desc(wl.c3_bias_res_layernorm(rows=8, n=64)[0])
+    d.inputs[0].dtype = 7
+    assert pf.pf_chain_validate(d) == pf.PF_ERR_DTYPE
+    d = pf.make_desc(wl.c3_bias_res_layernorm(rows=8, n=64)[0])
+    d.ops[2].f[0] = -1.0
+    assert pf.pf_chain_validate(d) == pf.PF_ERR_INVALID_ARG
+
+
+def _plan_status(spec, variant=None):
+    d = pf.make_desc(spec)
+    st, h = (pf.pf_chain_plan(d, 0) if variant is None else pf.pf_chain_plan_variant(d, 0, variant))
+    if h is not None:
+        pf.pf_chain_plan_destroy(h)
+    return st
+
+
+def test_plan_errors():
+    # ragged innermost extent
+    s = wl.ChainSpec(inputs=[("f16", (4, 12))])
+    s.out(s.op("softmax", 0), "f16")
+    assert _plan_status(s) == pf.PF_ERR_ALIGNMENT
+    # two cores
+    s = wl.ChainSpec(inputs=[("f16", (4, 16))])
+    v = s.op("softmax", 0)
+    s.out(s.op("softmax", v), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    assert "one reduce" in pf.pf_last_error()
+    # mixed dtypes
+    s = wl.ChainSpec(inputs=[("f16", (4, 16)), ("f32", (16,))])
+    s.out(s.op("add", 0, 1), "f16")
+    assert _plan_status(s) == pf.PF_ERR_DTYPE
+    # row too long for one workgroup's registers
+    s = wl.ChainSpec(inputs=[("f32", (2, 65536))])
+    s.out(s.op("softmax", 0), "f32")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # innermost-changing permutation is not implemented yet
+    s = wl.ChainSpec(inputs=[("f16", (8, 64, 64))])
+    s.out(s.op("permute", 0, i=[0, 2, 1]), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # a value computed before the core is used after it
+    s = wl.ChainSpec(inputs=[("f32", (4, 64))])
+    a = s.op("relu", 0)
+    b = s.op("softmax", a)
+    s.out(s.op("add", b, a), "f32")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # forcing a variant the shape does not allow
+    s = wl.ChainSpec(inputs=[("f32", (4, 8192))])
+    s.out(s.op("softmax", 0), "f32")
+    assert _plan_status(s, variant=pf.PF_VARIANT_ROW_WAVE) == pf.PF_ERR_UNSUPPORTED
+    assert _plan_status(s) == pf.PF_OK
+    # the last operator's result has to be an output
+    s = wl.ChainSpec(inputs=[("f32", (4, 64))])
+    a = s.op("relu", 0)
+    s.op("neg", a)
+    s.out(a, "f32")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+
+
+def test_null_arguments_are_errors_not_crashes():
+    lib = ctypes.CDLL(pf.LIB_PATH)
+    lib.pf_chain_validate.argtypes = [ctypes.c_void_p]
+    assert lib.pf_chain_validate(None) == pf.PF_ERR_INVALID_ARG
+    lib.pf_chain_plan_get_info.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.pf_chain_plan_get_info(None, None) == pf.PF_ERR_INVALID_ARG
+    lib.pf_chain_run.argtypes = [ctypes.c_void_p] * 4
+    assert lib.pf_chain_run(None, None, None, None) == pf.PF_ERR_INVALID_ARG
+    lib.pf_chain_plan_destroy.argtypes = [ctypes.c_void_p]
+    lib.pf_chain_plan_destroy(None)

@@ -1,0 +1,284 @@
+"""GPU parity: every kernel family, through the C ABI, element by element against the fp64 oracle on the
+same seeded inputs, at sizes that span several tiles and a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from pf_testlib import check_chain, compare, gpu_run, oracle_run
+
+pytestmark = pytest.mark.gpu
+
+
+def _pf():
+    from paper_2307_04995_amd import binding as pf
+    return pf
+
+
+# ------------------------------------------------------------------ the five benchmark chains, reduced
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("rows,n,dtype", [(37, 768, "f32"), (5, 256, "f32"), (67, 1024, "f16"), (9, 2048, "bf16")])
+def test_c1_chain(rows, n, dtype, generic):
+    spec, ins = wl.c1_bias_res_layernorm_gelu(rows=rows, n=n, dtype=dtype)
+    _, info, _ = check_chain(spec, ins, generic=generic, what=f"C1 {rows}x{n} {dtype}")
+    assert info.family == _pf().PF_FAMILY_ROW and info.n_launches == 1
+    assert (info.spec_id == 0) == generic
+
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("b,h,s,dtype", [(2, 3, 64, "f16"), (1, 2, 512, "f16"), (1, 1, 136, "bf16"), (1, 2, 48, "f32")])
+def test_c2_chain(b, h, s, dtype, generic):
+    spec, ins = wl.c2_causal_softmax(b=b, h=h, s=s, dtype=dtype)
+    outs, info, _ = check_chain(spec, ins, generic=generic, what=f"C2 {b}x{h}x{s} {dtype}")
+    y = wl.widen(outs[0])
+    iu = np.triu_indices(s, k=1)
+    assert np.all(y[..., iu[0], iu[1]] == 0.0), "masked positions must be exactly zero"
+    assert info.family == _pf().PF_FAMILY_ROW
+
+
+def test_c2_rectangular_scores():
+    # more keys than queries: the mask still compares column against row of the last two dims
+    spec, ins = wl.c2_causal_softmax(b=1, h=2, s=40, s_k=72, dtype="f16")
+    check_chain(spec, ins, what="C2 rectangular")
+
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("rows,n,dtype", [(131, 1024, "f16"), (7, 512, "f16"), (33, 1024, "bf16"), (10, 384, "f32")])
+def test_c3_chain(rows, n, dtype, generic):
+    spec, ins = wl.c3_bias_res_layernorm(rows=rows, n=n, dtype=dtype)
+    check_chain(spec, ins, generic=generic, what=f"C3 {rows}x{n} {dtype}")
+
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("b,s,h,d,dtype", [(2, 48, 16, 64, "bf16"), (1, 32, 4, 32, "f16"), (3, 16, 8, 16, "f32")])
+def test_c4_chain(b, s, h, d, dtype, variant, generic):
+    spec, ins = wl.c4_bias_scale_permute(b=b, s=s, h=h, d=d, dtype=dtype)
+    outs, info, _ = check_chain(spec, ins, variant=variant, generic=generic, what=f"C4 {dtype} v{variant}")
+    assert info.family == _pf().PF_FAMILY_TRANSPOSE and info.variant == variant
+    # layout part, bit-exact: the same element-wise chain without the permutation, permuted on the host
+    flat = wl.ChainSpec(inputs=list(spec.inputs))
+    v = flat.op("add", 0, 1)
+    v = flat.op("scale", v, f=[0.125])
+    flat.out(v, dtype)
+    (unpermuted,), _ = gpu_run(flat, ins)
+    want_bits = np.transpose(wl.raw_bits(unpermuted), (0, 2, 1, 3))
+    assert np.array_equal(wl.raw_bits(outs[0]), want_bits), "fused permutation is not a bit-exact re-layout"
+
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("n,h,w,c,g,dtype", [(2, 16, 16, 512, 32, "f16"), (3, 7, 9, 64, 4, "f16"), (1, 24, 24, 256, 8, "bf16"),
+                                             (2, 5, 5, 32, 2, "f32")])
+def test_c5_chain(n, h, w, c, g, dtype, variant, generic):
+    pf = _pf()
+    spec, ins = wl.c5_groupnorm_silu(n=n, h=h, w=w, ch=c, groups=g, dtype=dtype)
+    if variant == 1 and generic:
+        pytest.skip("the register-resident variant exists for catalogue chains only")
+    _, info, _ = check_chain(spec, ins, variant=variant, generic=generic, what=f"C5 {dtype} v{variant}")
+    assert info.family == pf.PF_FAMILY_GROUP and info.variant == variant
+    assert info.n_launches == (2 if variant == 0 else 1)
+
+
+# ------------------------------------------------------------------ layout-only chains, bit-exact
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((2, 24, 16, 64), (0, 2, 1, 3)), ((6, 5, 32), (1, 0, 2)), ((2, 3, 4, 5, 16), (3, 0, 2, 1, 4)),
+                                        ((4, 8, 8), (0, 1, 2))])
+def test_permute_only_bit_exact(shape, perm, dtype):
+    from oracle import pf_oracle as orc
+    g = np.random.default_rng(99)
+    nbits = 32 if dtype == "f32" else 16
+    bits = g.integers(0, 1 << nbits, size=shape, dtype=np.uint32 if nbits == 32 else np.uint16)
+    view = {"f32": torch.int32, "f16": torch.int16, "bf16": torch.int16}[dtype]
+    t = torch.from_numpy(bits.view(np.int32 if nbits == 32 else np.int16)).view(wl.DTYPES[dtype])
+    spec = wl.ChainSpec(inputs=[(dtype, shape)])
+    spec.out(spec.op("permute", 0, i=perm), dtype)
+    for variant in (None,):
+        (out,), info = gpu_run(spec, [t], variant=variant)
+        (want,) = orc.evaluate_layout_bits(spec, [bits])
+        assert np.array_equal(wl.raw_bits(out), want)
+
+
+# ------------------------------------------------------------------ other cores and the element-wise family
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_rmsnorm_and_residual(dtype):
+    rows, n = 45, 640
+    x = wl.random_tensor((rows, n), dtype, 1)
+    res = wl.random_tensor((rows, n), dtype, 2)
+    gamma = wl.random_tensor((n,), dtype, 3)
+    spec = wl.ChainSpec(inputs=[(dtype, (rows, n)), (dtype, (rows, n)), (dtype, (n,))])
+    v = spec.op("add", 0, 1)
+    v = spec.op("rmsnorm", v, 2, f=[1e-6])
+    spec.out(v, dtype)
+    check_chain(spec, [x, res, gamma], what="rmsnorm")
+    check_chain(spec, [x, res, gamma], generic=True, what="rmsnorm generic")
+
+
+@pytest.mark.parametrize("n", [8, 200, 1024, 4096, 12288])
+def test_softmax_row_lengths(n):
+    rows = 11
+    x = wl.random_tensor((rows, n), "f16", n, scale=3.0)
+    spec = wl.ChainSpec(inputs=[("f16", (rows, n))])
+    spec.out(spec.op("softmax", 0), "f16")
+    _, info, _ = check_chain(spec, [x], what=f"softmax n={n}")
+    y, _ = gpu_run(spec, [x])
+    np.testing.assert_allclose(wl.widen(y[0]).sum(-1), 1.0, atol=4e-3)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_layernorm_wave_and_block_variants_agree_with_oracle(variant):
+    rows, n = 19, 1024
+    spec, ins = wl.c3_bias_res_layernorm(rows=rows, n=n, dtype="f16", salt=3)
+    _, info, _ = check_chain(spec, ins, variant=variant, what=f"LN variant {variant}")
+    assert info.variant == variant
+
+
+@pytest.mark.parametrize("op", ["reduce_sum", "reduce_max", "reduce_mean"])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_reduce_keepdim(op, dtype):
+    rows, n = 23, 520
+    x = wl.random_tensor((rows, n), dtype, 5, scale=0.5)
+    spec = wl.ChainSpec(inputs=[(dtype, (rows, n))])
+    v = spec.op("scale", 0, f=[0.5])
+    v = spec.op(op, v)
+    v = spec.op("addc", v, f=[1.0])
+    spec.out(v, dtype)
+    outs, info, _ = check_chain(spec, [x], what=op)
+    assert tuple(outs[0].shape) == (rows, 1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_elementwise_chain_with_broadcasts(dtype):
+    shape = (3, 5, 7, 64)
+    x = wl.random_tensor(shape, dtype, 11)
+    y = wl.random_tensor(shape, dtype, 12, dist="positive")
+    bias = wl.random_tensor((64,), dtype, 13)
+    plane = wl.random_tensor((7, 64), dtype, 14)
+    spec = wl.ChainSpec(inputs=[(dtype, shape), (dtype, shape), (dtype, (64,)), (dtype, (7, 64))])
+    v = spec.op("add", 0, 2)          # + bias[64]
+    v = spec.op("div", v, 1)          # / y
+    v = spec.op("sub", 3, v)          # plane[7,64] - v   (broadcast operand on the left)
+    v = spec.op("gelu_erf", v)
+    v = spec.op("max", v, 2)
+    spec.out(v, dtype)
+    _, info, _ = check_chain(spec, [x, y, bias, plane], what="elementwise chain")
+    assert info.family == _pf().PF_FAMILY_ELEMENTWISE
+
+
+@pytest.mark.parametrize("name", ["relu", "sigmoid", "silu", "gelu_erf", "tanh", "exp", "neg"])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_unary_ops(name, dtype):
+    x = wl.random_tensor((6, 1000 if dtype == "f32" else 1024), dtype, 21, scale=2.0)
+    spec = wl.ChainSpec(inputs=[(dtype, tuple(x.shape))])
+    spec.out(spec.op(name, 0), dtype)
+    check_chain(spec, [x], what=name)
+
+
+def test_rsqrt_and_min():
+    x = wl.random_tensor((4, 256), "f32", 22, dist="positive", scale=4.0)
+    spec = wl.ChainSpec(inputs=[("f32", (4, 256))])
+    v = spec.op("rsqrt", 0)
+    v = spec.op("min", v, 0)
+    spec.out(v, "f32")
+    check_chain(spec, [x], what="rsqrt/min")
+
+
+def test_silu_composite_equals_decomposition():
+    # SiLU given as one op and as sigmoid followed by multiply (needs a temporary) must agree
+    x = wl.random_tensor((9, 512), "f32", 23, scale=3.0)
+    a = wl.ChainSpec(inputs=[("f32", (9, 512))])
+    a.out(a.op("silu", 0), "f32")
+    b = wl.ChainSpec(inputs=[("f32", (9, 512))])
+    s = b.op("sigmoid", 0)
+    b.out(b.op("mul", 0, s), "f32")
+    (ya,), _ = gpu_run(a, [x])
+    (yb,), _ = gpu_run(b, [x])
+    np.testing.assert_allclose(ya.numpy(), yb.numpy(), rtol=0, atol=1e-6)
+    check_chain(b, [x], what="decomposed silu")
+
+
+def test_dag_chain_with_temporaries():
+    # y = (x*x + x) * tanh(x) -> LayerNorm: values reused out of order force SAVE / TMP steps
+    rows, n = 13, 256
+    x = wl.random_tensor((rows, n), "f32", 24)
+    gamma = wl.random_tensor((n,), "f32", 25)
+    beta = wl.random_tensor((n,), "f32", 26)
+    spec = wl.ChainSpec(inputs=[("f32", (rows, n)), ("f32", (n,)), ("f32", (n,))])
+    sq = spec.op("mul", 0, 0)
+    s = spec.op("add", sq, 0)
+    t = spec.op("tanh", 0)
+    v = spec.op("mul", s, t)
+    v = spec.op("layernorm", v, 1, 2, f=[1e-5])
+    spec.out(v, "f32")
+    check_chain(spec, [x, gamma, beta], what="dag chain")
+
+
+def test_two_outputs_residual_stream():
+    rows, n = 21, 1024
+    x = wl.random_tensor((rows, n), "f16", 31)
+    res = wl.random_tensor((rows, n), "f16", 32)
+    gamma = wl.random_tensor((n,), "f16", 33)
+    beta = wl.random_tensor((n,), "f16", 34)
+    spec = wl.ChainSpec(inputs=[("f16", (rows, n)), ("f16", (rows, n)), ("f16", (n,)), ("f16", (n,))])
+    h = spec.op("add", 0, 1)
+    y = spec.op("layernorm", h, 2, 3, f=[1e-5])
+    spec.out(y, "f16")
+    spec.out(h, "f16")
+    check_chain(spec, [x, res, gamma, beta], what="two outputs")
+
+
+def test_reshape_is_free():
+    x = wl.random_tensor((4, 6, 128), "f16", 41)
+    spec = wl.ChainSpec(inputs=[("f16", (4, 6, 128))])
+    v = spec.op("reshape", 0, i=[24, 128])
+    v = spec.op("softmax", v)
+    v = spec.op("reshape", v, i=[4, 6, 128])
+    spec.out(v, "f16")
+    outs, _, _ = check_chain(spec, [x], what="reshape")
+    assert tuple(outs[0].shape) == (4, 6, 128)
+
+
+def test_in_place_row_chain():
+    pf = _pf()
+    spec, ins = wl.c3_bias_res_layernorm(rows=40, n=1024, dtype="f16", salt=5)
+    dev = [t.cuda() for t in ins]
+    want = oracle_run(spec, ins)[0]
+    plan = pf.Plan(spec, 0)
+    plan.run(dev, [dev[0]])          # output aliases x exactly
+    torch.cuda.synchronize()
+    compare(dev[0].cpu(), want, "f16", "in place")
+    plan.close()
+
+
+def test_run_rejects_bad_pointers():
+    pf = _pf()
+    spec, ins = wl.c4_bias_scale_permute(b=1, s=16, h=4, d=32)
+    dev = [t.cuda() for t in ins]
+    out = torch.empty((1, 4, 16, 32), dtype=torch.bfloat16, device="cuda")
+    plan = pf.Plan(spec, 0)
+    st = pf.pf_chain_run(plan.handle, [dev[0].data_ptr() + 2, dev[1].data_ptr()], [out.data_ptr()], 0)
+    assert st == pf.PF_ERR_ALIGNMENT
+    st = pf.pf_chain_run(plan.handle, [dev[0].data_ptr(), dev[1].data_ptr()], [dev[0].data_ptr()], 0)
+    assert st == pf.PF_ERR_ALIAS                      # the transpose family cannot run in place
+    st = pf.pf_chain_run(plan.handle, [0, dev[1].data_ptr()], [out.data_ptr()], 0)
+    assert st == pf.PF_ERR_INVALID_ARG
+    plan.close()
+
+
+def test_non_default_stream_and_repeated_runs():
+    pf = _pf()
+    spec, ins = wl.c5_groupnorm_silu(n=2, h=16, w=16, ch=512, groups=32, dtype="f16", salt=2)
+    dev = [t.cuda() for t in ins]
+    want = oracle_run(spec, ins)[0]
+    plan = pf.Plan(spec, 0)
+    out = torch.empty_like(dev[0])
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(5):           # the resident variant's arrival counters must survive re-launches
+            plan.run(dev, [out], stream.cuda_stream)
+    stream.synchronize()
+    compare(out.cpu(), want, "f16", "repeated runs")
+    plan.close()
