@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-chain hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: one `pf_chain_run` of the headline chain
+(benchmark configs[1]: fp16 scale -> causal mask -> softmax on [8, 12, 512, 512]) with its inputs already
+resident in HBM.  Successive steps rotate over enough buffer sets (> 600 MB in total) that no step finds
+its data in the 256 MB last-level cache: the number printed is the cold, HBM-bound one.
+
+One JSON line is printed.  `value` is GB/s of the bytes the chain has to move (inputs once + outputs once;
+for the causal chain the 16-byte vectors that lie wholly above the diagonal are never needed and are not
+counted).  `roofline` prices the same kernel against the 8 TB/s HBM peak from the average launch duration
+measured with HIP events on the launch stream.  `cpu_baseline` is the fp64 oracle timed on the host cores on
+a bounded sample of the same workload.  `chains` adds the same measurement for the other four benchmark
+chains and a plain copy kernel, for context.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+ROTATE_BYTES = 640 * 1024 * 1024
+
+
+def causal_needed_read_bytes(b, h, s, s_k, esize):
+    """Bytes of the score tensor that are not wholly masked 16-byte vectors."""
+    vec = 16 // esize
+    per_matrix = 0
+    for i in range(s):
+        keep = min(s_k, i + 1)
+        per_matrix += ((keep + vec - 1) // vec) * 16
+    return b * h * per_matrix
+
+
+def full_size_chain(name):
+    """(spec, inputs, algorithmic bytes, nominal bytes, label) at the benchmark's full size."""
+    import workloads as wl
+    spec, ins = wl.CONFIGS[name]()
+    esz = {"f32": 4, "f16": 2, "bf16": 2}
+    nominal = sum(t.numel() * t.element_size() for t in ins)
+    out_bytes = 0
+    import numpy as np
+    from paper_2307_04995_amd import binding as pf
+    plan = pf.Plan(spec, 0)
+    for shape, (_, dt) in zip(plan.output_shapes(), spec.outputs):
+        out_bytes += int(np.prod(shape)) * esz[dt]
+    plan.close()
+    nominal += out_bytes
+    algorithmic = nominal
+    if name == "C2":
+        b, h, s, s_k = spec.inputs[0][1]
+        algorithmic = causal_needed_read_bytes(b, h, s, s_k, 2) + out_bytes
+    labels = {
+        "C1": "C1 fp32 x+res+bias -> LayerNorm -> GELU(erf) [256x768]",
+        "C2": "C2 fp16 scale -> causal mask -> softmax [8,12,512,512]",
+        "C3": "C3 fp16 x+bias+res -> LayerNorm [16384x1024]",
+        "C4": "C4 bf16 (Q+bias)*0.125 -> permute [32,512,16,64]->[32,16,512,64]",
+        "C5": "C5 fp16 NHWC GroupNorm(32)+SiLU [16,64,64,512]",
+    }
+    return spec, ins, algorithmic, nominal, labels[name]
+
+
+def time_chain(spec, ins, steps, warmup, variant=None):
+    """Returns (ms per step from host clock, ms per launch from HIP events, plan info)."""
+    import numpy as np
+    import torch
+    from paper_2307_04995_amd import binding as pf
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    plan = pf.Plan(spec, 0, variant)
+    info = plan.info()
+    shapes = plan.output_shapes()
+    per_set = sum(t.numel() * t.element_size() for t in ins)
+    per_set += sum(int(np.prod(s)) * {"f32": 4, "f16": 2, "bf16": 2}[dt] for s, (_, dt) in zip(shapes, spec.outputs))
+    n_sets = max(3, min(64, -(-ROTATE_BYTES // per_set)))
+    base = [t.cuda() for t in ins]
+    sets = []
+    for k in range(n_sets):
+        # broadcast operands (a few KB) are shared; streamed tensors get their own copy per set
+        i_k = [t if t.numel() * t.element_size() < 65536 else t.clone() for t in base]
+        o_k = [torch.empty(s, dtype=tdt[dt], device="cuda") for s, (_, dt) in zip(shapes, spec.outputs)]
+        sets.append(([t.data_ptr() for t in i_k], [t.data_ptr() for t in o_k], i_k, o_k))
+    stream = torch.cuda.current_stream().cuda_stream
+    for k in range(warmup):
+        ip, op, _, _ = sets[k % n_sets]
+        plan.run_ptrs(ip, op, stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for k in range(steps):
+        ip, op, _, _ = sets[k % n_sets]
+        plan.run_ptrs(ip, op, stream)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    host_ms = (t1 - t0) * 1e3 / steps
+    event_ms = ev0.elapsed_time(ev1) / steps
+    plan.close()
+    del sets
+    torch.cuda.empty_cache()
+    return host_ms, event_ms, info
+
+
+def time_copy(nbytes, steps, warmup, variant=2):
+    import torch
+    from paper_2307_04995_amd import binding as pf
+    n_sets = max(3, -(-ROTATE_BYTES // (2 * nbytes)))
+    bufs = [(torch.empty(nbytes, dtype=torch.uint8, device="cuda"), torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
+            for _ in range(n_sets)]
+    for a, _ in bufs:
+        a.fill_(1)
+    stream = torch.cuda.current_stream().cuda_stream
+    for k in range(warmup):
+        a, b = bufs[k % n_sets]
+        pf.pf_copy_probe(a.data_ptr(), b.data_ptr(), nbytes, variant, stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for k in range(steps):
+        a, b = bufs[k % n_sets]
+        st = pf.pf_copy_probe(a.data_ptr(), b.data_ptr(), nbytes, variant, stream)
+        if st != 0:
+            raise RuntimeError(pf.pf_last_error())
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps
+
+
+def cpu_baseline(budget_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the headline workload."""
+    import workloads as wl
+    from oracle import pf_oracle as orc
+    threads = orc.max_threads()
+    orc.set_threads(threads)
+    heads = 2
+    best = None
+    while True:
+        spec, ins = wl.c2_causal_softmax(b=1, h=heads, s=512)
+        wide = [wl.widen(t) for t in ins]
+        t0 = time.perf_counter()
+        orc.evaluate_outputs(spec, wide)
+        dt = time.perf_counter() - t0
+        esz = 2
+        nbytes = causal_needed_read_bytes(1, heads, 512, 512, esz) + heads * 512 * 512 * esz
+        best = (nbytes / dt / 1e9, heads, dt)
+        if dt * 4 > budget_s or heads >= 96:
+            break
+        heads *= 4
+    gbps, heads, dt = best
+    return {"value": round(gbps, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"scores [1,{heads},512,512] of the [8,12,512,512] workload, one pass, {dt:.2f} s, fp64 unfused"}
+
+
+def read_traffic(name):
+    """HBM bytes per launch from the committed counter summary (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(name, {}).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--only", default="", help="comma-separated subset of C1..C5 for the context block")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-context", action="store_true", help="time the headline chain only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every chain shards by rows with no exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    headline = "C2"
+    spec, ins, alg_bytes, nominal_bytes, label = full_size_chain(headline)
+    host_ms, event_ms, info = time_chain(spec, ins, args.steps, args.warmup)
+    achieved = alg_bytes / (event_ms * 1e-3) / 1e9
+    result = {
+        "metric": "achieved HBM GB/s (fraction of MI355X peak) per fused chain; us per call",
+        "value": round(alg_bytes / (host_ms * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(host_ms, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": label, "storage": "fp16", "bytes_per_step": alg_bytes, "nominal_bytes_per_step": nominal_bytes,
+                   "us_per_call": round(host_ms * 1e3, 3), "family": info.family, "variant": info.variant,
+                   "spec_id": info.spec_id, "buffers": "rotating, > 600 MB (cold)"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(headline),
+                     "kernel_us": round(event_ms * 1e3, 3), "nominal_gbps": round(nominal_bytes / (event_ms * 1e-3) / 1e9, 1)},
+    }
+    if not args.no_context:
+        chains = {}
+        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5"]) if c]
+        for name in wanted:
+            s2, i2, alg2, nom2, lab2 = full_size_chain(name)
+            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2))
+            chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
+                            "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2,
+                            "variant": inf2.variant, "spec_id": inf2.spec_id, "launches": inf2.n_launches,
+                            "traffic": read_traffic(name)}
+            del s2, i2
+        nbytes = 64 * 1024 * 1024
+        best = None
+        for variant in (1, 2, 4):
+            ms = time_copy(nbytes, 100, 10, variant)
+            g = 2 * nbytes / (ms * 1e-3) / 1e9
+            if best is None or g > best[0]:
+                best = (g, variant, ms)
+        chains["copy_probe"] = {"workload": "plain 16-byte copy, 64 MiB in + 64 MiB out", "gbps": round(best[0], 1),
+                                "frac_of_peak": round(best[0] / HBM_PEAK_GBPS, 4), "us_per_call": round(best[2] * 1e3, 3),
+                                "unroll": best[1]}
+        result["chains"] = chains
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

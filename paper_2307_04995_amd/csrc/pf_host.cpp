@@ -310,6 +310,7 @@ struct Lowerer {
     // keep the accumulator's value if something still needs it
     bool spill_acc_if_live(int consumed_now) {
         if (acc_val < 0) return true;
+        if (acc_val < d->n_inputs) return true;  // an input can always be fetched again from its operand slot
         if (uses[acc_val] - consumed_now <= 0) return true;
         if (loc[acc_val].kind == LOC_TMP) return true;
         for (int t = 0; t < PF_DEV_MAX_TMP; ++t)
@@ -413,14 +414,18 @@ struct Lowerer {
         uint8_t code, kind, slot;
         if (a == b) {
             if (!load_acc(a)) return false;
-            // the same value on both sides: park a copy in a temporary
-            if (loc[a].kind != LOC_TMP && !spill_acc_if_live(0)) return false;  // uses[a] >= 2: this saves it
-            if (loc[a].kind != LOC_TMP) {
-                status = fail(PF_ERR_UNSUPPORTED, "internal: operand used twice could not be parked");
-                return false;
+            if (a < d->n_inputs) {
+                if (!operand_of(a, &kind, &slot)) return false;  // the same input on both sides
+            } else {
+                // the same computed value on both sides: park a copy in a temporary
+                if (loc[a].kind != LOC_TMP && !spill_acc_if_live(0)) return false;  // uses[a] >= 2: this saves it
+                if (loc[a].kind != LOC_TMP) {
+                    status = fail(PF_ERR_UNSUPPORTED, "internal: operand used twice could not be parked");
+                    return false;
+                }
+                kind = pf::K_TMP;
+                slot = (uint8_t)loc[a].slot;
             }
-            kind = pf::K_TMP;
-            slot = (uint8_t)loc[a].slot;
             code = fwd[o.op];
             if (!emit(code, kind, slot)) return false;
             consume(a);
@@ -725,7 +730,10 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "row length %lld is not a multiple of 16 bytes", (long long)n);
     if (rows > 0xffffffffLL || n > 0x7fffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the row family");
     const int64_t vpr = n / vec;
-    // candidates (waves per row, vectors per lane); prefer little idle lanes, small workgroups, a single wave
+    // candidates (waves per row, vectors per lane); prefer little idle lanes, a statically specialised
+    // kernel, small workgroups, a single wave per row
+    const bool reduce_only = L.core == pf::CORE_REDUCE_SUM || L.core == pf::CORE_REDUCE_MAX || L.core == pf::CORE_REDUCE_MEAN;
+    const int matched = (!reduce_only && env_int("PF_NO_STATIC", 0) == 0) ? match_spec(spec_table().row, L) : 0;
     int best_wpr = 0, best_k = 0;
     long best_score = -1;
     const int ks[3] = {1, 2, 4};
@@ -736,7 +744,9 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         if (forced_variant == PF_VARIANT_ROW_WAVE && wpr != 1) continue;
         if (forced_variant == PF_VARIANT_ROW_BLOCK && wpr == 1) continue;
         const double waste = 1.0 - (double)vpr / (double)(wpr * 64 * k);
+        const unsigned threads = 64u * (unsigned)wpr * (wpr >= 4 ? 1u : (unsigned)(4 / wpr));
         long score = (waste > 0.26 ? 4000 : (waste > 0.13 ? 2000 : 0)) + (wpr > 4 ? 1000 : 0) + (wpr > 1 ? 100 : 0) + k;
+        if (matched && !pf::row_static_available(matched, k, threads)) score += 500;
         if (best_score < 0 || score < best_score) {
             best_score = score;
             best_wpr = (int)wpr;
@@ -755,7 +765,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
     p->grid = dim3((uint32_t)((rows + p->row.rows_per_block - 1) / p->row.rows_per_block));
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
-    p->reduce_only = L.core == pf::CORE_REDUCE_SUM || L.core == pf::CORE_REDUCE_MAX || L.core == pf::CORE_REDUCE_MEAN;
+    p->reduce_only = reduce_only;
     if (p->reduce_only) {
         // the epilogue runs on one value per row: no tensor operands there
         for (int i = 0; i < L.epi.n; ++i)
@@ -768,11 +778,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     }
     p->args.n_inner = (uint32_t)n;
     p->args.rows = (uint64_t)rows;
-    p->spec_id = 0;
-    if (!p->reduce_only && env_int("PF_NO_STATIC", 0) == 0) {
-        const int id = match_spec(spec_table().row, L);
-        if (id && pf::row_static_available(id, p->k, p->block.x)) p->spec_id = id;
-    }
+    p->spec_id = (matched && pf::row_static_available(matched, p->k, p->block.x)) ? matched : 0;
     return PF_OK;
 }
 
@@ -1115,6 +1121,8 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
         p->args.mask_si = L.mask_si;
         p->args.pro = L.pro;
         p->args.epi = L.epi;
+        // pure layout work (nothing but the initial load): kernels move the raw bits, no conversion
+        p->args.raw_copy = (L.pro.n == 1 && L.epi.n == 0 && L.pro.u[0].code == pf::U_MOV && L.pro.u[0].kind == pf::K_FULL) ? 1u : 0u;
         s = fill_vec_args(p, c);
     }
     if (s == PF_OK) {

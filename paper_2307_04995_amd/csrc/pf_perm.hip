@@ -97,6 +97,13 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
         perm_offsets(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
     }
     perm_load_operands<DT, K, Spec>(a, g, s, in_off, out_off, valid);
+    if (a.raw_copy) {
+        // layout-only chain: the bits travel untouched (no fp32 round trip, NaN payloads survive)
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, s.fraw[0][k]);
+        return;
+    }
     set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
     set_positions<DT, K, Spec>(s, out_off, g.div_out_inner, g.out_n_inner);
@@ -142,6 +149,10 @@ __global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, c
         const uint32_t out_off = out_base + bi * g.out_stride[2] + ai * g.out_stride[1] + iv * VEC;
         const bool valid = true;
         perm_load_operands<DT, 1, Spec>(a, g, s, &in_off, &out_off, &valid);
+        if (a.raw_copy) {
+            tile[ai * pitch + r] = s.fraw[0][0];
+            continue;
+        }
         set_positions<DT, 1, Spec>(s, &in_off, g.div_in_inner, g.in_n_inner);
         run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
         set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);

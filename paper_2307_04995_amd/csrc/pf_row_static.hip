@@ -23,6 +23,7 @@ static hipError_t launch_spec_dt(const ChainArgs& a, const RowGeom& g, int k, di
     switch (k) {
         case 1: hipLaunchKernelGGL((row_kernel<DT, 1, Spec, 256>), grid, block, 0, st, a, g); break;
         case 2: hipLaunchKernelGGL((row_kernel<DT, 2, Spec, 256>), grid, block, 0, st, a, g); break;
+        case 4: hipLaunchKernelGGL((row_kernel<DT, 4, Spec, 256>), grid, block, 0, st, a, g); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -41,7 +42,7 @@ static hipError_t launch_spec(int dtype, const ChainArgs& a, const RowGeom& g, i
 
 // Whether (spec, k, block size) has a static instantiation.
 bool row_static_available(int spec_id, int k, unsigned block_threads) {
-    if (block_threads > 256 || (k != 1 && k != 2)) return false;
+    if (block_threads > 256 || (k != 1 && k != 2 && k != 4)) return false;
     switch (spec_id) {
 #define PF_CASE(id, ...) case id:
         PF_ROW_SPECS(PF_CASE)

@@ -48,7 +48,7 @@ def gpu_run(spec, inputs, variant=None, generic=False, guard=True):
     pad = 512  # elements
     for shape, (_, dt) in zip(shapes, spec.outputs):
         n = int(np.prod(shape))
-        buf = torch.full((n + 2 * pad,), 777.0, dtype=TORCH_DT[dt], device="cuda")
+        buf = torch.full((n + 2 * pad,), 768.0, dtype=TORCH_DT[dt], device="cuda")
         guards.append(buf)
         outs.append(buf[pad:pad + n].view(shape))
     plan.run_ptrs([t.data_ptr() for t in dev_in], [o.data_ptr() for o in outs],
@@ -59,7 +59,7 @@ def gpu_run(spec, inputs, variant=None, generic=False, guard=True):
         if guard:
             head = buf[:pad].float().cpu()
             tail = buf[-pad:].float().cpu()
-            assert torch.all(head == 777.0) and torch.all(tail == 777.0), "kernel wrote outside its output"
+            assert torch.all(head == 768.0) and torch.all(tail == 768.0), "kernel wrote outside its output"
         res.append(o.detach().cpu().clone())
     plan.close()
     return res, info
