@@ -93,6 +93,8 @@ struct ChainArgs {
     uint32_t n_inner;        // innermost extent (elements) of the value the programs run on
     uint32_t mask_si;        // > 0: the prologue masks columns > row % mask_si and loads may skip them
     uint32_t raw_copy;       // 1: the chain only moves data; kernels forward the raw bits unconverted
+    float core_scale;        // softmax: the input is multiplied by this (> 0) inside the core (folded SCALE step)
+    uint32_t core_mask;      // softmax: 1 = the causal mask (extent mask_si) is applied inside the core
     uint32_t pad0;
     uint64_t rows;           // number of rows (product of the other extents)
     Program pro, epi;

@@ -125,22 +125,51 @@ PF_DEVICE float read_lane(float v, int lane) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// DPP move where the lanes of rows not selected by ROW_MASK receive `old`
+template <int CTRL, int ROW_MASK>
+PF_DEVICE int dpp_move_rows(int old, int v) {
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Order-preserving map between fp32 bit patterns and signed integers (its own inverse).  Reducing the
+// keys with integer max avoids the NaN-quieting moves a floating-point max needs after every lane
+// permutation; a (positive) NaN maps above +inf, so it wins the reduction and poisons the row.
+PF_DEVICE int32_t float_to_key(float f) {
+    const int32_t b = __builtin_bit_cast(int32_t, f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+PF_DEVICE float key_to_float(int32_t k) { return __builtin_bit_cast(float, k ^ ((k >> 31) & 0x7fffffff)); }
+
 struct OpSum {
     static PF_DEVICE float apply(float a, float b) { return a + b; }
+    static PF_DEVICE float wave(float v) {
+        v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+        v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+        v += dpp_move<0x141>(v);  // row_half_mirror
+        v += dpp_move<0x140>(v);  // row_mirror: every lane holds its 16-lane row's sum
+        v += __builtin_bit_cast(float, dpp_move_rows<0x142, 0xa>(0, __builtin_bit_cast(int, v)));  // row_bcast15 -> rows 1, 3
+        v += __builtin_bit_cast(float, dpp_move_rows<0x143, 0xc>(0, __builtin_bit_cast(int, v)));  // row_bcast31 -> rows 2, 3
+        return read_lane(v, 63);
+    }
 };
 struct OpMax {
-    // NaN-propagating is not needed here: a NaN element poisons the row through the later arithmetic
     static PF_DEVICE float apply(float a, float b) { return fmaxf(a, b); }
+    static PF_DEVICE float wave(float f) {
+        int32_t v = float_to_key(f);
+        constexpr int32_t lowest = (int32_t)0x80000000;
+        v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0xB1, 0xf, 0xf, true));
+        v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x4E, 0xf, 0xf, true));
+        v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x141, 0xf, 0xf, true));
+        v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x140, 0xf, 0xf, true));
+        v = max(v, dpp_move_rows<0x142, 0xa>(lowest, v));
+        v = max(v, dpp_move_rows<0x143, 0xc>(lowest, v));
+        return key_to_float(__builtin_amdgcn_readlane(v, 63));
+    }
 };
 
 template <class Op>
 PF_DEVICE float wave_allreduce(float v) {
-    v = Op::apply(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = Op::apply(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = Op::apply(v, dpp_move<0x141>(v));  // row_half_mirror: 8-lane halves exchanged
-    v = Op::apply(v, dpp_move<0x140>(v));  // row_mirror: every lane of a 16-lane row holds the row result
-    const float r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
-    return Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
+    return Op::wave(v);
 }
 
 // all-reduce over groups of 2^LOG2 adjacent lanes (LOG2 <= 4), result in every lane of the group
@@ -391,10 +420,9 @@ PF_DEVICE void apply_uop(int code, int slot, int32_t ival, LaneState<DT, K, Spec
             const uint32_t si = (uint32_t)ival;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const uint32_t i_row = s.row[k] % si;
+                const int32_t last = (int32_t)(s.row[k] % si) - (int32_t)s.col[k];  // last unmasked element of the vector
 #pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    s.acc[k * VEC + e] = (s.col[k] + e > i_row) ? -__builtin_inff() : s.acc[k * VEC + e];
+                for (int e = 0; e < VEC; ++e) s.acc[k * VEC + e] = (e > last) ? -__builtin_inff() : s.acc[k * VEC + e];
             }
             break;
         }

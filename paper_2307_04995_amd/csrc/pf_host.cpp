@@ -204,6 +204,8 @@ struct Lowered {
     int core_vec[2] = {-1, -1};
     pf::Program pro, epi;
     uint32_t mask_si = 0;     // load skipping allowed for a causal mask of this extent
+    uint32_t core_mask = 0;   // the mask is applied inside the softmax core
+    float core_scale = 1.0f;  // scale folded into the softmax core
     int out_slot_to_user[PF_MAX_OUTPUTS];  // args.out[slot] <- user outputs[...]
     int n_out = 1;
     Shape pre_shape;          // shape of the value entering the core (or the final value if no core)
@@ -585,7 +587,9 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     // causal-mask load skipping: legal when the masked value depends on loaded data only through steps
     // that come before the mask and nothing computed before the mask is kept
     L->mask_si = 0;
-    if (L->core == pf::CORE_SOFTMAX || L->core == pf::CORE_NONE) {
+    L->core_mask = 0;
+    L->core_scale = 1.0f;
+    if (L->core == pf::CORE_SOFTMAX) {
         int mask_at = -1;
         for (int i = 0; i < L->pro.n; ++i)
             if (L->pro.u[i].code == pf::U_MASK_CAUSAL) mask_at = i;
@@ -597,7 +601,20 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
                 if (i > mask_at && (u.kind == pf::K_FULL || u.kind == pf::K_TMP)) ok = false;
                 if (i > mask_at && u.code == pf::U_MOV) ok = false;
             }
-            if (ok && L->core == pf::CORE_SOFTMAX) L->mask_si = (uint32_t)L->pro.u[mask_at].ival;
+            if (ok) L->mask_si = (uint32_t)L->pro.u[mask_at].ival;
+        }
+        // a mask that is the last prologue step moves into the softmax core ...
+        if (L->mask_si != 0 && mask_at == L->pro.n - 1) {
+            L->core_mask = 1;
+            L->pro.n -= 1;
+        }
+        // ... and so does a positive scale right before it: softmax(c * x) = exp(c * (x - max x)) / sum for c > 0
+        if (L->pro.n >= 2 && (L->core_mask || mask_at < 0)) {
+            const pf::Uop& u = L->pro.u[L->pro.n - 1];
+            if (u.code == pf::U_MUL && u.kind == pf::K_IMM && u.imm > 0.0f && std::isfinite(u.imm)) {
+                L->core_scale = u.imm;
+                L->pro.n -= 1;
+            }
         }
     }
     return PF_OK;
@@ -1119,6 +1136,8 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
         p->args.core_vec[1] = L.core_vec[1];
         p->args.eps = L.eps;
         p->args.mask_si = L.mask_si;
+        p->args.core_mask = L.core_mask;
+        p->args.core_scale = L.core_scale;
         p->args.pro = L.pro;
         p->args.epi = L.epi;
         // pure layout work (nothing but the initial load): kernels move the raw bits, no conversion

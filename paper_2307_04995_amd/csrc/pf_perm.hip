@@ -245,18 +245,61 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const u32x4* __restrict
     }
 }
 
+// read-only and write-only streams, to see how the two directions share the memory system
+template <int K>
+__global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n_vec) {
+    const uint64_t base = (uint64_t)blockIdx.x * (256u * K) + threadIdx.x;
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t v = base + 256u * k;
+        if (v < n_vec) acc ^= __builtin_nontemporal_load(src + v);
+    }
+    // the data is random-free (benchmark buffers hold a constant), so this store never happens; it only
+    // keeps the loads alive
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) dst[base % n_vec] = acc;
+}
+template <int K>
+__global__ void __launch_bounds__(256) write_probe_kernel(u32x4* __restrict__ dst, uint64_t n_vec) {
+    const uint64_t base = (uint64_t)blockIdx.x * (256u * K) + threadIdx.x;
+    const u32x4 val = u32x4{(uint32_t)base, 1u, 2u, 3u};
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t v = base + 256u * k;
+        if (v < n_vec) __builtin_nontemporal_store(val, dst + v);
+    }
+}
+
 hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int variant, hipStream_t st) {
     const uint64_t n_vec = bytes / 16;
     if (n_vec == 0) return hipSuccess;
     const u32x4* s = static_cast<const u32x4*>(src);
     u32x4* d = static_cast<u32x4*>(dst);
-    // variant = unroll (1, 2, 4, 8) + 16 for plain (temporal) accesses
+    // variant = unroll (1, 2, 4) | 16: plain (temporal) accesses | 32: read only | 64: write only
     const bool nt = (variant & 16) == 0;
     const int k = variant & 15;
     const uint64_t per_block = 256ull * (uint64_t)(k ? k : 1);
     const uint64_t blocks = (n_vec + per_block - 1) / per_block;
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
     dim3 grid((uint32_t)blocks), block(256);
+    if (variant & 32) {
+        switch (k) {
+            case 1: hipLaunchKernelGGL((read_probe_kernel<1>), grid, block, 0, st, s, d, n_vec); break;
+            case 2: hipLaunchKernelGGL((read_probe_kernel<2>), grid, block, 0, st, s, d, n_vec); break;
+            case 4: hipLaunchKernelGGL((read_probe_kernel<4>), grid, block, 0, st, s, d, n_vec); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
+    if (variant & 64) {
+        switch (k) {
+            case 1: hipLaunchKernelGGL((write_probe_kernel<1>), grid, block, 0, st, d, n_vec); break;
+            case 2: hipLaunchKernelGGL((write_probe_kernel<2>), grid, block, 0, st, d, n_vec); break;
+            case 4: hipLaunchKernelGGL((write_probe_kernel<4>), grid, block, 0, st, d, n_vec); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
 #define PF_COPY(KK)                                                                                   \
     if (nt) hipLaunchKernelGGL((copy_probe_kernel<KK, true>), grid, block, 0, st, s, d, n_vec);       \
     else hipLaunchKernelGGL((copy_probe_kernel<KK, false>), grid, block, 0, st, s, d, n_vec);
@@ -264,7 +307,6 @@ hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int var
         case 1: PF_COPY(1) break;
         case 2: PF_COPY(2) break;
         case 4: PF_COPY(4) break;
-        case 8: PF_COPY(8) break;
         default: return hipErrorInvalidValue;
     }
 #undef PF_COPY

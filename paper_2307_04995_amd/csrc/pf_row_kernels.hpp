@@ -86,7 +86,8 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
     }
 }
 
-template <int DT, int K, class Spec, int MAXT>
+// WPR1 = a wave owns a row (no LDS, no barrier, no per-wave index arithmetic).
+template <int DT, int K, class Spec, int MAXT, bool WPR1>
 __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -96,22 +97,24 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
-    const uint32_t wpr = g.waves_per_row;
-    const uint64_t row64 = (uint64_t)blockIdx.x * g.rows_per_block + wave / wpr;
+    const uint32_t wpr = WPR1 ? 1u : g.waves_per_row;
+    const uint32_t row_in_block = WPR1 ? wave : wave / wpr;
+    const uint64_t row64 = (uint64_t)blockIdx.x * g.rows_per_block + row_in_block;
     const bool row_ok = row64 < a.rows;
-    if (wpr == 1 && !row_ok) return;  // wave-uniform; no barrier is used in this configuration
+    if (WPR1 && !row_ok) return;  // wave-uniform; this configuration has no barrier
     const uint32_t row = (uint32_t)row64;
     const uint32_t n = a.n_inner;
 
     LaneState<DT, K, Spec> s;
     // columns this lane owns: consecutive lanes take consecutive 16-byte vectors
-    const uint32_t lane_in_row = (wave % wpr) * 64u + lane;
+    const uint32_t lane_in_row = WPR1 ? lane : (wave - row_in_block * wpr) * 64u + lane;
     const uint32_t limit = row_ok ? n : 0u;
     uint32_t load_limit = limit;
+    uint32_t i_row = 0;
     if (a.mask_si != 0u) {
         // columns beyond the diagonal are overwritten by the mask before they are used: skip their loads
-        const uint32_t keep = row % a.mask_si + 1u;
-        const uint32_t keep_vec = (keep + VEC - 1u) / VEC * VEC;
+        i_row = row % a.mask_si;
+        const uint32_t keep_vec = (i_row + VEC) / VEC * VEC;
         load_limit = load_limit < keep_vec ? load_limit : keep_vec;
     }
 #pragma unroll
@@ -125,6 +128,8 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     const RowStore store_fn{a.out[0], a.out[1], row_byte, limit};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
+    // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
+    const bool exact = (n == 64u * wpr * (uint32_t)E) && row_ok;
     bool valid[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) valid[k] = s.col[k] < limit;
@@ -132,31 +137,58 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     const float inv_n = 1.0f / (float)n;
     const int core = Spec::core(a);
     if (core == CORE_SOFTMAX) {
-        float m = -__builtin_inff();
+        if (a.core_mask) {
+            // causal mask folded into the core: elements right of the diagonal become -inf
 #pragma unroll
-        for (int k = 0; k < K; ++k)
+            for (int k = 0; k < K; ++k) {
+                const int32_t last = (int32_t)i_row - (int32_t)s.col[k];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) m = valid[k] ? fmaxf(m, s.acc[k * VEC + e]) : m;
-        m = row_allreduce<OpMax>(m, wpr, wave, lane, red[0]);
-        float sum = 0.0f;
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const float ex = pf_exp<PR>(s.acc[k * VEC + e] - m);
-                s.acc[k * VEC + e] = valid[k] ? ex : 0.0f;
-                sum += s.acc[k * VEC + e];
+                for (int e = 0; e < VEC; ++e) s.acc[k * VEC + e] = (e > last) ? -__builtin_inff() : s.acc[k * VEC + e];
             }
+        }
+        if (!exact) {
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s.acc[k * VEC + e] = valid[k] ? s.acc[k * VEC + e] : -__builtin_inff();
+        }
+        float m = s.acc[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) m = fmaxf(m, s.acc[e]);
+        m = row_allreduce<OpMax>(m, wpr, wave, lane, red[0]);
+        // exp(c * (x - m)); c is the folded scale (1 when there is none).  -inf - m = -inf -> 0; an all -inf
+        // row gives -inf - -inf = NaN, as the definition does.
+        const float c = a.core_scale;
+        float sum = 0.0f;
+        if (PR) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                s.acc[e] = expf((s.acc[e] - m) * c);
+                sum += s.acc[e];
+            }
+        } else {
+            const float c2 = c * kLog2e;
+            const float mc = -m * c2;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                s.acc[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s.acc[e], c2, mc));
+                sum += s.acc[e];
+            }
+        }
         sum = row_allreduce<OpSum>(sum, wpr, wave, lane, red[1]);
-        const float inv = 1.0f / sum;
+        const float inv = pf_rcp<PR>(sum);
 #pragma unroll
         for (int e = 0; e < E; ++e) s.acc[e] *= inv;
     } else if (core == CORE_LAYERNORM) {
+        if (!exact) {
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s.acc[k * VEC + e] = valid[k] ? s.acc[k * VEC + e] : 0.0f;
+        }
         float s1 = 0.0f;
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) s1 += valid[k] ? s.acc[k * VEC + e] : 0.0f;
+        for (int e = 0; e < E; ++e) s1 += s.acc[e];
         const float mean = row_allreduce<OpSum>(s1, wpr, wave, lane, red[0]) * inv_n;
         float s2 = 0.0f;
 #pragma unroll
@@ -165,7 +197,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             for (int e = 0; e < VEC; ++e) {
                 const float d = s.acc[k * VEC + e] - mean;
                 s.acc[k * VEC + e] = d;
-                s2 += valid[k] ? d * d : 0.0f;
+                s2 += (exact || valid[k]) ? d * d : 0.0f;
             }
         const float var = row_allreduce<OpSum>(s2, wpr, wave, lane, red[1]) * inv_n;
         const float rstd = pf_rsqrt<PR>(var + a.eps);
@@ -184,7 +216,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
         for (int k = 0; k < K; ++k)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) s2 += valid[k] ? s.acc[k * VEC + e] * s.acc[k * VEC + e] : 0.0f;
+            for (int e = 0; e < VEC; ++e) s2 += (exact || valid[k]) ? s.acc[k * VEC + e] * s.acc[k * VEC + e] : 0.0f;
         const float ms = row_allreduce<OpSum>(s2, wpr, wave, lane, red[0]) * inv_n;
         const float rstd = pf_rsqrt<PR>(ms + a.eps);
         float gm[E];

@@ -20,12 +20,19 @@ template <int ID, int DT>
 static hipError_t launch_spec_dt(const ChainArgs& a, const RowGeom& g, int k, dim3 grid, dim3 block, hipStream_t st) {
     using Spec = typename RowSpecOf<ID>::type;
     if (block.x > 256) return hipErrorInvalidValue;
+    const bool wave_rows = g.waves_per_row == 1;
+#define PF_K_CASE(KK)                                                                                     \
+    case KK:                                                                                              \
+        if (wave_rows) hipLaunchKernelGGL((row_kernel<DT, KK, Spec, 256, true>), grid, block, 0, st, a, g); \
+        else hipLaunchKernelGGL((row_kernel<DT, KK, Spec, 256, false>), grid, block, 0, st, a, g);        \
+        break;
     switch (k) {
-        case 1: hipLaunchKernelGGL((row_kernel<DT, 1, Spec, 256>), grid, block, 0, st, a, g); break;
-        case 2: hipLaunchKernelGGL((row_kernel<DT, 2, Spec, 256>), grid, block, 0, st, a, g); break;
-        case 4: hipLaunchKernelGGL((row_kernel<DT, 4, Spec, 256>), grid, block, 0, st, a, g); break;
+        PF_K_CASE(1)
+        PF_K_CASE(2)
+        PF_K_CASE(4)
         default: return hipErrorInvalidValue;
     }
+#undef PF_K_CASE
     return hipGetLastError();
 }
 

@@ -22,12 +22,7 @@
     /* x + bias + res -> LayerNorm */                                                                          \
     X(2, 2, 3, 0, CORE_LAYERNORM, 1, 2,                                                                        \
       PF_L(PF_U(U_MOV, K_FULL, 0), PF_U(U_ADD, K_VEC, 0), PF_U(U_ADD, K_FULL, 1)), PF_L())                     \
-    /* x * scale -> causal mask -> softmax */                                                                  \
-    X(3, 1, 0, 0, CORE_SOFTMAX, -1, -1,                                                                        \
-      PF_L(PF_U(U_MOV, K_FULL, 0), PF_U(U_MUL, K_IMM, 0), PF_U(U_MASK_CAUSAL, K_NONE, 0)), PF_L())             \
-    /* x * scale -> softmax */                                                                                 \
-    X(4, 1, 0, 0, CORE_SOFTMAX, -1, -1, PF_L(PF_U(U_MOV, K_FULL, 0), PF_U(U_MUL, K_IMM, 0)), PF_L())           \
-    /* softmax */                                                                                              \
+    /* softmax, with an optional positive scale and causal mask folded into the core */                                                                                            \
     X(5, 1, 0, 0, CORE_SOFTMAX, -1, -1, PF_L(PF_U(U_MOV, K_FULL, 0)), PF_L())                                  \
     /* LayerNorm */                                                                                            \
     X(6, 1, 2, 0, CORE_LAYERNORM, 0, 1, PF_L(PF_U(U_MOV, K_FULL, 0)), PF_L())                                  \
