@@ -81,6 +81,12 @@ enum CoreKind : int32_t {
     CORE_PERMUTE = 8
 };
 
+// Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every
+// 32-bit n (multiply-high, one correction add, two shifts).  Built on the host by make_fastdiv().
+struct FastDiv {
+    uint32_t m, s1, s2, d;
+};
+
 // Arguments common to all families.
 struct ChainArgs {
     const void* full[PF_DEV_MAX_FULL];
@@ -94,8 +100,10 @@ struct ChainArgs {
     uint32_t mask_si;        // > 0: the prologue masks columns > row % mask_si and loads may skip them
     uint32_t raw_copy;       // 1: the chain only moves data; kernels forward the raw bits unconverted
     float core_scale;        // softmax: the input is multiplied by this (> 0) inside the core (folded SCALE step)
-    uint32_t core_mask;      // softmax: 1 = the causal mask (extent mask_si) is applied inside the core
+    uint32_t core_mask;      // softmax: the causal mask (extent mask_si) is applied inside the core; 1 = element by
+                             // element, 2 = skipped vectors read as -inf and only the diagonal vector is masked
     uint32_t pad0;
+    FastDiv mask_div;        // division by mask_si
     uint64_t rows;           // number of rows (product of the other extents)
     Program pro, epi;
 };
@@ -103,13 +111,8 @@ struct ChainArgs {
 // Row family geometry.
 struct RowGeom {
     uint32_t waves_per_row;  // 1 = a wave owns a row; > 1 = a workgroup of that many waves owns a row
-    uint32_t rows_per_block; // wave variant: waves (= rows) per workgroup
-};
-
-// Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every
-// 32-bit n (multiply-high, one correction add, two shifts).  Built on the host by make_fastdiv().
-struct FastDiv {
-    uint32_t m, s1, s2, d;
+    uint32_t rows_per_block; // row slots per workgroup (a slot is rows_per_wave rows when a wave owns its rows)
+    uint32_t rows_per_wave;  // rows each wave processes at once (1 unless a wave owns its rows)
 };
 
 // Group family (channels-last GroupNorm) geometry.

@@ -98,6 +98,12 @@ struct Storage<DT_BF16> {
 };
 
 // Streamed data is touched once: mark it non-temporal so it does not displace the broadcast operands.
+PF_DEVICE u32x4 load_stream(const char* base, uint32_t byte_off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
+}
+PF_DEVICE void store_stream(char* base, uint32_t byte_off, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(base + byte_off));
+}
 PF_DEVICE u32x4 load_stream(const void* base, uint64_t byte_off) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off));
 }
@@ -334,6 +340,17 @@ PF_DEVICE void fetch_vec(const LaneState<DT, K, Spec>& s, int slot, float* b) {
 #pragma unroll
     for (int v = 0; v < Spec::NV; ++v)
         if (slot == v) unpack_slot<DT, K>(s.vraw[v], b);
+}
+
+// the KC vectors of a broadcast operand that start at vector k0
+template <int DT, int K, int KC, class Spec>
+PF_DEVICE void fetch_vec_part(const LaneState<DT, K, Spec>& s, int slot, int k0, float* b) {
+#pragma unroll
+    for (int v = 0; v < Spec::NV; ++v)
+        if (slot == v) {
+#pragma unroll
+            for (int c = 0; c < KC; ++c) Storage<DT>::unpack(s.vraw[v][k0 + c], b + c * Storage<DT>::VEC);
+        }
 }
 
 // Secondary-output hook: the families that support U_STORE pass a functor; others pass NoStore.

@@ -616,6 +616,8 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
                 L->pro.n -= 1;
             }
         }
+        // with nothing but the load left in front of the core, vectors that are skipped can stand in as -inf
+        if (L->core_mask && L->pro.n == 1 && L->pro.u[0].code == pf::U_MOV && L->pro.u[0].kind == pf::K_FULL) L->core_mask = 2;
     }
     return PF_OK;
 }
@@ -763,7 +765,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         const double waste = 1.0 - (double)vpr / (double)(wpr * 64 * k);
         const unsigned threads = 64u * (unsigned)wpr * (wpr >= 4 ? 1u : (unsigned)(4 / wpr));
         long score = (waste > 0.26 ? 4000 : (waste > 0.13 ? 2000 : 0)) + (wpr > 4 ? 1000 : 0) + (wpr > 1 ? 100 : 0) + k;
-        if (matched && !pf::row_static_available(matched, k, threads)) score += 500;
+        if (matched && !pf::row_static_available(matched, k, 1, wpr == 1, threads)) score += 500;
         if (best_score < 0 || score < best_score) {
             best_score = score;
             best_wpr = (int)wpr;
@@ -779,8 +781,19 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     p->k = best_k;
     p->row.waves_per_row = (uint32_t)best_wpr;
     p->row.rows_per_block = best_wpr >= 4 ? 1u : (uint32_t)(4 / best_wpr);
+    p->row.rows_per_wave = 1;
+    // Rows per wave: a wave that owns short rows takes several at once, so that it has about 4 KB of loads
+    // in flight (what it takes to cover the HBM latency at full occupancy), as long as enough waves remain
+    // (16 per SIMD) to fill the device evenly and a specialised kernel exists for the combination.
+    if (best_wpr == 1 && matched && L.n_out == 1) {
+        const int64_t bytes_per_row_in_flight = (int64_t)L.n_full * best_k * 1024;
+        int rpw = 1;
+        while (rpw < 4 && bytes_per_row_in_flight * rpw < 4096 && best_k * rpw * 2 <= 4 && rows / (rpw * 2) >= 16384) rpw *= 2;
+        const int forced = env_int("PF_ROWS_PER_WAVE", 0);
+        if (forced > 0) rpw = forced;
+        if (rpw > 1 && pf::row_static_available(matched, best_k, rpw, true, 256)) p->row.rows_per_wave = (uint32_t)rpw;
+    }
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
-    p->grid = dim3((uint32_t)((rows + p->row.rows_per_block - 1) / p->row.rows_per_block));
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
     p->reduce_only = reduce_only;
     if (p->reduce_only) {
@@ -795,7 +808,12 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     }
     p->args.n_inner = (uint32_t)n;
     p->args.rows = (uint64_t)rows;
-    p->spec_id = (matched && pf::row_static_available(matched, p->k, p->block.x)) ? matched : 0;
+    p->spec_id = (matched && pf::row_static_available(matched, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) ? matched : 0;
+    if (!p->spec_id) p->row.rows_per_wave = 1;
+    {
+        const int64_t rows_per_block = (int64_t)p->row.rows_per_block * p->row.rows_per_wave;
+        p->grid = dim3((uint32_t)((rows + rows_per_block - 1) / rows_per_block));
+    }
     return PF_OK;
 }
 
@@ -1137,6 +1155,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
         p->args.eps = L.eps;
         p->args.mask_si = L.mask_si;
         p->args.core_mask = L.core_mask;
+        p->args.mask_div = make_fastdiv(L.mask_si ? L.mask_si : 1u);
         p->args.core_scale = L.core_scale;
         p->args.pro = L.pro;
         p->args.epi = L.epi;
@@ -1159,8 +1178,8 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
             p->out_bytes[o] = (uint64_t)numel(p->out_shape[o]) * dtype_size(desc->out_dtype[o]);
         }
         if (env_int("PF_LOG", 0))
-            fprintf(stderr, "[pf_chain] family=%d variant=%d spec=%d k=%d grid=%u block=%u uops=%d+%d full=%d vec=%d tmp=%d mask_si=%u\n",
-                    p->family, p->variant, p->spec_id, p->k, p->grid.x, p->block.x, p->low.pro.n, p->low.epi.n, p->low.n_full,
+            fprintf(stderr, "[pf_chain] family=%d variant=%d spec=%d k=%d rpw=%u grid=%u block=%u uops=%d+%d full=%d vec=%d tmp=%d mask_si=%u\n",
+                    p->family, p->variant, p->spec_id, p->k, p->row.rows_per_wave, p->grid.x, p->block.x, p->low.pro.n, p->low.epi.n, p->low.n_full,
                     p->low.n_vec, p->low.n_tmp, p->low.mask_si);
         *out = p;
         return PF_OK;

@@ -8,7 +8,7 @@ namespace pf {
 
 hipError_t launch_row_generic(int dtype, const ChainArgs& a, const RowGeom& g, int k, bool reduce_only, dim3 grid,
                               dim3 block, hipStream_t st);
-bool row_static_available(int spec_id, int k, unsigned block_threads);
+bool row_static_available(int spec_id, int kc, int rpw, bool wave_rows, unsigned block_threads);
 hipError_t launch_row_static(int spec_id, int dtype, const ChainArgs& a, const RowGeom& g, int k, dim3 grid, dim3 block,
                              hipStream_t st);
 hipError_t launch_ew(int dtype, const ChainArgs& a, uint32_t total_vecs, uint32_t vecs_per_row, int k, dim3 grid,

@@ -11,8 +11,8 @@ static hipError_t launch_row_dt(const ChainArgs& a, const RowGeom& g, int k, boo
 #define PF_ROW_CASE(KK)                                                                                        \
     case KK:                                                                                                   \
         if (reduce_only) hipLaunchKernelGGL((row_reduce_kernel<DT, KK>), grid, block, 0, st, a, g);           \
-        else if (small) hipLaunchKernelGGL((row_kernel<DT, KK, GenericSpec, 256, false>), grid, block, 0, st, a, g); \
-        else hipLaunchKernelGGL((row_kernel<DT, KK, GenericSpec, 1024, false>), grid, block, 0, st, a, g);    \
+        else if (small) hipLaunchKernelGGL((row_kernel<DT, KK, 1, GenericSpec, 256, false>), grid, block, 0, st, a, g); \
+        else hipLaunchKernelGGL((row_kernel<DT, KK, 1, GenericSpec, 1024, false>), grid, block, 0, st, a, g);    \
         break;
     switch (k) {
         PF_ROW_CASE(1)

@@ -37,6 +37,36 @@ def test_c2_chain(b, h, s, dtype, generic):
     assert info.family == _pf().PF_FAMILY_ROW
 
 
+def test_causal_softmax_with_other_prologue_steps():
+    # a negative factor and a bias in front of the mask: the mask moves into the core but skipped loads may
+    # not stand in as -inf; a non-positive scale is not folded into the core at all
+    b, h, sq = 1, 3, 96
+    x = wl.random_tensor((b, h, sq, sq), "f16", 51, scale=2.0)
+    bias = wl.random_tensor((sq,), "f16", 52)
+    for factor in (-0.5, 0.25):
+        spec = wl.ChainSpec(inputs=[("f16", (b, h, sq, sq)), ("f16", (sq,))])
+        v = spec.op("add", 0, 1)
+        v = spec.op("scale", v, f=[factor])
+        v = spec.op("causal_mask", v)
+        v = spec.op("softmax", v)
+        spec.out(v, "f16")
+        check_chain(spec, [x, bias], what=f"masked softmax factor {factor}")
+        check_chain(spec, [x, bias], generic=True, what=f"masked softmax factor {factor} generic")
+    spec = wl.ChainSpec(inputs=[("f16", (b, h, sq, sq))])
+    v = spec.op("scale", 0, f=[-1.0])
+    v = spec.op("causal_mask", v)
+    v = spec.op("softmax", v)
+    spec.out(v, "f16")
+    check_chain(spec, [x], what="masked softmax negative scale")
+    # mask first, then more arithmetic: stays an ordinary prologue step
+    spec = wl.ChainSpec(inputs=[("f16", (b, h, sq, sq))])
+    v = spec.op("causal_mask", 0)
+    v = spec.op("scale", v, f=[0.5])
+    v = spec.op("softmax", v)
+    spec.out(v, "f16")
+    check_chain(spec, [x], what="mask then scale")
+
+
 def test_c2_rectangular_scores():
     # more keys than queries: the mask still compares column against row of the last two dims
     spec, ins = wl.c2_causal_softmax(b=1, h=2, s=40, s_k=72, dtype="f16")
