@@ -122,9 +122,12 @@ struct GroupGeom {
     uint32_t vpg;                // vectors per group (power of two)
     uint32_t log2_vpg;
     uint32_t pos_per_step;       // positions a workgroup covers per step (blockDim / cv)
-    uint32_t pos_per_block;      // positions one workgroup owns
+    uint32_t pos_per_block;      // positions one workgroup owns (a tile)
+    uint32_t lanes_per_group;    // lanes that share a group when a sample's partials are merged (power of two)
+    uint32_t vec_per_channel;    // 1: every broadcast operand is indexed by channel only
     uint32_t blocks_per_sample;
     float* ws_partial;           // [samples][blocks_per_sample][groups][4] = (count, mean, M2, -)
+    uint64_t* ws_final;          // [2][samples][groups] (mean, rstd) words per launch parity; all-ones = not ready
     uint32_t* ws_counter;        // [samples] arrival counters (resident variant)
     uint32_t epoch;              // launch number; the counters reach epoch * blocks_per_sample
     uint32_t spin_limit;         // resident variant: bounded wait, then the error flag is raised

@@ -6,11 +6,11 @@
 // exchanged at device scope -- the widest synchronisation scope of the paper's scheme (section 5.1), the
 // one it pays a DRAM round trip for.  Two variants:
 //
-//   TWO_PASS  kernel 1 writes per-workgroup partial statistics, kernel 2 combines them and normalises.
+//   TWO_PASS  launch 1 writes per-workgroup partial statistics, launch 2 merges them and normalises.
 //             x is read twice (the second read usually hits the last-level cache).
-//   RESIDENT  one kernel.  Every workgroup keeps its slice of x in registers, publishes partial
-//             statistics, waits on a per-sample arrival counter (device-scope release / acquire), combines
-//             and normalises straight from registers.  x is read once: compulsory traffic only.
+//   RESIDENT  one launch.  Every workgroup keeps its slice of x in registers, publishes partial
+//             statistics, takes part in a per-sample device-scope exchange and normalises straight from
+//             registers.  x is read once: compulsory traffic only.
 //
 // Statistics are (count, mean, M2) triples merged with the parallel-variance update, each lane summing
 // deviations from its first element, so a large common offset does not cancel catastrophically in fp32.
@@ -25,9 +25,10 @@ struct Stat {
     float n, mean, m2;
 };
 
+// parallel-variance update; counts are small integers, so the approximate reciprocal is exact enough
 PF_DEVICE Stat stat_merge(Stat a, Stat b) {
     const float n = a.n + b.n;
-    const float inv = n > 0.0f ? 1.0f / n : 0.0f;
+    const float inv = n > 0.0f ? __builtin_amdgcn_rcpf(n) : 0.0f;
     const float delta = b.mean - a.mean;
     Stat r;
     r.n = n;
@@ -68,15 +69,49 @@ struct LaneAcc {
     }
 };
 
+// Statistics straight from the packed 16-bit vector, without widening every element: two dot-product
+// instructions per pair of elements accumulate the sum and the sum of squares in fp32.  Products of 16-bit
+// values are exact in fp32 and a lane sums at most a few dozen elements, so the only cancellation left is
+// in the lane's own M2 = ss - s^2/n, whose relative error is about 1e-7 * mean^2 / var: harmless for any
+// offset a 16-bit type can carry over its spread (beyond mean/std of a few hundred the storage type itself
+// cannot resolve the spread).  Lanes are then merged with the offset-safe parallel-variance update.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int DT>
+PF_DEVICE void lean_add_vector(LaneAcc& la, u32x4 raw) {
+    if (DT == DT_F16) {
+        const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = raw[j];  // (a bit cast applied directly to a vector element is miscompiled)
+            const f16x2 x = __builtin_bit_cast(f16x2, w);
+            la.s = __builtin_amdgcn_fdot2(x, ones, la.s, false);
+            la.ss = __builtin_amdgcn_fdot2(x, x, la.ss, false);
+        }
+    } else {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = raw[j];
+            const bf16x2 x = __builtin_bit_cast(bf16x2, w);
+            la.s = __builtin_amdgcn_fdot2_f32_bf16(x, ones, la.s, false);
+            la.ss = __builtin_amdgcn_fdot2_f32_bf16(x, x, la.ss, false);
+        }
+    }
+    la.n += 8.0f;
+}
+
 // lanes of one group are vpg adjacent lanes; afterwards the group's first lane holds the merged triple
 PF_DEVICE Stat group_lanes_merge(Stat st, uint32_t log2_vpg) {
     for (uint32_t b = 0; b < log2_vpg; ++b) st = stat_merge(st, stat_shfl_xor(st, 1 << b));
     return st;
 }
 
-// workgroup partial: merge over the position steps of the workgroup and publish
-PF_DEVICE void block_partial(const GroupGeom& g, Stat st, uint32_t pstep, uint32_t cvi, bool active, float* lds,
-                             float* dst /* [groups][4] */) {
+// workgroup partial: merge over the position steps of the workgroup and publish [groups][4] floats.
+// COHERENT: written through with device-coherent stores (read by other workgroups of the same launch).
+template <bool COHERENT>
+PF_DEVICE void block_partial(const GroupGeom& g, Stat st, uint32_t pstep, uint32_t cvi, bool active, float* lds, float* dst) {
     const uint32_t grp = cvi >> g.log2_vpg;
     if (active && (cvi & (g.vpg - 1u)) == 0u) {
         float* p = lds + (pstep * g.groups + grp) * 3u;
@@ -92,252 +127,282 @@ PF_DEVICE void block_partial(const GroupGeom& g, Stat st, uint32_t pstep, uint32
             acc = stat_merge(acc, Stat{p[0], p[1], p[2]});
         }
         float* o = dst + threadIdx.x * 4u;
-        o[0] = acc.n;
-        o[1] = acc.mean;
-        o[2] = acc.m2;
-        o[3] = 0.0f;
-        __threadfence();  // the partial must be visible device-wide before this workgroup signals arrival
-    }
-}
-
-// merge the published partials of one sample; every workgroup does it for all groups.  The fetch is spread
-// over the workgroup (one triple per lane) so its latency is paid once, then one lane per group merges
-// from LDS.  blocks_per_sample * groups <= PF_GROUP_MAX_PARTIALS is guaranteed by the planner.
-#define PF_GROUP_MAX_PARTIALS 2048
-template <bool COHERENT>
-PF_DEVICE void combine_sample(const GroupGeom& g, uint32_t sample, float eps, float* lds_part /* [partials][3] */,
-                              float* lds_stat /* [groups][2] */) {
-    const uint32_t n_part = g.blocks_per_sample * g.groups;
-    const float* base = g.ws_partial + (uint64_t)sample * n_part * 4u;
-    for (uint32_t i = threadIdx.x; i < n_part; i += blockDim.x) {
-        const float* p = base + (uint64_t)i * 4u;
-        float n, mean, m2;
         if (COHERENT) {
-            n = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            mean = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            m2 = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(o + 0, acc.n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(o + 1, acc.mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(o + 2, acc.m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
-            n = p[0];
-            mean = p[1];
-            m2 = p[2];
+            o[0] = acc.n;
+            o[1] = acc.mean;
+            o[2] = acc.m2;
         }
-        lds_part[i * 3u] = n;
-        lds_part[i * 3u + 1u] = mean;
-        lds_part[i * 3u + 2u] = m2;
     }
-    __syncthreads();
-    if (threadIdx.x < g.groups) {
-        Stat acc = {0.0f, 0.0f, 0.0f};
-        for (uint32_t b = 0; b < g.blocks_per_sample; ++b) {
-            const float* p = lds_part + (b * g.groups + threadIdx.x) * 3u;
-            acc = stat_merge(acc, Stat{p[0], p[1], p[2]});
-        }
-        const float var = acc.n > 0.0f ? acc.m2 / acc.n : 0.0f;
-        lds_stat[threadIdx.x * 2u] = acc.mean;
-        lds_stat[threadIdx.x * 2u + 1u] = 1.0f / sqrtf(var + eps);
-    }
-    __syncthreads();
 }
 
-template <int DT, int K, class Spec>
-PF_DEVICE void group_load(const ChainArgs& a, const GroupGeom& g, LaneState<DT, K, Spec>& s, uint32_t sample, const uint32_t* pos,
-                          uint32_t cvi, const bool* valid) {
-    using S = Storage<DT>;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        s.row[k] = sample * g.hw + pos[k];
-        s.col[k] = cvi * S::VEC;
-    }
-#pragma unroll
-    for (int f = 0; f < Spec::NF; ++f) {
-        if (f < Spec::n_full(a)) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
-                if (valid[k])
-                    s.fraw[f][k] = load_stream(a.full[f], ((uint64_t)s.row[k] * g.channels + s.col[k]) * S::ESIZE);
+// Merge the published partials of one sample into (mean, rstd) per group.  lanes_per_group (a power of
+// two, <= 64) adjacent lanes share a group: each merges a strided subset of the sample's partials straight
+// from memory, then the lanes are merged by a shuffle tree.  Returns true in the lane that holds a group's
+// result (its group index in *grp_out).
+template <bool COHERENT>
+PF_DEVICE bool combine_sample(const GroupGeom& g, uint32_t sample, float eps, uint32_t* grp_out, float* mean_out, float* rstd_out) {
+    const uint32_t lpg = g.lanes_per_group;
+    const uint32_t grp = threadIdx.x / lpg, j = threadIdx.x - grp * lpg;
+    const bool in_range = grp < g.groups;
+    const float* base = g.ws_partial + ((uint64_t)sample * g.blocks_per_sample * g.groups + (in_range ? grp : 0u)) * 4u;
+    Stat acc = {0.0f, 0.0f, 0.0f};
+    for (uint32_t b = j; b < g.blocks_per_sample; b += lpg) {
+        const float* p = base + (uint64_t)b * g.groups * 4u;
+        Stat q = {0.0f, 0.0f, 0.0f};
+        if (in_range) {
+            if (COHERENT) {
+                q.n = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                q.mean = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                q.m2 = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                q.n = p[0];
+                q.mean = p[1];
+                q.m2 = p[2];
             }
         }
+        acc = stat_merge(acc, q);
     }
-#pragma unroll
-    for (int v = 0; v < Spec::NV; ++v) {
-        if (v < Spec::n_vec(a)) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
-                if (valid[k]) s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], s.row[k], s.col[k], g.channels);
-            }
+    for (uint32_t m = 1; m < lpg; m <<= 1) acc = stat_merge(acc, stat_shfl_xor(acc, (int)m));
+    const float var = acc.n > 0.0f ? acc.m2 / acc.n : 0.0f;
+    *grp_out = grp;
+    *mean_out = acc.mean;
+    *rstd_out = 1.0f / sqrtf(var + eps);
+    return in_range && j == 0u;
+}
+
+// Polls are spaced about a microsecond apart: many workgroups wait on the same few words, and a tight
+// polling loop would queue up in front of the very atomics it is waiting for.
+PF_DEVICE bool wait_for_counter(const uint32_t* word, uint32_t target, uint32_t spin_limit, uint32_t* error) {
+    uint32_t spins = 0;
+    for (;;) {
+        const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((int32_t)(v - target) >= 0) return true;
+        if (++spins >= spin_limit) {
+            __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
         }
+        __builtin_amdgcn_s_sleep(32);
     }
 }
 
-template <int DT, int K, class Spec>
-PF_DEVICE void group_normalise(const ChainArgs& a, const GroupGeom& g, LaneState<DT, K, Spec>& s, uint32_t cvi, const float* lds_stat) {
-    constexpr int E = LaneState<DT, K, Spec>::E;
-    const uint32_t grp = cvi >> g.log2_vpg;
-    const float mean = lds_stat[grp * 2u], rstd = lds_stat[grp * 2u + 1u];
-    float gm[E], bt[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        gm[e] = 1.0f;
-        bt[e] = 0.0f;
-    }
-    if (Spec::gamma(a) >= 0) fetch_vec<DT, K, Spec>(s, Spec::gamma(a), gm);
-    if (Spec::beta(a) >= 0) fetch_vec<DT, K, Spec>(s, Spec::beta(a), bt);
-#pragma unroll
-    for (int e = 0; e < E; ++e) s.acc[e] = (s.acc[e] - mean) * rstd * gm[e] + bt[e];
-}
+constexpr uint64_t kFinalEmpty = ~0ull;  // (NaN, NaN): never a valid (mean, rstd) pair
 
-// ---- two-pass, kernel 1: partial statistics
-template <int DT, int K, class Spec>
-__global__ void __launch_bounds__(1024) group_stats_kernel(const ChainArgs a, const GroupGeom g) {
+// One kernel template, three phases:
+//   PHASE 0  fused: statistics, device-scope exchange and normalisation in one launch (RESIDENT variant)
+//   PHASE 1  statistics only: writes the workgroup partials               (TWO_PASS, first launch)
+//   PHASE 2  normalisation only: re-reads x, merges the partials itself   (TWO_PASS, second launch)
+//
+// A workgroup owns tiles blockIdx.x, blockIdx.x + gridDim.x, ... of NV position steps each; a lane holds NV
+// 16-byte vectors of x in registers, all loads issued before the first use.  Workgroups start at different
+// steps of their slice (register i holds step (i + rot) mod NV): all slices begin at multiples of the same
+// power of two, and walking them in lockstep would keep every workgroup on the same few HBM channels.
+//
+// PHASE 0 requirements, checked by the planner: one full operand, per-channel broadcast operands only, and
+// all workgroups of a launch co-resident (the grid is sized to what the device holds and is a multiple of
+// the workgroups per sample), so every wait below ends.  Waits are bounded anyway: after spin_limit polls the
+// error word is set and the kernel carries on.
+//
+// Exchange protocol of PHASE 0 (per sample and launch): every workgroup publishes its per-group partials
+// with device-coherent stores, waits for them to complete and bumps the sample's arrival counter.  The
+// workgroup that arrives last merges all partials of the sample and publishes one 8-byte (mean, rstd) word
+// per group into the slot of this launch's parity, re-arming the other parity's slot for the next launch;
+// every other workgroup polls the words of its groups until they are no longer empty.  All shared words
+// travel by device-coherent (agent-scope atomic) accesses, so no cache write-back or invalidate is needed
+// around them -- a write-back here would wait for every output line other workgroups have just stored.
+//
+// Staggered start (PHASE 0, two workgroups per compute unit): the second half of the grid begins loading
+// only when the matching sample of the first half has finished loading (its arrival counter is complete).
+// The halves then run half a phase apart: one normalises and stores while the other loads.
+template <int DT, int NV, class Spec, int PHASE>
+__global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles,
+                                                        const uint32_t stagger_tiles) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
-    __shared__ float g_lds_part[1024 * 3];
+    // kLean: 16-bit storage and nothing but the load in front of the normalisation
+    constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
+    __shared__ float lds_part[512 * 3];
+    __shared__ float lds_stat[512 * 2];
+    __shared__ uint32_t s_last;
     const uint32_t t = threadIdx.x;
     const uint32_t pstep = fast_div(t, g.div_cv);
     const uint32_t cvi = t - pstep * g.cv;
     const bool active = pstep < g.pos_per_step;
-    const uint32_t sample = blockIdx.y;
-    const uint32_t p_begin = blockIdx.x * g.pos_per_block;
-    const uint32_t p_end = min(g.hw, p_begin + g.pos_per_block);
-    LaneAcc la;
-    LaneState<DT, K, Spec> s;
-    for (uint32_t p0 = p_begin; p0 < p_end; p0 += g.pos_per_step * K) {  // uniform trip count
-        uint32_t pos[K];
-        bool valid[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            pos[k] = p0 + pstep + k * g.pos_per_step;
-            valid[k] = active && pos[k] < p_end;
-        }
-        group_load<DT, K, Spec>(a, g, s, sample, pos, cvi, valid);
-        run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (valid[k]) la.template add_vector<VEC>(s.acc + k * VEC);
-    }
-    const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
-    float* dst = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + blockIdx.x) * g.groups) * 4u;
-    block_partial(g, st, pstep, cvi, active, g_lds_part, dst);
-}
 
-// ---- two-pass, kernel 2: combine and normalise
-template <int DT, int K, class Spec>
-__global__ void __launch_bounds__(1024) group_apply_kernel(const ChainArgs a, const GroupGeom g) {
-    using S = Storage<DT>;
-    constexpr int VEC = S::VEC;
-    __shared__ float g_lds_part[PF_GROUP_MAX_PARTIALS * 3];
-    __shared__ float g_lds_stat[1024 * 2];
-    const uint32_t t = threadIdx.x;
-    const uint32_t pstep = fast_div(t, g.div_cv);
-    const uint32_t cvi = t - pstep * g.cv;
-    const bool active = pstep < g.pos_per_step;
-    const uint32_t sample = blockIdx.y;
-    const uint32_t p_begin = blockIdx.x * g.pos_per_block;
-    const uint32_t p_end = min(g.hw, p_begin + g.pos_per_block);
-    combine_sample<false>(g, sample, a.eps, g_lds_part, g_lds_stat);
-    LaneState<DT, K, Spec> s;
-    for (uint32_t p0 = p_begin; p0 < p_end; p0 += g.pos_per_step * K) {
-        uint32_t pos[K];
-        bool valid[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            pos[k] = p0 + pstep + k * g.pos_per_step;
-            valid[k] = active && pos[k] < p_end;
-        }
-        group_load<DT, K, Spec>(a, g, s, sample, pos, cvi, valid);
-        run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
-        group_normalise<DT, K, Spec>(a, g, s, cvi, g_lds_stat);
-        run_program<DT, K, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (valid[k])
-                store_stream(a.out[0], ((uint64_t)s.row[k] * g.channels + s.col[k]) * S::ESIZE, S::pack(s.acc + k * VEC));
-    }
-}
-
-// ---- resident: one kernel, x stays in registers across the device-scope exchange.
-// Requirements checked by the planner: one full operand; the workgroup's NV position steps cover its
-// whole slice; all workgroups of a launch are co-resident (the grid is sized to what the device holds
-// and a workgroup loops over its tiles), so every wait below ends.  The wait is bounded anyway: when
-// spin_limit polls pass without the counter arriving, the error word is set and the kernel carries on.
-template <int DT, int NV, class Spec>
-__global__ void __launch_bounds__(1024) group_resident_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles,
-                                                              const uint32_t tiles_per_round) {
-    using S = Storage<DT>;
-    constexpr int VEC = S::VEC;
-    __shared__ float g_lds_part[PF_GROUP_MAX_PARTIALS * 3];
-    __shared__ float g_lds_stat[1024 * 2];
-    const uint32_t t = threadIdx.x;
-    const uint32_t pstep = fast_div(t, g.div_cv);
-    const uint32_t cvi = t - pstep * g.cv;
-    const bool active = pstep < g.pos_per_step;
-    uint32_t round = 0;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += tiles_per_round, ++round) {
-        const uint32_t sample = tile / g.blocks_per_sample;
-        const uint32_t bx = tile - sample * g.blocks_per_sample;
-        const uint32_t p_begin = bx * g.pos_per_block;
-        const uint32_t p_end = min(g.hw, p_begin + g.pos_per_block);
-        // ---- the whole slice into registers, every load issued before the first use
-        u32x4 raw[NV];
-        bool valid[NV];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const uint32_t pos = p_begin + pstep + i * g.pos_per_step;
-            valid[i] = active && pos < p_end;
-            raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid[i])
-                raw[i] = load_stream(a.full[0], ((uint64_t)(sample * g.hw + pos) * g.channels + cvi * VEC) * S::ESIZE);
-        }
-        LaneState<DT, 1, Spec> s;
-        s.col[0] = cvi * VEC;
+    LaneState<DT, 1, Spec> s;
+    s.col[0] = cvi * VEC;
+    if (g.vec_per_channel) {
+        // broadcast operands that are per channel: the same vector for every position and tile
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v) {
             if (v < Spec::n_vec(a)) {
-                // broadcast operands of this family are per channel: the same vector for every position
                 s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
                 if (active) s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], 0u, s.col[0], g.channels);
             }
         }
-        // ---- partial statistics from registers
-        LaneAcc la;
+    }
+
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const uint32_t sample = tile / g.blocks_per_sample;
+        const uint32_t bx = tile - sample * g.blocks_per_sample;
+        const uint32_t p_begin = bx * g.pos_per_block;
+        const uint32_t p_end = min(g.hw, p_begin + g.pos_per_block);
+
+        if (PHASE == 0 && stagger_tiles != 0u && tile >= stagger_tiles) {
+            if (t == 0)
+                wait_for_counter(g.ws_counter + (tile - stagger_tiles) / g.blocks_per_sample, g.epoch * g.blocks_per_sample,
+                                 g.spin_limit, g.ws_error);
+            __syncthreads();
+        }
+
+        // ---- the whole slice into registers
+        u32x4 raw[NV];
+        bool valid[NV];
+        uint32_t rel[NV];
+        const uint32_t rot = tile % NV;
+        const char* in_base = static_cast<const char*>(a.full[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            s.row[0] = sample * g.hw + p_begin + pstep + i * g.pos_per_step;
-            s.fraw[0][0] = raw[i];
-            run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
-            if (valid[i]) la.template add_vector<VEC>(s.acc);
+            rel[i] = pstep + ((i + rot) % NV) * g.pos_per_step;
+            valid[i] = active && p_begin + rel[i] < p_end;
+            raw[i] = u32x4{0u, 0u, 0u, 0u};
+            if (valid[i]) raw[i] = load_stream(in_base, (rel[i] * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
         }
-        const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
-        float* dst = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.groups) * 4u;
-        block_partial(g, st, pstep, cvi, active, g_lds_part, dst);
-        // ---- device-scope exchange: publish, arrive, wait for the sample's other workgroups
-        __syncthreads();  // all partial stores of this workgroup are issued
-        if (t == 0) {
-            __hip_atomic_fetch_add(g.ws_counter + sample, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            const uint32_t target = g.epoch * g.blocks_per_sample;
-            uint32_t spins = 0;
-            while ((int32_t)(__hip_atomic_load(g.ws_counter + sample, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-                if (++spins >= g.spin_limit) {
-                    __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
+
+        // Run the prologue on slice i (lean chains have none).
+        auto prologue = [&](int i) {
+            s.row[0] = sample * g.hw + p_begin + rel[i];
+            s.fraw[0][0] = raw[i];
+            if (!g.vec_per_channel) {
+#pragma unroll
+                for (int v = 0; v < Spec::NV; ++v) {
+                    if (v < Spec::n_vec(a)) {
+                        s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
+                        if (valid[i]) s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], s.row[0], s.col[0], g.channels);
+                    }
                 }
-                __builtin_amdgcn_s_sleep(8);
             }
+            if (kLean) Storage<DT>::unpack(raw[i], s.acc);
+            else run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
+        };
+
+        if (PHASE != 2) {
+            // ---- partial statistics from registers
+            LaneAcc la;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                if (kLean) {
+                    if (valid[i]) lean_add_vector<DT>(la, raw[i]);
+                } else {
+                    prologue(i);
+                    if (valid[i]) la.template add_vector<VEC>(s.acc);
+                }
+            }
+            const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
+            float* dst = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.groups) * 4u;
+            block_partial<PHASE == 0>(g, st, pstep, cvi, active, lds_part, dst);
         }
-        __syncthreads();
-        combine_sample<true>(g, sample, a.eps, g_lds_part, g_lds_stat);
-        // ---- normalise straight from registers
+        if (PHASE == 1) {
+            __syncthreads();  // LDS staging is reused by the next tile
+            continue;
+        }
+
+        if (PHASE == 0) {
+            // ---- device-scope exchange
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's coherent stores have completed
+            __syncthreads();
+            if (t == 0) {
+                const uint32_t before = __hip_atomic_fetch_add(g.ws_counter + sample, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (before + 1u == g.epoch * g.blocks_per_sample) ? 1u : 0u;
+            }
+            __syncthreads();
+            uint64_t* final_now = g.ws_final + ((uint64_t)(g.epoch & 1u) * g.samples + sample) * g.groups;
+            if (s_last) {
+                uint32_t grp;
+                float mean, rstd;
+                if (combine_sample<true>(g, sample, a.eps, &grp, &mean, &rstd)) {
+                    lds_stat[grp * 2u] = mean;
+                    lds_stat[grp * 2u + 1u] = rstd;
+                    const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, mean) | ((uint64_t)__builtin_bit_cast(uint32_t, rstd) << 32);
+                    uint64_t* final_next = g.ws_final + ((uint64_t)((g.epoch + 1u) & 1u) * g.samples + sample) * g.groups;
+                    __hip_atomic_store(final_next + grp, kFinalEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(final_now + grp, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else {
+                // one lane watches the sample's first word; once it is there every group's lane fetches its own
+                // word (re-polling the rare one that is a moment behind)
+                if (t == 0) {
+                    uint32_t spins = 0;
+                    while (__hip_atomic_load(final_now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kFinalEmpty) {
+                        if (++spins >= g.spin_limit) {
+                            __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+                }
+                __syncthreads();
+                if (t < g.groups) {
+                    uint64_t word;
+                    uint32_t spins = 0;
+                    for (;;) {
+                        word = __hip_atomic_load(final_now + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (word != kFinalEmpty) break;
+                        if (++spins >= g.spin_limit) {
+                            __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(4);
+                    }
+                    lds_stat[t * 2u] = __builtin_bit_cast(float, (uint32_t)word);
+                    lds_stat[t * 2u + 1u] = __builtin_bit_cast(float, (uint32_t)(word >> 32));
+                }
+            }
+            __syncthreads();
+        } else {
+            // PHASE 2: the partials were written by the previous launch
+            uint32_t grp;
+            float mean, rstd;
+            if (combine_sample<false>(g, sample, a.eps, &grp, &mean, &rstd)) {
+                lds_stat[grp * 2u] = mean;
+                lds_stat[grp * 2u + 1u] = rstd;
+            }
+            __syncthreads();
+        }
+
+        // ---- normalise straight from registers: y = x * A + B with A = rstd * gamma, B = beta - mean * A per
+        // channel, so each element costs one fused multiply-add (taken directly from the fp16 value)
+        const uint32_t my_grp = cvi >> g.log2_vpg;
+        const float mean = lds_stat[my_grp * 2u], rstd = lds_stat[my_grp * 2u + 1u];
+        float A[VEC], B[VEC];
+        auto affine = [&]() {
+            float gm[VEC], bt[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                gm[e] = 1.0f;
+                bt[e] = 0.0f;
+            }
+            if (Spec::gamma(a) >= 0) fetch_vec<DT, 1, Spec>(s, Spec::gamma(a), gm);
+            if (Spec::beta(a) >= 0) fetch_vec<DT, 1, Spec>(s, Spec::beta(a), bt);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                A[e] = rstd * gm[e];
+                B[e] = bt[e] - mean * A[e];
+            }
+        };
+        if (g.vec_per_channel) affine();
+        char* out_base = static_cast<char*>(a.out[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            s.row[0] = sample * g.hw + p_begin + pstep + i * g.pos_per_step;
-            s.fraw[0][0] = raw[i];
-            run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
-            group_normalise<DT, 1, Spec>(a, g, s, cvi, g_lds_stat);
+            prologue(i);
+            if (!g.vec_per_channel) affine();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-            if (valid[i])
-                store_stream(a.out[0], ((uint64_t)s.row[0] * g.channels + s.col[0]) * S::ESIZE, S::pack(s.acc));
+            if (valid[i]) store_stream(out_base, (rel[i] * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
         }
         __syncthreads();  // LDS staging is reused by the next tile
     }
@@ -358,66 +423,57 @@ struct GroupSpecOf<0> {
     using type = GenericSpec;
 };
 
-template <int ID, int DT>
-static hipError_t launch_group_dt(int which, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, dim3 grid,
+template <int ID, int DT, int PHASE>
+static hipError_t launch_group_nv(const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, uint32_t stagger, dim3 grid,
                                   dim3 block, hipStream_t st) {
     using Spec = typename GroupSpecOf<ID>::type;
-    if (which == 0) hipLaunchKernelGGL((group_stats_kernel<DT, 2, Spec>), grid, block, 0, st, a, g);
-    else if (which == 1) hipLaunchKernelGGL((group_apply_kernel<DT, 2, Spec>), grid, block, 0, st, a, g);
-    else {
-        if (ID == 0) return hipErrorInvalidValue;  // the resident variant exists for catalogue entries only
-        if constexpr (ID != 0) {
-            switch (nv) {
-                case 4: hipLaunchKernelGGL((group_resident_kernel<DT, 4, Spec>), grid, block, 0, st, a, g, tiles, grid.x); break;
-                case 8: hipLaunchKernelGGL((group_resident_kernel<DT, 8, Spec>), grid, block, 0, st, a, g, tiles, grid.x); break;
-                case 16: hipLaunchKernelGGL((group_resident_kernel<DT, 16, Spec>), grid, block, 0, st, a, g, tiles, grid.x); break;
-                default: return hipErrorInvalidValue;
-            }
-        }
+    switch (nv) {
+        case 4: hipLaunchKernelGGL((group_kernel<DT, 4, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
+        case 8: hipLaunchKernelGGL((group_kernel<DT, 8, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
+        case 16: hipLaunchKernelGGL((group_kernel<DT, 16, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
+        default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-template <int ID>
-static hipError_t launch_group_id(int which, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
+template <int ID, int DT>
+static hipError_t launch_group_dt(int phase, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, uint32_t stagger,
                                   dim3 grid, dim3 block, hipStream_t st) {
+    if (phase == 1) return launch_group_nv<ID, DT, 1>(a, g, nv, tiles, 0, grid, block, st);
+    if (phase == 2) return launch_group_nv<ID, DT, 2>(a, g, nv, tiles, 0, grid, block, st);
+    if constexpr (ID != 0) return launch_group_nv<ID, DT, 0>(a, g, nv, tiles, stagger, grid, block, st);
+    return hipErrorInvalidValue;  // the fused variant exists for catalogue entries only
+}
+
+template <int ID>
+static hipError_t launch_group_id(int phase, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
+                                  uint32_t stagger, dim3 grid, dim3 block, hipStream_t st) {
     switch (dtype) {
-        case DT_F32: return launch_group_dt<ID, DT_F32>(which, a, g, nv, tiles, grid, block, st);
-        case DT_F16: return launch_group_dt<ID, DT_F16>(which, a, g, nv, tiles, grid, block, st);
-        case DT_BF16: return launch_group_dt<ID, DT_BF16>(which, a, g, nv, tiles, grid, block, st);
+        case DT_F32: return launch_group_dt<ID, DT_F32>(phase, a, g, nv, tiles, stagger, grid, block, st);
+        case DT_F16: return launch_group_dt<ID, DT_F16>(phase, a, g, nv, tiles, stagger, grid, block, st);
+        case DT_BF16: return launch_group_dt<ID, DT_BF16>(phase, a, g, nv, tiles, stagger, grid, block, st);
         default: return hipErrorInvalidValue;
     }
 }
 
-static hipError_t launch_group_any(int which, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv,
-                                   uint32_t tiles, dim3 grid, dim3 block, hipStream_t st) {
+hipError_t launch_group(int phase, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
+                        uint32_t stagger, dim3 grid, dim3 block, hipStream_t st) {
     switch (spec_id) {
-        case 0: return launch_group_id<0>(which, dtype, a, g, nv, tiles, grid, block, st);
+        case 0: return launch_group_id<0>(phase, dtype, a, g, nv, tiles, stagger, grid, block, st);
 #define PF_CASE(id, ...) \
-    case id: return launch_group_id<id>(which, dtype, a, g, nv, tiles, grid, block, st);
+    case id: return launch_group_id<id>(phase, dtype, a, g, nv, tiles, stagger, grid, block, st);
             PF_GROUP_SPECS(PF_CASE)
 #undef PF_CASE
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_group_stats(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, dim3 grid, dim3 block, hipStream_t st) {
-    return launch_group_any(0, spec_id, dtype, a, g, 0, 0, grid, block, st);
-}
-hipError_t launch_group_apply(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, dim3 grid, dim3 block, hipStream_t st) {
-    return launch_group_any(1, spec_id, dtype, a, g, 0, 0, grid, block, st);
-}
-hipError_t launch_group_resident(int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, dim3 grid,
-                                 dim3 block, hipStream_t st) {
-    return launch_group_any(2, spec_id, dtype, a, g, nv, tiles, grid, block, st);
-}
-
-// how many workgroups of the resident kernel one compute unit holds (for sizing a co-resident grid)
+// how many workgroups of the fused kernel one compute unit holds (for sizing a co-resident grid)
 int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads) {
     int n = 0;
 #define PF_OCC(ID, DT, NVV)                                                                                          \
     if (spec_id == ID && dtype == DT && nv == NVV)                                                                   \
-        (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, group_resident_kernel<DT, NVV, typename GroupSpecOf<ID>::type>, \
+        (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, group_kernel<DT, NVV, typename GroupSpecOf<ID>::type, 0>, \
                                                            block_threads, 0);
 #define PF_OCC_ALL(id, ...)                                                                            \
     PF_OCC(id, DT_F32, 4) PF_OCC(id, DT_F32, 8) PF_OCC(id, DT_F32, 16) PF_OCC(id, DT_F16, 4) PF_OCC(id, DT_F16, 8) \

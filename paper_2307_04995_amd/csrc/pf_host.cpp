@@ -704,6 +704,7 @@ struct pf_plan_s {
     Shape out_shape[PF_MAX_OUTPUTS];
     int n_launches = 1;
     mutable uint32_t epoch = 0;
+    uint32_t stagger_tiles = 0;  // group family, resident variant: tiles of the first half of a staggered launch
 };
 
 namespace {
@@ -998,7 +999,6 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     if (cpg % vec != 0) return fail(PF_ERR_UNSUPPORTED, "channels per group (%lld) must be a multiple of %d", (long long)cpg, vec);
     const int64_t vpg = cpg / vec, cv = C / vec;
     if ((vpg & (vpg - 1)) != 0 || vpg > 64) return fail(PF_ERR_UNSUPPORTED, "channels per group / %d must be a power of two <= 64", vec);
-    if (cv > 1024) return fail(PF_ERR_UNSUPPORTED, "more than %d channels", 1024 * vec);
     if (samples * hw > 0xffffffffLL || samples > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
     for (int v = 0; v < L.n_vec; ++v)
         if (p->args.vec[v].numel > (uint32_t)C && p->args.vec[v].numel != 1)
@@ -1018,7 +1018,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     g.log2_vpg = 0;
     while ((1u << g.log2_vpg) < g.vpg) ++g.log2_vpg;
     g.div_cv = make_fastdiv(g.cv);
-    g.spin_limit = 1u << 22;
+    g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().group, L);
 
@@ -1027,36 +1027,56 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
         return fail(PF_ERR_HIP, "cannot query device %d (the group family needs the device at plan time)", p->device);
     const int n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-    const uint32_t threads = 1024;
+    // Workgroups of 512 threads; a tile is NV position steps of 512 / cv positions each.
+    const uint32_t threads = 512;
+    if (g.cv > threads) return fail(PF_ERR_UNSUPPORTED, "more than %d channels", (int)threads * vec);
     g.pos_per_step = threads / g.cv;
-
-    // resident variant: catalogue entry, one full operand, per-channel broadcast operands only
-    bool resident_ok = p->spec_id != 0 && L.n_full == 1;
+    g.vec_per_channel = 1;
     for (int v = 0; v < L.n_vec; ++v)
-        if (p->args.vec[v].numel > (uint32_t)C) resident_ok = false;
+        if (p->args.vec[v].numel > (uint32_t)C) g.vec_per_channel = 0;
+    // lanes that share a group when partials are merged: as many as fit, a power of two, at most 64
+    g.lanes_per_group = 1;
+    while (g.lanes_per_group < 64u && g.lanes_per_group * 2u * g.groups <= threads) g.lanes_per_group *= 2u;
+
+    auto tiling = [&](int nv_c, uint32_t* bps_out) {
+        const uint32_t ppb = (uint32_t)nv_c * g.pos_per_step;
+        *bps_out = (uint32_t)((hw + ppb - 1) / ppb);
+    };
+    // the largest tile that still gives every compute unit two workgroups
+    const int cands[3] = {16, 8, 4};
+    const int forced_nv = env_int("PF_GROUP_NV", 0);
     int nv = 0;
-    uint32_t res_bps = 0, res_grid = 0;
-    if (resident_ok) {
-        // largest slice per workgroup that still gives every compute unit work
-        const int cands[3] = {16, 8, 4};
-        for (int ci = 0; ci < 3 && nv == 0; ++ci) {
-            const uint32_t ppb = cands[ci] * g.pos_per_step;
-            const uint32_t bps = (uint32_t)((hw + ppb - 1) / ppb);
-            const uint64_t tiles = (uint64_t)bps * samples;
-            if (bps * g.groups > 2048u) continue;
-            if (tiles >= (uint64_t)n_cu || ci == 2) {
-                const int per_cu = pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, cands[ci], (int)threads);
-                if (per_cu < 1) continue;
-                uint64_t cap = (uint64_t)per_cu * n_cu;
-                uint64_t grid = std::min<uint64_t>(tiles, cap);
-                grid = grid / bps * bps;  // whole samples per round, so every wait is for co-resident workgroups
-                if (grid < bps) continue;
-                nv = cands[ci];
-                res_bps = bps;
-                res_grid = (uint32_t)grid;
-            }
+    uint32_t bps = 0;
+    for (int ci = 0; ci < 3 && nv == 0; ++ci) {
+        if (forced_nv && cands[ci] != forced_nv) continue;
+        uint32_t b;
+        tiling(cands[ci], &b);
+        if ((uint64_t)b * samples >= 2 * (uint64_t)n_cu || ci == 2 || forced_nv) {
+            nv = cands[ci];
+            bps = b;
         }
-        if (nv == 0) resident_ok = false;
+    }
+    if (nv == 0) return fail(PF_ERR_INVALID_ARG, "PF_GROUP_NV must be 4, 8 or 16");
+    const uint64_t tiles = (uint64_t)bps * samples;
+    if (tiles > 0x7fffffffull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
+
+    // resident variant: catalogue entry, one full operand, per-channel broadcast operands only, and a grid the
+    // device holds at once
+    bool resident_ok = p->spec_id != 0 && L.n_full == 1 && g.vec_per_channel;
+    uint32_t res_grid = 0, res_stagger = 0;
+    if (resident_ok) {
+        const int per_cu = pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, nv, (int)threads);
+        const uint64_t cap = (uint64_t)std::max(per_cu, 0) * n_cu;
+        uint64_t grid = std::min<uint64_t>(tiles, cap);
+        grid = grid / bps * bps;  // whole samples per round, so every wait is for co-resident workgroups
+        if (grid < bps) resident_ok = false;
+        else {
+            res_grid = (uint32_t)grid;
+            // staggering the two halves of a single-round launch is available for experiments (PF_GROUP_STAGGER=1);
+            // measured on MI355X it does not pay: the exchange latency of the second half stays on the critical path
+            if (grid == tiles && samples % 2 == 0 && tiles >= (uint64_t)n_cu && env_int("PF_GROUP_STAGGER", 0) != 0)
+                res_stagger = (uint32_t)(tiles / 2);
+        }
     }
     int variant = forced_variant >= 0 ? forced_variant : (resident_ok ? PF_VARIANT_GROUP_RESIDENT : PF_VARIANT_GROUP_TWO_PASS);
     if (variant == PF_VARIANT_GROUP_RESIDENT && !resident_ok)
@@ -1065,41 +1085,34 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
         return fail(PF_ERR_UNSUPPORTED, "unknown group variant %d", variant);
     p->variant = variant;
     p->block = dim3(threads);
+    g.pos_per_block = (uint32_t)nv * g.pos_per_step;
+    g.blocks_per_sample = bps;
+    p->k = nv;
     if (variant == PF_VARIANT_GROUP_RESIDENT) {
-        g.pos_per_block = nv * g.pos_per_step;
-        g.blocks_per_sample = res_bps;
-        p->k = nv;
         p->grid = dim3(res_grid);
+        p->stagger_tiles = res_stagger;
         p->n_launches = 1;
     } else {
-        // enough workgroups to fill the device, whole steps of two positions-steps per iteration
-        const uint32_t step = g.pos_per_step * 2u;
-        uint32_t want_bps = (uint32_t)std::max<int64_t>(1, (4 * n_cu + samples - 1) / samples);
-        uint32_t ppb = (uint32_t)((hw + want_bps - 1) / want_bps);
-        ppb = (ppb + step - 1) / step * step;
-        uint32_t bps = (uint32_t)((hw + ppb - 1) / ppb);
-        while (bps * g.groups > 2048u) {
-            ppb *= 2;
-            bps = (uint32_t)((hw + ppb - 1) / ppb);
-        }
-        g.pos_per_block = ppb;
-        g.blocks_per_sample = bps;
-        p->k = 2;
-        p->grid = dim3(bps, (uint32_t)samples);
+        p->grid = dim3((uint32_t)tiles);
         p->grid2 = p->grid;
         p->block2 = p->block;
+        p->stagger_tiles = 0;
         p->n_launches = 2;
     }
-    p->lds_bytes = 2048 * 3 * 4 + 1024 * 2 * 4;
-    // workspace: partials, arrival counters, error word
+    p->lds_bytes = 512 * 3 * 4 + 512 * 2 * 4 + 4;
+    // workspace: partials, two parities of per-sample (mean, rstd) words, arrival counters, error word
     const uint64_t part_bytes = (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
+    const uint64_t final_bytes = (((uint64_t)2 * samples * g.groups * sizeof(uint64_t)) + 255) / 256 * 256;
     const uint64_t cnt_bytes = ((uint64_t)samples * sizeof(uint32_t) + 255) / 256 * 256;
-    p->workspace_bytes = part_bytes + cnt_bytes + 256;
+    p->workspace_bytes = part_bytes + final_bytes + cnt_bytes + 256;
     if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
-    if (hipMemset(p->workspace, 0, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
-    g.ws_partial = static_cast<float*>(p->workspace);
-    g.ws_counter = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
-    g.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes + cnt_bytes);
+    char* ws = static_cast<char*>(p->workspace);
+    if (hipMemset(ws, 0, p->workspace_bytes) != hipSuccess || hipMemset(ws + part_bytes, 0xff, final_bytes) != hipSuccess)
+        return fail(PF_ERR_HIP, "workspace clear failed");
+    g.ws_partial = reinterpret_cast<float*>(ws);
+    g.ws_final = reinterpret_cast<uint64_t*>(ws + part_bytes);
+    g.ws_counter = reinterpret_cast<uint32_t*>(ws + part_bytes + final_bytes);
+    g.ws_error = reinterpret_cast<uint32_t*>(ws + part_bytes + final_bytes + cnt_bytes);
     p->args.n_inner = (uint32_t)C;
     p->args.rows = (uint64_t)(samples * hw);
     return PF_OK;
@@ -1252,12 +1265,12 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
         case PF_FAMILY_GROUP: {
             pf::GroupGeom g = plan->group;
             g.epoch = ++plan->epoch;
+            const uint32_t tiles = g.samples * g.blocks_per_sample;
             if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
-                e = pf::launch_group_stats(plan->spec_id, L.main_dtype, a, g, plan->grid, plan->block, st);
-                if (e == hipSuccess) e = pf::launch_group_apply(plan->spec_id, L.main_dtype, a, g, plan->grid2, plan->block2, st);
+                e = pf::launch_group(1, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, 0, plan->grid, plan->block, st);
+                if (e == hipSuccess) e = pf::launch_group(2, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, 0, plan->grid2, plan->block2, st);
             } else {
-                e = pf::launch_group_resident(plan->spec_id, L.main_dtype, a, g, plan->k, g.samples * g.blocks_per_sample, plan->grid,
-                                              plan->block, st);
+                e = pf::launch_group(0, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->stagger_tiles, plan->grid, plan->block, st);
             }
             break;
         }
