@@ -258,30 +258,30 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             __syncthreads();
         }
 
-        // ---- the whole slice into registers
+        // ---- the whole slice into registers (positions and validity are recomputed where needed rather than
+        // kept: the registers are for data)
         u32x4 raw[NV];
-        bool valid[NV];
-        uint32_t rel[NV];
         const uint32_t rot = tile % NV;
+        const uint32_t p_count = p_end - p_begin;
+        auto rel_of = [&](int i) { return pstep + (((uint32_t)i + rot) % NV) * g.pos_per_step; };
+        auto valid_of = [&](int i) { return active && rel_of(i) < p_count; };
         const char* in_base = static_cast<const char*>(a.full[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            rel[i] = pstep + ((i + rot) % NV) * g.pos_per_step;
-            valid[i] = active && p_begin + rel[i] < p_end;
             raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid[i]) raw[i] = load_stream(in_base, (rel[i] * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
+            if (valid_of(i)) raw[i] = load_stream(in_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
         }
 
         // Run the prologue on slice i (lean chains have none).
         auto prologue = [&](int i) {
-            s.row[0] = sample * g.hw + p_begin + rel[i];
+            s.row[0] = sample * g.hw + p_begin + rel_of(i);
             s.fraw[0][0] = raw[i];
             if (!g.vec_per_channel) {
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v) {
                     if (v < Spec::n_vec(a)) {
                         s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                        if (valid[i]) s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], s.row[0], s.col[0], g.channels);
+                        if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], s.row[0], s.col[0], g.channels);
                     }
                 }
             }
@@ -295,10 +295,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 if (kLean) {
-                    if (valid[i]) lean_add_vector<DT>(la, raw[i]);
+                    if (valid_of(i)) lean_add_vector<DT>(la, raw[i]);
                 } else {
                     prologue(i);
-                    if (valid[i]) la.template add_vector<VEC>(s.acc);
+                    if (valid_of(i)) la.template add_vector<VEC>(s.acc);
                 }
             }
             const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
@@ -402,7 +402,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 #pragma unroll
             for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-            if (valid[i]) store_stream(out_base, (rel[i] * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
+            if (valid_of(i)) store_stream(out_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
         }
         __syncthreads();  // LDS staging is reused by the next tile
     }
