@@ -191,6 +191,14 @@ pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
  */
 pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *const *outputs, void *stream);
 
+/*
+ * Kernels that wait for other workgroups (the fused GroupNorm variant) bound every wait; when a wait runs
+ * out they set an error word in the plan's workspace and carry on, so a launch always terminates.  This call
+ * synchronises with the device (hipMemcpy), stores the word in *flag (0 = no wait ever gave up since the
+ * plan was made) and clears it.  Plans without workspace always report 0.
+ */
+pf_status pf_chain_plan_poll_error(const pf_plan *plan, int32_t *flag);
+
 void pf_chain_plan_destroy(pf_plan *plan);
 
 const char *pf_status_str(pf_status s);

@@ -62,8 +62,8 @@ class pf_plan_info(C.Structure):
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
-           "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_destroy", "pf_status_str", "pf_last_error",
-           "pf_copy_probe"]
+           "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
+           "pf_last_error", "pf_copy_probe"]
 
 
 def _load() -> C.CDLL:
@@ -79,6 +79,7 @@ def _load() -> C.CDLL:
     lib.pf_chain_plan_variant.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.c_int32, C.POINTER(vp)]
     lib.pf_chain_plan_get_info.argtypes = [vp, C.POINTER(pf_plan_info)]
     lib.pf_chain_run.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.pf_chain_plan_poll_error.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.pf_chain_plan_destroy.argtypes = [vp]
     lib.pf_chain_plan_destroy.restype = None
     lib.pf_status_str.argtypes = [C.c_int]
@@ -148,6 +149,13 @@ def pf_chain_run(plan, input_ptrs: Sequence[int], output_ptrs: Sequence[int], st
     ins = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
     outs = (C.c_void_p * len(output_ptrs))(*[C.c_void_p(int(p)) for p in output_ptrs])
     return _lib.pf_chain_run(plan, ins, outs, C.c_void_p(int(stream)))
+
+
+def pf_chain_plan_poll_error(plan):
+    """Returns (status, flag)."""
+    flag = C.c_int32(0)
+    st = _lib.pf_chain_plan_poll_error(plan, C.byref(flag))
+    return st, flag.value
 
 
 def pf_chain_plan_destroy(plan) -> None:
@@ -233,6 +241,12 @@ class Plan:
             if not t.is_cuda or not t.is_contiguous():
                 raise ValueError("tensors must be contiguous device tensors")
         self.run_ptrs([t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], stream)
+
+    def poll_error(self) -> int:
+        st, flag = pf_chain_plan_poll_error(self.handle)
+        if st != PF_OK:
+            raise PfError(st, pf_last_error())
+        return flag
 
     def close(self) -> None:
         if getattr(self, "handle", None) is not None:

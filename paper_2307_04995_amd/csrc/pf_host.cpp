@@ -1284,6 +1284,18 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
     return PF_OK;
 }
 
+pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
+    if (!plan || !flag) return fail(PF_ERR_INVALID_ARG, "null argument");
+    *flag = 0;
+    if (plan->family != PF_FAMILY_GROUP || !plan->group.ws_error) return PF_OK;
+    uint32_t word = 0;
+    if (hipMemcpy(&word, plan->group.ws_error, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(PF_ERR_HIP, "cannot read the error word");
+    if (word != 0u && hipMemset(plan->group.ws_error, 0, sizeof(word)) != hipSuccess) return fail(PF_ERR_HIP, "cannot clear the error word");
+    *flag = (int32_t)word;
+    return PF_OK;
+}
+
 void pf_chain_plan_destroy(pf_plan* plan) {
     if (!plan) return;
     if (plan->workspace) (void)hipFree(plan->workspace);

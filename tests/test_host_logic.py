@@ -16,8 +16,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "pf_chain.h")).read()
     declared = set(re.findall(r"^\s*(?:pf_status|void|const char \*)\s*\*?(pf_[a-z_]+)\s*\(", header, flags=re.M))
     assert {"pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
-            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_destroy", "pf_status_str", "pf_last_error",
-            "pf_copy_probe"} <= declared
+            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
+            "pf_last_error", "pf_copy_probe"} <= declared
     lib = ctypes.CDLL(pf.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in pf_chain.h but not exported"
