@@ -61,6 +61,7 @@ def full_size_chain(name):
         "C3": "C3 fp16 x+bias+res -> LayerNorm [16384x1024]",
         "C4": "C4 bf16 (Q+bias)*0.125 -> permute [32,512,16,64]->[32,16,512,64]",
         "C5": "C5 fp16 NHWC GroupNorm(32)+SiLU [16,64,64,512]",
+        "X1": "X1 bf16 (K+bias)*0.125 -> transpose [32,512,1024]->[32,1024,512] (not a BASELINE config)",
     }
     return spec, ins, algorithmic, nominal, labels[name]
 
@@ -208,7 +209,7 @@ def main():
     }
     if not args.no_context:
         chains = {}
-        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5"]) if c]
+        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5", "X1"]) if c]
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
             h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2))

@@ -147,7 +147,8 @@ typedef struct {
 #define PF_VARIANT_GROUP_RESIDENT 1   /* group family: x held in registers across a device-scope exchange    */
 #define PF_VARIANT_T_ROWS 0           /* transpose family: innermost dim kept, 16-byte vectors re-addressed  */
 #define PF_VARIANT_T_LDS_ROWS 1       /* transpose family: innermost dim kept, LDS tile makes both sides long*/
-#define PF_VARIANT_T_LDS_TILE 2       /* transpose family: innermost dim changes, padded LDS tile transposed */
+#define PF_VARIANT_T_TILE 2           /* transpose family: innermost dim changes, square tiles, blocks of elements
+                                         transposed in registers                                               */
 
 typedef struct pf_plan_s pf_plan; /* opaque plan object, owned by the library */
 

@@ -147,8 +147,11 @@ struct PermGeom {
     FastDiv div_in_inner, div_out_inner;
     uint32_t total_vecs;
     uint32_t epi_full_mask, epi_vec_mask;       // operands addressed in the output layout
-    // LDS-staged variant (innermost dim kept): a workgroup moves a [tile_a x tile_b] block of inner rows
+    // LDS-staged variant (innermost dim kept): a workgroup moves a [tile_a x tile_b] block of inner rows.
+    // Tile variant (innermost dim changes): tile_a / tile_b = extents of the input's / output's innermost dim.
     uint32_t tile_a, tile_b;
+    uint32_t t_in_stride_o;   // tile variant: input stride (elements) of the output's innermost dim
+    uint32_t t_out_stride_i;  // tile variant: output stride (elements) of the input's innermost dim
 };
 
 }  // namespace pf

@@ -889,10 +889,6 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     }
     if (od.empty()) od.push_back(Dim{1, 1});
     const int m = (int)od.size();
-    if (od.back().in_stride != 1)
-        return fail(PF_ERR_UNSUPPORTED, "permutations that change the innermost dimension are not implemented yet");
-    const int64_t inner = od.back().extent;
-    if ((inner * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost run of %lld elements is not a multiple of 16 bytes", (long long)inner);
     // the vectors of broadcast operands must not straddle rows of either layout
     if ((L.pre_shape.back() * es) % 16 != 0 || (L.post_shape.back() * es) % 16 != 0)
         return fail(PF_ERR_ALIGNMENT, "innermost extent is not a multiple of 16 bytes");
@@ -911,6 +907,63 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     for (int q = m - 1; q >= 0; --q) { ostr[q] = acc; acc *= od[q].extent; }
     p->family = PF_FAMILY_TRANSPOSE;
     p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().perm, L);
+    p->args.n_inner = g.in_n_inner;
+    p->args.rows = (uint64_t)(numel(in) / g.in_n_inner);
+
+    if (od.back().in_stride != 1) {
+        // ---- the innermost dimension changes: square tiles over (input-innermost I, output-innermost O)
+        if (forced_variant >= 0 && forced_variant != PF_VARIANT_T_TILE)
+            return fail(PF_ERR_UNSUPPORTED, "variant %d is not implemented for this permutation", forced_variant);
+        int qi = -1;
+        for (int q = 0; q < m; ++q)
+            if (od[q].in_stride == 1) qi = q;
+        if (qi < 0) return fail(PF_ERR_UNSUPPORTED, "internal: no contiguous input dimension");
+        const int64_t n_i = od[qi].extent, n_o = od.back().extent;
+        if ((n_i * es) % 16 != 0 || (n_o * es) % 16 != 0)
+            return fail(PF_ERR_ALIGNMENT, "transposed extents (%lld, %lld) are not multiples of 16 bytes", (long long)n_i, (long long)n_o);
+        const bool pro_trivial = L.pro.n == 1 && L.pro.u[0].code == pf::U_MOV && L.pro.u[0].kind == pf::K_FULL && L.pro.u[0].slot == 0;
+        if (es == 2 && !pro_trivial && L.epi.n != 0)
+            return fail(PF_ERR_UNSUPPORTED, "16-bit chains may compute on one side of an innermost-changing permutation only");
+        if (L.n_full < 1 || L.pro.n < 1 || L.pro.u[0].code != pf::U_MOV || L.pro.u[0].kind != pf::K_FULL || L.pro.u[0].slot != 0)
+            return fail(PF_ERR_UNSUPPORTED, "the permuted value must start from a full-shape input");
+        const int64_t te = 8 * vec;
+        int r = 0;
+        uint64_t total_tiles = 1;
+        for (int q = 0; q < m - 1; ++q) {
+            if (q == qi) continue;
+            g.extent[r] = (uint32_t)od[q].extent;
+            g.in_stride[r] = (uint32_t)od[q].in_stride;
+            g.out_stride[r] = (uint32_t)ostr[q];
+            ++r;
+        }
+        g.extent[r] = (uint32_t)((n_i + te - 1) / te);
+        g.in_stride[r] = (uint32_t)te;
+        g.out_stride[r] = (uint32_t)(te * ostr[qi]);
+        ++r;
+        g.extent[r] = (uint32_t)((n_o + te - 1) / te);
+        g.in_stride[r] = (uint32_t)(te * od.back().in_stride);
+        g.out_stride[r] = (uint32_t)te;
+        ++r;
+        g.rank = r;
+        for (int q = 0; q < r; ++q) {
+            g.div[q] = make_fastdiv(g.extent[q]);
+            total_tiles *= g.extent[q];
+        }
+        if (total_tiles > 0x7fffffffull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the transpose family");
+        g.total_vecs = (uint32_t)total_tiles;
+        g.tile_a = (uint32_t)n_i;
+        g.tile_b = (uint32_t)n_o;
+        g.t_in_stride_o = (uint32_t)od.back().in_stride;
+        g.t_out_stride_i = (uint32_t)ostr[qi];
+        p->variant = PF_VARIANT_T_TILE;
+        p->k = vec;
+        p->block = dim3(256);
+        p->grid = dim3((uint32_t)((total_tiles + 3) / 4));
+        p->lds_bytes = 0;
+        return PF_OK;
+    }
+    const int64_t inner = od.back().extent;
+    if ((inner * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost run of %lld elements is not a multiple of 16 bytes", (long long)inner);
     // LDS-staged variant: [batch, A, B, inner] -> [batch, B, A, inner]
     bool lds_ok = false;
     uint32_t ta = 0, tb = 0;
@@ -980,8 +1033,6 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
         p->lds_bytes = 0;
     }
-    p->args.n_inner = g.in_n_inner;
-    p->args.rows = (uint64_t)(numel(in) / g.in_n_inner);
     return PF_OK;
 }
 

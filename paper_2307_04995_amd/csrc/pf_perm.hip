@@ -10,6 +10,8 @@
 //               other side is contiguous in runs of the innermost extent;
 //   T_LDS_ROWS  a workgroup stages a [tile_a x tile_b] block of innermost rows in LDS between a read phase
 //               and a write phase, so both sides are walked in long contiguous runs.
+// Variant for permutations that change the innermost dimension:
+//   T_TILE      a wave owns a square tile; each lane transposes a VEC x VEC block of elements in registers.
 #include "pf_device.hpp"
 #include "pf_launch.h"
 #include "pf_row_kernels.hpp"
@@ -40,7 +42,8 @@ PF_DEVICE void perm_offsets(const PermGeom& g, uint32_t v, uint32_t vec, uint32_
     *out_off = oo;
 }
 
-template <int DT, int K, class Spec>
+// SIDES: 3 = operands of both programs, 1 = prologue operands only (input layout), 2 = epilogue operands only
+template <int DT, int K, class Spec, int SIDES = 3>
 PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneState<DT, K, Spec>& s, const uint32_t* in_off,
                                   const uint32_t* out_off, const bool* valid) {
     using S = Storage<DT>;
@@ -48,6 +51,7 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
     for (int f = 0; f < Spec::NF; ++f) {
         if (f < Spec::n_full(a)) {
             const bool epi = (g.epi_full_mask >> f) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
@@ -59,6 +63,7 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
     for (int v = 0; v < Spec::NV; ++v) {
         if (v < Spec::n_vec(a)) {
             const bool epi = (g.epi_vec_mask >> v) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
             const uint32_t inner = epi ? g.out_n_inner : g.in_n_inner;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -170,6 +175,88 @@ __global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, c
     }
 }
 
+// Variant for permutations that change the innermost dimension.  Let I be the input's innermost dim and O
+// the output's.  A wave owns a square tile of 8 x 8 lanes; lane (ti, to) loads VEC vectors -- rows
+// o = to * VEC + r of the tile, columns i = ti * VEC .. + VEC - 1 -- so every load instruction of the wave
+// reads 8 runs of 8 * 16 = 128 contiguous bytes.  The lane transposes its VEC x VEC block of elements in
+// registers (byte permutes for 16-bit types, pure renaming for fp32) and stores VEC vectors -- rows
+// i = ti * VEC + c, columns o = to * VEC .. -- so every store instruction writes 8 runs of 128 contiguous
+// bytes as well.  Both sides move whole 128-byte lines and nothing passes through LDS: the exchange the
+// layout change needs fits inside one lane's registers (lane scope in the paper's terms) once the tile is
+// cut this way.  Element-wise steps run on the side whose layout their operands have; to keep a single
+// rounding, 16-bit chains may compute on one side only (the planner enforces it).
+template <int DT>
+PF_DEVICE void transpose_block(const u32x4 (&in)[Storage<DT>::VEC], u32x4 (&out)[Storage<DT>::VEC]) {
+    if (DT == DT_F32) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[c][r] = in[r][c];
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // output vector c, dword j = elements (row 2j, column c) and (row 2j + 1, column c)
+                const uint32_t lo = in[2 * j][c / 2], hi = in[2 * j + 1][c / 2];
+                out[c][j] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            }
+    }
+}
+
+template <int DT, class Spec>
+__global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr uint32_t TE = 8u * VEC;  // tile edge in elements
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x * 4u + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (tile >= g.total_vecs) return;  // total_vecs counts tiles in this variant; wave-uniform exit
+    uint32_t in_base, out_base;
+    perm_offsets(g, tile, 1u, &in_base, &out_base);
+    const uint32_t q_o = fast_div(tile, g.div[g.rank - 1]);
+    const uint32_t ot = tile - q_o * g.extent[g.rank - 1];
+    const uint32_t it = q_o - fast_div(q_o, g.div[g.rank - 2]) * g.extent[g.rank - 2];
+    const uint32_t ti = lane & 7u, to = lane >> 3;
+    const bool valid = (it * TE + ti * VEC < g.tile_a) && (ot * TE + to * VEC < g.tile_b);
+
+    LaneState<DT, 1, Spec> s;
+    u32x4 blk[VEC], outv[VEC];
+    const bool pro_trivial = a.pro.n == 1;  // nothing but the load
+    uint32_t in_off[VEC];
+#pragma unroll
+    for (int r = 0; r < VEC; ++r) {
+        in_off[r] = in_base + (to * VEC + r) * g.t_in_stride_o + ti * VEC;
+        blk[r] = u32x4{0u, 0u, 0u, 0u};
+        if (valid) blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
+    }
+    if (!pro_trivial) {
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+            const uint32_t zero = 0u;
+            perm_load_operands<DT, 1, Spec, 1>(a, g, s, &in_off[r], &zero, &valid);
+            s.fraw[0][0] = blk[r];
+            set_positions<DT, 1, Spec>(s, &in_off[r], g.div_in_inner, g.in_n_inner);
+            run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+            blk[r] = S::pack(s.acc);
+        }
+    }
+    transpose_block<DT>(blk, outv);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        const uint32_t out_off = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
+        if (a.epi.n != 0) {
+            const uint32_t zero = 0u;
+            perm_load_operands<DT, 1, Spec, 2>(a, g, s, &zero, &out_off, &valid);
+            S::unpack(outv[c], s.acc);
+            set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
+            run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+            outv[c] = S::pack(s.acc);
+        }
+        if (valid) store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, outv[c]);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 template <int ID>
 struct PermSpecOf;
@@ -189,7 +276,9 @@ template <int ID, int DT>
 static hipError_t launch_perm_spec_dt(const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid, dim3 block,
                                       uint32_t lds, hipStream_t st) {
     using Spec = typename PermSpecOf<ID>::type;
-    if (variant == 1) {
+    if (variant == 2) {
+        hipLaunchKernelGGL((perm_tile_kernel<DT, Spec>), grid, block, 0, st, a, g);
+    } else if (variant == 1) {
         hipLaunchKernelGGL((perm_lds_rows_kernel<DT, Spec>), grid, block, lds, st, a, g);
     } else if (k == 2) {
         hipLaunchKernelGGL((perm_rows_kernel<DT, 2, Spec>), grid, block, 0, st, a, g);

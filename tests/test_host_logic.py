@@ -189,10 +189,19 @@ def test_plan_errors():
     s = wl.ChainSpec(inputs=[("f32", (2, 65536))])
     s.out(s.op("softmax", 0), "f32")
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
-    # innermost-changing permutation is not implemented yet
+    # an innermost-changing permutation of 16-bit data may compute on one side only
+    s = wl.ChainSpec(inputs=[("f16", (8, 64, 64))])
+    v = s.op("relu", 0)
+    v = s.op("permute", v, i=[0, 2, 1])
+    s.out(s.op("tanh", v), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
     s = wl.ChainSpec(inputs=[("f16", (8, 64, 64))])
     s.out(s.op("permute", 0, i=[0, 2, 1]), "f16")
-    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    assert _plan_status(s) == pf.PF_OK
+    # ... and its transposed extents must both be whole 16-byte vectors
+    s = wl.ChainSpec(inputs=[("f16", (8, 12, 64))])
+    s.out(s.op("permute", 0, i=[0, 2, 1]), "f16")
+    assert _plan_status(s) == pf.PF_ERR_ALIGNMENT
     # a value computed before the core is used after it
     s = wl.ChainSpec(inputs=[("f32", (4, 64))])
     a = s.op("relu", 0)

@@ -131,6 +131,60 @@ def test_permute_only_bit_exact(shape, perm, dtype):
         assert np.array_equal(wl.raw_bits(out), want)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((3, 64, 128), (0, 2, 1)), ((72, 40), (1, 0)), ((2, 24, 3, 16), (0, 3, 2, 1)),
+                                        ((2, 8, 136, 200), (1, 3, 0, 2)), ((5, 8, 8, 16), (3, 1, 0, 2))])
+def test_innermost_changing_permute_bit_exact(shape, perm, dtype):
+    from oracle import pf_oracle as orc
+    g = np.random.default_rng(101)
+    nbits = 32 if dtype == "f32" else 16
+    bits = g.integers(0, 1 << nbits, size=shape, dtype=np.uint32 if nbits == 32 else np.uint16)
+    t = torch.from_numpy(bits.view(np.int32 if nbits == 32 else np.int16)).view(wl.DTYPES[dtype])
+    spec = wl.ChainSpec(inputs=[(dtype, shape)])
+    spec.out(spec.op("permute", 0, i=perm), dtype)
+    (out,), info = gpu_run(spec, [t])
+    assert info.variant == _pf().PF_VARIANT_T_TILE
+    (want,) = orc.evaluate_layout_bits(spec, [bits])
+    assert np.array_equal(wl.raw_bits(out), want)
+
+
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_transpose_fused_with_elementwise(dtype, generic):
+    # K^T-style chain: (x + bias) * scale computed on the input layout, then [b, s, d] -> [b, d, s]
+    b, sq, d = 3, 200, 64
+    x = wl.random_tensor((b, sq, d), dtype, 61)
+    bias = wl.random_tensor((d,), dtype, 62)
+    spec = wl.ChainSpec(inputs=[(dtype, (b, sq, d)), (dtype, (d,))])
+    v = spec.op("add", 0, 1)
+    v = spec.op("scale", v, f=[0.125])
+    v = spec.op("permute", v, i=[0, 2, 1])
+    spec.out(v, dtype)
+    outs, info, _ = check_chain(spec, [x, bias], generic=generic, what="fused transpose, prologue side")
+    assert info.variant == _pf().PF_VARIANT_T_TILE
+    # compute on the output layout instead: permute first, then an operand shaped like the output rows
+    col = wl.random_tensor((sq,), dtype, 63, scale=0.5)     # keeps |result| small: the 16-bit bars are absolute
+    spec2 = wl.ChainSpec(inputs=[(dtype, (b, sq, d)), (dtype, (sq,))])
+    v = spec2.op("permute", 0, i=[0, 2, 1])
+    v = spec2.op("mul", v, 1)
+    v = spec2.op("gelu_erf", v)
+    spec2.out(v, dtype)
+    check_chain(spec2, [x, col], generic=generic, what="fused transpose, epilogue side")
+
+
+def test_transpose_fp32_computes_on_both_sides():
+    b, sq, d = 2, 72, 40
+    x = wl.random_tensor((b, sq, d), "f32", 64)
+    bias = wl.random_tensor((d,), "f32", 65)
+    col = wl.random_tensor((sq,), "f32", 66)
+    spec = wl.ChainSpec(inputs=[("f32", (b, sq, d)), ("f32", (d,)), ("f32", (sq,))])
+    v = spec.op("add", 0, 1)
+    v = spec.op("permute", v, i=[0, 2, 1])
+    v = spec.op("mul", v, 2)
+    spec.out(v, "f32")
+    check_chain(spec, [x, bias, col], what="fp32 transpose, both sides")
+
+
 # ------------------------------------------------------------------ other cores and the element-wise family
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])

@@ -168,12 +168,27 @@ def c5_groupnorm_silu(n: int = 16, h: int = 64, w: int = 64, ch: int = 512, grou
     return c, [quantise(t, dtype) for t in (x, gamma, beta)]
 
 
+def x1_bias_scale_transpose(b: int = 32, s: int = 512, d: int = 1024, dtype: str = "bf16", scale: float = 0.125,
+                            salt: int = 0):
+    """(K + bias[d]) * scale -> [b, s, d] -> [b, d, s]: a chain whose permutation changes the innermost dim."""
+    g = _rng(6, salt)
+    k = g.uniform(-1.0, 1.0, (b, s, d)).astype(np.float32)
+    bias = g.uniform(-1.0, 1.0, d).astype(np.float32)
+    c = ChainSpec(inputs=[(dtype, (b, s, d)), (dtype, (d,))])
+    v = c.op("add", 0, 1)
+    v = c.op("scale", v, f=[scale])
+    v = c.op("permute", v, i=[0, 2, 1])
+    c.out(v, dtype)
+    return c, [quantise(k, dtype), quantise(bias, dtype)]
+
+
 CONFIGS = {
     "C1": c1_bias_res_layernorm_gelu,
     "C2": c2_causal_softmax,
     "C3": c3_bias_res_layernorm,
     "C4": c4_bias_scale_permute,
     "C5": c5_groupnorm_silu,
+    "X1": x1_bias_scale_transpose,      # not a BASELINE config: the innermost-changing transpose, for context
 }
 
 
