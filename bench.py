@@ -173,6 +173,7 @@ def main():
     ap.add_argument("--only", default="", help="comma-separated subset of C1..C5 for the context block")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-context", action="store_true", help="time the headline chain only")
+    ap.add_argument("--variant", default="", help="force a kernel variant for chains of the context block, e.g. C4=1,C5=0")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (every chain shards by rows with no exchange); "
@@ -210,9 +211,10 @@ def main():
     if not args.no_context:
         chains = {}
         wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5", "X1"]) if c]
+        forced = dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.variant.split(",") if "=" in kv)
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
-            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2))
+            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name))
             chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
                             "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2,
                             "variant": inf2.variant, "spec_id": inf2.spec_id, "launches": inf2.n_launches,

@@ -150,6 +150,7 @@ struct PermGeom {
     // LDS-staged variant (innermost dim kept): a workgroup moves a [tile_a x tile_b] block of inner rows.
     // Tile variant (innermost dim changes): tile_a / tile_b = extents of the input's / output's innermost dim.
     uint32_t tile_a, tile_b;
+    uint32_t lds_pitch;       // LDS-staged variant: pitch of a staged line in 16-byte vectors
     uint32_t t_in_stride_o;   // tile variant: input stride (elements) of the output's innermost dim
     uint32_t t_out_stride_i;  // tile variant: output stride (elements) of the input's innermost dim
 };

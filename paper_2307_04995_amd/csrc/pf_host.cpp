@@ -982,7 +982,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
                 if (B.extent % cand_b != 0) continue;
                 for (int64_t cand_a = 32; cand_a >= 2; --cand_a) {
                     if (A.extent % cand_a != 0) continue;
-                    const int64_t bytes = cand_a * (cand_b * inner_v + 1) * 16;
+                    const int64_t bytes = cand_a * (cand_b * inner_v + 16) * 16;
                     if (bytes > 48 * 1024 || cand_a * cand_b * inner_v < 256) continue;
                     ta = (uint32_t)cand_a; tb = (uint32_t)cand_b; lds_ok = true;
                     break;
@@ -1015,10 +1015,17 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         g.out_stride[3] = 1;
         g.tile_a = ta;
         g.tile_b = tb;
+        {
+            // pad the staged line so that stepping one line advances the bank index (256 bytes of bank space =
+            // 16 vectors) by one inner row: pitch = row (mod 16 vectors) must equal inner (mod 16 vectors)
+            const int64_t inner_v = inner / vec, row_v = tb * inner_v;
+            const int64_t pad = (((inner_v - row_v) % 16) + 16) % 16;
+            g.lds_pitch = (uint32_t)(row_v + (env_int("PF_LDS_PAD", -1) >= 0 ? env_int("PF_LDS_PAD", 0) : pad));
+        }
         p->k = 1;
         p->block = dim3(256);
         p->grid = dim3((uint32_t)(batch * (A.extent / ta) * (B.extent / tb)));
-        p->lds_bytes = (uint32_t)(ta * (tb * (inner / vec) + 1) * 16);
+        p->lds_bytes = (uint32_t)(ta * g.lds_pitch * 16);
     } else {
         if (m > PF_DEV_MAX_RANK) return fail(PF_ERR_UNSUPPORTED, "too many dimensions");
         g.rank = m;

@@ -122,9 +122,12 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
 // (input order ... A, B, inner; output order ... B, A, inner).  A workgroup owns a tile of tile_a x tile_b
 // inner rows: it reads tile_a runs of tile_b * inner contiguous elements, runs the prologue, parks the
 // fp32 -> storage converted vectors in LDS, and after one barrier writes tile_b runs of tile_a * inner
-// contiguous elements, running the epilogue on the way out.  LDS traffic is 16 bytes per lane both ways
-// with consecutive lanes on consecutive 16-byte slots in the write phase and a stride of whole inner rows
-// in the read phase; a one-vector pad per staged row keeps the read phase off a single bank group.
+// contiguous elements, running the epilogue on the way out.  LDS traffic is 16 bytes per lane both ways:
+// consecutive lanes fill consecutive 16-byte slots in the staging phase; in the read-out phase a group of
+// lanes reads one inner row (inner * element size contiguous bytes) and the next group the inner row one
+// staged line further.  The staged line pitch is padded so that this step advances the bank index by
+// exactly one inner row: the groups that are served together then tile the 256 bytes of bank space
+// side by side instead of landing on top of each other.
 template <int DT, class Spec>
 __global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, const PermGeom g) {
     using S = Storage<DT>;
@@ -143,7 +146,7 @@ __global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, c
     const uint32_t in_base = batch * g.in_stride[0] + at * ta * g.in_stride[1] + bt * tb * g.in_stride[2];
     const uint32_t out_base = batch * g.out_stride[0] + at * ta * g.out_stride[1] + bt * tb * g.out_stride[2];
     const uint32_t row_v = tb * inner_v;           // vectors per staged input run
-    const uint32_t pitch = row_v + 1u;             // padded LDS pitch in vectors
+    const uint32_t pitch = g.lds_pitch;            // padded LDS pitch in vectors (chosen by the planner)
     const uint32_t tile_v = ta * row_v;
     LaneState<DT, 1, Spec> s;
     // ---- read phase: input-contiguous
@@ -334,6 +337,26 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const u32x4* __restrict
     }
 }
 
+// persistent form: a fixed grid, each workgroup strides over the buffer
+template <int K>
+__global__ void __launch_bounds__(256) copy_persistent_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n_vec) {
+    const uint64_t step = (uint64_t)gridDim.x * (256u * K);
+    for (uint64_t base = (uint64_t)blockIdx.x * (256u * K) + threadIdx.x; base < n_vec; base += step) {
+        u32x4 r[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint64_t v = base + 256u * k;
+            r[k] = u32x4{0u, 0u, 0u, 0u};
+            if (v < n_vec) r[k] = __builtin_nontemporal_load(src + v);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint64_t v = base + 256u * k;
+            if (v < n_vec) __builtin_nontemporal_store(r[k], dst + v);
+        }
+    }
+}
+
 // read-only and write-only streams, to see how the two directions share the memory system
 template <int K>
 __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n_vec) {
@@ -365,12 +388,25 @@ hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int var
     const u32x4* s = static_cast<const u32x4*>(src);
     u32x4* d = static_cast<u32x4*>(dst);
     // variant = unroll (1, 2, 4) | 16: plain (temporal) accesses | 32: read only | 64: write only
+    //           | 128: persistent grid with (variant >> 8) workgroups per compute unit
     const bool nt = (variant & 16) == 0;
     const int k = variant & 15;
     const uint64_t per_block = 256ull * (uint64_t)(k ? k : 1);
     const uint64_t blocks = (n_vec + per_block - 1) / per_block;
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
     dim3 grid((uint32_t)blocks), block(256);
+    if (variant & 128) {
+        // persistent: (variant >> 8) workgroups per compute unit, 256 compute units assumed
+        const uint32_t per_cu = (uint32_t)(variant >> 8) ? (uint32_t)(variant >> 8) : 8u;
+        dim3 pgrid(256u * per_cu);
+        switch (k) {
+            case 1: hipLaunchKernelGGL((copy_persistent_kernel<1>), pgrid, block, 0, st, s, d, n_vec); break;
+            case 2: hipLaunchKernelGGL((copy_persistent_kernel<2>), pgrid, block, 0, st, s, d, n_vec); break;
+            case 4: hipLaunchKernelGGL((copy_persistent_kernel<4>), pgrid, block, 0, st, s, d, n_vec); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     if (variant & 32) {
         switch (k) {
             case 1: hipLaunchKernelGGL((read_probe_kernel<1>), grid, block, 0, st, s, d, n_vec); break;
