@@ -66,8 +66,10 @@ def full_size_chain(name):
     return spec, ins, algorithmic, nominal, labels[name]
 
 
-def time_chain(spec, ins, steps, warmup, variant=None):
-    """Returns (ms per step from host clock, ms per launch from HIP events, plan info)."""
+def time_chain(spec, ins, steps, warmup, variant=None, hot=None):
+    """Returns (ms per step from host clock, ms per launch from HIP events, plan info).  The timed launches
+    rotate over the buffer sets (cold).  If `hot` is a list, the average launch duration of the same number
+    of launches on ONE buffer set (data resident in the last-level cache where it fits) is appended to it."""
     import numpy as np
     import torch
     from paper_2307_04995_amd import binding as pf
@@ -101,6 +103,16 @@ def time_chain(spec, ins, steps, warmup, variant=None):
     t1 = time.perf_counter()
     host_ms = (t1 - t0) * 1e3 / steps
     event_ms = ev0.elapsed_time(ev1) / steps
+    if hot is not None:
+        ip, op, _, _ = sets[0]
+        for k in range(warmup):
+            plan.run_ptrs(ip, op, stream)
+        ev0.record()
+        for k in range(steps):
+            plan.run_ptrs(ip, op, stream)
+        ev1.record()
+        torch.cuda.synchronize()
+        hot.append(ev0.elapsed_time(ev1) / steps)
     plan.close()
     del sets
     torch.cuda.empty_cache()
@@ -150,9 +162,18 @@ def cpu_baseline(budget_s=12.0):
         total += time.perf_counter() - t0
         passes += 1
     gbps = nbytes * passes / total / 1e9
+    orc.set_threads(1)
+    p1, t1 = 0, 0.0
+    while t1 < budget_s / 4 and p1 < 100:
+        t0 = time.perf_counter()
+        orc.evaluate_outputs(spec, wide)
+        t1 += time.perf_counter() - t0
+        p1 += 1
+    orc.set_threads(threads)
     return {"value": round(gbps, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "single_thread_value": round(nbytes * p1 / t1 / 1e9, 4),
             "sample": f"scores [2,12,512,512] (a quarter of the [8,12,512,512] workload), {passes} passes in {total:.1f} s, "
-                      f"fp64 unfused, {threads} OpenMP threads"}
+                      f"fp64 unfused, {threads} OpenMP threads (then {p1} passes in {t1:.1f} s on one thread)"}
 
 
 def read_traffic(name):
@@ -173,6 +194,9 @@ def main():
     ap.add_argument("--only", default="", help="comma-separated subset of C1..C5 for the context block")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-context", action="store_true", help="time the headline chain only")
+    ap.add_argument("--hot", action="store_true",
+                    help="also time every chain on ONE buffer set (cache-resident where it fits); adds launches of the "
+                         "same kernels, so leave it off under a kernel trace")
     ap.add_argument("--variant", default="", help="force a kernel variant for chains of the context block, e.g. C4=1,C5=0")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -186,7 +210,8 @@ def main():
 
     headline = "C2"
     spec, ins, alg_bytes, nominal_bytes, label = full_size_chain(headline)
-    host_ms, event_ms, info = time_chain(spec, ins, args.steps, args.warmup)
+    hot = [] if args.hot else None
+    host_ms, event_ms, info = time_chain(spec, ins, args.steps, args.warmup, hot=hot)
     achieved = alg_bytes / (event_ms * 1e-3) / 1e9
     result = {
         "metric": "achieved HBM GB/s (fraction of MI355X peak) per fused chain; us per call",
@@ -208,17 +233,23 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(headline),
                      "kernel_us": round(event_ms * 1e3, 3), "nominal_gbps": round(nominal_bytes / (event_ms * 1e-3) / 1e9, 1)},
     }
+    if hot:
+        result["config"]["hot_us_per_call"] = round(hot[0] * 1e3, 3)
     if not args.no_context:
         chains = {}
         wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5", "X1"]) if c]
         forced = dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.variant.split(",") if "=" in kv)
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
-            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name))
-            chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
+            hot2 = [] if args.hot else None
+            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name), hot=hot2)
+            chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3),
+                            "host_us_per_call": round(h2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
                             "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2,
                             "variant": inf2.variant, "spec_id": inf2.spec_id, "launches": inf2.n_launches,
                             "traffic": read_traffic(name)}
+            if hot2:
+                chains[name]["hot_us_per_call"] = round(hot2[0] * 1e3, 3)
             del s2, i2
         nbytes = 64 * 1024 * 1024
         best = None
