@@ -126,10 +126,10 @@ struct GroupGeom {
     uint32_t lanes_per_group;    // lanes that share a group when a sample's partials are merged (power of two)
     uint32_t vec_per_channel;    // 1: every broadcast operand is indexed by channel only
     uint32_t blocks_per_sample;
-    float* ws_partial;           // [samples][blocks_per_sample][groups][4] = (count, mean, M2, -)
-    uint64_t* ws_final;          // [2][samples][groups] (mean, rstd) words per launch parity; all-ones = not ready
-    uint32_t* ws_counter;        // [samples] arrival counters (resident variant)
-    uint32_t epoch;              // launch number; the counters reach epoch * blocks_per_sample
+    float* ws_partial;           // two-launch variant: [samples][blocks_per_sample][groups][4] = (count, mean, M2, -)
+    uint64_t* ws_gather;         // resident variant: [2][samples][groups][blocks_per_sample] (mean, M2) words per launch
+                                 // parity; all-ones = not written yet
+    uint32_t epoch;              // launch number (its parity selects the half of ws_gather in use)
     uint32_t spin_limit;         // resident variant: bounded wait, then the error flag is raised
     uint32_t* ws_error;          // resident variant: set to 1 if a wait ran out
     FastDiv div_cv;

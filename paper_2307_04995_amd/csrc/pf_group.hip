@@ -108,9 +108,8 @@ PF_DEVICE Stat group_lanes_merge(Stat st, uint32_t log2_vpg) {
     return st;
 }
 
-// workgroup partial: merge over the position steps of the workgroup and publish [groups][4] floats.
-// COHERENT: written through with device-coherent stores (read by other workgroups of the same launch).
-template <bool COHERENT>
+// workgroup partial of the two-launch variant: merge over the position steps of the workgroup and write
+// [groups][4] floats for the second launch
 PF_DEVICE void block_partial(const GroupGeom& g, Stat st, uint32_t pstep, uint32_t cvi, bool active, float* lds, float* dst) {
     const uint32_t grp = cvi >> g.log2_vpg;
     if (active && (cvi & (g.vpg - 1u)) == 0u) {
@@ -127,23 +126,16 @@ PF_DEVICE void block_partial(const GroupGeom& g, Stat st, uint32_t pstep, uint32
             acc = stat_merge(acc, Stat{p[0], p[1], p[2]});
         }
         float* o = dst + threadIdx.x * 4u;
-        if (COHERENT) {
-            __hip_atomic_store(o + 0, acc.n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(o + 1, acc.mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(o + 2, acc.m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            o[0] = acc.n;
-            o[1] = acc.mean;
-            o[2] = acc.m2;
-        }
+        o[0] = acc.n;
+        o[1] = acc.mean;
+        o[2] = acc.m2;
     }
 }
 
-// Merge the published partials of one sample into (mean, rstd) per group.  lanes_per_group (a power of
+// Merge the partials a previous launch wrote for one sample into (mean, rstd) per group.  lanes_per_group (a power of
 // two, <= 64) adjacent lanes share a group: each merges a strided subset of the sample's partials straight
 // from memory, then the lanes are merged by a shuffle tree.  Returns true in the lane that holds a group's
 // result (its group index in *grp_out).
-template <bool COHERENT>
 PF_DEVICE bool combine_sample(const GroupGeom& g, uint32_t sample, float eps, uint32_t* grp_out, float* mean_out, float* rstd_out) {
     const uint32_t lpg = g.lanes_per_group;
     const uint32_t grp = threadIdx.x / lpg, j = threadIdx.x - grp * lpg;
@@ -154,15 +146,9 @@ PF_DEVICE bool combine_sample(const GroupGeom& g, uint32_t sample, float eps, ui
         const float* p = base + (uint64_t)b * g.groups * 4u;
         Stat q = {0.0f, 0.0f, 0.0f};
         if (in_range) {
-            if (COHERENT) {
-                q.n = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                q.mean = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                q.m2 = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                q.n = p[0];
-                q.mean = p[1];
-                q.m2 = p[2];
-            }
+            q.n = p[0];
+            q.mean = p[1];
+            q.m2 = p[2];
         }
         acc = stat_merge(acc, q);
     }
@@ -174,22 +160,86 @@ PF_DEVICE bool combine_sample(const GroupGeom& g, uint32_t sample, float eps, ui
     return in_range && j == 0u;
 }
 
-// Polls are spaced about a microsecond apart: many workgroups wait on the same few words, and a tight
-// polling loop would queue up in front of the very atomics it is waiting for.
-PF_DEVICE bool wait_for_counter(const uint32_t* word, uint32_t target, uint32_t spin_limit, uint32_t* error) {
-    uint32_t spins = 0;
-    for (;;) {
-        const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((int32_t)(v - target) >= 0) return true;
-        if (++spins >= spin_limit) {
-            __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return false;
+// ---- device-scope exchange of the fused kernel: an all-gather of self-describing words ----------------
+// A workgroup publishes, per group, ONE 8-byte word (mean, M2) of its tile (the count follows from the tile's
+// position in the sample) into a slot of its own, with a device-coherent store.  A slot that still reads
+// all-ones has not been written in this launch.  Every workgroup of the sample then reads all slots of the
+// sample itself, re-reading the ones that are still empty, and merges them: the critical path is one
+// coherent store followed by one coherent load, with no counter, no elected merger and no second
+// publish/poll round trip behind it.  Slots exist twice, selected by the parity of the launch number; a
+// workgroup re-arms its slots of the other parity, which nobody reads before the next launch.
+constexpr uint64_t kSlotEmpty = ~0ull;  // (NaN, NaN) with an all-ones payload: arithmetic never produces it
+
+PF_DEVICE uint64_t pack_slot(float mean, float m2) {
+    uint64_t w = (uint64_t)__builtin_bit_cast(uint32_t, mean) | ((uint64_t)__builtin_bit_cast(uint32_t, m2) << 32);
+    if (w == kSlotEmpty) w = 0x7fc000007fc00000ull;  // keep NaN statistics distinguishable from "empty"
+    return w;
+}
+
+// LDS-merge the position steps of the workgroup, then publish one word per group.
+PF_DEVICE void publish_tile(const GroupGeom& g, Stat st, uint32_t pstep, uint32_t cvi, bool active, float* lds, uint32_t sample,
+                            uint32_t bx) {
+    const uint32_t grp = cvi >> g.log2_vpg;
+    if (active && (cvi & (g.vpg - 1u)) == 0u) {
+        float* p = lds + (pstep * g.groups + grp) * 3u;
+        p[0] = st.n;
+        p[1] = st.mean;
+        p[2] = st.m2;
+    }
+    __syncthreads();
+    if (threadIdx.x < g.groups) {
+        Stat acc = {0.0f, 0.0f, 0.0f};
+        for (uint32_t s = 0; s < g.pos_per_step; ++s) {
+            const float* p = lds + (s * g.groups + threadIdx.x) * 3u;
+            acc = stat_merge(acc, Stat{p[0], p[1], p[2]});
         }
-        __builtin_amdgcn_s_sleep(32);
+        const uint64_t per_parity = (uint64_t)g.samples * g.groups * g.blocks_per_sample;
+        const uint64_t slot = ((uint64_t)sample * g.groups + threadIdx.x) * g.blocks_per_sample + bx;
+        const uint32_t par = g.epoch & 1u;
+        __hip_atomic_store(g.ws_gather + (par ^ 1u) * per_parity + slot, kSlotEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(g.ws_gather + par * per_parity + slot, pack_slot(acc.mean, acc.m2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-constexpr uint64_t kFinalEmpty = ~0ull;  // (NaN, NaN): never a valid (mean, rstd) pair
+// Gather and merge the words of one sample.  Thread mapping as in combine_sample: lanes_per_group adjacent
+// lanes share a group, each takes a strided subset of the sample's tiles.  Every wait is bounded: after
+// spin_limit re-reads the error word is set and the tile is left out.
+PF_DEVICE bool gather_sample(const GroupGeom& g, uint32_t sample, float eps, uint32_t* grp_out, float* mean_out, float* rstd_out) {
+    const uint32_t lpg = g.lanes_per_group;
+    const uint32_t grp = threadIdx.x / lpg, j = threadIdx.x - grp * lpg;
+    const bool in_range = grp < g.groups;
+    const uint64_t per_parity = (uint64_t)g.samples * g.groups * g.blocks_per_sample;
+    const uint64_t* base = g.ws_gather + (g.epoch & 1u) * per_parity + ((uint64_t)sample * g.groups + (in_range ? grp : 0u)) * g.blocks_per_sample;
+    const float per_pos = (float)(g.channels / g.groups);
+    Stat acc = {0.0f, 0.0f, 0.0f};
+    uint32_t spins = 0;
+    for (uint32_t b = j; b < g.blocks_per_sample; b += lpg) {
+        if (!in_range) break;
+        uint64_t w;
+        for (;;) {
+            w = __hip_atomic_load(base + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (w != kSlotEmpty) break;
+            if (++spins >= g.spin_limit) {
+                __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        if (w == kSlotEmpty) continue;
+        const uint32_t p0 = b * g.pos_per_block;
+        Stat q;
+        q.n = (float)(min(g.hw, p0 + g.pos_per_block) - p0) * per_pos;
+        q.mean = __builtin_bit_cast(float, (uint32_t)w);
+        q.m2 = __builtin_bit_cast(float, (uint32_t)(w >> 32));
+        acc = stat_merge(acc, q);
+    }
+    for (uint32_t m = 1; m < lpg; m <<= 1) acc = stat_merge(acc, stat_shfl_xor(acc, (int)m));
+    const float var = acc.n > 0.0f ? acc.m2 / acc.n : 0.0f;
+    *grp_out = grp;
+    *mean_out = acc.mean;
+    *rstd_out = 1.0f / sqrtf(var + eps);
+    return in_range && j == 0u;
+}
 
 // One kernel template, three phases:
 //   PHASE 0  fused: statistics, device-scope exchange and normalisation in one launch (RESIDENT variant)
@@ -206,35 +256,30 @@ constexpr uint64_t kFinalEmpty = ~0ull;  // (NaN, NaN): never a valid (mean, rst
 // the workgroups per sample), so every wait below ends.  Waits are bounded anyway: after spin_limit polls the
 // error word is set and the kernel carries on.
 //
-// Exchange protocol of PHASE 0 (per sample and launch): every workgroup publishes its per-group partials
-// with device-coherent stores, waits for them to complete and bumps the sample's arrival counter.  The
-// workgroup that arrives last merges all partials of the sample and publishes one 8-byte (mean, rstd) word
-// per group into the slot of this launch's parity, re-arming the other parity's slot for the next launch;
-// every other workgroup polls the words of its groups until they are no longer empty.  All shared words
-// travel by device-coherent (agent-scope atomic) accesses, so no cache write-back or invalidate is needed
-// around them -- a write-back here would wait for every output line other workgroups have just stored.
-//
-// Staggered start (PHASE 0, two workgroups per compute unit): the second half of the grid begins loading
-// only when the matching sample of the first half has finished loading (its arrival counter is complete).
-// The halves then run half a phase apart: one normalises and stores while the other loads.
+// Exchange of PHASE 0: see publish_tile / gather_sample above.  All shared words travel by device-coherent
+// (agent-scope atomic) accesses, so no cache write-back or invalidate is needed around them -- a write-back
+// here would wait for every output line other workgroups have just stored.
 template <int DT, int NV, class Spec, int PHASE>
-__global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles,
-                                                        const uint32_t stagger_tiles) {
+__global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     // kLean: 16-bit storage and nothing but the load in front of the normalisation
     constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
     __shared__ float lds_part[512 * 3];
     __shared__ float lds_stat[512 * 2];
-    __shared__ uint32_t s_last;
     const uint32_t t = threadIdx.x;
     const uint32_t pstep = fast_div(t, g.div_cv);
     const uint32_t cvi = t - pstep * g.cv;
     const bool active = pstep < g.pos_per_step;
 
+    // The fused kernel is only planned for per-channel broadcast operands; making that a compile-time fact keeps
+    // the per-position operand loads (and the waits the compiler puts at their control-flow joins, which would
+    // also wait for every output store just issued) out of its loops.
+    const bool vec_per_channel = PHASE == 0 ? true : g.vec_per_channel != 0u;
+
     LaneState<DT, 1, Spec> s;
     s.col[0] = cvi * VEC;
-    if (g.vec_per_channel) {
+    if (vec_per_channel) {
         // broadcast operands that are per channel: the same vector for every position and tile
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v) {
@@ -250,13 +295,6 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         const uint32_t bx = tile - sample * g.blocks_per_sample;
         const uint32_t p_begin = bx * g.pos_per_block;
         const uint32_t p_end = min(g.hw, p_begin + g.pos_per_block);
-
-        if (PHASE == 0 && stagger_tiles != 0u && tile >= stagger_tiles) {
-            if (t == 0)
-                wait_for_counter(g.ws_counter + (tile - stagger_tiles) / g.blocks_per_sample, g.epoch * g.blocks_per_sample,
-                                 g.spin_limit, g.ws_error);
-            __syncthreads();
-        }
 
         // ---- the whole slice into registers (positions and validity are recomputed where needed rather than
         // kept: the registers are for data)
@@ -276,7 +314,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         auto prologue = [&](int i) {
             s.row[0] = sample * g.hw + p_begin + rel_of(i);
             s.fraw[0][0] = raw[i];
-            if (!g.vec_per_channel) {
+            if (!vec_per_channel) {
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v) {
                     if (v < Spec::n_vec(a)) {
@@ -302,8 +340,12 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 }
             }
             const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
-            float* dst = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.groups) * 4u;
-            block_partial<PHASE == 0>(g, st, pstep, cvi, active, lds_part, dst);
+            if (PHASE == 0) {
+                publish_tile(g, st, pstep, cvi, active, lds_part, sample, bx);
+            } else {
+                float* dst = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.groups) * 4u;
+                block_partial(g, st, pstep, cvi, active, lds_part, dst);
+            }
         }
         if (PHASE == 1) {
             __syncthreads();  // LDS staging is reused by the next tile
@@ -312,61 +354,18 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 
         if (PHASE == 0) {
             // ---- device-scope exchange
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's coherent stores have completed
-            __syncthreads();
-            if (t == 0) {
-                const uint32_t before = __hip_atomic_fetch_add(g.ws_counter + sample, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_last = (before + 1u == g.epoch * g.blocks_per_sample) ? 1u : 0u;
-            }
-            __syncthreads();
-            uint64_t* final_now = g.ws_final + ((uint64_t)(g.epoch & 1u) * g.samples + sample) * g.groups;
-            if (s_last) {
-                uint32_t grp;
-                float mean, rstd;
-                if (combine_sample<true>(g, sample, a.eps, &grp, &mean, &rstd)) {
-                    lds_stat[grp * 2u] = mean;
-                    lds_stat[grp * 2u + 1u] = rstd;
-                    const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, mean) | ((uint64_t)__builtin_bit_cast(uint32_t, rstd) << 32);
-                    uint64_t* final_next = g.ws_final + ((uint64_t)((g.epoch + 1u) & 1u) * g.samples + sample) * g.groups;
-                    __hip_atomic_store(final_next + grp, kFinalEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(final_now + grp, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            } else {
-                // one lane watches the sample's first word; once it is there every group's lane fetches its own
-                // word (re-polling the rare one that is a moment behind)
-                if (t == 0) {
-                    uint32_t spins = 0;
-                    while (__hip_atomic_load(final_now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kFinalEmpty) {
-                        if (++spins >= g.spin_limit) {
-                            __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(16);
-                    }
-                }
-                __syncthreads();
-                if (t < g.groups) {
-                    uint64_t word;
-                    uint32_t spins = 0;
-                    for (;;) {
-                        word = __hip_atomic_load(final_now + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (word != kFinalEmpty) break;
-                        if (++spins >= g.spin_limit) {
-                            __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(4);
-                    }
-                    lds_stat[t * 2u] = __builtin_bit_cast(float, (uint32_t)word);
-                    lds_stat[t * 2u + 1u] = __builtin_bit_cast(float, (uint32_t)(word >> 32));
-                }
+            uint32_t grp;
+            float mean, rstd;
+            if (gather_sample(g, sample, a.eps, &grp, &mean, &rstd)) {
+                lds_stat[grp * 2u] = mean;
+                lds_stat[grp * 2u + 1u] = rstd;
             }
             __syncthreads();
         } else {
             // PHASE 2: the partials were written by the previous launch
             uint32_t grp;
             float mean, rstd;
-            if (combine_sample<false>(g, sample, a.eps, &grp, &mean, &rstd)) {
+            if (combine_sample(g, sample, a.eps, &grp, &mean, &rstd)) {
                 lds_stat[grp * 2u] = mean;
                 lds_stat[grp * 2u + 1u] = rstd;
             }
@@ -393,12 +392,12 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 B[e] = bt[e] - mean * A[e];
             }
         };
-        if (g.vec_per_channel) affine();
+        if (vec_per_channel) affine();
         char* out_base = static_cast<char*>(a.out[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             prologue(i);
-            if (!g.vec_per_channel) affine();
+            if (!vec_per_channel) affine();
 #pragma unroll
             for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
@@ -424,44 +423,44 @@ struct GroupSpecOf<0> {
 };
 
 template <int ID, int DT, int PHASE>
-static hipError_t launch_group_nv(const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, uint32_t stagger, dim3 grid,
+static hipError_t launch_group_nv(const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, dim3 grid,
                                   dim3 block, hipStream_t st) {
     using Spec = typename GroupSpecOf<ID>::type;
     switch (nv) {
-        case 4: hipLaunchKernelGGL((group_kernel<DT, 4, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
-        case 8: hipLaunchKernelGGL((group_kernel<DT, 8, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
-        case 16: hipLaunchKernelGGL((group_kernel<DT, 16, Spec, PHASE>), grid, block, 0, st, a, g, tiles, stagger); break;
+        case 4: hipLaunchKernelGGL((group_kernel<DT, 4, Spec, PHASE>), grid, block, 0, st, a, g, tiles); break;
+        case 8: hipLaunchKernelGGL((group_kernel<DT, 8, Spec, PHASE>), grid, block, 0, st, a, g, tiles); break;
+        case 16: hipLaunchKernelGGL((group_kernel<DT, 16, Spec, PHASE>), grid, block, 0, st, a, g, tiles); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 template <int ID, int DT>
-static hipError_t launch_group_dt(int phase, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles, uint32_t stagger,
+static hipError_t launch_group_dt(int phase, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
                                   dim3 grid, dim3 block, hipStream_t st) {
-    if (phase == 1) return launch_group_nv<ID, DT, 1>(a, g, nv, tiles, 0, grid, block, st);
-    if (phase == 2) return launch_group_nv<ID, DT, 2>(a, g, nv, tiles, 0, grid, block, st);
-    if constexpr (ID != 0) return launch_group_nv<ID, DT, 0>(a, g, nv, tiles, stagger, grid, block, st);
+    if (phase == 1) return launch_group_nv<ID, DT, 1>(a, g, nv, tiles, grid, block, st);
+    if (phase == 2) return launch_group_nv<ID, DT, 2>(a, g, nv, tiles, grid, block, st);
+    if constexpr (ID != 0) return launch_group_nv<ID, DT, 0>(a, g, nv, tiles, grid, block, st);
     return hipErrorInvalidValue;  // the fused variant exists for catalogue entries only
 }
 
 template <int ID>
 static hipError_t launch_group_id(int phase, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
-                                  uint32_t stagger, dim3 grid, dim3 block, hipStream_t st) {
+                                  dim3 grid, dim3 block, hipStream_t st) {
     switch (dtype) {
-        case DT_F32: return launch_group_dt<ID, DT_F32>(phase, a, g, nv, tiles, stagger, grid, block, st);
-        case DT_F16: return launch_group_dt<ID, DT_F16>(phase, a, g, nv, tiles, stagger, grid, block, st);
-        case DT_BF16: return launch_group_dt<ID, DT_BF16>(phase, a, g, nv, tiles, stagger, grid, block, st);
+        case DT_F32: return launch_group_dt<ID, DT_F32>(phase, a, g, nv, tiles, grid, block, st);
+        case DT_F16: return launch_group_dt<ID, DT_F16>(phase, a, g, nv, tiles, grid, block, st);
+        case DT_BF16: return launch_group_dt<ID, DT_BF16>(phase, a, g, nv, tiles, grid, block, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_group(int phase, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
-                        uint32_t stagger, dim3 grid, dim3 block, hipStream_t st) {
+                        dim3 grid, dim3 block, hipStream_t st) {
     switch (spec_id) {
-        case 0: return launch_group_id<0>(phase, dtype, a, g, nv, tiles, stagger, grid, block, st);
+        case 0: return launch_group_id<0>(phase, dtype, a, g, nv, tiles, grid, block, st);
 #define PF_CASE(id, ...) \
-    case id: return launch_group_id<id>(phase, dtype, a, g, nv, tiles, stagger, grid, block, st);
+    case id: return launch_group_id<id>(phase, dtype, a, g, nv, tiles, grid, block, st);
             PF_GROUP_SPECS(PF_CASE)
 #undef PF_CASE
         default: return hipErrorInvalidValue;

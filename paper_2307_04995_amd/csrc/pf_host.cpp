@@ -704,7 +704,6 @@ struct pf_plan_s {
     Shape out_shape[PF_MAX_OUTPUTS];
     int n_launches = 1;
     mutable uint32_t epoch = 0;
-    uint32_t stagger_tiles = 0;  // group family, resident variant: tiles of the first half of a staggered launch
 };
 
 namespace {
@@ -1121,20 +1120,14 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     // resident variant: catalogue entry, one full operand, per-channel broadcast operands only, and a grid the
     // device holds at once
     bool resident_ok = p->spec_id != 0 && L.n_full == 1 && g.vec_per_channel;
-    uint32_t res_grid = 0, res_stagger = 0;
+    uint32_t res_grid = 0;
     if (resident_ok) {
         const int per_cu = pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, nv, (int)threads);
         const uint64_t cap = (uint64_t)std::max(per_cu, 0) * n_cu;
         uint64_t grid = std::min<uint64_t>(tiles, cap);
         grid = grid / bps * bps;  // whole samples per round, so every wait is for co-resident workgroups
         if (grid < bps) resident_ok = false;
-        else {
-            res_grid = (uint32_t)grid;
-            // staggering the two halves of a single-round launch is available for experiments (PF_GROUP_STAGGER=1);
-            // measured on MI355X it does not pay: the exchange latency of the second half stays on the critical path
-            if (grid == tiles && samples % 2 == 0 && tiles >= (uint64_t)n_cu && env_int("PF_GROUP_STAGGER", 0) != 0)
-                res_stagger = (uint32_t)(tiles / 2);
-        }
+        else res_grid = (uint32_t)grid;
     }
     int variant = forced_variant >= 0 ? forced_variant : (resident_ok ? PF_VARIANT_GROUP_RESIDENT : PF_VARIANT_GROUP_TWO_PASS);
     if (variant == PF_VARIANT_GROUP_RESIDENT && !resident_ok)
@@ -1148,29 +1141,27 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     p->k = nv;
     if (variant == PF_VARIANT_GROUP_RESIDENT) {
         p->grid = dim3(res_grid);
-        p->stagger_tiles = res_stagger;
         p->n_launches = 1;
     } else {
         p->grid = dim3((uint32_t)tiles);
         p->grid2 = p->grid;
         p->block2 = p->block;
-        p->stagger_tiles = 0;
         p->n_launches = 2;
     }
     p->lds_bytes = 512 * 3 * 4 + 512 * 2 * 4 + 4;
-    // workspace: partials, two parities of per-sample (mean, rstd) words, arrival counters, error word
-    const uint64_t part_bytes = (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
-    const uint64_t final_bytes = (((uint64_t)2 * samples * g.groups * sizeof(uint64_t)) + 255) / 256 * 256;
-    const uint64_t cnt_bytes = ((uint64_t)samples * sizeof(uint32_t) + 255) / 256 * 256;
-    p->workspace_bytes = part_bytes + final_bytes + cnt_bytes + 256;
+    // workspace: partials of the two-launch variant, or two parities of exchange words (all-ones = empty) of the
+    // resident one; then the error word
+    const uint64_t part_bytes = variant == PF_VARIANT_GROUP_RESIDENT ? 0 : (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
+    const uint64_t gather_bytes =
+        variant == PF_VARIANT_GROUP_RESIDENT ? (((uint64_t)2 * samples * g.groups * g.blocks_per_sample * sizeof(uint64_t)) + 255) / 256 * 256 : 0;
+    p->workspace_bytes = part_bytes + gather_bytes + 256;
     if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
     char* ws = static_cast<char*>(p->workspace);
-    if (hipMemset(ws, 0, p->workspace_bytes) != hipSuccess || hipMemset(ws + part_bytes, 0xff, final_bytes) != hipSuccess)
+    if (hipMemset(ws, 0, p->workspace_bytes) != hipSuccess || (gather_bytes && hipMemset(ws + part_bytes, 0xff, gather_bytes) != hipSuccess))
         return fail(PF_ERR_HIP, "workspace clear failed");
-    g.ws_partial = reinterpret_cast<float*>(ws);
-    g.ws_final = reinterpret_cast<uint64_t*>(ws + part_bytes);
-    g.ws_counter = reinterpret_cast<uint32_t*>(ws + part_bytes + final_bytes);
-    g.ws_error = reinterpret_cast<uint32_t*>(ws + part_bytes + final_bytes + cnt_bytes);
+    g.ws_partial = part_bytes ? reinterpret_cast<float*>(ws) : nullptr;
+    g.ws_gather = gather_bytes ? reinterpret_cast<uint64_t*>(ws + part_bytes) : nullptr;
+    g.ws_error = reinterpret_cast<uint32_t*>(ws + part_bytes + gather_bytes);
     p->args.n_inner = (uint32_t)C;
     p->args.rows = (uint64_t)(samples * hw);
     return PF_OK;
@@ -1325,10 +1316,10 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             g.epoch = ++plan->epoch;
             const uint32_t tiles = g.samples * g.blocks_per_sample;
             if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
-                e = pf::launch_group(1, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, 0, plan->grid, plan->block, st);
-                if (e == hipSuccess) e = pf::launch_group(2, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, 0, plan->grid2, plan->block2, st);
+                e = pf::launch_group(1, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, st);
+                if (e == hipSuccess) e = pf::launch_group(2, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid2, plan->block2, st);
             } else {
-                e = pf::launch_group(0, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->stagger_tiles, plan->grid, plan->block, st);
+                e = pf::launch_group(0, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, st);
             }
             break;
         }
