@@ -143,6 +143,7 @@ typedef struct {
 #define PF_VARIANT_EW_FLAT 0          /* element-wise: one 16-byte vector per lane per step                  */
 #define PF_VARIANT_ROW_WAVE 0         /* row family: one 64-lane wave owns a row                             */
 #define PF_VARIANT_ROW_BLOCK 1        /* row family: one workgroup owns a row                                */
+#define PF_VARIANT_ROW_STREAM 2       /* row family: a workgroup walks a long row twice in chunks            */
 #define PF_VARIANT_GROUP_TWO_PASS 0   /* group family: statistics pass, then normalise pass (re-reads x)     */
 #define PF_VARIANT_GROUP_RESIDENT 1   /* group family: x held in registers across a device-scope exchange    */
 #define PF_VARIANT_T_ROWS 0           /* transpose family: innermost dim kept, 16-byte vectors re-addressed  */

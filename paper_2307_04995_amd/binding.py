@@ -30,7 +30,7 @@ OP_CODE = {name: i for i, name in enumerate([
     "rmsnorm", "groupnorm", "permute", "reshape"])}
 # pf_family
 PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE = range(4)
-PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK = 0, 1
+PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK, PF_VARIANT_ROW_STREAM = 0, 1, 2
 PF_VARIANT_GROUP_TWO_PASS, PF_VARIANT_GROUP_RESIDENT = 0, 1
 PF_VARIANT_T_ROWS, PF_VARIANT_T_LDS_ROWS, PF_VARIANT_T_TILE = 0, 1, 2
 

@@ -114,6 +114,52 @@ PF_DEVICE u32x4 load_cached(const void* base, uint64_t byte_off) {
     return *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off);
 }
 
+// Element-granular access, for rows whose byte length is not a multiple of 16: their vectors are not
+// 16-byte aligned and the last one is partial.  The first `count` elements of the vector are touched; the
+// others read as the matching half of `fill` and are not stored.
+template <int DT>
+PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill) {
+    u32x4 r = {fill, fill, fill, fill};
+    if (DT == DT_F32) {
+        const uint32_t* p = static_cast<const uint32_t*>(base) + elem;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((uint32_t)e < count) r[e] = __builtin_nontemporal_load(p + e);
+    } else {
+        const uint16_t* p = static_cast<const uint16_t*>(base) + elem;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t lo = fill & 0xffffu, hi = fill >> 16;
+            if ((uint32_t)(2 * j) < count) lo = __builtin_nontemporal_load(p + 2 * j);
+            if ((uint32_t)(2 * j + 1) < count) hi = __builtin_nontemporal_load(p + 2 * j + 1);
+            r[j] = lo | (hi << 16);
+        }
+    }
+    return r;
+}
+template <int DT>
+PF_DEVICE void store_elems(void* base, uint64_t elem, uint32_t count, u32x4 v) {
+    if (DT == DT_F32) {
+        uint32_t* p = static_cast<uint32_t*>(base) + elem;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((uint32_t)e < count) __builtin_nontemporal_store(v[e], p + e);
+    } else {
+        uint16_t* p = static_cast<uint16_t*>(base) + elem;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = v[j];
+            if ((uint32_t)(2 * j) < count) __builtin_nontemporal_store((uint16_t)(w & 0xffffu), p + 2 * j);
+            if ((uint32_t)(2 * j + 1) < count) __builtin_nontemporal_store((uint16_t)(w >> 16), p + 2 * j + 1);
+        }
+    }
+}
+// how many elements of the vector that starts at `col` lie below `limit` (0 .. VEC)
+template <int VEC>
+PF_DEVICE uint32_t elems_below(uint32_t col, uint32_t limit) {
+    return col < limit ? (limit - col < (uint32_t)VEC ? limit - col : (uint32_t)VEC) : 0u;
+}
+
 PF_DEVICE uint32_t fast_div(uint32_t n, const FastDiv& f) {
     const uint32_t t = __umulhi(f.m, n);
     return (t + ((n - t) >> f.s1)) >> f.s2;
@@ -187,6 +233,57 @@ PF_DEVICE float subrow_allreduce(float v) {
     if (LOG2 >= 4) v = Op::apply(v, dpp_move<0x140>(v));
     return v;
 }
+
+// ---------------------------------------------------------------------------------------------
+// mean / variance statistics as (count, mean, M2) triples
+// ---------------------------------------------------------------------------------------------
+struct Stat {
+    float n, mean, m2;
+};
+
+// parallel-variance update; counts are small integers, so the approximate reciprocal is exact enough
+PF_DEVICE Stat stat_merge(Stat a, Stat b) {
+    const float n = a.n + b.n;
+    const float inv = n > 0.0f ? __builtin_amdgcn_rcpf(n) : 0.0f;
+    const float delta = b.mean - a.mean;
+    Stat r;
+    r.n = n;
+    r.mean = a.mean + delta * (b.n * inv);
+    r.m2 = a.m2 + b.m2 + delta * delta * (a.n * b.n * inv);
+    return r;
+}
+
+PF_DEVICE Stat stat_shfl_xor(Stat s, int mask) {
+    Stat r;
+    r.n = __shfl_xor(s.n, mask, 64);
+    r.mean = __shfl_xor(s.mean, mask, 64);
+    r.m2 = __shfl_xor(s.m2, mask, 64);
+    return r;
+}
+
+// running sums of deviations from a pivot
+struct LaneAcc {
+    float n = 0.0f, s = 0.0f, ss = 0.0f, pivot = 0.0f;
+    template <int VEC>
+    PF_DEVICE void add_vector(const float* x) {
+        if (n == 0.0f) pivot = x[0];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float d = x[e] - pivot;
+            s += d;
+            ss += d * d;
+        }
+        n += (float)VEC;
+    }
+    PF_DEVICE Stat finish() const {
+        Stat r;
+        r.n = n;
+        const float inv = n > 0.0f ? 1.0f / n : 0.0f;
+        r.mean = pivot + s * inv;
+        r.m2 = fmaxf(ss - s * s * inv, 0.0f);
+        return r;
+    }
+};
 
 // ---------------------------------------------------------------------------------------------
 // element-wise math
@@ -320,6 +417,30 @@ PF_DEVICE u32x4 load_vec_operand(const VecArg& va, uint32_t row, uint32_t col, u
     if (va.numel == 1) return Storage<DT>::splat(va.ptr);
     const uint32_t off = vec_offset(va, row, col, n_inner);
     return load_cached(va.ptr, (uint64_t)off * Storage<DT>::ESIZE);
+}
+
+// The same for a position whose vector may be unaligned or partial: gathered element by element.
+template <int DT>
+PF_DEVICE u32x4 load_vec_operand_elems(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner, uint32_t count) {
+    using S = Storage<DT>;
+    if (va.numel == 1) return S::splat(va.ptr);
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (DT == DT_F32) {
+        const uint32_t* p = static_cast<const uint32_t*>(va.ptr);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((uint32_t)e < count) r[e] = p[vec_offset(va, row, col + e, n_inner)];
+    } else {
+        const uint16_t* p = static_cast<const uint16_t*>(va.ptr);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t lo = 0u, hi = 0u;
+            if ((uint32_t)(2 * j) < count) lo = p[vec_offset(va, row, col + 2 * j, n_inner)];
+            if ((uint32_t)(2 * j + 1) < count) hi = p[vec_offset(va, row, col + 2 * j + 1, n_inner)];
+            r[j] = lo | (hi << 16);
+        }
+    }
+    return r;
 }
 
 template <int DT, int K>

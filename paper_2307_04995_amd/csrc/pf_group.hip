@@ -21,54 +21,6 @@
 
 namespace pf {
 
-struct Stat {
-    float n, mean, m2;
-};
-
-// parallel-variance update; counts are small integers, so the approximate reciprocal is exact enough
-PF_DEVICE Stat stat_merge(Stat a, Stat b) {
-    const float n = a.n + b.n;
-    const float inv = n > 0.0f ? __builtin_amdgcn_rcpf(n) : 0.0f;
-    const float delta = b.mean - a.mean;
-    Stat r;
-    r.n = n;
-    r.mean = a.mean + delta * (b.n * inv);
-    r.m2 = a.m2 + b.m2 + delta * delta * (a.n * b.n * inv);
-    return r;
-}
-
-PF_DEVICE Stat stat_shfl_xor(Stat s, int mask) {
-    Stat r;
-    r.n = __shfl_xor(s.n, mask, 64);
-    r.mean = __shfl_xor(s.mean, mask, 64);
-    r.m2 = __shfl_xor(s.m2, mask, 64);
-    return r;
-}
-
-// running sums of deviations from a pivot
-struct LaneAcc {
-    float n = 0.0f, s = 0.0f, ss = 0.0f, pivot = 0.0f;
-    template <int VEC>
-    PF_DEVICE void add_vector(const float* x) {
-        if (n == 0.0f) pivot = x[0];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const float d = x[e] - pivot;
-            s += d;
-            ss += d * d;
-        }
-        n += (float)VEC;
-    }
-    PF_DEVICE Stat finish() const {
-        Stat r;
-        r.n = n;
-        const float inv = n > 0.0f ? 1.0f / n : 0.0f;
-        r.mean = pivot + s * inv;
-        r.m2 = fmaxf(ss - s * s * inv, 0.0f);
-        return r;
-    }
-};
-
 // Statistics straight from the packed 16-bit vector, without widening every element: two dot-product
 // instructions per pair of elements accumulate the sum and the sum of squares in fp32.  Products of 16-bit
 // values are exact in fp32 and a lane sums at most a few dozen elements, so the only cancellation left is

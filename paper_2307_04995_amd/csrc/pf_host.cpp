@@ -689,6 +689,7 @@ struct pf_plan_s {
     int spec_id = 0;          // 0 = generic interpreter
     int k = 1;                // 16-byte vectors per lane
     bool reduce_only = false;
+    bool ragged = false;      // rows or broadcast operands that are not whole 16-byte vectors: element-granular kernels
     pf::ChainArgs args;       // pointers are filled per run
     pf::RowGeom row;
     pf::GroupGeom group;
@@ -729,7 +730,7 @@ pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
         va.numel = (uint32_t)n;
         va.period_rows = 1;
         if (n == 1) continue;
-        if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "broadcast input %d: size is not a multiple of 16 bytes", in);
+        if ((n * es) % 16 != 0) p->ragged = true;  // gathered element by element (row and element-wise families)
         if (n >= inner) {
             if (n % inner != 0) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d does not tile the kernel's rows", in);
             va.period_rows = (uint32_t)(n / inner);
@@ -746,17 +747,17 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     const int vec = 16 / es;
     const int64_t n = L.pre_shape.back();
     const int64_t rows = numel(L.pre_shape) / n;
-    if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "row length %lld is not a multiple of 16 bytes", (long long)n);
+    if ((n * es) % 16 != 0) p->ragged = true;
     if (rows > 0xffffffffLL || n > 0x7fffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the row family");
-    const int64_t vpr = n / vec;
+    const int64_t vpr = (n + vec - 1) / vec;
     // candidates (waves per row, vectors per lane); prefer little idle lanes, a statically specialised
     // kernel, small workgroups, a single wave per row
     const bool reduce_only = L.core == pf::CORE_REDUCE_SUM || L.core == pf::CORE_REDUCE_MAX || L.core == pf::CORE_REDUCE_MEAN;
-    const int matched = (!reduce_only && env_int("PF_NO_STATIC", 0) == 0) ? match_spec(spec_table().row, L) : 0;
+    const int matched = (!reduce_only && !p->ragged && env_int("PF_NO_STATIC", 0) == 0) ? match_spec(spec_table().row, L) : 0;
     int best_wpr = 0, best_k = 0;
     long best_score = -1;
     const int ks[3] = {1, 2, 4};
-    for (int ki = 0; ki < 3; ++ki) {
+    for (int ki = 0; ki < 3 && forced_variant != PF_VARIANT_ROW_STREAM; ++ki) {
         const int k = ks[ki];
         const int64_t wpr = (vpr + 64 * k - 1) / (64 * k);
         if (wpr > 16) continue;
@@ -772,11 +773,37 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
             best_k = k;
         }
     }
-    if (best_score < 0) {
-        if (forced_variant >= 0) return fail(PF_ERR_UNSUPPORTED, "variant %d is not possible for row length %lld", forced_variant, (long long)n);
-        return fail(PF_ERR_UNSUPPORTED, "row length %lld exceeds what one workgroup keeps in registers", (long long)n);
+    p->reduce_only = reduce_only;
+    if (p->reduce_only) {
+        // the epilogue runs on one value per row: no tensor operands there
+        for (int i = 0; i < L.epi.n; ++i)
+            if (L.epi.u[i].kind != pf::K_NONE && L.epi.u[i].kind != pf::K_IMM)
+                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
+        for (int i = 0; i < L.epi.n; ++i)
+            if (L.epi.u[i].code == pf::U_MASK_CAUSAL || L.epi.u[i].code == pf::U_STORE)
+                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
+        if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "a keep-dim reduction has one output");
     }
     p->family = PF_FAMILY_ROW;
+    p->args.n_inner = (uint32_t)n;
+    p->args.rows = (uint64_t)rows;
+    if (best_score < 0) {
+        // Rows longer than a workgroup keeps in registers (or on request): the streaming variant, a workgroup
+        // per row, two walks over the row.
+        if (forced_variant >= 0 && forced_variant != PF_VARIANT_ROW_STREAM)
+            return fail(PF_ERR_UNSUPPORTED, "variant %d is not possible for row length %lld", forced_variant, (long long)n);
+        if (rows > 0x7fffffffLL || n * es > 0x7fffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the streaming row variant");
+        p->variant = PF_VARIANT_ROW_STREAM;
+        p->k = 2;
+        p->spec_id = 0;
+        p->row.waves_per_row = 8;
+        p->row.rows_per_block = 1;
+        p->row.rows_per_wave = 1;
+        p->block = dim3(512);
+        p->grid = dim3((uint32_t)rows);
+        p->lds_bytes = (2 * 16 + 8 * 3) * 4;
+        return PF_OK;
+    }
     p->variant = best_wpr == 1 ? PF_VARIANT_ROW_WAVE : PF_VARIANT_ROW_BLOCK;
     p->k = best_k;
     p->row.waves_per_row = (uint32_t)best_wpr;
@@ -795,19 +822,6 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     }
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
-    p->reduce_only = reduce_only;
-    if (p->reduce_only) {
-        // the epilogue runs on one value per row: no tensor operands there
-        for (int i = 0; i < L.epi.n; ++i)
-            if (L.epi.u[i].kind != pf::K_NONE && L.epi.u[i].kind != pf::K_IMM)
-                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
-        for (int i = 0; i < L.epi.n; ++i)
-            if (L.epi.u[i].code == pf::U_MASK_CAUSAL || L.epi.u[i].code == pf::U_STORE)
-                return fail(PF_ERR_UNSUPPORTED, "after a keep-dim reduction only unary and constant steps are implemented");
-        if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "a keep-dim reduction has one output");
-    }
-    p->args.n_inner = (uint32_t)n;
-    p->args.rows = (uint64_t)rows;
     p->spec_id = (matched && pf::row_static_available(matched, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) ? matched : 0;
     if (!p->spec_id) p->row.rows_per_wave = 1;
     {
@@ -823,14 +837,19 @@ pf_status plan_ew(pf_plan_s* p) {
     const int vec = 16 / es;
     const int64_t n = L.pre_shape.back();
     const int64_t total = numel(L.pre_shape);
-    if ((n * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost extent %lld is not a multiple of 16 bytes", (long long)n);
-    const int64_t total_vecs = total / vec;
+    if ((n * es) % 16 != 0) p->ragged = true;
+    if (p->ragged) {
+        for (int i = 0; i < L.pro.n; ++i)
+            if (L.pro.u[i].code == pf::U_MASK_CAUSAL)
+                return fail(PF_ERR_UNSUPPORTED, "a causal mask without a row reduction needs rows of whole 16-byte vectors");
+    }
+    const int64_t total_vecs = (total + vec - 1) / vec;
     if (total_vecs > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the element-wise family");
     p->family = PF_FAMILY_ELEMENTWISE;
     p->variant = PF_VARIANT_EW_FLAT;
     p->k = 1;
     p->ew_total_vecs = (uint32_t)total_vecs;
-    p->ew_vecs_per_row = (uint32_t)(n / vec);
+    p->ew_vecs_per_row = (uint32_t)std::max<int64_t>(1, n / vec);
     p->block = dim3(256);
     p->grid = dim3((uint32_t)((total_vecs + 256 * p->k - 1) / (256 * p->k)));
     p->args.n_inner = (uint32_t)n;
@@ -865,6 +884,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     const Shape& in = L.pre_shape;
     const int rank = (int)in.size();
     if (numel(in) > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the transpose family");
+    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the transpose family is not a multiple of 16 bytes");
     for (int i = 0; i < L.pro.n; ++i)
         if (L.pro.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the transpose family");
     for (int i = 0; i < L.epi.n; ++i)
@@ -1052,6 +1072,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     const int64_t hw = numel(sh) / (samples * C);
     const int64_t G = L.groups;
     if ((C * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)C);
+    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the group family is not a multiple of 16 bytes");
     const int64_t cpg = C / G;
     if (cpg % vec != 0) return fail(PF_ERR_UNSUPPORTED, "channels per group (%lld) must be a multiple of %d", (long long)cpg, vec);
     const int64_t vpg = cpg / vec, cv = C / vec;
@@ -1305,11 +1326,12 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
     hipError_t e = hipSuccess;
     switch (plan->family) {
         case PF_FAMILY_ROW:
-            if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
-            else e = pf::launch_row_generic(L.main_dtype, a, plan->row, plan->k, plan->reduce_only, plan->grid, plan->block, st);
+            if (plan->variant == PF_VARIANT_ROW_STREAM) e = pf::launch_row_stream(L.main_dtype, a, plan->ragged, plan->grid, st);
+            else if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
+            else e = pf::launch_row_generic(L.main_dtype, a, plan->row, plan->k, plan->reduce_only, plan->ragged, plan->grid, plan->block, st);
             break;
         case PF_FAMILY_ELEMENTWISE:
-            e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->grid, st);
+            e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->ragged, plan->grid, st);
             break;
         case PF_FAMILY_GROUP: {
             pf::GroupGeom g = plan->group;

@@ -6,13 +6,14 @@
 
 namespace pf {
 
-hipError_t launch_row_generic(int dtype, const ChainArgs& a, const RowGeom& g, int k, bool reduce_only, dim3 grid,
-                              dim3 block, hipStream_t st);
+hipError_t launch_row_generic(int dtype, const ChainArgs& a, const RowGeom& g, int k, bool reduce_only, bool ragged,
+                              dim3 grid, dim3 block, hipStream_t st);
+hipError_t launch_row_stream(int dtype, const ChainArgs& a, bool ragged, dim3 grid, hipStream_t st);
 bool row_static_available(int spec_id, int kc, int rpw, bool wave_rows, unsigned block_threads);
 hipError_t launch_row_static(int spec_id, int dtype, const ChainArgs& a, const RowGeom& g, int k, dim3 grid, dim3 block,
                              hipStream_t st);
-hipError_t launch_ew(int dtype, const ChainArgs& a, uint32_t total_vecs, uint32_t vecs_per_row, int k, dim3 grid,
-                     hipStream_t st);
+hipError_t launch_ew(int dtype, const ChainArgs& a, uint32_t total_vecs, uint32_t vecs_per_row, int k, bool ragged,
+                     dim3 grid, hipStream_t st);
 hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
                        dim3 block, uint32_t lds, hipStream_t st);
 // phase 0: fused (resident) kernel; 1: statistics launch; 2: normalisation launch

@@ -13,6 +13,7 @@
 namespace pf {
 
 // Secondary-output stores (U_STORE) for layouts where a value's position equals the input's.
+template <bool RAGGED = false>
 struct RowStore {
     void* out0;
     void* out1;
@@ -23,23 +24,33 @@ struct RowStore {
         using S = Storage<DT>;
         void* dst = slot == 0 ? out0 : out1;
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (st.col[k] < limit)
+        for (int k = 0; k < K; ++k) {
+            if (RAGGED)
+                store_elems<DT>(dst, row_byte / S::ESIZE + st.col[k], elems_below<S::VEC>(st.col[k], limit), S::pack(st.acc + k * S::VEC));
+            else if (st.col[k] < limit)
                 store_stream(dst, row_byte + (uint64_t)st.col[k] * S::ESIZE, S::pack(st.acc + k * S::VEC));
+        }
     }
 };
+template <bool RAGGED = false>
 struct FlatStore {
     void* out0;
     void* out1;
     uint32_t total_vecs, vecs_per_row;
+    uint64_t total_elems;
     template <int DT, int K, class Spec>
-    PF_DEVICE void operator()(int slot, const LaneState<DT, K, Spec>& st) const {
+    PF_DEVICE void operator()(int slot, const LaneState<DT, K, Spec>& st, const uint32_t (&gv)[K]) const {
         using S = Storage<DT>;
         void* dst = slot == 0 ? out0 : out1;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const uint32_t gv = st.row[k] * vecs_per_row + st.col[k] / S::VEC;
-            if (gv < total_vecs) store_stream(dst, (uint64_t)gv * 16u, S::pack(st.acc + k * S::VEC));
+            if (RAGGED) {
+                const uint64_t first = (uint64_t)gv[k] * S::VEC;
+                const uint32_t cnt = first < total_elems ? (uint32_t)(total_elems - first < S::VEC ? total_elems - first : S::VEC) : 0u;
+                store_elems<DT>(dst, first, cnt, S::pack(st.acc + k * S::VEC));
+            } else if (gv[k] < total_vecs) {
+                store_stream(dst, (uint64_t)gv[k] * 16u, S::pack(st.acc + k * S::VEC));
+            }
         }
     }
 };
@@ -61,7 +72,8 @@ PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, ui
 // Issue the loads of every operand of a row tile before anything is used.  `row_byte` is wave-uniform,
 // so each load is a scalar base plus a 32-bit lane offset.  Vectors that are not loaded read as `fill`.
 // The KC vectors starting at k0 belong to the row at `row_byte`.
-template <int DT, int K, int KC, class Spec>
+// RAGGED: the row's byte length is not a multiple of 16; its vectors are gathered element by element.
+template <int DT, int K, int KC, class Spec, bool RAGGED = false>
 PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, int k0, uint64_t row_byte, uint32_t row,
                                  uint32_t load_limit, uint32_t limit, uint32_t fill) {
     using S = Storage<DT>;
@@ -73,7 +85,8 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
             for (int c = 0; c < KC; ++c) {
                 const int k = k0 + c;
                 s.fraw[f][k] = u32x4{fill, fill, fill, fill};
-                if (s.col[k] < load_limit) s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
+                if (RAGGED) s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill);
+                else if (s.col[k] < load_limit) s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
             }
         }
     }
@@ -84,7 +97,9 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
             for (int c = 0; c < KC; ++c) {
                 const int k = k0 + c;
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
-                if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, s.col[k], a.n_inner);
+                if (RAGGED)
+                    s.vraw[v][k] = load_vec_operand_elems<DT>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
+                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, s.col[k], a.n_inner);
             }
         }
     }
@@ -95,7 +110,9 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 //                 rows per wave put more loads in flight per wave, which is what short rows need to cover
 //                 the HBM latency.
 //   WPR1 = false: waves_per_row waves of a workgroup share one row (RPW must be 1).
-template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1>
+//   RAGGED      : the row length is not a multiple of a 16-byte vector (element-granular loads, stores and
+//                 validity; RPW must be 1).
+template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false>
 __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -103,6 +120,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     constexpr int EC = KC * VEC;  // elements per lane per row
     constexpr bool PR = S::PRECISE;
     static_assert(WPR1 || RPW == 1, "several rows per wave only when a wave owns its rows");
+    static_assert(!RAGGED || RPW == 1, "ragged rows are taken one per wave or workgroup");
     __shared__ float red[2][16];
 
     const uint32_t lane = threadIdx.x & 63u;
@@ -139,11 +157,11 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             s.col[r * KC + c] = (lane_in_row + 64u * wpr * c) * VEC;
         }
         row_byte[r] = row64 * n * S::ESIZE;
-        load_row_operands<DT, K, KC, Spec>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
+        load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
     }
 
     // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
-    const RowStore store_fn{a.out[0], a.out[1], row_byte[0], limit[0]};
+    const RowStore<RAGGED> store_fn{a.out[0], a.out[1], row_byte[0], limit[0]};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
     // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
@@ -153,9 +171,11 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         float* acc = s.acc + r * EC;
-        bool valid[KC];
+        uint32_t nvalid[KC];  // valid elements of vector c: 0 or VEC unless the row is ragged
 #pragma unroll
-        for (int c = 0; c < KC; ++c) valid[c] = s.col[r * KC + c] < limit[r];
+        for (int c = 0; c < KC; ++c)
+            nvalid[c] = RAGGED ? elems_below<VEC>(s.col[r * KC + c], limit[r]) : (s.col[r * KC + c] < limit[r] ? (uint32_t)VEC : 0u);
+        auto valid_elem = [&](int c, int e) { return RAGGED ? (uint32_t)e < nvalid[c] : nvalid[c] != 0u; };
         const bool all_valid = exact && limit[r] != 0u;
         if (core == CORE_SOFTMAX) {
             if (a.core_mask == 2u) {
@@ -185,7 +205,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
                 for (int c = 0; c < KC; ++c)
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc[c * VEC + e] = valid[c] ? acc[c * VEC + e] : -__builtin_inff();
+                    for (int e = 0; e < VEC; ++e) acc[c * VEC + e] = valid_elem(c, e) ? acc[c * VEC + e] : -__builtin_inff();
             }
             float m = acc[0];
 #pragma unroll
@@ -219,7 +239,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
                 for (int c = 0; c < KC; ++c)
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc[c * VEC + e] = valid[c] ? acc[c * VEC + e] : 0.0f;
+                    for (int e = 0; e < VEC; ++e) acc[c * VEC + e] = valid_elem(c, e) ? acc[c * VEC + e] : 0.0f;
             }
             float s1 = 0.0f;
 #pragma unroll
@@ -232,7 +252,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                 for (int e = 0; e < VEC; ++e) {
                     const float d = acc[c * VEC + e] - mean;
                     acc[c * VEC + e] = d;
-                    s2 += (all_valid || valid[c]) ? d * d : 0.0f;
+                    s2 += (all_valid || valid_elem(c, e)) ? d * d : 0.0f;
                 }
             const float var = row_allreduce<OpSum>(s2, wpr, wave, lane, red[1]) * inv_n;
             const float rstd = pf_rsqrt<PR>(var + a.eps);
@@ -251,7 +271,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
             for (int c = 0; c < KC; ++c)
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s2 += (all_valid || valid[c]) ? acc[c * VEC + e] * acc[c * VEC + e] : 0.0f;
+                for (int e = 0; e < VEC; ++e) s2 += (all_valid || valid_elem(c, e)) ? acc[c * VEC + e] * acc[c * VEC + e] : 0.0f;
             const float ms = row_allreduce<OpSum>(s2, wpr, wave, lane, red[0]) * inv_n;
             const float rstd = pf_rsqrt<PR>(ms + a.eps);
             float gm[EC];
@@ -271,14 +291,15 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
         for (int c = 0; c < KC; ++c) {
             const int k = r * KC + c;
-            if (s.col[k] < limit[r]) store_stream(out_row, s.col[k] * (uint32_t)S::ESIZE, S::pack(s.acc + k * VEC));
+            if (RAGGED) store_elems<DT>(out_row, s.col[k], elems_below<VEC>(s.col[k], limit[r]), S::pack(s.acc + k * VEC));
+            else if (s.col[k] < limit[r]) store_stream(out_row, s.col[k] * (uint32_t)S::ESIZE, S::pack(s.acc + k * VEC));
         }
     }
 }
 
 // Reduction cores whose result is one value per row (REDUCE_SUM / MAX / MEAN, keepdim): the epilogue runs
 // on that single value and one lane stores it.
-template <int DT, int K>
+template <int DT, int K, bool RAGGED = false>
 __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
     using Spec = GenericSpec;
@@ -301,8 +322,9 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
         s.col[k] = (lane_in_row + 64u * wpr * k) * VEC;
     }
     const uint64_t row_byte = row64 * n * S::ESIZE;
-    load_row_operands<DT, K, K, Spec>(a, s, 0, row_byte, row, limit, limit, 0u);
+    load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_byte, row, limit, limit, 0u);
     run_program<DT, K, Spec>(ProgView<DynList>{a.pro}, s, NoStore{});
+    auto valid_elem = [&](int k, int e) { return RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit; };
     float r;
     if (a.core == CORE_REDUCE_MAX) {
         float m = -__builtin_inff();
@@ -312,7 +334,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const float x = s.acc[k * VEC + e];
-                if (s.col[k] < limit) {
+                if (valid_elem(k, e)) {
                     m = fmaxf(m, x);
                     nan_seen = (x != x) ? 1.0f : nan_seen;
                 }
@@ -325,7 +347,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
 #pragma unroll
         for (int k = 0; k < K; ++k)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) sum += (s.col[k] < limit) ? s.acc[k * VEC + e] : 0.0f;
+            for (int e = 0; e < VEC; ++e) sum += valid_elem(k, e) ? s.acc[k * VEC + e] : 0.0f;
         r = row_allreduce<OpSum>(sum, wpr, wave, lane, red[0]);
         if (a.core == CORE_REDUCE_MEAN) r = r / (float)n;
     }
@@ -347,20 +369,30 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
 }
 
 // Element-wise family: a flat stream of vectors, K per lane, lanes of a workgroup adjacent for each k.
-template <int DT, int K, class Spec>
+// RAGGED: the innermost extent is not a multiple of a vector.  The tensors themselves are still 16-byte
+// aligned streams (only the last vector is partial), but a vector no longer lies inside one row: broadcast
+// operands are gathered per element at (flat index mod operand size).
+template <int DT, int K, class Spec, bool RAGGED = false>
 __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32_t total_vecs, const uint32_t vecs_per_row) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     LaneState<DT, K, Spec> s;
     const uint32_t base = blockIdx.x * (256u * K) + threadIdx.x;
-    uint32_t gv[K];
-    bool valid[K];
+    const uint64_t total_elems = a.rows * a.n_inner;
+    uint32_t gv[K], cnt[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         gv[k] = base + 256u * k;
-        valid[k] = gv[k] < total_vecs;
-        s.row[k] = gv[k] / vecs_per_row;
-        s.col[k] = (gv[k] - s.row[k] * vecs_per_row) * VEC;
+        if (RAGGED) {
+            const uint64_t first = (uint64_t)gv[k] * VEC;
+            cnt[k] = first < total_elems ? (uint32_t)(total_elems - first < VEC ? total_elems - first : VEC) : 0u;
+            s.row[k] = (uint32_t)(first / a.n_inner);
+            s.col[k] = (uint32_t)(first - (uint64_t)s.row[k] * a.n_inner);
+        } else {
+            cnt[k] = gv[k] < total_vecs ? (uint32_t)VEC : 0u;
+            s.row[k] = gv[k] / vecs_per_row;
+            s.col[k] = (gv[k] - s.row[k] * vecs_per_row) * VEC;
+        }
     }
 #pragma unroll
     for (int f = 0; f < Spec::NF; ++f) {
@@ -368,7 +400,8 @@ __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
-                if (valid[k]) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)gv[k] * 16u);
+                if (RAGGED && cnt[k] != (uint32_t)VEC) s.fraw[f][k] = load_elems<DT>(a.full[f], (uint64_t)gv[k] * VEC, cnt[k], 0u);
+                else if (cnt[k] != 0u) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)gv[k] * 16u);
             }
         }
     }
@@ -378,15 +411,42 @@ __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
-                if (valid[k]) s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], s.row[k], s.col[k], a.n_inner);
+                if (RAGGED) {
+                    // a flat position's element of a broadcast operand is (flat index mod operand size) in every
+                    // supported broadcast pattern
+                    const VecArg& va = a.vec[v];
+                    if (va.numel == 1) {
+                        s.vraw[v][k] = S::splat(va.ptr);
+                    } else {
+                        const uint32_t m0 = (uint32_t)(((uint64_t)gv[k] * VEC) % va.numel);
+                        uint32_t bits[VEC];
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            uint32_t off = m0 + (uint32_t)e;
+                            off = off >= va.numel ? off % va.numel : off;
+                            bits[e] = 0u;
+                            if ((uint32_t)e < cnt[k])
+                                bits[e] = DT == DT_F32 ? static_cast<const uint32_t*>(va.ptr)[off] : (uint32_t) static_cast<const uint16_t*>(va.ptr)[off];
+                        }
+                        if (DT == DT_F32) s.vraw[v][k] = u32x4{bits[0], bits[1], bits[2], bits[3]};
+                        else
+                            s.vraw[v][k] = u32x4{bits[0] | (bits[1 % VEC] << 16), bits[2 % VEC] | (bits[3 % VEC] << 16),
+                                                 bits[4 % VEC] | (bits[5 % VEC] << 16), bits[6 % VEC] | (bits[7 % VEC] << 16)};
+                    }
+                } else if (cnt[k] != 0u) {
+                    s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], s.row[k], s.col[k], a.n_inner);
+                }
             }
         }
     }
-    const FlatStore store_fn{a.out[0], a.out[1], total_vecs, vecs_per_row};
+    const FlatStore<RAGGED> flat{a.out[0], a.out[1], total_vecs, vecs_per_row, total_elems};
+    auto store_fn = [&](int slot, const LaneState<DT, K, Spec>& st) { flat(slot, st, gv); };
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-        if (valid[k]) store_stream(a.out[0], (uint64_t)gv[k] * 16u, S::pack(s.acc + k * VEC));
+    for (int k = 0; k < K; ++k) {
+        if (RAGGED && cnt[k] != (uint32_t)VEC) store_elems<DT>(a.out[0], (uint64_t)gv[k] * VEC, cnt[k], S::pack(s.acc + k * VEC));
+        else if (cnt[k] != 0u) store_stream(a.out[0], (uint64_t)gv[k] * 16u, S::pack(s.acc + k * VEC));
+    }
 }
 
 // Static program lists: each step packed as code | kind << 8 | slot << 16.

@@ -171,9 +171,13 @@ def _plan_status(spec, variant=None):
 
 
 def test_plan_errors():
-    # ragged innermost extent
+    # a ragged innermost extent is fine in the row and element-wise families (element-granular kernels) ...
     s = wl.ChainSpec(inputs=[("f16", (4, 12))])
     s.out(s.op("softmax", 0), "f16")
+    assert _plan_status(s) == pf.PF_OK
+    # ... but not (yet) in the group family
+    s = wl.ChainSpec(inputs=[("f16", (2, 4, 4, 12)), ("f16", (12,)), ("f16", (12,))])
+    s.out(s.op("groupnorm", 0, 1, 2, f=[1e-5], i=[3]), "f16")
     assert _plan_status(s) == pf.PF_ERR_ALIGNMENT
     # two cores
     s = wl.ChainSpec(inputs=[("f16", (4, 16))])
@@ -185,10 +189,11 @@ def test_plan_errors():
     s = wl.ChainSpec(inputs=[("f16", (4, 16)), ("f32", (16,))])
     s.out(s.op("add", 0, 1), "f16")
     assert _plan_status(s) == pf.PF_ERR_DTYPE
-    # row too long for one workgroup's registers
+    # a row too long for one workgroup's registers takes the streaming variant; the resident ones refuse it
     s = wl.ChainSpec(inputs=[("f32", (2, 65536))])
     s.out(s.op("softmax", 0), "f32")
-    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    assert _plan_status(s) == pf.PF_OK
+    assert _plan_status(s, pf.PF_VARIANT_ROW_BLOCK) == pf.PF_ERR_UNSUPPORTED
     # an innermost-changing permutation of 16-bit data may compute on one side only
     s = wl.ChainSpec(inputs=[("f16", (8, 64, 64))])
     v = s.op("relu", 0)

@@ -1,0 +1,107 @@
+"""GPU parity for innermost extents that are not a multiple of a 16-byte vector (element-granular kernels of
+the row and element-wise families), through the C ABI, element by element against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from pf_testlib import check_chain, gpu_run
+
+pytestmark = pytest.mark.gpu
+
+
+def _pf():
+    from paper_2307_04995_amd import binding as pf
+    return pf
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n", [197, 50, 3, 1])
+def test_ragged_scaled_softmax(n, dtype):
+    # attention scores of a sequence length that is not a multiple of 8 (e.g. 196 patches + 1 class token)
+    shape = (2, 3, min(n, 40), n)
+    x = wl.random_tensor(shape, dtype, 700 + n, scale=2.0)
+    spec = wl.ChainSpec(inputs=[(dtype, shape)])
+    v = spec.op("scale", 0, f=[0.125])
+    spec.out(spec.op("softmax", v), dtype)
+    _, info, _ = check_chain(spec, [x], what=f"ragged softmax n={n} {dtype}")
+    assert info.family == _pf().PF_FAMILY_ROW
+    y, _ = gpu_run(spec, [x])
+    np.testing.assert_allclose(wl.widen(y[0]).sum(-1), 1.0, atol=6e-3)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_ragged_causal_softmax(dtype):
+    spec, ins = wl.c2_causal_softmax(b=1, h=2, s=50, dtype=dtype)
+    check_chain(spec, ins, what="ragged causal softmax")
+    spec, ins = wl.c2_causal_softmax(b=1, h=1, s=37, s_k=61, dtype=dtype)
+    check_chain(spec, ins, what="ragged rectangular causal softmax")
+
+
+@pytest.mark.parametrize("rows,n,dtype", [(13, 100, "f16"), (5, 770, "f32"), (3, 4099, "bf16"), (7, 1001, "f16")])
+def test_ragged_bias_residual_layernorm_two_outputs(rows, n, dtype):
+    # magnitudes kept below 4 so that one bf16 rounding step of the stored sum stays inside the absolute bar
+    x = wl.random_tensor((rows, n), dtype, 711, scale=0.4)
+    res = wl.random_tensor((rows, n), dtype, 712, scale=0.4)
+    bias = wl.random_tensor((n,), dtype, 713, scale=0.4)
+    gamma = wl.random_tensor((n,), dtype, 714, dist="positive", scale=0.6)
+    beta = wl.random_tensor((n,), dtype, 715, scale=0.3)
+    spec = wl.ChainSpec(inputs=[(dtype, (rows, n)), (dtype, (rows, n)), (dtype, (n,)), (dtype, (n,)), (dtype, (n,))])
+    h = spec.op("add", 0, 1)
+    h = spec.op("add", h, 2)
+    y = spec.op("layernorm", h, 3, 4, f=[1e-5])
+    y = spec.op("gelu_erf", y)
+    spec.out(y, dtype)
+    spec.out(h, dtype)
+    check_chain(spec, [x, res, bias, gamma, beta], what=f"ragged layernorm n={n} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_rmsnorm(dtype):
+    rows, n = 9, 1001
+    x = wl.random_tensor((rows, n), dtype, 721)
+    gamma = wl.random_tensor((n,), dtype, 722, dist="positive", scale=0.8)   # |output| < 4: bf16 steps inside the bar
+    spec = wl.ChainSpec(inputs=[(dtype, (rows, n)), (dtype, (n,))])
+    spec.out(spec.op("rmsnorm", 0, 1, f=[1e-6]), dtype)
+    check_chain(spec, [x, gamma], what="ragged rmsnorm")
+
+
+@pytest.mark.parametrize("op", ["reduce_sum", "reduce_max", "reduce_mean"])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_ragged_reduce_keepdim(op, dtype):
+    shape = (5, 7, 45)
+    x = wl.random_tensor(shape, dtype, 731, scale=0.25)
+    spec = wl.ChainSpec(inputs=[(dtype, shape)])
+    v = spec.op("relu", 0)
+    v = spec.op(op, v)
+    spec.out(spec.op("scale", v, f=[0.5]), dtype)
+    check_chain(spec, [x], what=f"ragged {op}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_ragged_elementwise_chain_with_broadcasts(dtype):
+    shape = (3, 5, 7, 30)
+    x = wl.random_tensor(shape, dtype, 741)
+    y = wl.random_tensor(shape, dtype, 742, dist="positive", scale=4.0)
+    bias = wl.random_tensor((30,), dtype, 743)
+    plane = wl.random_tensor((7, 30), dtype, 744)
+    spec = wl.ChainSpec(inputs=[(dtype, shape), (dtype, shape), (dtype, (30,)), (dtype, (7, 30))])
+    v = spec.op("add", 0, 2)
+    v = spec.op("div", v, 1)
+    v = spec.op("sub", 3, v)
+    v = spec.op("silu", v)
+    v = spec.op("max", v, 2)
+    spec.out(v, dtype)
+    spec.out(spec.op("relu", 0), dtype)
+    _, info, _ = check_chain(spec, [x, y, bias, plane], what="ragged elementwise chain")
+    assert info.family == _pf().PF_FAMILY_ELEMENTWISE
+
+
+def test_ragged_single_odd_row():
+    # 16-bit rows of odd length: every second row starts on a 2-byte boundary only
+    x = wl.random_tensor((6, 33), "f16", 751)
+    spec = wl.ChainSpec(inputs=[("f16", (6, 33))])
+    spec.out(spec.op("tanh", 0), "f16")
+    check_chain(spec, [x], what="odd rows, element-wise")
+    spec = wl.ChainSpec(inputs=[("f16", (6, 33))])
+    spec.out(spec.op("softmax", 0), "f16")
+    check_chain(spec, [x], what="odd rows, softmax")
