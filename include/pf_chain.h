@@ -136,11 +136,13 @@ typedef struct {
     uint64_t compulsory_write_bytes;   /* every output once */
     int32_t n_launches;                /* kernels enqueued per pf_chain_run */
     int32_t n_micro_ops;               /* element-wise steps the kernel executes per element */
-    int32_t spec_id;                   /* > 0: a statically specialised kernel was chosen; 0: the generic one */
+    int32_t spec_id;                   /* 0: run-time interpreted kernel; 1..254: built-in catalogue entry;
+                                          PF_SPEC_JIT: specialised for this chain when the plan was made      */
     int32_t vectors_per_lane;          /* 16-byte vectors each lane keeps in registers */
 } pf_plan_info;
 
 #define PF_VARIANT_EW_FLAT 0          /* element-wise: one 16-byte vector per lane per step                  */
+#define PF_SPEC_JIT 255               /* pf_plan_info.spec_id of a plan-time specialised kernel                */
 #define PF_VARIANT_ROW_WAVE 0         /* row family: one 64-lane wave owns a row                             */
 #define PF_VARIANT_ROW_BLOCK 1        /* row family: one workgroup owns a row                                */
 #define PF_VARIANT_ROW_STREAM 2       /* row family: a workgroup walks a long row twice in chunks            */
@@ -212,6 +214,15 @@ const char *pf_last_error(void); /* thread-local, valid until the next failing c
  * hardware traffic counters against a transfer of known size.
  */
 pf_status pf_copy_probe(const void *src, void *dst, uint64_t bytes, int32_t variant, void *stream);
+
+/*
+ * Diagnostic: how many kernels this process has specialised at plan time so far.  A chain whose structure
+ * (operand counts, steps, core; not shapes or constants) is not in the built-in catalogue has the library's
+ * kernel templates instantiated for it when its plan is made -- the counterpart of the paper's per-subgraph
+ * code generation from GIR templates (section 6) -- and later plans of the same structure reuse the kernel.
+ * PF_JIT=0 in the environment switches this off (such chains then run on the run-time-interpreted kernels).
+ */
+uint64_t pf_jit_compile_count(void);
 
 #ifdef __cplusplus
 }

@@ -31,6 +31,7 @@ OP_CODE = {name: i for i, name in enumerate([
 # pf_family
 PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE = range(4)
 PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK, PF_VARIANT_ROW_STREAM = 0, 1, 2
+PF_SPEC_GENERIC, PF_SPEC_JIT = 0, 255
 PF_VARIANT_GROUP_TWO_PASS, PF_VARIANT_GROUP_RESIDENT = 0, 1
 PF_VARIANT_T_ROWS, PF_VARIANT_T_LDS_ROWS, PF_VARIANT_T_TILE = 0, 1, 2
 
@@ -63,7 +64,7 @@ class pf_plan_info(C.Structure):
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
-           "pf_last_error", "pf_copy_probe"]
+           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count"]
 
 
 def _load() -> C.CDLL:
@@ -87,8 +88,10 @@ def _load() -> C.CDLL:
     lib.pf_last_error.argtypes = []
     lib.pf_last_error.restype = C.c_char_p
     lib.pf_copy_probe.argtypes = [vp, vp, C.c_uint64, C.c_int32, vp]
+    lib.pf_jit_compile_count.argtypes = []
+    lib.pf_jit_compile_count.restype = C.c_uint64
     for name in EXPORTS:
-        if name not in ("pf_chain_plan_destroy", "pf_status_str", "pf_last_error"):
+        if name not in ("pf_chain_plan_destroy", "pf_status_str", "pf_last_error", "pf_jit_compile_count"):
             getattr(lib, name).restype = C.c_int
     return lib
 
@@ -165,6 +168,10 @@ def pf_chain_plan_destroy(plan) -> None:
 def pf_copy_probe(src_ptr: int, dst_ptr: int, nbytes: int, variant: int = 2, stream: int = 0) -> int:
     return _lib.pf_copy_probe(C.c_void_p(int(src_ptr)), C.c_void_p(int(dst_ptr)), C.c_uint64(int(nbytes)),
                               C.c_int32(int(variant)), C.c_void_p(int(stream)))
+
+
+def pf_jit_compile_count() -> int:
+    return int(_lib.pf_jit_compile_count())
 
 
 # ---- marshalling helpers -------------------------------------------------------------------------

@@ -12,7 +12,16 @@
 // by hand the two merging rules of the paper (section 5.1): every write-then-read pair between operators
 // collapsed into a register, every repeated read of an input served by the same load.
 #pragma once
+#ifndef __HIPCC_RTC__
 #include <stdint.h>
+#else  // the run-time compiler has no C library headers
+typedef unsigned char uint8_t;
+typedef unsigned short uint16_t;
+typedef unsigned int uint32_t;
+typedef int int32_t;
+typedef unsigned long uint64_t;
+typedef long int64_t;
+#endif
 
 #define PF_DEV_MAX_FULL 3
 #define PF_DEV_MAX_VEC 4

@@ -11,7 +11,9 @@
 // All control flow inside the interpreter depends only on kernel arguments, so it is wave-uniform and
 // costs scalar branches, not divergence.
 #pragma once
+#ifndef __HIPCC_RTC__  // the run-time compiler brings the HIP device declarations with it
 #include <hip/hip_runtime.h>
+#endif
 
 #include "pf_common.h"
 
@@ -117,8 +119,17 @@ PF_DEVICE u32x4 load_cached(const void* base, uint64_t byte_off) {
 // Element-granular access, for rows whose byte length is not a multiple of 16: their vectors are not
 // 16-byte aligned and the last one is partial.  The first `count` elements of the vector are touched; the
 // others read as the matching half of `fill` and are not stored.
+//
+// Whole vectors of such a row move as one 16-byte access at element alignment (the device runs with
+// unaligned global access enabled, and the compiler emits a single dwordx4 access for this pointer type); only
+// the partial vector at the end of a row goes element by element, so nothing outside the row is touched.
+typedef u32x4 u32x4_elem_aligned __attribute__((aligned(2)));
+
 template <int DT>
 PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill) {
+    if (count == (uint32_t)Storage<DT>::VEC)
+        return __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
     u32x4 r = {fill, fill, fill, fill};
     if (DT == DT_F32) {
         const uint32_t* p = static_cast<const uint32_t*>(base) + elem;
@@ -139,6 +150,10 @@ PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint
 }
 template <int DT>
 PF_DEVICE void store_elems(void* base, uint64_t elem, uint32_t count, u32x4 v) {
+    if (count == (uint32_t)Storage<DT>::VEC) {
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_elem_aligned*>(static_cast<char*>(base) + elem * Storage<DT>::ESIZE));
+        return;
+    }
     if (DT == DT_F32) {
         uint32_t* p = static_cast<uint32_t*>(base) + elem;
 #pragma unroll

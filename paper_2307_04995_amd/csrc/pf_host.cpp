@@ -24,6 +24,7 @@
 
 #include "../../include/pf_chain.h"
 #include "pf_common.h"
+#include "pf_jit.h"
 #include "pf_launch.h"
 #include "pf_specs.h"
 
@@ -689,6 +690,7 @@ struct pf_plan_s {
     int spec_id = 0;          // 0 = generic interpreter
     int k = 1;                // 16-byte vectors per lane
     bool reduce_only = false;
+    hipFunction_t jit_fn = nullptr;  // kernel specialised for this chain's structure when the plan was made (spec_id == kSpecJit)
     bool ragged = false;      // rows or broadcast operands that are not whole 16-byte vectors: element-granular kernels
     pf::ChainArgs args;       // pointers are filled per run
     pf::RowGeom row;
@@ -713,6 +715,30 @@ int env_int(const char* name, int dflt) {
     const char* s = getenv(name);
     if (!s || !*s) return dflt;
     return atoi(s);
+}
+
+// the chain's structure as template arguments for the plan-time specialisation
+pf::JitSpec make_jit_spec(const Lowered& L) {
+    pf::JitSpec j;
+    j.nf = L.n_full;
+    j.nv = L.n_vec;
+    j.nt = L.n_tmp;
+    j.core = L.core;
+    j.gamma = L.core_vec[0];
+    j.beta = L.core_vec[1];
+    for (int i = 0; i < L.pro.n; ++i)
+        j.pro.push_back((uint32_t)L.pro.u[i].code | ((uint32_t)L.pro.u[i].kind << 8) | ((uint32_t)L.pro.u[i].slot << 16));
+    for (int i = 0; i < L.epi.n; ++i)
+        j.epi.push_back((uint32_t)L.epi.u[i].code | ((uint32_t)L.epi.u[i].kind << 8) | ((uint32_t)L.epi.u[i].slot << 16));
+    return j;
+}
+
+// Plan-time specialisation needs the device (the compiled kernel is loaded onto it).
+bool jit_possible(int device) {
+    if (!pf::jit_enabled()) return false;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return false;
+    return hipSetDevice(device) == hipSuccess;
 }
 
 pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
@@ -754,6 +780,15 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     // kernel, small workgroups, a single wave per row
     const bool reduce_only = L.core == pf::CORE_REDUCE_SUM || L.core == pf::CORE_REDUCE_MAX || L.core == pf::CORE_REDUCE_MEAN;
     const int matched = (!reduce_only && !p->ragged && env_int("PF_NO_STATIC", 0) == 0) ? match_spec(spec_table().row, L) : 0;
+    // no catalogue entry: the same kernel templates are specialised for this chain's structure at plan time
+    // (also catalogue entries in launch shapes that were not instantiated at build time)
+    const bool jit_ok = jit_possible(p->device);
+    auto have_static = [&](int k, int rpw, bool wave_rows, unsigned threads) {
+        if (matched && pf::row_static_available(matched, k, rpw, wave_rows, threads)) return true;
+        if (!jit_ok) return false;
+        return (k == 1 || k == 2 || k == 4) && (rpw == 1 || rpw == 2 || rpw == 4) && k * rpw <= 4 && (wave_rows || rpw == 1) &&
+               threads <= 1024;
+    };
     int best_wpr = 0, best_k = 0;
     long best_score = -1;
     const int ks[3] = {1, 2, 4};
@@ -766,7 +801,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         const double waste = 1.0 - (double)vpr / (double)(wpr * 64 * k);
         const unsigned threads = 64u * (unsigned)wpr * (wpr >= 4 ? 1u : (unsigned)(4 / wpr));
         long score = (waste > 0.26 ? 4000 : (waste > 0.13 ? 2000 : 0)) + (wpr > 4 ? 1000 : 0) + (wpr > 1 ? 100 : 0) + k;
-        if (matched && !pf::row_static_available(matched, k, 1, wpr == 1, threads)) score += 500;
+        if ((matched || jit_ok) && !have_static(k, 1, wpr == 1, threads)) score += 500;
         if (best_score < 0 || score < best_score) {
             best_score = score;
             best_wpr = (int)wpr;
@@ -802,6 +837,12 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         p->block = dim3(512);
         p->grid = dim3((uint32_t)rows);
         p->lds_bytes = (2 * 16 + 8 * 3) * 4;
+        if (jit_ok) {
+            std::string err;
+            p->jit_fn = pf::jit_row_stream_kernel(p->device, L.main_dtype, p->ragged, make_jit_spec(L), &err);
+            if (p->jit_fn) p->spec_id = pf::kSpecJit;
+            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        }
         return PF_OK;
     }
     p->variant = best_wpr == 1 ? PF_VARIANT_ROW_WAVE : PF_VARIANT_ROW_BLOCK;
@@ -812,17 +853,25 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     // Rows per wave: a wave that owns short rows takes several at once, so that it has about 4 KB of loads
     // in flight (what it takes to cover the HBM latency at full occupancy), as long as enough waves remain
     // (16 per SIMD) to fill the device evenly and a specialised kernel exists for the combination.
-    if (best_wpr == 1 && matched && L.n_out == 1) {
+    if (best_wpr == 1 && (matched || jit_ok) && L.n_out == 1) {
         const int64_t bytes_per_row_in_flight = (int64_t)L.n_full * best_k * 1024;
         int rpw = 1;
         while (rpw < 4 && bytes_per_row_in_flight * rpw < 4096 && best_k * rpw * 2 <= 4 && rows / (rpw * 2) >= 16384) rpw *= 2;
         const int forced = env_int("PF_ROWS_PER_WAVE", 0);
         if (forced > 0) rpw = forced;
-        if (rpw > 1 && pf::row_static_available(matched, best_k, rpw, true, 256)) p->row.rows_per_wave = (uint32_t)rpw;
+        if (rpw > 1 && have_static(best_k, rpw, true, 256)) p->row.rows_per_wave = (uint32_t)rpw;
     }
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
     p->spec_id = (matched && pf::row_static_available(matched, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) ? matched : 0;
+    if (!p->spec_id && jit_ok && have_static(p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) {
+        std::string err;
+        if (reduce_only) p->jit_fn = pf::jit_row_reduce_kernel(p->device, L.main_dtype, p->k, p->ragged, make_jit_spec(L), &err);
+        else p->jit_fn = pf::jit_row_kernel(p->device, L.main_dtype, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->ragged,
+                                       p->block.x <= 256 ? 256 : 1024, make_jit_spec(L), &err);
+        if (p->jit_fn) p->spec_id = pf::kSpecJit;
+        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+    }
     if (!p->spec_id) p->row.rows_per_wave = 1;
     {
         const int64_t rows_per_block = (int64_t)p->row.rows_per_block * p->row.rows_per_wave;
@@ -854,6 +903,12 @@ pf_status plan_ew(pf_plan_s* p) {
     p->grid = dim3((uint32_t)((total_vecs + 256 * p->k - 1) / (256 * p->k)));
     p->args.n_inner = (uint32_t)n;
     p->args.rows = (uint64_t)(total / n);
+    if (jit_possible(p->device)) {
+        std::string err;
+        p->jit_fn = pf::jit_ew_kernel(p->device, L.main_dtype, p->k, p->ragged, make_jit_spec(L), &err);
+        if (p->jit_fn) p->spec_id = pf::kSpecJit;
+        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+    }
     return PF_OK;
 }
 
@@ -1326,12 +1381,28 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
     hipError_t e = hipSuccess;
     switch (plan->family) {
         case PF_FAMILY_ROW:
-            if (plan->variant == PF_VARIANT_ROW_STREAM) e = pf::launch_row_stream(L.main_dtype, a, plan->ragged, plan->grid, st);
-            else if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
+            if (plan->variant == PF_VARIANT_ROW_STREAM) {
+                if (plan->spec_id == pf::kSpecJit) {
+                    void* params[] = {&a};
+                    e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+                } else {
+                    e = pf::launch_row_stream(L.main_dtype, a, plan->ragged, plan->grid, st);
+                }
+            } else if (plan->spec_id == pf::kSpecJit) {
+                pf::RowGeom g = plan->row;
+                void* params[] = {&a, &g};
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+            } else if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
             else e = pf::launch_row_generic(L.main_dtype, a, plan->row, plan->k, plan->reduce_only, plan->ragged, plan->grid, plan->block, st);
             break;
         case PF_FAMILY_ELEMENTWISE:
-            e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->ragged, plan->grid, st);
+            if (plan->spec_id == pf::kSpecJit) {
+                uint32_t total_vecs = plan->ew_total_vecs, vecs_per_row = plan->ew_vecs_per_row;
+                void* params[] = {&a, &total_vecs, &vecs_per_row};
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+            } else {
+                e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->ragged, plan->grid, st);
+            }
             break;
         case PF_FAMILY_GROUP: {
             pf::GroupGeom g = plan->group;
@@ -1389,6 +1460,8 @@ const char* pf_status_str(pf_status s) {
 }
 
 const char* pf_last_error(void) { return g_last_error.c_str(); }
+
+uint64_t pf_jit_compile_count(void) { return pf::jit_compile_count(); }
 
 pf_status pf_copy_probe(const void* src, void* dst, uint64_t bytes, int32_t variant, void* stream) {
     if (!src || !dst) return fail(PF_ERR_INVALID_ARG, "null argument");

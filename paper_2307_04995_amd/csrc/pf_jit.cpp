@@ -1,0 +1,171 @@
+// Plan-time specialisation of the kernel templates for chains that are not in the built-in catalogue.
+//
+// The paper generates a kernel per fused subgraph from GIR templates: a graph structure chosen ahead of
+// time, parameters filled in per use (section 6, "GIR-Graph generation").  Here the kernel templates of the
+// library play that role.  A chain's lowered micro-programs become the template arguments of the same
+// kernels the catalogue instantiates at build time (StaticSpec / StaticList), and the HIP run-time compiler
+// instantiates them for gfx950 when the plan is made.  Nothing is traced or searched: the "code generator"
+// writes one template-id; shapes and immediates stay run-time arguments, so one compiled kernel serves every
+// chain with the same structure.  Compiled kernels are kept for the life of the process.
+//
+// If the run-time compiler or the kernel headers are not available the planner falls back to the
+// run-time-interpreted kernels (still on the GPU); nothing else changes.
+#include "pf_jit.h"
+
+#include <dlfcn.h>
+#include <hip/hiprtc.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <map>
+#include <mutex>
+#include <sstream>
+#include <string>
+#include <vector>
+
+namespace pf {
+
+namespace {
+
+std::mutex g_mutex;
+std::map<std::string, hipFunction_t> g_cache;  // (device, template-id) -> kernel
+uint64_t g_compiles = 0;
+
+// the directory that holds the kernel headers: next to the shared library (<package>/lib -> <package>/csrc),
+// unless PF_JIT_INCLUDE names another one
+std::string include_dir() {
+    if (const char* e = getenv("PF_JIT_INCLUDE"))
+        if (*e) return e;
+    Dl_info info;
+    if (dladdr(reinterpret_cast<const void*>(&include_dir), &info) == 0 || !info.dli_fname) return "";
+    std::string lib = info.dli_fname;
+    const size_t slash = lib.rfind('/');
+    if (slash == std::string::npos) return "";
+    return lib.substr(0, slash) + "/../csrc";
+}
+
+bool file_exists(const std::string& p) {
+    FILE* f = fopen(p.c_str(), "rb");
+    if (!f) return false;
+    fclose(f);
+    return true;
+}
+
+std::string list_text(const std::vector<uint32_t>& l) {
+    std::ostringstream o;
+    o << "pf::StaticList<";
+    for (size_t i = 0; i < l.size(); ++i) o << (i ? ", " : "") << l[i] << "u";
+    o << ">";
+    return o.str();
+}
+
+std::string spec_text(const JitSpec& s) {
+    std::ostringstream o;
+    o << "pf::StaticSpec<" << s.nf << ", " << s.nv << ", " << s.nt << ", " << s.core << ", " << s.gamma << ", " << s.beta << ", "
+      << list_text(s.pro) << ", " << list_text(s.epi) << ">";
+    return o.str();
+}
+
+// Compile `source`, which must define the kernel named by the C++ expression `name_expr`, and return it
+// loaded on the current device.
+hipFunction_t compile(int device, const std::string& source, const std::string& name_expr, std::string* err) {
+    const std::string key = std::to_string(device) + "|" + name_expr;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    auto it = g_cache.find(key);
+    if (it != g_cache.end()) return it->second;
+    auto fail = [&](const std::string& what) -> hipFunction_t {
+        if (err) *err = what;
+        g_cache[key] = nullptr;  // do not try again for this structure
+        return nullptr;
+    };
+    const std::string inc = include_dir();
+    if (inc.empty() || !file_exists(inc + "/pf_row_kernels.hpp")) return fail("kernel headers not found (looked in '" + inc + "')");
+
+    hiprtcProgram prog = nullptr;
+    if (hiprtcCreateProgram(&prog, source.c_str(), "pf_jit.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+        return fail("hiprtcCreateProgram failed");
+    hiprtcAddNameExpression(prog, name_expr.c_str());
+    const std::string inc_opt = "-I" + inc;
+    // the same code generation options as the build-time kernels
+    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", inc_opt.c_str(), "-Wno-pass-failed",
+                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
+    if (rc != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        std::string log;
+        if (hiprtcGetProgramLogSize(prog, &n) == HIPRTC_SUCCESS && n > 1) {
+            log.resize(n);
+            hiprtcGetProgramLog(prog, &log[0]);
+        }
+        hiprtcDestroyProgram(&prog);
+        return fail("run-time compilation failed: " + log.substr(0, 2000));
+    }
+    const char* lowered = nullptr;
+    if (hiprtcGetLoweredName(prog, name_expr.c_str(), &lowered) != HIPRTC_SUCCESS || !lowered) {
+        hiprtcDestroyProgram(&prog);
+        return fail("cannot resolve the compiled kernel's name");
+    }
+    const std::string symbol = lowered;
+    size_t size = 0;
+    if (hiprtcGetCodeSize(prog, &size) != HIPRTC_SUCCESS || size == 0) {
+        hiprtcDestroyProgram(&prog);
+        return fail("empty code object");
+    }
+    std::vector<char> code(size);
+    hiprtcGetCode(prog, code.data());
+    hiprtcDestroyProgram(&prog);
+    hipModule_t mod = nullptr;
+    hipFunction_t fn = nullptr;
+    if (hipModuleLoadData(&mod, code.data()) != hipSuccess) return fail("hipModuleLoadData failed");
+    if (hipModuleGetFunction(&fn, mod, symbol.c_str()) != hipSuccess) return fail("hipModuleGetFunction failed");
+    ++g_compiles;
+    g_cache[key] = fn;  // the module stays loaded until the process ends
+    return fn;
+}
+
+}  // namespace
+
+bool jit_enabled() {
+    const char* e = getenv("PF_JIT");
+    if (e && *e && atoi(e) == 0) return false;
+    const char* ns = getenv("PF_NO_STATIC");
+    if (ns && *ns && atoi(ns) != 0) return false;
+    return true;
+}
+
+uint64_t jit_compile_count() {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return g_compiles;
+}
+
+hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads,
+                             const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::row_kernel<" << dtype << ", " << kc << ", " << rpw << ", " << spec_text(spec) << ", " << max_threads << ", "
+         << (wave_rows ? "true" : "false") << ", " << (ragged ? "true" : "false") << ">";
+    return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
+}
+
+hipFunction_t jit_row_reduce_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::row_reduce_kernel<" << dtype << ", " << k << ", " << (ragged ? "true" : "false") << ", " << spec_text(spec) << ">";
+    return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
+}
+
+hipFunction_t jit_row_stream_kernel(int device, int dtype, bool ragged, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::row_stream_kernel<" << dtype << ", " << (ragged ? "true" : "false") << ", " << spec_text(spec) << ">";
+    return compile(device, "#include \"pf_row_stream.hpp\"\n", name.str(), err);
+}
+
+hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::ew_kernel<" << dtype << ", " << k << ", " << spec_text(spec) << ", " << (ragged ? "true" : "false") << ">";
+    return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
+}
+
+hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, void** params, hipStream_t st) {
+    return hipModuleLaunchKernel(fn, grid.x, grid.y, grid.z, block.x, block.y, block.z, 0, st, params, nullptr);
+}
+
+}  // namespace pf

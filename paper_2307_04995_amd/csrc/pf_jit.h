@@ -1,0 +1,37 @@
+// Plan-time specialisation of the kernel templates (see pf_jit.cpp).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "pf_common.h"
+
+namespace pf {
+
+// Spec id reported for a kernel that was specialised when the plan was made.
+constexpr int kSpecJit = 255;
+
+// The structure of a chain as template arguments: operand counts, core, and the packed micro-programs
+// (code | kind << 8 | slot << 16 per step).
+struct JitSpec {
+    int nf = 0, nv = 0, nt = 0, core = 0, gamma = -1, beta = -1;
+    std::vector<uint32_t> pro, epi;
+};
+
+// false when PF_JIT=0 or PF_NO_STATIC=1
+bool jit_enabled();
+// kernels compiled so far in this process (cache hits do not count)
+uint64_t jit_compile_count();
+
+// Each returns the kernel for the current device, or nullptr (reason in *err) when it cannot be produced.
+hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads,
+                             const JitSpec& spec, std::string* err);
+hipFunction_t jit_row_reduce_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);
+hipFunction_t jit_row_stream_kernel(int device, int dtype, bool ragged, const JitSpec& spec, std::string* err);
+hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);
+
+// params: addresses of the kernel's arguments, in order
+hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, void** params, hipStream_t st);
+
+}  // namespace pf

@@ -110,8 +110,8 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 //                 rows per wave put more loads in flight per wave, which is what short rows need to cover
 //                 the HBM latency.
 //   WPR1 = false: waves_per_row waves of a workgroup share one row (RPW must be 1).
-//   RAGGED      : the row length is not a multiple of a 16-byte vector (element-granular loads, stores and
-//                 validity; RPW must be 1).
+//   RAGGED      : the row length is not a multiple of a 16-byte vector (element-aligned vector access, a
+//                 partial last vector, element-granular validity).
 template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false>
 __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
@@ -120,7 +120,6 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     constexpr int EC = KC * VEC;  // elements per lane per row
     constexpr bool PR = S::PRECISE;
     static_assert(WPR1 || RPW == 1, "several rows per wave only when a wave owns its rows");
-    static_assert(!RAGGED || RPW == 1, "ragged rows are taken one per wave or workgroup");
     __shared__ float red[2][16];
 
     const uint32_t lane = threadIdx.x & 63u;
@@ -299,10 +298,9 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 
 // Reduction cores whose result is one value per row (REDUCE_SUM / MAX / MEAN, keepdim): the epilogue runs
 // on that single value and one lane stores it.
-template <int DT, int K, bool RAGGED = false>
+template <int DT, int K, bool RAGGED = false, class Spec = GenericSpec>
 __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
-    using Spec = GenericSpec;
     constexpr int VEC = S::VEC;
     __shared__ float red[2][16];
     const uint32_t lane = threadIdx.x & 63u;
@@ -323,10 +321,10 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
     }
     const uint64_t row_byte = row64 * n * S::ESIZE;
     load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_byte, row, limit, limit, 0u);
-    run_program<DT, K, Spec>(ProgView<DynList>{a.pro}, s, NoStore{});
+    run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
     auto valid_elem = [&](int k, int e) { return RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit; };
     float r;
-    if (a.core == CORE_REDUCE_MAX) {
+    if (Spec::core(a) == CORE_REDUCE_MAX) {
         float m = -__builtin_inff();
         float nan_seen = 0.0f;
 #pragma unroll
@@ -349,7 +347,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
 #pragma unroll
             for (int e = 0; e < VEC; ++e) sum += valid_elem(k, e) ? s.acc[k * VEC + e] : 0.0f;
         r = row_allreduce<OpSum>(sum, wpr, wave, lane, red[0]);
-        if (a.core == CORE_REDUCE_MEAN) r = r / (float)n;
+        if (Spec::core(a) == CORE_REDUCE_MEAN) r = r / (float)n;
     }
     // epilogue on the row value: immediates and unary steps only (the planner guarantees it)
     LaneState<DT, 1, Spec> t;
@@ -357,7 +355,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
     t.col[0] = 0;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) t.acc[e] = r;
-    run_program<DT, 1, Spec>(ProgView<DynList>{a.epi}, t, NoStore{});
+    run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, t, NoStore{});
     if (row_ok && lane_in_row == 0) {
         if (DT == DT_F32) {
             static_cast<float*>(a.out[0])[row64] = t.acc[0];

@@ -90,10 +90,20 @@ def compare(got: torch.Tensor, want: np.ndarray, dtype: str, what: str = ""):
     return max_abs, max_rel
 
 
+SPEC_JIT = 255   # plan info spec_id of a kernel specialised for the chain when the plan was made
+
+
 def check_chain(spec, inputs, variant=None, generic=False, what=""):
     outs, info = gpu_run(spec, inputs, variant=variant, generic=generic)
     wants = oracle_run(spec, inputs)
     stats = []
     for o, w, (_, dt) in zip(outs, wants, spec.outputs):
         stats.append(compare(o, w, dt, what))
+    if not generic and info.spec_id == SPEC_JIT:
+        # the chain is not in the built-in catalogue and got a kernel of its own: the run-time-interpreted
+        # kernel it would have used otherwise is held to the same bar
+        outs_i, info_i = gpu_run(spec, inputs, variant=variant, generic=True)
+        assert info_i.spec_id == 0
+        for o, w, (_, dt) in zip(outs_i, wants, spec.outputs):
+            compare(o, w, dt, what + " (interpreted)")
     return outs, info, stats

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "pf_chain.h")).read()
-    declared = set(re.findall(r"^\s*(?:pf_status|void|const char \*)\s*\*?(pf_[a-z_]+)\s*\(", header, flags=re.M))
+    declared = set(re.findall(r"^\s*(?:pf_status|void|uint64_t|const char \*)\s*\*?(pf_[a-z_]+)\s*\(", header, flags=re.M))
     assert {"pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
             "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
             "pf_last_error", "pf_copy_probe"} <= declared
