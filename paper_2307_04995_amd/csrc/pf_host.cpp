@@ -690,6 +690,7 @@ struct pf_plan_s {
     int spec_id = 0;          // 0 = generic interpreter
     int k = 1;                // 16-byte vectors per lane
     bool reduce_only = false;
+    hipFunction_t jit_fn2 = nullptr; // second launch of a two-launch plan
     hipFunction_t jit_fn = nullptr;  // kernel specialised for this chain's structure when the plan was made (spec_id == kSpecJit)
     bool ragged = false;      // rows or broadcast operands that are not whole 16-byte vectors: element-granular kernels
     pf::ChainArgs args;       // pointers are filled per run
@@ -1034,6 +1035,12 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         p->block = dim3(256);
         p->grid = dim3((uint32_t)((total_tiles + 3) / 4));
         p->lds_bytes = 0;
+        if (!p->spec_id && jit_possible(p->device)) {
+            std::string err;
+            p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, make_jit_spec(L), &err);
+            if (p->jit_fn) p->spec_id = pf::kSpecJit;
+            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        }
         return PF_OK;
     }
     const int64_t inner = od.back().extent;
@@ -1113,6 +1120,12 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         p->block = dim3(256);
         p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
         p->lds_bytes = 0;
+    }
+    if (!p->spec_id && jit_possible(p->device)) {
+        std::string err;
+        p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, make_jit_spec(L), &err);
+        if (p->jit_fn) p->spec_id = pf::kSpecJit;
+        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
     }
     return PF_OK;
 }
@@ -1195,10 +1208,20 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
 
     // resident variant: catalogue entry, one full operand, per-channel broadcast operands only, and a grid the
     // device holds at once
-    bool resident_ok = p->spec_id != 0 && L.n_full == 1 && g.vec_per_channel;
+    const bool jit_ok = p->spec_id == 0 && jit_possible(p->device);
+    const pf::JitSpec jspec = make_jit_spec(L);
+    std::string jit_err;
+    hipFunction_t fused_fn = nullptr;
+    bool resident_ok = L.n_full == 1 && g.vec_per_channel && forced_variant != PF_VARIANT_GROUP_TWO_PASS;
+    if (resident_ok && p->spec_id == 0) {
+        // not in the catalogue: the fused kernel exists only if it can be specialised now
+        fused_fn = jit_ok ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 0, jspec, &jit_err) : nullptr;
+        if (!fused_fn) resident_ok = false;
+    }
     uint32_t res_grid = 0;
     if (resident_ok) {
-        const int per_cu = pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, nv, (int)threads);
+        const int per_cu = fused_fn ? pf::jit_blocks_per_cu(fused_fn, (int)threads)
+                                    : pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, nv, (int)threads);
         const uint64_t cap = (uint64_t)std::max(per_cu, 0) * n_cu;
         uint64_t grid = std::min<uint64_t>(tiles, cap);
         grid = grid / bps * bps;  // whole samples per round, so every wait is for co-resident workgroups
@@ -1218,12 +1241,23 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     if (variant == PF_VARIANT_GROUP_RESIDENT) {
         p->grid = dim3(res_grid);
         p->n_launches = 1;
+        if (fused_fn) {
+            p->jit_fn = fused_fn;
+            p->spec_id = pf::kSpecJit;
+        }
     } else {
         p->grid = dim3((uint32_t)tiles);
         p->grid2 = p->grid;
         p->block2 = p->block;
         p->n_launches = 2;
+        if (jit_ok) {
+            p->jit_fn = pf::jit_group_kernel(p->device, L.main_dtype, nv, 1, jspec, &jit_err);
+            p->jit_fn2 = p->jit_fn ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 2, jspec, &jit_err) : nullptr;
+            if (p->jit_fn && p->jit_fn2) p->spec_id = pf::kSpecJit;
+        }
     }
+    if (jit_ok && p->spec_id == 0 && env_int("PF_LOG", 0))
+        fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", jit_err.c_str());
     p->lds_bytes = 512 * 3 * 4 + 512 * 2 * 4 + 4;
     // workspace: partials of the two-launch variant, or two parities of exchange words (all-ones = empty) of the
     // resident one; then the error word
@@ -1384,14 +1418,14 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (plan->variant == PF_VARIANT_ROW_STREAM) {
                 if (plan->spec_id == pf::kSpecJit) {
                     void* params[] = {&a};
-                    e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+                    e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
                 } else {
                     e = pf::launch_row_stream(L.main_dtype, a, plan->ragged, plan->grid, st);
                 }
             } else if (plan->spec_id == pf::kSpecJit) {
                 pf::RowGeom g = plan->row;
                 void* params[] = {&a, &g};
-                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
             } else if (plan->spec_id) e = pf::launch_row_static(plan->spec_id, L.main_dtype, a, plan->row, plan->k, plan->grid, plan->block, st);
             else e = pf::launch_row_generic(L.main_dtype, a, plan->row, plan->k, plan->reduce_only, plan->ragged, plan->grid, plan->block, st);
             break;
@@ -1399,7 +1433,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (plan->spec_id == pf::kSpecJit) {
                 uint32_t total_vecs = plan->ew_total_vecs, vecs_per_row = plan->ew_vecs_per_row;
                 void* params[] = {&a, &total_vecs, &vecs_per_row};
-                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, params, st);
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
             } else {
                 e = pf::launch_ew(L.main_dtype, a, plan->ew_total_vecs, plan->ew_vecs_per_row, plan->k, plan->ragged, plan->grid, st);
             }
@@ -1408,7 +1442,13 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             pf::GroupGeom g = plan->group;
             g.epoch = ++plan->epoch;
             const uint32_t tiles = g.samples * g.blocks_per_sample;
-            if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
+            if (plan->spec_id == pf::kSpecJit) {
+                uint32_t t = tiles;
+                void* params[] = {&a, &g, &t};
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
+                if (e == hipSuccess && plan->variant == PF_VARIANT_GROUP_TWO_PASS)
+                    e = pf::jit_launch(plan->jit_fn2, plan->grid2, plan->block2, 0, params, st);
+            } else if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
                 e = pf::launch_group(1, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, st);
                 if (e == hipSuccess) e = pf::launch_group(2, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid2, plan->block2, st);
             } else {
@@ -1417,8 +1457,14 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             break;
         }
         case PF_FAMILY_TRANSPOSE:
-            e = pf::launch_perm(plan->spec_id, L.main_dtype, a, plan->permg, plan->variant, plan->k, plan->grid, plan->block,
-                                plan->lds_bytes, st);
+            if (plan->spec_id == pf::kSpecJit) {
+                pf::PermGeom g = plan->permg;
+                void* params[] = {&a, &g};
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, plan->variant == PF_VARIANT_T_LDS_ROWS ? plan->lds_bytes : 0u, params, st);
+            } else {
+                e = pf::launch_perm(plan->spec_id, L.main_dtype, a, plan->permg, plan->variant, plan->k, plan->grid, plan->block,
+                                    plan->lds_bytes, st);
+            }
             break;
         default: return fail(PF_ERR_INVALID_ARG, "corrupt plan");
     }

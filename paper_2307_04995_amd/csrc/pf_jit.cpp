@@ -164,8 +164,28 @@ hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const Jit
     return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
 }
 
-hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, void** params, hipStream_t st) {
-    return hipModuleLaunchKernel(fn, grid.x, grid.y, grid.z, block.x, block.y, block.z, 0, st, params, nullptr);
+hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    if (variant == 2) name << "pf::perm_tile_kernel<" << dtype << ", " << spec_text(spec) << ">";
+    else if (variant == 1) name << "pf::perm_lds_rows_kernel<" << dtype << ", " << spec_text(spec) << ">";
+    else name << "pf::perm_rows_kernel<" << dtype << ", " << k << ", " << spec_text(spec) << ">";
+    return compile(device, "#include \"pf_perm_kernels.hpp\"\n", name.str(), err);
+}
+
+hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::group_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << phase << ">";
+    return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
+}
+
+int jit_blocks_per_cu(hipFunction_t fn, int block_threads) {
+    int n = 0;
+    if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, block_threads, 0) != hipSuccess) return 0;
+    return n;
+}
+
+hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, uint32_t lds_bytes, void** params, hipStream_t st) {
+    return hipModuleLaunchKernel(fn, grid.x, grid.y, grid.z, block.x, block.y, block.z, lds_bytes, st, params, nullptr);
 }
 
 }  // namespace pf

@@ -1,0 +1,261 @@
+// Transpose family: prologue -> permutation of dimensions -> epilogue in one kernel.
+//
+// A layout change is a synchronisation step whose read and write slice patterns differ (paper section 4,
+// synchronisation gOperators).  Element-wise steps commute with it (section 5.1, gOperator swapping), so
+// the prologue runs on values addressed in the input layout, the epilogue on values addressed in the
+// output layout, and the permuted tensor itself never exists in HBM twice.
+//
+// Variants for permutations that keep the innermost dimension (every 16-byte vector moves intact):
+//   T_ROWS      each lane re-addresses its vector: one side of the transfer is contiguous per wave, the
+//               other side is contiguous in runs of the innermost extent;
+//   T_LDS_ROWS  a workgroup stages a [tile_a x tile_b] block of innermost rows in LDS between a read phase
+//               and a write phase, so both sides are walked in long contiguous runs.
+// Variant for permutations that change the innermost dimension:
+//   T_TILE      a wave owns a square tile; each lane transposes a VEC x VEC block of elements in registers.
+#pragma once
+#include "pf_row_kernels.hpp"
+
+namespace pf {
+
+struct NoStoreT {
+    template <int DT, int K, class Spec>
+    PF_DEVICE void operator()(int, const LaneState<DT, K, Spec>&) const {}
+};
+
+// Split a vector index of the iteration space into element offsets on both sides.
+PF_DEVICE void perm_offsets(const PermGeom& g, uint32_t v, uint32_t vec, uint32_t* in_off, uint32_t* out_off) {
+    uint32_t io = 0, oo = 0, rem = v;
+#pragma unroll
+    for (int q = PF_DEV_MAX_RANK - 1; q >= 0; --q) {
+        if (q < g.rank) {
+            const uint32_t quo = (q == 0) ? 0u : fast_div(rem, g.div[q]);
+            const uint32_t idx = (q == 0) ? rem : rem - quo * g.extent[q];
+            const uint32_t scale = (q == g.rank - 1) ? vec : 1u;
+            io += idx * scale * g.in_stride[q];
+            oo += idx * scale * g.out_stride[q];
+            rem = quo;
+        }
+    }
+    *in_off = io;
+    *out_off = oo;
+}
+
+// SIDES: 3 = operands of both programs, 1 = prologue operands only (input layout), 2 = epilogue operands only
+template <int DT, int K, class Spec, int SIDES = 3>
+PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneState<DT, K, Spec>& s, const uint32_t* in_off,
+                                  const uint32_t* out_off, const bool* valid) {
+    using S = Storage<DT>;
+#pragma unroll
+    for (int f = 0; f < Spec::NF; ++f) {
+        if (f < Spec::n_full(a)) {
+            const bool epi = (g.epi_full_mask >> f) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
+                if (valid[k]) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)(epi ? out_off[k] : in_off[k]) * S::ESIZE);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < Spec::NV; ++v) {
+        if (v < Spec::n_vec(a)) {
+            const bool epi = (g.epi_vec_mask >> v) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
+            const uint32_t inner = epi ? g.out_n_inner : g.in_n_inner;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
+                if (valid[k]) {
+                    const uint32_t off = epi ? out_off[k] : in_off[k];
+                    const uint32_t row = fast_div(off, epi ? g.div_out_inner : g.div_in_inner);
+                    s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, off - row * inner, inner);
+                }
+            }
+        }
+    }
+}
+
+template <int DT, int K, class Spec>
+PF_DEVICE void set_positions(LaneState<DT, K, Spec>& s, const uint32_t* off, const FastDiv& d, uint32_t inner) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        s.row[k] = fast_div(off[k], d);
+        s.col[k] = off[k] - s.row[k] * inner;
+    }
+}
+
+template <int DT, int K, class Spec>
+__global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    LaneState<DT, K, Spec> s;
+    uint32_t in_off[K], out_off[K];
+    bool valid[K];
+    const uint32_t base = blockIdx.x * (256u * K) + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t v = base + 256u * k;
+        valid[k] = v < g.total_vecs;
+        perm_offsets(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
+    }
+    perm_load_operands<DT, K, Spec>(a, g, s, in_off, out_off, valid);
+    if (a.raw_copy) {
+        // layout-only chain: the bits travel untouched (no fp32 round trip, NaN payloads survive)
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, s.fraw[0][k]);
+        return;
+    }
+    set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
+    run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+    set_positions<DT, K, Spec>(s, out_off, g.div_out_inner, g.out_n_inner);
+    run_program<DT, K, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, S::pack(s.acc + k * VEC));
+}
+
+// LDS-staged variant for permutations that keep the innermost dimension and swap two outer dims A and B
+// (input order ... A, B, inner; output order ... B, A, inner).  A workgroup owns a tile of tile_a x tile_b
+// inner rows: it reads tile_a runs of tile_b * inner contiguous elements, runs the prologue, parks the
+// fp32 -> storage converted vectors in LDS, and after one barrier writes tile_b runs of tile_a * inner
+// contiguous elements, running the epilogue on the way out.  LDS traffic is 16 bytes per lane both ways:
+// consecutive lanes fill consecutive 16-byte slots in the staging phase; in the read-out phase a group of
+// lanes reads one inner row (inner * element size contiguous bytes) and the next group the inner row one
+// staged line further.  The staged line pitch is padded so that this step advances the bank index by
+// exactly one inner row: the groups that are served together then tile the 256 bytes of bank space
+// side by side instead of landing on top of each other.
+template <int DT, class Spec>
+__global__ void __launch_bounds__(256) perm_lds_rows_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    extern __shared__ u32x4 tile[];
+    // iteration dims: [rank-3] = outer (merged batch), [rank-2]... are described by the host as:
+    //   extent[0] = batch, extent[1] = A tiles, extent[2] = B tiles; inner vectors = extent[3]
+    const uint32_t inner_v = g.extent[3];
+    const uint32_t ta = g.tile_a, tb = g.tile_b;
+    uint32_t blk = blockIdx.x;
+    const uint32_t bt = blk % g.extent[2];
+    blk /= g.extent[2];
+    const uint32_t at = blk % g.extent[1];
+    const uint32_t batch = blk / g.extent[1];
+    // element offsets of the tile origin on both sides
+    const uint32_t in_base = batch * g.in_stride[0] + at * ta * g.in_stride[1] + bt * tb * g.in_stride[2];
+    const uint32_t out_base = batch * g.out_stride[0] + at * ta * g.out_stride[1] + bt * tb * g.out_stride[2];
+    const uint32_t row_v = tb * inner_v;           // vectors per staged input run
+    const uint32_t pitch = g.lds_pitch;            // padded LDS pitch in vectors (chosen by the planner)
+    const uint32_t tile_v = ta * row_v;
+    LaneState<DT, 1, Spec> s;
+    // ---- read phase: input-contiguous
+    for (uint32_t v = threadIdx.x; v < tile_v; v += 256u) {
+        const uint32_t ai = v / row_v, r = v - ai * row_v;  // r = bi * inner_v + iv
+        const uint32_t in_off = in_base + ai * g.in_stride[1] + r * VEC;   // B and inner are contiguous in the input
+        const uint32_t bi = r / inner_v, iv = r - bi * inner_v;
+        const uint32_t out_off = out_base + bi * g.out_stride[2] + ai * g.out_stride[1] + iv * VEC;
+        const bool valid = true;
+        perm_load_operands<DT, 1, Spec>(a, g, s, &in_off, &out_off, &valid);
+        if (a.raw_copy) {
+            tile[ai * pitch + r] = s.fraw[0][0];
+            continue;
+        }
+        set_positions<DT, 1, Spec>(s, &in_off, g.div_in_inner, g.in_n_inner);
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+        set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+        tile[ai * pitch + r] = S::pack(s.acc);
+    }
+    __syncthreads();
+    // ---- write phase: output-contiguous (for each b: ta runs of inner)
+    const uint32_t orow_v = ta * inner_v;
+    for (uint32_t v = threadIdx.x; v < tile_v; v += 256u) {
+        const uint32_t bi = v / orow_v, r = v - bi * orow_v;  // r = ai * inner_v + iv
+        const uint32_t ai = r / inner_v, iv = r - ai * inner_v;
+        const uint32_t out_off = out_base + bi * g.out_stride[2] + r * VEC;  // A and inner are contiguous in the output
+        store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, tile[ai * pitch + bi * inner_v + iv]);
+    }
+}
+
+// Variant for permutations that change the innermost dimension.  Let I be the input's innermost dim and O
+// the output's.  A wave owns a square tile of 8 x 8 lanes; lane (ti, to) loads VEC vectors -- rows
+// o = to * VEC + r of the tile, columns i = ti * VEC .. + VEC - 1 -- so every load instruction of the wave
+// reads 8 runs of 8 * 16 = 128 contiguous bytes.  The lane transposes its VEC x VEC block of elements in
+// registers (byte permutes for 16-bit types, pure renaming for fp32) and stores VEC vectors -- rows
+// i = ti * VEC + c, columns o = to * VEC .. -- so every store instruction writes 8 runs of 128 contiguous
+// bytes as well.  Both sides move whole 128-byte lines and nothing passes through LDS: the exchange the
+// layout change needs fits inside one lane's registers (lane scope in the paper's terms) once the tile is
+// cut this way.  Element-wise steps run on the side whose layout their operands have; to keep a single
+// rounding, 16-bit chains may compute on one side only (the planner enforces it).
+template <int DT>
+PF_DEVICE void transpose_block(const u32x4 (&in)[Storage<DT>::VEC], u32x4 (&out)[Storage<DT>::VEC]) {
+    if (DT == DT_F32) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[c][r] = in[r][c];
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // output vector c, dword j = elements (row 2j, column c) and (row 2j + 1, column c)
+                const uint32_t lo = in[2 * j][c / 2], hi = in[2 * j + 1][c / 2];
+                out[c][j] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            }
+    }
+}
+
+template <int DT, class Spec>
+__global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const PermGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr uint32_t TE = 8u * VEC;  // tile edge in elements
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x * 4u + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (tile >= g.total_vecs) return;  // total_vecs counts tiles in this variant; wave-uniform exit
+    uint32_t in_base, out_base;
+    perm_offsets(g, tile, 1u, &in_base, &out_base);
+    const uint32_t q_o = fast_div(tile, g.div[g.rank - 1]);
+    const uint32_t ot = tile - q_o * g.extent[g.rank - 1];
+    const uint32_t it = q_o - fast_div(q_o, g.div[g.rank - 2]) * g.extent[g.rank - 2];
+    const uint32_t ti = lane & 7u, to = lane >> 3;
+    const bool valid = (it * TE + ti * VEC < g.tile_a) && (ot * TE + to * VEC < g.tile_b);
+
+    LaneState<DT, 1, Spec> s;
+    u32x4 blk[VEC], outv[VEC];
+    const bool pro_trivial = a.pro.n == 1;  // nothing but the load
+    uint32_t in_off[VEC];
+#pragma unroll
+    for (int r = 0; r < VEC; ++r) {
+        in_off[r] = in_base + (to * VEC + r) * g.t_in_stride_o + ti * VEC;
+        blk[r] = u32x4{0u, 0u, 0u, 0u};
+        if (valid) blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
+    }
+    if (!pro_trivial) {
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+            const uint32_t zero = 0u;
+            perm_load_operands<DT, 1, Spec, 1>(a, g, s, &in_off[r], &zero, &valid);
+            s.fraw[0][0] = blk[r];
+            set_positions<DT, 1, Spec>(s, &in_off[r], g.div_in_inner, g.in_n_inner);
+            run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+            blk[r] = S::pack(s.acc);
+        }
+    }
+    transpose_block<DT>(blk, outv);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        const uint32_t out_off = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
+        if (a.epi.n != 0) {
+            const uint32_t zero = 0u;
+            perm_load_operands<DT, 1, Spec, 2>(a, g, s, &zero, &out_off, &valid);
+            S::unpack(outv[c], s.acc);
+            set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
+            run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
+            outv[c] = S::pack(s.acc);
+        }
+        if (valid) store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, outv[c]);
+    }
+}
+
+}  // namespace pf

@@ -62,3 +62,45 @@ def test_elementwise_and_ragged_chains_are_specialised():
     spec.out(spec.op("softmax", 0), "f16")
     _, info, _ = check_chain(spec, [x], what="ragged softmax, specialised")
     assert info.spec_id == SPEC_JIT
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_groupnorm_relu_gets_the_fused_kernel(dtype):
+    # GroupNorm -> ReLU is not a catalogue entry: the fused (register-resident) kernel is specialised for it
+    from paper_2307_04995_amd import binding as pf
+    n, h, w, c, g = 2, 12, 12, 128, 8
+    x = wl.random_tensor((n, h, w, c), dtype, 921)
+    gamma = wl.random_tensor((c,), dtype, 922, dist="positive", scale=1.0)
+    beta = wl.random_tensor((c,), dtype, 923, scale=0.5)
+    bias = wl.random_tensor((c,), dtype, 924, scale=0.5)
+    spec = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (c,)), (dtype, (c,)), (dtype, (c,))])
+    v = spec.op("add", 0, 3)
+    v = spec.op("groupnorm", v, 1, 2, f=[1e-5], i=[g])
+    spec.out(spec.op("relu", v), dtype)
+    _, info, _ = check_chain(spec, [x, gamma, beta, bias], what="groupnorm + relu, specialised")
+    assert info.spec_id == SPEC_JIT
+    assert info.variant == pf.PF_VARIANT_GROUP_RESIDENT and info.n_launches == 1
+    _, info, _ = check_chain(spec, [x, gamma, beta, bias], variant=pf.PF_VARIANT_GROUP_TWO_PASS, what="groupnorm + relu, two launches")
+    assert info.spec_id == SPEC_JIT and info.n_launches == 2
+
+
+def test_transposes_with_unlisted_elementwise_steps():
+    from paper_2307_04995_amd import binding as pf
+    # innermost dimension kept
+    x = wl.random_tensor((2, 24, 8, 64), "f16", 931)
+    spec = wl.ChainSpec(inputs=[("f16", (2, 24, 8, 64))])
+    v = spec.op("tanh", 0)
+    v = spec.op("permute", v, i=[0, 2, 1, 3])
+    spec.out(spec.op("scale", v, f=[0.5]), "f16")
+    for variant in (pf.PF_VARIANT_T_ROWS, pf.PF_VARIANT_T_LDS_ROWS):
+        _, info, _ = check_chain(spec, [x], variant=variant, what=f"tanh -> permute -> scale, variant {variant}")
+        assert info.spec_id == SPEC_JIT and info.variant == variant
+    # innermost dimension changed
+    x = wl.random_tensor((3, 64, 128), "f32", 932)
+    b = wl.random_tensor((64,), "f32", 933)
+    spec = wl.ChainSpec(inputs=[("f32", (3, 64, 128)), ("f32", (64,))])
+    v = spec.op("relu", 0)
+    v = spec.op("permute", v, i=[0, 2, 1])
+    spec.out(spec.op("add", v, 1), "f32")
+    _, info, _ = check_chain(spec, [x, b], what="relu -> transpose -> + bias")
+    assert info.spec_id == SPEC_JIT and info.variant == pf.PF_VARIANT_T_TILE
