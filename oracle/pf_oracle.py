@@ -92,8 +92,24 @@ def _is_trailing(small: Sequence[int], big: Sequence[int]) -> bool:
 
 # ---- one function per operator ---------------------------------------------------------------
 
+def _is_row_value(small, big) -> bool:
+    """`small` is `big` with the last extent collapsed to 1: what a keep-dim reduction over the last dim gives."""
+    return len(small) == len(big) and small[-1] == 1 and big[-1] != 1 and tuple(small[:-1]) == tuple(big[:-1])
+
+
+def broadcast_rows(v: np.ndarray, n: int) -> np.ndarray:
+    """The broadcast basic operator (section 6) in the direction a reduction needs: a per-row value repeated
+    over a last dimension of extent n.  Data movement only."""
+    v = _f64(v)
+    return np.ascontiguousarray(np.repeat(v, n, axis=-1))
+
+
 def ew_binary(name: str, a: np.ndarray, b: np.ndarray) -> np.ndarray:
     a, b = _f64(a), _f64(b)
+    if _is_row_value(b.shape, a.shape):
+        b = broadcast_rows(b, a.shape[-1])
+    elif _is_row_value(a.shape, b.shape):
+        a = broadcast_rows(a, b.shape[-1])
     if a.size >= b.size:
         if not _is_trailing(b.shape, a.shape):
             raise ValueError(f"oracle: cannot broadcast {b.shape} over {a.shape}")

@@ -27,6 +27,7 @@ typedef long int64_t;
 #define PF_DEV_MAX_VEC 4
 #define PF_DEV_MAX_UOPS 24
 #define PF_DEV_MAX_TMP 2
+#define PF_DEV_MAX_ROWV 4
 #define PF_DEV_MAX_OUT 2
 #define PF_DEV_MAX_RANK 6
 
@@ -44,10 +45,14 @@ enum UopCode : uint8_t {
     U_MASK_CAUSAL, // acc = (col > row % ival) ? -inf : acc ; ival = extent of the second-to-last dim
     U_SAVE,        // tmp[slot] = acc
     U_STORE,       // write acc to output[slot] at the current position (secondary outputs)
+    U_RED_SUM,     // rowv[slot] = sum over the row of acc      (row programs: reductions inside the step list; the
+    U_RED_MAX,     // rowv[slot] = max over the row of acc       accumulator is left as it is)
+    U_RED_MEAN,    // rowv[slot] = mean over the row of acc
     U_COUNT_
 };
 
-enum OperandKind : uint8_t { K_NONE = 0, K_IMM = 1, K_FULL = 2, K_VEC = 3, K_TMP = 4 };
+// K_ROW: a per-row value (the result of a U_RED_* step), the same for every element of the row
+enum OperandKind : uint8_t { K_NONE = 0, K_IMM = 1, K_FULL = 2, K_VEC = 3, K_TMP = 4, K_ROW = 5 };
 
 struct Uop {
     uint8_t code;  // UopCode
@@ -87,7 +92,8 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MAX = 5,
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
-    CORE_PERMUTE = 8
+    CORE_PERMUTE = 8,
+    CORE_ROWPROG = 9   // no fixed core: the prologue itself holds row reductions (U_RED_*) and their broadcasts
 };
 
 // Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every

@@ -416,6 +416,7 @@ struct LaneState {
     float tmp[at_least_1(Spec::NT)][E];
     uint32_t row[K];  // row (index over all but the innermost dim) of vector k
     uint32_t col[K];  // column of the first element of vector k
+    float rowv[PF_DEV_MAX_ROWV];  // per-row values produced by U_RED_* steps (row programs)
 };
 
 // Where a broadcast operand's 16-byte vector for position (row, col) starts, in elements.
@@ -494,6 +495,11 @@ struct NoStore {
     template <int DT, int K, class Spec>
     PF_DEVICE void operator()(int, const LaneState<DT, K, Spec>&) const {}
 };
+
+// Row-reduction hook (U_RED_*): only the row kernel's hook type overloads this; everywhere else the planner
+// never emits such a step.
+template <class Hook, int DT, int K, class Spec>
+PF_DEVICE void hook_reduce(const Hook&, int, int, LaneState<DT, K, Spec>&) {}
 
 template <int DT, int K, class Spec>
 PF_DEVICE void apply_uop(int code, int slot, int32_t ival, LaneState<DT, K, Spec>& s, const float* b) {
@@ -614,12 +620,21 @@ PF_DEVICE void run_step(const ProgView<L>& pv, int i, LaneState<DT, K, Spec>& s,
                     for (int e = 0; e < E; ++e) b[e] = s.tmp[t][e];
                 }
             break;
+        case K_ROW:
+#pragma unroll
+            for (int t = 0; t < PF_DEV_MAX_ROWV; ++t)
+                if (slot == t) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) b[e] = s.rowv[t];
+                }
+            break;
         default:
 #pragma unroll
             for (int e = 0; e < E; ++e) b[e] = 0.0f;
             break;
     }
     if (code == U_STORE) store_fn(slot, s);
+    else if (code == U_RED_SUM || code == U_RED_MAX || code == U_RED_MEAN) hook_reduce(store_fn, code, slot, s);
     else apply_uop<DT, K, Spec>(code, slot, pv.ival(i), s, b);
 }
 

@@ -79,6 +79,12 @@ bool is_trailing(const Shape& small_in, const Shape& big) {
     return std::equal(small.begin(), small.end(), big.end() - small.size());
 }
 
+// `small` is `big` with the last extent collapsed to 1 (the shape a keep-dim reduction over the last dim gives)
+bool is_row_value_of(const Shape& small, const Shape& big) {
+    if (small.size() != big.size() || small.size() < 1 || small.back() != 1 || big.back() == 1) return false;
+    return std::equal(small.begin(), small.end() - 1, big.begin());
+}
+
 int dtype_size(int dt) { return dt == PF_F32 ? 4 : 2; }
 
 struct Checked {
@@ -119,6 +125,8 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
             case OC_BINARY: {
                 const Shape& b = sh[o.src[1]];
                 if (a == b) r = a;
+                else if (is_row_value_of(b, a)) r = a;  // a keep-dim reduction result broadcast back over its row
+                else if (is_row_value_of(a, b)) r = b;
                 else if (numel(a) >= numel(b) && is_trailing(b, a)) r = a;
                 else if (numel(b) > numel(a) && is_trailing(a, b)) r = b;
                 else return fail(PF_ERR_SHAPE, "op %d (%s): operand shapes do not broadcast", k, tr.name);
@@ -221,13 +229,15 @@ struct Lowerer {
     Lowered* L;
     std::vector<int> alias;      // value id -> root value id (reshape chains collapse)
     std::vector<int> uses;       // remaining uses per root value
-    enum LocKind { LOC_NONE, LOC_ACC, LOC_TMP, LOC_FULL, LOC_VEC };
+    enum LocKind { LOC_NONE, LOC_ACC, LOC_TMP, LOC_FULL, LOC_VEC, LOC_ROW };
     struct Loc {
         LocKind kind = LOC_NONE;
         int slot = -1;
     };
     std::vector<Loc> loc;
     bool tmp_busy[PF_DEV_MAX_TMP] = {false, false};
+    bool row_busy[PF_DEV_MAX_ROWV] = {false, false, false, false};
+    bool row_prog = false;       // reductions are lowered as steps of the program (CORE_ROWPROG)
     int acc_val = -1;
     pf::Program* prog = nullptr;
     bool in_epi = false;
@@ -264,6 +274,10 @@ struct Lowerer {
             return true;
         }
         const int64_t n = numel(c->shape[v]);
+        if (n != 1 && n != region_numel && c->shape[v].back() == 1 && region_inner != 1) {
+            status = fail(PF_ERR_UNSUPPORTED, "input %d: per-row values are supported as results of reductions, not as inputs", v);
+            return false;
+        }
         if (d->inputs[v].dtype != L->main_dtype) {
             status = fail(PF_ERR_DTYPE, "input %d: dtype differs from the chain's main dtype", v);
             return false;
@@ -302,6 +316,7 @@ struct Lowerer {
             case LOC_FULL: *kind = pf::K_FULL; break;
             case LOC_VEC: *kind = pf::K_VEC; break;
             case LOC_TMP: *kind = pf::K_TMP; break;
+            case LOC_ROW: *kind = pf::K_ROW; break;
             default:
                 status = fail(PF_ERR_UNSUPPORTED, "value %d is not available where it is used (crosses the core step?)", v);
                 return false;
@@ -314,6 +329,7 @@ struct Lowerer {
     bool spill_acc_if_live(int consumed_now) {
         if (acc_val < 0) return true;
         if (acc_val < d->n_inputs) return true;  // an input can always be fetched again from its operand slot
+        if (loc[acc_val].kind == LOC_ROW) return true;  // so can a row value
         if (uses[acc_val] - consumed_now <= 0) return true;
         if (loc[acc_val].kind == LOC_TMP) return true;
         for (int t = 0; t < PF_DEV_MAX_TMP; ++t)
@@ -330,8 +346,12 @@ struct Lowerer {
     }
 
     void consume(int v) {
-        if (--uses[v] == 0 && loc[v].kind == LOC_TMP) {
+        if (--uses[v] != 0) return;
+        if (loc[v].kind == LOC_TMP) {
             tmp_busy[loc[v].slot] = false;
+            loc[v].kind = LOC_NONE;
+        } else if (loc[v].kind == LOC_ROW) {
+            row_busy[loc[v].slot] = false;
             loc[v].kind = LOC_NONE;
         }
     }
@@ -358,6 +378,10 @@ struct Lowerer {
         if (v == final_value) return true;  // the kernel's last store writes it
         for (int o = 0; o < d->n_outputs; ++o) {
             if (root(d->out_value[o]) != v) continue;
+            if (numel(c->shape[v]) != region_numel) {
+                status = fail(PF_ERR_UNSUPPORTED, "output %d: only full-shape values can be secondary outputs", o);
+                return false;
+            }
             L->out_slot_to_user[1] = o;
             L->n_out = 2;
             if (!emit(pf::U_STORE, pf::K_NONE, 1)) return false;
@@ -373,8 +397,39 @@ struct Lowerer {
         const int id = d->n_inputs + k;
         const OpTraits& tr = kOps[o.op];
         if (tr.cls == OC_RESHAPE) return true;  // alias only
+        if (tr.cls == OC_REDUCE) {
+            // row program: the reduction is a step; the accumulator keeps the reduced value's source
+            const int a = root(o.src[0]);
+            if (!row_prog || numel(c->shape[o.src[0]]) != region_numel) {
+                status = fail(PF_ERR_UNSUPPORTED, "op %d (%s): reductions inside a chain reduce full-shape values over the last dimension", k, tr.name);
+                return false;
+            }
+            if (!load_acc(a)) return false;
+            int r = -1;
+            for (int t = 0; t < PF_DEV_MAX_ROWV && r < 0; ++t)
+                if (!row_busy[t]) r = t;
+            if (r < 0) {
+                status = fail(PF_ERR_UNSUPPORTED, "chain keeps more than %d per-row values alive", PF_DEV_MAX_ROWV);
+                return false;
+            }
+            row_busy[r] = true;
+            const uint8_t code = o.op == PF_REDUCE_SUM ? pf::U_RED_SUM : (o.op == PF_REDUCE_MAX ? pf::U_RED_MAX : pf::U_RED_MEAN);
+            if (!emit(code, pf::K_NONE, (uint8_t)r)) return false;
+            loc[id].kind = LOC_ROW;
+            loc[id].slot = r;
+            consume(a);  // a stays in the accumulator if something else still needs it
+            if (uses[id] == 0) {  // a reduction nobody reads
+                row_busy[r] = false;
+                loc[id].kind = LOC_NONE;
+            }
+            return true;
+        }
         if (tr.cls == OC_UNARY || tr.cls == OC_MASK) {
             const int a = root(o.src[0]);
+            if (tr.cls == OC_MASK && numel(c->shape[o.src[0]]) != region_numel) {
+                status = fail(PF_ERR_UNSUPPORTED, "op %d (causal_mask): needs a full-shape value", k);
+                return false;
+            }
             if (!load_acc(a)) return false;
             if (!spill_acc_if_live(1)) return false;
             consume(a);
@@ -440,8 +495,9 @@ struct Lowerer {
             else if (acc_val == b) { in_acc = b; other = a; reversed = true; }
             else {
                 // prefer loading a computed / full-shape value into the accumulator
-                const bool a_small = a < d->n_inputs && numel(c->shape[a]) != region_numel;
-                if (a_small && !(b < d->n_inputs && numel(c->shape[b]) != region_numel)) { in_acc = b; other = a; reversed = true; }
+                const bool a_small = (a < d->n_inputs && numel(c->shape[a]) != region_numel) || loc[a].kind == LOC_ROW;
+                const bool b_small = (b < d->n_inputs && numel(c->shape[b]) != region_numel) || loc[b].kind == LOC_ROW;
+                if (a_small && !b_small) { in_acc = b; other = a; reversed = true; }
                 else { in_acc = a; other = b; reversed = false; }
                 if (!load_acc(in_acc)) return false;
             }
@@ -464,9 +520,20 @@ struct Lowerer {
 
 pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     const int n_in = d->n_inputs, n_val = d->n_inputs + d->n_ops;
+    // Row program: a chain written in basic operators only (element-wise, reduce over the last dimension,
+    // broadcast of the reduced value back over its row; paper section 6) whose result has the full shape.
+    // The reduce -> broadcast pairs need a synchronisation no wider than a row (section 5.1), so they become
+    // steps of one register-resident program instead of a kernel boundary.
+    int n_reduce = 0, n_other_core = 0;
+    for (int k = 0; k < d->n_ops; ++k) {
+        const OpClass cls = kOps[d->ops[k].op].cls;
+        if (cls == OC_REDUCE) ++n_reduce;
+        else if (!is_elementwise(cls) && cls != OC_RESHAPE) ++n_other_core;
+    }
+    const bool row_prog = n_reduce >= 1 && n_other_core == 0 && c.shape[n_in + d->n_ops - 1].back() != 1;
     // the core: first operator that is neither element-wise nor a reshape
     L->core_op = -1;
-    for (int k = 0; k < d->n_ops; ++k) {
+    for (int k = 0; k < d->n_ops && !row_prog; ++k) {
         const OpClass cls = kOps[d->ops[k].op].cls;
         if (!is_elementwise(cls) && cls != OC_RESHAPE) {
             if (L->core_op >= 0)
@@ -478,6 +545,7 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     lw.d = d;
     lw.c = &c;
     lw.L = L;
+    lw.row_prog = row_prog;
     lw.alias.resize(n_val);
     for (int v = 0; v < n_val; ++v) lw.alias[v] = v;
     for (int k = 0; k < d->n_ops; ++k)
@@ -521,6 +589,12 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     L->pre_shape = c.shape[pre_value];
     L->post_shape = core_k >= 0 ? c.shape[n_in + core_k] : L->pre_shape;
 
+    if (row_prog) {
+        L->core = pf::CORE_ROWPROG;
+        for (int k = 0; k < d->n_ops; ++k)
+            if (kOps[d->ops[k].op].cls == OC_RESHAPE)
+                return fail(PF_ERR_UNSUPPORTED, "reshapes inside a chain with in-line reductions are not implemented");
+    }
     if (core_k >= 0) {
         const pf_op_desc& o = d->ops[core_k];
         switch (o.op) {
@@ -590,7 +664,7 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     L->mask_si = 0;
     L->core_mask = 0;
     L->core_scale = 1.0f;
-    if (L->core == pf::CORE_SOFTMAX) {
+    if (L->core == pf::CORE_SOFTMAX || L->core == pf::CORE_ROWPROG) {
         int mask_at = -1;
         for (int i = 0; i < L->pro.n; ++i)
             if (L->pro.u[i].code == pf::U_MASK_CAUSAL) mask_at = i;
@@ -605,12 +679,12 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
             if (ok) L->mask_si = (uint32_t)L->pro.u[mask_at].ival;
         }
         // a mask that is the last prologue step moves into the softmax core ...
-        if (L->mask_si != 0 && mask_at == L->pro.n - 1) {
+        if (L->core == pf::CORE_SOFTMAX && L->mask_si != 0 && mask_at == L->pro.n - 1) {
             L->core_mask = 1;
             L->pro.n -= 1;
         }
         // ... and so does a positive scale right before it: softmax(c * x) = exp(c * (x - max x)) / sum for c > 0
-        if (L->pro.n >= 2 && (L->core_mask || mask_at < 0)) {
+        if (L->core == pf::CORE_SOFTMAX && L->pro.n >= 2 && (L->core_mask || mask_at < 0)) {
             const pf::Uop& u = L->pro.u[L->pro.n - 1];
             if (u.code == pf::U_MUL && u.kind == pf::K_IMM && u.imm > 0.0f && std::isfinite(u.imm)) {
                 L->core_scale = u.imm;
@@ -823,6 +897,8 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     p->family = PF_FAMILY_ROW;
     p->args.n_inner = (uint32_t)n;
     p->args.rows = (uint64_t)rows;
+    if (best_score < 0 && L.core == pf::CORE_ROWPROG)
+        return fail(PF_ERR_UNSUPPORTED, "chains with in-line reductions need rows that fit one workgroup's registers (row length %lld)", (long long)n);
     if (best_score < 0) {
         // Rows longer than a workgroup keeps in registers (or on request): the streaming variant, a workgroup
         // per row, two walks over the row.
@@ -854,7 +930,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     // Rows per wave: a wave that owns short rows takes several at once, so that it has about 4 KB of loads
     // in flight (what it takes to cover the HBM latency at full occupancy), as long as enough waves remain
     // (16 per SIMD) to fill the device evenly and a specialised kernel exists for the combination.
-    if (best_wpr == 1 && (matched || jit_ok) && L.n_out == 1) {
+    if (best_wpr == 1 && (matched || jit_ok) && L.n_out == 1 && L.core != pf::CORE_ROWPROG) {
         const int64_t bytes_per_row_in_flight = (int64_t)L.n_full * best_k * 1024;
         int rpw = 1;
         while (rpw < 4 && bytes_per_row_in_flight * rpw < 4096 && best_k * rpw * 2 <= 4 && rows / (rpw * 2) >= 16384) rpw *= 2;

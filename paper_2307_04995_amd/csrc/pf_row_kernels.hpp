@@ -69,6 +69,67 @@ PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, ui
     return r;
 }
 
+// What the interpreter calls back into from inside the row kernel: secondary-output stores, and the row
+// reductions of a row program (one row per wave or workgroup).  A reduction leaves the accumulator as it is
+// and puts the row's value, the same in every lane, into rowv[slot].  Successive reductions alternate between
+// the two LDS staging areas; one barrier per reduction separates their reuse.
+template <bool RAGGED>
+struct RowHooks {
+    RowStore<RAGGED> store;
+    uint32_t wpr, wave, lane, limit;
+    float inv_n;
+    float (*red)[16];
+    uint32_t* flip;
+    template <int DT, int K, class Spec>
+    PF_DEVICE void operator()(int slot, const LaneState<DT, K, Spec>& st) const {
+        store(slot, st);
+    }
+};
+
+template <bool RAGGED, int DT, int K, class Spec>
+PF_DEVICE void hook_reduce(const RowHooks<RAGGED>& h, int code, int slot, LaneState<DT, K, Spec>& s) {
+    constexpr int VEC = Storage<DT>::VEC;
+    float* stage = h.red[*h.flip & 1u];
+    *h.flip += 1u;
+    float r;
+    if (code == U_RED_MAX) {
+        float m = -__builtin_inff(), nan_seen = 0.0f;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const bool valid = RAGGED ? s.col[k] + (uint32_t)e < h.limit : s.col[k] < h.limit;
+                const float x = s.acc[k * VEC + e];
+                m = valid ? fmaxf(m, x) : m;
+                nan_seen = (valid && x != x) ? 1.0f : nan_seen;
+            }
+        // a NaN anywhere in the row makes the row's maximum NaN
+        if (h.wpr == 1u) {
+            // the wave reduction runs on order-preserving integer keys in which a positive NaN ranks above +inf
+            r = wave_allreduce<OpMax>(nan_seen > 0.0f ? __builtin_nanf("") : m);
+        } else {
+            m = row_allreduce<OpMax>(m, h.wpr, h.wave, h.lane, stage);
+            nan_seen = row_allreduce<OpMax>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
+            *h.flip += 1u;
+            r = nan_seen > 0.0f ? __builtin_nanf("") : m;
+        }
+    } else {
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const bool valid = RAGGED ? s.col[k] + (uint32_t)e < h.limit : s.col[k] < h.limit;
+                sum += valid ? s.acc[k * VEC + e] : 0.0f;
+            }
+        r = row_allreduce<OpSum>(sum, h.wpr, h.wave, h.lane, stage);
+        if (code == U_RED_MEAN) r *= h.inv_n;
+    }
+#pragma unroll
+    for (int t = 0; t < PF_DEV_MAX_ROWV; ++t)
+        if (slot == t) s.rowv[t] = r;
+}
+
 // Issue the loads of every operand of a row tile before anything is used.  `row_byte` is wave-uniform,
 // so each load is a scalar base plus a 32-bit lane offset.  Vectors that are not loaded read as `fill`.
 // The KC vectors starting at k0 belong to the row at `row_byte`.
@@ -159,13 +220,15 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
         load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
     }
 
-    // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
-    const RowStore<RAGGED> store_fn{a.out[0], a.out[1], row_byte[0], limit[0]};
+    // secondary outputs (U_STORE) and row programs (U_RED_*) are supported for one row per wave only; the
+    // planner enforces it
+    const float inv_n = 1.0f / (float)n;
+    uint32_t flip = 0;
+    const RowHooks<RAGGED> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit[0], inv_n, red, &flip};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
     // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
     const bool exact = n == 64u * wpr * (uint32_t)EC;
-    const float inv_n = 1.0f / (float)n;
     const int core = Spec::core(a);
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {

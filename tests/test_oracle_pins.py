@@ -382,3 +382,68 @@ def test_thread_count_does_not_change_results():
     (b,) = orc.evaluate_outputs(spec, wide)
     orc.set_threads(orc.max_threads())
     np.testing.assert_array_equal(a, b)
+
+
+# ---- broadcast of a reduced value back over its row (chains written in basic operators, section 6) ----
+
+def test_row_broadcast_direction_and_values():
+    x = np.array([[1.0, 2.0, 4.0], [8.0, 16.0, 32.0]])
+    v = np.array([[2.0], [4.0]])
+    # worked by hand: the row value meets every element of its own row, operand order kept
+    np.testing.assert_array_equal(orc.ew_binary("sub", x, v), [[-1.0, 0.0, 2.0], [4.0, 12.0, 28.0]])
+    np.testing.assert_array_equal(orc.ew_binary("sub", v, x), [[1.0, 0.0, -2.0], [-4.0, -12.0, -28.0]])
+    np.testing.assert_array_equal(orc.ew_binary("div", x, v), [[0.5, 1.0, 2.0], [2.0, 4.0, 8.0]])
+    np.testing.assert_array_equal(orc.ew_binary("div", v, x), [[2.0, 1.0, 0.5], [0.5, 0.25, 0.125]])
+    np.testing.assert_array_equal(orc.ew_binary("max", x, v), [[2.0, 2.0, 4.0], [8.0, 16.0, 32.0]])
+    # higher rank: one value per row of the last dimension
+    x3 = np.arange(12, dtype=np.float64).reshape(2, 2, 3)
+    v3 = np.array([[[1.0], [10.0]], [[100.0], [1000.0]]])
+    want = x3 + np.array([1.0, 10.0, 100.0, 1000.0]).reshape(2, 2, 1)
+    np.testing.assert_array_equal(orc.ew_binary("add", x3, v3), want)
+    # not a row value: different leading extents
+    with pytest.raises(ValueError):
+        orc.ew_binary("add", x, np.ones((3, 1)))
+
+
+def _softmax_in_basic_operators(shape):
+    s = wl.ChainSpec(inputs=[("f32", shape)])
+    m = s.op("reduce_max", 0)
+    d = s.op("sub", 0, m)
+    e = s.op("exp", d)
+    t = s.op("reduce_sum", e)
+    s.out(s.op("div", e, t), "f32")
+    return s
+
+
+def test_softmax_written_in_basic_operators():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 33)) * 3.0
+    y = orc.evaluate_outputs(_softmax_in_basic_operators((7, 33)), [x])[0]
+    # the composite is defined as exactly these steps
+    np.testing.assert_array_equal(y, orc.softmax(x))
+    # closed form: softmax of logarithms of positive weights is the weights normalised
+    w = rng.uniform(0.5, 2.0, (4, 9))
+    y = orc.evaluate_outputs(_softmax_in_basic_operators((4, 9)), [np.log(w)])[0]
+    np.testing.assert_allclose(y, w / w.sum(-1, keepdims=True), rtol=1e-14)
+
+
+def test_layernorm_written_in_basic_operators():
+    rng = np.random.default_rng(6)
+    rows, n, eps = 5, 40, 1e-5
+    x = rng.standard_normal((rows, n)) * 2.0 + 1.5
+    g = rng.standard_normal(n)
+    b = rng.standard_normal(n)
+    s = wl.ChainSpec(inputs=[("f32", (rows, n)), ("f32", (n,)), ("f32", (n,))])
+    mu = s.op("reduce_mean", 0)
+    c = s.op("sub", 0, mu)
+    var = s.op("reduce_mean", s.op("mul", c, c))
+    r = s.op("rsqrt", s.op("addc", var, f=[eps]))
+    y = s.op("mul", c, r)
+    y = s.op("add", s.op("mul", y, 1), 2)
+    s.out(y, "f32")
+    got = orc.evaluate_outputs(s, [x, g, b])[0]
+    np.testing.assert_allclose(got, orc.layernorm(x, g, b, eps), rtol=1e-13, atol=1e-14)
+    # textbook definition, written independently
+    mean = x.mean(-1, keepdims=True)
+    want = (x - mean) / np.sqrt(((x - mean) ** 2).mean(-1, keepdims=True) + eps) * g + b
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-14)
