@@ -195,6 +195,52 @@ int orc_row_broadcast_binary(int op, const double *x, int64_t rows, int64_t n, c
 }
 
 /*
+ * The three operators of an attention layer that generates one token against cached keys and values
+ * (paper section 8, the GPT-2 case study): with a sequence length of one, both matrix products of the
+ * layer are matrix-vector products, and the cache grows by one row through a concatenation.
+ *
+ * concat_rows: y[o, 0..t-1, :] = x[o, :, :]; y[o, t, :] = r[o, :]     (x: [outer, t, d], r: [outer, d])
+ */
+int orc_concat_rows(const double *x, int64_t outer, int64_t t, int64_t d, const double *r, double *out)
+{
+    if (outer <= 0 || t < 0 || d <= 0) return ORC_BAD_ARG;
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t j = 0; j < t; ++j)
+            for (int64_t c = 0; c < d; ++c) out[(o * (t + 1) + j) * d + c] = x[(o * t + j) * d + c];
+        for (int64_t c = 0; c < d; ++c) out[(o * (t + 1) + t) * d + c] = r[o * d + c];
+    }
+    return ORC_OK;
+}
+
+/* matvec: y[o, j] = sum_c a[o, j, c] * x[o, c]      (a: [outer, t, d], x: [outer, d]) -- contracts the last axis */
+int orc_matvec(const double *a, int64_t outer, int64_t t, int64_t d, const double *x, double *out)
+{
+    if (outer <= 0 || t <= 0 || d <= 0) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o)
+        for (int64_t j = 0; j < t; ++j) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < d; ++c) acc += a[(o * t + j) * d + c] * x[o * d + c];
+            out[o * t + j] = acc;
+        }
+    return ORC_OK;
+}
+
+/* vecmat: y[o, c] = sum_j p[o, j] * a[o, j, c]      (p: [outer, t], a: [outer, t, d]) -- contracts the row axis */
+int orc_vecmat(const double *p, int64_t outer, int64_t t, int64_t d, const double *a, double *out)
+{
+    if (outer <= 0 || t <= 0 || d <= 0) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o)
+        for (int64_t c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < t; ++j) acc += p[o * t + j] * a[(o * t + j) * d + c];
+            out[o * d + c] = acc;
+        }
+    return ORC_OK;
+}
+
+/*
  * Softmax over the last dimension, as the sequence of basic operators it consists of:
  *   m = reduce-max(x); d = x - m; e = exp(d); s = reduce-sum(e); y = e / s.
  * exp(-inf) = 0, so masked positions come out as exactly 0; a row that is -inf everywhere gives

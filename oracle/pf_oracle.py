@@ -53,6 +53,9 @@ def _load():
         lib.orc_reduce_last.argtypes = [ctypes.c_int, dp, i64, i64, dp]
         lib.orc_row_broadcast_binary.argtypes = [ctypes.c_int, dp, i64, i64, dp, dp]
         lib.orc_softmax_last.argtypes = [dp, i64, i64, dp]
+        lib.orc_concat_rows.argtypes = [dp, i64, i64, i64, dp, dp]
+        lib.orc_matvec.argtypes = [dp, i64, i64, i64, dp, dp]
+        lib.orc_vecmat.argtypes = [dp, i64, i64, i64, dp, dp]
         lib.orc_layernorm_last.argtypes = [dp, i64, i64, dp, dp, ctypes.c_double, dp]
         lib.orc_rmsnorm_last.argtypes = [dp, i64, i64, dp, ctypes.c_double, dp]
         lib.orc_groupnorm_nhwc.argtypes = [dp, i64, i64, i64, i64, dp, dp, ctypes.c_double, dp]
@@ -155,6 +158,41 @@ def reduce_last(name: str, x: np.ndarray) -> np.ndarray:
     return out
 
 
+def concat_rows(x: np.ndarray, r: np.ndarray) -> np.ndarray:
+    """x [..., t, d] with one more row r [..., d] appended along the second-to-last axis (the cache
+    concatenation of an attention layer that generates one token: section 8, GPT-2 case study)."""
+    x, r = _f64(x), _f64(r)
+    if x.ndim < 2 or tuple(r.shape) != tuple(x.shape[:-2]) + (x.shape[-1],):
+        raise ValueError(f"oracle: concat_rows shapes {x.shape} and {r.shape}")
+    t, d = x.shape[-2], x.shape[-1]
+    outer = x.size // (t * d)
+    out = np.empty(x.shape[:-2] + (t + 1, d), dtype=np.float64)
+    _check(_load().orc_concat_rows(_p(x), outer, t, d, _p(r), _p(out)), "concat_rows")
+    return out
+
+
+def matvec(a: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """y[..., j] = sum_c a[..., j, c] * x[..., c]."""
+    a, x = _f64(a), _f64(x)
+    if a.ndim < 2 or tuple(x.shape) != tuple(a.shape[:-2]) + (a.shape[-1],):
+        raise ValueError(f"oracle: matvec shapes {a.shape} and {x.shape}")
+    t, d = a.shape[-2], a.shape[-1]
+    out = np.empty(a.shape[:-1], dtype=np.float64)
+    _check(_load().orc_matvec(_p(a), a.size // (t * d), t, d, _p(x), _p(out)), "matvec")
+    return out
+
+
+def vecmat(p: np.ndarray, a: np.ndarray) -> np.ndarray:
+    """y[..., c] = sum_j p[..., j] * a[..., j, c]."""
+    p, a = _f64(p), _f64(a)
+    if a.ndim < 2 or tuple(p.shape) != tuple(a.shape[:-1]):
+        raise ValueError(f"oracle: vecmat shapes {p.shape} and {a.shape}")
+    t, d = a.shape[-2], a.shape[-1]
+    out = np.empty(a.shape[:-2] + (d,), dtype=np.float64)
+    _check(_load().orc_vecmat(_p(p), a.size // (t * d), t, d, _p(a), _p(out)), "vecmat")
+    return out
+
+
 def softmax(x: np.ndarray) -> np.ndarray:
     x = _f64(x)
     n = x.shape[-1]
@@ -245,6 +283,12 @@ def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
         return reduce_last(name, a[0])
     if name == "softmax":
         return softmax(a[0])
+    if name == "concat_rows":
+        return concat_rows(a[0], a[1])
+    if name == "matvec":
+        return matvec(a[0], a[1])
+    if name == "vecmat":
+        return vecmat(a[0], a[1])
     if name == "layernorm":
         return layernorm(a[0], a[1], a[2], op.f[0])
     if name == "rmsnorm":

@@ -447,3 +447,60 @@ def test_layernorm_written_in_basic_operators():
     mean = x.mean(-1, keepdims=True)
     want = (x - mean) / np.sqrt(((x - mean) ** 2).mean(-1, keepdims=True) + eps) * g + b
     np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-14)
+
+
+# ---- one-token attention against cached keys and values (section 8, GPT-2 case study) ----
+
+def test_concat_matvec_vecmat_worked_by_hand():
+    # t = 2 cached rows, d = 3: rows and columns deliberately of different extent so that a transposed operand
+    # or a contraction over the wrong axis cannot give the same numbers
+    K = np.array([[[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]]])          # [1, 2, 3]
+    k = np.array([[7.0, 8.0, 9.0]])                               # [1, 3]
+    Kc = orc.concat_rows(K, k)
+    np.testing.assert_array_equal(Kc, [[[1.0, 2.0, 3.0], [4.0, 5.0, 6.0], [7.0, 8.0, 9.0]]])
+    q = np.array([[1.0, 0.0, -1.0]])
+    np.testing.assert_array_equal(orc.matvec(Kc, q), [[-2.0, -2.0, -2.0]])          # row . q
+    q = np.array([[1.0, 10.0, 100.0]])
+    np.testing.assert_array_equal(orc.matvec(Kc, q), [[321.0, 654.0, 987.0]])
+    p = np.array([[1.0, 10.0, 100.0]])
+    np.testing.assert_array_equal(orc.vecmat(p, Kc), [[741.0, 852.0, 963.0]])       # sum_j p_j row_j
+    # several heads stay apart
+    A = np.stack([np.eye(3), 2.0 * np.eye(3)])[None]               # [1, 2, 3, 3]
+    x = np.array([[[1.0, 2.0, 3.0], [1.0, 2.0, 3.0]]])
+    np.testing.assert_array_equal(orc.matvec(A, x), [[[1.0, 2.0, 3.0], [2.0, 4.0, 6.0]]])
+    np.testing.assert_array_equal(orc.vecmat(x, A), [[[1.0, 2.0, 3.0], [2.0, 4.0, 6.0]]])
+    with pytest.raises(ValueError):
+        orc.matvec(Kc, np.ones((1, 2)))
+    with pytest.raises(ValueError):
+        orc.vecmat(np.ones((1, 2)), Kc)
+
+
+def test_matvec_vecmat_against_library_contractions_and_linearity():
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((2, 3, 17, 5))
+    x = rng.standard_normal((2, 3, 5))
+    p = rng.standard_normal((2, 3, 17))
+    np.testing.assert_allclose(orc.matvec(A, x), np.einsum("bhtd,bhd->bht", A, x), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(orc.vecmat(p, A), np.einsum("bht,bhtd->bhd", p, A), rtol=1e-13, atol=1e-13)
+    # adjointness: <A x, p> = <x, p A>
+    lhs = (orc.matvec(A, x) * p).sum()
+    rhs = (x * orc.vecmat(p, A)).sum()
+    assert abs(lhs - rhs) < 1e-11
+
+
+def test_one_token_attention_chain_equals_its_definition():
+    spec, ins = wl.x2_decode_attention(b=2, h=3, t=13, d=8, dtype="f32", cache_outputs=True)
+    q, k, v, K, V = [wl.widen(t) for t in ins]
+    o, Kc, Vc = orc.evaluate_outputs(spec, [q, k, v, K, V])
+    Kd = np.concatenate([K, k[:, :, None, :]], axis=2)
+    Vd = np.concatenate([V, v[:, :, None, :]], axis=2)
+    np.testing.assert_array_equal(Kc, Kd)
+    np.testing.assert_array_equal(Vc, Vd)
+    s = np.einsum("bhtd,bhd->bht", Kd, q) / np.sqrt(8.0)
+    w = np.exp(s - s.max(-1, keepdims=True))
+    w /= w.sum(-1, keepdims=True)
+    np.testing.assert_allclose(o, np.einsum("bht,bhtd->bhd", w, Vd), rtol=1e-12, atol=1e-13)
+    # a constant value cache returns that constant whatever the keys are (weights sum to one)
+    Vconst = np.full_like(V, 0.75)
+    o2 = orc.evaluate_outputs(spec, [q, k, np.full_like(v, 0.75), K, Vconst])[0]
+    np.testing.assert_allclose(o2, 0.75, rtol=1e-14)

@@ -29,6 +29,8 @@ OP_ARITY: Dict[str, int] = {
     "reduce_sum": 1, "reduce_max": 1, "reduce_mean": 1,
     "softmax": 1, "layernorm": 3, "rmsnorm": 2, "groupnorm": 3,
     "permute": 1, "reshape": 1,
+    # one-token attention against cached keys / values: append a row, matrix-vector, vector-matrix
+    "concat_rows": 2, "matvec": 2, "vecmat": 2,
 }
 
 
@@ -182,6 +184,31 @@ def x1_bias_scale_transpose(b: int = 32, s: int = 512, d: int = 1024, dtype: str
     return c, [quantise(k, dtype), quantise(bias, dtype)]
 
 
+def x2_decode_attention(b: int = 8, h: int = 25, t: int = 1023, d: int = 64, dtype: str = "f16",
+                        cache_outputs: bool = False, salt: int = 0):
+    """Attention of one new token against t cached keys and values per head (not a BASELINE config; the
+    paper's GPT-2 case study with a key-value cache): K' = concat(K, k), V' = concat(V, v),
+    o = softmax(K' q / sqrt(d)) V'.  q, k, v [b, h, d]; K, V [b, h, t, d]; o [b, h, d]."""
+    g = _rng(7, salt)
+    q = g.standard_normal((b, h, d), dtype=np.float32)
+    k = g.standard_normal((b, h, d), dtype=np.float32)
+    v = g.standard_normal((b, h, d), dtype=np.float32)
+    kc = g.standard_normal((b, h, t, d), dtype=np.float32)
+    vc = g.standard_normal((b, h, t, d), dtype=np.float32)
+    c = ChainSpec(inputs=[(dtype, (b, h, d)), (dtype, (b, h, d)), (dtype, (b, h, d)), (dtype, (b, h, t, d)), (dtype, (b, h, t, d))])
+    k_all = c.op("concat_rows", 3, 1)
+    s = c.op("matvec", k_all, 0)
+    s = c.op("scale", s, f=[1.0 / float(np.sqrt(d))])
+    p = c.op("softmax", s)
+    v_all = c.op("concat_rows", 4, 2)
+    o = c.op("vecmat", p, v_all)
+    c.out(o, dtype)
+    if cache_outputs:
+        c.out(k_all, dtype)
+        c.out(v_all, dtype)
+    return c, [quantise(x, dtype) for x in (q, k, v, kc, vc)]
+
+
 CONFIGS = {
     "C1": c1_bias_res_layernorm_gelu,
     "C2": c2_causal_softmax,
@@ -189,6 +216,7 @@ CONFIGS = {
     "C4": c4_bias_scale_permute,
     "C5": c5_groupnorm_silu,
     "X1": x1_bias_scale_transpose,      # not a BASELINE config: the innermost-changing transpose, for context
+    "X2": x2_decode_attention,          # not a BASELINE config: one-token attention against a key-value cache
 }
 
 
