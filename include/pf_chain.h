@@ -26,7 +26,7 @@ extern "C" {
 #define PF_MAX_RANK 6
 #define PF_MAX_INPUTS 8
 #define PF_MAX_OPS 32
-#define PF_MAX_OUTPUTS 2
+#define PF_MAX_OUTPUTS 3
 
 typedef enum {
     PF_OK = 0,
@@ -79,7 +79,13 @@ typedef enum {
     PF_PERMUTE = 24,    /* i[0..rank-1] = perm; output dim k is input dim perm[k]                           */
     PF_RESHAPE = 25,    /* i[0..n_i-1] = new shape with the same element count; contiguous data is
                            reinterpreted, nothing moves                                                     */
-    PF_OP_COUNT_ = 26
+    /* one-token attention against cached keys and values (section 8, GPT-2 case study).  These three are
+       accepted only in the arrangement  o = VECMAT(SOFTMAX([SCALE](MATVEC(K', q))), V')  with K' and V' either
+       chain inputs or CONCAT_ROWS(cache, new row); outputs: o, and optionally K' and V'.                    */
+    PF_CONCAT_ROWS = 26,/* src0 [..., t, d], src1 [..., d] -> [..., t+1, d]: src1 appended as the last row  */
+    PF_MATVEC = 27,     /* src0 [..., t, d], src1 [..., d] -> [..., t]:   y_j = sum_c a_jc x_c              */
+    PF_VECMAT = 28,     /* src0 [..., t],    src1 [..., t, d] -> [..., d]: y_c = sum_j p_j a_jc              */
+    PF_OP_COUNT_ = 29
 } pf_op;
 
 /* A contiguous row-major tensor. */
@@ -123,7 +129,9 @@ typedef enum {
     PF_FAMILY_ELEMENTWISE = 0, /* lane scope only: values never leave their register                        */
     PF_FAMILY_ROW = 1,         /* row reduction then broadcast: wave shuffle, LDS when a row spans waves     */
     PF_FAMILY_GROUP = 2,       /* GroupNorm: a group spans workgroups, partial statistics cross the device   */
-    PF_FAMILY_TRANSPOSE = 3    /* layout change staged through an LDS tile                                   */
+    PF_FAMILY_TRANSPOSE = 3,   /* layout change staged through an LDS tile                                   */
+    PF_FAMILY_ATTENTION = 4    /* one-token attention: a head's rows span workgroups, partial results are
+                                  merged by the last workgroup to arrive                                     */
 } pf_family;
 
 typedef struct {

@@ -1,0 +1,206 @@
+// Attention family: one new token against cached keys and values, as ONE memory-bound kernel.
+//
+//   K' = concat(K, k),  V' = concat(V, v),  s = K' q * scale,  p = softmax(s),  o = p V'
+//
+// With a sequence length of one both matrix products of the attention layer are matrix-vector products,
+// bound by reading the cache once (paper section 8, the GPT-2 case study).  The two products have the same
+// shape but are laid out differently here, as in the paper's best plan: the first contracts the contiguous
+// head dimension, so the lanes that share a cache row combine their partial dot products by lane
+// permutations; the second contracts the row dimension, so every lane accumulates its own columns over the
+// rows it has seen and the row groups are combined once at the end.  Keys and values are loaded once, as
+// 16-byte vectors, all loads of a workgroup's slice in flight before the first use; scores and probabilities
+// never leave registers; the concatenations cost nothing unless the grown caches are asked for as outputs.
+//
+// A head's rows are split over several workgroups (a head alone would leave most of the device idle).
+// Each split produces a partial result in the usual mergeable form (maximum, sum of exponentials, weighted
+// value sum); the workgroup whose arrival completes the head's counter merges them -- a device-scope
+// synchronisation (section 5.1) in which nobody waits: every workgroup but the last simply ends.
+#include "pf_device.hpp"
+#include "pf_launch.h"
+
+namespace pf {
+
+PF_DEVICE float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+template <int DT, int NV>
+__global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr bool PR = S::PRECISE;
+    __shared__ float lds_m[4], lds_l[4];
+    __shared__ float lds_o[4][256];  // per-wave partial output, head dimension <= 256
+    __shared__ uint32_t s_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lpr = a.lanes_per_row;            // lanes that share one cache row (power of two, <= 64)
+    const uint32_t in_row = tid & (lpr - 1u);        // which 16-byte piece of the row
+    const uint32_t row_in_step = tid >> a.log2_lpr;  // which row of a step of 256 / lpr rows
+    const uint32_t rps = 256u >> a.log2_lpr;
+    const uint32_t head = blockIdx.y, split = blockIdx.x;
+    const uint32_t row0 = split * (uint32_t)NV * rps;
+    const uint32_t d = a.d, t = a.t, t_total = a.t_total;
+
+    const uint64_t head_vec = (uint64_t)head * d + in_row * VEC;  // element offset inside q / k / v / o
+    float qf[VEC];
+    S::unpack(load_cached(a.q, head_vec * S::ESIZE), qf);
+
+    // ---- every key and value vector of this slice, loaded before anything is used
+    u32x4 kraw[NV], vraw[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const uint32_t row = row0 + (uint32_t)i * rps + row_in_step;
+        kraw[i] = u32x4{0u, 0u, 0u, 0u};
+        vraw[i] = u32x4{0u, 0u, 0u, 0u};
+        if (row < t) {
+            const uint64_t off = (((uint64_t)head * t + row) * d + in_row * VEC) * S::ESIZE;
+            kraw[i] = load_stream(a.k_cache, off);
+            vraw[i] = load_stream(a.v_cache, off);
+        } else if (row < t_total) {  // the appended row
+            kraw[i] = load_cached(a.k_new, head_vec * S::ESIZE);
+            vraw[i] = load_cached(a.v_new, head_vec * S::ESIZE);
+        }
+    }
+    // the grown caches, if they are outputs
+    if (a.k_out != nullptr || a.v_out != nullptr) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t row = row0 + (uint32_t)i * rps + row_in_step;
+            if (row < t_total) {
+                const uint64_t off = (((uint64_t)head * t_total + row) * d + in_row * VEC) * S::ESIZE;
+                if (a.k_out != nullptr) store_stream(a.k_out, off, kraw[i]);
+                if (a.v_out != nullptr) store_stream(a.v_out, off, vraw[i]);
+            }
+        }
+    }
+
+    // ---- first product: contract the head dimension (lanes of a row combine by lane permutations)
+    float sc[NV];
+    float m = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const uint32_t row = row0 + (uint32_t)i * rps + row_in_step;
+        float kf[VEC];
+        S::unpack(kraw[i], kf);
+        float dot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dot = __builtin_fmaf(kf[e], qf[e], dot);
+        for (uint32_t msk = 1; msk < lpr; msk <<= 1) dot += shfl_xor_f(dot, (int)msk);
+        sc[i] = row < t_total ? dot * a.scale : -__builtin_inff();
+        m = fmaxf(m, sc[i]);
+    }
+    // the slice's maximum: over the row groups of the wave, then over the four waves
+    for (uint32_t msk = lpr; msk < 64u; msk <<= 1) m = fmaxf(m, shfl_xor_f(m, (int)msk));
+    if (lane == 0) lds_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(lds_m[0], lds_m[1]), fmaxf(lds_m[2], lds_m[3]));
+
+    // ---- softmax numerators and the second product: contract the row dimension (per-lane accumulation)
+    float l = 0.0f;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        // exp(-inf - m) = 0 for rows past the end; m is finite because every slice holds at least one row
+        const float p = PR ? expf(sc[i] - m) : __builtin_amdgcn_exp2f((sc[i] - m) * kLog2e);
+        l += p;
+        float vf[VEC];
+        S::unpack(vraw[i], vf);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(p, vf[e], acc[e]);
+    }
+    for (uint32_t msk = lpr; msk < 64u; msk <<= 1) {
+        l += shfl_xor_f(l, (int)msk);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += shfl_xor_f(acc[e], (int)msk);
+    }
+    if (lane == 0) lds_l[wave] = l;
+    if (lane < lpr) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) lds_o[wave][in_row * VEC + e] = acc[e];
+    }
+    __syncthreads();
+
+    // ---- the slice's partial result
+    const uint32_t n_split = gridDim.x;
+    float* part = a.ws_partial + ((uint64_t)head * n_split + split) * (d + 2u);
+    float o_mine = 0.0f;
+    if (tid < d) o_mine = lds_o[0][tid] + lds_o[1][tid] + lds_o[2][tid] + lds_o[3][tid];
+    const float l_blk = lds_l[0] + lds_l[1] + lds_l[2] + lds_l[3];
+    if (n_split == 1u) {
+        if (tid < d) {
+            const float r = PR ? o_mine / l_blk : o_mine * __builtin_amdgcn_rcpf(l_blk);
+            if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
+            else {
+                float tmp[VEC] = {r};
+                static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+            }
+        }
+        return;
+    }
+    // published with device-coherent stores: the merging workgroup may run on another compute die
+    if (tid < d) __hip_atomic_store(part + tid, o_mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        __hip_atomic_store(part + d, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part + d + 1u, l_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(a.ws_counter + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = before + 1u == n_split;
+        // nobody touches the counter again before the next launch on this stream: re-arm it
+        if (last) __hip_atomic_store(a.ws_counter + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- the last workgroup of the head merges the slices: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M)
+    const float* base = a.ws_partial + (uint64_t)head * n_split * (d + 2u);
+    float big = -__builtin_inff();
+    for (uint32_t s = 0; s < n_split; ++s)
+        big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * (d + 2u) + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (tid < d) {
+        float num = 0.0f, den = 0.0f;
+        for (uint32_t s = 0; s < n_split; ++s) {
+            const float* ps = base + (uint64_t)s * (d + 2u);
+            const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float os = __hip_atomic_load(ps + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
+            num = __builtin_fmaf(os, w, num);
+            den = __builtin_fmaf(ls, w, den);
+        }
+        const float r = PR ? num / den : num * __builtin_amdgcn_rcpf(den);
+        if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
+        else {
+            float tmp[VEC] = {r};
+            static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+        }
+    }
+}
+
+template <int DT>
+static hipError_t launch_attn_dt(const AttnArgs& a, int nv, dim3 grid, hipStream_t st) {
+    switch (nv) {
+        case 1: hipLaunchKernelGGL((attn_decode_kernel<DT, 1>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((attn_decode_kernel<DT, 2>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((attn_decode_kernel<DT, 4>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((attn_decode_kernel<DT, 8>), grid, dim3(256), 0, st, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int nv, dim3 grid, hipStream_t st) {
+    switch (dtype) {
+        case DT_F32: return launch_attn_dt<DT_F32>(a, nv, grid, st);
+        case DT_F16: return launch_attn_dt<DT_F16>(a, nv, grid, st);
+        case DT_BF16: return launch_attn_dt<DT_BF16>(a, nv, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace pf

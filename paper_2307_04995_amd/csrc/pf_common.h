@@ -93,6 +93,7 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
     CORE_PERMUTE = 8,
+    CORE_ATTN_DECODE = 10,  // concat -> matrix-vector -> softmax -> concat -> vector-matrix (one-token attention)
     CORE_ROWPROG = 9   // no fixed core: the prologue itself holds row reductions (U_RED_*) and their broadcasts
 };
 
@@ -148,6 +149,24 @@ struct GroupGeom {
     uint32_t spin_limit;         // resident variant: bounded wait, then the error flag is raised
     uint32_t* ws_error;          // resident variant: set to 1 if a wait ran out
     FastDiv div_cv;
+};
+
+// Attention family (one new token against cached keys and values); all tensors of one storage type.
+struct AttnArgs {
+    const void* q;        // [heads, d]
+    const void* k_new;    // [heads, d] row appended to the keys, or null when the cache already holds it
+    const void* v_new;
+    const void* k_cache;  // [heads, t, d]
+    const void* v_cache;
+    void* o;              // [heads, d]
+    void* k_out;          // [heads, t_total, d] grown caches, or null when they are not outputs
+    void* v_out;
+    float* ws_partial;    // [heads][splits][d + 2]: weighted value sum, maximum, sum of exponentials
+    uint32_t* ws_counter; // [heads] arrivals of the current launch (re-armed by the last arrival)
+    uint32_t t, t_total;  // cached rows; rows after the concatenation (t or t + 1)
+    uint32_t d;           // head dimension (elements), at most 256
+    uint32_t lanes_per_row, log2_lpr;
+    float scale;
 };
 
 // Transpose family geometry.  The iteration space lists the merged dims from outermost to innermost in

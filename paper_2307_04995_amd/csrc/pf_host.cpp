@@ -42,7 +42,8 @@ pf_status fail(pf_status s, const char* fmt, ...) {
     return s;
 }
 
-enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE };
+enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE,
+               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT };
 
 struct OpTraits {
     OpClass cls;
@@ -58,6 +59,7 @@ const OpTraits kOps[PF_OP_COUNT_] = {
     {OC_MASK, 1, "causal_mask"}, {OC_REDUCE, 1, "reduce_sum"}, {OC_REDUCE, 1, "reduce_max"}, {OC_REDUCE, 1, "reduce_mean"},
     {OC_SOFTMAX, 1, "softmax"}, {OC_LAYERNORM, 3, "layernorm"}, {OC_RMSNORM, 2, "rmsnorm"}, {OC_GROUPNORM, 3, "groupnorm"},
     {OC_PERMUTE, 1, "permute"}, {OC_RESHAPE, 1, "reshape"},
+    {OC_CONCAT_ROWS, 2, "concat_rows"}, {OC_MATVEC, 2, "matvec"}, {OC_VECMAT, 2, "vecmat"},
 };
 
 bool is_elementwise(OpClass c) { return c == OC_BINARY || c == OC_UNARY || c == OC_MASK; }
@@ -176,6 +178,26 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 }
                 break;
             }
+            case OC_CONCAT_ROWS:
+            case OC_MATVEC: {
+                // a [..., t, d] with b [..., d]
+                const Shape& b = sh[o.src[1]];
+                if (a.size() < 2 || b.size() != a.size() - 1 || !std::equal(a.begin(), a.end() - 2, b.begin()) || b.back() != a.back())
+                    return fail(PF_ERR_SHAPE, "op %d (%s): needs [..., t, d] and [..., d]", k, tr.name);
+                r = a;
+                if (tr.cls == OC_CONCAT_ROWS) r[r.size() - 2] += 1;
+                else r.pop_back();
+                break;
+            }
+            case OC_VECMAT: {
+                // a [..., t] with b [..., t, d]
+                const Shape& b = sh[o.src[1]];
+                if (b.size() < 2 || a.size() != b.size() - 1 || !std::equal(a.begin(), a.end(), b.begin()))
+                    return fail(PF_ERR_SHAPE, "op %d (vecmat): needs [..., t] and [..., t, d]", k);
+                r.assign(b.begin(), b.end() - 2);
+                r.push_back(b.back());
+                break;
+            }
             case OC_RESHAPE: {
                 if (o.n_i < 1 || o.n_i > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "op %d (reshape): n_i out of range", k);
                 r.assign(o.i, o.i + o.n_i);
@@ -221,6 +243,11 @@ struct Lowered {
     Shape post_shape;         // shape of the value leaving the core
     int64_t groups = 0;
     int perm[PF_MAX_RANK];
+    // one-token attention: chain input index of q, new key row, new value row, key cache, value cache (-1: the
+    // caches already hold the new rows); user output index of o, grown key cache, grown value cache (-1: not an output)
+    int attn_in[5] = {-1, -1, -1, -1, -1};
+    int attn_out[3] = {-1, -1, -1};
+    float attn_scale = 1.0f;
 };
 
 struct Lowerer {
@@ -518,8 +545,83 @@ struct Lowerer {
 // value ids of chain inputs never reach zero uses through consume() bookkeeping problems: inputs keep
 // LOC_FULL / LOC_VEC for the whole region, so only computed values matter for temporaries.
 
+// One-token attention (paper section 8, GPT-2 case study): the three contraction / concatenation operators are
+// accepted in exactly one arrangement, matched structurally from the final operator backwards:
+//   o = VECMAT(SOFTMAX([SCALE](MATVEC(K', q))), V'),  K' = CONCAT_ROWS(K, k) or an input, V' likewise.
+pf_status lower_attention(const pf_chain_desc* d, const Checked& c, Lowered* L) {
+    const int n_in = d->n_inputs;
+    auto op_of = [&](int v) -> const pf_op_desc* { return v >= n_in ? &d->ops[v - n_in] : nullptr; };
+    auto bad = [&](const char* what) { return fail(PF_ERR_UNSUPPORTED, "attention chain: %s", what); };
+    const int final_v = n_in + d->n_ops - 1;
+    const pf_op_desc* vm = op_of(final_v);
+    if (!vm || vm->op != PF_VECMAT) return bad("the last operator must be vecmat(softmax(...), values)");
+    const pf_op_desc* sm = op_of(vm->src[0]);
+    if (!sm || sm->op != PF_SOFTMAX) return bad("vecmat's first operand must be a softmax");
+    int used_ops = 2;
+    const pf_op_desc* x = op_of(sm->src[0]);
+    L->attn_scale = 1.0f;
+    if (x && x->op == PF_SCALE) {
+        L->attn_scale = x->f[0];
+        x = op_of(x->src[0]);
+        ++used_ops;
+    }
+    if (!x || x->op != PF_MATVEC) return bad("the softmax must be taken over (scaled) matvec(keys, q)");
+    ++used_ops;
+    const int q_in = x->src[1];
+    if (q_in >= n_in) return bad("q must be a chain input");
+    int k_val = x->src[0], v_val = vm->src[1];
+    int kc_val = -1, vc_val = -1;  // value ids of the concatenation results
+    int K_in = k_val, V_in = v_val, kn_in = -1, vn_in = -1;
+    if (const pf_op_desc* kc = op_of(k_val)) {
+        if (kc->op != PF_CONCAT_ROWS || kc->src[0] >= n_in || kc->src[1] >= n_in) return bad("keys must be an input or concat_rows(input, input)");
+        kc_val = k_val;
+        K_in = kc->src[0];
+        kn_in = kc->src[1];
+        ++used_ops;
+    }
+    if (const pf_op_desc* vc = op_of(v_val)) {
+        if (vc->op != PF_CONCAT_ROWS || vc->src[0] >= n_in || vc->src[1] >= n_in) return bad("values must be an input or concat_rows(input, input)");
+        vc_val = v_val;
+        V_in = vc->src[0];
+        vn_in = vc->src[1];
+        ++used_ops;
+    }
+    if ((kn_in < 0) != (vn_in < 0)) return bad("keys and values must both be concatenated or both be inputs");
+    if (used_ops != d->n_ops) return bad("operators outside the attention pattern");
+    if (c.shape[K_in] != c.shape[V_in]) return bad("key and value caches differ in shape");
+    L->core = pf::CORE_ATTN_DECODE;
+    L->attn_in[0] = q_in;
+    L->attn_in[1] = kn_in;
+    L->attn_in[2] = vn_in;
+    L->attn_in[3] = K_in;
+    L->attn_in[4] = V_in;
+    for (int o = 0; o < d->n_outputs; ++o) {
+        const int v = d->out_value[o];
+        if (v == final_v) L->attn_out[0] = o;
+        else if (v == kc_val) L->attn_out[1] = o;
+        else if (v == vc_val) L->attn_out[2] = o;
+        else return bad("only the attention result and the grown caches can be outputs");
+    }
+    if (L->attn_out[0] < 0) return bad("the attention result must be an output");
+    L->main_dtype = d->out_dtype[L->attn_out[0]];
+    for (int o = 0; o < d->n_outputs; ++o)
+        if (d->out_dtype[o] != L->main_dtype) return fail(PF_ERR_DTYPE, "outputs of different dtypes are not implemented");
+    for (int i = 0; i < 5; ++i)
+        if (L->attn_in[i] >= 0 && d->inputs[L->attn_in[i]].dtype != L->main_dtype)
+            return fail(PF_ERR_DTYPE, "input %d: dtype differs from the chain's main dtype", L->attn_in[i]);
+    if (!std::isfinite(L->attn_scale) || !(L->attn_scale > 0.0f)) return bad("the score scale must be positive and finite");
+    L->pre_shape = c.shape[K_in];
+    L->post_shape = c.shape[final_v];
+    L->n_out = d->n_outputs;
+    return PF_OK;
+}
+
 pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     const int n_in = d->n_inputs, n_val = d->n_inputs + d->n_ops;
+    for (int k = 0; k < d->n_ops; ++k) {
+        const OpClass cls = kOps[d->ops[k].op].cls;
+        if (cls == OC_CONCAT_ROWS || cls == OC_MATVEC || cls == OC_VECMAT) return lower_attention(d, c, L);
+    }
     // Row program: a chain written in basic operators only (element-wise, reduce over the last dimension,
     // broadcast of the reduced value back over its row; paper section 6) whose result has the full shape.
     // The reduce -> broadcast pairs need a synchronisation no wider than a row (section 5.1), so they become
@@ -771,6 +873,7 @@ struct pf_plan_s {
     pf::RowGeom row;
     pf::GroupGeom group;
     pf::PermGeom permg;
+    pf::AttnArgs attn;
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -1353,6 +1456,65 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     return PF_OK;
 }
 
+// ---- attention family
+pf_status plan_attn(pf_plan_s* p) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const Shape& ks = L.pre_shape;  // [..., t, d]
+    const int64_t d = ks.back(), t = ks[ks.size() - 2];
+    const int64_t heads = numel(ks) / (t * d);
+    const bool grows = L.attn_in[1] >= 0;
+    const int64_t t_total = t + (grows ? 1 : 0);
+    if ((d * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "head dimension %lld is not a multiple of 16 bytes", (long long)d);
+    const int64_t lpr = d / vec;
+    if (lpr > 64 || (lpr & (lpr - 1)) != 0 || d > 256)
+        return fail(PF_ERR_UNSUPPORTED, "head dimension %lld: needs a power-of-two number (<= 64) of 16-byte vectors and at most 256 elements", (long long)d);
+    if (heads > 65535 || t_total > 0x7fffffffLL || t_total < 1) return fail(PF_ERR_UNSUPPORTED, "attention shape out of range");
+    hipDeviceProp_t prop;
+    if (hipSetDevice(p->device) != hipSuccess || hipGetDeviceProperties(&prop, p->device) != hipSuccess)
+        return fail(PF_ERR_HIP, "cannot query device %d (the attention family needs the device at plan time)", p->device);
+    const int n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    pf::AttnArgs& a = p->attn;
+    memset(&a, 0, sizeof(a));
+    a.t = (uint32_t)t;
+    a.t_total = (uint32_t)t_total;
+    a.d = (uint32_t)d;
+    a.lanes_per_row = (uint32_t)lpr;
+    a.log2_lpr = 0;
+    while ((1u << a.log2_lpr) < a.lanes_per_row) ++a.log2_lpr;
+    a.scale = L.attn_scale;
+    // rows per workgroup: as many steps of 256 / lpr rows as still leave two workgroups per compute unit
+    const int64_t rps = 256 / lpr;
+    int nv = 1;
+    const int forced_nv = env_int("PF_ATTN_NV", 0);
+    for (int cand = 8; cand >= 1; cand /= 2) {
+        const int64_t splits = (t_total + rps * cand - 1) / (rps * cand);
+        if (forced_nv ? cand == forced_nv : heads * splits >= 2 * (int64_t)n_cu) {
+            nv = cand;
+            break;
+        }
+    }
+    const int64_t splits = (t_total + rps * nv - 1) / (rps * nv);
+    if (splits > 65535) return fail(PF_ERR_UNSUPPORTED, "too many cached rows for the attention family");
+    p->family = PF_FAMILY_ATTENTION;
+    p->variant = 0;
+    p->k = nv;
+    p->spec_id = 0;
+    p->block = dim3(256);
+    p->grid = dim3((uint32_t)splits, (uint32_t)heads);
+    p->lds_bytes = (8 + 4 * 256 + 1) * 4;
+    p->n_launches = 1;
+    const uint64_t part_bytes = ((uint64_t)heads * splits * (d + 2) * sizeof(float) + 255) / 256 * 256;
+    const uint64_t cnt_bytes = ((uint64_t)heads * sizeof(uint32_t) + 255) / 256 * 256;
+    p->workspace_bytes = part_bytes + cnt_bytes;
+    if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
+    if (hipMemset(p->workspace, 0, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
+    a.ws_partial = reinterpret_cast<float*>(p->workspace);
+    a.ws_counter = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
+    return PF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1392,8 +1554,9 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
     memset(&p->row, 0, sizeof(p->row));
     memset(&p->group, 0, sizeof(p->group));
     memset(&p->permg, 0, sizeof(p->permg));
+    memset(&p->attn, 0, sizeof(p->attn));
     s = lower_chain(desc, c, &p->low);
-    if (s == PF_OK) {
+    if (s == PF_OK && p->low.core != pf::CORE_ATTN_DECODE) {
         const Lowered& L = p->low;
         p->args.n_full = L.n_full;
         p->args.n_vec = L.n_vec;
@@ -1416,6 +1579,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
             case pf::CORE_NONE: s = plan_ew(p); break;
             case pf::CORE_GROUPNORM: s = plan_group(p, variant); break;
             case pf::CORE_PERMUTE: s = plan_perm(p, variant); break;
+            case pf::CORE_ATTN_DECODE: s = plan_attn(p); break;
             default: s = plan_row(p, variant); break;
         }
     }
@@ -1482,8 +1646,22 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (ob < je && jb < oe) return fail(PF_ERR_ALIAS, "outputs %d and %d overlap", j, o);
         }
     }
-    pf::ChainArgs a = plan->args;
     const Lowered& L = plan->low;
+    if (plan->family == PF_FAMILY_ATTENTION) {
+        pf::AttnArgs at = plan->attn;
+        at.q = inputs[L.attn_in[0]];
+        at.k_new = L.attn_in[1] >= 0 ? inputs[L.attn_in[1]] : nullptr;
+        at.v_new = L.attn_in[2] >= 0 ? inputs[L.attn_in[2]] : nullptr;
+        at.k_cache = inputs[L.attn_in[3]];
+        at.v_cache = inputs[L.attn_in[4]];
+        at.o = outputs[L.attn_out[0]];
+        at.k_out = L.attn_out[1] >= 0 ? outputs[L.attn_out[1]] : nullptr;
+        at.v_out = L.attn_out[2] >= 0 ? outputs[L.attn_out[2]] : nullptr;
+        const hipError_t ea = pf::launch_attn_decode(L.main_dtype, at, plan->k, plan->grid, (hipStream_t)stream);
+        if (ea != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ea));
+        return PF_OK;
+    }
+    pf::ChainArgs a = plan->args;
     for (int f = 0; f < L.n_full; ++f) a.full[f] = inputs[L.full_input[f]];
     for (int v = 0; v < L.n_vec; ++v) a.vec[v].ptr = inputs[L.vec_input[v]];
     for (int s = 0; s < L.n_out; ++s) a.out[s] = outputs[L.out_slot_to_user[s]];
