@@ -157,21 +157,40 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     __syncthreads();
     if (!s_last) return;
 
-    // ---- the last workgroup of the head merges the slices: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M)
+    // ---- the last workgroup of the head merges the slices: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+    // All 256 threads take part: thread (g, c) sums column c over the slices s = g, g + G, ... (G = 256 / d'
+    // groups, d' = d rounded up to a power of two), so the loads of many slices are in flight together; the
+    // groups are then combined through LDS.
     const float* base = a.ws_partial + (uint64_t)head * n_split * (d + 2u);
+    uint32_t dp = 1;
+    while (dp < d) dp <<= 1;
+    const uint32_t groups = 256u / dp, g = tid / dp, c = tid - g * dp;
     float big = -__builtin_inff();
-    for (uint32_t s = 0; s < n_split; ++s)
+    for (uint32_t s = lane; s < n_split; s += 64u)
         big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * (d + 2u) + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    for (int msk = 1; msk < 64; msk <<= 1) big = fmaxf(big, shfl_xor_f(big, msk));  // every wave finds the same maximum
+    float num = 0.0f, den = 0.0f;
+    for (uint32_t s = g; s < n_split; s += groups) {
+        const float* ps = base + (uint64_t)s * (d + 2u);
+        const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float os = c < d ? __hip_atomic_load(ps + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+        const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
+        num = __builtin_fmaf(os, w, num);
+        den = __builtin_fmaf(ls, w, den);
+    }
+    float* red_num = &lds_o[0][0];  // [groups][dp] (the per-wave partials are no longer needed)
+    float* red_den = &lds_o[2][0];
+    __syncthreads();
+    red_num[tid] = num;
+    red_den[tid] = den;
+    __syncthreads();
     if (tid < d) {
-        float num = 0.0f, den = 0.0f;
-        for (uint32_t s = 0; s < n_split; ++s) {
-            const float* ps = base + (uint64_t)s * (d + 2u);
-            const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float os = __hip_atomic_load(ps + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
-            num = __builtin_fmaf(os, w, num);
-            den = __builtin_fmaf(ls, w, den);
+        num = 0.0f;
+        den = 0.0f;
+        for (uint32_t gg = 0; gg < groups; ++gg) {
+            num += red_num[gg * dp + tid];
+            den += red_den[gg * dp + tid];
         }
         const float r = PR ? num / den : num * __builtin_amdgcn_rcpf(den);
         if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;

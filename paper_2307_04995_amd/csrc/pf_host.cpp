@@ -1484,17 +1484,14 @@ pf_status plan_attn(pf_plan_s* p) {
     a.log2_lpr = 0;
     while ((1u << a.log2_lpr) < a.lanes_per_row) ++a.log2_lpr;
     a.scale = L.attn_scale;
-    // rows per workgroup: as many steps of 256 / lpr rows as still leave two workgroups per compute unit
+    // Rows per workgroup: 8 steps of 256 / lpr rows when that still gives every compute unit two workgroups,
+    // else 4 (measured on MI355X: fewer, longer slices win until the device runs short of workgroups; one or
+    // two steps per workgroup lose to the per-slice overhead, sixteen to register pressure).
     const int64_t rps = 256 / lpr;
-    int nv = 1;
+    int nv = 4;
+    if (heads * ((t_total + rps * 8 - 1) / (rps * 8)) >= 2 * (int64_t)n_cu) nv = 8;
     const int forced_nv = env_int("PF_ATTN_NV", 0);
-    for (int cand = 8; cand >= 1; cand /= 2) {
-        const int64_t splits = (t_total + rps * cand - 1) / (rps * cand);
-        if (forced_nv ? cand == forced_nv : heads * splits >= 2 * (int64_t)n_cu) {
-            nv = cand;
-            break;
-        }
-    }
+    if (forced_nv == 1 || forced_nv == 2 || forced_nv == 4 || forced_nv == 8) nv = forced_nv;
     const int64_t splits = (t_total + rps * nv - 1) / (rps * nv);
     if (splits > 65535) return fail(PF_ERR_UNSUPPORTED, "too many cached rows for the attention family");
     p->family = PF_FAMILY_ATTENTION;
