@@ -405,3 +405,53 @@ int orc_permute_bytes(const void *x, int32_t rank, const int64_t *shape, const i
     }
     return ORC_OK;
 }
+
+/*
+ * Concatenation and slicing along one axis (data movement only; the ShuffleNet fragment
+ * concat -> channel shuffle -> split of section 2 is made of these, a reshape and a permutation).
+ * Elements are moved as `esize` raw bytes.
+ *
+ * concat: out[..., 0..la-1, ...] = a, out[..., la..la+lb-1, ...] = b along `axis`; all other extents equal.
+ */
+int orc_concat_bytes(const void *a, const void *b, int32_t rank, const int64_t *shape_a, const int64_t *shape_b,
+                     int32_t axis, int32_t esize, void *out)
+{
+    if (rank < 1 || rank > 8 || axis < 0 || axis >= rank || esize < 1) return ORC_BAD_ARG;
+    int64_t outer = 1, inner = 1;
+    for (int k = 0; k < rank; ++k) {
+        if (shape_a[k] <= 0 || shape_b[k] <= 0) return ORC_BAD_ARG;
+        if (k != axis && shape_a[k] != shape_b[k]) return ORC_BAD_ARG;
+        if (k < axis) outer *= shape_a[k];
+        if (k > axis) inner *= shape_a[k];
+    }
+    const int64_t la = shape_a[axis] * inner, lb = shape_b[axis] * inner;
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    char *po = (char *)out;
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t i = 0; i < la; ++i) memcpy(po + (o * (la + lb) + i) * esize, pa + (o * la + i) * esize, (size_t)esize);
+        for (int64_t i = 0; i < lb; ++i) memcpy(po + (o * (la + lb) + la + i) * esize, pb + (o * lb + i) * esize, (size_t)esize);
+    }
+    return ORC_OK;
+}
+
+/* slice: out[..., j, ...] = x[..., start + j, ...] for 0 <= j < length along `axis` */
+int orc_slice_bytes(const void *x, int32_t rank, const int64_t *shape, int32_t axis, int64_t start, int64_t length,
+                    int32_t esize, void *out)
+{
+    if (rank < 1 || rank > 8 || axis < 0 || axis >= rank || esize < 1) return ORC_BAD_ARG;
+    int64_t outer = 1, inner = 1;
+    for (int k = 0; k < rank; ++k) {
+        if (shape[k] <= 0) return ORC_BAD_ARG;
+        if (k < axis) outer *= shape[k];
+        if (k > axis) inner *= shape[k];
+    }
+    if (start < 0 || length < 1 || start + length > shape[axis]) return ORC_BAD_ARG;
+    const char *px = (const char *)x;
+    char *po = (char *)out;
+    for (int64_t o = 0; o < outer; ++o)
+        for (int64_t j = 0; j < length; ++j)
+            for (int64_t i = 0; i < inner; ++i)
+                memcpy(po + ((o * length + j) * inner + i) * esize,
+                       px + ((o * shape[axis] + start + j) * inner + i) * esize, (size_t)esize);
+    return ORC_OK;
+}

@@ -53,6 +53,10 @@ def _load():
         lib.orc_reduce_last.argtypes = [ctypes.c_int, dp, i64, i64, dp]
         lib.orc_row_broadcast_binary.argtypes = [ctypes.c_int, dp, i64, i64, dp, dp]
         lib.orc_softmax_last.argtypes = [dp, i64, i64, dp]
+        lib.orc_concat_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        lib.orc_slice_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(i64), ctypes.c_int32, i64, i64,
+                                        ctypes.c_int32, ctypes.c_void_p]
         lib.orc_concat_rows.argtypes = [dp, i64, i64, i64, dp, dp]
         lib.orc_matvec.argtypes = [dp, i64, i64, i64, dp, dp]
         lib.orc_vecmat.argtypes = [dp, i64, i64, i64, dp, dp]
@@ -259,6 +263,37 @@ def permute(x: np.ndarray, perm: Sequence[int]) -> np.ndarray:
     return out
 
 
+def concat(a: np.ndarray, b: np.ndarray, axis: int) -> np.ndarray:
+    """Concatenation along `axis`; any fixed-size dtype, elements moved as raw bytes."""
+    a, b = np.ascontiguousarray(a), np.ascontiguousarray(b)
+    if a.ndim != b.ndim or a.dtype != b.dtype or not 0 <= axis < a.ndim:
+        raise ValueError("oracle: concat operands")
+    if any(a.shape[k] != b.shape[k] for k in range(a.ndim) if k != axis):
+        raise ValueError(f"oracle: concat shapes {a.shape} and {b.shape}")
+    sa = (ctypes.c_int64 * a.ndim)(*a.shape)
+    sb = (ctypes.c_int64 * b.ndim)(*b.shape)
+    shape = list(a.shape)
+    shape[axis] += b.shape[axis]
+    out = np.empty(tuple(shape), dtype=a.dtype)
+    _check(_load().orc_concat_bytes(a.ctypes.data, b.ctypes.data, a.ndim, sa, sb, int(axis), a.dtype.itemsize,
+                                    out.ctypes.data), "concat")
+    return out
+
+
+def slice_axis(x: np.ndarray, axis: int, start: int, length: int) -> np.ndarray:
+    """x[..., start:start+length, ...] along `axis`; elements moved as raw bytes."""
+    x = np.ascontiguousarray(x)
+    if not 0 <= axis < x.ndim or start < 0 or length < 1 or start + length > x.shape[axis]:
+        raise ValueError("oracle: slice range")
+    sx = (ctypes.c_int64 * x.ndim)(*x.shape)
+    shape = list(x.shape)
+    shape[axis] = int(length)
+    out = np.empty(tuple(shape), dtype=x.dtype)
+    _check(_load().orc_slice_bytes(x.ctypes.data, x.ndim, sx, int(axis), int(start), int(length), x.dtype.itemsize,
+                                   out.ctypes.data), "slice")
+    return out
+
+
 def reshape(x: np.ndarray, shape: Sequence[int]) -> np.ndarray:
     x = np.ascontiguousarray(x)
     if int(np.prod(shape, dtype=np.int64)) != x.size:
@@ -299,6 +334,10 @@ def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
         return permute(a[0], op.i)
     if name == "reshape":
         return reshape(a[0], op.i)
+    if name == "concat":
+        return concat(a[0], a[1], op.i[0])
+    if name == "slice":
+        return slice_axis(a[0], op.i[0], op.i[1], op.i[2])
     raise KeyError(f"oracle: unknown op {name}")
 
 
@@ -330,6 +369,10 @@ def evaluate_layout_bits(spec, inputs_bits: Sequence[np.ndarray]) -> List[np.nda
             vals.append(permute(vals[op.src[0]], op.i))
         elif op.name == "reshape":
             vals.append(reshape(vals[op.src[0]], op.i))
+        elif op.name == "concat":
+            vals.append(concat(vals[op.src[0]], vals[op.src[1]], op.i[0]))
+        elif op.name == "slice":
+            vals.append(slice_axis(vals[op.src[0]], op.i[0], op.i[1], op.i[2]))
         else:
-            raise ValueError("oracle: evaluate_layout_bits accepts only permute and reshape")
+            raise ValueError("oracle: evaluate_layout_bits accepts only permute, reshape, concat and slice")
     return [vals[v] for v, _ in spec.outputs]

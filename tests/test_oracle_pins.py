@@ -504,3 +504,55 @@ def test_one_token_attention_chain_equals_its_definition():
     Vconst = np.full_like(V, 0.75)
     o2 = orc.evaluate_outputs(spec, [q, k, np.full_like(v, 0.75), K, Vconst])[0]
     np.testing.assert_allclose(o2, 0.75, rtol=1e-14)
+
+
+# ---- concatenation / slicing / channel shuffle (the ShuffleNet fragment of section 2) ----
+
+def test_concat_and_slice_worked_by_hand():
+    a = np.array([[[1, 2], [3, 4]], [[5, 6], [7, 8]]], dtype=np.uint16)            # [2, 2, 2]
+    b = np.array([[[11, 12]], [[13, 14]]], dtype=np.uint16)                         # [2, 1, 2]
+    y = orc.concat(a, b, 1)
+    np.testing.assert_array_equal(y, [[[1, 2], [3, 4], [11, 12]], [[5, 6], [7, 8], [13, 14]]])
+    np.testing.assert_array_equal(orc.slice_axis(y, 1, 2, 1), b)
+    np.testing.assert_array_equal(orc.slice_axis(y, 1, 0, 2), a)
+    np.testing.assert_array_equal(orc.slice_axis(y, 2, 1, 1), [[[2], [4], [12]], [[6], [8], [14]]])
+    np.testing.assert_array_equal(orc.concat(a, a, 2)[0], [[1, 2, 1, 2], [3, 4, 3, 4]])
+    np.testing.assert_array_equal(orc.concat(a, a, 0).shape, (4, 2, 2))
+    with pytest.raises(ValueError):
+        orc.concat(a, b, 2)
+    with pytest.raises(ValueError):
+        orc.slice_axis(a, 1, 1, 2)
+
+
+def test_concat_slice_against_library_and_inverse():
+    rng = np.random.default_rng(21)
+    for dt in (np.uint16, np.uint32, np.float64):
+        a = rng.integers(0, 60000, (3, 4, 5, 2)).astype(dt)
+        b = rng.integers(0, 60000, (3, 7, 5, 2)).astype(dt)
+        y = orc.concat(a, b, 1)
+        np.testing.assert_array_equal(y, np.concatenate([a, b], axis=1))
+        np.testing.assert_array_equal(orc.slice_axis(y, 1, 0, 4), a)
+        np.testing.assert_array_equal(orc.slice_axis(y, 1, 4, 7), b)
+        np.testing.assert_array_equal(orc.slice_axis(y, 2, 1, 3), y[:, :, 1:4])
+
+
+def test_channel_shuffle_chain_has_its_closed_form():
+    # shuffled[n, j * g + i] = concat[n, i * (c / g) + j]: with g = 2 the halves of a and b interleave
+    for groups, c in ((2, 12), (4, 16)):
+        spec, ins = wl.x3_channel_shuffle(n=2, c=c, h=3, w=5, groups=groups, dtype="f16")
+        bits = [wl.raw_bits(t) for t in ins]
+        o0, o1 = orc.evaluate_layout_bits(spec, bits)
+        cat = np.concatenate(bits, axis=1)
+        want = np.empty_like(cat)
+        per = c // groups
+        for i in range(groups):
+            for j in range(per):
+                want[:, j * groups + i] = cat[:, i * per + j]
+        np.testing.assert_array_equal(o0, want[:, :c // 2])
+        np.testing.assert_array_equal(o1, want[:, c // 2:])
+    # g = 2: output 0 interleaves the first halves of a and b channel by channel
+    spec, ins = wl.x3_channel_shuffle(n=1, c=8, h=1, w=2, groups=2, dtype="f32")
+    a, b = [wl.raw_bits(t) for t in ins]
+    o0, o1 = orc.evaluate_layout_bits(spec, [a, b])
+    np.testing.assert_array_equal(o0[0], [a[0, 0], b[0, 0], a[0, 1], b[0, 1]])
+    np.testing.assert_array_equal(o1[0], [a[0, 2], b[0, 2], a[0, 3], b[0, 3]])

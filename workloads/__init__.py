@@ -31,6 +31,8 @@ OP_ARITY: Dict[str, int] = {
     "permute": 1, "reshape": 1,
     # one-token attention against cached keys / values: append a row, matrix-vector, vector-matrix
     "concat_rows": 2, "matvec": 2, "vecmat": 2,
+    # layout: concatenation along axis i[0]; slice [i[1], i[1] + i[2]) along axis i[0]
+    "concat": 2, "slice": 1,
 }
 
 
@@ -209,6 +211,23 @@ def x2_decode_attention(b: int = 8, h: int = 25, t: int = 1023, d: int = 64, dty
     return c, [quantise(x, dtype) for x in (q, k, v, kc, vc)]
 
 
+def x3_channel_shuffle(n: int = 32, c: int = 232, h: int = 28, w: int = 28, groups: int = 2, dtype: str = "f16",
+                       salt: int = 0):
+    """concat -> channel shuffle -> split on NCHW tensors (not a BASELINE config; the ShuffleNet fragment of
+    the paper's section 2): a, b [n, c/2, h, w]; y = shuffle_groups(concat(a, b)); outputs y[:, :c/2], y[:, c/2:]."""
+    g = _rng(8, salt)
+    a = g.standard_normal((n, c // 2, h, w), dtype=np.float32)
+    b = g.standard_normal((n, c // 2, h, w), dtype=np.float32)
+    s = ChainSpec(inputs=[(dtype, (n, c // 2, h, w)), (dtype, (n, c // 2, h, w))])
+    y = s.op("concat", 0, 1, i=[1])
+    y = s.op("reshape", y, i=[n, groups, c // groups, h, w])
+    y = s.op("permute", y, i=[0, 2, 1, 3, 4])
+    y = s.op("reshape", y, i=[n, c, h, w])
+    s.out(s.op("slice", y, i=[1, 0, c // 2]), dtype)
+    s.out(s.op("slice", y, i=[1, c // 2, c // 2]), dtype)
+    return s, [quantise(a, dtype), quantise(b, dtype)]
+
+
 CONFIGS = {
     "C1": c1_bias_res_layernorm_gelu,
     "C2": c2_causal_softmax,
@@ -216,6 +235,7 @@ CONFIGS = {
     "C4": c4_bias_scale_permute,
     "C5": c5_groupnorm_silu,
     "X1": x1_bias_scale_transpose,      # not a BASELINE config: the innermost-changing transpose, for context
+    "X3": x3_channel_shuffle,           # not a BASELINE config: concat -> channel shuffle -> split
     "X2": x2_decode_attention,          # not a BASELINE config: one-token attention against a key-value cache
 }
 
