@@ -85,7 +85,11 @@ typedef enum {
     PF_CONCAT_ROWS = 26,/* src0 [..., t, d], src1 [..., d] -> [..., t+1, d]: src1 appended as the last row  */
     PF_MATVEC = 27,     /* src0 [..., t, d], src1 [..., d] -> [..., t]:   y_j = sum_c a_jc x_c              */
     PF_VECMAT = 28,     /* src0 [..., t],    src1 [..., t, d] -> [..., d]: y_c = sum_j p_j a_jc              */
-    PF_OP_COUNT_ = 29
+    /* layout only (with PERMUTE and RESHAPE): chains made of nothing but these four move every element exactly
+       once and are run as one index-map copy with any number of inputs (<= PF_MAX_INPUTS) and outputs          */
+    PF_CONCAT = 29,     /* src0, src1 joined along axis i[0] (all other extents equal)                          */
+    PF_SLICE = 30,      /* elements [i[1], i[1] + i[2]) of src0 along axis i[0]                                  */
+    PF_OP_COUNT_ = 31
 } pf_op;
 
 /* A contiguous row-major tensor. */
@@ -130,6 +134,8 @@ typedef enum {
     PF_FAMILY_ROW = 1,         /* row reduction then broadcast: wave shuffle, LDS when a row spans waves     */
     PF_FAMILY_GROUP = 2,       /* GroupNorm: a group spans workgroups, partial statistics cross the device   */
     PF_FAMILY_TRANSPOSE = 3,   /* layout change staged through an LDS tile                                   */
+    PF_FAMILY_GATHER = 5,      /* layout-only chains (concat / slice / permute / reshape): a copy driven by a table
+                                  of contiguous runs computed when the plan is made                          */
     PF_FAMILY_ATTENTION = 4    /* one-token attention: a head's rows span workgroups, partial results are
                                   merged by the last workgroup to arrive                                     */
 } pf_family;

@@ -93,6 +93,7 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
     CORE_PERMUTE = 8,
+    CORE_GATHER = 11,       // layout-only chain with concatenations / slices
     CORE_ATTN_DECODE = 10,  // concat -> matrix-vector -> softmax -> concat -> vector-matrix (one-token attention)
     CORE_ROWPROG = 9   // no fixed core: the prologue itself holds row reductions (U_RED_*) and their broadcasts
 };
@@ -167,6 +168,21 @@ struct AttnArgs {
     uint32_t d;           // head dimension (elements), at most 256
     uint32_t lanes_per_row, log2_lpr;
     float scale;
+};
+
+// Gather family: layout-only chains as a copy of contiguous runs.  Run k of the table moves run_elems elements
+// from input src_id at element src_off to output dst_id at element dst_off.
+struct GatherRun {
+    uint32_t src_off, dst_off;
+    uint8_t src_id, dst_id;
+    uint16_t pad;
+};
+struct GatherArgs {
+    const void* in[8];
+    void* out[3];
+    const GatherRun* table;
+    uint32_t n_runs, run_elems, vec_per_run;
+    FastDiv div_vpr;
 };
 
 // Transpose family geometry.  The iteration space lists the merged dims from outermost to innermost in

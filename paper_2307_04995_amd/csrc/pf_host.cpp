@@ -43,7 +43,7 @@ pf_status fail(pf_status s, const char* fmt, ...) {
 }
 
 enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE,
-               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT };
+               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT, OC_CONCAT, OC_SLICE };
 
 struct OpTraits {
     OpClass cls;
@@ -60,6 +60,7 @@ const OpTraits kOps[PF_OP_COUNT_] = {
     {OC_SOFTMAX, 1, "softmax"}, {OC_LAYERNORM, 3, "layernorm"}, {OC_RMSNORM, 2, "rmsnorm"}, {OC_GROUPNORM, 3, "groupnorm"},
     {OC_PERMUTE, 1, "permute"}, {OC_RESHAPE, 1, "reshape"},
     {OC_CONCAT_ROWS, 2, "concat_rows"}, {OC_MATVEC, 2, "matvec"}, {OC_VECMAT, 2, "vecmat"},
+    {OC_CONCAT, 2, "concat"}, {OC_SLICE, 1, "slice"},
 };
 
 bool is_elementwise(OpClass c) { return c == OC_BINARY || c == OC_UNARY || c == OC_MASK; }
@@ -187,6 +188,25 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 r = a;
                 if (tr.cls == OC_CONCAT_ROWS) r[r.size() - 2] += 1;
                 else r.pop_back();
+                break;
+            }
+            case OC_CONCAT: {
+                const Shape& b = sh[o.src[1]];
+                const int64_t ax = o.n_i == 1 ? o.i[0] : -1;
+                if (ax < 0 || ax >= (int64_t)a.size() || b.size() != a.size())
+                    return fail(PF_ERR_INVALID_ARG, "op %d (concat): i[0] must name an axis of both operands", k);
+                for (size_t q = 0; q < a.size(); ++q)
+                    if ((int64_t)q != ax && a[q] != b[q]) return fail(PF_ERR_SHAPE, "op %d (concat): operands differ outside the axis", k);
+                r = a;
+                r[ax] += b[ax];
+                break;
+            }
+            case OC_SLICE: {
+                const int64_t ax = o.n_i == 3 ? o.i[0] : -1;
+                if (ax < 0 || ax >= (int64_t)a.size()) return fail(PF_ERR_INVALID_ARG, "op %d (slice): i = {axis, start, length}", k);
+                if (o.i[1] < 0 || o.i[2] < 1 || o.i[1] + o.i[2] > a[ax]) return fail(PF_ERR_SHAPE, "op %d (slice): range outside the axis", k);
+                r = a;
+                r[ax] = o.i[2];
                 break;
             }
             case OC_VECMAT: {
@@ -545,6 +565,25 @@ struct Lowerer {
 // value ids of chain inputs never reach zero uses through consume() bookkeeping problems: inputs keep
 // LOC_FULL / LOC_VEC for the whole region, so only computed values matter for temporaries.
 
+// Layout-only chains with concatenations or slices: nothing to lower, the planner evaluates the index map.
+pf_status lower_layout(const pf_chain_desc* d, const Checked& c, Lowered* L) {
+    (void)c;
+    for (int k = 0; k < d->n_ops; ++k) {
+        const OpClass cls = kOps[d->ops[k].op].cls;
+        if (cls != OC_CONCAT && cls != OC_SLICE && cls != OC_PERMUTE && cls != OC_RESHAPE)
+            return fail(PF_ERR_UNSUPPORTED, "op %d (%s): concat / slice are implemented in layout-only chains (with permute and reshape)", k,
+                        kOps[d->ops[k].op].name);
+    }
+    L->core = pf::CORE_GATHER;
+    L->main_dtype = d->out_dtype[0];
+    for (int o = 0; o < d->n_outputs; ++o)
+        if (d->out_dtype[o] != L->main_dtype) return fail(PF_ERR_DTYPE, "outputs of different dtypes are not implemented");
+    for (int k = 0; k < d->n_inputs; ++k)
+        if (d->inputs[k].dtype != L->main_dtype) return fail(PF_ERR_DTYPE, "input %d: a layout-only chain cannot convert between dtypes", k);
+    L->n_out = d->n_outputs;
+    return PF_OK;
+}
+
 // One-token attention (paper section 8, GPT-2 case study): the three contraction / concatenation operators are
 // accepted in exactly one arrangement, matched structurally from the final operator backwards:
 //   o = VECMAT(SOFTMAX([SCALE](MATVEC(K', q))), V'),  K' = CONCAT_ROWS(K, k) or an input, V' likewise.
@@ -621,6 +660,10 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
     for (int k = 0; k < d->n_ops; ++k) {
         const OpClass cls = kOps[d->ops[k].op].cls;
         if (cls == OC_CONCAT_ROWS || cls == OC_MATVEC || cls == OC_VECMAT) return lower_attention(d, c, L);
+    }
+    for (int k = 0; k < d->n_ops; ++k) {
+        const OpClass cls = kOps[d->ops[k].op].cls;
+        if (cls == OC_CONCAT || cls == OC_SLICE) return lower_layout(d, c, L);
     }
     // Row program: a chain written in basic operators only (element-wise, reduce over the last dimension,
     // broadcast of the reduced value back over its row; paper section 6) whose result has the full shape.
@@ -874,6 +917,7 @@ struct pf_plan_s {
     pf::GroupGeom group;
     pf::PermGeom permg;
     pf::AttnArgs attn;
+    pf::GatherArgs gather;
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -1456,6 +1500,144 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     return PF_OK;
 }
 
+// ---- gather family
+int64_t gcd64(int64_t a, int64_t b) {
+    while (b != 0) {
+        const int64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+
+// Where element `e` (flat index) of value `v` comes from: walks the operators backwards to a chain input.
+void gather_source(const pf_chain_desc* d, const Checked& c, int v, int64_t e, int* in_id, int64_t* in_flat) {
+    const int n_in = d->n_inputs;
+    while (v >= n_in) {
+        const pf_op_desc& o = d->ops[v - n_in];
+        const Shape& os = c.shape[v];
+        const int rank = (int)os.size();
+        if (o.op == PF_RESHAPE) {
+            v = o.src[0];
+            continue;
+        }
+        int64_t idx[PF_MAX_RANK];
+        int64_t rem = e;
+        for (int q = rank - 1; q >= 0; --q) {
+            idx[q] = rem % os[q];
+            rem /= os[q];
+        }
+        int src = o.src[0];
+        int64_t sidx[PF_MAX_RANK];
+        if (o.op == PF_PERMUTE) {
+            for (int q = 0; q < rank; ++q) sidx[o.i[q]] = idx[q];
+        } else if (o.op == PF_SLICE) {
+            for (int q = 0; q < rank; ++q) sidx[q] = idx[q];
+            sidx[o.i[0]] += o.i[1];
+        } else {  // PF_CONCAT
+            for (int q = 0; q < rank; ++q) sidx[q] = idx[q];
+            const int64_t first = c.shape[o.src[0]][o.i[0]];
+            if (idx[o.i[0]] >= first) {
+                src = o.src[1];
+                sidx[o.i[0]] -= first;
+            }
+        }
+        const Shape& ss = c.shape[src];
+        int64_t flat = 0;
+        for (int q = 0; q < rank; ++q) flat = flat * ss[q] + sidx[q];
+        e = flat;
+        v = src;
+    }
+    *in_id = v;
+    *in_flat = e;
+}
+
+pf_status plan_gather(pf_plan_s* p, const Checked& c) {
+    const pf_chain_desc* d = &p->desc;
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const int n_in = d->n_inputs;
+    // Run length: for every value, a length G such that each aligned block of G elements (flat, row-major)
+    // is contiguous inside one chain input.  0 stands for "the whole tensor" (gcd(0, x) = x).
+    std::vector<int64_t> G(n_in + d->n_ops, 0);
+    for (int k = 0; k < d->n_ops; ++k) {
+        const pf_op_desc& o = d->ops[k];
+        const int v = n_in + k;
+        const Shape& os = c.shape[v];
+        const int rank = (int)os.size();
+        int64_t g = G[o.src[0]] ? G[o.src[0]] : numel(c.shape[o.src[0]]);
+        if (o.op == PF_PERMUTE) {
+            int64_t inner = 1;
+            for (int q = rank - 1; q >= 0 && o.i[q] == q; --q) inner *= os[q];
+            g = gcd64(g, inner);
+        } else if (o.op == PF_SLICE) {
+            int64_t inner = 1;
+            for (int q = (int)o.i[0] + 1; q < rank; ++q) inner *= os[q];
+            g = gcd64(gcd64(g, o.i[2] * inner), gcd64(o.i[1] * inner, c.shape[o.src[0]][o.i[0]] * inner));
+        } else if (o.op == PF_CONCAT) {
+            int64_t inner = 1;
+            for (int q = (int)o.i[0] + 1; q < rank; ++q) inner *= os[q];
+            const int64_t g1 = G[o.src[1]] ? G[o.src[1]] : numel(c.shape[o.src[1]]);
+            g = gcd64(gcd64(g, g1), gcd64(c.shape[o.src[0]][o.i[0]] * inner, c.shape[o.src[1]][o.i[0]] * inner));
+        }
+        G[v] = g;
+    }
+    int64_t run = 0, total = 0;
+    for (int o = 0; o < d->n_outputs; ++o) {
+        const int v = d->out_value[o];
+        run = gcd64(run, G[v] ? G[v] : numel(c.shape[v]));
+        total += numel(c.shape[v]);
+    }
+    for (int k = 0; k < n_in; ++k)
+        if (numel(c.shape[k]) > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the gather family");
+    if (total > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the gather family");
+    // very long runs are cut so that the copy has enough workgroups; cuts keep whole vectors
+    while (run > 65536 && run % 2 == 0 && (run / 2) % vec == 0) run /= 2;
+    const int64_t n_runs = total / run;
+    if (n_runs > (1 << 22))
+        return fail(PF_ERR_UNSUPPORTED, "layout chain moves runs of only %lld elements: %lld runs exceed the run table", (long long)run, (long long)n_runs);
+    std::vector<pf::GatherRun> table((size_t)n_runs);
+    size_t at = 0;
+    for (int o = 0; o < d->n_outputs; ++o) {
+        const int v = d->out_value[o];
+        const int64_t n = numel(c.shape[v]);
+        for (int64_t e = 0; e < n; e += run) {
+            int in_id;
+            int64_t in_flat;
+            gather_source(d, c, v, e, &in_id, &in_flat);
+            pf::GatherRun& r = table[at++];
+            r.src_off = (uint32_t)in_flat;
+            r.dst_off = (uint32_t)e;
+            r.src_id = (uint8_t)in_id;
+            r.dst_id = (uint8_t)o;
+            r.pad = 0;
+        }
+    }
+    if (hipSetDevice(p->device) != hipSuccess) return fail(PF_ERR_HIP, "cannot select device %d", p->device);
+    p->workspace_bytes = (uint64_t)n_runs * sizeof(pf::GatherRun);
+    if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "run table allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
+    if (hipMemcpy(p->workspace, table.data(), p->workspace_bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(PF_ERR_HIP, "run table upload failed");
+    pf::GatherArgs& a = p->gather;
+    memset(&a, 0, sizeof(a));
+    a.table = static_cast<const pf::GatherRun*>(p->workspace);
+    a.n_runs = (uint32_t)n_runs;
+    a.run_elems = (uint32_t)run;
+    a.vec_per_run = (uint32_t)((run + vec - 1) / vec);
+    a.div_vpr = make_fastdiv(a.vec_per_run);
+    const uint64_t work = (uint64_t)n_runs * a.vec_per_run;
+    if (work > 0x7fffffffull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the gather family");
+    p->family = PF_FAMILY_GATHER;
+    p->variant = 0;
+    p->k = 1;
+    p->spec_id = 0;
+    p->block = dim3(256);
+    p->grid = dim3((uint32_t)((work + 255) / 256));
+    p->lds_bytes = 0;
+    p->n_launches = 1;
+    return PF_OK;
+}
+
 // ---- attention family
 pf_status plan_attn(pf_plan_s* p) {
     const Lowered& L = p->low;
@@ -1553,7 +1735,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
     memset(&p->permg, 0, sizeof(p->permg));
     memset(&p->attn, 0, sizeof(p->attn));
     s = lower_chain(desc, c, &p->low);
-    if (s == PF_OK && p->low.core != pf::CORE_ATTN_DECODE) {
+    if (s == PF_OK && p->low.core != pf::CORE_ATTN_DECODE && p->low.core != pf::CORE_GATHER) {
         const Lowered& L = p->low;
         p->args.n_full = L.n_full;
         p->args.n_vec = L.n_vec;
@@ -1577,6 +1759,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
             case pf::CORE_GROUPNORM: s = plan_group(p, variant); break;
             case pf::CORE_PERMUTE: s = plan_perm(p, variant); break;
             case pf::CORE_ATTN_DECODE: s = plan_attn(p); break;
+            case pf::CORE_GATHER: s = plan_gather(p, c); break;
             default: s = plan_row(p, variant); break;
         }
     }
@@ -1656,6 +1839,14 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
         at.v_out = L.attn_out[2] >= 0 ? outputs[L.attn_out[2]] : nullptr;
         const hipError_t ea = pf::launch_attn_decode(L.main_dtype, at, plan->k, plan->grid, (hipStream_t)stream);
         if (ea != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ea));
+        return PF_OK;
+    }
+    if (plan->family == PF_FAMILY_GATHER) {
+        pf::GatherArgs ga = plan->gather;
+        for (int k = 0; k < plan->desc.n_inputs; ++k) ga.in[k] = inputs[k];
+        for (int o = 0; o < plan->desc.n_outputs; ++o) ga.out[o] = outputs[o];
+        const hipError_t eg = pf::launch_gather(L.main_dtype, ga, plan->grid, (hipStream_t)stream);
+        if (eg != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(eg));
         return PF_OK;
     }
     pf::ChainArgs a = plan->args;

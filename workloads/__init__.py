@@ -211,7 +211,7 @@ def x2_decode_attention(b: int = 8, h: int = 25, t: int = 1023, d: int = 64, dty
     return c, [quantise(x, dtype) for x in (q, k, v, kc, vc)]
 
 
-def x3_channel_shuffle(n: int = 32, c: int = 232, h: int = 28, w: int = 28, groups: int = 2, dtype: str = "f16",
+def x3_channel_shuffle(n: int = 128, c: int = 232, h: int = 28, w: int = 28, groups: int = 2, dtype: str = "f16",
                        salt: int = 0):
     """concat -> channel shuffle -> split on NCHW tensors (not a BASELINE config; the ShuffleNet fragment of
     the paper's section 2): a, b [n, c/2, h, w]; y = shuffle_groups(concat(a, b)); outputs y[:, :c/2], y[:, c/2:]."""
