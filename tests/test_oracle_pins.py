@@ -556,3 +556,54 @@ def test_channel_shuffle_chain_has_its_closed_form():
     o0, o1 = orc.evaluate_layout_bits(spec, [a, b])
     np.testing.assert_array_equal(o0[0], [a[0, 0], b[0, 0], a[0, 1], b[0, 1]])
     np.testing.assert_array_equal(o1[0], [a[0, 2], b[0, 2], a[0, 3], b[0, 3]])
+
+
+# ---- depthwise convolution (section 6, the EfficientNet fragment) ----
+
+def test_depthwise_convolution_worked_by_hand():
+    # one channel, 3 x 3 image 1..9, kernel with nine different weights: correlation (not flipped), zero padding
+    x = np.arange(1.0, 10.0).reshape(1, 3, 3, 1)
+    k = np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0], [7.0, 8.0, 9.0]]).reshape(3, 3, 1)
+    y = orc.dwconv2d_nhwc(x, k)[0, :, :, 0]
+    # centre: sum_{a,b} k[a,b] x[a,b] = 1*1 + 2*2 + ... + 9*9 = 285
+    assert y[1, 1] == 285.0
+    # top-left output sees x[0:2, 0:2] under k[1:3, 1:3]: 5*1 + 6*2 + 8*4 + 9*5 = 94
+    assert y[0, 0] == 94.0
+    # bottom-right output sees x[1:3, 1:3] under k[0:2, 0:2]: 1*5 + 2*6 + 4*8 + 5*9 = 94
+    assert y[2, 2] == 94.0
+    # top-right: x[0:2, 1:3] under k[1:3, 0:2]: 4*2 + 5*3 + 7*5 + 8*6 = 106 ; bottom-left: x[1:3,0:2] under k[0:2,1:3]
+    assert y[0, 2] == 106.0 and y[2, 0] == 2 * 4 + 3 * 5 + 5 * 7 + 6 * 8
+    # a kernel that is 1 at (row 0, col 1) reads the pixel above: y[i, j] = x[i - 1, j], zero in the first row
+    k = np.zeros((3, 3, 1))
+    k[0, 1, 0] = 1.0
+    y = orc.dwconv2d_nhwc(x, k)[0, :, :, 0]
+    np.testing.assert_array_equal(y, [[0, 0, 0], [1, 2, 3], [4, 5, 6]])
+    # ... and at (row 1, col 2) the pixel to the right
+    k = np.zeros((3, 3, 1))
+    k[1, 2, 0] = 1.0
+    np.testing.assert_array_equal(orc.dwconv2d_nhwc(x, k)[0, :, :, 0], [[2, 3, 0], [5, 6, 0], [8, 9, 0]])
+
+
+def test_depthwise_convolution_against_library_and_invariants():
+    rng = np.random.default_rng(31)
+    for kh, kw in ((3, 3), (5, 5), (1, 3)):
+        x = rng.standard_normal((2, 7, 6, 5))
+        k = rng.standard_normal((kh, kw, 5))
+        y = orc.dwconv2d_nhwc(x, k)
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(k).permute(2, 0, 1)[:, None],
+                                         padding=(kh // 2, kw // 2), groups=5).permute(0, 2, 3, 1).numpy()
+        np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-12)
+        # channels do not mix: changing one channel of x changes only that channel of y
+        x2 = x.copy()
+        x2[..., 3] += 1.0
+        d = orc.dwconv2d_nhwc(x2, k) - y
+        assert np.abs(d[..., [0, 1, 2, 4]]).max() == 0.0 and np.abs(d[..., 3]).max() > 0.0
+    # the centre-one kernel is the identity
+    k = np.zeros((3, 3, 5))
+    k[1, 1] = 1.0
+    np.testing.assert_array_equal(orc.dwconv2d_nhwc(x, k), x)
+    # the chain RELU -> dwconv -> + bias pads with zeros AFTER the activation
+    spec, ins = wl.x4_relu_dwconv(n=1, h=4, w=5, c=8, dtype="f32")
+    xs, ws, bs = [wl.widen(t) for t in ins]
+    got = orc.evaluate_outputs(spec, [xs, ws, bs])[0]
+    np.testing.assert_allclose(got, orc.dwconv2d_nhwc(np.maximum(xs, 0.0), ws) + bs, rtol=1e-14)

@@ -33,6 +33,8 @@ OP_ARITY: Dict[str, int] = {
     "concat_rows": 2, "matvec": 2, "vecmat": 2,
     # layout: concatenation along axis i[0]; slice [i[1], i[1] + i[2]) along axis i[0]
     "concat": 2, "slice": 1,
+    # depthwise convolution of channels-last x [n, h, w, c] with kernels [kh, kw, c], stride 1, "same" zero padding
+    "dwconv2d": 2,
 }
 
 
@@ -211,6 +213,21 @@ def x2_decode_attention(b: int = 8, h: int = 25, t: int = 1023, d: int = 64, dty
     return c, [quantise(x, dtype) for x in (q, k, v, kc, vc)]
 
 
+def x4_relu_dwconv(n: int = 32, h: int = 56, w: int = 56, c: int = 240, k: int = 3, dtype: str = "f16", salt: int = 0):
+    """RELU -> depthwise k x k convolution -> + bias on channels-last x [n, h, w, c] (not a BASELINE config; the
+    EfficientNet fragment of the paper's section 6).  Weights [k, k, c] ~ N(0, 1/k), bias [c] ~ N(0, 1)."""
+    g = _rng(9, salt)
+    x = g.standard_normal((n, h, w, c), dtype=np.float32)
+    wgt = (g.standard_normal((k, k, c), dtype=np.float32) / np.float32(k))
+    bias = g.standard_normal(c, dtype=np.float32)
+    s = ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (k, k, c)), (dtype, (c,))])
+    v = s.op("relu", 0)
+    v = s.op("dwconv2d", v, 1)
+    v = s.op("add", v, 2)
+    s.out(v, dtype)
+    return s, [quantise(x, dtype), quantise(wgt, dtype), quantise(bias, dtype)]
+
+
 def x3_channel_shuffle(n: int = 128, c: int = 232, h: int = 28, w: int = 28, groups: int = 2, dtype: str = "f16",
                        salt: int = 0):
     """concat -> channel shuffle -> split on NCHW tensors (not a BASELINE config; the ShuffleNet fragment of
@@ -235,6 +252,7 @@ CONFIGS = {
     "C4": c4_bias_scale_permute,
     "C5": c5_groupnorm_silu,
     "X1": x1_bias_scale_transpose,      # not a BASELINE config: the innermost-changing transpose, for context
+    "X4": x4_relu_dwconv,               # not a BASELINE config: activation + depthwise convolution
     "X3": x3_channel_shuffle,           # not a BASELINE config: concat -> channel shuffle -> split
     "X2": x2_decode_attention,          # not a BASELINE config: one-token attention against a key-value cache
 }
