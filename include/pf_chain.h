@@ -89,7 +89,12 @@ typedef enum {
        once and are run as one index-map copy with any number of inputs (<= PF_MAX_INPUTS) and outputs          */
     PF_CONCAT = 29,     /* src0, src1 joined along axis i[0] (all other extents equal)                          */
     PF_SLICE = 30,      /* elements [i[1], i[1] + i[2]) of src0 along axis i[0]                                  */
-    PF_OP_COUNT_ = 31
+    /* depthwise convolution (section 6, the EfficientNet fragment): src0 x [n, h, w, c] channels-last, src1
+       kernels [kh, kw, c] (a chain input); cross-correlation, stride 1, zero padding that keeps h and w.
+       Implemented for kh = kw = 3.  Element-wise operators may precede it (they run before the padding) and
+       follow it.                                                                                             */
+    PF_DWCONV2D = 31,
+    PF_OP_COUNT_ = 32
 } pf_op;
 
 /* A contiguous row-major tensor. */
@@ -134,6 +139,7 @@ typedef enum {
     PF_FAMILY_ROW = 1,         /* row reduction then broadcast: wave shuffle, LDS when a row spans waves     */
     PF_FAMILY_GROUP = 2,       /* GroupNorm: a group spans workgroups, partial statistics cross the device   */
     PF_FAMILY_TRANSPOSE = 3,   /* layout change staged through an LDS tile                                   */
+    PF_FAMILY_STENCIL = 6,     /* depthwise convolution: overlapping reads kept on chip in a register window         */
     PF_FAMILY_GATHER = 5,      /* layout-only chains (concat / slice / permute / reshape): a copy driven by a table
                                   of contiguous runs computed when the plan is made                          */
     PF_FAMILY_ATTENTION = 4    /* one-token attention: a head's rows span workgroups, partial results are

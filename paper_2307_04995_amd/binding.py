@@ -27,9 +27,9 @@ DTYPE_CODE = {"f32": PF_F32, "f16": PF_F16, "bf16": PF_BF16}
 OP_CODE = {name: i for i, name in enumerate([
     "add", "sub", "mul", "div", "max", "min", "scale", "addc", "neg", "relu", "sigmoid", "silu", "gelu_erf",
     "tanh", "exp", "rsqrt", "causal_mask", "reduce_sum", "reduce_max", "reduce_mean", "softmax", "layernorm",
-    "rmsnorm", "groupnorm", "permute", "reshape", "concat_rows", "matvec", "vecmat", "concat", "slice"])}
+    "rmsnorm", "groupnorm", "permute", "reshape", "concat_rows", "matvec", "vecmat", "concat", "slice", "dwconv2d"])}
 # pf_family
-PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE, PF_FAMILY_ATTENTION, PF_FAMILY_GATHER = range(6)
+PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE, PF_FAMILY_ATTENTION, PF_FAMILY_GATHER, PF_FAMILY_STENCIL = range(7)
 PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK, PF_VARIANT_ROW_STREAM = 0, 1, 2
 PF_SPEC_GENERIC, PF_SPEC_JIT = 0, 255
 PF_VARIANT_GROUP_TWO_PASS, PF_VARIANT_GROUP_RESIDENT = 0, 1

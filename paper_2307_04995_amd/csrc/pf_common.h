@@ -93,6 +93,7 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
     CORE_PERMUTE = 8,
+    CORE_DWCONV = 12,       // depthwise convolution (stencil family); core_vec[0] = slot of the kernels
     CORE_GATHER = 11,       // layout-only chain with concatenations / slices
     CORE_ATTN_DECODE = 10,  // concat -> matrix-vector -> softmax -> concat -> vector-matrix (one-token attention)
     CORE_ROWPROG = 9   // no fixed core: the prologue itself holds row reductions (U_RED_*) and their broadcasts
@@ -168,6 +169,15 @@ struct AttnArgs {
     uint32_t d;           // head dimension (elements), at most 256
     uint32_t lanes_per_row, log2_lpr;
     float scale;
+};
+
+// Stencil family (depthwise 3 x 3 convolution on a channels-last tensor) geometry.
+struct StencilGeom {
+    uint32_t n, h, w, c;
+    uint32_t cv;        // 16-byte vectors per position (c / VEC)
+    uint32_t row_vecs;  // w * cv: lanes needed for one image row
+    uint32_t epi_full_mask, epi_vec_mask;  // operands that belong to the epilogue (read at the output position)
+    FastDiv div_cv;
 };
 
 // Gather family: layout-only chains as a copy of contiguous runs.  Run k of the table moves run_elems elements

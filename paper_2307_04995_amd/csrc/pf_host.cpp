@@ -43,7 +43,7 @@ pf_status fail(pf_status s, const char* fmt, ...) {
 }
 
 enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE,
-               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT, OC_CONCAT, OC_SLICE };
+               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT, OC_CONCAT, OC_SLICE, OC_DWCONV };
 
 struct OpTraits {
     OpClass cls;
@@ -60,7 +60,7 @@ const OpTraits kOps[PF_OP_COUNT_] = {
     {OC_SOFTMAX, 1, "softmax"}, {OC_LAYERNORM, 3, "layernorm"}, {OC_RMSNORM, 2, "rmsnorm"}, {OC_GROUPNORM, 3, "groupnorm"},
     {OC_PERMUTE, 1, "permute"}, {OC_RESHAPE, 1, "reshape"},
     {OC_CONCAT_ROWS, 2, "concat_rows"}, {OC_MATVEC, 2, "matvec"}, {OC_VECMAT, 2, "vecmat"},
-    {OC_CONCAT, 2, "concat"}, {OC_SLICE, 1, "slice"},
+    {OC_CONCAT, 2, "concat"}, {OC_SLICE, 1, "slice"}, {OC_DWCONV, 2, "dwconv2d"},
 };
 
 bool is_elementwise(OpClass c) { return c == OC_BINARY || c == OC_UNARY || c == OC_MASK; }
@@ -188,6 +188,13 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 r = a;
                 if (tr.cls == OC_CONCAT_ROWS) r[r.size() - 2] += 1;
                 else r.pop_back();
+                break;
+            }
+            case OC_DWCONV: {
+                const Shape& b = sh[o.src[1]];
+                if (a.size() != 4 || b.size() != 3 || b[2] != a[3]) return fail(PF_ERR_SHAPE, "op %d (dwconv2d): needs x [n, h, w, c] and kernels [kh, kw, c]", k);
+                if (b[0] % 2 == 0 || b[1] % 2 == 0) return fail(PF_ERR_SHAPE, "op %d (dwconv2d): kernel extents must be odd", k);
+                r = a;
                 break;
             }
             case OC_CONCAT: {
@@ -750,6 +757,7 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
             case PF_REDUCE_SUM: L->core = pf::CORE_REDUCE_SUM; break;
             case PF_REDUCE_MAX: L->core = pf::CORE_REDUCE_MAX; break;
             case PF_REDUCE_MEAN: L->core = pf::CORE_REDUCE_MEAN; break;
+            case PF_DWCONV2D: L->core = pf::CORE_DWCONV; break;
             case PF_PERMUTE:
                 L->core = pf::CORE_PERMUTE;
                 for (int q = 0; q < o.n_i; ++q) L->perm[q] = (int)o.i[q];
@@ -918,6 +926,7 @@ struct pf_plan_s {
     pf::PermGeom permg;
     pf::AttnArgs attn;
     pf::GatherArgs gather;
+    pf::StencilGeom stencil;
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -932,6 +941,8 @@ struct pf_plan_s {
 };
 
 namespace {
+
+constexpr int kStencilRowsHost = 6;  // output rows per strip of the stencil kernel (kStencilRows on the device side)
 
 int env_int(const char* name, int dflt) {
     const char* s = getenv(name);
@@ -1500,6 +1511,55 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     return PF_OK;
 }
 
+// ---- stencil family
+pf_status plan_stencil(pf_plan_s* p, const Checked& c) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype);
+    const int vec = 16 / es;
+    const Shape& xs = L.pre_shape;  // [n, h, w, c]
+    const Shape& ks = c.shape[p->desc.ops[L.core_op].src[1]];
+    if (ks[0] != 3 || ks[1] != 3) return fail(PF_ERR_UNSUPPORTED, "dwconv2d: only 3 x 3 kernels are implemented (got %lld x %lld)", (long long)ks[0], (long long)ks[1]);
+    const int64_t n = xs[0], h = xs[1], w = xs[2], ch = xs[3];
+    if ((ch * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)ch);
+    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the stencil family is not a multiple of 16 bytes");
+    if (n * h * w > 0xffffffffLL || n > 65535 || (h + kStencilRowsHost - 1) / kStencilRowsHost > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
+    if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the stencil family");
+    for (int i = 0; i < L.pro.n; ++i)
+        if (L.pro.u[i].code == pf::U_MASK_CAUSAL) return fail(PF_ERR_UNSUPPORTED, "causal_mask next to a convolution is not implemented");
+    for (int i = 0; i < L.epi.n; ++i)
+        if (L.epi.u[i].code == pf::U_MASK_CAUSAL) return fail(PF_ERR_UNSUPPORTED, "causal_mask next to a convolution is not implemented");
+    pf::StencilGeom& g = p->stencil;
+    memset(&g, 0, sizeof(g));
+    g.n = (uint32_t)n;
+    g.h = (uint32_t)h;
+    g.w = (uint32_t)w;
+    g.c = (uint32_t)ch;
+    g.cv = (uint32_t)(ch / vec);
+    g.row_vecs = (uint32_t)(w * g.cv);
+    g.div_cv = make_fastdiv(g.cv);
+    for (int f = 0; f < L.n_full; ++f)
+        if (L.full_is_epi[f]) g.epi_full_mask |= 1u << f;
+    for (int v = 0; v < L.n_vec; ++v)
+        if (L.vec_is_epi[v]) g.epi_vec_mask |= 1u << v;
+    p->family = PF_FAMILY_STENCIL;
+    p->variant = 0;
+    p->k = 1;
+    p->spec_id = 0;
+    p->block = dim3(256);
+    p->grid = dim3((g.row_vecs + 255u) / 256u, (uint32_t)((h + kStencilRowsHost - 1) / kStencilRowsHost), (uint32_t)n);
+    p->lds_bytes = 0;
+    p->n_launches = 1;
+    p->args.n_inner = (uint32_t)ch;
+    p->args.rows = (uint64_t)(n * h * w);
+    if (jit_possible(p->device)) {
+        std::string err;
+        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, make_jit_spec(L), &err);
+        if (p->jit_fn) p->spec_id = pf::kSpecJit;
+        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+    }
+    return PF_OK;
+}
+
 // ---- gather family
 int64_t gcd64(int64_t a, int64_t b) {
     while (b != 0) {
@@ -1760,6 +1820,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
             case pf::CORE_PERMUTE: s = plan_perm(p, variant); break;
             case pf::CORE_ATTN_DECODE: s = plan_attn(p); break;
             case pf::CORE_GATHER: s = plan_gather(p, c); break;
+            case pf::CORE_DWCONV: s = plan_stencil(p, c); break;
             default: s = plan_row(p, variant); break;
         }
     }
@@ -1898,6 +1959,15 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             }
             break;
         }
+        case PF_FAMILY_STENCIL:
+            if (plan->spec_id == pf::kSpecJit) {
+                pf::StencilGeom g = plan->stencil;
+                void* params[] = {&a, &g};
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
+            } else {
+                e = pf::launch_stencil(L.main_dtype, a, plan->stencil, plan->grid, st);
+            }
+            break;
         case PF_FAMILY_TRANSPOSE:
             if (plan->spec_id == pf::kSpecJit) {
                 pf::PermGeom g = plan->permg;

@@ -178,6 +178,12 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, const J
     return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
 }
 
+hipFunction_t jit_stencil_kernel(int device, int dtype, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::dwconv3x3_kernel<" << dtype << ", " << spec_text(spec) << ">";
+    return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
+}
+
 int jit_blocks_per_cu(hipFunction_t fn, int block_threads) {
     int n = 0;
     if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, block_threads, 0) != hipSuccess) return 0;

@@ -1,0 +1,75 @@
+"""GPU parity for the stencil family: element-wise steps fused around a depthwise 3 x 3 convolution on a
+channels-last tensor (the EfficientNet fragment), through the C ABI, element by element against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from pf_testlib import check_chain, SPEC_JIT
+
+pytestmark = pytest.mark.gpu
+
+
+def _pf():
+    from paper_2307_04995_amd import binding as pf
+    return pf
+
+
+@pytest.mark.parametrize("n,h,w,c,dtype", [(2, 13, 11, 64, "f16"), (1, 7, 7, 240, "f16"), (3, 5, 9, 8, "f32"), (1, 20, 3, 144, "bf16"),
+                                           (1, 1, 1, 16, "f16"), (2, 6, 6, 32, "f32"), (1, 1, 40, 24, "bf16"), (1, 19, 1, 8, "f16")])
+def test_relu_depthwise_conv_bias(n, h, w, c, dtype):
+    spec, ins = wl.x4_relu_dwconv(n=n, h=h, w=w, c=c, dtype=dtype)
+    _, info, _ = check_chain(spec, ins, what=f"relu -> dwconv -> bias [{n},{h},{w},{c}] {dtype}")
+    pf = _pf()
+    assert info.family == pf.PF_FAMILY_STENCIL and info.n_launches == 1
+    assert info.spec_id == SPEC_JIT
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_convolution_alone_and_asymmetric_kernel(dtype):
+    # distinct weights in all nine taps, no other operator: tap order and padding show directly
+    n, h, w, c = 1, 9, 10, 16
+    x = wl.random_tensor((n, h, w, c), dtype, 1301)
+    k = wl.quantise(np.arange(1, 10, dtype=np.float32).reshape(3, 3, 1).repeat(c, 2) / 16.0, dtype)
+    spec = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (3, 3, c))])
+    spec.out(spec.op("dwconv2d", 0, 1), dtype)
+    check_chain(spec, [x, k], what="dwconv alone")
+
+
+def test_operands_on_both_sides_of_the_convolution():
+    # y = silu(dwconv(relu(x + shift[c])) + bias[c]) + res: a broadcast operand before the convolution, a
+    # broadcast and a full-shape operand after it
+    dtype = "f16"
+    n, h, w, c = 2, 11, 7, 48
+    x = wl.random_tensor((n, h, w, c), dtype, 1311)
+    shift = wl.random_tensor((c,), dtype, 1312, scale=0.5)
+    k = wl.random_tensor((3, 3, c), dtype, 1313, scale=0.3)
+    bias = wl.random_tensor((c,), dtype, 1314, scale=0.5)
+    res = wl.random_tensor((n, h, w, c), dtype, 1315, scale=0.5)
+    s = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (c,)), (dtype, (3, 3, c)), (dtype, (c,)), (dtype, (n, h, w, c))])
+    v = s.op("relu", s.op("add", 0, 1))
+    v = s.op("dwconv2d", v, 2)
+    v = s.op("silu", s.op("add", v, 3))
+    s.out(s.op("add", v, 4), dtype)
+    check_chain(s, [x, shift, k, bias, res], what="operands on both sides of a dwconv")
+
+
+def test_padding_comes_after_the_activation():
+    # sigmoid(0) = 0.5: if the padding were applied before the activation the border would see 0.5, not 0
+    dtype = "f32"
+    n, h, w, c = 1, 4, 4, 8
+    x = wl.random_tensor((n, h, w, c), dtype, 1321)
+    k = wl.quantise(np.ones((3, 3, c), dtype=np.float32), dtype)
+    s = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (3, 3, c))])
+    s.out(s.op("dwconv2d", s.op("sigmoid", 0), 1), dtype)
+    check_chain(s, [x, k], what="sigmoid -> dwconv")
+
+
+def test_other_kernel_sizes_are_refused():
+    pf = _pf()
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (5, 5, 16))])
+    s.out(s.op("dwconv2d", 0, 1), "f16")
+    st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
+    assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (3, 3, 8))])
+    s.out(s.op("dwconv2d", 0, 1), "f16")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
