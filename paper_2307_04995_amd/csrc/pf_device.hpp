@@ -403,6 +403,29 @@ struct StaticSpec {
 
 constexpr int at_least_1(int n) { return n < 1 ? 1 : n; }
 
+// Facts about a static step list that kernels can use at compile time.
+// Which slots of operand kind `kind` the list reads (bit per slot).
+template <class L>
+constexpr uint32_t list_operand_mask(int kind) {
+    uint32_t m = 0;
+    for (int i = 0; i < L::n; ++i)
+        if (L::at(i).kind == kind) m |= 1u << L::at(i).slot;
+    return m;
+}
+// Whether the list only loads one full operand and applies steps whose results are again exactly representable
+// in the storage type (so they can be kept packed without changing any later result).
+template <class L>
+constexpr bool list_keeps_storage_precision() {
+    if (L::kDynamic || L::n < 1) return false;
+    for (int i = 0; i < L::n; ++i) {
+        const UopC u = L::at(i);
+        const bool load = u.code == U_MOV && u.kind == K_FULL && i == 0;
+        const bool exact = (u.code == U_RELU || u.code == U_NEG) && i > 0;
+        if (!load && !exact) return false;
+    }
+    return true;
+}
+
 // ---------------------------------------------------------------------------------------------
 // per-lane state: K 16-byte vectors of every operand, an fp32 accumulator, temporaries
 // ---------------------------------------------------------------------------------------------

@@ -1512,7 +1512,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
 }
 
 // ---- stencil family
-pf_status plan_stencil(pf_plan_s* p, const Checked& c) {
+pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype);
     const int vec = 16 / es;
@@ -1542,20 +1542,47 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c) {
     for (int v = 0; v < L.n_vec; ++v)
         if (L.vec_is_epi[v]) g.epi_vec_mask |= 1u << v;
     p->family = PF_FAMILY_STENCIL;
-    p->variant = 0;
     p->k = 1;
     p->spec_id = 0;
     p->block = dim3(256);
     p->grid = dim3((g.row_vecs + 255u) / 256u, (uint32_t)((h + kStencilRowsHost - 1) / kStencilRowsHost), (uint32_t)n);
-    p->lds_bytes = 0;
     p->n_launches = 1;
     p->args.n_inner = (uint32_t)ch;
     p->args.rows = (uint64_t)(n * h * w);
-    if (jit_possible(p->device)) {
+    // Staged variant (values activated once, shared through an LDS tile) when the tile fits; its entries are
+    // packed in the storage type if the prologue keeps storage precision and the kernel is specialised.
+    const bool jit_ok = jit_possible(p->device);
+    bool exact_pro = L.main_dtype != PF_F32 && L.pro.n >= 1 && L.pro.u[0].code == pf::U_MOV && L.pro.u[0].kind == pf::K_FULL;
+    for (int i = 1; i < L.pro.n; ++i)
+        if (L.pro.u[i].code != pf::U_RELU && L.pro.u[i].code != pf::U_NEG) exact_pro = false;
+    const uint32_t entry_bytes = (L.main_dtype == PF_F32 || (exact_pro && jit_ok)) ? 16u : 32u;
+    const uint64_t tile_bytes = (uint64_t)(kStencilRowsHost + 2) * (256u + 2u * g.cv) * entry_bytes;
+    const uint64_t lds_limit = 64 * 1024;  // per workgroup
+    const bool staged_ok = tile_bytes <= lds_limit;
+    int variant = forced_variant >= 0 ? forced_variant : (staged_ok ? PF_VARIANT_STENCIL_STAGED : PF_VARIANT_STENCIL_DIRECT);
+    if (variant != PF_VARIANT_STENCIL_STAGED && variant != PF_VARIANT_STENCIL_DIRECT) return fail(PF_ERR_UNSUPPORTED, "unknown stencil variant %d", variant);
+    if (variant == PF_VARIANT_STENCIL_STAGED && !staged_ok)
+        return fail(PF_ERR_UNSUPPORTED, "the staged variant needs an LDS tile of %llu bytes (limit %llu)", (unsigned long long)tile_bytes,
+                    (unsigned long long)lds_limit);
+    p->variant = variant;
+    p->lds_bytes = variant == PF_VARIANT_STENCIL_STAGED ? (uint32_t)tile_bytes : 0u;
+    if (jit_ok) {
         std::string err;
-        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, make_jit_spec(L), &err);
+        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
-        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        else {
+            if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+            // the interpreted kernel never packs its tile
+            if (variant == PF_VARIANT_STENCIL_STAGED && entry_bytes == 16u && L.main_dtype != PF_F32) {
+                const uint64_t big = tile_bytes * 2;
+                if (big > lds_limit) {
+                    p->variant = PF_VARIANT_STENCIL_DIRECT;
+                    p->lds_bytes = 0;
+                } else {
+                    p->lds_bytes = (uint32_t)big;
+                }
+            }
+        }
     }
     return PF_OK;
 }
@@ -1820,7 +1847,7 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
             case pf::CORE_PERMUTE: s = plan_perm(p, variant); break;
             case pf::CORE_ATTN_DECODE: s = plan_attn(p); break;
             case pf::CORE_GATHER: s = plan_gather(p, c); break;
-            case pf::CORE_DWCONV: s = plan_stencil(p, c); break;
+            case pf::CORE_DWCONV: s = plan_stencil(p, c, variant); break;
             default: s = plan_row(p, variant); break;
         }
     }
@@ -1963,9 +1990,9 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (plan->spec_id == pf::kSpecJit) {
                 pf::StencilGeom g = plan->stencil;
                 void* params[] = {&a, &g};
-                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, plan->lds_bytes, params, st);
             } else {
-                e = pf::launch_stencil(L.main_dtype, a, plan->stencil, plan->grid, st);
+                e = pf::launch_stencil(L.main_dtype, a, plan->stencil, plan->variant, plan->lds_bytes, plan->grid, st);
             }
             break;
         case PF_FAMILY_TRANSPOSE:

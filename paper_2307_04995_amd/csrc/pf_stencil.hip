@@ -4,14 +4,20 @@
 
 namespace pf {
 
-hipError_t launch_stencil(int dtype, const ChainArgs& a, const StencilGeom& g, dim3 grid, hipStream_t st) {
+template <int DT>
+static hipError_t launch_stencil_dt(const ChainArgs& a, const StencilGeom& g, int variant, uint32_t lds, dim3 grid, hipStream_t st) {
+    if (variant == 1) hipLaunchKernelGGL((dwconv3x3_staged_kernel<DT, GenericSpec>), grid, dim3(256), lds, st, a, g);
+    else hipLaunchKernelGGL((dwconv3x3_kernel<DT, GenericSpec>), grid, dim3(256), 0, st, a, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_stencil(int dtype, const ChainArgs& a, const StencilGeom& g, int variant, uint32_t lds, dim3 grid, hipStream_t st) {
     switch (dtype) {
-        case DT_F32: hipLaunchKernelGGL((dwconv3x3_kernel<DT_F32, GenericSpec>), grid, dim3(256), 0, st, a, g); break;
-        case DT_F16: hipLaunchKernelGGL((dwconv3x3_kernel<DT_F16, GenericSpec>), grid, dim3(256), 0, st, a, g); break;
-        case DT_BF16: hipLaunchKernelGGL((dwconv3x3_kernel<DT_BF16, GenericSpec>), grid, dim3(256), 0, st, a, g); break;
+        case DT_F32: return launch_stencil_dt<DT_F32>(a, g, variant, lds, grid, st);
+        case DT_F16: return launch_stencil_dt<DT_F16>(a, g, variant, lds, grid, st);
+        case DT_BF16: return launch_stencil_dt<DT_BF16>(a, g, variant, lds, grid, st);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace pf

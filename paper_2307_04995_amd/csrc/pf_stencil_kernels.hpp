@@ -37,47 +37,91 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
     for (int k = 0; k < 9; ++k)
         wraw[k] = load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE);
 
+    // which operands each side of the convolution reads: known at compile time for a specialised kernel
+    const uint32_t pro_full = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_FULL) : ~g.epi_full_mask;
+    const uint32_t pro_vec = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_VEC) : ~g.epi_vec_mask;
+    const uint32_t epi_full = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_FULL) : g.epi_full_mask;
+    const uint32_t epi_vec = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_VEC) : g.epi_vec_mask;
+    // When the prologue only loads and applies steps that stay exact in the storage type (RELU in front of the
+    // convolution is the standard case), the window holds the activated values packed: half the registers.
+    constexpr bool kPacked = DT != DT_F32 && list_keeps_storage_precision<typename Spec::Pro>();
+    constexpr int WE = kPacked ? 4 : VEC;  // 32-bit words per window entry
+
     LaneState<DT, 1, Spec> s;
     s.col[0] = cvi * VEC;
-    // operands of one position: prologue side (is_epi = false) or epilogue side
-    auto load_operands = [&](uint32_t pos, bool is_epi) {
+    // the epilogue's operands, read at the output position
+    auto load_epilogue_operands = [&](uint32_t pos) {
         s.row[0] = pos;
-        const uint32_t fmask = is_epi ? g.epi_full_mask : ~g.epi_full_mask;
-        const uint32_t vmask = is_epi ? g.epi_vec_mask : ~g.epi_vec_mask;
 #pragma unroll
         for (int f = 0; f < Spec::NF; ++f)
-            if (f < Spec::n_full(a) && ((fmask >> f) & 1u))
+            if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
                 s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
-            if (v < Spec::n_vec(a) && v != wslot && ((vmask >> v) & 1u))
+            if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
                 s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], pos, s.col[0], g.c);
     };
 
-    float win[3][3][VEC];  // activated values: window row (input row mod 3), column offset -1 / 0 / +1
-    // bring input row r (may lie outside the image) into its window row
-    auto load_row = [&](int r, int slot) {
+    uint32_t win[3][3][WE];  // activated values (fp32 bits, or packed): window row (input row mod 3), column -1 / 0 / +1
+    // An input row enters the window in two steps so that its loads are in flight while the previous output
+    // row is computed: fetch_row issues the loads of the three columns, admit_row runs the prologue on them.
+    u32x4 pend_f[3][at_least_1(Spec::NF)], pend_v[3][at_least_1(Spec::NV)];
+    auto inside_image = [&](int r, int dw) {
+        const int col = (int)wcol + dw - 1;
+        return r >= 0 && r < (int)g.h && col >= 0 && col < (int)g.w;
+    };
+    auto fetch_row = [&](int r) {
 #pragma unroll
         for (int dw = 0; dw < 3; ++dw) {
-            const int col = (int)wcol + dw - 1;
-            const bool inside = r >= 0 && r < (int)g.h && col >= 0 && col < (int)g.w;
+            if (!inside_image(r, dw)) continue;
+            const uint32_t pos = (sample * g.h + (uint32_t)r) * g.w + (uint32_t)((int)wcol + dw - 1);
+#pragma unroll
+            for (int f = 0; f < Spec::NF; ++f)
+                if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
+                    pend_f[dw][f] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+#pragma unroll
+            for (int v = 0; v < Spec::NV; ++v)
+                if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
+                    pend_v[dw][v] = load_vec_operand<DT>(a.vec[v], pos, s.col[0], g.c);
+        }
+    };
+    auto admit_row = [&](int r, int slot) {
+#pragma unroll
+        for (int dw = 0; dw < 3; ++dw) {
+            const bool inside = inside_image(r, dw);
             if (inside) {
-                load_operands((sample * g.h + (uint32_t)r) * g.w + (uint32_t)col, false);
+                s.row[0] = (sample * g.h + (uint32_t)r) * g.w + (uint32_t)((int)wcol + dw - 1);
+#pragma unroll
+                for (int f = 0; f < Spec::NF; ++f)
+                    if (f < Spec::n_full(a) && ((pro_full >> f) & 1u)) s.fraw[f][0] = pend_f[dw][f];
+#pragma unroll
+                for (int v = 0; v < Spec::NV; ++v)
+                    if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u)) s.vraw[v][0] = pend_v[dw][v];
                 run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
             }
+            if (kPacked) {
+                const u32x4 packed = S::pack(s.acc);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) win[slot][dw][e] = inside ? s.acc[e] : 0.0f;
+                for (int e = 0; e < 4; ++e) win[slot][dw][e] = inside ? packed[e] : 0u;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) win[slot][dw][e % WE] = inside ? __builtin_bit_cast(uint32_t, s.acc[e]) : 0u;
+            }
         }
     };
 
-    load_row((int)h0 - 1, 2);  // input row h0 - 1 sits in slot (h0 - 1 + 3) mod 3 relative to h0: see below
-    load_row((int)h0, 0);
-    // relative numbering: input row h0 + k lives in slot k mod 3 (k = -1 -> slot 2)
+    // relative numbering: input row h0 + k lives in window row k mod 3 (k = -1 -> 2)
+    fetch_row((int)h0 - 1);
+    admit_row((int)h0 - 1, 2);
+    fetch_row((int)h0);
+    admit_row((int)h0, 0);
+    fetch_row((int)h0 + 1);
 #pragma unroll
     for (int i = 0; i < kStencilRows; ++i) {
         const uint32_t row = h0 + (uint32_t)i;
         if (row >= g.h) break;
-        load_row((int)row + 1, (i + 1) % 3);
+        admit_row((int)row + 1, (i + 1) % 3);
+        if (i + 1 < kStencilRows) fetch_row((int)row + 2);  // in flight during this row's arithmetic
         float acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
@@ -86,14 +130,178 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
             const int slot = (i + dh + 2) % 3;  // input row row + dh - 1 = h0 + (i + dh - 1)
 #pragma unroll
             for (int dw = 0; dw < 3; ++dw) {
-                float wf[VEC];
+                float wf[VEC], xf[VEC];
                 S::unpack(wraw[dh * 3 + dw], wf);
+                if (kPacked) {
+                    S::unpack(u32x4{win[slot][dw][0], win[slot][dw][1 % WE], win[slot][dw][2 % WE], win[slot][dw][3 % WE]}, xf);
+                } else {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[e], win[slot][dw][e], acc[e]);
+                    for (int e = 0; e < VEC; ++e) xf[e] = __builtin_bit_cast(float, win[slot][dw][e % WE]);
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[e], xf[e], acc[e]);
             }
         }
         const uint32_t pos = (sample * g.h + row) * g.w + wcol;
-        load_operands(pos, true);
+        load_epilogue_operands(pos);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
+        store_stream(a.out[0], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE, S::pack(s.acc));
+    }
+}
+
+// Staged variant: the workgroup activates every input value of its tile ONCE and shares it through LDS.
+//
+// The direct variant above runs the prologue on each of the three columns a lane reads per input row, i.e.
+// three times per input value, and its neighbouring columns come from the cache.  Here a workgroup first
+// brings the eight input rows of its strip, for its 256 lanes plus a halo of one image column on either side,
+// through the prologue and into an LDS tile (one barrier), then every lane reads its nine taps per output row
+// from the tile.  The prologue runs about 1.3 times per input value (halo rows and columns), the loads of a
+// whole strip are in flight together, and no window lives in registers.
+//
+// LDS layout: tile[input row 0..7][staging lane 0 .. 256 + 2 cv), entries of 16 bytes (packed storage type, when
+// the prologue keeps storage precision) or 32 bytes (fp32).  Lanes read consecutive entries: no bank conflicts.
+template <int DT, class Spec>
+__global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a, const StencilGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr bool kPacked = DT != DT_F32 && list_keeps_storage_precision<typename Spec::Pro>();
+    constexpr int EV = (kPacked || DT == DT_F32) ? 1 : 2;  // 16-byte vectors per tile entry
+    constexpr int kRows = kStencilRows + 2;
+    extern __shared__ u32x4 tile[];
+
+    const uint32_t t0 = blockIdx.x * 256u;  // first (column, channel vector) lane of this workgroup
+    const uint32_t sample = blockIdx.z;
+    const uint32_t h0 = blockIdx.y * (uint32_t)kStencilRows;
+    const int wslot = Spec::gamma(a);
+    const uint32_t cv = g.cv;
+    const uint32_t tw = 256u + 2u * cv;  // staging lanes per row
+    const uint32_t pro_full = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_FULL) : ~g.epi_full_mask;
+    const uint32_t pro_vec = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_VEC) : ~g.epi_vec_mask;
+    const uint32_t epi_full = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_FULL) : g.epi_full_mask;
+    const uint32_t epi_vec = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_VEC) : g.epi_vec_mask;
+
+    LaneState<DT, 1, Spec> s;
+
+    // ---- stage: staging lane j of input row h0 - 1 + r holds image lane t0 - cv + j
+    for (uint32_t j = threadIdx.x; j < tw; j += 256u) {
+        const int64_t lane_pos = (int64_t)t0 - cv + j;
+        const bool lane_ok = lane_pos >= 0 && lane_pos < (int64_t)g.row_vecs;
+        const uint32_t lp = lane_ok ? (uint32_t)lane_pos : 0u;
+        const uint32_t wcol = fast_div(lp, g.div_cv);
+        const uint32_t cvi = lp - wcol * cv;
+        s.col[0] = cvi * VEC;
+        u32x4 pend_f[kRows][at_least_1(Spec::NF)];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const int row = (int)h0 - 1 + r;
+            const bool ok = lane_ok && row >= 0 && row < (int)g.h;
+            const uint32_t pos = (sample * g.h + (uint32_t)(ok ? row : 0)) * g.w + wcol;
+#pragma unroll
+            for (int f = 0; f < Spec::NF; ++f) {
+                pend_f[r][f] = u32x4{0u, 0u, 0u, 0u};
+                if (f < Spec::n_full(a) && ((pro_full >> f) & 1u) && ok)
+                    pend_f[r][f] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const int row = (int)h0 - 1 + r;
+            const bool ok = lane_ok && row >= 0 && row < (int)g.h;
+            if (ok) {
+                s.row[0] = (sample * g.h + (uint32_t)row) * g.w + wcol;
+#pragma unroll
+                for (int f = 0; f < Spec::NF; ++f)
+                    if (f < Spec::n_full(a) && ((pro_full >> f) & 1u)) s.fraw[f][0] = pend_f[r][f];
+#pragma unroll
+                for (int v = 0; v < Spec::NV; ++v)
+                    if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
+                        s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], s.row[0], s.col[0], g.c);
+                run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
+            }
+            u32x4* dst = tile + ((uint32_t)r * tw + j) * EV;
+            if (kPacked) {
+                dst[0] = ok ? S::pack(s.acc) : u32x4{0u, 0u, 0u, 0u};
+            } else {
+#pragma unroll
+                for (int q = 0; q < EV; ++q) {
+                    u32x4 w4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w4[e] = ok ? __builtin_bit_cast(uint32_t, s.acc[(q * 4 + e) % VEC]) : 0u;
+                    dst[q] = w4;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- compute: lane t0 + tid, six output rows, nine taps each from the tile
+    const uint32_t t = t0 + threadIdx.x;
+    if (t >= g.row_vecs) return;
+    const uint32_t wcol = fast_div(t, g.div_cv);
+    const uint32_t cvi = t - wcol * cv;
+    s.col[0] = cvi * VEC;
+    // fp16 tile entries meet fp16 kernels: the multiply-add takes both halves of the packed registers directly
+    // (v_fma_mix_f32 widens them on the fly), so nothing is unpacked in the inner loop
+    constexpr bool kMix = kPacked && DT == DT_F16;
+    u32x4 wraw[9];
+    float wf[kMix ? 1 : 9][VEC];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) {
+        wraw[k] = load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE);
+        if (!kMix) S::unpack(wraw[k], wf[k % (kMix ? 1 : 9)]);
+    }
+#pragma unroll
+    for (int i = 0; i < kStencilRows; ++i) {
+        const uint32_t row = h0 + (uint32_t)i;
+        if (row >= g.h) break;
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int dh = 0; dh < 3; ++dh)
+#pragma unroll
+            for (int dw = 0; dw < 3; ++dw) {
+                const u32x4* src = tile + ((uint32_t)(i + dh) * tw + threadIdx.x + (uint32_t)dw * cv) * EV;
+                if (kMix) {
+                    const u32x4 xv = src[0];
+                    const u32x4 wv = wraw[dh * 3 + dw];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t xp = xv[j], wp = wv[j];
+                        asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "+v"(acc[(2 * j) % VEC]) : "v"(xp), "v"(wp));
+                        asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "+v"(acc[(2 * j + 1) % VEC]) : "v"(xp), "v"(wp));
+                    }
+                    continue;
+                }
+                float xf[VEC];
+                if (kPacked) {
+                    S::unpack(src[0], xf);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < EV; ++q) {
+                        const u32x4 w4 = src[q];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t bits = w4[e];  // (a bit cast applied directly to a vector element is miscompiled)
+                            if (q * 4 + e < VEC) xf[(q * 4 + e) % VEC] = __builtin_bit_cast(float, bits);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[(dh * 3 + dw) % (kMix ? 1 : 9)][e], xf[e], acc[e]);
+            }
+        const uint32_t pos = (sample * g.h + row) * g.w + wcol;
+        s.row[0] = pos;
+#pragma unroll
+        for (int f = 0; f < Spec::NF; ++f)
+            if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
+                s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+#pragma unroll
+        for (int v = 0; v < Spec::NV; ++v)
+            if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
+                s.vraw[v][0] = load_vec_operand<DT>(a.vec[v], pos, s.col[0], g.c);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});

@@ -102,7 +102,14 @@ def check_chain(spec, inputs, variant=None, generic=False, what=""):
     if not generic and info.spec_id == SPEC_JIT:
         # the chain is not in the built-in catalogue and got a kernel of its own: the run-time-interpreted
         # kernel it would have used otherwise is held to the same bar
-        outs_i, info_i = gpu_run(spec, inputs, variant=variant, generic=True)
+        from paper_2307_04995_amd import binding as pf
+        try:
+            outs_i, info_i = gpu_run(spec, inputs, variant=variant, generic=True)
+        except pf.PfError as e:
+            # a forced variant may exist only in specialised form (e.g. an LDS tile that fits only when packed)
+            if variant is None or e.status != pf.PF_ERR_UNSUPPORTED:
+                raise
+            outs_i, info_i = gpu_run(spec, inputs, variant=None, generic=True)
         assert info_i.spec_id == 0
         for o, w, (_, dt) in zip(outs_i, wants, spec.outputs):
             compare(o, w, dt, what + " (interpreted)")

@@ -14,13 +14,14 @@ def _pf():
     return pf
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("n,h,w,c,dtype", [(2, 13, 11, 64, "f16"), (1, 7, 7, 240, "f16"), (3, 5, 9, 8, "f32"), (1, 20, 3, 144, "bf16"),
                                            (1, 1, 1, 16, "f16"), (2, 6, 6, 32, "f32"), (1, 1, 40, 24, "bf16"), (1, 19, 1, 8, "f16")])
-def test_relu_depthwise_conv_bias(n, h, w, c, dtype):
+def test_relu_depthwise_conv_bias(n, h, w, c, dtype, variant):
     spec, ins = wl.x4_relu_dwconv(n=n, h=h, w=w, c=c, dtype=dtype)
-    _, info, _ = check_chain(spec, ins, what=f"relu -> dwconv -> bias [{n},{h},{w},{c}] {dtype}")
+    _, info, _ = check_chain(spec, ins, variant=variant, what=f"relu -> dwconv -> bias [{n},{h},{w},{c}] {dtype} variant {variant}")
     pf = _pf()
-    assert info.family == pf.PF_FAMILY_STENCIL and info.n_launches == 1
+    assert info.family == pf.PF_FAMILY_STENCIL and info.n_launches == 1 and info.variant == variant
     assert info.spec_id == SPEC_JIT
 
 
@@ -32,7 +33,8 @@ def test_convolution_alone_and_asymmetric_kernel(dtype):
     k = wl.quantise(np.arange(1, 10, dtype=np.float32).reshape(3, 3, 1).repeat(c, 2) / 16.0, dtype)
     spec = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (3, 3, c))])
     spec.out(spec.op("dwconv2d", 0, 1), dtype)
-    check_chain(spec, [x, k], what="dwconv alone")
+    for variant in (0, 1):
+        check_chain(spec, [x, k], variant=variant, what=f"dwconv alone, variant {variant}")
 
 
 def test_operands_on_both_sides_of_the_convolution():
@@ -50,7 +52,14 @@ def test_operands_on_both_sides_of_the_convolution():
     v = s.op("dwconv2d", v, 2)
     v = s.op("silu", s.op("add", v, 3))
     s.out(s.op("add", v, 4), dtype)
-    check_chain(s, [x, shift, k, bias, res], what="operands on both sides of a dwconv")
+    # (fp16 values that went through an addition are kept in fp32: the staged variant's tile would not fit)
+    for variant in (0, None):
+        check_chain(s, [x, shift, k, bias, res], variant=variant, what=f"operands on both sides of a dwconv, variant {variant}")
+    # the same chain in fp32 fits the tile
+    ins32 = [wl.quantise(wl.widen(t).astype(np.float32), "f32") for t in (x, shift, k, bias, res)]
+    s32 = wl.ChainSpec(inputs=[("f32", sh) for _, sh in s.inputs], ops=s.ops, outputs=[(v, "f32") for v, _ in s.outputs])
+    _, info, _ = check_chain(s32, ins32, variant=1, what="operands on both sides of a dwconv, fp32, staged")
+    assert info.variant == 1
 
 
 def test_padding_comes_after_the_activation():
@@ -61,7 +70,19 @@ def test_padding_comes_after_the_activation():
     k = wl.quantise(np.ones((3, 3, c), dtype=np.float32), dtype)
     s = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (3, 3, c))])
     s.out(s.op("dwconv2d", s.op("sigmoid", 0), 1), dtype)
-    check_chain(s, [x, k], what="sigmoid -> dwconv")
+    for variant in (0, 1):
+        check_chain(s, [x, k], variant=variant, what=f"sigmoid -> dwconv, variant {variant}")
+
+
+def test_wide_channel_counts_fall_back_to_the_direct_variant():
+    # 1152 channels in fp16: the LDS tile of the staged variant would not fit
+    pf = _pf()
+    spec, ins = wl.x4_relu_dwconv(n=1, h=7, w=7, c=1152, dtype="f16")
+    _, info, _ = check_chain(spec, ins, what="relu -> dwconv -> bias, 1152 channels")
+    assert info.variant in (pf.PF_VARIANT_STENCIL_DIRECT, pf.PF_VARIANT_STENCIL_STAGED)
+    spec, ins = wl.x4_relu_dwconv(n=1, h=5, w=5, c=2048, dtype="f32")
+    _, info, _ = check_chain(spec, ins, what="relu -> dwconv -> bias, 2048 fp32 channels")
+    assert info.variant == pf.PF_VARIANT_STENCIL_DIRECT
 
 
 def test_other_kernel_sizes_are_refused():
