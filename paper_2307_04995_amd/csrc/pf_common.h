@@ -177,6 +177,8 @@ struct StencilGeom {
     uint32_t cv;        // 16-byte vectors per position (c / VEC)
     uint32_t row_vecs;  // w * cv: lanes needed for one image row
     uint32_t epi_full_mask, epi_vec_mask;  // operands that belong to the epilogue (read at the output position)
+    uint32_t tiles_x, tiles_y, tiles;      // staged variant: tiles per image row, strips per image, tiles in all
+    uint32_t tiles_per_die;                // ceil(tiles / 8)
     FastDiv div_cv;
 };
 

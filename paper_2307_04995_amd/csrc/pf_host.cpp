@@ -1566,6 +1566,16 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
                     (unsigned long long)lds_limit);
     p->variant = variant;
     p->lds_bytes = variant == PF_VARIANT_STENCIL_STAGED ? (uint32_t)tile_bytes : 0u;
+    if (variant == PF_VARIANT_STENCIL_STAGED) {
+        // one-dimensional grid, tiles numbered so that neighbours share a compute die's L2
+        g.tiles_x = p->grid.x;
+        g.tiles_y = p->grid.y;
+        const uint64_t tiles = (uint64_t)p->grid.x * p->grid.y * p->grid.z;
+        if (tiles > 0x7ffffff0ull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
+        g.tiles = (uint32_t)tiles;
+        g.tiles_per_die = (uint32_t)((tiles + 7) / 8);
+        p->grid = dim3(g.tiles_per_die * 8u);
+    }
     if (jit_ok) {
         std::string err;
         p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, make_jit_spec(L), &err);
@@ -1578,6 +1588,7 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
                 if (big > lds_limit) {
                     p->variant = PF_VARIANT_STENCIL_DIRECT;
                     p->lds_bytes = 0;
+                    p->grid = dim3(g.tiles_x, g.tiles_y, (uint32_t)n);
                 } else {
                     p->lds_bytes = (uint32_t)big;
                 }

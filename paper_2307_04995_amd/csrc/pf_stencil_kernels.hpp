@@ -171,9 +171,17 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
     constexpr int kRows = kStencilRows + 2;
     extern __shared__ u32x4 tile[];
 
-    const uint32_t t0 = blockIdx.x * 256u;  // first (column, channel vector) lane of this workgroup
-    const uint32_t sample = blockIdx.z;
-    const uint32_t h0 = blockIdx.y * (uint32_t)kStencilRows;
+    // Tile of this workgroup.  Workgroups are dealt to the eight compute dies round-robin by their linear index,
+    // and each die has its own L2.  Tiles that share halo rows and columns are therefore numbered so that
+    // neighbours fall on the same die (tile = (index mod 8) * tiles_per_die + index / 8): a halo fetched by one
+    // workgroup is an L2 hit for the next instead of a second trip to HBM.
+    const uint32_t tile_id = (blockIdx.x & 7u) * g.tiles_per_die + (blockIdx.x >> 3);
+    if (tile_id >= g.tiles) return;  // (the grid is rounded up to a multiple of eight)
+    const uint32_t tx = tile_id % g.tiles_x;
+    const uint32_t ty = (tile_id / g.tiles_x) % g.tiles_y;
+    const uint32_t t0 = tx * 256u;  // first (column, channel vector) lane of this workgroup
+    const uint32_t sample = tile_id / (g.tiles_x * g.tiles_y);
+    const uint32_t h0 = ty * (uint32_t)kStencilRows;
     const int wslot = Spec::gamma(a);
     const uint32_t cv = g.cv;
     const uint32_t tw = 256u + 2u * cv;  // staging lanes per row
