@@ -46,6 +46,30 @@ def test_full_size_chain_matches_oracle(name):
         assert info.variant == pf.PF_VARIANT_GROUP_RESIDENT
 
 
+@pytest.mark.parametrize("name", ["X2", "X4"])
+def test_full_size_extra_chains_match_oracle(name):
+    # the attention and depthwise-convolution chains bench.py times for context, every element
+    from paper_2307_04995_amd import binding as pf
+    spec, ins = wl.CONFIGS[name]()
+    outs, info = _run_default(spec, ins)
+    want = oracle_run(spec, ins)
+    max_abs, max_rel = compare(outs[0], want[0], spec.outputs[0][1], f"{name} full size")
+    print(f"{name}: family {info.family} variant {info.variant} spec {info.spec_id} max-abs {max_abs:.3e} max-rel {max_rel:.3e}")
+    assert info.n_launches == 1
+    if name == "X4":
+        assert info.variant == pf.PF_VARIANT_STENCIL_STAGED and info.spec_id == pf.PF_SPEC_JIT
+
+
+def test_full_size_channel_shuffle_is_bit_exact():
+    from oracle import pf_oracle as orc
+    spec, ins = wl.CONFIGS["X3"]()
+    outs, info = _run_default(spec, ins)
+    wants = orc.evaluate_layout_bits(spec, [wl.raw_bits(t) for t in ins])
+    for o, w in zip(outs, wants):
+        assert np.array_equal(wl.raw_bits(o), w)
+    assert info.n_launches == 1
+
+
 def test_full_size_c4_layout_is_bit_exact():
     from oracle import pf_oracle as orc
     spec, ins = wl.c4_bias_scale_permute()
