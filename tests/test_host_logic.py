@@ -236,3 +236,76 @@ def test_null_arguments_are_errors_not_crashes():
     assert lib.pf_chain_run(None, None, None, None) == pf.PF_ERR_INVALID_ARG
     lib.pf_chain_plan_destroy.argtypes = [ctypes.c_void_p]
     lib.pf_chain_plan_destroy(None)
+
+
+def test_shapes_of_the_contraction_layout_and_convolution_operators():
+    def shape_of(s, value):
+        d = pf.make_desc(s)
+        st, t = pf.pf_chain_infer_shape(d, value)
+        assert st == pf.PF_OK, pf.pf_last_error()
+        return tuple(t.shape[:t.rank])
+
+    s = wl.ChainSpec(inputs=[("f16", (2, 3, 5, 8)), ("f16", (2, 3, 8)), ("f16", (2, 3, 6))])
+    kc = s.op("concat_rows", 0, 1)
+    mv = s.op("matvec", kc, 1)
+    vm = s.op("vecmat", 2, kc)
+    s.out(vm, "f16")
+    assert shape_of(s, kc) == (2, 3, 6, 8) and shape_of(s, mv) == (2, 3, 6) and shape_of(s, vm) == (2, 3, 8)
+
+    s = wl.ChainSpec(inputs=[("f32", (4, 6, 10)), ("f32", (4, 2, 10))])
+    c = s.op("concat", 0, 1, i=[1])
+    sl = s.op("slice", c, i=[2, 3, 4])
+    s.out(sl, "f32")
+    assert shape_of(s, c) == (4, 8, 10) and shape_of(s, sl) == (4, 8, 4)
+
+    s = wl.ChainSpec(inputs=[("bf16", (1, 9, 7, 16)), ("bf16", (3, 3, 16))])
+    y = s.op("dwconv2d", 0, 1)
+    s.out(y, "bf16")
+    assert shape_of(s, y) == (1, 9, 7, 16)
+
+    bad = [
+        (lambda s: s.op("matvec", 0, 1), [("f16", (2, 5, 8)), ("f16", (2, 7))]),
+        (lambda s: s.op("vecmat", 1, 0), [("f16", (2, 5, 8)), ("f16", (2, 4))]),
+        (lambda s: s.op("concat_rows", 0, 1), [("f16", (2, 5, 8)), ("f16", (3, 8))]),
+        (lambda s: s.op("concat", 0, 1, i=[0]), [("f16", (2, 5)), ("f16", (2, 6))]),
+        (lambda s: s.op("slice", 0, i=[1, 3, 4]), [("f16", (2, 5))]),
+        (lambda s: s.op("dwconv2d", 0, 1), [("f16", (1, 4, 4, 8)), ("f16", (2, 3, 8))]),
+    ]
+    for make, inputs in bad:
+        s = wl.ChainSpec(inputs=inputs)
+        s.out(make(s), "f16")
+        assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+    s = wl.ChainSpec(inputs=[("f16", (2, 5)), ("f16", (2, 6))])
+    s.out(s.op("concat", 0, 1, i=[2]), "f16")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_INVALID_ARG
+
+
+def test_row_values_broadcast_over_their_rows():
+    # a keep-dim reduction result may meet the full value it came from; anything else must still match exactly
+    s = wl.ChainSpec(inputs=[("f32", (3, 4, 20))])
+    m = s.op("reduce_max", 0)
+    s.out(s.op("sub", 0, m), "f32")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_OK
+    s = wl.ChainSpec(inputs=[("f32", (3, 4, 20)), ("f32", (3, 5, 1))])
+    s.out(s.op("sub", 0, 1), "f32")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+
+
+def test_patterns_refused_before_any_device_work():
+    # an element-wise step inside the attention pattern; arithmetic next to a concatenation
+    s = wl.ChainSpec(inputs=[("f16", (1, 2, 64)), ("f16", (1, 2, 16, 64)), ("f16", (1, 2, 16, 64))])
+    p = s.op("relu", s.op("softmax", s.op("matvec", 1, 0)))
+    s.out(s.op("vecmat", p, 2), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    s = wl.ChainSpec(inputs=[("f16", (4, 8)), ("f16", (4, 8))])
+    s.out(s.op("relu", s.op("concat", 0, 1, i=[1])), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # a 5 x 5 depthwise kernel
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (5, 5, 16))])
+    s.out(s.op("dwconv2d", 0, 1), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # a chain with in-line reductions whose rows do not fit a workgroup
+    s = wl.ChainSpec(inputs=[("f32", (2, 70000))])
+    m = s.op("reduce_max", 0)
+    s.out(s.op("sub", 0, m), "f32")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
