@@ -439,7 +439,8 @@ struct LaneState {
     float tmp[at_least_1(Spec::NT)][E];
     uint32_t row[K];  // row (index over all but the innermost dim) of vector k
     uint32_t col[K];  // column of the first element of vector k
-    float rowv[PF_DEV_MAX_ROWV];  // per-row values produced by U_RED_* steps (row programs)
+    float rowv[PF_DEV_MAX_ROWV][K];  // per-row values produced by U_RED_* steps (row programs), one per vector: a lane
+                                     // may hold vectors of several rows
 };
 
 // Where a broadcast operand's 16-byte vector for position (row, col) starts, in elements.
@@ -624,6 +625,7 @@ PF_DEVICE void apply_uop(int code, int slot, int32_t ival, LaneState<DT, K, Spec
 template <int DT, int K, class Spec, class L, class StoreFn>
 PF_DEVICE void run_step(const ProgView<L>& pv, int i, LaneState<DT, K, Spec>& s, const StoreFn& store_fn) {
     constexpr int E = LaneState<DT, K, Spec>::E;
+    constexpr int VEC = LaneState<DT, K, Spec>::VEC;
     const int kind = pv.kind(i), code = pv.code(i), slot = pv.slot(i);
     float b[E];
     switch (kind) {
@@ -648,7 +650,7 @@ PF_DEVICE void run_step(const ProgView<L>& pv, int i, LaneState<DT, K, Spec>& s,
             for (int t = 0; t < PF_DEV_MAX_ROWV; ++t)
                 if (slot == t) {
 #pragma unroll
-                    for (int e = 0; e < E; ++e) b[e] = s.rowv[t];
+                    for (int e = 0; e < E; ++e) b[e] = s.rowv[t][e / VEC];
                 }
             break;
         default:

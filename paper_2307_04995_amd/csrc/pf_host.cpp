@@ -1088,7 +1088,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     // Rows per wave: a wave that owns short rows takes several at once, so that it has about 4 KB of loads
     // in flight (what it takes to cover the HBM latency at full occupancy), as long as enough waves remain
     // (16 per SIMD) to fill the device evenly and a specialised kernel exists for the combination.
-    if (best_wpr == 1 && (matched || jit_ok) && L.n_out == 1 && L.core != pf::CORE_ROWPROG) {
+    if (best_wpr == 1 && (matched || jit_ok) && L.n_out == 1) {
         const int64_t bytes_per_row_in_flight = (int64_t)L.n_full * best_k * 1024;
         int rpw = 1;
         while (rpw < 4 && bytes_per_row_in_flight * rpw < 4096 && best_k * rpw * 2 <= 4 && rows / (rpw * 2) >= 16384) rpw *= 2;

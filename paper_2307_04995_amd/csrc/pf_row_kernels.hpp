@@ -70,13 +70,15 @@ PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, ui
 }
 
 // What the interpreter calls back into from inside the row kernel: secondary-output stores, and the row
-// reductions of a row program (one row per wave or workgroup).  A reduction leaves the accumulator as it is
-// and puts the row's value, the same in every lane, into rowv[slot].  Successive reductions alternate between
-// the two LDS staging areas; one barrier per reduction separates their reuse.
-template <bool RAGGED>
+// reductions of a row program.  A reduction leaves the accumulator as it is and puts each row's value, the
+// same in every lane, into rowv[slot][k] for the vectors k of that row (a wave may hold RPW rows of KC
+// vectors).  Successive reductions alternate between the two LDS staging areas; one barrier per reduction
+// separates their reuse (several waves per row imply RPW = 1).
+template <bool RAGGED, int KC, int RPW>
 struct RowHooks {
     RowStore<RAGGED> store;
-    uint32_t wpr, wave, lane, limit;
+    uint32_t wpr, wave, lane;
+    const uint32_t* limit;  // [RPW] row lengths (0 for rows past the end)
     float inv_n;
     float (*red)[16];
     uint32_t* flip;
@@ -86,48 +88,58 @@ struct RowHooks {
     }
 };
 
-template <bool RAGGED, int DT, int K, class Spec>
-PF_DEVICE void hook_reduce(const RowHooks<RAGGED>& h, int code, int slot, LaneState<DT, K, Spec>& s) {
+template <bool RAGGED, int KC, int RPW, int DT, int K, class Spec>
+PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW>& h, int code, int slot, LaneState<DT, K, Spec>& s) {
     constexpr int VEC = Storage<DT>::VEC;
-    float* stage = h.red[*h.flip & 1u];
-    *h.flip += 1u;
-    float r;
-    if (code == U_RED_MAX) {
-        float m = -__builtin_inff(), nan_seen = 0.0f;
+    static_assert(K == KC * RPW, "row hooks and lane state disagree");
 #pragma unroll
-        for (int k = 0; k < K; ++k)
+    for (int r = 0; r < RPW; ++r) {
+        const uint32_t limit = h.limit[r];
+        float* stage = h.red[*h.flip & 1u];
+        *h.flip += 1u;
+        float v;
+        if (code == U_RED_MAX) {
+            float m = -__builtin_inff(), nan_seen = 0.0f;
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const bool valid = RAGGED ? s.col[k] + (uint32_t)e < h.limit : s.col[k] < h.limit;
-                const float x = s.acc[k * VEC + e];
-                m = valid ? fmaxf(m, x) : m;
-                nan_seen = (valid && x != x) ? 1.0f : nan_seen;
+            for (int c = 0; c < KC; ++c)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int k = r * KC + c;
+                    const bool valid = RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit;
+                    const float x = s.acc[k * VEC + e];
+                    m = valid ? fmaxf(m, x) : m;
+                    nan_seen = (valid && x != x) ? 1.0f : nan_seen;
+                }
+            // a NaN anywhere in the row makes the row's maximum NaN
+            if (h.wpr == 1u) {
+                // the wave reduction runs on order-preserving integer keys in which a positive NaN ranks above +inf
+                v = wave_allreduce<OpMax>(nan_seen > 0.0f ? __builtin_nanf("") : m);
+            } else {
+                m = row_allreduce<OpMax>(m, h.wpr, h.wave, h.lane, stage);
+                nan_seen = row_allreduce<OpMax>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
+                *h.flip += 1u;
+                v = nan_seen > 0.0f ? __builtin_nanf("") : m;
             }
-        // a NaN anywhere in the row makes the row's maximum NaN
-        if (h.wpr == 1u) {
-            // the wave reduction runs on order-preserving integer keys in which a positive NaN ranks above +inf
-            r = wave_allreduce<OpMax>(nan_seen > 0.0f ? __builtin_nanf("") : m);
         } else {
-            m = row_allreduce<OpMax>(m, h.wpr, h.wave, h.lane, stage);
-            nan_seen = row_allreduce<OpMax>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
-            *h.flip += 1u;
-            r = nan_seen > 0.0f ? __builtin_nanf("") : m;
+            float sum = 0.0f;
+#pragma unroll
+            for (int c = 0; c < KC; ++c)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int k = r * KC + c;
+                    const bool valid = RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit;
+                    sum += valid ? s.acc[k * VEC + e] : 0.0f;
+                }
+            v = row_allreduce<OpSum>(sum, h.wpr, h.wave, h.lane, stage);
+            if (code == U_RED_MEAN) v *= h.inv_n;
         }
-    } else {
-        float sum = 0.0f;
 #pragma unroll
-        for (int k = 0; k < K; ++k)
+        for (int t = 0; t < PF_DEV_MAX_ROWV; ++t)
+            if (slot == t) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const bool valid = RAGGED ? s.col[k] + (uint32_t)e < h.limit : s.col[k] < h.limit;
-                sum += valid ? s.acc[k * VEC + e] : 0.0f;
+                for (int c = 0; c < KC; ++c) s.rowv[t][r * KC + c] = v;
             }
-        r = row_allreduce<OpSum>(sum, h.wpr, h.wave, h.lane, stage);
-        if (code == U_RED_MEAN) r *= h.inv_n;
     }
-#pragma unroll
-    for (int t = 0; t < PF_DEV_MAX_ROWV; ++t)
-        if (slot == t) s.rowv[t] = r;
 }
 
 // Issue the loads of every operand of a row tile before anything is used.  `row_byte` is wave-uniform,
@@ -220,11 +232,10 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
         load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
     }
 
-    // secondary outputs (U_STORE) and row programs (U_RED_*) are supported for one row per wave only; the
-    // planner enforces it
+    // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
     const float inv_n = 1.0f / (float)n;
     uint32_t flip = 0;
-    const RowHooks<RAGGED> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit[0], inv_n, red, &flip};
+    const RowHooks<RAGGED, KC, RPW> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit, inv_n, red, &flip};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
     // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
