@@ -69,10 +69,12 @@ def full_size_chain(name):
     return spec, ins, algorithmic, nominal, labels[name]
 
 
-def time_chain(spec, ins, steps, warmup, variant=None, hot=None):
+def time_chain(spec, ins, steps, warmup, variant=None, hot=None, graph=None):
     """Returns (ms per step from host clock, ms per launch from HIP events, plan info).  The timed launches
     rotate over the buffer sets (cold).  If `hot` is a list, the average launch duration of the same number
-    of launches on ONE buffer set (data resident in the last-level cache where it fits) is appended to it."""
+    of launches on ONE buffer set (data resident in the last-level cache where it fits) is appended to it.
+    If `graph` is a list, the launches are also recorded into a HIP graph (one launch per buffer set) and the
+    average launch duration under graph replay is appended: what a launch-bound chain gains from it."""
     import numpy as np
     import torch
     from paper_2307_04995_amd import binding as pf
@@ -116,6 +118,25 @@ def time_chain(spec, ins, steps, warmup, variant=None, hot=None):
         ev1.record()
         torch.cuda.synchronize()
         hot.append(ev0.elapsed_time(ev1) / steps)
+    if graph is not None:
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            plan.run_ptrs(sets[0][0], sets[0][1], side.cuda_stream)
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                cs = torch.cuda.current_stream().cuda_stream
+                for k in range(n_sets):
+                    plan.run_ptrs(sets[k][0], sets[k][1], cs)
+        reps = max(1, steps // n_sets)
+        g.replay()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            g.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        graph.append(ev0.elapsed_time(ev1) / (reps * n_sets))
     plan.close()
     del sets
     torch.cuda.empty_cache()
@@ -245,7 +266,8 @@ def main():
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
             hot2 = [] if args.hot else None
-            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name), hot=hot2)
+            gr2 = [] if (args.hot and name == "C1") else None   # the launch-bound chain, replayed from a HIP graph
+            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name), hot=hot2, graph=gr2)
             chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3),
                             "host_us_per_call": round(h2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
                             "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2,
@@ -253,6 +275,8 @@ def main():
                             "traffic": read_traffic(name)}
             if hot2:
                 chains[name]["hot_us_per_call"] = round(hot2[0] * 1e3, 3)
+            if gr2:
+                chains[name]["graph_replay_us_per_call"] = round(gr2[0] * 1e3, 3)
             del s2, i2
         nbytes = 64 * 1024 * 1024
         best = None

@@ -211,9 +211,11 @@ pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
  * the shapes and dtypes of the description, 16-byte aligned, owned by the caller and not retained.
  * No allocation, no host synchronisation, no host work proportional to tensor size.
  * An output may be the same buffer as an input of identical shape and dtype in the element-wise, row and
- * group families (each element is read before it is written by the same lane); the transpose family
- * returns PF_ERR_ALIAS for any overlap.  A plan with workspace (group family) must not run on two streams
- * at the same time.
+ * group families (each element is read before it is written by the same lane); the other families
+ * return PF_ERR_ALIAS for any overlap.  A plan with workspace (group, attention families) must not run on
+ * two streams at the same time.
+ * The launches may be recorded into a HIP graph (stream capture) and replayed, except those of the one-launch
+ * GroupNorm variant (PF_ERR_UNSUPPORTED while the stream is capturing; plan PF_VARIANT_GROUP_TWO_PASS instead).
  */
 pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *const *outputs, void *stream);
 

@@ -1916,7 +1916,9 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             const uintptr_t ib = (uintptr_t)inputs[k], ie = ib + plan->in_bytes[k];
             if (ob < ie && ib < oe) {
                 const bool same = ob == ib && plan->out_bytes[o] == plan->in_bytes[k];
-                if (!same || plan->family == PF_FAMILY_TRANSPOSE)
+                // in place only where every element is read before it is written by the same lane
+                const bool in_place_ok = plan->family == PF_FAMILY_ELEMENTWISE || plan->family == PF_FAMILY_ROW || plan->family == PF_FAMILY_GROUP;
+                if (!same || !in_place_ok)
                     return fail(PF_ERR_ALIAS, "output %d overlaps input %d", o, k);
             }
         }
@@ -1980,6 +1982,13 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             }
             break;
         case PF_FAMILY_GROUP: {
+            if (plan->variant == PF_VARIANT_GROUP_RESIDENT) {
+                // the fused kernel alternates between two sets of exchange slots by launch number, which is a
+                // kernel argument: a recorded launch would replay the same number
+                hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+                if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone)
+                    return fail(PF_ERR_UNSUPPORTED, "the one-launch GroupNorm variant cannot be recorded into a graph; plan the two-launch variant for that");
+            }
             pf::GroupGeom g = plan->group;
             g.epoch = ++plan->epoch;
             const uint32_t tiles = g.samples * g.blocks_per_sample;
