@@ -91,7 +91,7 @@ typedef enum {
     PF_SLICE = 30,      /* elements [i[1], i[1] + i[2]) of src0 along axis i[0]                                  */
     /* depthwise convolution (section 6, the EfficientNet fragment): src0 x [n, h, w, c] channels-last, src1
        kernels [kh, kw, c] (a chain input); cross-correlation, stride 1, zero padding that keeps h and w.
-       Implemented for kh = kw = 3.  Element-wise operators may precede it (they run before the padding) and
+       Implemented for kh = kw = 3 and kh = kw = 5.  Element-wise operators may precede it (they run before the padding) and
        follow it.                                                                                             */
     PF_DWCONV2D = 31,
     PF_OP_COUNT_ = 32

@@ -927,6 +927,7 @@ struct pf_plan_s {
     pf::AttnArgs attn;
     pf::GatherArgs gather;
     pf::StencilGeom stencil;
+    int stencil_ks = 3;       // kernel extent of the depthwise convolution
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -942,7 +943,8 @@ struct pf_plan_s {
 
 namespace {
 
-constexpr int kStencilRowsHost = 6;  // output rows per strip of the stencil kernel (kStencilRows on the device side)
+constexpr int kStencilRowsHost = 6;   // output rows per strip of the stencil kernels (kStencilRows on the device side)
+constexpr int kStencilRows5Host = 4;  // ... for 5 x 5 kernels (kStencilRows5)
 
 int env_int(const char* name, int dflt) {
     const char* s = getenv(name);
@@ -1518,11 +1520,14 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     const int vec = 16 / es;
     const Shape& xs = L.pre_shape;  // [n, h, w, c]
     const Shape& ks = c.shape[p->desc.ops[L.core_op].src[1]];
-    if (ks[0] != 3 || ks[1] != 3) return fail(PF_ERR_UNSUPPORTED, "dwconv2d: only 3 x 3 kernels are implemented (got %lld x %lld)", (long long)ks[0], (long long)ks[1]);
+    if (ks[0] != ks[1] || (ks[0] != 3 && ks[0] != 5))
+        return fail(PF_ERR_UNSUPPORTED, "dwconv2d: 3 x 3 and 5 x 5 kernels are implemented (got %lld x %lld)", (long long)ks[0], (long long)ks[1]);
+    const int ksz = (int)ks[0];
+    const int out_rows = ksz == 3 ? kStencilRowsHost : kStencilRows5Host;
     const int64_t n = xs[0], h = xs[1], w = xs[2], ch = xs[3];
     if ((ch * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)ch);
     if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the stencil family is not a multiple of 16 bytes");
-    if (n * h * w > 0xffffffffLL || n > 65535 || (h + kStencilRowsHost - 1) / kStencilRowsHost > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
+    if (n * h * w > 0xffffffffLL || n > 65535 || (h + out_rows - 1) / out_rows > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
     if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the stencil family");
     for (int i = 0; i < L.pro.n; ++i)
         if (L.pro.u[i].code == pf::U_MASK_CAUSAL) return fail(PF_ERR_UNSUPPORTED, "causal_mask next to a convolution is not implemented");
@@ -1545,8 +1550,9 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     p->k = 1;
     p->spec_id = 0;
     p->block = dim3(256);
-    p->grid = dim3((g.row_vecs + 255u) / 256u, (uint32_t)((h + kStencilRowsHost - 1) / kStencilRowsHost), (uint32_t)n);
+    p->grid = dim3((g.row_vecs + 255u) / 256u, (uint32_t)((h + out_rows - 1) / out_rows), (uint32_t)n);
     p->n_launches = 1;
+    p->stencil_ks = ksz;
     p->args.n_inner = (uint32_t)ch;
     p->args.rows = (uint64_t)(n * h * w);
     // Staged variant (values activated once, shared through an LDS tile) when the tile fits; its entries are
@@ -1556,10 +1562,18 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     for (int i = 1; i < L.pro.n; ++i)
         if (L.pro.u[i].code != pf::U_RELU && L.pro.u[i].code != pf::U_NEG) exact_pro = false;
     const uint32_t entry_bytes = (L.main_dtype == PF_F32 || (exact_pro && jit_ok)) ? 16u : 32u;
-    const uint64_t tile_bytes = (uint64_t)(kStencilRowsHost + 2) * (256u + 2u * g.cv) * entry_bytes;
-    const uint64_t lds_limit = 64 * 1024;  // per workgroup
+    const uint64_t tile_bytes = (uint64_t)(out_rows + ksz - 1) * (256u + 2u * (uint32_t)(ksz / 2) * g.cv) * entry_bytes;
+    // per workgroup: 64 KB everywhere; up to 96 KB where the device offers 160 KB (gfx950), which still leaves
+    // room for a second, smaller workgroup on the compute unit
+    uint64_t lds_limit = 64 * 1024;
+    {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, p->device) == hipSuccess && prop.sharedMemPerBlock >= 160 * 1024) lds_limit = 96 * 1024;
+    }
     const bool staged_ok = tile_bytes <= lds_limit;
     int variant = forced_variant >= 0 ? forced_variant : (staged_ok ? PF_VARIANT_STENCIL_STAGED : PF_VARIANT_STENCIL_DIRECT);
+    if (variant == PF_VARIANT_STENCIL_DIRECT && ksz != 3)
+        return fail(PF_ERR_UNSUPPORTED, "5 x 5 kernels need the staged variant, whose LDS tile (%llu bytes) does not fit here", (unsigned long long)tile_bytes);
     if (variant != PF_VARIANT_STENCIL_STAGED && variant != PF_VARIANT_STENCIL_DIRECT) return fail(PF_ERR_UNSUPPORTED, "unknown stencil variant %d", variant);
     if (variant == PF_VARIANT_STENCIL_STAGED && !staged_ok)
         return fail(PF_ERR_UNSUPPORTED, "the staged variant needs an LDS tile of %llu bytes (limit %llu)", (unsigned long long)tile_bytes,
@@ -1578,13 +1592,14 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     }
     if (jit_ok) {
         std::string err;
-        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, make_jit_spec(L), &err);
+        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, ksz, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else {
             if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
             // the interpreted kernel never packs its tile
             if (variant == PF_VARIANT_STENCIL_STAGED && entry_bytes == 16u && L.main_dtype != PF_F32) {
                 const uint64_t big = tile_bytes * 2;
+                if (big > lds_limit && ksz != 3) return fail(PF_ERR_UNSUPPORTED, "5 x 5 kernels need the staged variant, whose LDS tile does not fit here");
                 if (big > lds_limit) {
                     p->variant = PF_VARIANT_STENCIL_DIRECT;
                     p->lds_bytes = 0;
@@ -2012,7 +2027,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
                 void* params[] = {&a, &g};
                 e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, plan->lds_bytes, params, st);
             } else {
-                e = pf::launch_stencil(L.main_dtype, a, plan->stencil, plan->variant, plan->lds_bytes, plan->grid, st);
+                e = pf::launch_stencil(L.main_dtype, a, plan->stencil, plan->variant, plan->stencil_ks, plan->lds_bytes, plan->grid, st);
             }
             break;
         case PF_FAMILY_TRANSPOSE:

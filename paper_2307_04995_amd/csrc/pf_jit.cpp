@@ -178,9 +178,10 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, const J
     return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
 }
 
-hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, const JitSpec& spec, std::string* err) {
+hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
-    name << (variant == 1 ? "pf::dwconv3x3_staged_kernel<" : "pf::dwconv3x3_kernel<") << dtype << ", " << spec_text(spec) << ">";
+    if (variant == 1) name << "pf::dwconv_staged_kernel<" << dtype << ", " << spec_text(spec) << ", " << ks << ">";
+    else name << "pf::dwconv3x3_kernel<" << dtype << ", " << spec_text(spec) << ">";
     return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
 }
 

@@ -20,7 +20,7 @@ hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeo
 hipError_t launch_group(int phase, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
                         dim3 grid, dim3 block, hipStream_t st);
 hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int nv, dim3 grid, hipStream_t st);
-hipError_t launch_stencil(int dtype, const ChainArgs& a, const StencilGeom& g, int variant, uint32_t lds, dim3 grid, hipStream_t st);
+hipError_t launch_stencil(int dtype, const ChainArgs& a, const StencilGeom& g, int variant, int ks, uint32_t lds, dim3 grid, hipStream_t st);
 hipError_t launch_gather(int dtype, const GatherArgs& a, dim3 grid, hipStream_t st);
 int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads);
 hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int variant, hipStream_t st);

@@ -1,5 +1,5 @@
-// Stencil family: prologue -> depthwise 3 x 3 convolution (channels-last, stride 1, zero "same" padding) ->
-// epilogue, one kernel.
+// Stencil family: prologue -> depthwise 3 x 3 or 5 x 5 convolution (channels-last, stride 1, zero "same" padding)
+// -> epilogue, one kernel.
 //
 // The depthwise convolution of the paper's EfficientNet fragment (section 6, preprocessing of the computation
 // graph) does 9 multiply-adds per element it reads and writes: memory-intensive, so it is expressed with the
@@ -17,7 +17,8 @@
 
 namespace pf {
 
-constexpr int kStencilRows = 6;  // output rows per strip (8 input rows are read for them)
+constexpr int kStencilRows = 6;   // output rows per strip, 3 x 3 kernels (8 input rows are read for them)
+constexpr int kStencilRows5 = 4;  // output rows per strip, 5 x 5 kernels (staged variant only; 8 input rows as well)
 
 template <int DT, class Spec>
 __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const StencilGeom g) {
@@ -162,13 +163,16 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 //
 // LDS layout: tile[input row 0..7][staging lane 0 .. 256 + 2 cv), entries of 16 bytes (packed storage type, when
 // the prologue keeps storage precision) or 32 bytes (fp32).  Lanes read consecutive entries: no bank conflicts.
-template <int DT, class Spec>
-__global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a, const StencilGeom g) {
+template <int DT, class Spec, int KS>
+__global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, const StencilGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     constexpr bool kPacked = DT != DT_F32 && list_keeps_storage_precision<typename Spec::Pro>();
     constexpr int EV = (kPacked || DT == DT_F32) ? 1 : 2;  // 16-byte vectors per tile entry
-    constexpr int kRows = kStencilRows + 2;
+    static_assert(KS == 3 || KS == 5, "kernel extents 3 and 5");
+    constexpr int R = KS / 2;                      // halo rows above and below, halo image columns left and right
+    constexpr int kOut = KS == 3 ? kStencilRows : kStencilRows5;  // output rows per strip
+    constexpr int kRows = kOut + KS - 1;           // input rows of a strip: eight for both kernel extents
     extern __shared__ u32x4 tile[];
 
     // Tile of this workgroup.  Workgroups are dealt to the eight compute dies round-robin by their linear index,
@@ -181,10 +185,10 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
     const uint32_t ty = (tile_id / g.tiles_x) % g.tiles_y;
     const uint32_t t0 = tx * 256u;  // first (column, channel vector) lane of this workgroup
     const uint32_t sample = tile_id / (g.tiles_x * g.tiles_y);
-    const uint32_t h0 = ty * (uint32_t)kStencilRows;
+    const uint32_t h0 = ty * (uint32_t)kOut;
     const int wslot = Spec::gamma(a);
     const uint32_t cv = g.cv;
-    const uint32_t tw = 256u + 2u * cv;  // staging lanes per row
+    const uint32_t tw = 256u + 2u * R * cv;  // staging lanes per row
     const uint32_t pro_full = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_FULL) : ~g.epi_full_mask;
     const uint32_t pro_vec = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_VEC) : ~g.epi_vec_mask;
     const uint32_t epi_full = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_FULL) : g.epi_full_mask;
@@ -192,9 +196,9 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
 
     LaneState<DT, 1, Spec> s;
 
-    // ---- stage: staging lane j of input row h0 - 1 + r holds image lane t0 - cv + j
+    // ---- stage: staging lane j of input row h0 - R + r holds image lane t0 - R * cv + j
     for (uint32_t j = threadIdx.x; j < tw; j += 256u) {
-        const int64_t lane_pos = (int64_t)t0 - cv + j;
+        const int64_t lane_pos = (int64_t)t0 - (int64_t)R * cv + j;
         const bool lane_ok = lane_pos >= 0 && lane_pos < (int64_t)g.row_vecs;
         const uint32_t lp = lane_ok ? (uint32_t)lane_pos : 0u;
         const uint32_t wcol = fast_div(lp, g.div_cv);
@@ -203,7 +207,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
         u32x4 pend_f[kRows][at_least_1(Spec::NF)];
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
-            const int row = (int)h0 - 1 + r;
+            const int row = (int)h0 - R + r;
             const bool ok = lane_ok && row >= 0 && row < (int)g.h;
             const uint32_t pos = (sample * g.h + (uint32_t)(ok ? row : 0)) * g.w + wcol;
 #pragma unroll
@@ -215,7 +219,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
         }
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
-            const int row = (int)h0 - 1 + r;
+            const int row = (int)h0 - R + r;
             const bool ok = lane_ok && row >= 0 && row < (int)g.h;
             if (ok) {
                 s.row[0] = (sample * g.h + (uint32_t)row) * g.w + wcol;
@@ -253,28 +257,34 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
     // fp16 tile entries meet fp16 kernels: the multiply-add takes both halves of the packed registers directly
     // (v_fma_mix_f32 widens them on the fly), so nothing is unpacked in the inner loop
     constexpr bool kMix = kPacked && DT == DT_F16;
-    u32x4 wraw[9];
-    float wf[kMix ? 1 : 9][VEC];
+    // 3 x 3: the nine kernel vectors live in registers; 5 x 5: they are read where they are used (first-level cache)
+    constexpr bool kKeepW = KS == 3;
+    constexpr int NW = kKeepW ? KS * KS : 1;
+    u32x4 wraw[NW];
+    float wf[(kMix || !kKeepW) ? 1 : NW][VEC];
+    auto load_w = [&](int k) { return load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE); };
+    if (kKeepW) {
 #pragma unroll
-    for (int k = 0; k < 9; ++k) {
-        wraw[k] = load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE);
-        if (!kMix) S::unpack(wraw[k], wf[k % (kMix ? 1 : 9)]);
+        for (int k = 0; k < NW; ++k) {
+            wraw[k] = load_w(k);
+            if (!kMix) S::unpack(wraw[k], wf[k % ((kMix || !kKeepW) ? 1 : NW)]);
+        }
     }
 #pragma unroll
-    for (int i = 0; i < kStencilRows; ++i) {
+    for (int i = 0; i < kOut; ++i) {
         const uint32_t row = h0 + (uint32_t)i;
         if (row >= g.h) break;
         float acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
 #pragma unroll
-        for (int dh = 0; dh < 3; ++dh)
+        for (int dh = 0; dh < KS; ++dh)
 #pragma unroll
-            for (int dw = 0; dw < 3; ++dw) {
+            for (int dw = 0; dw < KS; ++dw) {
                 const u32x4* src = tile + ((uint32_t)(i + dh) * tw + threadIdx.x + (uint32_t)dw * cv) * EV;
+                const u32x4 wv = kKeepW ? wraw[(dh * KS + dw) % NW] : load_w(dh * KS + dw);
                 if (kMix) {
                     const u32x4 xv = src[0];
-                    const u32x4 wv = wraw[dh * 3 + dw];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const uint32_t xp = xv[j], wp = wv[j];
@@ -283,7 +293,13 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
                     }
                     continue;
                 }
-                float xf[VEC];
+                float xf[VEC], wu[VEC];
+                if (kKeepW) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) wu[e] = wf[(dh * KS + dw) % ((kMix || !kKeepW) ? 1 : NW)][e];
+                } else {
+                    S::unpack(wv, wu);
+                }
                 if (kPacked) {
                     S::unpack(src[0], xf);
                 } else {
@@ -298,7 +314,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_staged_kernel(const ChainArgs a
                     }
                 }
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[(dh * 3 + dw) % (kMix ? 1 : 9)][e], xf[e], acc[e]);
+                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wu[e], xf[e], acc[e]);
             }
         const uint32_t pos = (sample * g.h + row) * g.w + wcol;
         s.row[0] = pos;

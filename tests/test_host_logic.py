@@ -300,8 +300,8 @@ def test_patterns_refused_before_any_device_work():
     s = wl.ChainSpec(inputs=[("f16", (4, 8)), ("f16", (4, 8))])
     s.out(s.op("relu", s.op("concat", 0, 1, i=[1])), "f16")
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
-    # a 5 x 5 depthwise kernel
-    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (5, 5, 16))])
+    # a 7 x 7 depthwise kernel
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (7, 7, 16))])
     s.out(s.op("dwconv2d", 0, 1), "f16")
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
     # a chain with in-line reductions whose rows do not fit a workgroup

@@ -85,9 +85,23 @@ def test_wide_channel_counts_fall_back_to_the_direct_variant():
     assert info.variant == pf.PF_VARIANT_STENCIL_DIRECT
 
 
+@pytest.mark.parametrize("n,h,w,c,dtype", [(2, 13, 11, 64, "f16"), (1, 7, 7, 240, "f16"), (2, 5, 9, 8, "f32"), (1, 9, 3, 48, "bf16"), (1, 1, 1, 16, "f16"),
+                                           (1, 2, 30, 24, "f32")])
+def test_five_by_five_kernels(n, h, w, c, dtype):
+    spec, ins = wl.x4_relu_dwconv(n=n, h=h, w=w, c=c, k=5, dtype=dtype)
+    _, info, _ = check_chain(spec, ins, what=f"relu -> 5x5 dwconv -> bias [{n},{h},{w},{c}] {dtype}")
+    assert info.variant == _pf().PF_VARIANT_STENCIL_STAGED
+    # asymmetric 5 x 5 kernel alone: tap order and the two-wide padding
+    x = wl.random_tensor((1, 6, 7, 8), dtype, 1331)
+    k = wl.quantise(np.arange(1, 26, dtype=np.float32).reshape(5, 5, 1).repeat(8, 2) / 64.0, dtype)
+    s = wl.ChainSpec(inputs=[(dtype, (1, 6, 7, 8)), (dtype, (5, 5, 8))])
+    s.out(s.op("dwconv2d", 0, 1), dtype)
+    check_chain(s, [x, k], what="5x5 dwconv alone")
+
+
 def test_other_kernel_sizes_are_refused():
     pf = _pf()
-    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (5, 5, 16))])
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (7, 7, 16))])
     s.out(s.op("dwconv2d", 0, 1), "f16")
     st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
     assert st == pf.PF_ERR_UNSUPPORTED and h is None
