@@ -309,3 +309,23 @@ def test_patterns_refused_before_any_device_work():
     m = s.op("reduce_max", 0)
     s.out(s.op("sub", 0, m), "f32")
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+
+
+def test_empty_and_oversized_tensors_are_refused_cleanly():
+    # an extent of zero is a shape error, not an empty launch
+    s = wl.ChainSpec(inputs=[("f16", (4, 0, 16))])
+    s.out(s.op("relu", 0), "f16")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+    # more rows than the row kernels index (32-bit row numbers)
+    s = wl.ChainSpec(inputs=[("f16", (1 << 33, 8))])
+    s.out(s.op("softmax", 0), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    assert "too large" in pf.pf_last_error()
+    # more 16-byte vectors than the element-wise kernels index
+    s = wl.ChainSpec(inputs=[("f32", (1 << 20, 1 << 15))])
+    s.out(s.op("relu", 0), "f32")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+    # a permutation of more than 2^32 elements
+    s = wl.ChainSpec(inputs=[("f16", (1 << 12, 1 << 12, 1 << 9))])
+    s.out(s.op("permute", 0, i=[1, 0, 2]), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
