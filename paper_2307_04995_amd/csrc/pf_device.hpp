@@ -249,6 +249,17 @@ PF_DEVICE float subrow_allreduce(float v) {
     return v;
 }
 
+// all-reduce over aligned segments of 2^LOG2 lanes (LOG2 = 6: the whole wave), result in every lane of the segment
+template <class Op, int LOG2>
+PF_DEVICE float seg_allreduce(float v) {
+    if (LOG2 >= 6) return Op::wave(v);
+    if (LOG2 == 5) {
+        v = subrow_allreduce<Op, 4>(v);
+        return Op::apply(v, __shfl_xor(v, 16, 64));
+    }
+    return subrow_allreduce<Op, LOG2>(v);
+}
+
 // ---------------------------------------------------------------------------------------------
 // mean / variance statistics as (count, mean, M2) triples
 // ---------------------------------------------------------------------------------------------

@@ -928,6 +928,7 @@ struct pf_plan_s {
     pf::GatherArgs gather;
     pf::StencilGeom stencil;
     int stencil_ks = 3;       // kernel extent of the depthwise convolution
+    int row_log2l = 6;        // row family: log2 of the lanes of a wave that share a row
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -1100,18 +1101,33 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     }
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
-    p->spec_id = (matched && pf::row_static_available(matched, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) ? matched : 0;
+    // Short rows (at most 32 vectors): several rows side by side in a wave, 8 / 16 / 32 lanes each, instead of
+    // one row on a wave whose other lanes idle.  Exists in plan-time specialised form only.
+    int log2l = 6;
+    if (best_wpr == 1 && best_k == 1 && vpr <= 32 && jit_ok && !reduce_only && L.n_out == 1 && rows >= 256) {
+        log2l = 3;
+        while ((1 << log2l) < vpr) ++log2l;
+    }
+    {
+        const int forced_l = env_int("PF_ROW_LOG2_LANES", 0);
+        if (forced_l >= 3 && forced_l <= 6 && best_wpr == 1 && best_k == 1 && vpr <= (1 << forced_l) && jit_ok && !reduce_only && L.n_out == 1) log2l = forced_l;
+    }
+    p->row_log2l = log2l;
+    p->spec_id = (log2l == 6 && matched && pf::row_static_available(matched, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) ? matched : 0;
     if (!p->spec_id && jit_ok && have_static(p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->block.x)) {
         std::string err;
         if (reduce_only) p->jit_fn = pf::jit_row_reduce_kernel(p->device, L.main_dtype, p->k, p->ragged, make_jit_spec(L), &err);
         else p->jit_fn = pf::jit_row_kernel(p->device, L.main_dtype, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->ragged,
-                                       p->block.x <= 256 ? 256 : 1024, make_jit_spec(L), &err);
+                                       p->block.x <= 256 ? 256 : 1024, log2l, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
     }
-    if (!p->spec_id) p->row.rows_per_wave = 1;
+    if (!p->spec_id) {
+        p->row.rows_per_wave = 1;
+        p->row_log2l = 6;
+    }
     {
-        const int64_t rows_per_block = (int64_t)p->row.rows_per_block * p->row.rows_per_wave;
+        const int64_t rows_per_block = (int64_t)p->row.rows_per_block * p->row.rows_per_wave * (64 >> p->row_log2l);
         p->grid = dim3((uint32_t)((rows + rows_per_block - 1) / rows_per_block));
     }
     return PF_OK;

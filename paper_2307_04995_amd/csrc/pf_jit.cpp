@@ -138,11 +138,11 @@ uint64_t jit_compile_count() {
     return g_compiles;
 }
 
-hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads,
+hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads, int log2_lanes,
                              const JitSpec& spec, std::string* err) {
     std::ostringstream name;
     name << "pf::row_kernel<" << dtype << ", " << kc << ", " << rpw << ", " << spec_text(spec) << ", " << max_threads << ", "
-         << (wave_rows ? "true" : "false") << ", " << (ragged ? "true" : "false") << ">";
+         << (wave_rows ? "true" : "false") << ", " << (ragged ? "true" : "false") << ", " << log2_lanes << ">";
     return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
 }
 

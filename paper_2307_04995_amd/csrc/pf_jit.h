@@ -25,7 +25,8 @@ bool jit_enabled();
 uint64_t jit_compile_count();
 
 // Each returns the kernel for the current device, or nullptr (reason in *err) when it cannot be produced.
-hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads,
+// log2_lanes: lanes of a wave that share one row (6 = the whole wave; less: several rows side by side)
+hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads, int log2_lanes,
                              const JitSpec& spec, std::string* err);
 hipFunction_t jit_row_reduce_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);
 hipFunction_t jit_row_stream_kernel(int device, int dtype, bool ragged, const JitSpec& spec, std::string* err);

@@ -57,9 +57,10 @@ struct FlatStore {
 
 // Combine per-wave partials of the waves that share a row through LDS (block scope).  `red` must be a
 // staging area no earlier reduction of this workgroup may still be reading.
-template <class Op>
+// LOG2L < 6: a row occupies an aligned segment of 2^LOG2L lanes of one wave (waves_per_row is then 1).
+template <class Op, int LOG2L = 6>
 PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, uint32_t lane, float* red) {
-    v = wave_allreduce<Op>(v);
+    v = seg_allreduce<Op, LOG2L>(v);
     if (waves_per_row == 1) return v;
     if (lane == 0) red[wave] = v;
     __syncthreads();
@@ -74,7 +75,7 @@ PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, ui
 // same in every lane, into rowv[slot][k] for the vectors k of that row (a wave may hold RPW rows of KC
 // vectors).  Successive reductions alternate between the two LDS staging areas; one barrier per reduction
 // separates their reuse (several waves per row imply RPW = 1).
-template <bool RAGGED, int KC, int RPW>
+template <bool RAGGED, int KC, int RPW, int LOG2L = 6>
 struct RowHooks {
     RowStore<RAGGED> store;
     uint32_t wpr, wave, lane;
@@ -88,8 +89,8 @@ struct RowHooks {
     }
 };
 
-template <bool RAGGED, int KC, int RPW, int DT, int K, class Spec>
-PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW>& h, int code, int slot, LaneState<DT, K, Spec>& s) {
+template <bool RAGGED, int KC, int RPW, int LOG2L, int DT, int K, class Spec>
+PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, int slot, LaneState<DT, K, Spec>& s) {
     constexpr int VEC = Storage<DT>::VEC;
     static_assert(K == KC * RPW, "row hooks and lane state disagree");
 #pragma unroll
@@ -111,12 +112,12 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW>& h, int code, int slo
                     nan_seen = (valid && x != x) ? 1.0f : nan_seen;
                 }
             // a NaN anywhere in the row makes the row's maximum NaN
-            if (h.wpr == 1u) {
+            if (h.wpr == 1u && LOG2L == 6) {
                 // the wave reduction runs on order-preserving integer keys in which a positive NaN ranks above +inf
                 v = wave_allreduce<OpMax>(nan_seen > 0.0f ? __builtin_nanf("") : m);
             } else {
-                m = row_allreduce<OpMax>(m, h.wpr, h.wave, h.lane, stage);
-                nan_seen = row_allreduce<OpMax>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
+                m = row_allreduce<OpMax, LOG2L>(m, h.wpr, h.wave, h.lane, stage);
+                nan_seen = row_allreduce<OpMax, LOG2L>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
                 *h.flip += 1u;
                 v = nan_seen > 0.0f ? __builtin_nanf("") : m;
             }
@@ -130,7 +131,7 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW>& h, int code, int slo
                     const bool valid = RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit;
                     sum += valid ? s.acc[k * VEC + e] : 0.0f;
                 }
-            v = row_allreduce<OpSum>(sum, h.wpr, h.wave, h.lane, stage);
+            v = row_allreduce<OpSum, LOG2L>(sum, h.wpr, h.wave, h.lane, stage);
             if (code == U_RED_MEAN) v *= h.inv_n;
         }
 #pragma unroll
@@ -185,7 +186,10 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 //   WPR1 = false: waves_per_row waves of a workgroup share one row (RPW must be 1).
 //   RAGGED      : the row length is not a multiple of a 16-byte vector (element-aligned vector access, a
 //                 partial last vector, element-granular validity).
-template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false>
+//   LOG2L       : (WPR1 only) a row occupies an aligned segment of 2^LOG2L lanes, so a wave holds 64 >> LOG2L
+//                 rows side by side (times RPW in registers): short rows no longer leave most lanes idle.
+//                 Row addressing is then per lane instead of per wave.
+template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false, int LOG2L = 6>
 __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -193,6 +197,9 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     constexpr int EC = KC * VEC;  // elements per lane per row
     constexpr bool PR = S::PRECISE;
     static_assert(WPR1 || RPW == 1, "several rows per wave only when a wave owns its rows");
+    static_assert(WPR1 || LOG2L == 6, "rows side by side in a wave only when a wave owns its rows");
+    constexpr uint32_t LPR = 1u << LOG2L;   // lanes per row inside a wave
+    constexpr uint32_t SUB = 64u >> LOG2L;  // rows side by side in a wave
     __shared__ float red[2][16];
 
     const uint32_t lane = threadIdx.x & 63u;
@@ -200,10 +207,11 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t wpr = WPR1 ? 1u : g.waves_per_row;
     const uint32_t slot_in_block = WPR1 ? wave : wave / wpr;
-    const uint64_t row0 = ((uint64_t)blockIdx.x * g.rows_per_block + slot_in_block) * RPW;
+    const uint64_t row0 = ((uint64_t)blockIdx.x * g.rows_per_block + slot_in_block) * (RPW * SUB);
     if (WPR1 && row0 >= a.rows) return;  // wave-uniform; this configuration has no barrier
     const uint32_t n = a.n_inner;
-    const uint32_t lane_in_row = WPR1 ? lane : (wave - slot_in_block * wpr) * 64u + lane;
+    const uint32_t sub = LOG2L == 6 ? 0u : lane >> LOG2L;  // which of the wave's side-by-side rows this lane serves
+    const uint32_t lane_in_row = WPR1 ? (lane & (LPR - 1u)) : (wave - slot_in_block * wpr) * 64u + lane;
 
     LaneState<DT, K, Spec> s;
     uint32_t limit[RPW], i_row[RPW];
@@ -212,7 +220,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     const uint32_t fill = fill_inf ? (DT == DT_F32 ? 0xff800000u : (DT == DT_F16 ? 0xfc00fc00u : 0xff80ff80u)) : 0u;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const uint64_t row64 = row0 + r;
+        const uint64_t row64 = row0 + (uint32_t)r * SUB + sub;
         const uint32_t row = (uint32_t)row64;
         limit[r] = row64 < a.rows ? n : 0u;
         uint32_t load_limit = limit[r];
@@ -226,7 +234,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
 #pragma unroll
         for (int c = 0; c < KC; ++c) {
             s.row[r * KC + c] = row;
-            s.col[r * KC + c] = (lane_in_row + 64u * wpr * c) * VEC;
+            s.col[r * KC + c] = (lane_in_row + LPR * wpr * c) * VEC;
         }
         row_byte[r] = row64 * n * S::ESIZE;
         load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
@@ -235,11 +243,11 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
     const float inv_n = 1.0f / (float)n;
     uint32_t flip = 0;
-    const RowHooks<RAGGED, KC, RPW> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit, inv_n, red, &flip};
+    const RowHooks<RAGGED, KC, RPW, LOG2L> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit, inv_n, red, &flip};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
     // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
-    const bool exact = n == 64u * wpr * (uint32_t)EC;
+    const bool exact = n == LPR * wpr * (uint32_t)EC;
     const int core = Spec::core(a);
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
@@ -283,7 +291,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             float m = acc[0];
 #pragma unroll
             for (int e = 1; e < EC; ++e) m = fmaxf(m, acc[e]);
-            m = row_allreduce<OpMax>(m, wpr, wave, lane, red[0]);
+            m = row_allreduce<OpMax, LOG2L>(m, wpr, wave, lane, red[0]);
             // exp(c * (x - m)); c is the folded scale (1 when there is none).  -inf - m = -inf -> 0; an all
             // -inf row gives -inf - -inf = NaN, as the definition does.
             const float cs = a.core_scale;
@@ -303,7 +311,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                     sum += acc[e];
                 }
             }
-            sum = row_allreduce<OpSum>(sum, wpr, wave, lane, red[1]);
+            sum = row_allreduce<OpSum, LOG2L>(sum, wpr, wave, lane, red[1]);
             const float inv = pf_rcp<PR>(sum);
 #pragma unroll
             for (int e = 0; e < EC; ++e) acc[e] *= inv;
@@ -317,7 +325,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             float s1 = 0.0f;
 #pragma unroll
             for (int e = 0; e < EC; ++e) s1 += acc[e];
-            const float mean = row_allreduce<OpSum>(s1, wpr, wave, lane, red[0]) * inv_n;
+            const float mean = row_allreduce<OpSum, LOG2L>(s1, wpr, wave, lane, red[0]) * inv_n;
             float s2 = 0.0f;
 #pragma unroll
             for (int c = 0; c < KC; ++c)
@@ -327,7 +335,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                     acc[c * VEC + e] = d;
                     s2 += (all_valid || valid_elem(c, e)) ? d * d : 0.0f;
                 }
-            const float var = row_allreduce<OpSum>(s2, wpr, wave, lane, red[1]) * inv_n;
+            const float var = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, lane, red[1]) * inv_n;
             const float rstd = pf_rsqrt<PR>(var + a.eps);
             float gm[EC], bt[EC];
 #pragma unroll
@@ -345,7 +353,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             for (int c = 0; c < KC; ++c)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) s2 += (all_valid || valid_elem(c, e)) ? acc[c * VEC + e] * acc[c * VEC + e] : 0.0f;
-            const float ms = row_allreduce<OpSum>(s2, wpr, wave, lane, red[0]) * inv_n;
+            const float ms = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, lane, red[0]) * inv_n;
             const float rstd = pf_rsqrt<PR>(ms + a.eps);
             float gm[EC];
 #pragma unroll

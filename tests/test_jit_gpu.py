@@ -104,3 +104,41 @@ def test_transposes_with_unlisted_elementwise_steps():
     spec.out(spec.op("add", v, 1), "f32")
     _, info, _ = check_chain(spec, [x, b], what="relu -> transpose -> + bias")
     assert info.spec_id == SPEC_JIT and info.variant == pf.PF_VARIANT_T_TILE
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n", [197, 200, 64, 24, 100])
+def test_short_rows_sit_side_by_side_in_a_wave(n, dtype):
+    # rows of at most 32 vectors: 2, 4 or 8 rows share a wave (specialised kernels only); causal mask, ragged
+    # widths and a row count that does not fill the last wave included
+    from paper_2307_04995_amd import binding as pf
+    rows_shape = (3, 5, 23, n)                      # 345 rows
+    x = wl.random_tensor(rows_shape, dtype, 1500 + n, scale=2.0)
+    spec = wl.ChainSpec(inputs=[(dtype, rows_shape)])
+    spec.out(spec.op("softmax", spec.op("scale", 0, f=[0.25])), dtype)
+    _, info, _ = check_chain(spec, [x], what=f"short-row softmax n={n} {dtype}")
+    vec = 4 if dtype == "f32" else 8
+    vpr = -(-n // vec)
+    if vpr <= 32:
+        lanes = max(8, 1 << (vpr - 1).bit_length())
+        assert info.spec_id == SPEC_JIT
+        # 64 / lanes rows side by side: the grid covers the 345 rows with that many rows per wave (times the
+        # rows a wave holds one after the other in registers)
+        waves = info.grid[0] * (info.block[0] // 64)
+        assert waves * (64 // lanes) >= 345 // 4
+        assert waves * (64 // lanes) <= 345 + 64
+    # bias + residual + LayerNorm on the same short rows
+    g = wl.random_tensor((n,), dtype, 1511, dist="positive", scale=0.8)
+    b = wl.random_tensor((n,), dtype, 1512, scale=0.3)
+    res = wl.random_tensor(rows_shape, dtype, 1513, scale=0.5)
+    spec = wl.ChainSpec(inputs=[(dtype, rows_shape), (dtype, rows_shape), (dtype, (n,)), (dtype, (n,))])
+    spec.out(spec.op("layernorm", spec.op("add", 0, 1), 2, 3, f=[1e-5]), dtype)
+    check_chain(spec, [wl.random_tensor(rows_shape, dtype, 1514, scale=0.5), res, g, b], what=f"short-row layernorm n={n} {dtype}")
+
+
+def test_short_causal_rows_side_by_side():
+    spec, ins = wl.c2_causal_softmax(b=2, h=4, s=48, dtype="f16")      # 384 rows of 6 vectors: 8 lanes each
+    _, info, _ = check_chain(spec, ins, what="short causal rows")
+    assert info.spec_id == SPEC_JIT
+    spec, ins = wl.c2_causal_softmax(b=1, h=3, s=100, s_k=197, dtype="bf16")
+    check_chain(spec, ins, what="short ragged causal rows")
