@@ -191,6 +191,21 @@ pf_status pf_chain_validate(const pf_chain_desc *desc);
 pf_status pf_chain_infer_shape(const pf_chain_desc *desc, int32_t value, pf_tensor_desc *out);
 
 /*
+ * Rewrite sub-graphs of basic operators that spell out a composite operator over the last dimension into that
+ * operator (host only).  The paper splits operators into the four basic kinds before it optimises (section 6);
+ * a chain that arrives in that form gets the tuned kernel of the composite this way.  Recognised:
+ *   exp(x - reduce_max x) / reduce_sum(exp(x - reduce_max x))                          -> softmax(x)
+ *   ((h - reduce_mean h) * rsqrt(reduce_mean((h - mean)^2) + eps)) * gamma + beta      -> layernorm(h, gamma, beta)
+ *   (x * rsqrt(reduce_mean(x * x) + eps)) * gamma                                      -> rmsnorm(x, gamma)
+ * with multiplication and addition in either operand order, gamma and beta chain inputs of shape [n], and no
+ * interior value used anywhere else.  `out` receives the rewritten chain (inputs and outputs unchanged, value
+ * ids renumbered), or a copy of `desc` when nothing matched; *changed (may be null) says which.
+ * pf_chain_plan applies the same rewrite by itself (and keeps the original chain when the rewritten one
+ * cannot be planned); PF_RECOMPOSE=0 in the environment switches that off.
+ */
+pf_status pf_chain_recompose(const pf_chain_desc *desc, pf_chain_desc *out, int32_t *changed);
+
+/*
  * Map the chain onto a kernel family and fix launch geometry (section 6: the parallelism and tile size of
  * a GIR template are parameters chosen before code is produced; here they are chosen once per plan).
  * `device` is a HIP device ordinal.  May allocate plan-owned device workspace; launches no kernel.

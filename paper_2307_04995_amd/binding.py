@@ -65,7 +65,7 @@ class pf_plan_info(C.Structure):
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
-           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count"]
+           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose"]
 
 
 def _load() -> C.CDLL:
@@ -89,6 +89,7 @@ def _load() -> C.CDLL:
     lib.pf_last_error.argtypes = []
     lib.pf_last_error.restype = C.c_char_p
     lib.pf_copy_probe.argtypes = [vp, vp, C.c_uint64, C.c_int32, vp]
+    lib.pf_chain_recompose.argtypes = [C.POINTER(pf_chain_desc), C.POINTER(pf_chain_desc), C.POINTER(C.c_int32)]
     lib.pf_jit_compile_count.argtypes = []
     lib.pf_jit_compile_count.restype = C.c_uint64
     for name in EXPORTS:
@@ -171,6 +172,14 @@ def pf_copy_probe(src_ptr: int, dst_ptr: int, nbytes: int, variant: int = 2, str
                               C.c_int32(int(variant)), C.c_void_p(int(stream)))
 
 
+def pf_chain_recompose(desc: pf_chain_desc):
+    """(status, rewritten desc or None, changed)."""
+    out = pf_chain_desc()
+    changed = C.c_int32(0)
+    st = _lib.pf_chain_recompose(C.byref(desc), C.byref(out), C.byref(changed))
+    return st, (out if st == PF_OK else None), bool(changed.value)
+
+
 def pf_jit_compile_count() -> int:
     return int(_lib.pf_jit_compile_count())
 
@@ -206,6 +215,22 @@ def make_desc(spec) -> pf_chain_desc:
         d.out_value[k] = int(v)
         d.out_dtype[k] = DTYPE_CODE[dt]
     return d
+
+
+def desc_to_spec(d: pf_chain_desc):
+    """C struct -> workloads.ChainSpec (the inverse of make_desc)."""
+    import workloads as wl
+    names = {v: k for k, v in OP_CODE.items()}
+    dts = {v: k for k, v in DTYPE_CODE.items()}
+    spec = wl.ChainSpec(inputs=[(dts[d.inputs[k].dtype], tuple(d.inputs[k].shape[j] for j in range(d.inputs[k].rank)))
+                                for k in range(d.n_inputs)])
+    for k in range(d.n_ops):
+        o = d.ops[k]
+        spec.ops.append(wl.OpSpec(names[o.op], tuple(o.src[j] for j in range(o.n_src)), (o.f[0], o.f[1]),
+                                  tuple(o.i[j] for j in range(o.n_i))))
+    for k in range(d.n_outputs):
+        spec.out(d.out_value[k], dts[d.out_dtype[k]])
+    return spec
 
 
 class Plan:

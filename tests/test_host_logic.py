@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import workloads as wl
@@ -15,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "pf_chain.h")).read()
     declared = set(re.findall(r"^\s*(?:pf_status|void|uint64_t|const char \*)\s*\*?(pf_[a-z_]+)\s*\(", header, flags=re.M))
-    assert {"pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
+    assert {"pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant", "pf_chain_recompose",
             "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
             "pf_last_error", "pf_copy_probe"} <= declared
     lib = ctypes.CDLL(pf.LIB_PATH)
@@ -329,3 +330,102 @@ def test_empty_and_oversized_tensors_are_refused_cleanly():
     s = wl.ChainSpec(inputs=[("f16", (1 << 12, 1 << 12, 1 << 9))])
     s.out(s.op("permute", 0, i=[1, 0, 2]), "f16")
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
+
+
+# ---- recomposition of basic operators into composite ones (host only)
+
+def _recompose(spec):
+    st, out, changed = pf.pf_chain_recompose(pf.make_desc(spec))
+    assert st == pf.PF_OK
+    return pf.desc_to_spec(out), changed
+
+
+def _oracle_outputs(spec, inputs):
+    from oracle import pf_oracle as orc
+    return orc.evaluate_outputs(spec, [wl.widen(t) for t in inputs])
+
+
+def _basic_softmax(shape, scale=None, causal=False, swap_tail=None):
+    s = wl.ChainSpec(inputs=[("f32", shape)])
+    v = 0
+    if scale is not None:
+        v = s.op("scale", v, f=[scale])
+    if causal:
+        v = s.op("causal_mask", v)
+    e = s.op("exp", s.op("sub", v, s.op("reduce_max", v)))
+    y = s.op("div", e, s.op("reduce_sum", e))
+    if swap_tail:
+        y = s.op(swap_tail, y)
+    s.out(y, "f32")
+    return s
+
+
+def test_recompose_softmax_keeps_the_function():
+    spec = _basic_softmax((2, 5, 5), scale=0.25, causal=True, swap_tail="neg")
+    new, changed = _recompose(spec)
+    assert changed and [o.name for o in new.ops] == ["scale", "causal_mask", "softmax", "neg"]
+    assert new.outputs == [(4, "f32")]
+    x = wl.random_tensor((2, 5, 5), "f32", 3001, scale=2.0)
+    a, b = _oracle_outputs(spec, [x]), _oracle_outputs(new, [x])
+    np.testing.assert_allclose(a[0], b[0], rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_recompose_layernorm_and_rmsnorm(order):
+    rows, n = 4, 24
+    ins = [("f32", (rows, n)), ("f32", (rows, n)), ("f32", (n,)), ("f32", (n,))]
+    s = wl.ChainSpec(inputs=list(ins))
+    h = s.op("add", 0, 1)
+    c = s.op("sub", h, s.op("reduce_mean", h))
+    r = s.op("rsqrt", s.op("addc", s.op("reduce_mean", s.op("mul", c, c)), f=[2.0 ** -10]))     # (exact in fp32, the type the C struct carries it in)
+    y = s.op("mul", c, r) if order & 1 else s.op("mul", r, c)
+    y = s.op("mul", y, 2) if order & 2 else s.op("mul", 2, y)
+    y = s.op("add", y, 3) if order & 1 else s.op("add", 3, y)
+    s.out(s.op("gelu_erf", y), "f32")
+    s.out(h, "f32")
+    new, changed = _recompose(s)
+    assert changed and [o.name for o in new.ops] == ["add", "layernorm", "gelu_erf"]
+    assert new.ops[1].src == (4, 2, 3) and new.ops[1].f[0] == 2.0 ** -10
+    assert new.outputs == [(6, "f32"), (4, "f32")]
+    inputs = [wl.random_tensor(sh, dt, 3010 + k) for k, (dt, sh) in enumerate(ins)]
+    for a, b in zip(_oracle_outputs(s, inputs), _oracle_outputs(new, inputs)):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-13)
+
+    s = wl.ChainSpec(inputs=[("f32", (rows, n)), ("f32", (n,))])
+    r = s.op("rsqrt", s.op("addc", s.op("reduce_mean", s.op("mul", 0, 0)), f=[2.0 ** -20]))
+    y = s.op("mul", 0, r) if order & 1 else s.op("mul", r, 0)
+    s.out(s.op("mul", y, 1) if order & 2 else s.op("mul", 1, y), "f32")
+    new, changed = _recompose(s)
+    assert changed and [o.name for o in new.ops] == ["rmsnorm"] and new.ops[0].src == (0, 1)
+    inputs = [wl.random_tensor((rows, n), "f32", 3020), wl.random_tensor((n,), "f32", 3021)]
+    np.testing.assert_allclose(_oracle_outputs(s, inputs)[0], _oracle_outputs(new, inputs)[0], rtol=0, atol=1e-13)
+
+
+def test_recompose_leaves_near_misses_alone():
+    # the exponentials are also an output: an interior value is used elsewhere
+    s = wl.ChainSpec(inputs=[("f32", (3, 16))])
+    e = s.op("exp", s.op("sub", 0, s.op("reduce_max", 0)))
+    s.out(s.op("div", e, s.op("reduce_sum", e)), "f32")
+    s.out(e, "f32")
+    new, changed = _recompose(s)
+    assert not changed and [o.name for o in new.ops] == [o.name for o in s.ops]
+    # the maximum is taken of another tensor than the one it is subtracted from
+    s = wl.ChainSpec(inputs=[("f32", (3, 16)), ("f32", (3, 16))])
+    e = s.op("exp", s.op("sub", 0, s.op("reduce_max", 1)))
+    s.out(s.op("div", e, s.op("reduce_sum", e)), "f32")
+    assert not _recompose(s)[1]
+    # the divisor is the mean, not the sum
+    s = wl.ChainSpec(inputs=[("f32", (3, 16))])
+    e = s.op("exp", s.op("sub", 0, s.op("reduce_max", 0)))
+    s.out(s.op("div", e, s.op("reduce_mean", e)), "f32")
+    assert not _recompose(s)[1]
+    # gamma is computed inside the chain: not a parameter the composite operator can take
+    s = wl.ChainSpec(inputs=[("f32", (3, 16)), ("f32", (16,))])
+    r = s.op("rsqrt", s.op("addc", s.op("reduce_mean", s.op("mul", 0, 0)), f=[1e-6]))
+    s.out(s.op("mul", s.op("mul", 0, r), s.op("relu", 1)), "f32")
+    assert not _recompose(s)[1]
+    # the square is of another tensor than the one that gets scaled
+    s = wl.ChainSpec(inputs=[("f32", (3, 16)), ("f32", (16,)), ("f32", (3, 16))])
+    r = s.op("rsqrt", s.op("addc", s.op("reduce_mean", s.op("mul", 2, 2)), f=[1e-6]))
+    s.out(s.op("mul", s.op("mul", 0, r), 1), "f32")
+    assert not _recompose(s)[1]

@@ -5,9 +5,19 @@ import numpy as np
 import pytest
 
 import workloads as wl
-from pf_testlib import check_chain, gpu_run, SPEC_JIT
+from pf_testlib import check_chain, env, gpu_run, SPEC_JIT
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(params=["row program", "recomposed"])
+def recompose(request):
+    """Chains that spell out a softmax or a normalisation run twice: as the row program their basic operators
+    lower to (the rewrite into the composite operator switched off), and the way the planner takes them by
+    default."""
+    on = request.param == "recomposed"
+    with env(PF_RECOMPOSE=None if on else "0"):
+        yield on
 
 
 def _pf():
@@ -32,24 +42,29 @@ def _softmax_chain(dtype, shape, scale=None, causal=False):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("n", [512, 200, 197, 4096])
-def test_softmax_in_basic_operators(n, dtype):
+def test_softmax_in_basic_operators(n, dtype, recompose):
     shape = (3, 7, n)
     x = wl.random_tensor(shape, dtype, 1000 + n, scale=2.0)
     spec = _softmax_chain(dtype, shape, scale=0.25)
     _, info, _ = check_chain(spec, [x], what=f"softmax in basic operators n={n} {dtype}")
     pf = _pf()
     assert info.family == pf.PF_FAMILY_ROW and info.n_launches == 1
-    assert info.spec_id == SPEC_JIT
-    # the same numbers as the composite operator, to the storage type's rounding
     comp = wl.ChainSpec(inputs=[(dtype, shape)])
     comp.out(comp.op("softmax", comp.op("scale", 0, f=[0.25])), dtype)
     y0, _ = gpu_run(spec, [x])
-    y1, _ = gpu_run(comp, [x])
-    np.testing.assert_allclose(wl.widen(y0[0]), wl.widen(y1[0]), atol=4e-3 if dtype != "f32" else 1e-6)
+    y1, info1 = gpu_run(comp, [x])
+    if recompose:
+        # planned as the composite operator: the same kernel, the same bits
+        assert (info.spec_id, info.variant, info.n_micro_ops) == (info1.spec_id, info1.variant, info1.n_micro_ops)
+        assert np.array_equal(wl.raw_bits(y0[0]), wl.raw_bits(y1[0]))
+    else:
+        assert info.spec_id == SPEC_JIT and info.n_micro_ops > info1.n_micro_ops
+        # the same numbers as the composite operator, to the storage type's rounding
+        np.testing.assert_allclose(wl.widen(y0[0]), wl.widen(y1[0]), atol=4e-3 if dtype != "f32" else 1e-6)
 
 
 @pytest.mark.parametrize("variant", [0, 1])
-def test_causal_softmax_in_basic_operators(variant):
+def test_causal_softmax_in_basic_operators(variant, recompose):
     shape = (2, 2, 64, 64) if variant == 0 else (1, 2, 1024, 1024)
     x = wl.random_tensor(shape, "f16", 1011, scale=2.0)
     spec = _softmax_chain("f16", shape, scale=0.125, causal=True)
@@ -59,7 +74,7 @@ def test_causal_softmax_in_basic_operators(variant):
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 @pytest.mark.parametrize("rows,n", [(37, 768), (5, 1000), (9, 3000)])
-def test_layernorm_in_basic_operators(rows, n, dtype):
+def test_layernorm_in_basic_operators(rows, n, dtype, recompose):
     x = wl.random_tensor((rows, n), dtype, 1021, scale=0.5)
     res = wl.random_tensor((rows, n), dtype, 1022, scale=0.5)
     gamma = wl.random_tensor((n,), dtype, 1023, dist="positive", scale=0.8)
@@ -76,9 +91,10 @@ def test_layernorm_in_basic_operators(rows, n, dtype):
     s.out(h, dtype)                      # the residual stream as a second output
     _, info, _ = check_chain(s, [x, res, gamma, beta], what=f"layernorm in basic operators n={n} {dtype}")
     assert info.family == _pf().PF_FAMILY_ROW and info.n_launches == 1
+    assert (info.n_micro_ops < 6) if recompose else (info.n_micro_ops >= 10)
 
 
-def test_rmsnorm_and_l1_normalisation_in_basic_operators():
+def test_rmsnorm_and_l1_normalisation_in_basic_operators(recompose):
     rows, n = 11, 520
     x = wl.random_tensor((rows, n), "bf16", 1031)
     gamma = wl.random_tensor((n,), "bf16", 1032, dist="positive", scale=0.8)
@@ -110,9 +126,17 @@ def test_three_reductions_and_row_values_combined():
 
 def test_in_line_reductions_need_rows_that_fit_a_workgroup():
     pf = _pf()
-    s = _softmax_chain("f32", (2, 70000))
+    s = wl.ChainSpec(inputs=[("f32", (2, 70000))])
+    s.out(s.op("div", 0, s.op("addc", s.op("reduce_max", 0), f=[1.0])), "f32")
     st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
     assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    # a softmax spelled in basic operators is planned as the operator, whose streaming variant has no such limit
+    with env(PF_RECOMPOSE="0"):
+        st, h = pf.pf_chain_plan(pf.make_desc(_softmax_chain("f32", (2, 70000))), 0)
+        assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    x = wl.random_tensor((2, 70000), "f32", 1061, scale=2.0)
+    _, info, _ = check_chain(_softmax_chain("f32", (2, 70000)), [x], what="long softmax in basic operators")
+    assert info.variant == pf.PF_VARIANT_ROW_STREAM
 
 
 @pytest.mark.parametrize("n", [256, 2048])
