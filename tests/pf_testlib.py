@@ -90,6 +90,23 @@ def compare(got: torch.Tensor, want: np.ndarray, dtype: str, what: str = ""):
     return max_abs, max_rel
 
 
+def ulp_histogram(got: torch.Tensor, want: np.ndarray, dtype: str):
+    """Distance, in units in the last place of the storage type, between the result and the oracle rounded to
+    that type; counts for 0, 1, 2, 3-4, 5-8 and more ulps.  A report, not a gate: the bars above decide."""
+    tdt = TORCH_DT[dtype]
+    ref = torch.from_numpy(want).to(torch.float32).to(tdt) if dtype != "f32" else torch.from_numpy(want).to(tdt)
+    def ordered(t):  # bit patterns -> integers ordered like the values (negative zero and zero coincide)
+        b = wl.raw_bits(t).astype(np.int64)
+        sign = np.int64(1) << (8 * t.element_size() - 1)
+        return np.where(b & sign, -(b & (sign - 1)), b)
+    finite = np.isfinite(want)
+    d = np.abs(ordered(got) - ordered(ref))[finite]
+    edges = [0, 1, 2, 3, 5, 9, np.iinfo(np.int64).max]
+    counts, _ = np.histogram(d, bins=edges)
+    return {"0": int(counts[0]), "1": int(counts[1]), "2": int(counts[2]), "3-4": int(counts[3]), "5-8": int(counts[4]),
+            ">8": int(counts[5]), "max": int(d.max()) if d.size else 0, "elements": int(d.size)}
+
+
 SPEC_JIT = 255   # plan info spec_id of a kernel specialised for the chain when the plan was made
 
 

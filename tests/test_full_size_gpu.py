@@ -6,9 +6,21 @@ import pytest
 import torch
 
 import workloads as wl
-from pf_testlib import compare, oracle_run
+from pf_testlib import compare, oracle_run, ulp_histogram
 
 pytestmark = pytest.mark.gpu
+
+
+def _report_ulps(name, out, want, dtype):
+    """Print the ulp histogram of a full-size result and append it to gpurun_out/ulp_histogram.jsonl."""
+    import json
+    import os
+    h = ulp_histogram(out, want, dtype)
+    print(f"{name}: ulp distance to the oracle rounded to {dtype}: {h}")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(root, "gpurun_out", "ulp_histogram.jsonl"), "a") as f:
+        f.write(json.dumps({"chain": name, "dtype": dtype, **h}) + "\n")
 
 
 def _run_default(spec, ins):
@@ -35,6 +47,7 @@ def test_full_size_chain_matches_oracle(name):
     want = oracle_run(spec, ins)
     dtype = spec.outputs[0][1]
     max_abs, max_rel = compare(outs[0], want[0], dtype, f"{name} full size")
+    _report_ulps(name, outs[0], want[0], dtype)
     print(f"{name}: family {info.family} variant {info.variant} spec {info.spec_id} max-abs {max_abs:.3e} max-rel {max_rel:.3e}")
     assert info.spec_id > 0 and info.n_launches == 1          # a catalogue kernel, one launch per chain
     if name == "C2":
@@ -54,6 +67,7 @@ def test_full_size_extra_chains_match_oracle(name):
     outs, info = _run_default(spec, ins)
     want = oracle_run(spec, ins)
     max_abs, max_rel = compare(outs[0], want[0], spec.outputs[0][1], f"{name} full size")
+    _report_ulps(name, outs[0], want[0], spec.outputs[0][1])
     print(f"{name}: family {info.family} variant {info.variant} spec {info.spec_id} max-abs {max_abs:.3e} max-rel {max_rel:.3e}")
     assert info.n_launches == 1
     if name == "X4":
