@@ -151,6 +151,9 @@ struct GroupGeom {
     uint32_t spin_limit;         // resident variant: bounded wait, then the error flag is raised
     uint32_t* ws_error;          // resident variant: set to 1 if a wait ran out
     FastDiv div_cv;
+    // groups of any width (GEN kernels): channels per group, its divider, and the most groups one vector touches
+    uint32_t cpg, parts;
+    FastDiv div_cpg;
 };
 
 // Attention family (one new token against cached keys and values); all tensors of one storage type.

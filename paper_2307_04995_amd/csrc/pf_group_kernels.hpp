@@ -191,6 +191,35 @@ PF_DEVICE bool gather_sample(const GroupGeom& g, uint32_t sample, float eps, uin
     return in_range && j == 0u;
 }
 
+// ---- groups of any width (GEN instantiations) ---------------------------------------------------------
+// When the channels of a group are not a power-of-two number of whole 16-byte vectors (10 channels per group
+// in a 320-channel layer, 4 in a 128-channel one), a lane's vector can straddle groups and the lanes of a
+// group are no aligned power-of-two run.  Every lane then keeps its sums per element, cuts them into `parts`
+// (one per group its vector touches), and parks one (count, mean, M2) triple per part in LDS; the triples of
+// a group are merged by lanes_per_group threads that walk the lanes whose vectors touch that group.
+// Returns true in the thread that ends up with group *grp_out's merged triple.
+template <int VEC>
+PF_DEVICE bool merge_parts_of_block(const GroupGeom& g, const float* lds_gen, uint32_t* grp_out, Stat* out) {
+    const uint32_t lpg = g.lanes_per_group;
+    const uint32_t grp = threadIdx.x / lpg, j = threadIdx.x - grp * lpg;
+    const bool in_range = grp < g.groups;
+    Stat acc = {0.0f, 0.0f, 0.0f};
+    if (in_range) {
+        const uint32_t cv_lo = (grp * g.cpg) / (uint32_t)VEC, cv_hi = ((grp + 1u) * g.cpg - 1u) / (uint32_t)VEC;
+        const uint32_t ncv = cv_hi - cv_lo + 1u, entries = ncv * g.pos_per_step;
+        for (uint32_t idx = j; idx < entries; idx += lpg) {
+            const uint32_t ps = idx / ncv, cvx = cv_lo + (idx - ps * ncv);
+            const uint32_t part = grp - fast_div(cvx * (uint32_t)VEC, g.div_cpg);
+            const float* q = lds_gen + ((ps * g.cv + cvx) * g.parts + part) * 3u;
+            acc = stat_merge(acc, Stat{q[0], q[1], q[2]});
+        }
+    }
+    for (uint32_t m = 1; m < lpg; m <<= 1) acc = stat_merge(acc, stat_shfl_xor(acc, (int)m));
+    *grp_out = grp;
+    *out = acc;
+    return in_range && j == 0u;
+}
+
 // One kernel template, three phases:
 //   PHASE 0  fused: statistics, device-scope exchange and normalisation in one launch (RESIDENT variant)
 //   PHASE 1  statistics only: writes the workgroup partials               (TWO_PASS, first launch)
@@ -209,18 +238,31 @@ PF_DEVICE bool gather_sample(const GroupGeom& g, uint32_t sample, float eps, uin
 // Exchange of PHASE 0: see publish_tile / gather_sample above.  All shared words travel by device-coherent
 // (agent-scope atomic) accesses, so no cache write-back or invalidate is needed around them -- a write-back
 // here would wait for every output line other workgroups have just stored.
-template <int DT, int NV, class Spec, int PHASE>
+//
+// GEN > 0: groups of any width (see merge_parts_of_block); GEN bounds the groups one vector can touch
+// (geometry `parts` <= GEN); needs 512 * parts * 12 bytes of dynamic LDS.
+template <int DT, int NV, class Spec, int PHASE, int GEN = 0>
 __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     // kLean: 16-bit storage and nothing but the load in front of the normalisation
-    constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
-    __shared__ float lds_part[512 * 3];
+    constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32 && !GEN;
+    __shared__ float lds_part[GEN ? 1 : 512 * 3];
     __shared__ float lds_stat[512 * 2];
+    extern __shared__ float lds_gen[];  // GEN: [lane][part] (count, mean, M2)
     const uint32_t t = threadIdx.x;
     const uint32_t pstep = fast_div(t, g.div_cv);
     const uint32_t cvi = t - pstep * g.cv;
     const bool active = pstep < g.pos_per_step;
+    // GEN: the part (group, relative to the lane's first group) each element of the lane's vector belongs to,
+    // four bits per element
+    uint32_t part_code = 0, first_grp = 0;
+    if (GEN) {
+        first_grp = fast_div(cvi * (uint32_t)VEC, g.div_cpg);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) part_code |= (fast_div(cvi * (uint32_t)VEC + (uint32_t)e, g.div_cpg) - first_grp) << (4 * e);
+    }
+    auto part_of = [&](int e) { return (part_code >> (4 * e)) & 15u; };
 
     // The fused kernel is only planned for per-channel broadcast operands; making that a compile-time fact keeps
     // the per-position operand loads (and the waits the compiler puts at their control-flow joins, which would
@@ -277,7 +319,80 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             else run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
         };
 
-        if (PHASE != 2) {
+        if (PHASE != 2 && GEN) {
+            // ---- partial statistics: sums of deviations from the lane's first value, kept per part (per element
+            // when a vector can touch more than two groups), then one (count, mean, M2) triple per part into LDS
+            constexpr int NACC = GEN == 0 ? 1 : GEN <= 2 ? GEN : VEC;
+            float pivot = 0.0f, npos = 0.0f, sa[NACC], ssa[NACC];
+#pragma unroll
+            for (int q = 0; q < NACC; ++q) sa[q] = ssa[q] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                prologue(i);
+                if (valid_of(i)) {
+                    if (npos == 0.0f) pivot = s.acc[0];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const float d = s.acc[e] - pivot;
+                        if (GEN == 1) {
+                            sa[0] += d;
+                            ssa[0] += d * d;
+                        } else if (GEN == 2) {
+                            const bool hi = part_of(e) != 0u;
+                            const float d0 = hi ? 0.0f : d, d1 = hi ? d : 0.0f;
+                            sa[0] += d0;
+                            ssa[0] += d0 * d0;
+                            sa[NACC - 1] += d1;
+                            ssa[NACC - 1] += d1 * d1;
+                        } else {
+                            sa[e % NACC] += d;
+                            ssa[e % NACC] += d * d;
+                        }
+                    }
+                    npos += 1.0f;
+                }
+            }
+            for (uint32_t part = 0; part < g.parts; ++part) {
+                float sum = 0.0f, sq = 0.0f, cnt = 0.0f;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if (part_of(e) == part) {
+                        cnt += 1.0f;
+                        if (GEN > 2) {
+                            sum += sa[e % NACC];
+                            sq += ssa[e % NACC];
+                        }
+                    }
+                if (GEN <= 2) {
+                    sum = part == 0u ? sa[0] : sa[NACC - 1];
+                    sq = part == 0u ? ssa[0] : ssa[NACC - 1];
+                }
+                const float n = active ? npos * cnt : 0.0f;
+                const float inv = n > 0.0f ? 1.0f / n : 0.0f;
+                float* q = lds_gen + (t * g.parts + part) * 3u;
+                q[0] = n;
+                q[1] = pivot + sum * inv;
+                q[2] = fmaxf(sq - sum * sum * inv, 0.0f);
+            }
+            __syncthreads();
+            uint32_t grp;
+            Stat acc;
+            if (merge_parts_of_block<VEC>(g, lds_gen, &grp, &acc)) {
+                if (PHASE == 0) {
+                    const uint64_t per_parity = (uint64_t)g.samples * g.groups * g.blocks_per_sample;
+                    const uint64_t slot = ((uint64_t)sample * g.groups + grp) * g.blocks_per_sample + bx;
+                    const uint32_t par = g.epoch & 1u;
+                    __hip_atomic_store(g.ws_gather + (par ^ 1u) * per_parity + slot, kSlotEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(g.ws_gather + par * per_parity + slot, pack_slot(acc.mean, acc.m2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    float* o = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.groups + grp) * 4u;
+                    o[0] = acc.n;
+                    o[1] = acc.mean;
+                    o[2] = acc.m2;
+                }
+            }
+        }
+        if (PHASE != 2 && !GEN) {
             // ---- partial statistics from registers
             LaneAcc la;
 #pragma unroll
@@ -322,9 +437,21 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             __syncthreads();
         }
 
+        if (PHASE == 0 && !kLean) {
+            // The prologue is run again on the packed values below.  Without this fence the compiler keeps the
+            // widened values of the statistics pass alive across the exchange instead (NV * VEC more registers).
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t w = raw[i][j];
+                    asm volatile("" : "+v"(w));
+                    raw[i][j] = w;
+                }
+        }
         // ---- normalise straight from registers: y = x * A + B with A = rstd * gamma, B = beta - mean * A per
         // channel, so each element costs one fused multiply-add (taken directly from the fp16 value)
-        const uint32_t my_grp = cvi >> g.log2_vpg;
+        const uint32_t my_grp = GEN ? first_grp : cvi >> g.log2_vpg;
         const float mean = lds_stat[my_grp * 2u], rstd = lds_stat[my_grp * 2u + 1u];
         float A[VEC], B[VEC];
         auto affine = [&]() {
@@ -338,8 +465,11 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             if (Spec::beta(a) >= 0) fetch_vec<DT, 1, Spec>(s, Spec::beta(a), bt);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
-                A[e] = rstd * gm[e];
-                B[e] = bt[e] - mean * A[e];
+                // GEN: the element's own group (its statistics sit part_of[e] entries further)
+                const float r = GEN ? lds_stat[(my_grp + part_of(e)) * 2u + 1u] : rstd;
+                const float m = GEN ? lds_stat[(my_grp + part_of(e)) * 2u] : mean;
+                A[e] = r * gm[e];
+                B[e] = bt[e] - m * A[e];
             }
         };
         if (vec_per_channel) affine();

@@ -1094,6 +1094,8 @@ struct pf_plan_s {
     pf::StencilGeom stencil;
     int stencil_ks = 3;       // kernel extent of the depthwise convolution
     int row_log2l = 6;        // row family: log2 of the lanes of a wave that share a row
+    bool group_general = false; // group family: groups of any width (general kernels)
+    uint32_t dyn_lds = 0;     // group family: dynamic LDS bytes of each launch
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
     dim3 grid2, block2;       // second launch (two-pass group variant)
@@ -1559,9 +1561,11 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     if ((C * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)C);
     if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the group family is not a multiple of 16 bytes");
     const int64_t cpg = C / G;
-    if (cpg % vec != 0) return fail(PF_ERR_UNSUPPORTED, "channels per group (%lld) must be a multiple of %d", (long long)cpg, vec);
     const int64_t vpg = cpg / vec, cv = C / vec;
-    if ((vpg & (vpg - 1)) != 0 || vpg > 64) return fail(PF_ERR_UNSUPPORTED, "channels per group / %d must be a power of two <= 64", vec);
+    // Groups that are a power-of-two number of whole vectors take the kernels' shuffle-tree path; any other width
+    // takes the general one (per-element sums, parts merged through LDS).
+    const bool general = cpg % vec != 0 || (vpg & (vpg - 1)) != 0 || vpg > 64 || env_int("PF_GROUP_GENERAL", 0) != 0;
+    if (general && G > 512) return fail(PF_ERR_UNSUPPORTED, "more than 512 groups");
     if (samples * hw > 0xffffffffLL || samples > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
     for (int v = 0; v < L.n_vec; ++v)
         if (p->args.vec[v].numel > (uint32_t)C && p->args.vec[v].numel != 1)
@@ -1581,9 +1585,17 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     g.log2_vpg = 0;
     while ((1u << g.log2_vpg) < g.vpg) ++g.log2_vpg;
     g.div_cv = make_fastdiv(g.cv);
+    g.cpg = (uint32_t)cpg;
+    g.div_cpg = make_fastdiv(g.cpg);
+    g.parts = 1;
+    for (int64_t v = 0; v < cv; ++v) g.parts = std::max<uint32_t>(g.parts, (uint32_t)((v * vec + vec - 1) / cpg - (v * vec) / cpg + 1));
+    const uint32_t gen_lds = general ? 512u * g.parts * 3u * (uint32_t)sizeof(float) : 0u;
+    p->group_general = general;
+    // specialised kernels know the bound exactly (1, 2, or up to 8 = a vector's elements)
+    const int gen_parts = !general ? 0 : g.parts <= 2 ? (int)g.parts : 8;
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
-    p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().group, L);
+    p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);
 
     hipDeviceProp_t prop;
     if (hipSetDevice(p->device) != hipSuccess || hipGetDeviceProperties(&prop, p->device) != hipSuccess)
@@ -1612,6 +1624,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     uint32_t bps = 0;
     for (int ci = 0; ci < 3 && nv == 0; ++ci) {
         if (forced_nv && cands[ci] != forced_nv) continue;
+        if (general && cands[ci] == 16 && !forced_nv) continue;  // (the general kernels' registers hold 8 vectors at most)
         uint32_t b;
         tiling(cands[ci], &b);
         if ((uint64_t)b * samples >= 2 * (uint64_t)n_cu || ci == 2 || forced_nv) {
@@ -1632,12 +1645,12 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     bool resident_ok = L.n_full == 1 && g.vec_per_channel && forced_variant != PF_VARIANT_GROUP_TWO_PASS;
     if (resident_ok && p->spec_id == 0) {
         // not in the catalogue: the fused kernel exists only if it can be specialised now
-        fused_fn = jit_ok ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 0, jspec, &jit_err) : nullptr;
+        fused_fn = jit_ok ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 0, gen_parts, jspec, &jit_err) : nullptr;
         if (!fused_fn) resident_ok = false;
     }
     uint32_t res_grid = 0;
     if (resident_ok) {
-        const int per_cu = fused_fn ? pf::jit_blocks_per_cu(fused_fn, (int)threads)
+        const int per_cu = fused_fn ? pf::jit_blocks_per_cu(fused_fn, (int)threads, gen_lds)
                                     : pf::group_resident_blocks_per_cu(p->spec_id, L.main_dtype, nv, (int)threads);
         const uint64_t cap = (uint64_t)std::max(per_cu, 0) * n_cu;
         uint64_t grid = std::min<uint64_t>(tiles, cap);
@@ -1668,14 +1681,15 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
         p->block2 = p->block;
         p->n_launches = 2;
         if (jit_ok) {
-            p->jit_fn = pf::jit_group_kernel(p->device, L.main_dtype, nv, 1, jspec, &jit_err);
-            p->jit_fn2 = p->jit_fn ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 2, jspec, &jit_err) : nullptr;
+            p->jit_fn = pf::jit_group_kernel(p->device, L.main_dtype, nv, 1, gen_parts, jspec, &jit_err);
+            p->jit_fn2 = p->jit_fn ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 2, gen_parts, jspec, &jit_err) : nullptr;
             if (p->jit_fn && p->jit_fn2) p->spec_id = pf::kSpecJit;
         }
     }
     if (jit_ok && p->spec_id == 0 && env_int("PF_LOG", 0))
         fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", jit_err.c_str());
-    p->lds_bytes = 512 * 3 * 4 + 512 * 2 * 4 + 4;
+    p->lds_bytes = general ? gen_lds + 512 * 2 * 4 + 4 : 512 * 3 * 4 + 512 * 2 * 4 + 4;
+    p->dyn_lds = gen_lds;
     // workspace: partials of the two-launch variant, or two parities of exchange words (all-ones = empty) of the
     // resident one; then the error word
     const uint64_t part_bytes = variant == PF_VARIANT_GROUP_RESIDENT ? 0 : (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
@@ -2229,14 +2243,16 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (plan->spec_id == pf::kSpecJit) {
                 uint32_t t = tiles;
                 void* params[] = {&a, &g, &t};
-                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, 0, params, st);
+                e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, plan->dyn_lds, params, st);
                 if (e == hipSuccess && plan->variant == PF_VARIANT_GROUP_TWO_PASS)
-                    e = pf::jit_launch(plan->jit_fn2, plan->grid2, plan->block2, 0, params, st);
+                    e = pf::jit_launch(plan->jit_fn2, plan->grid2, plan->block2, plan->dyn_lds, params, st);
             } else if (plan->variant == PF_VARIANT_GROUP_TWO_PASS) {
-                e = pf::launch_group(1, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, st);
-                if (e == hipSuccess) e = pf::launch_group(2, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid2, plan->block2, st);
+                const bool gen = plan->group_general;
+                e = pf::launch_group(1, gen, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, plan->dyn_lds, st);
+                if (e == hipSuccess)
+                    e = pf::launch_group(2, gen, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid2, plan->block2, plan->dyn_lds, st);
             } else {
-                e = pf::launch_group(0, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, st);
+                e = pf::launch_group(0, false, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, 0, st);
             }
             break;
         }

@@ -172,9 +172,9 @@ hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, const J
     return compile(device, "#include \"pf_perm_kernels.hpp\"\n", name.str(), err);
 }
 
-hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, const JitSpec& spec, std::string* err) {
+hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
-    name << "pf::group_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << phase << ">";
+    name << "pf::group_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << phase << ", " << general_parts << ">";
     return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
 }
 
@@ -185,9 +185,9 @@ hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, con
     return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
 }
 
-int jit_blocks_per_cu(hipFunction_t fn, int block_threads) {
+int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes) {
     int n = 0;
-    if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, block_threads, 0) != hipSuccess) return 0;
+    if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, block_threads, lds_bytes) != hipSuccess) return 0;
     return n;
 }
 

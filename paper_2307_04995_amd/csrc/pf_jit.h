@@ -35,11 +35,11 @@ hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const Jit
 // transpose family: variant 0 rows (k vectors per lane), 1 LDS-staged rows, 2 register-transposed tiles
 hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, const JitSpec& spec, std::string* err);
 // group family: phase 0 fused, 1 statistics, 2 normalisation
-hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, const JitSpec& spec, std::string* err);
+hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err);
 // stencil family (depthwise 3 x 3 convolution)
 hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, const JitSpec& spec, std::string* err);
 // workgroups of `block_threads` threads one compute unit holds at once
-int jit_blocks_per_cu(hipFunction_t fn, int block_threads);
+int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes = 0);
 
 // params: addresses of the kernel's arguments, in order; lds_bytes: dynamic LDS
 hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, uint32_t lds_bytes, void** params, hipStream_t st);

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as wl
-from pf_testlib import check_chain, compare, gpu_run, oracle_run
+from pf_testlib import check_chain, compare, gpu_run, oracle_run, SPEC_JIT
 
 pytestmark = pytest.mark.gpu
 
@@ -109,6 +109,38 @@ def test_c5_chain(n, h, w, c, g, dtype, variant, generic):
     _, info, _ = check_chain(spec, ins, variant=variant, generic=generic, what=f"C5 {dtype} v{variant}")
     assert info.family == pf.PF_FAMILY_GROUP and info.variant == variant
     assert info.n_launches == (2 if variant == 0 else 1)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("n,h,w,c,g,dtype", [
+    (2, 16, 16, 320, 32, "f16"),    # 10 channels per group: a 16-byte vector straddles two groups
+    (2, 8, 8, 128, 32, "f16"),      # 4 per group: two groups per vector
+    (1, 12, 12, 96, 32, "bf16"),    # 3 per group: up to four groups per vector
+    (2, 6, 6, 1280, 32, "f16"),     # 40 per group: five vectors, not a power of two
+    (2, 9, 9, 48, 4, "f32"),        # 12 per group in fp32: three vectors
+    (1, 8, 8, 64, 64, "f16"),       # one channel per group
+    (2, 5, 7, 24, 1, "f16"),        # one group over the whole sample
+    (3, 40, 40, 320, 32, "f16"),    # several workgroups per sample
+])
+def test_groupnorm_groups_of_any_width(n, h, w, c, g, dtype, variant):
+    pf = _pf()
+    spec, ins = wl.c5_groupnorm_silu(n=n, h=h, w=w, ch=c, groups=g, dtype=dtype, salt=7)
+    _, info, _ = check_chain(spec, ins, variant=variant, what=f"GroupNorm {c} channels / {g} groups {dtype} v{variant}")
+    assert info.family == pf.PF_FAMILY_GROUP and info.variant == variant
+    assert info.n_launches == (2 if variant == 0 else 1)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_groupnorm_general_path_matches_the_aligned_one(variant):
+    # the same chain through both statistics paths (the general one forced on a shape that does not need it)
+    from pf_testlib import env
+    spec, ins = wl.c5_groupnorm_silu(n=2, h=24, w=24, ch=512, groups=32, dtype="f16", salt=8)
+    fast, _ = gpu_run(spec, ins, variant=variant)
+    with env(PF_GROUP_GENERAL="1"):
+        outs, info, _ = check_chain(spec, ins, variant=variant, what="general statistics path on an aligned shape")
+    assert info.spec_id == SPEC_JIT
+    diff = np.abs(wl.widen(outs[0]) - wl.widen(fast[0]))
+    assert diff.max() <= 4e-3
 
 
 # ------------------------------------------------------------------ layout-only chains, bit-exact
