@@ -163,6 +163,8 @@ typedef struct {
 
 #define PF_VARIANT_EW_FLAT 0          /* element-wise: one 16-byte vector per lane per step                  */
 #define PF_SPEC_JIT 255               /* pf_plan_info.spec_id of a plan-time specialised kernel                */
+#define PF_VARIANT_ATTN_ONE_PASS 0    /* attention family: a workgroup's slice of the cache in registers at once       */
+#define PF_VARIANT_ATTN_STREAM 1      /* attention family: longer slices walked in chunks, next chunk's loads in flight */
 #define PF_VARIANT_STENCIL_DIRECT 0   /* stencil family: a register window per lane, neighbours through the cache */
 #define PF_VARIANT_STENCIL_STAGED 1   /* stencil family: the workgroup's tile is activated once and shared in LDS  */
 #define PF_VARIANT_ROW_WAVE 0         /* row family: one 64-lane wave owns a row                             */

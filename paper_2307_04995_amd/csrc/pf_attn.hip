@@ -22,6 +22,92 @@ namespace pf {
 
 PF_DEVICE float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
+// Publish a slice's partial result (weighted value sum of column `tid` in o_mine, maximum m, sum of exponentials
+// l_blk); the workgroup whose arrival completes the head's counter merges all slices and writes the output row.
+// lds_o is workgroup scratch of 4 x 256 floats, s_last one shared word.
+template <int DT>
+PF_DEVICE void finish_slice(const AttnArgs& a, uint32_t head, uint32_t split, float o_mine, float m, float l_blk,
+                            float (*lds_o)[256], uint32_t* s_last_p) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr bool PR = S::PRECISE;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t d = a.d;
+    const uint32_t n_split = gridDim.x;
+    float* part = a.ws_partial + ((uint64_t)head * n_split + split) * (d + 2u);
+    if (n_split == 1u) {
+        if (tid < d) {
+            const float r = PR ? o_mine / l_blk : o_mine * __builtin_amdgcn_rcpf(l_blk);
+            if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
+            else {
+                float tmp[VEC] = {r};
+                static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+            }
+        }
+        return;
+    }
+    // published with device-coherent stores: the merging workgroup may run on another compute die
+    if (tid < d) __hip_atomic_store(part + tid, o_mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        __hip_atomic_store(part + d, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part + d + 1u, l_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(a.ws_counter + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = before + 1u == n_split;
+        // nobody touches the counter again before the next launch on this stream: re-arm it
+        if (last) __hip_atomic_store(a.ws_counter + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_last_p = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!*s_last_p) return;
+
+    // ---- the last workgroup of the head merges the slices: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+    // All 256 threads take part: thread (g, c) sums column c over the slices s = g, g + G, ... (G = 256 / d'
+    // groups, d' = d rounded up to a power of two), so the loads of many slices are in flight together; the
+    // groups are then combined through LDS.
+    const float* base = a.ws_partial + (uint64_t)head * n_split * (d + 2u);
+    uint32_t dp = 1;
+    while (dp < d) dp <<= 1;
+    const uint32_t groups = 256u / dp, g = tid / dp, c = tid - g * dp;
+    float big = -__builtin_inff();
+    for (uint32_t s = lane; s < n_split; s += 64u)
+        big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * (d + 2u) + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    for (int msk = 1; msk < 64; msk <<= 1) big = fmaxf(big, shfl_xor_f(big, msk));  // every wave finds the same maximum
+    float num = 0.0f, den = 0.0f;
+    for (uint32_t s = g; s < n_split; s += groups) {
+        const float* ps = base + (uint64_t)s * (d + 2u);
+        const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float os = c < d ? __hip_atomic_load(ps + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+        const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
+        num = __builtin_fmaf(os, w, num);
+        den = __builtin_fmaf(ls, w, den);
+    }
+    float* red_num = &lds_o[0][0];  // [groups][dp] (the per-wave partials are no longer needed)
+    float* red_den = &lds_o[2][0];
+    __syncthreads();
+    red_num[tid] = num;
+    red_den[tid] = den;
+    __syncthreads();
+    if (tid < d) {
+        num = 0.0f;
+        den = 0.0f;
+        for (uint32_t gg = 0; gg < groups; ++gg) {
+            num += red_num[gg * dp + tid];
+            den += red_den[gg * dp + tid];
+        }
+        const float r = PR ? num / den : num * __builtin_amdgcn_rcpf(den);
+        if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
+        else {
+            float tmp[VEC] = {r};
+            static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+        }
+    }
+}
+
 template <int DT, int NV>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     using S = Storage<DT>;
@@ -123,86 +209,160 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     __syncthreads();
 
     // ---- the slice's partial result
-    const uint32_t n_split = gridDim.x;
-    float* part = a.ws_partial + ((uint64_t)head * n_split + split) * (d + 2u);
     float o_mine = 0.0f;
     if (tid < d) o_mine = lds_o[0][tid] + lds_o[1][tid] + lds_o[2][tid] + lds_o[3][tid];
     const float l_blk = lds_l[0] + lds_l[1] + lds_l[2] + lds_l[3];
-    if (n_split == 1u) {
-        if (tid < d) {
-            const float r = PR ? o_mine / l_blk : o_mine * __builtin_amdgcn_rcpf(l_blk);
-            if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
-            else {
-                float tmp[VEC] = {r};
-                static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+    finish_slice<DT>(a, head, split, o_mine, m, l_blk, lds_o, &s_last);
+}
+
+// Streaming variant: a workgroup walks a longer slice of the head in chunks of NV steps, the loads of the next
+// chunk in flight while the current one is consumed (two register buffers).  Every lane keeps its own running
+// (maximum, sum of exponentials, weighted value sum) over the rows it has seen -- the mergeable form again, so
+// nothing crosses lanes per chunk except the dot products of the lanes that share a row; row groups, waves and
+// finally slices are merged once at the end.  Fewer, longer slices mean fewer partial results and fewer
+// workgroups that sit through the publish / count / merge tail with nothing in flight.
+template <int DT, int NV>
+__global__ void __launch_bounds__(256) attn_decode_stream_kernel(const AttnArgs a) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr bool PR = S::PRECISE;
+    __shared__ float lds_m[4], lds_l[4];
+    __shared__ float lds_o[4][256];
+    __shared__ uint32_t s_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lpr = a.lanes_per_row;
+    const uint32_t in_row = tid & (lpr - 1u);
+    const uint32_t row_in_step = tid >> a.log2_lpr;
+    const uint32_t rps = 256u >> a.log2_lpr;
+    const uint32_t head = blockIdx.y, split = blockIdx.x;
+    const uint32_t chunk_rows = (uint32_t)NV * rps;
+    const uint32_t d = a.d, t = a.t, t_total = a.t_total;
+    const uint32_t row_begin = split * a.chunks * chunk_rows;
+    const uint32_t row_end = min(t_total, row_begin + a.chunks * chunk_rows);
+    const uint32_t n_chunks = (row_end - row_begin + chunk_rows - 1u) / chunk_rows;  // >= 1: the planner leaves no slice empty
+
+    const uint64_t head_vec = (uint64_t)head * d + in_row * VEC;
+    float qf[VEC];
+    S::unpack(load_cached(a.q, head_vec * S::ESIZE), qf);
+    auto neg_exp = [](float x) { return PR ? expf(x) : __builtin_amdgcn_exp2f(x * kLog2e); };
+
+    auto load_chunk = [&](uint32_t c, u32x4 (&kr)[NV], u32x4 (&vr)[NV]) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t row = row_begin + c * chunk_rows + (uint32_t)i * rps + row_in_step;
+            kr[i] = u32x4{0u, 0u, 0u, 0u};
+            vr[i] = u32x4{0u, 0u, 0u, 0u};
+            if (row < t) {
+                const uint64_t off = (((uint64_t)head * t + row) * d + in_row * VEC) * S::ESIZE;
+                kr[i] = load_stream(a.k_cache, off);
+                vr[i] = load_stream(a.v_cache, off);
+            } else if (row < t_total) {  // the appended row
+                kr[i] = load_cached(a.k_new, head_vec * S::ESIZE);
+                vr[i] = load_cached(a.v_new, head_vec * S::ESIZE);
             }
         }
-        return;
-    }
-    // published with device-coherent stores: the merging workgroup may run on another compute die
-    if (tid < d) __hip_atomic_store(part + tid, o_mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) {
-        __hip_atomic_store(part + d, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(part + d + 1u, l_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t before = __hip_atomic_fetch_add(a.ws_counter + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = before + 1u == n_split;
-        // nobody touches the counter again before the next launch on this stream: re-arm it
-        if (last) __hip_atomic_store(a.ws_counter + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = last ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!s_last) return;
+    };
+    float m = -__builtin_inff(), l = 0.0f, acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+    auto consume = [&](uint32_t c, const u32x4 (&kr)[NV], const u32x4 (&vr)[NV]) {
+        // the grown caches, if they are outputs
+        if (a.k_out != nullptr || a.v_out != nullptr) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const uint32_t row = row_begin + c * chunk_rows + (uint32_t)i * rps + row_in_step;
+                if (row < t_total) {
+                    const uint64_t off = (((uint64_t)head * t_total + row) * d + in_row * VEC) * S::ESIZE;
+                    if (a.k_out != nullptr) store_stream(a.k_out, off, kr[i]);
+                    if (a.v_out != nullptr) store_stream(a.v_out, off, vr[i]);
+                }
+            }
+        }
+        float sc[NV], cm = -__builtin_inff();
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t row = row_begin + c * chunk_rows + (uint32_t)i * rps + row_in_step;
+            float kf[VEC];
+            S::unpack(kr[i], kf);
+            float dot = 0.0f;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) dot = __builtin_fmaf(kf[e], qf[e], dot);
+            for (uint32_t msk = 1; msk < lpr; msk <<= 1) dot += shfl_xor_f(dot, (int)msk);
+            sc[i] = row < t_total ? dot * a.scale : -__builtin_inff();
+            cm = fmaxf(cm, sc[i]);
+        }
+        const float m_new = fmaxf(m, cm);
+        if (m_new == -__builtin_inff()) return;  // this lane has not seen a row yet
+        const float keep = m == -__builtin_inff() ? 0.0f : neg_exp(m - m_new);
+        l *= keep;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] *= keep;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const float p = neg_exp(sc[i] - m_new);  // exp(-inf) = 0 for rows past the end
+            l += p;
+            float vf[VEC];
+            S::unpack(vr[i], vf);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(p, vf[e], acc[e]);
+        }
+        m = m_new;
+    };
 
-    // ---- the last workgroup of the head merges the slices: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M).
-    // All 256 threads take part: thread (g, c) sums column c over the slices s = g, g + G, ... (G = 256 / d'
-    // groups, d' = d rounded up to a power of two), so the loads of many slices are in flight together; the
-    // groups are then combined through LDS.
-    const float* base = a.ws_partial + (uint64_t)head * n_split * (d + 2u);
-    uint32_t dp = 1;
-    while (dp < d) dp <<= 1;
-    const uint32_t groups = 256u / dp, g = tid / dp, c = tid - g * dp;
-    float big = -__builtin_inff();
-    for (uint32_t s = lane; s < n_split; s += 64u)
-        big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * (d + 2u) + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    for (int msk = 1; msk < 64; msk <<= 1) big = fmaxf(big, shfl_xor_f(big, msk));  // every wave finds the same maximum
-    float num = 0.0f, den = 0.0f;
-    for (uint32_t s = g; s < n_split; s += groups) {
-        const float* ps = base + (uint64_t)s * (d + 2u);
-        const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float os = c < d ? __hip_atomic_load(ps + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
-        const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
-        num = __builtin_fmaf(os, w, num);
-        den = __builtin_fmaf(ls, w, den);
-    }
-    float* red_num = &lds_o[0][0];  // [groups][dp] (the per-wave partials are no longer needed)
-    float* red_den = &lds_o[2][0];
-    __syncthreads();
-    red_num[tid] = num;
-    red_den[tid] = den;
-    __syncthreads();
-    if (tid < d) {
-        num = 0.0f;
-        den = 0.0f;
-        for (uint32_t gg = 0; gg < groups; ++gg) {
-            num += red_num[gg * dp + tid];
-            den += red_den[gg * dp + tid];
-        }
-        const float r = PR ? num / den : num * __builtin_amdgcn_rcpf(den);
-        if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
-        else {
-            float tmp[VEC] = {r};
-            static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+    u32x4 k0[NV], v0[NV], k1[NV], v1[NV];
+    load_chunk(0u, k0, v0);
+    for (uint32_t c = 0; c < n_chunks; c += 2u) {
+        if (c + 1u < n_chunks) load_chunk(c + 1u, k1, v1);
+        consume(c, k0, v0);
+        if (c + 1u < n_chunks) {
+            if (c + 2u < n_chunks) load_chunk(c + 2u, k0, v0);
+            consume(c + 1u, k1, v1);
         }
     }
+
+    // ---- merge the row groups of the wave, then the four waves
+    auto weight = [&](float mine, float top) { return mine == -__builtin_inff() ? 0.0f : neg_exp(mine - top); };
+    for (uint32_t msk = lpr; msk < 64u; msk <<= 1) {
+        const float m_o = shfl_xor_f(m, (int)msk), l_o = shfl_xor_f(l, (int)msk);
+        const float top = fmaxf(m, m_o);
+        const float wa = weight(m, top), wb = weight(m_o, top);
+        l = l * wa + l_o * wb;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = acc[e] * wa + shfl_xor_f(acc[e], (int)msk) * wb;
+        m = top;
+    }
+    if (lane == 0) {
+        lds_m[wave] = m;
+        lds_l[wave] = l;
+    }
+    if (lane < lpr) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) lds_o[wave][in_row * VEC + e] = acc[e];
+    }
+    __syncthreads();
+    const float top = fmaxf(fmaxf(lds_m[0], lds_m[1]), fmaxf(lds_m[2], lds_m[3]));
+    float o_mine = 0.0f, l_blk = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float ww = weight(lds_m[w], top);
+        l_blk += lds_l[w] * ww;
+        if (tid < d) o_mine += lds_o[w][tid] * ww;
+    }
+    finish_slice<DT>(a, head, split, o_mine, top, l_blk, lds_o, &s_last);
 }
 
 template <int DT>
-static hipError_t launch_attn_dt(const AttnArgs& a, int nv, dim3 grid, hipStream_t st) {
+static hipError_t launch_attn_dt(const AttnArgs& a, int variant, int nv, dim3 grid, hipStream_t st) {
+    if (variant == 1) {
+        switch (nv) {
+            case 2: hipLaunchKernelGGL((attn_decode_stream_kernel<DT, 2>), grid, dim3(256), 0, st, a); break;
+            case 4: hipLaunchKernelGGL((attn_decode_stream_kernel<DT, 4>), grid, dim3(256), 0, st, a); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     switch (nv) {
         case 1: hipLaunchKernelGGL((attn_decode_kernel<DT, 1>), grid, dim3(256), 0, st, a); break;
         case 2: hipLaunchKernelGGL((attn_decode_kernel<DT, 2>), grid, dim3(256), 0, st, a); break;
@@ -213,11 +373,11 @@ static hipError_t launch_attn_dt(const AttnArgs& a, int nv, dim3 grid, hipStream
     return hipGetLastError();
 }
 
-hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int nv, dim3 grid, hipStream_t st) {
+hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int variant, int nv, dim3 grid, hipStream_t st) {
     switch (dtype) {
-        case DT_F32: return launch_attn_dt<DT_F32>(a, nv, grid, st);
-        case DT_F16: return launch_attn_dt<DT_F16>(a, nv, grid, st);
-        case DT_BF16: return launch_attn_dt<DT_BF16>(a, nv, grid, st);
+        case DT_F32: return launch_attn_dt<DT_F32>(a, variant, nv, grid, st);
+        case DT_F16: return launch_attn_dt<DT_F16>(a, variant, nv, grid, st);
+        case DT_BF16: return launch_attn_dt<DT_BF16>(a, variant, nv, grid, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -172,6 +172,7 @@ struct AttnArgs {
     uint32_t d;           // head dimension (elements), at most 256
     uint32_t lanes_per_row, log2_lpr;
     float scale;
+    uint32_t chunks;      // streaming variant: chunks (of NV steps of 256 / lanes_per_row rows) a workgroup walks
 };
 
 // Stencil family (depthwise 3 x 3 convolution on a channels-last tensor) geometry.

@@ -19,7 +19,7 @@ hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeo
 // phase 0: fused (resident) kernel; 1: statistics launch; 2: normalisation launch
 hipError_t launch_group(int phase, bool general, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,
                         dim3 grid, dim3 block, uint32_t lds, hipStream_t st);
-hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int nv, dim3 grid, hipStream_t st);
+hipError_t launch_attn_decode(int dtype, const AttnArgs& a, int variant, int nv, dim3 grid, hipStream_t st);
 hipError_t launch_stencil(int dtype, const ChainArgs& a, const StencilGeom& g, int variant, int ks, uint32_t lds, dim3 grid, hipStream_t st);
 hipError_t launch_gather(int dtype, const GatherArgs& a, dim3 grid, hipStream_t st);
 int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads);

@@ -37,6 +37,41 @@ def test_every_split_shape_gives_the_same_answer(nv):
     assert info.grid[0] == -(-200 // (32 * nv))
 
 
+@pytest.mark.parametrize("b,h,t,d,dtype", [(1, 12, 1023, 64, "f16"), (2, 3, 37, 64, "bf16"), (1, 2, 129, 128, "f16"),
+                                           (1, 4, 300, 64, "f32"), (1, 1, 1, 64, "f16"), (1, 3, 2049, 256, "bf16")])
+@pytest.mark.parametrize("chunks", [2, 3, 8])
+def test_streaming_walk_over_longer_slices(b, h, t, d, dtype, chunks):
+    # the variant that walks its slice in chunks with running (maximum, sum, weighted values) per lane; slices
+    # that end inside a chunk, lanes and waves that never see a row, a single slice (no merge) all occur here
+    pf = _pf()
+    spec, ins = wl.x2_decode_attention(b=b, h=h, t=t, d=d, dtype=dtype)
+    with env(PF_ATTN_CHUNKS=chunks):
+        _, info, _ = check_chain(spec, ins, variant=pf.PF_VARIANT_ATTN_STREAM, what=f"streamed attention t={t} d={d} {dtype} chunks={chunks}")
+    assert info.variant == pf.PF_VARIANT_ATTN_STREAM and info.n_launches == 1
+    rows_per_wg = (256 // (d * (4 if dtype == "f32" else 2) // 16)) * info.vectors_per_lane * chunks
+    assert info.grid[0] == -(-(t + 1) // rows_per_wg)
+
+
+def test_many_heads_take_the_streaming_walk_by_default():
+    # enough heads that one slice per head fills the device: no partial results, no merge
+    pf = _pf()
+    spec, ins = wl.x2_decode_attention(b=32, h=25, t=511, d=64, dtype="f16")
+    _, info, _ = check_chain(spec, ins, what="attention, 800 heads")
+    assert info.variant == pf.PF_VARIANT_ATTN_STREAM and tuple(info.grid)[:2] == (1, 800)
+
+
+def test_streaming_walk_with_cache_outputs_and_peaked_scores():
+    pf = _pf()
+    spec, ins = wl.x2_decode_attention(b=2, h=3, t=333, d=64, dtype="bf16", cache_outputs=True)
+    q, k, v, K, V = ins
+    K = K.clone()
+    K[1, 1, 300] = q[1, 1] * 6.0          # a late row dominates: every earlier running sum is rescaled away
+    outs, info, _ = check_chain(spec, [q, k, v, K, V], variant=pf.PF_VARIANT_ATTN_STREAM, what="streamed attention, cache outputs")
+    assert info.variant == pf.PF_VARIANT_ATTN_STREAM
+    assert torch.equal(outs[1].view(torch.int16), torch.cat([K, k[:, :, None, :]], dim=2).view(torch.int16))
+    assert torch.equal(outs[2].view(torch.int16), torch.cat([V, v[:, :, None, :]], dim=2).view(torch.int16))
+
+
 def test_grown_caches_as_outputs_are_bit_exact():
     spec, ins = wl.x2_decode_attention(b=2, h=3, t=77, d=64, dtype="bf16", cache_outputs=True)
     outs, info, _ = check_chain(spec, ins, what="attention with cache outputs")
