@@ -112,12 +112,38 @@ def broadcast_rows(v: np.ndarray, n: int) -> np.ndarray:
     return np.ascontiguousarray(np.repeat(v, n, axis=-1))
 
 
+def _broadcasts_onto(small, big) -> bool:
+    """`small` broadcasts onto `big`: aligned at the last dimension, every extent equal or 1."""
+    if len(small) > len(big):
+        return False
+    return all(s == g or s == 1 for s, g in zip(small, big[len(big) - len(small):]))
+
+
+def broadcast_to(v: np.ndarray, shape) -> np.ndarray:
+    """The broadcast basic operator (section 6) in full: align the shapes at the last dimension and repeat the
+    operand along every dimension where its extent is 1 (or missing).  Data movement only; the copy is
+    written out in full like every other intermediate here."""
+    v = _f64(v)
+    shape = tuple(shape)
+    if not _broadcasts_onto(v.shape, shape):
+        raise ValueError(f"oracle: cannot broadcast {v.shape} to {shape}")
+    out = v.reshape((1,) * (len(shape) - v.ndim) + v.shape)
+    for axis, extent in enumerate(shape):
+        if out.shape[axis] != extent:
+            out = np.repeat(out, extent, axis=axis)
+    return np.ascontiguousarray(out)
+
+
 def ew_binary(name: str, a: np.ndarray, b: np.ndarray) -> np.ndarray:
     a, b = _f64(a), _f64(b)
     if _is_row_value(b.shape, a.shape):
         b = broadcast_rows(b, a.shape[-1])
     elif _is_row_value(a.shape, b.shape):
         a = broadcast_rows(a, b.shape[-1])
+    elif a.size >= b.size and not _is_trailing(b.shape, a.shape) and _broadcasts_onto(b.shape, a.shape):
+        b = broadcast_to(b, a.shape)      # extents of 1 in the middle: an attention mask [B, 1, 1, S], a per-sample bias
+    elif b.size > a.size and not _is_trailing(a.shape, b.shape) and _broadcasts_onto(a.shape, b.shape):
+        a = broadcast_to(a, b.shape)
     if a.size >= b.size:
         if not _is_trailing(b.shape, a.shape):
             raise ValueError(f"oracle: cannot broadcast {b.shape} over {a.shape}")

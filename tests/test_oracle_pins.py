@@ -607,3 +607,61 @@ def test_depthwise_convolution_against_library_and_invariants():
     xs, ws, bs = [wl.widen(t) for t in ins]
     got = orc.evaluate_outputs(spec, [xs, ws, bs])[0]
     np.testing.assert_allclose(got, orc.dwconv2d_nhwc(np.maximum(xs, 0.0), ws) + bs, rtol=1e-14)
+
+
+# ---- the broadcast basic operator with extents of 1 anywhere (paper section 6)
+
+def test_broadcast_to_against_explicit_loops():
+    rng = np.random.default_rng(77)
+    v = rng.standard_normal((2, 1, 3, 1))
+    out = orc.broadcast_to(v, (2, 4, 3, 5))
+    assert out.shape == (2, 4, 3, 5) and out.flags["C_CONTIGUOUS"]
+    for b in range(2):
+        for h in range(4):
+            for i in range(3):
+                for j in range(5):
+                    assert out[b, h, i, j] == v[b, 0, i, 0]
+    # a lower-rank operand is aligned at the last dimension
+    w = rng.standard_normal((3, 1))
+    out = orc.broadcast_to(w, (2, 4, 3, 5))
+    for b in range(2):
+        for h in range(4):
+            for i in range(3):
+                for j in range(5):
+                    assert out[b, h, i, j] == w[i, 0]
+    with pytest.raises(ValueError):
+        orc.broadcast_to(rng.standard_normal((2, 3)), (2, 4, 3, 5))      # 2 is neither 3 nor 1
+    with pytest.raises(ValueError):
+        orc.broadcast_to(rng.standard_normal((1, 2, 4, 3, 5)), (2, 4, 3, 5))   # more dimensions than the target
+    out = orc.broadcast_to(rng.standard_normal((4, 1, 1)), (2, 4, 3, 5))       # aligned at the right: 4 meets 4
+    assert out.shape == (2, 4, 3, 5) and np.all(out[0] == out[1]) and np.all(out[:, :, :1, :1] == out)
+
+
+def test_binary_operator_with_a_mask_broadcast_over_heads_and_rows():
+    # scores [B, H, S, S] + mask [B, 1, 1, S]: the padding mask of an encoder, added before the softmax
+    rng = np.random.default_rng(78)
+    B, H, S = 2, 3, 4
+    a = rng.standard_normal((B, H, S, S))
+    m = rng.standard_normal((B, 1, 1, S))
+    out = orc.ew_binary("add", a, m)
+    rev = orc.ew_binary("sub", m, a)                 # operand order is kept when the first operand is the small one
+    for b in range(B):
+        for h in range(H):
+            for i in range(S):
+                for j in range(S):
+                    assert out[b, h, i, j] == a[b, h, i, j] + m[b, 0, 0, j]
+                    assert rev[b, h, i, j] == m[b, 0, 0, j] - a[b, h, i, j]
+    # [B, 1, S, 1]: one value per (batch, row), shared by heads and columns
+    r = rng.standard_normal((B, 1, S, 1))
+    out = orc.ew_binary("mul", a, r)
+    for b in range(B):
+        for h in range(H):
+            for i in range(S):
+                for j in range(S):
+                    assert out[b, h, i, j] == a[b, h, i, j] * r[b, 0, i, 0]
+    # the chain walker takes the same path
+    spec = wl.ChainSpec(inputs=[("f32", (B, H, S, S)), ("f32", (B, 1, 1, S))])
+    spec.out(spec.op("softmax", spec.op("add", 0, 1)), "f32")
+    (y,) = orc.evaluate_outputs(spec, [a, m])
+    e = np.exp((a + m) - (a + m).max(-1, keepdims=True))
+    np.testing.assert_allclose(y, e / e.sum(-1, keepdims=True), rtol=0, atol=1e-15)
