@@ -47,8 +47,11 @@ typedef enum { PF_F32 = 0, PF_F16 = 1, PF_BF16 = 2 } pf_dtype;
  * (element-wise, broadcast, reduce, transpose: section 6, "GIR-Graph generation"), plus the usual
  * composites, which the library treats as one reduce-then-broadcast step.
  *
- * Element-wise binary operators take two values; if their shapes differ, the lower-rank one must equal
- * the trailing dimensions of the other and is broadcast over the leading ones.  Operand order is kept
+ * Element-wise binary operators take two values; if their shapes differ, one operand must have the result's
+ * shape and the other is broadcast to it: the two shapes are aligned at the innermost dimension and every
+ * extent of the smaller operand equals the other's or is 1 (a bias [D] or a mask [S, S] over leading dimensions,
+ * an attention mask [B, 1, 1, S] under scores [B, H, S, S], a per-sample bias [N, 1, 1, C], one value per row
+ * [..., 1]).  At most three separate runs of kept dimensions above the innermost one.  Operand order is kept
  * (SUB = src0 - src1, DIV = src0 / src1).  MAX, MIN and RELU return NaN when an operand is NaN.
  * All arithmetic is done in fp32 whatever the storage type; results are rounded to the output type once,
  * on the final store (round to nearest even).

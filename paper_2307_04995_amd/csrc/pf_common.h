@@ -72,15 +72,33 @@ struct Program {
 
 enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
 
+// Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every
+// 32-bit n (multiply-high, one correction add, two shifts).  Built on the host by make_fastdiv().
+struct FastDiv {
+    uint32_t m, s1, s2, d;
+};
+
 // A broadcast operand with `numel` elements laid over a value whose innermost extent is n_inner:
 //   numel >= n_inner (numel = m * n_inner): element (row, col) reads vec[(row % m) * n_inner + col]
 //   numel <  n_inner (n_inner % numel == 0): reads vec[col % numel]; numel == 1 is a scalar.
+// General broadcasting (operand dimensions of extent 1 anywhere, numpy style): the operand's row for row r of
+// the value is sum_k ((r / div_k) mod mod_k) * stride_k over n_terms terms, one per run of kept dimensions.
+#define PF_DEV_MAX_BCAST_TERMS 3
+struct BcastTerm {
+    FastDiv div, mod;  // mod.d is the modulus
+    uint32_t stride;   // in operand rows
+    uint32_t pad[3];
+};
+
 struct VecArg {
     const void* ptr;
     uint32_t numel;
     uint32_t period_rows;  // m above (1 when numel <= n_inner)
     int32_t dtype;         // DType of the storage; may differ from the chain's main dtype only as f32
-    int32_t pad;
+    uint32_t n_terms;      // > 0: general broadcasting, described by terms[0 .. n_terms)
+    uint32_t col_bcast;    // general broadcasting: the operand's innermost extent is 1 (one value per operand row)
+    uint32_t pad;
+    const BcastTerm* terms;  // device memory owned by the plan (kept out of the kernel arguments, which every launch copies)
 };
 
 enum CoreKind : int32_t {
@@ -97,12 +115,6 @@ enum CoreKind : int32_t {
     CORE_GATHER = 11,       // layout-only chain with concatenations / slices
     CORE_ATTN_DECODE = 10,  // concat -> matrix-vector -> softmax -> concat -> vector-matrix (one-token attention)
     CORE_ROWPROG = 9   // no fixed core: the prologue itself holds row reductions (U_RED_*) and their broadcasts
-};
-
-// Division of a 32-bit index by a run-time constant without a divide instruction: q = n / d for every
-// 32-bit n (multiply-high, one correction add, two shifts).  Built on the host by make_fastdiv().
-struct FastDiv {
-    uint32_t m, s1, s2, d;
 };
 
 // Arguments common to all families.

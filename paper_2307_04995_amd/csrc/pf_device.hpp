@@ -389,6 +389,7 @@ struct ProgView {
 
 struct GenericSpec {
     static constexpr bool kStatic = false;
+    static constexpr bool kBcast = true;  // general broadcasting of operands is a run-time property here
     static constexpr int NF = 3, NV = 4, NT = PF_DEV_MAX_TMP;
     using Pro = DynList;
     using Epi = DynList;
@@ -399,9 +400,11 @@ struct GenericSpec {
     static PF_DEVICE int beta(const ChainArgs& a) { return a.core_vec[1]; }
 };
 
-template <int NF_, int NV_, int NT_, int CORE_, int GAMMA_, int BETA_, class ProL, class EpiL>
+// FLAGS_: bit 0 = some operand broadcasts the general way (extents of 1 anywhere)
+template <int NF_, int NV_, int NT_, int CORE_, int GAMMA_, int BETA_, class ProL, class EpiL, int FLAGS_ = 0>
 struct StaticSpec {
     static constexpr bool kStatic = true;
+    static constexpr bool kBcast = (FLAGS_ & 1) != 0;
     static constexpr int NF = NF_, NV = NV_, NT = NT_;
     using Pro = ProL;
     using Epi = EpiL;
@@ -455,7 +458,20 @@ struct LaneState {
 };
 
 // Where a broadcast operand's 16-byte vector for position (row, col) starts, in elements.
+// BC = false: the kernel was built for chains without general broadcasting (the check and its code drop out).
+template <bool BC = true>
 PF_DEVICE uint32_t vec_offset(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner) {
+    if (BC && va.n_terms != 0u) {
+        uint32_t r = 0;
+#pragma unroll
+        for (int k = 0; k < PF_DEV_MAX_BCAST_TERMS; ++k)
+            if ((uint32_t)k < va.n_terms) {
+                const BcastTerm t = va.terms[k];
+                const uint32_t q = fast_div(row, t.div);
+                r += (q - fast_div(q, t.mod) * t.mod.d) * t.stride;
+            }
+        return va.col_bcast ? r : r * n_inner + col;
+    }
     if (va.numel >= n_inner) {
         const uint32_t r = (va.period_rows == 1) ? 0u : row % va.period_rows;
         return r * n_inner + col;
@@ -463,31 +479,33 @@ PF_DEVICE uint32_t vec_offset(const VecArg& va, uint32_t row, uint32_t col, uint
     return col % va.numel;
 }
 
-template <int DT>
+template <int DT, bool BC = true>
 PF_DEVICE u32x4 load_vec_operand(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner) {
     if (va.numel == 1) return Storage<DT>::splat(va.ptr);
-    const uint32_t off = vec_offset(va, row, col, n_inner);
+    const uint32_t off = vec_offset<BC>(va, row, col, n_inner);
+    if (BC && va.n_terms != 0u && va.col_bcast) return Storage<DT>::splat(static_cast<const char*>(va.ptr) + (uint64_t)off * Storage<DT>::ESIZE);
     return load_cached(va.ptr, (uint64_t)off * Storage<DT>::ESIZE);
 }
 
 // The same for a position whose vector may be unaligned or partial: gathered element by element.
-template <int DT>
+template <int DT, bool BC = true>
 PF_DEVICE u32x4 load_vec_operand_elems(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner, uint32_t count) {
     using S = Storage<DT>;
     if (va.numel == 1) return S::splat(va.ptr);
+    if (BC && va.n_terms != 0u && va.col_bcast) return S::splat(static_cast<const char*>(va.ptr) + (uint64_t)vec_offset<BC>(va, row, col, n_inner) * S::ESIZE);
     u32x4 r = {0u, 0u, 0u, 0u};
     if (DT == DT_F32) {
         const uint32_t* p = static_cast<const uint32_t*>(va.ptr);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if ((uint32_t)e < count) r[e] = p[vec_offset(va, row, col + e, n_inner)];
+            if ((uint32_t)e < count) r[e] = p[vec_offset<BC>(va, row, col + e, n_inner)];
     } else {
         const uint16_t* p = static_cast<const uint16_t*>(va.ptr);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             uint32_t lo = 0u, hi = 0u;
-            if ((uint32_t)(2 * j) < count) lo = p[vec_offset(va, row, col + 2 * j, n_inner)];
-            if ((uint32_t)(2 * j + 1) < count) hi = p[vec_offset(va, row, col + 2 * j + 1, n_inner)];
+            if ((uint32_t)(2 * j) < count) lo = p[vec_offset<BC>(va, row, col + 2 * j, n_inner)];
+            if ((uint32_t)(2 * j + 1) < count) hi = p[vec_offset<BC>(va, row, col + 2 * j + 1, n_inner)];
             r[j] = lo | (hi << 16);
         }
     }

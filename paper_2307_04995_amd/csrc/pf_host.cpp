@@ -88,6 +88,15 @@ bool is_row_value_of(const Shape& small, const Shape& big) {
     return std::equal(small.begin(), small.end() - 1, big.begin());
 }
 
+// `small` broadcasts onto `big` the numpy way: aligned at the innermost dimension, every extent equal or 1
+bool broadcasts_onto(const Shape& small, const Shape& big) {
+    if (small.size() > big.size()) return false;
+    const size_t off = big.size() - small.size();
+    for (size_t i = 0; i < small.size(); ++i)
+        if (small[i] != big[off + i] && small[i] != 1) return false;
+    return true;
+}
+
 int dtype_size(int dt) { return dt == PF_F32 ? 4 : 2; }
 
 struct Checked {
@@ -132,6 +141,8 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 else if (is_row_value_of(a, b)) r = b;
                 else if (numel(a) >= numel(b) && is_trailing(b, a)) r = a;
                 else if (numel(b) > numel(a) && is_trailing(a, b)) r = b;
+                else if (broadcasts_onto(b, a)) r = a;  // extents of 1 anywhere (an attention mask [B, 1, 1, S], a per-sample bias)
+                else if (broadcasts_onto(a, b)) r = b;
                 else return fail(PF_ERR_SHAPE, "op %d (%s): operand shapes do not broadcast", k, tr.name);
                 break;
             }
@@ -259,6 +270,8 @@ struct Lowered {
     bool full_is_epi[PF_DEV_MAX_FULL];
     int vec_input[PF_DEV_MAX_VEC];
     bool vec_is_epi[PF_DEV_MAX_VEC];
+    bool general_bcast = false;         // some broadcast input needs the general (term-based) addressing
+    Shape vec_partner[PF_DEV_MAX_VEC];  // shape of the value the operand is broadcast against (where it is first used)
     int core_vec[2] = {-1, -1};
     pf::Program pro, epi;
     uint32_t mask_si = 0;     // load skipping allowed for a causal mask of this extent
@@ -316,6 +329,8 @@ struct Lowerer {
     }
 
     // location of a raw input operand (assigning a slot on first use)
+    Shape cur_result_shape;  // result shape of the operator being lowered (what a broadcast input is broadcast against)
+
     bool input_loc(int v, Loc* out) {
         if (loc[v].kind == LOC_FULL || loc[v].kind == LOC_VEC) {
             // an input used on both sides of a layout change would need two layouts
@@ -328,10 +343,6 @@ struct Lowerer {
             return true;
         }
         const int64_t n = numel(c->shape[v]);
-        if (n != 1 && n != region_numel && c->shape[v].back() == 1 && region_inner != 1) {
-            status = fail(PF_ERR_UNSUPPORTED, "input %d: per-row values are supported as results of reductions, not as inputs", v);
-            return false;
-        }
         if (d->inputs[v].dtype != L->main_dtype) {
             status = fail(PF_ERR_DTYPE, "input %d: dtype differs from the chain's main dtype", v);
             return false;
@@ -352,6 +363,7 @@ struct Lowerer {
             }
             L->vec_input[L->n_vec] = v;
             L->vec_is_epi[L->n_vec] = in_epi;
+            L->vec_partner[L->n_vec] = cur_result_shape;
             loc[v].kind = LOC_VEC;
             loc[v].slot = L->n_vec++;
         }
@@ -449,6 +461,7 @@ struct Lowerer {
     bool lower_elementwise_op(int k) {
         const pf_op_desc& o = d->ops[k];
         const int id = d->n_inputs + k;
+        cur_result_shape = c->shape[id];
         const OpTraits& tr = kOps[o.op];
         if (tr.cls == OC_RESHAPE) return true;  // alias only
         if (tr.cls == OC_REDUCE) {
@@ -782,7 +795,8 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
         // temporaries do not survive the core step
         for (int t = 0; t < PF_DEV_MAX_TMP; ++t)
             if (lw.tmp_busy[t]) return fail(PF_ERR_UNSUPPORTED, "a value computed before the core step is used after it");
-        // affine parameters
+        // affine parameters (and convolution kernels): indexed by the core step itself, not broadcast
+        lw.cur_result_shape.clear();
         const pf_op_desc& o = d->ops[core_k];
         for (int s = 1; s < o.n_src; ++s) {
             const int p = lw.root(o.src[s]);
@@ -1059,6 +1073,7 @@ bool list_equal(const pf::Program& p, const uint32_t* list, int n) {
 }
 
 int match_spec(const std::vector<pf::SpecDesc>& table, const Lowered& L) {
+    if (L.general_bcast) return 0;  // catalogue kernels are built without the general broadcast addressing
     if (L.n_out != 1) return 0;
     for (const pf::SpecDesc& s : table) {
         if (s.nf != L.n_full || s.nv != L.n_vec || s.nt != L.n_tmp || s.core != L.core) continue;
@@ -1094,6 +1109,8 @@ struct pf_plan_s {
     pf::StencilGeom stencil;
     int stencil_ks = 3;       // kernel extent of the depthwise convolution
     int row_log2l = 6;        // row family: log2 of the lanes of a wave that share a row
+    pf::BcastTerm bcast_host[PF_DEV_MAX_VEC][PF_DEV_MAX_BCAST_TERMS];  // general broadcasting terms, staged on the host
+    void* bcast_dev = nullptr;  // ... and their copy in device memory
     bool group_general = false; // group family: groups of any width (general kernels)
     uint32_t dyn_lds = 0;     // group family: dynamic LDS bytes of each launch
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
@@ -1129,6 +1146,7 @@ pf::JitSpec make_jit_spec(const Lowered& L) {
     j.core = L.core;
     j.gamma = L.core_vec[0];
     j.beta = L.core_vec[1];
+    j.flags = L.general_bcast ? 1 : 0;
     for (int i = 0; i < L.pro.n; ++i)
         j.pro.push_back((uint32_t)L.pro.u[i].code | ((uint32_t)L.pro.u[i].kind << 8) | ((uint32_t)L.pro.u[i].slot << 16));
     for (int i = 0; i < L.epi.n; ++i)
@@ -1144,6 +1162,8 @@ bool jit_possible(int device) {
     return hipSetDevice(device) == hipSuccess;
 }
 
+pf::FastDiv make_fastdiv(uint32_t d);
+
 pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype);
@@ -1155,10 +1175,61 @@ pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
         va.ptr = nullptr;
         va.dtype = L.main_dtype;
         va.pad = 0;
+        va.terms = nullptr;
         if (n > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d too large", in);
         va.numel = (uint32_t)n;
         va.period_rows = 1;
+        va.n_terms = 0;
+        va.col_bcast = 0;
         if (n == 1) continue;
+        const Shape& os = c.shape[in];
+        const Shape& ps = L.vec_partner[v];
+        if (!ps.empty() && !is_trailing(os, ps)) {
+            // ---- general broadcasting: extents of 1 anywhere.  One term per run of kept row dimensions.
+            const Shape& region = L.vec_is_epi[v] ? L.post_shape : L.pre_shape;
+            if (!broadcasts_onto(os, ps) || ps.back() != inner || numel(ps) != numel(region))
+                return fail(PF_ERR_UNSUPPORTED, "broadcast input %d: its shape does not broadcast over the kernel's rows", in);
+            const size_t rank = ps.size(), off = rank - os.size();
+            auto op_extent = [&](size_t i) { return i < off ? (int64_t)1 : os[i - off]; };
+            p->low.general_bcast = true;
+            va.col_bcast = (op_extent(rank - 1) == 1 && inner != 1) ? 1u : 0u;
+            if (!va.col_bcast && (inner * es) % 16 != 0) p->ragged = true;
+            int64_t div = 1, stride = 1;  // rows of the value / operand rows inside the dimension being looked at
+            bool in_run = false;
+            for (size_t q = rank - 1; q-- > 0;) {
+                const int64_t e = ps[q], oe = op_extent(q);
+                if (e == 1) continue;
+                if (oe == e) {
+                    if (in_run) {
+                        pf::BcastTerm& t = p->bcast_host[v][va.n_terms - 1];
+                        t.mod = make_fastdiv((uint32_t)(t.mod.d * e));
+                    } else {
+                        if (va.n_terms == PF_DEV_MAX_BCAST_TERMS)
+                            return fail(PF_ERR_UNSUPPORTED, "broadcast input %d: more than %d separate runs of kept dimensions", in, PF_DEV_MAX_BCAST_TERMS);
+                        pf::BcastTerm& t = p->bcast_host[v][va.n_terms++];
+                        memset(&t, 0, sizeof(t));
+                        t.div = make_fastdiv((uint32_t)div);
+                        t.mod = make_fastdiv((uint32_t)e);
+                        t.stride = (uint32_t)stride;
+                        in_run = true;
+                    }
+                    stride *= e;
+                } else {
+                    in_run = false;
+                }
+                div *= e;
+                if (div > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d: too many rows", in);
+            }
+            if (va.n_terms == 0) {
+                // nothing kept among the row dimensions: one operand row for every row of the value
+                pf::BcastTerm& t = p->bcast_host[v][va.n_terms++];
+                memset(&t, 0, sizeof(t));
+                t.div = make_fastdiv(1u);
+                t.mod = make_fastdiv(1u);
+                t.stride = 0;
+            }
+            continue;
+        }
         if ((n * es) % 16 != 0) p->ragged = true;  // gathered element by element (row and element-wise families)
         if (n >= inner) {
             if (n % inner != 0) return fail(PF_ERR_UNSUPPORTED, "broadcast input %d does not tile the kernel's rows", in);
@@ -1166,6 +1237,15 @@ pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
         } else if (inner % n != 0) {
             return fail(PF_ERR_UNSUPPORTED, "broadcast input %d does not tile the kernel's rows", in);
         }
+    }
+    if (L.general_bcast) {
+        if (hipSetDevice(p->device) != hipSuccess || hipMalloc(&p->bcast_dev, sizeof(p->bcast_host)) != hipSuccess)
+            return fail(PF_ERR_NOMEM, "device memory for broadcast terms");
+        if (hipMemcpy(p->bcast_dev, p->bcast_host, sizeof(p->bcast_host), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(PF_ERR_HIP, "upload of broadcast terms failed");
+        for (int v = 0; v < L.n_vec; ++v)
+            if (p->args.vec[v].n_terms)
+                p->args.vec[v].terms = static_cast<const pf::BcastTerm*>(p->bcast_dev) + (size_t)v * PF_DEV_MAX_BCAST_TERMS;
     }
     return PF_OK;
 }
@@ -1608,7 +1688,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     g.pos_per_step = threads / g.cv;
     g.vec_per_channel = 1;
     for (int v = 0; v < L.n_vec; ++v)
-        if (p->args.vec[v].numel > (uint32_t)C) g.vec_per_channel = 0;
+        if (p->args.vec[v].numel > (uint32_t)C || p->args.vec[v].n_terms != 0) g.vec_per_channel = 0;
     // lanes that share a group when partials are merged: as many as fit, a power of two, at most 64
     g.lanes_per_group = 1;
     while (g.lanes_per_group < 64u && g.lanes_per_group * 2u * g.groups <= threads) g.lanes_per_group *= 2u;
@@ -2161,7 +2241,7 @@ pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
     info->grid[0] = plan->grid.x; info->grid[1] = plan->grid.y; info->grid[2] = plan->grid.z;
     info->block[0] = plan->block.x; info->block[1] = plan->block.y; info->block[2] = plan->block.z;
     info->lds_bytes = plan->lds_bytes;
-    info->workspace_bytes = plan->workspace_bytes;
+    info->workspace_bytes = plan->workspace_bytes + (plan->bcast_dev ? sizeof(plan->bcast_host) : 0);
     for (int k = 0; k < plan->desc.n_inputs; ++k) info->compulsory_read_bytes += plan->in_bytes[k];
     for (int o = 0; o < plan->desc.n_outputs; ++o) info->compulsory_write_bytes += plan->out_bytes[o];
     info->n_launches = plan->n_launches;
@@ -2318,6 +2398,7 @@ pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
 void pf_chain_plan_destroy(pf_plan* plan) {
     if (!plan) return;
     if (plan->workspace) (void)hipFree(plan->workspace);
+    if (plan->bcast_dev) (void)hipFree(plan->bcast_dev);
     delete plan;
 }
 

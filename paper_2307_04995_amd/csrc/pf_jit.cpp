@@ -62,7 +62,7 @@ std::string list_text(const std::vector<uint32_t>& l) {
 std::string spec_text(const JitSpec& s) {
     std::ostringstream o;
     o << "pf::StaticSpec<" << s.nf << ", " << s.nv << ", " << s.nt << ", " << s.core << ", " << s.gamma << ", " << s.beta << ", "
-      << list_text(s.pro) << ", " << list_text(s.epi) << ">";
+      << list_text(s.pro) << ", " << list_text(s.epi) << ", " << s.flags << ">";
     return o.str();
 }
 

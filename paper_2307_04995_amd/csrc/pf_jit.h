@@ -16,6 +16,7 @@ constexpr int kSpecJit = 255;
 // (code | kind << 8 | slot << 16 per step).
 struct JitSpec {
     int nf = 0, nv = 0, nt = 0, core = 0, gamma = -1, beta = -1;
+    int flags = 0;  // StaticSpec FLAGS_
     std::vector<uint32_t> pro, epi;
 };
 

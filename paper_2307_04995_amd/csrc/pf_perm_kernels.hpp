@@ -69,7 +69,7 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
                 if (valid[k]) {
                     const uint32_t off = epi ? out_off[k] : in_off[k];
                     const uint32_t row = fast_div(off, epi ? g.div_out_inner : g.div_in_inner);
-                    s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, off - row * inner, inner);
+                    s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner);
                 }
             }
         }

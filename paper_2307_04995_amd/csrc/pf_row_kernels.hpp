@@ -172,8 +172,8 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                 const int k = k0 + c;
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
                 if (RAGGED)
-                    s.vraw[v][k] = load_vec_operand_elems<DT>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
-                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], row, s.col[k], a.n_inner);
+                    s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kBcast>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
+                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, s.col[k], a.n_inner);
             }
         }
     }
@@ -497,6 +497,26 @@ __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32
                     const VecArg& va = a.vec[v];
                     if (va.numel == 1) {
                         s.vraw[v][k] = S::splat(va.ptr);
+                    } else if (Spec::kBcast && va.n_terms != 0u) {
+                        // general broadcasting: (row, column) of every element; a vector may run over row ends
+                        uint32_t bits[VEC], r = s.row[k], cc = s.col[k];
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            while (cc >= a.n_inner) {
+                                cc -= a.n_inner;
+                                ++r;
+                            }
+                            bits[e] = 0u;
+                            if ((uint32_t)e < cnt[k]) {
+                                const uint32_t off = vec_offset<Spec::kBcast>(va, r, cc, a.n_inner);
+                                bits[e] = DT == DT_F32 ? static_cast<const uint32_t*>(va.ptr)[off] : (uint32_t) static_cast<const uint16_t*>(va.ptr)[off];
+                            }
+                            ++cc;
+                        }
+                        if (DT == DT_F32) s.vraw[v][k] = u32x4{bits[0], bits[1], bits[2], bits[3]};
+                        else
+                            s.vraw[v][k] = u32x4{bits[0] | (bits[1 % VEC] << 16), bits[2 % VEC] | (bits[3 % VEC] << 16),
+                                                 bits[4 % VEC] | (bits[5 % VEC] << 16), bits[6 % VEC] | (bits[7 % VEC] << 16)};
                     } else {
                         const uint32_t m0 = (uint32_t)(((uint64_t)gv[k] * VEC) % va.numel);
                         uint32_t bits[VEC];
@@ -514,7 +534,7 @@ __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32
                                                  bits[4 % VEC] | (bits[5 % VEC] << 16), bits[6 % VEC] | (bits[7 % VEC] << 16)};
                     }
                 } else if (cnt[k] != 0u) {
-                    s.vraw[v][k] = load_vec_operand<DT>(a.vec[v], s.row[k], s.col[k], a.n_inner);
+                    s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], s.row[k], s.col[k], a.n_inner);
                 }
             }
         }
