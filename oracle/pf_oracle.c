@@ -459,27 +459,30 @@ int orc_slice_bytes(const void *x, int32_t rank, const int64_t *shape, int32_t a
 /*
  * Depthwise convolution on a channels-last tensor, the memory-intensive convolution of the paper's
  * EfficientNet fragment (section 6, preprocessing of the computation graph), in the usual DNN sense
- * (cross-correlation), stride 1, zero padding that keeps the spatial size ("same"), odd kernel extents:
- *   y[n, i, j, c] = sum_{a < kh, b < kw} w[a, b, c] * x[n, i + a - kh/2, j + b - kw/2, c]
- * with x taken as 0 outside [0, h) x [0, w).   x: [n, h, w, c], w: [kh, kw, c].
+ * (cross-correlation), zero padding of kh/2 rows and kw/2 columns on every side, odd kernel extents, the
+ * same stride s >= 1 along both axes (that network's blocks use 1 and 2):
+ *   y[n, i, j, c] = sum_{a < kh, b < kw} w[a, b, c] * x[n, i*s + a - kh/2, j*s + b - kw/2, c]
+ * with x taken as 0 outside [0, h) x [0, w), for i < (h - 1)/s + 1, j < (w - 1)/s + 1 (stride 1 keeps the
+ * spatial size).   x: [n, h, w, c], w: [kh, kw, c], y: [n, (h - 1)/s + 1, (w - 1)/s + 1, c].
  */
 int orc_dwconv2d_nhwc(const double *x, int64_t n, int64_t h, int64_t w, int64_t c, const double *wgt, int64_t kh,
-                      int64_t kw, double *out)
+                      int64_t kw, int64_t stride, double *out)
 {
-    if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return ORC_BAD_ARG;
+    if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0 || stride < 1) return ORC_BAD_ARG;
+    const int64_t oh = (h - 1) / stride + 1, ow = (w - 1) / stride + 1;
 #pragma omp parallel for schedule(static) collapse(2)
     for (int64_t b = 0; b < n; ++b)
-        for (int64_t i = 0; i < h; ++i)
-            for (int64_t j = 0; j < w; ++j)
+        for (int64_t i = 0; i < oh; ++i)
+            for (int64_t j = 0; j < ow; ++j)
                 for (int64_t ch = 0; ch < c; ++ch) {
                     double acc = 0.0;
                     for (int64_t a = 0; a < kh; ++a)
                         for (int64_t q = 0; q < kw; ++q) {
-                            const int64_t ii = i + a - kh / 2, jj = j + q - kw / 2;
+                            const int64_t ii = i * stride + a - kh / 2, jj = j * stride + q - kw / 2;
                             if (ii < 0 || ii >= h || jj < 0 || jj >= w) continue;
                             acc += wgt[(a * kw + q) * c + ch] * x[((b * h + ii) * w + jj) * c + ch];
                         }
-                    out[((b * h + i) * w + j) * c + ch] = acc;
+                    out[((b * oh + i) * ow + j) * c + ch] = acc;
                 }
     return ORC_OK;
 }

@@ -57,7 +57,7 @@ def _load():
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         lib.orc_slice_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(i64), ctypes.c_int32, i64, i64,
                                         ctypes.c_int32, ctypes.c_void_p]
-        lib.orc_dwconv2d_nhwc.argtypes = [dp, i64, i64, i64, i64, dp, i64, i64, dp]
+        lib.orc_dwconv2d_nhwc.argtypes = [dp, i64, i64, i64, i64, dp, i64, i64, i64, dp]
         lib.orc_concat_rows.argtypes = [dp, i64, i64, i64, dp, dp]
         lib.orc_matvec.argtypes = [dp, i64, i64, i64, dp, dp]
         lib.orc_vecmat.argtypes = [dp, i64, i64, i64, dp, dp]
@@ -189,15 +189,16 @@ def reduce_last(name: str, x: np.ndarray) -> np.ndarray:
     return out
 
 
-def dwconv2d_nhwc(x: np.ndarray, wgt: np.ndarray) -> np.ndarray:
-    """Depthwise convolution (cross-correlation, stride 1, zero "same" padding) of channels-last x [n, h, w, c]
-    with per-channel kernels wgt [kh, kw, c] (section 6, the EfficientNet fragment)."""
+def dwconv2d_nhwc(x: np.ndarray, wgt: np.ndarray, stride: int = 1) -> np.ndarray:
+    """Depthwise convolution (cross-correlation, zero padding of half the kernel extent on every side, the same
+    stride along both axes) of channels-last x [n, h, w, c] with per-channel kernels wgt [kh, kw, c]
+    (section 6, the EfficientNet fragment).  Stride 1 keeps the spatial size."""
     x, wgt = _f64(x), _f64(wgt)
-    if x.ndim != 4 or wgt.ndim != 3 or wgt.shape[2] != x.shape[3]:
-        raise ValueError(f"oracle: dwconv2d shapes {x.shape} and {wgt.shape}")
+    if x.ndim != 4 or wgt.ndim != 3 or wgt.shape[2] != x.shape[3] or stride < 1:
+        raise ValueError(f"oracle: dwconv2d shapes {x.shape} and {wgt.shape}, stride {stride}")
     n, h, w, c = x.shape
-    out = np.empty_like(x)
-    _check(_load().orc_dwconv2d_nhwc(_p(x), n, h, w, c, _p(wgt), wgt.shape[0], wgt.shape[1], _p(out)), "dwconv2d")
+    out = np.empty((n, (h - 1) // stride + 1, (w - 1) // stride + 1, c), dtype=np.float64)
+    _check(_load().orc_dwconv2d_nhwc(_p(x), n, h, w, c, _p(wgt), wgt.shape[0], wgt.shape[1], int(stride), _p(out)), "dwconv2d")
     return out
 
 
@@ -358,7 +359,7 @@ def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
     if name == "softmax":
         return softmax(a[0])
     if name == "dwconv2d":
-        return dwconv2d_nhwc(a[0], a[1])
+        return dwconv2d_nhwc(a[0], a[1], stride=int(op.i[0]) if len(op.i) else 1)
     if name == "concat_rows":
         return concat_rows(a[0], a[1])
     if name == "matvec":

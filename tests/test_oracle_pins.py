@@ -609,6 +609,38 @@ def test_depthwise_convolution_against_library_and_invariants():
     np.testing.assert_allclose(got, orc.dwconv2d_nhwc(np.maximum(xs, 0.0), ws) + bs, rtol=1e-14)
 
 
+def test_strided_depthwise_convolution():
+    # worked by hand: 4 x 5 image 1..20, one channel, stride 2, the kernel that reads the pixel to the left
+    x = np.arange(1.0, 21.0).reshape(1, 4, 5, 1)
+    k = np.zeros((3, 3, 1))
+    k[1, 0, 0] = 1.0
+    y = orc.dwconv2d_nhwc(x, k, stride=2)
+    assert y.shape == (1, 2, 3, 1)                       # (4 - 1) // 2 + 1, (5 - 1) // 2 + 1
+    # outputs sit at input positions (0, 0), (0, 2), (0, 4), (2, 0), (2, 2), (2, 4); each reads column j - 1
+    np.testing.assert_array_equal(y[0, :, :, 0], [[0, 2, 4], [0, 12, 14]])
+    # all-ones 3 x 3 kernel: sums of the 3 x 3 neighbourhoods of those positions (zero outside the image)
+    y = orc.dwconv2d_nhwc(x, np.ones((3, 3, 1)), stride=2)[0, :, :, 0]
+    assert y[0, 0] == 1 + 2 + 6 + 7 and y[1, 1] == 7 + 8 + 9 + 12 + 13 + 14 + 17 + 18 + 19 and y[1, 2] == 9 + 10 + 14 + 15 + 19 + 20
+    rng = np.random.default_rng(33)
+    for (kh, kw), stride, (h, w) in (((3, 3), 2, (7, 6)), ((5, 5), 2, (8, 9)), ((3, 3), 3, (7, 7)), ((5, 5), 1, (6, 5))):
+        x = rng.standard_normal((2, h, w, 4))
+        k = rng.standard_normal((kh, kw, 4))
+        y = orc.dwconv2d_nhwc(x, k, stride=stride)
+        # a strided result is the dense one sampled at every stride-th position (same padding, same taps)
+        np.testing.assert_array_equal(y, orc.dwconv2d_nhwc(x, k)[:, ::stride, ::stride, :])
+        # and the library's grouped convolution agrees
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(k).permute(2, 0, 1)[:, None],
+                                         stride=stride, padding=(kh // 2, kw // 2), groups=4).permute(0, 2, 3, 1).numpy()
+        np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-12)
+    # through the chain walker: the attribute i[0] is the stride
+    x = rng.standard_normal((2, 8, 9, 4))
+    k = rng.standard_normal((5, 5, 4))
+    spec = wl.ChainSpec(inputs=[("f32", (2, 8, 9, 4)), ("f32", (5, 5, 4))])
+    spec.out(spec.op("dwconv2d", spec.op("relu", 0), 1, i=[2]), "f32")
+    (got,) = orc.evaluate_outputs(spec, [x, k])
+    np.testing.assert_array_equal(got, orc.dwconv2d_nhwc(np.maximum(x, 0.0), k, stride=2))
+
+
 # ---- the broadcast basic operator with extents of 1 anywhere (paper section 6)
 
 def test_broadcast_to_against_explicit_loops():
