@@ -93,9 +93,10 @@ typedef enum {
     PF_CONCAT = 29,     /* src0, src1 joined along axis i[0] (all other extents equal)                          */
     PF_SLICE = 30,      /* elements [i[1], i[1] + i[2]) of src0 along axis i[0]                                  */
     /* depthwise convolution (section 6, the EfficientNet fragment): src0 x [n, h, w, c] channels-last, src1
-       kernels [kh, kw, c] (a chain input); cross-correlation, stride 1, zero padding that keeps h and w.
-       Implemented for kh = kw = 3 and kh = kw = 5.  Element-wise operators may precede it (they run before the padding) and
-       follow it.                                                                                             */
+       kernels [kh, kw, c] (a chain input); cross-correlation, zero padding of kh/2 rows and kw/2 columns on every
+       side; n_i = 0: stride 1 (h and w are kept); n_i = 1: stride i[0] (1 .. 8) along both axes, the result is
+       [n, (h - 1) / stride + 1, (w - 1) / stride + 1, c].  Implemented for kh = kw = 3 and kh = kw = 5.  Element-wise
+       operators may precede it (they run before the padding) and follow it (on the result's shape).           */
     PF_DWCONV2D = 31,
     PF_OP_COUNT_ = 32
 } pf_op;
@@ -170,6 +171,7 @@ typedef struct {
 #define PF_VARIANT_ATTN_STREAM 1      /* attention family: longer slices walked in chunks, next chunk's loads in flight */
 #define PF_VARIANT_STENCIL_DIRECT 0   /* stencil family: a register window per lane, neighbours through the cache */
 #define PF_VARIANT_STENCIL_STAGED 1   /* stencil family: the workgroup's tile is activated once and shared in LDS  */
+#define PF_VARIANT_STENCIL_STRIDED 2  /* stencil family: strides above 1, taps loaded where they are used             */
 #define PF_VARIANT_ROW_WAVE 0         /* row family: one 64-lane wave owns a row                             */
 #define PF_VARIANT_ROW_BLOCK 1        /* row family: one workgroup owns a row                                */
 #define PF_VARIANT_ROW_STREAM 2       /* row family: a workgroup walks a long row twice in chunks            */

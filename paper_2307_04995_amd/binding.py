@@ -32,7 +32,7 @@ OP_CODE = {name: i for i, name in enumerate([
 PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE, PF_FAMILY_ATTENTION, PF_FAMILY_GATHER, PF_FAMILY_STENCIL = range(7)
 PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK, PF_VARIANT_ROW_STREAM = 0, 1, 2
 PF_SPEC_GENERIC, PF_SPEC_JIT = 0, 255
-PF_VARIANT_STENCIL_DIRECT, PF_VARIANT_STENCIL_STAGED = 0, 1
+PF_VARIANT_STENCIL_DIRECT, PF_VARIANT_STENCIL_STAGED, PF_VARIANT_STENCIL_STRIDED = 0, 1, 2
 PF_VARIANT_ATTN_ONE_PASS, PF_VARIANT_ATTN_STREAM = 0, 1
 PF_VARIANT_GROUP_TWO_PASS, PF_VARIANT_GROUP_RESIDENT = 0, 1
 PF_VARIANT_T_ROWS, PF_VARIANT_T_LDS_ROWS, PF_VARIANT_T_TILE = 0, 1, 2

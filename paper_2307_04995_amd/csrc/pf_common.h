@@ -196,6 +196,8 @@ struct StencilGeom {
     uint32_t tiles_x, tiles_y, tiles;      // staged variant: tiles per image row, strips per image, tiles in all
     uint32_t tiles_per_die;                // ceil(tiles / 8)
     FastDiv div_cv;
+    uint32_t stride, oh, ow, out_row_vecs; // strided variant: stride along both axes, output extents, ow * cv
+    uint32_t strip_rows;                   // strided variant: output rows per workgroup
 };
 
 // Gather family: layout-only chains as a copy of contiguous runs.  Run k of the table moves run_elems elements

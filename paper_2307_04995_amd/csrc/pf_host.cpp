@@ -205,7 +205,13 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 const Shape& b = sh[o.src[1]];
                 if (a.size() != 4 || b.size() != 3 || b[2] != a[3]) return fail(PF_ERR_SHAPE, "op %d (dwconv2d): needs x [n, h, w, c] and kernels [kh, kw, c]", k);
                 if (b[0] % 2 == 0 || b[1] % 2 == 0) return fail(PF_ERR_SHAPE, "op %d (dwconv2d): kernel extents must be odd", k);
+                if (o.n_i > 1 || (o.n_i == 1 && (o.i[0] < 1 || o.i[0] > 8)))
+                    return fail(PF_ERR_INVALID_ARG, "op %d (dwconv2d): i[0] is the stride (1 .. 8), at most one integer attribute", k);
                 r = a;
+                if (o.n_i == 1) {
+                    r[1] = (a[1] - 1) / o.i[0] + 1;
+                    r[2] = (a[2] - 1) / o.i[0] + 1;
+                }
                 break;
             }
             case OC_CONCAT: {
@@ -1647,9 +1653,6 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     const bool general = cpg % vec != 0 || (vpg & (vpg - 1)) != 0 || vpg > 64 || env_int("PF_GROUP_GENERAL", 0) != 0;
     if (general && G > 512) return fail(PF_ERR_UNSUPPORTED, "more than 512 groups");
     if (samples * hw > 0xffffffffLL || samples > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
-    for (int v = 0; v < L.n_vec; ++v)
-        if (p->args.vec[v].numel > (uint32_t)C && p->args.vec[v].numel != 1)
-            ;  // per-position broadcast operands are fine in the two-pass variant
     for (int i = 0; i < L.pro.n; ++i)
         if (L.pro.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the group family");
     for (int i = 0; i < L.epi.n; ++i)
@@ -1830,6 +1833,38 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     p->stencil_ks = ksz;
     p->args.n_inner = (uint32_t)ch;
     p->args.rows = (uint64_t)(n * h * w);
+    const pf_op_desc& conv = p->desc.ops[L.core_op];
+    const int64_t stride = conv.n_i == 1 ? conv.i[0] : 1;
+    if (stride > 1) {
+        // down-sampling convolution: one lane per output column and channel vector, taps loaded where they are used
+        if (forced_variant >= 0 && forced_variant != PF_VARIANT_STENCIL_STRIDED)
+            return fail(PF_ERR_UNSUPPORTED, "a strided convolution runs on the strided variant only");
+        const int64_t oh = (h - 1) / stride + 1, ow = (w - 1) / stride + 1;
+        g.stride = (uint32_t)stride;
+        g.oh = (uint32_t)oh;
+        g.ow = (uint32_t)ow;
+        g.out_row_vecs = (uint32_t)(ow * g.cv);
+        // output rows per workgroup: 4 (the kernel vectors are loaded once per workgroup), fewer while that leaves
+        // a compute unit with less than about eight workgroups
+        hipDeviceProp_t prop;
+        const int n_cu = (hipGetDeviceProperties(&prop, p->device) == hipSuccess && prop.multiProcessorCount > 0) ? prop.multiProcessorCount : 256;
+        const int64_t tiles_x = (g.out_row_vecs + 255) / 256;
+        int64_t strip = 4;
+        while (strip > 1 && tiles_x * ((oh + strip - 1) / strip) * n < 8 * (int64_t)n_cu) strip /= 2;
+        g.strip_rows = (uint32_t)strip;
+        if ((oh + strip - 1) / strip > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
+        p->variant = PF_VARIANT_STENCIL_STRIDED;
+        p->lds_bytes = 0;
+        p->grid = dim3((uint32_t)tiles_x, (uint32_t)((oh + strip - 1) / strip), (uint32_t)n);
+        if (jit_possible(p->device)) {
+            std::string err;
+            p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, p->variant, ksz, make_jit_spec(L), &err);
+            if (p->jit_fn) p->spec_id = pf::kSpecJit;
+            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        }
+        return PF_OK;
+    }
+    if (forced_variant == PF_VARIANT_STENCIL_STRIDED) return fail(PF_ERR_UNSUPPORTED, "the strided variant is for strides above 1");
     // Staged variant (values activated once, shared through an LDS tile) when the tile fits; its entries are
     // packed in the storage type if the prologue keeps storage precision and the kernel is specialised.
     const bool jit_ok = jit_possible(p->device);

@@ -6,7 +6,9 @@ namespace pf {
 
 template <int DT>
 static hipError_t launch_stencil_dt(const ChainArgs& a, const StencilGeom& g, int variant, int ks, uint32_t lds, dim3 grid, hipStream_t st) {
-    if (variant == 1 && ks == 5) hipLaunchKernelGGL((dwconv_staged_kernel<DT, GenericSpec, 5>), grid, dim3(256), lds, st, a, g);
+    if (variant == 2 && ks == 5) hipLaunchKernelGGL((dwconv_strided_kernel<DT, GenericSpec, 5>), grid, dim3(256), 0, st, a, g);
+    else if (variant == 2) hipLaunchKernelGGL((dwconv_strided_kernel<DT, GenericSpec, 3>), grid, dim3(256), 0, st, a, g);
+    else if (variant == 1 && ks == 5) hipLaunchKernelGGL((dwconv_staged_kernel<DT, GenericSpec, 5>), grid, dim3(256), lds, st, a, g);
     else if (variant == 1) hipLaunchKernelGGL((dwconv_staged_kernel<DT, GenericSpec, 3>), grid, dim3(256), lds, st, a, g);
     else if (ks == 3) hipLaunchKernelGGL((dwconv3x3_kernel<DT, GenericSpec>), grid, dim3(256), 0, st, a, g);
     else return hipErrorInvalidValue;

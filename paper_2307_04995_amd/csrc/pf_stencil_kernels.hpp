@@ -333,4 +333,100 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
     }
 }
 
+// Strided variant (stride >= 2 along both axes, as in the down-sampling blocks of the network the paper's fragment
+// comes from): a lane owns 8 channels of one OUTPUT column and walks down a strip of output rows.  Consecutive
+// outputs share at most one input row and one input column, so there is no window worth keeping: the KS x KS
+// taps of an output are loaded where they are used, one kernel row's loads in flight together, and what
+// neighbouring lanes and rows read twice comes from the first-level cache.  The prologue runs on every tap.
+
+template <int DT, class Spec, int KS>
+__global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, const StencilGeom g) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr int R = KS / 2;
+    static_assert(KS == 3 || KS == 5, "kernel extents 3 and 5");
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;  // (output column, channel vector), channel fastest
+    if (t >= g.out_row_vecs) return;
+    const uint32_t ocol = fast_div(t, g.div_cv);
+    const uint32_t cvi = t - ocol * g.cv;
+    const uint32_t sample = blockIdx.z;
+    const uint32_t i0 = blockIdx.y * g.strip_rows;  // strip_rows output rows per workgroup (the planner keeps the grid large)
+    const int wslot = Spec::gamma(a);
+    const uint32_t pro_full = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_FULL) : ~g.epi_full_mask;
+    const uint32_t pro_vec = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_VEC) : ~g.epi_vec_mask;
+    const uint32_t epi_full = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_FULL) : g.epi_full_mask;
+    const uint32_t epi_vec = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_VEC) : g.epi_vec_mask;
+    auto load_w = [&](int k) { return load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE); };
+    // 3 x 3: the nine kernel vectors stay in registers; 5 x 5: read where they are used (first-level cache)
+    constexpr bool kKeepW = KS == 3;
+    u32x4 wraw[kKeepW ? KS * KS : 1];
+    if (kKeepW) {
+#pragma unroll
+        for (int k = 0; k < KS * KS; ++k) wraw[k % (kKeepW ? KS * KS : 1)] = load_w(k);
+    }
+
+    LaneState<DT, 1, Spec> s;
+    s.col[0] = cvi * VEC;
+#pragma unroll 1
+    for (uint32_t r = 0; r < g.strip_rows; ++r) {
+        const uint32_t orow = i0 + r;
+        if (orow >= g.oh) break;
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int dh = 0; dh < KS; ++dh) {
+            const int ii = (int)(orow * g.stride) + dh - R;
+            u32x4 pend_f[KS][at_least_1(Spec::NF)], pend_v[KS][at_least_1(Spec::NV)];
+            bool ok[KS];
+            uint32_t pos[KS];
+#pragma unroll
+            for (int dw = 0; dw < KS; ++dw) {
+                const int jj = (int)(ocol * g.stride) + dw - R;
+                ok[dw] = ii >= 0 && ii < (int)g.h && jj >= 0 && jj < (int)g.w;
+                pos[dw] = ok[dw] ? (sample * g.h + (uint32_t)ii) * g.w + (uint32_t)jj : 0u;
+                if (!ok[dw]) continue;
+#pragma unroll
+                for (int f = 0; f < Spec::NF; ++f)
+                    if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
+                        pend_f[dw][f] = load_cached(a.full[f], ((uint64_t)pos[dw] * g.c + cvi * VEC) * S::ESIZE);
+#pragma unroll
+                for (int v = 0; v < Spec::NV; ++v)
+                    if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
+                        pend_v[dw][v] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos[dw], s.col[0], g.c);
+            }
+#pragma unroll
+            for (int dw = 0; dw < KS; ++dw) {
+                if (!ok[dw]) continue;  // zero padding: the tap contributes nothing (the prologue is not applied to it)
+                s.row[0] = pos[dw];
+#pragma unroll
+                for (int f = 0; f < Spec::NF; ++f)
+                    if (f < Spec::n_full(a) && ((pro_full >> f) & 1u)) s.fraw[f][0] = pend_f[dw][f];
+#pragma unroll
+                for (int v = 0; v < Spec::NV; ++v)
+                    if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u)) s.vraw[v][0] = pend_v[dw][v];
+                run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
+                float wf[VEC];
+                S::unpack(kKeepW ? wraw[(dh * KS + dw) % (kKeepW ? KS * KS : 1)] : load_w(dh * KS + dw), wf);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[e], s.acc[e], acc[e]);
+            }
+        }
+        const uint32_t opos = (sample * g.oh + orow) * g.ow + ocol;
+        s.row[0] = opos;
+#pragma unroll
+        for (int f = 0; f < Spec::NF; ++f)
+            if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
+                s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)opos * g.c + cvi * VEC) * S::ESIZE);
+#pragma unroll
+        for (int v = 0; v < Spec::NV; ++v)
+            if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
+                s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], opos, s.col[0], g.c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
+        run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
+        store_stream(a.out[0], ((uint64_t)opos * g.c + cvi * VEC) * S::ESIZE, S::pack(s.acc));
+    }
+}
+
 }  // namespace pf

@@ -99,6 +99,47 @@ def test_five_by_five_kernels(n, h, w, c, dtype):
     check_chain(s, [x, k], what="5x5 dwconv alone")
 
 
+@pytest.mark.parametrize("n,h,w,c,k,stride,dtype", [(2, 14, 14, 96, 3, 2, "f16"), (1, 9, 7, 40, 5, 2, "f16"), (3, 16, 15, 32, 3, 2, "bf16"),
+                                                    (1, 13, 13, 16, 3, 3, "f32"), (2, 28, 28, 144, 5, 2, "f16"), (1, 1, 1, 8, 3, 2, "f32")])
+def test_strided_depthwise_convolution(n, h, w, c, k, stride, dtype):
+    # the down-sampling blocks: stride 2 (3 once), even and odd image extents, both kernel sizes
+    pf = _pf()
+    spec, ins = wl.x4_relu_dwconv(n=n, h=h, w=w, c=c, k=k, dtype=dtype, stride=stride, salt=5)
+    outs, info, _ = check_chain(spec, ins, what=f"strided dwconv {k}x{k}/{stride} {dtype}")
+    assert info.family == pf.PF_FAMILY_STENCIL and info.variant == pf.PF_VARIANT_STENCIL_STRIDED and info.n_launches == 1
+    assert tuple(outs[0].shape) == (n, (h - 1) // stride + 1, (w - 1) // stride + 1, c)
+
+
+def test_strided_convolution_with_operands_on_both_sides():
+    # silu(dwconv_stride2(relu(x + t[n,1,1,c])) + bias[c]) + res[n, h/2, w/2, c]: epilogue operands have the
+    # result's shape, the prologue's the input's (and one of them broadcasts the general way)
+    dtype = "f16"
+    n, h, w, c = 2, 12, 10, 48
+    oh, ow = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    x = wl.random_tensor((n, h, w, c), dtype, 1341)
+    t = wl.random_tensor((n, 1, 1, c), dtype, 1342, scale=0.5)
+    k = wl.random_tensor((3, 3, c), dtype, 1343, scale=0.3)
+    bias = wl.random_tensor((c,), dtype, 1344, scale=0.5)
+    res = wl.random_tensor((n, oh, ow, c), dtype, 1345, scale=0.5)
+    s = wl.ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (n, 1, 1, c)), (dtype, (3, 3, c)), (dtype, (c,)), (dtype, (n, oh, ow, c))])
+    v = s.op("relu", s.op("add", 0, 1))
+    v = s.op("dwconv2d", v, 2, i=[2])
+    v = s.op("silu", s.op("add", v, 3))
+    s.out(s.op("add", v, 4), dtype)
+    check_chain(s, [x, t, k, bias, res], what="strided dwconv, operands on both sides")
+
+
+def test_stride_attribute_is_checked():
+    pf = _pf()
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 8)), ("f16", (3, 3, 8))])
+    s.out(s.op("dwconv2d", 0, 1, i=[0]), "f16")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_INVALID_ARG
+    s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 8)), ("f16", (3, 3, 8))])
+    s.out(s.op("dwconv2d", 0, 1, i=[2]), "f16")
+    st, t = pf.pf_chain_infer_shape(pf.make_desc(s), 2)
+    assert st == pf.PF_OK and [t.shape[q] for q in range(t.rank)] == [1, 4, 4, 8]
+
+
 def test_other_kernel_sizes_are_refused():
     pf = _pf()
     s = wl.ChainSpec(inputs=[("f16", (1, 8, 8, 16)), ("f16", (7, 7, 16))])

@@ -213,16 +213,18 @@ def x2_decode_attention(b: int = 8, h: int = 25, t: int = 1023, d: int = 64, dty
     return c, [quantise(x, dtype) for x in (q, k, v, kc, vc)]
 
 
-def x4_relu_dwconv(n: int = 32, h: int = 56, w: int = 56, c: int = 240, k: int = 3, dtype: str = "f16", salt: int = 0):
-    """RELU -> depthwise k x k convolution -> + bias on channels-last x [n, h, w, c] (not a BASELINE config; the
-    EfficientNet fragment of the paper's section 6).  Weights [k, k, c] ~ N(0, 1/k), bias [c] ~ N(0, 1)."""
+def x4_relu_dwconv(n: int = 32, h: int = 56, w: int = 56, c: int = 240, k: int = 3, dtype: str = "f16", salt: int = 0,
+                   stride: int = 1):
+    """RELU -> depthwise k x k convolution (stride 1 or more) -> + bias on channels-last x [n, h, w, c] (not a
+    BASELINE config; the EfficientNet fragment of the paper's section 6).  Weights [k, k, c] ~ N(0, 1/k),
+    bias [c] ~ N(0, 1)."""
     g = _rng(9, salt)
     x = g.standard_normal((n, h, w, c), dtype=np.float32)
     wgt = (g.standard_normal((k, k, c), dtype=np.float32) / np.float32(k))
     bias = g.standard_normal(c, dtype=np.float32)
     s = ChainSpec(inputs=[(dtype, (n, h, w, c)), (dtype, (k, k, c)), (dtype, (c,))])
     v = s.op("relu", 0)
-    v = s.op("dwconv2d", v, 1)
+    v = s.op("dwconv2d", v, 1, i=[stride] if stride != 1 else [])
     v = s.op("add", v, 2)
     s.out(v, dtype)
     return s, [quantise(x, dtype), quantise(wgt, dtype), quantise(bias, dtype)]
