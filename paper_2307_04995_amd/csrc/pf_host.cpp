@@ -337,7 +337,9 @@ struct Lowerer {
     // location of a raw input operand (assigning a slot on first use)
     Shape cur_result_shape;  // result shape of the operator being lowered (what a broadcast input is broadcast against)
 
-    bool input_loc(int v, Loc* out) {
+    // force_vec: classify the input as a broadcast operand even if it has as many elements as the value (a
+    // normalisation parameter of a single-row tensor)
+    bool input_loc(int v, Loc* out, bool force_vec = false) {
         if (loc[v].kind == LOC_FULL || loc[v].kind == LOC_VEC) {
             // an input used on both sides of a layout change would need two layouts
             const bool was_epi = loc[v].kind == LOC_FULL ? L->full_is_epi[loc[v].slot] : L->vec_is_epi[loc[v].slot];
@@ -353,7 +355,7 @@ struct Lowerer {
             status = fail(PF_ERR_DTYPE, "input %d: dtype differs from the chain's main dtype", v);
             return false;
         }
-        if (n == region_numel) {
+        if (n == region_numel && !force_vec) {
             if (L->n_full >= PF_DEV_MAX_FULL) {
                 status = fail(PF_ERR_UNSUPPORTED, "more than %d full-shape inputs", PF_DEV_MAX_FULL);
                 return false;
@@ -808,8 +810,8 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
             const int p = lw.root(o.src[s]);
             if (p >= n_in) return fail(PF_ERR_UNSUPPORTED, "normalisation parameters must be chain inputs");
             Lowerer::Loc l;
-            if (!lw.input_loc(p, &l)) return lw.status;
-            if (l.kind != Lowerer::LOC_VEC) return fail(PF_ERR_UNSUPPORTED, "normalisation parameter has the full shape");
+            if (!lw.input_loc(p, &l, true)) return lw.status;
+            if (l.kind != Lowerer::LOC_VEC) return fail(PF_ERR_UNSUPPORTED, "a normalisation parameter is also used as a full-shape operand");
             L->core_vec[s - 1] = l.slot;
             lw.consume(p);
         }

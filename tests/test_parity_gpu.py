@@ -143,6 +143,20 @@ def test_groupnorm_general_path_matches_the_aligned_one(variant):
     assert diff.max() <= 4e-3
 
 
+@pytest.mark.parametrize("dtype,n", [("f16", 1024), ("f32", 200), ("bf16", 64)])
+def test_normalisation_of_a_single_row(dtype, n):
+    # one token: gamma and beta have as many elements as the value itself, and are parameters all the same
+    x = wl.random_tensor((1, n), dtype, 1501)
+    gamma = wl.random_tensor((n,), dtype, 1502, dist="positive")
+    beta = wl.random_tensor((n,), dtype, 1503, scale=0.3)
+    s = wl.ChainSpec(inputs=[(dtype, (1, n)), (dtype, (n,)), (dtype, (n,))])
+    s.out(s.op("gelu_erf", s.op("layernorm", 0, 1, 2, f=[1e-5])), dtype)
+    check_chain(s, [x, gamma, beta], what=f"LayerNorm of one row {dtype}")
+    s = wl.ChainSpec(inputs=[(dtype, (1, 1, n)), (dtype, (n,))])
+    s.out(s.op("rmsnorm", 0, 1, f=[1e-6]), dtype)
+    check_chain(s, [x.reshape(1, 1, n), gamma], what=f"RMSNorm of one row {dtype}")
+
+
 # ------------------------------------------------------------------ layout-only chains, bit-exact
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])

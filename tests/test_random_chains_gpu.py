@@ -1,0 +1,26 @@
+"""Differential test on seeded random chains: random shapes, dtypes, operand kinds (full shape, trailing
+broadcast, extents of 1, one value per row, scalar), element-wise steps on both sides of a random core.  Every
+chain goes through the C ABI (as planned by default, and again on the run-time-interpreted kernels when the
+default was a specialised one) and is compared element by element with the fp64 oracle."""
+import pytest
+
+import workloads as wl
+from pf_testlib import check_chain
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("block", range(16))
+def test_random_chains_match_the_oracle(block):
+    from paper_2307_04995_amd import binding as pf
+    ran = 0
+    for seed in range(block * 12, block * 12 + 12):
+        spec, ins, desc = wl.random_chain(seed)
+        try:
+            check_chain(spec, ins, what=desc)
+            ran += 1
+        except pf.PfError as e:
+            # a chain shape the library does not take must be refused as unsupported, never mis-run
+            assert e.status in (pf.PF_ERR_UNSUPPORTED, pf.PF_ERR_ALIGNMENT), f"{desc}: {e}"
+            print(f"refused ({pf.pf_status_str(e.status)}): {desc}: {e}")
+    assert ran >= 8, "most random chains are expected to be supported"

@@ -283,3 +283,111 @@ def random_tensor(shape, dtype: str, seed: int, dist: str = "normal", scale: flo
     else:
         raise ValueError(dist)
     return quantise(x, dtype)
+
+
+# ---------------------------------------------------------------------------------------------
+# Seeded random chains for the differential tests: structure only (which operators, which operands,
+# which shapes); values stay O(1) so that the absolute fp32 bar is meaningful.
+# ---------------------------------------------------------------------------------------------
+
+def random_chain(seed: int):
+    """A random chain of the canonical form `element-wise* -> [core] -> element-wise*` with random shapes,
+    operand kinds (full shape, trailing broadcast, broadcast with extents of 1, scalar) and dtypes.
+    Returns (ChainSpec, inputs, description)."""
+    g = np.random.default_rng(BASE_SEED * 13 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    inner = int(g.choice([8, 24, 64, 96, 197, 200, 512, 1000, 2048]))
+    rank = int(g.integers(2, 5))
+    lead = [int(g.integers(1, 6)) for _ in range(rank - 1)]
+    shape = tuple(lead + [inner])
+    core = str(g.choice(["none", "softmax", "layernorm", "rmsnorm", "reduce_sum", "reduce_max", "reduce_mean", "permute",
+                         "row_program"]))
+    if core == "permute" and (rank < 3 or (inner * (4 if dtype == "f32" else 2)) % 16 != 0):
+        core = "none"
+    inputs, tensors = [(dtype, shape)], [random_tensor(shape, dtype, 100 * seed, scale=0.7)]
+
+    def new_input(shp, dist="normal", scale=0.7):
+        inputs.append((dtype, tuple(shp)))
+        tensors.append(random_tensor(tuple(shp), dtype, 100 * seed + len(inputs), dist=dist, scale=scale))
+        return len(inputs) - 1
+
+    ops = []          # (name, src placeholders, f, i); value ids are fixed up once the input count is known
+    def emit(name, *src, f=(), i=()):
+        ops.append((name, src, tuple(f), tuple(i)))
+        return ("op", len(ops) - 1)
+
+    def operand_for(cur_shape):
+        kind = str(g.choice(["full", "trailing", "ones", "scalar", "row"]))
+        if kind == "full":
+            return ("in", new_input(cur_shape))
+        if kind == "trailing":
+            k = int(g.integers(1, len(cur_shape)))
+            return ("in", new_input(cur_shape[-k:]))
+        if kind == "ones":
+            shp = [e if g.random() < 0.5 else 1 for e in cur_shape]
+            if all(e == 1 for e in shp) or shp == list(cur_shape):
+                shp = [1] * (len(cur_shape) - 1) + [cur_shape[-1]]
+            return ("in", new_input(shp))
+        if kind == "row":
+            return ("in", new_input(list(cur_shape[:-1]) + [1]))
+        return ("in", new_input((1,)))
+
+    def elementwise_steps(v, cur_shape, n):
+        for _ in range(n):
+            name = str(g.choice(["add", "sub", "mul", "max", "min", "scale", "addc", "neg", "relu", "sigmoid", "silu",
+                                 "gelu_erf", "tanh"]))
+            if name in ("add", "sub", "mul", "max", "min"):
+                o = operand_for(cur_shape)
+                v = emit(name, v, o) if g.random() < 0.7 else emit(name, o, v)
+                if name == "mul":
+                    v = emit("tanh", v)          # keeps magnitudes bounded
+            elif name == "scale":
+                v = emit("scale", v, f=[float(g.choice([0.5, -0.75, 1.25]))])
+            elif name == "addc":
+                v = emit("addc", v, f=[float(g.choice([0.25, -0.5, 1.0]))])
+            else:
+                v = emit(name, v)
+        return v
+
+    v = elementwise_steps(("in", 0), shape, int(g.integers(0, 4)))
+    out_shape = shape
+    if core == "softmax":
+        v = emit("softmax", v)
+    elif core == "layernorm":
+        v = emit("layernorm", v, ("in", new_input((inner,), "positive")), ("in", new_input((inner,))), f=[1e-5])
+    elif core == "rmsnorm":
+        v = emit("rmsnorm", v, ("in", new_input((inner,), "positive")), f=[1e-6])
+    elif core.startswith("reduce_"):
+        if core == "reduce_sum":
+            v = emit("scale", v, f=[2.0 / inner])     # keeps the sum O(1)
+        elif v == ("in", 0):
+            v = emit("scale", v, f=[1.0])
+        v = emit(core, v)
+        out_shape = tuple(list(shape[:-1]) + [1])
+    elif core == "permute":
+        perm = list(range(rank - 1))
+        g.shuffle(perm)
+        perm = [int(p) for p in perm] + [rank - 1]
+        v = emit("permute", v, i=perm)
+        out_shape = tuple(shape[p] for p in perm)
+    elif core == "row_program":
+        # (x - mean x) / (max x - mean x + 1): two reductions, row values combined with each other
+        if v == ("in", 0):
+            v = emit("tanh", v)
+        mean = emit("reduce_mean", v)
+        top = emit("reduce_max", v)
+        span = emit("addc", emit("sub", top, mean), f=[1.0])
+        v = emit("div", emit("sub", v, mean), span)
+    if not core.startswith("reduce_"):
+        v = elementwise_steps(v, out_shape, int(g.integers(0, 3)))
+    if v == ("in", 0):
+        v = emit("relu", v)
+
+    spec = ChainSpec(inputs=inputs)
+    n_in = len(inputs)
+    def vid(ref):
+        return ref[1] if ref[0] == "in" else n_in + ref[1]
+    for name, src, f, i in ops:
+        spec.ops.append(OpSpec(name, tuple(vid(r) for r in src), f, i))
+    spec.out(vid(v), dtype)
+    return spec, tensors, f"seed {seed}: {dtype} {shape} core={core} ops={[o[0] for o in ops]}"
