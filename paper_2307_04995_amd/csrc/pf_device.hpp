@@ -287,28 +287,32 @@ PF_DEVICE Stat stat_shfl_xor(Stat s, int mask) {
     return r;
 }
 
-// running sums of deviations from a pivot
+// A lane's running statistics.  Each vector is reduced on its own (mean of its elements, then squared deviations
+// from that mean: everything is in registers, so the two passes cost nothing extra) and merged into the running
+// triple with the parallel-variance update.  No step subtracts large nearly-equal sums, so a spread that is
+// tiny against the values' offset (a channel that is almost constant) keeps its relative accuracy.
 struct LaneAcc {
-    float n = 0.0f, s = 0.0f, ss = 0.0f, pivot = 0.0f;
+    float n = 0.0f, mean = 0.0f, m2 = 0.0f;
     template <int VEC>
     PF_DEVICE void add_vector(const float* x) {
-        if (n == 0.0f) pivot = x[0];
+        float sv = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sv += x[e];
+        const float mv = sv * (1.0f / (float)VEC);
+        float m2v = 0.0f;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            const float d = x[e] - pivot;
-            s += d;
-            ss += d * d;
+            const float d = x[e] - mv;
+            m2v = __builtin_fmaf(d, d, m2v);
         }
-        n += (float)VEC;
+        const float nn = n + (float)VEC;
+        const float inv = __builtin_amdgcn_rcpf(nn);
+        const float delta = mv - mean;
+        mean = __builtin_fmaf(delta, (float)VEC * inv, mean);
+        m2 += m2v + delta * delta * (n * (float)VEC * inv);
+        n = nn;
     }
-    PF_DEVICE Stat finish() const {
-        Stat r;
-        r.n = n;
-        const float inv = n > 0.0f ? 1.0f / n : 0.0f;
-        r.mean = pivot + s * inv;
-        r.m2 = fmaxf(ss - s * s * inv, 0.0f);
-        return r;
-    }
+    PF_DEVICE Stat finish() const { return Stat{n, mean, m2}; }
 };
 
 // ---------------------------------------------------------------------------------------------

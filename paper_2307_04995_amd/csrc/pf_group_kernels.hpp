@@ -12,8 +12,9 @@
 //             statistics, takes part in a per-sample device-scope exchange and normalises straight from
 //             registers.  x is read once: compulsory traffic only.
 //
-// Statistics are (count, mean, M2) triples merged with the parallel-variance update, each lane summing
-// deviations from its first element, so a large common offset does not cancel catastrophically in fp32.
+// Statistics are (count, mean, M2) triples merged with the parallel-variance update.  A lane reduces each of
+// its vectors on its own (mean, then squared deviations from it) before merging, so neither a large common
+// offset nor a spread that is tiny against the values cancels in fp32.
 #pragma once
 #include "pf_row_kernels.hpp"
 
@@ -28,8 +29,17 @@ namespace pf {
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// plain sums for the packed statistics below
+struct LeanAcc {
+    float n = 0.0f, s = 0.0f, ss = 0.0f;
+    PF_DEVICE Stat finish() const {
+        const float inv = n > 0.0f ? 1.0f / n : 0.0f;
+        return Stat{n, s * inv, fmaxf(ss - s * s * inv, 0.0f)};
+    }
+};
+
 template <int DT>
-PF_DEVICE void lean_add_vector(LaneAcc& la, u32x4 raw) {
+PF_DEVICE void lean_add_vector(LeanAcc& la, u32x4 raw) {
     if (DT == DT_F16) {
         const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
@@ -194,9 +204,10 @@ PF_DEVICE bool gather_sample(const GroupGeom& g, uint32_t sample, float eps, uin
 // ---- groups of any width (GEN instantiations) ---------------------------------------------------------
 // When the channels of a group are not a power-of-two number of whole 16-byte vectors (10 channels per group
 // in a 320-channel layer, 4 in a 128-channel one), a lane's vector can straddle groups and the lanes of a
-// group are no aligned power-of-two run.  Every lane then keeps its sums per element, cuts them into `parts`
-// (one per group its vector touches), and parks one (count, mean, M2) triple per part in LDS; the triples of
-// a group are merged by lanes_per_group threads that walk the lanes whose vectors touch that group.
+// group are no aligned power-of-two run.  Every lane then keeps a running (mean, M2) per element slot over its
+// positions, merges the slots of each part (one part per group its vector touches; they are adjacent) and parks
+// one (count, mean, M2) triple per part in LDS; the triples of a group are merged by lanes_per_group threads
+// that walk the lanes whose vectors touch that group.
 // Returns true in the thread that ends up with group *grp_out's merged triple.
 template <int VEC>
 PF_DEVICE bool merge_parts_of_block(const GroupGeom& g, const float* lds_gen, uint32_t* grp_out, Stat* out) {
@@ -239,8 +250,8 @@ PF_DEVICE bool merge_parts_of_block(const GroupGeom& g, const float* lds_gen, ui
 // (agent-scope atomic) accesses, so no cache write-back or invalidate is needed around them -- a write-back
 // here would wait for every output line other workgroups have just stored.
 //
-// GEN > 0: groups of any width (see merge_parts_of_block); GEN bounds the groups one vector can touch
-// (geometry `parts` <= GEN); needs 512 * parts * 12 bytes of dynamic LDS.
+// GEN != 0: groups of any width (see merge_parts_of_block); needs 512 * parts * 12 bytes of dynamic LDS, `parts`
+// being the most groups one vector touches.
 template <int DT, int NV, class Spec, int PHASE, int GEN = 0>
 __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles) {
     using S = Storage<DT>;
@@ -320,59 +331,48 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         };
 
         if (PHASE != 2 && GEN) {
-            // ---- partial statistics: sums of deviations from the lane's first value, kept per part (per element
-            // when a vector can touch more than two groups), then one (count, mean, M2) triple per part into LDS
-            constexpr int NACC = GEN == 0 ? 1 : GEN <= 2 ? GEN : VEC;
-            float pivot = 0.0f, npos = 0.0f, sa[NACC], ssa[NACC];
+            // ---- partial statistics: a running (mean, M2) per element slot over the lane's positions (one shared
+            // count), then the slots of each part merged into one (count, mean, M2) triple per part in LDS
+            float npos = 0.0f, mean_e[VEC], m2_e[VEC];
 #pragma unroll
-            for (int q = 0; q < NACC; ++q) sa[q] = ssa[q] = 0.0f;
+            for (int e = 0; e < VEC; ++e) mean_e[e] = m2_e[e] = 0.0f;
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 prologue(i);
                 if (valid_of(i)) {
-                    if (npos == 0.0f) pivot = s.acc[0];
+                    npos += 1.0f;
+                    const float inv = __builtin_amdgcn_rcpf(npos);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
-                        const float d = s.acc[e] - pivot;
-                        if (GEN == 1) {
-                            sa[0] += d;
-                            ssa[0] += d * d;
-                        } else if (GEN == 2) {
-                            const bool hi = part_of(e) != 0u;
-                            const float d0 = hi ? 0.0f : d, d1 = hi ? d : 0.0f;
-                            sa[0] += d0;
-                            ssa[0] += d0 * d0;
-                            sa[NACC - 1] += d1;
-                            ssa[NACC - 1] += d1 * d1;
-                        } else {
-                            sa[e % NACC] += d;
-                            ssa[e % NACC] += d * d;
-                        }
+                        const float d = s.acc[e] - mean_e[e];
+                        mean_e[e] = __builtin_fmaf(d, inv, mean_e[e]);
+                        m2_e[e] = __builtin_fmaf(d, s.acc[e] - mean_e[e], m2_e[e]);
                     }
-                    npos += 1.0f;
                 }
             }
-            for (uint32_t part = 0; part < g.parts; ++part) {
-                float sum = 0.0f, sq = 0.0f, cnt = 0.0f;
+            // slots of one part are adjacent: walk them once, flushing a part when the next one begins
+            const float n_slot = active ? npos : 0.0f;
+            Stat cur = {n_slot, mean_e[0], m2_e[0]};
 #pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    if (part_of(e) == part) {
-                        cnt += 1.0f;
-                        if (GEN > 2) {
-                            sum += sa[e % NACC];
-                            sq += ssa[e % NACC];
-                        }
-                    }
-                if (GEN <= 2) {
-                    sum = part == 0u ? sa[0] : sa[NACC - 1];
-                    sq = part == 0u ? ssa[0] : ssa[NACC - 1];
+            for (int e = 1; e <= VEC; ++e) {
+                const bool flush = e == VEC || part_of(e % VEC) != part_of(e - 1);
+                if (flush) {
+                    float* q = lds_gen + (t * g.parts + part_of(e - 1)) * 3u;
+                    q[0] = cur.n;
+                    q[1] = cur.mean;
+                    q[2] = cur.m2;
                 }
-                const float n = active ? npos * cnt : 0.0f;
-                const float inv = n > 0.0f ? 1.0f / n : 0.0f;
+                if (e < VEC) {
+                    const Stat slot = {n_slot, mean_e[e % VEC], m2_e[e % VEC]};
+                    cur = flush ? slot : stat_merge(cur, slot);
+                }
+            }
+            // parts this lane's vector does not reach stay empty
+            for (uint32_t part = part_of(VEC - 1) + 1u; part < g.parts; ++part) {
                 float* q = lds_gen + (t * g.parts + part) * 3u;
-                q[0] = n;
-                q[1] = pivot + sum * inv;
-                q[2] = fmaxf(sq - sum * sum * inv, 0.0f);
+                q[0] = 0.0f;
+                q[1] = 0.0f;
+                q[2] = 0.0f;
             }
             __syncthreads();
             uint32_t grp;
@@ -395,16 +395,17 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         if (PHASE != 2 && !GEN) {
             // ---- partial statistics from registers
             LaneAcc la;
+            LeanAcc lean;
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 if (kLean) {
-                    if (valid_of(i)) lean_add_vector<DT>(la, raw[i]);
+                    if (valid_of(i)) lean_add_vector<DT>(lean, raw[i]);
                 } else {
                     prologue(i);
                     if (valid_of(i)) la.template add_vector<VEC>(s.acc);
                 }
             }
-            const Stat st = group_lanes_merge(la.finish(), g.log2_vpg);
+            const Stat st = group_lanes_merge(kLean ? lean.finish() : la.finish(), g.log2_vpg);
             if (PHASE == 0) {
                 publish_tile(g, st, pstep, cvi, active, lds_part, sample, bx);
             } else {

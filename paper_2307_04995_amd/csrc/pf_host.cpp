@@ -1676,8 +1676,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     for (int64_t v = 0; v < cv; ++v) g.parts = std::max<uint32_t>(g.parts, (uint32_t)((v * vec + vec - 1) / cpg - (v * vec) / cpg + 1));
     const uint32_t gen_lds = general ? 512u * g.parts * 3u * (uint32_t)sizeof(float) : 0u;
     p->group_general = general;
-    // specialised kernels know the bound exactly (1, 2, or up to 8 = a vector's elements)
-    const int gen_parts = !general ? 0 : g.parts <= 2 ? (int)g.parts : 8;
+    const int gen_parts = general ? 1 : 0;
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);

@@ -24,3 +24,18 @@ def test_random_chains_match_the_oracle(block):
             assert e.status in (pf.PF_ERR_UNSUPPORTED, pf.PF_ERR_ALIGNMENT), f"{desc}: {e}"
             print(f"refused ({pf.pf_status_str(e.status)}): {desc}: {e}")
     assert ran >= 8, "most random chains are expected to be supported"
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_groupnorm_chains_match_the_oracle(block):
+    # groups of any width, small and large tiles, one or several workgroups per sample; both variants
+    from paper_2307_04995_amd import binding as pf
+    for seed in range(block * 10, block * 10 + 10):
+        spec, ins, desc = wl.random_groupnorm_chain(seed)
+        _, info, _ = check_chain(spec, ins, what=desc)
+        assert info.family == pf.PF_FAMILY_GROUP
+        other = pf.PF_VARIANT_GROUP_TWO_PASS if info.variant == pf.PF_VARIANT_GROUP_RESIDENT else pf.PF_VARIANT_GROUP_RESIDENT
+        try:
+            check_chain(spec, ins, variant=other, what=desc + f" (variant {other})")
+        except pf.PfError as e:
+            assert e.status == pf.PF_ERR_UNSUPPORTED, f"{desc}: {e}"     # e.g. the fused variant with a per-sample operand

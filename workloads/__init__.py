@@ -391,3 +391,47 @@ def random_chain(seed: int):
         spec.ops.append(OpSpec(name, tuple(vid(r) for r in src), f, i))
     spec.out(vid(v), dtype)
     return spec, tensors, f"seed {seed}: {dtype} {shape} core={core} ops={[o[0] for o in ops]}"
+
+
+def random_groupnorm_chain(seed: int):
+    """A random channels-last GroupNorm chain: random sample count, spatial extents, channel and group counts
+    (groups of any width), optional element-wise steps before and after.  Returns (ChainSpec, inputs, description)."""
+    g = np.random.default_rng(BASE_SEED * 17 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    vec = 4 if dtype == "f32" else 8
+    c = vec * int(g.integers(1, 41))
+    divisors = [d for d in range(1, c + 1) if c % d == 0 and d <= 512]
+    groups = int(g.choice(divisors))
+    n = int(g.integers(1, 5))
+    spatial = [int(g.integers(1, 30)) for _ in range(int(g.integers(1, 3)))]
+    shape = tuple([n] + spatial + [c])
+    x = random_tensor(shape, dtype, 300 * seed, scale=0.8)
+    off = random_tensor((c,), "f32", 300 * seed + 1, dist="uniform", scale=2.0)
+    x = quantise(widen(x).astype(np.float32) + widen(off).astype(np.float32), dtype)   # per-channel offsets
+    gamma = random_tensor((c,), dtype, 300 * seed + 2, dist="positive")
+    beta = random_tensor((c,), dtype, 300 * seed + 3, scale=0.5)
+    ins, tensors = [(dtype, shape), (dtype, (c,)), (dtype, (c,))], [x, gamma, beta]
+    s = ChainSpec(inputs=ins)
+    v = 0
+    pre = str(g.choice(["none", "relu", "bias", "sample_bias"]))
+    if pre == "relu":
+        v = s.op("relu", v)
+    elif pre in ("bias", "sample_bias"):
+        shp = (c,) if pre == "bias" else tuple([n] + [1] * len(spatial) + [c])
+        s.inputs.append((dtype, shp))
+        tensors.append(random_tensor(shp, dtype, 300 * seed + 4, scale=0.5))
+        v = s.op("add", v, len(s.inputs) - 1)
+    # operator ids depend on the final input count: rebuild with it known
+    n_in = len(s.inputs)
+    s.ops = []
+    v = 0
+    if pre == "relu":
+        v = s.op("relu", v)
+    elif pre in ("bias", "sample_bias"):
+        v = s.op("add", v, n_in - 1)
+    v = s.op("groupnorm", v, 1, 2, f=[1e-5], i=[groups])
+    post = str(g.choice(["none", "silu", "relu"]))
+    if post != "none":
+        v = s.op(post, v)
+    s.out(v, dtype)
+    return s, tensors, f"seed {seed}: {dtype} {shape} groups={groups} pre={pre} post={post}"
