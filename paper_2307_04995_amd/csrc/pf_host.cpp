@@ -851,6 +851,10 @@ pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
                 if (i > mask_at && (u.kind == pf::K_FULL || u.kind == pf::K_TMP)) ok = false;
                 if (i > mask_at && u.code == pf::U_MOV) ok = false;
             }
+            // the kernels skip every full-shape operand beyond the diagonal alike: none may belong to the epilogue,
+            // which runs on the masked columns too (softmax gives 0 there, later steps need not)
+            for (int f = 0; f < L->n_full; ++f)
+                if (L->full_is_epi[f]) ok = false;
             if (ok) L->mask_si = (uint32_t)L->pro.u[mask_at].ival;
         }
         // a mask that is the last prologue step moves into the softmax core ...

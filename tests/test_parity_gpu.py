@@ -67,6 +67,18 @@ def test_causal_softmax_with_other_prologue_steps():
     check_chain(spec, [x], what="mask then scale")
 
 
+def test_full_shape_operand_after_a_causal_softmax():
+    # softmax(causal(x)) * keep: the epilogue reads `keep` on the masked columns too (0 * keep, but min / add of
+    # it are not 0), so columns beyond the diagonal cannot be skipped for that operand
+    shape = (2, 3, 16, 64)
+    x = wl.random_tensor(shape, "f32", 1601, scale=2.0)
+    keep = wl.random_tensor(shape, "f32", 1602)
+    for name in ("min", "add", "mul"):
+        s = wl.ChainSpec(inputs=[("f32", shape), ("f32", shape)])
+        s.out(s.op(name, s.op("softmax", s.op("causal_mask", s.op("scale", 0, f=[0.5]))), 1), "f32")
+        check_chain(s, [x, keep], what=f"causal softmax then {name} with a full-shape operand")
+
+
 def test_c2_rectangular_scores():
     # more keys than queries: the mask still compares column against row of the last two dims
     spec, ins = wl.c2_causal_softmax(b=1, h=2, s=40, s_k=72, dtype="f16")

@@ -39,3 +39,35 @@ def test_random_groupnorm_chains_match_the_oracle(block):
             check_chain(spec, ins, variant=other, what=desc + f" (variant {other})")
         except pf.PfError as e:
             assert e.status == pf.PF_ERR_UNSUPPORTED, f"{desc}: {e}"     # e.g. the fused variant with a per-sample operand
+
+
+def _run_random(builder, seeds, allowed=()):
+    from paper_2307_04995_amd import binding as pf
+    ran = 0
+    for seed in seeds:
+        spec, ins, desc = builder(seed)
+        try:
+            check_chain(spec, ins, what=desc)
+            ran += 1
+        except pf.PfError as e:
+            assert e.status in allowed, f"{desc}: {e}"
+            print(f"refused ({pf.pf_status_str(e.status)}): {desc}: {e}")
+    return ran
+
+
+@pytest.mark.parametrize("block", range(5))
+def test_random_depthwise_convolution_chains_match_the_oracle(block):
+    assert _run_random(wl.random_stencil_chain, range(block * 12, block * 12 + 12)) == 12
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_attention_chains_match_the_oracle(block):
+    assert _run_random(wl.random_attention_chain, range(block * 10, block * 10 + 10)) == 10
+
+
+@pytest.mark.parametrize("block", range(5))
+def test_random_permutation_chains_match_the_oracle(block):
+    from paper_2307_04995_amd import binding as pf
+    # (a permutation that leaves the layout as it is has nothing to do and is refused)
+    ran = _run_random(wl.random_permute_chain, range(block * 12, block * 12 + 12), allowed=(pf.PF_ERR_UNSUPPORTED,))
+    assert ran >= 9

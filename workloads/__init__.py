@@ -351,7 +351,12 @@ def random_chain(seed: int):
 
     v = elementwise_steps(("in", 0), shape, int(g.integers(0, 4)))
     out_shape = shape
+    second = None     # a second output: the value that enters the core (the residual stream of a normalisation)
+    if core in ("softmax", "layernorm", "rmsnorm") and v != ("in", 0) and g.random() < 0.3:
+        second = v
     if core == "softmax":
+        if g.random() < 0.4:
+            v = emit("causal_mask", v)
         v = emit("softmax", v)
     elif core == "layernorm":
         v = emit("layernorm", v, ("in", new_input((inner,), "positive")), ("in", new_input((inner,))), f=[1e-5])
@@ -390,7 +395,9 @@ def random_chain(seed: int):
     for name, src, f, i in ops:
         spec.ops.append(OpSpec(name, tuple(vid(r) for r in src), f, i))
     spec.out(vid(v), dtype)
-    return spec, tensors, f"seed {seed}: {dtype} {shape} core={core} ops={[o[0] for o in ops]}"
+    if second is not None:
+        spec.out(vid(second), dtype)
+    return spec, tensors, f"seed {seed}: {dtype} {shape} core={core} ops={[o[0] for o in ops]} outputs={len(spec.outputs)}"
 
 
 def random_groupnorm_chain(seed: int):
@@ -435,3 +442,82 @@ def random_groupnorm_chain(seed: int):
         v = s.op(post, v)
     s.out(v, dtype)
     return s, tensors, f"seed {seed}: {dtype} {shape} groups={groups} pre={pre} post={post}"
+
+
+def random_stencil_chain(seed: int):
+    """A random depthwise-convolution chain: random image and channel extents, 3 x 3 or 5 x 5 kernels, stride
+    1 to 3, a random element-wise step in front (it decides whether the staged tile is packed) and behind."""
+    g = np.random.default_rng(BASE_SEED * 19 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    vec = 4 if dtype == "f32" else 8
+    c = vec * int(g.integers(1, 25))
+    n, h, w = int(g.integers(1, 4)), int(g.integers(1, 24)), int(g.integers(1, 24))
+    k = int(g.choice([3, 5]))
+    stride = int(g.choice([1, 1, 2, 3]))
+    oh, ow = (h - 1) // stride + 1, (w - 1) // stride + 1
+    pre = str(g.choice(["none", "relu", "sigmoid", "bias", "neg"]))
+    post = str(g.choice(["none", "bias", "silu", "residual"]))
+    ins = [(dtype, (n, h, w, c)), (dtype, (k, k, c))]
+    tensors = [random_tensor((n, h, w, c), dtype, 500 * seed, scale=0.8), random_tensor((k, k, c), dtype, 500 * seed + 1, scale=1.0 / k)]
+    extra = []
+    if pre == "bias":
+        extra.append(("pre", (c,)))
+    if post == "bias":
+        extra.append(("post", (c,)))
+    if post == "residual":
+        extra.append(("post", (n, oh, ow, c)))
+    for j, (_, shp) in enumerate(extra):
+        ins.append((dtype, shp))
+        tensors.append(random_tensor(shp, dtype, 500 * seed + 2 + j, scale=0.5))
+    s = ChainSpec(inputs=ins)
+    v, nxt = 0, 2
+    if pre == "bias":
+        v = s.op("add", v, nxt)
+        nxt += 1
+    elif pre != "none":
+        v = s.op(pre, v)
+    v = s.op("dwconv2d", v, 1, i=[stride] if stride != 1 else [])
+    if post in ("bias", "residual"):
+        v = s.op("add", v, nxt)
+    elif post == "silu":
+        v = s.op("silu", v)
+    s.out(v, dtype)
+    return s, tensors, f"seed {seed}: {dtype} [{n},{h},{w},{c}] {k}x{k}/{stride} pre={pre} post={post}"
+
+
+def random_attention_chain(seed: int):
+    """One-token attention with random batch, head count, cache length, head dimension and storage type."""
+    g = np.random.default_rng(BASE_SEED * 23 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    d = int(g.choice([32, 64, 128, 256] if dtype != "f32" else [16, 32, 64, 128]))
+    b, h = int(g.integers(1, 4)), int(g.integers(1, 7))
+    t = int(g.choice([1, 2, 31, 64, 100, 255, 256, 257, 700, 1500, 3000]))
+    spec, ins = x2_decode_attention(b=b, h=h, t=t, d=d, dtype=dtype, cache_outputs=bool(g.random() < 0.3), salt=seed)
+    return spec, ins, f"seed {seed}: {dtype} b={b} h={h} t={t} d={d} outputs={len(spec.outputs)}"
+
+
+def random_permute_chain(seed: int):
+    """(x [+ bias] [* scale]) -> random permutation of 2 to 5 dimensions whose extents are multiples of a vector
+    wherever the kernels need whole vectors (the innermost dimensions of both layouts)."""
+    g = np.random.default_rng(BASE_SEED * 29 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    vec = 4 if dtype == "f32" else 8
+    rank = int(g.integers(2, 6))
+    perm = [int(p) for p in g.permutation(rank)]
+    shape = [int(g.integers(1, 9)) for _ in range(rank)]
+    shape[rank - 1] = vec * int(g.integers(1, 13))           # innermost of the input
+    shape[perm[rank - 1]] = vec * int(g.integers(1, 13))     # innermost of the output
+    shape = tuple(shape)
+    ins, tensors = [(dtype, shape)], [random_tensor(shape, dtype, 700 * seed, dist="uniform")]
+    s = ChainSpec(inputs=ins)
+    v = 0
+    step = str(g.choice(["none", "bias", "scale", "bias_scale"]))
+    if step in ("bias", "bias_scale"):
+        s.inputs.append((dtype, (shape[-1],)))
+        tensors.append(random_tensor((shape[-1],), dtype, 700 * seed + 1, dist="uniform"))
+        v = s.op("add", v, 1)
+    if step in ("scale", "bias_scale"):
+        v = s.op("scale", v, f=[0.125])
+    v = s.op("permute", v, i=perm)
+    s.out(v, dtype)
+    return s, tensors, f"seed {seed}: {dtype} {shape} perm={perm} step={step}"
