@@ -144,7 +144,7 @@ def ew_binary(name: str, a: np.ndarray, b: np.ndarray) -> np.ndarray:
         b = broadcast_to(b, a.shape)      # extents of 1 in the middle: an attention mask [B, 1, 1, S], a per-sample bias
     elif b.size > a.size and not _is_trailing(a.shape, b.shape) and _broadcasts_onto(a.shape, b.shape):
         a = broadcast_to(a, b.shape)
-    if a.size >= b.size:
+    if a.size > b.size or (a.size == b.size and a.ndim >= b.ndim):
         if not _is_trailing(b.shape, a.shape):
             raise ValueError(f"oracle: cannot broadcast {b.shape} over {a.shape}")
         shape = a.shape

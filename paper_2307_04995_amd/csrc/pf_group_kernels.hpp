@@ -317,6 +317,18 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         auto prologue = [&](int i) {
             s.row[0] = sample * g.hw + p_begin + rel_of(i);
             s.fraw[0][0] = raw[i];
+            if (PHASE != 0) {
+                // further full-shape operands (a residual added in front of or behind the normalisation) are not kept
+                // in registers: each is read where the programs run (the fused variant is planned for one only)
+#pragma unroll
+                for (int f = 1; f < Spec::NF; ++f) {
+                    if (f < Spec::n_full(a)) {
+                        s.fraw[f][0] = u32x4{0u, 0u, 0u, 0u};
+                        if (valid_of(i))
+                            s.fraw[f][0] = load_stream(a.full[f], (((uint64_t)sample * g.hw + p_begin + rel_of(i)) * g.channels + cvi * VEC) * S::ESIZE);
+                    }
+                }
+            }
             if (!vec_per_channel) {
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v) {

@@ -139,6 +139,7 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
                 if (a == b) r = a;
                 else if (is_row_value_of(b, a)) r = a;  // a keep-dim reduction result broadcast back over its row
                 else if (is_row_value_of(a, b)) r = b;
+                else if (numel(a) == numel(b) && b.size() > a.size() && is_trailing(a, b)) r = b;  // [n] with [1, n]: the higher rank
                 else if (numel(a) >= numel(b) && is_trailing(b, a)) r = a;
                 else if (numel(b) > numel(a) && is_trailing(a, b)) r = b;
                 else if (broadcasts_onto(b, a)) r = a;  // extents of 1 anywhere (an attention mask [B, 1, 1, S], a per-sample bias)

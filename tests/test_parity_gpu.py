@@ -142,6 +142,29 @@ def test_groupnorm_groups_of_any_width(n, h, w, c, g, dtype, variant):
     assert info.n_launches == (2 if variant == 0 else 1)
 
 
+@pytest.mark.parametrize("c,g", [(64, 8), (320, 32)])
+def test_groupnorm_with_residuals_on_both_sides(c, g):
+    # GroupNorm(x + res) + skip: two full-shape operands in front, one behind (two-launch variant: the fused one
+    # keeps a single operand in registers)
+    pf = _pf()
+    shape = (2, 9, 7, c)
+    x, res, skip = (wl.random_tensor(shape, "f16", 1701 + k) for k in range(3))
+    gamma = wl.random_tensor((c,), "f16", 1704, dist="positive")
+    beta = wl.random_tensor((c,), "f16", 1705, scale=0.3)
+    s = wl.ChainSpec(inputs=[("f16", shape), ("f16", shape), ("f16", (c,)), ("f16", (c,)), ("f16", shape)])
+    v = s.op("groupnorm", s.op("add", 0, 1), 2, 3, f=[1e-5], i=[g])
+    s.out(s.op("add", s.op("silu", v), 4), "f16")
+    _, info, _ = check_chain(s, [x, res, gamma, beta, skip], what=f"GroupNorm with residuals, {c} channels")
+    assert info.family == pf.PF_FAMILY_GROUP and info.variant == pf.PF_VARIANT_GROUP_TWO_PASS
+    # a single position per sample: the per-sample operand has the full shape
+    shape = (4, 1, 232)
+    x, t = wl.random_tensor(shape, "f16", 1711), wl.random_tensor(shape, "f16", 1712)
+    gamma, beta = wl.random_tensor((232,), "f16", 1713, dist="positive"), wl.random_tensor((232,), "f16", 1714)
+    s = wl.ChainSpec(inputs=[("f16", shape), ("f16", (232,)), ("f16", (232,)), ("f16", shape)])
+    s.out(s.op("groupnorm", s.op("add", 0, 3), 1, 2, f=[1e-5], i=[29]), "f16")
+    check_chain(s, [x, gamma, beta, t], what="GroupNorm of single positions with a second full-shape operand")
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_groupnorm_general_path_matches_the_aligned_one(variant):
     # the same chain through both statistics paths (the general one forced on a shape that does not need it)
