@@ -71,3 +71,35 @@ def test_random_permutation_chains_match_the_oracle(block):
     # (a permutation that leaves the layout as it is has nothing to do and is refused)
     ran = _run_random(wl.random_permute_chain, range(block * 12, block * 12 + 12), allowed=(pf.PF_ERR_UNSUPPORTED,))
     assert ran >= 9
+
+
+@pytest.mark.parametrize("block", range(5))
+def test_random_layout_chains_are_bit_exact(block):
+    # joins, slices, permutations and reshapes at random: every output bit pattern must come from the right place
+    import numpy as np
+    import torch
+    from oracle import pf_oracle as orc
+    from paper_2307_04995_amd import binding as pf
+    from pf_testlib import gpu_run
+    ran = 0
+    for seed in range(block * 16, block * 16 + 16):
+        spec, desc = wl.random_layout_chain(seed)
+        g = np.random.default_rng(9000 + seed)
+        bits, tensors = [], []
+        for dt, shape in spec.inputs:
+            wide = dt == "f32"
+            b = g.integers(0, 1 << (32 if wide else 16), size=shape, dtype=np.uint32 if wide else np.uint16)
+            bits.append(b)
+            tensors.append(torch.from_numpy(b.view(np.int32 if wide else np.int16)).view(wl.DTYPES[dt]))
+        try:
+            outs, info = gpu_run(spec, tensors)
+        except pf.PfError as e:
+            assert e.status in (pf.PF_ERR_UNSUPPORTED, pf.PF_ERR_ALIGNMENT), f"{desc}: {e}"
+            print(f"refused ({pf.pf_status_str(e.status)}): {desc}: {e}")
+            continue
+        wants = orc.evaluate_layout_bits(spec, bits)
+        for k, (o, w) in enumerate(zip(outs, wants)):
+            assert tuple(o.shape) == tuple(w.shape), f"{desc}: output {k} shape"
+            assert np.array_equal(wl.raw_bits(o), w), f"{desc}: output {k} differs"
+        ran += 1
+    assert ran >= 12

@@ -525,3 +525,78 @@ def random_permute_chain(seed: int):
     v = s.op("permute", v, i=perm)
     s.out(v, dtype)
     return s, tensors, f"seed {seed}: {dtype} {shape} perm={perm} step={step}"
+
+
+def random_layout_chain(seed: int):
+    """A random layout-only chain: 1 to 3 inputs joined, sliced, permuted and reshaped at random, 1 or 2 outputs.
+    Returns (ChainSpec, description); the tests fill the inputs with arbitrary bit patterns."""
+    g = np.random.default_rng(BASE_SEED * 31 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    rank = int(g.integers(2, 5))
+    shape = [int(g.integers(1, 13)) for _ in range(rank)]
+    n_inputs = int(g.integers(1, 4))
+    s = ChainSpec(inputs=[(dtype, tuple(shape)) for _ in range(n_inputs)])
+    pool = list(range(n_inputs))          # inputs not joined in yet
+    v, cur = pool.pop(0), list(shape)
+    steps = []
+    for _ in range(int(g.integers(2, 7))):
+        kind = str(g.choice(["concat", "slice", "permute", "reshape"]))
+        if kind == "concat" and pool and cur == shape:
+            ax = int(g.integers(0, len(cur)))
+            v = s.op("concat", v, pool.pop(0), i=[ax]) if g.random() < 0.5 else s.op("concat", pool.pop(0), v, i=[ax])
+            cur = list(cur)
+            cur[ax] *= 2
+        elif kind == "slice":
+            ax = int(g.integers(0, len(cur)))
+            if cur[ax] < 2:
+                continue
+            length = int(g.integers(1, cur[ax]))
+            start = int(g.integers(0, cur[ax] - length + 1))
+            v = s.op("slice", v, i=[ax, start, length])
+            cur[ax] = length
+        elif kind == "permute" and len(cur) > 1:
+            perm = [int(p) for p in g.permutation(len(cur))]
+            v = s.op("permute", v, i=perm)
+            cur = [cur[p] for p in perm]
+        elif kind == "reshape":
+            if len(cur) > 1 and g.random() < 0.5:
+                q = int(g.integers(0, len(cur) - 1))
+                cur = cur[:q] + [cur[q] * cur[q + 1]] + cur[q + 2:]
+            elif len(cur) < 6:
+                q = int(g.integers(0, len(cur)))
+                f = [d for d in (2, 3, 4, 5) if cur[q] % d == 0]
+                if not f:
+                    continue
+                d = int(g.choice(f))
+                cur = cur[:q] + [d, cur[q] // d] + cur[q + 1:]
+            else:
+                continue
+            v = s.op("reshape", v, i=cur)
+        else:
+            continue
+        steps.append(kind)
+    if not any(k in ("concat", "slice") for k in steps):
+        ax = int(np.argmax(cur))
+        if cur[ax] >= 2:
+            v = s.op("slice", v, i=[ax, 0, cur[ax] - 1])
+            cur[ax] -= 1
+            steps.append("slice")
+    if v < n_inputs:                      # nothing was emitted at all
+        v = s.op("permute", v, i=list(range(len(cur)))[::-1])
+    ax = int(np.argmax(cur))
+    if cur[ax] >= 2 and g.random() < 0.4:
+        half = cur[ax] // 2
+        s.out(s.op("slice", v, i=[ax, 0, half]), dtype)
+        s.out(s.op("slice", v, i=[ax, half, cur[ax] - half]), dtype)
+    else:
+        s.out(v, dtype)
+    # inputs never joined in are dropped from the description
+    used = sorted({src for o in s.ops for src in o.src if src < n_inputs})
+    if len(used) != n_inputs:
+        remap = {old: new for new, old in enumerate(used)}
+        shift = n_inputs - len(used)
+        fix = lambda x: remap[x] if x < n_inputs else x - shift
+        s = ChainSpec(inputs=[s.inputs[u] for u in used],
+                      ops=[OpSpec(o.name, tuple(fix(x) for x in o.src), o.f, o.i) for o in s.ops],
+                      outputs=[(fix(x), dt) for x, dt in s.outputs])
+    return s, f"seed {seed}: {dtype} {tuple(shape)} x{len(s.inputs)} steps={steps} outputs={len(s.outputs)}"
