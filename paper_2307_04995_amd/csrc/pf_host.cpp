@@ -1452,7 +1452,11 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     const Shape& in = L.pre_shape;
     const int rank = (int)in.size();
     if (numel(in) > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the transpose family");
-    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the transpose family is not a multiple of 16 bytes");
+    // extents that are not whole vectors on either side (or a broadcast operand that is not): element-granular kernels
+    const bool ragged = p->ragged || (L.pre_shape.back() * es) % 16 != 0 || (L.post_shape.back() * es) % 16 != 0;
+    p->ragged = ragged;
+    if (ragged && (L.pre_shape.back() == 1 || L.post_shape.back() == 1))
+        return fail(PF_ERR_UNSUPPORTED, "permutations of tensors whose innermost extent is 1 are not implemented (reshape it away)");
     for (int i = 0; i < L.pro.n; ++i)
         if (L.pro.u[i].code == pf::U_STORE) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the transpose family");
     for (int i = 0; i < L.epi.n; ++i)
@@ -1467,7 +1471,9 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     for (int q = 0; q < rank; ++q) {
         const int src = L.perm[q];
         if (in[src] == 1) continue;
-        if (!od.empty() && od.back().in_stride == in[src] * istr[src]) {
+        // (ragged: dimensions are not merged, so that the innermost dimension of each side is one the vectors of
+        // broadcast operands and the partial last vector can be told from)
+        if (!ragged && !od.empty() && od.back().in_stride == in[src] * istr[src]) {
             od.back().extent *= in[src];
             od.back().in_stride = istr[src];
         } else {
@@ -1476,9 +1482,6 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     }
     if (od.empty()) od.push_back(Dim{1, 1});
     const int m = (int)od.size();
-    // the vectors of broadcast operands must not straddle rows of either layout
-    if ((L.pre_shape.back() * es) % 16 != 0 || (L.post_shape.back() * es) % 16 != 0)
-        return fail(PF_ERR_ALIGNMENT, "innermost extent is not a multiple of 16 bytes");
     pf::PermGeom& g = p->permg;
     memset(&g, 0, sizeof(g));
     g.in_n_inner = (uint32_t)L.pre_shape.back();
@@ -1493,7 +1496,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     acc = 1;
     for (int q = m - 1; q >= 0; --q) { ostr[q] = acc; acc *= od[q].extent; }
     p->family = PF_FAMILY_TRANSPOSE;
-    p->spec_id = env_int("PF_NO_STATIC", 0) ? 0 : match_spec(spec_table().perm, L);
+    p->spec_id = (env_int("PF_NO_STATIC", 0) || ragged) ? 0 : match_spec(spec_table().perm, L);
     p->args.n_inner = g.in_n_inner;
     p->args.rows = (uint64_t)(numel(in) / g.in_n_inner);
 
@@ -1506,7 +1509,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
             if (od[q].in_stride == 1) qi = q;
         if (qi < 0) return fail(PF_ERR_UNSUPPORTED, "internal: no contiguous input dimension");
         const int64_t n_i = od[qi].extent, n_o = od.back().extent;
-        if ((n_i * es) % 16 != 0 || (n_o * es) % 16 != 0)
+        if (!ragged && ((n_i * es) % 16 != 0 || (n_o * es) % 16 != 0))
             return fail(PF_ERR_ALIGNMENT, "transposed extents (%lld, %lld) are not multiples of 16 bytes", (long long)n_i, (long long)n_o);
         const bool pro_trivial = L.pro.n == 1 && L.pro.u[0].code == pf::U_MOV && L.pro.u[0].kind == pf::K_FULL && L.pro.u[0].slot == 0;
         if (es == 2 && !pro_trivial && L.epi.n != 0)
@@ -1549,19 +1552,25 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         p->lds_bytes = 0;
         if (!p->spec_id && jit_possible(p->device)) {
             std::string err;
-            p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, make_jit_spec(L), &err);
+            p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, ragged, make_jit_spec(L), &err);
             if (p->jit_fn) p->spec_id = pf::kSpecJit;
             else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
         }
         return PF_OK;
     }
     const int64_t inner = od.back().extent;
-    if ((inner * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost run of %lld elements is not a multiple of 16 bytes", (long long)inner);
+    if (!ragged && (inner * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "innermost run of %lld elements is not a multiple of 16 bytes", (long long)inner);
+    const int64_t inner_vecs = (inner + vec - 1) / vec;  // the last one partial when ragged
+    if (ragged) {
+        const int64_t tv = numel(in) / inner * inner_vecs;
+        if (tv > 0xffffffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the transpose family");
+        g.total_vecs = (uint32_t)tv;
+    }
     // LDS-staged variant: [batch, A, B, inner] -> [batch, B, A, inner]
     bool lds_ok = false;
     uint32_t ta = 0, tb = 0;
     int ia = -1, ib = -1;  // output positions of B (first) and A (second): out = [batch?, B, A, inner]
-    if (m == 3 || m == 4) {
+    if (!ragged && (m == 3 || m == 4)) {
         ib = m - 3;
         ia = m - 2;
         const Dim& B = od[ib];
@@ -1623,19 +1632,20 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         if (m > PF_DEV_MAX_RANK) return fail(PF_ERR_UNSUPPORTED, "too many dimensions");
         g.rank = m;
         for (int q = 0; q < m; ++q) {
-            g.extent[q] = (uint32_t)(q == m - 1 ? od[q].extent / vec : od[q].extent);
+            g.extent[q] = (uint32_t)(q == m - 1 ? inner_vecs : od[q].extent);
             g.in_stride[q] = (uint32_t)od[q].in_stride;
             g.out_stride[q] = (uint32_t)ostr[q];
             g.div[q] = make_fastdiv(g.extent[q]);
         }
-        p->k = g.total_vecs >= 65536u ? 2 : 1;
+        p->k = (g.total_vecs >= 65536u && !ragged) ? 2 : 1;
+        g.tile_a = (uint32_t)inner;  // (ragged kernels: length of the innermost run)
         p->block = dim3(256);
         p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
         p->lds_bytes = 0;
     }
     if (!p->spec_id && jit_possible(p->device)) {
         std::string err;
-        p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, make_jit_spec(L), &err);
+        p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, ragged, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
     }
@@ -2414,7 +2424,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
                 void* params[] = {&a, &g};
                 e = pf::jit_launch(plan->jit_fn, plan->grid, plan->block, plan->variant == PF_VARIANT_T_LDS_ROWS ? plan->lds_bytes : 0u, params, st);
             } else {
-                e = pf::launch_perm(plan->spec_id, L.main_dtype, a, plan->permg, plan->variant, plan->k, plan->grid, plan->block,
+                e = pf::launch_perm(plan->spec_id, L.main_dtype, a, plan->permg, plan->variant, plan->k, plan->ragged, plan->grid, plan->block,
                                     plan->lds_bytes, st);
             }
             break;

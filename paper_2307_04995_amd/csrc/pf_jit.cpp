@@ -164,11 +164,12 @@ hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const Jit
     return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
 }
 
-hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, const JitSpec& spec, std::string* err) {
+hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, bool ragged, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
-    if (variant == 2) name << "pf::perm_tile_kernel<" << dtype << ", " << spec_text(spec) << ">";
+    const char* rg = ragged ? "true" : "false";
+    if (variant == 2) name << "pf::perm_tile_kernel<" << dtype << ", " << spec_text(spec) << ", " << rg << ">";
     else if (variant == 1) name << "pf::perm_lds_rows_kernel<" << dtype << ", " << spec_text(spec) << ">";
-    else name << "pf::perm_rows_kernel<" << dtype << ", " << k << ", " << spec_text(spec) << ">";
+    else name << "pf::perm_rows_kernel<" << dtype << ", " << k << ", " << spec_text(spec) << ", " << rg << ">";
     return compile(device, "#include \"pf_perm_kernels.hpp\"\n", name.str(), err);
 }
 

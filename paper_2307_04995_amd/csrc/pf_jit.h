@@ -34,7 +34,7 @@ hipFunction_t jit_row_stream_kernel(int device, int dtype, bool ragged, const Ji
 hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);
 
 // transpose family: variant 0 rows (k vectors per lane), 1 LDS-staged rows, 2 register-transposed tiles
-hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, const JitSpec& spec, std::string* err);
+hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, bool ragged, const JitSpec& spec, std::string* err);
 // group family: phase 0 fused, 1 statistics, 2 normalisation
 hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err);
 // stencil family (depthwise 3 x 3 convolution)

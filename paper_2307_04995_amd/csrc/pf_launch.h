@@ -14,7 +14,7 @@ hipError_t launch_row_static(int spec_id, int dtype, const ChainArgs& a, const R
                              hipStream_t st);
 hipError_t launch_ew(int dtype, const ChainArgs& a, uint32_t total_vecs, uint32_t vecs_per_row, int k, bool ragged,
                      dim3 grid, hipStream_t st);
-hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, bool ragged, dim3 grid,
                        dim3 block, uint32_t lds, hipStream_t st);
 // phase 0: fused (resident) kernel; 1: statistics launch; 2: normalisation launch
 hipError_t launch_group(int phase, bool general, int spec_id, int dtype, const ChainArgs& a, const GroupGeom& g, int nv, uint32_t tiles,

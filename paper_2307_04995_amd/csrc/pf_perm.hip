@@ -22,9 +22,19 @@ struct PermSpecOf<0> {
 };
 
 template <int ID, int DT>
-static hipError_t launch_perm_spec_dt(const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid, dim3 block,
+static hipError_t launch_perm_spec_dt(const ChainArgs& a, const PermGeom& g, int variant, int k, bool ragged, dim3 grid, dim3 block,
                                       uint32_t lds, hipStream_t st) {
     using Spec = typename PermSpecOf<ID>::type;
+    if (ragged) {
+        // extents that are not whole vectors: built in the run-time-interpreted form only (specialised when the plan is made)
+        if constexpr (ID == 0) {
+            if (variant == 2) hipLaunchKernelGGL((perm_tile_kernel<DT, Spec, true>), grid, block, 0, st, a, g);
+            else if (variant == 0 && k == 1) hipLaunchKernelGGL((perm_rows_kernel<DT, 1, Spec, true>), grid, block, 0, st, a, g);
+            else return hipErrorInvalidValue;
+            return hipGetLastError();
+        }
+        return hipErrorInvalidValue;
+    }
     if (variant == 2) {
         hipLaunchKernelGGL((perm_tile_kernel<DT, Spec>), grid, block, 0, st, a, g);
     } else if (variant == 1) {
@@ -38,22 +48,22 @@ static hipError_t launch_perm_spec_dt(const ChainArgs& a, const PermGeom& g, int
 }
 
 template <int ID>
-static hipError_t launch_perm_spec(int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+static hipError_t launch_perm_spec(int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, bool ragged, dim3 grid,
                                    dim3 block, uint32_t lds, hipStream_t st) {
     switch (dtype) {
-        case DT_F32: return launch_perm_spec_dt<ID, DT_F32>(a, g, variant, k, grid, block, lds, st);
-        case DT_F16: return launch_perm_spec_dt<ID, DT_F16>(a, g, variant, k, grid, block, lds, st);
-        case DT_BF16: return launch_perm_spec_dt<ID, DT_BF16>(a, g, variant, k, grid, block, lds, st);
+        case DT_F32: return launch_perm_spec_dt<ID, DT_F32>(a, g, variant, k, ragged, grid, block, lds, st);
+        case DT_F16: return launch_perm_spec_dt<ID, DT_F16>(a, g, variant, k, ragged, grid, block, lds, st);
+        case DT_BF16: return launch_perm_spec_dt<ID, DT_BF16>(a, g, variant, k, ragged, grid, block, lds, st);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, dim3 grid,
+hipError_t launch_perm(int spec_id, int dtype, const ChainArgs& a, const PermGeom& g, int variant, int k, bool ragged, dim3 grid,
                        dim3 block, uint32_t lds, hipStream_t st) {
     switch (spec_id) {
-        case 0: return launch_perm_spec<0>(dtype, a, g, variant, k, grid, block, lds, st);
+        case 0: return launch_perm_spec<0>(dtype, a, g, variant, k, ragged, grid, block, lds, st);
 #define PF_CASE(id, ...) \
-    case id: return launch_perm_spec<id>(dtype, a, g, variant, k, grid, block, lds, st);
+    case id: return launch_perm_spec<id>(dtype, a, g, variant, k, ragged, grid, block, lds, st);
             PF_PERM_SPECS(PF_CASE)
 #undef PF_CASE
         default: return hipErrorInvalidValue;

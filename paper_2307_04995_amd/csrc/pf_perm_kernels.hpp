@@ -41,9 +41,10 @@ PF_DEVICE void perm_offsets(const PermGeom& g, uint32_t v, uint32_t vec, uint32_
 }
 
 // SIDES: 3 = operands of both programs, 1 = prologue operands only (input layout), 2 = epilogue operands only
-template <int DT, int K, class Spec, int SIDES = 3>
+// RAGGED: vectors may start at any element and hold fewer than VEC elements (cnt[k] of them; 0 = none)
+template <int DT, int K, class Spec, int SIDES = 3, bool RAGGED = false>
 PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneState<DT, K, Spec>& s, const uint32_t* in_off,
-                                  const uint32_t* out_off, const bool* valid) {
+                                  const uint32_t* out_off, const bool* valid, const uint32_t* cnt = nullptr) {
     using S = Storage<DT>;
 #pragma unroll
     for (int f = 0; f < Spec::NF; ++f) {
@@ -53,7 +54,9 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
-                if (valid[k]) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)(epi ? out_off[k] : in_off[k]) * S::ESIZE);
+                if (!valid[k]) continue;
+                if (RAGGED) s.fraw[f][k] = load_elems<DT>(a.full[f], epi ? out_off[k] : in_off[k], cnt[k], 0u);
+                else s.fraw[f][k] = load_stream(a.full[f], (uint64_t)(epi ? out_off[k] : in_off[k]) * S::ESIZE);
             }
         }
     }
@@ -69,7 +72,8 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
                 if (valid[k]) {
                     const uint32_t off = epi ? out_off[k] : in_off[k];
                     const uint32_t row = fast_div(off, epi ? g.div_out_inner : g.div_in_inner);
-                    s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner);
+                    if (RAGGED) s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner, cnt[k]);
+                    else s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner);
                 }
             }
         }
@@ -85,12 +89,14 @@ PF_DEVICE void set_positions(LaneState<DT, K, Spec>& s, const uint32_t* off, con
     }
 }
 
-template <int DT, int K, class Spec>
+// RAGGED: the innermost extent (kept by the permutation) is not a whole number of vectors; the last vector of
+// every innermost run is partial and all of them start at element alignment.
+template <int DT, int K, class Spec, bool RAGGED = false>
 __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const PermGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     LaneState<DT, K, Spec> s;
-    uint32_t in_off[K], out_off[K];
+    uint32_t in_off[K], out_off[K], cnt[K];
     bool valid[K];
     const uint32_t base = blockIdx.x * (256u * K) + threadIdx.x;
 #pragma unroll
@@ -98,13 +104,24 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
         const uint32_t v = base + 256u * k;
         valid[k] = v < g.total_vecs;
         perm_offsets(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
+        cnt[k] = (uint32_t)VEC;
+        if (RAGGED) {
+            // position inside the innermost run (tile_a elements long here): the last iteration dimension counts its vectors
+            const uint32_t vv = valid[k] ? v : 0u;
+            const uint32_t iv = vv - fast_div(vv, g.div[g.rank - 1]) * g.extent[g.rank - 1];
+            cnt[k] = elems_below<VEC>(iv * (uint32_t)VEC, g.tile_a);
+        }
     }
-    perm_load_operands<DT, K, Spec>(a, g, s, in_off, out_off, valid);
+    perm_load_operands<DT, K, Spec, 3, RAGGED>(a, g, s, in_off, out_off, valid, cnt);
+    auto store = [&](int k, u32x4 v) {
+        if (RAGGED) store_elems<DT>(a.out[0], out_off[k], cnt[k], v);
+        else store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, v);
+    };
     if (a.raw_copy) {
         // layout-only chain: the bits travel untouched (no fp32 round trip, NaN payloads survive)
 #pragma unroll
         for (int k = 0; k < K; ++k)
-            if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, s.fraw[0][k]);
+            if (valid[k]) store(k, s.fraw[0][k]);
         return;
     }
     set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
@@ -113,7 +130,7 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
     run_program<DT, K, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
 #pragma unroll
     for (int k = 0; k < K; ++k)
-        if (valid[k]) store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, S::pack(s.acc + k * VEC));
+        if (valid[k]) store(k, S::pack(s.acc + k * VEC));
 }
 
 // LDS-staged variant for permutations that keep the innermost dimension and swap two outer dims A and B
@@ -205,7 +222,9 @@ PF_DEVICE void transpose_block(const u32x4 (&in)[Storage<DT>::VEC], u32x4 (&out)
     }
 }
 
-template <int DT, class Spec>
+// RAGGED: the two transposed extents need not be whole vectors: a lane's block is ni x no elements (0 .. VEC
+// each), rows and columns beyond that are neither loaded nor stored, and every access is element-aligned.
+template <int DT, class Spec, bool RAGGED = false>
 __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const PermGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -219,7 +238,9 @@ __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const
     const uint32_t ot = tile - q_o * g.extent[g.rank - 1];
     const uint32_t it = q_o - fast_div(q_o, g.div[g.rank - 2]) * g.extent[g.rank - 2];
     const uint32_t ti = lane & 7u, to = lane >> 3;
-    const bool valid = (it * TE + ti * VEC < g.tile_a) && (ot * TE + to * VEC < g.tile_b);
+    // elements of this lane's block along the input's innermost dimension (ni) and the output's (no)
+    const uint32_t ni = elems_below<VEC>(it * TE + ti * VEC, g.tile_a), no = elems_below<VEC>(ot * TE + to * VEC, g.tile_b);
+    const bool valid = ni != 0u && no != 0u;
 
     LaneState<DT, 1, Spec> s;
     u32x4 blk[VEC], outv[VEC];
@@ -229,13 +250,18 @@ __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const
     for (int r = 0; r < VEC; ++r) {
         in_off[r] = in_base + (to * VEC + r) * g.t_in_stride_o + ti * VEC;
         blk[r] = u32x4{0u, 0u, 0u, 0u};
-        if (valid) blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
+        if (RAGGED) {
+            if (valid && (uint32_t)r < no) blk[r] = load_elems<DT>(a.full[0], in_off[r], ni, 0u);
+        } else if (valid) {
+            blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
+        }
     }
     if (!pro_trivial) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
             const uint32_t zero = 0u;
-            perm_load_operands<DT, 1, Spec, 1>(a, g, s, &in_off[r], &zero, &valid);
+            const bool row_ok = valid && (!RAGGED || (uint32_t)r < no);
+            perm_load_operands<DT, 1, Spec, 1, RAGGED>(a, g, s, &in_off[r], &zero, &row_ok, &ni);
             s.fraw[0][0] = blk[r];
             set_positions<DT, 1, Spec>(s, &in_off[r], g.div_in_inner, g.in_n_inner);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
@@ -246,15 +272,20 @@ __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
         const uint32_t out_off = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
+        const bool row_ok = valid && (!RAGGED || (uint32_t)c < ni);
         if (a.epi.n != 0) {
             const uint32_t zero = 0u;
-            perm_load_operands<DT, 1, Spec, 2>(a, g, s, &zero, &out_off, &valid);
+            perm_load_operands<DT, 1, Spec, 2, RAGGED>(a, g, s, &zero, &out_off, &row_ok, &no);
             S::unpack(outv[c], s.acc);
             set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
             outv[c] = S::pack(s.acc);
         }
-        if (valid) store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, outv[c]);
+        if (RAGGED) {
+            if (row_ok) store_elems<DT>(a.out[0], out_off, no, outv[c]);
+        } else if (valid) {
+            store_stream(a.out[0], (uint64_t)out_off * S::ESIZE, outv[c]);
+        }
     }
 }
 

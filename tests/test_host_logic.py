@@ -204,10 +204,14 @@ def test_plan_errors():
     s = wl.ChainSpec(inputs=[("f16", (8, 64, 64))])
     s.out(s.op("permute", 0, i=[0, 2, 1]), "f16")
     assert _plan_status(s) == pf.PF_OK
-    # ... and its transposed extents must both be whole 16-byte vectors
+    # ... its transposed extents need not be whole 16-byte vectors (element-granular kernels)
     s = wl.ChainSpec(inputs=[("f16", (8, 12, 64))])
     s.out(s.op("permute", 0, i=[0, 2, 1]), "f16")
-    assert _plan_status(s) == pf.PF_ERR_ALIGNMENT
+    assert _plan_status(s) == pf.PF_OK
+    # ... but an innermost extent of 1 is refused
+    s = wl.ChainSpec(inputs=[("f16", (8, 12, 1))])
+    s.out(s.op("permute", 0, i=[1, 0, 2]), "f16")
+    assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
     # a value computed before the core is used after it
     s = wl.ChainSpec(inputs=[("f32", (4, 64))])
     a = s.op("relu", 0)

@@ -1,5 +1,5 @@
 """GPU parity for innermost extents that are not a multiple of a 16-byte vector (element-granular kernels of
-the row and element-wise families), through the C ABI, element by element against the fp64 oracle."""
+the row, element-wise and transpose families), through the C ABI, element by element against the fp64 oracle."""
 import numpy as np
 import pytest
 
@@ -105,3 +105,57 @@ def test_ragged_single_odd_row():
     spec = wl.ChainSpec(inputs=[("f16", (6, 33))])
     spec.out(spec.op("softmax", 0), "f16")
     check_chain(spec, [x], what="odd rows, softmax")
+
+
+# ---- transposes of extents that are not whole 16-byte vectors
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((3, 197, 64), (0, 2, 1)), ((2, 12, 197, 197), (0, 1, 3, 2)), ((100, 50), (1, 0)),
+                                        ((5, 7, 9, 11), (3, 1, 0, 2)), ((2, 67, 3, 70), (3, 2, 1, 0)), ((1, 3, 13), (2, 0, 1))])
+def test_ragged_innermost_changing_permute_bit_exact(shape, perm, dtype):
+    from oracle import pf_oracle as orc
+    from paper_2307_04995_amd import binding as pf
+    x = wl.random_tensor(shape, dtype, 2101, dist="uniform")
+    s = wl.ChainSpec(inputs=[(dtype, shape)])
+    s.out(s.op("permute", 0, i=list(perm)), dtype)
+    for generic in (False, True):
+        outs, info = gpu_run(s, [x], generic=generic)
+        (want,) = orc.evaluate_layout_bits(s, [wl.raw_bits(x)])
+        assert np.array_equal(wl.raw_bits(outs[0]), want), f"{shape} {perm} {dtype} generic={generic}"
+        assert info.family == pf.PF_FAMILY_TRANSPOSE
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((4, 12, 197), (1, 0, 2)), ((2, 5, 3, 50), (2, 0, 1, 3)), ((3, 7, 1000), (1, 0, 2))])
+def test_ragged_permute_that_keeps_the_innermost_dimension(shape, perm, dtype):
+    from oracle import pf_oracle as orc
+    from paper_2307_04995_amd import binding as pf
+    x = wl.random_tensor(shape, dtype, 2111, dist="uniform")
+    s = wl.ChainSpec(inputs=[(dtype, shape)])
+    s.out(s.op("permute", 0, i=list(perm)), dtype)
+    for generic in (False, True):
+        outs, info = gpu_run(s, [x], generic=generic)
+        (want,) = orc.evaluate_layout_bits(s, [wl.raw_bits(x)])
+        assert np.array_equal(wl.raw_bits(outs[0]), want), f"{shape} {perm} {dtype} generic={generic}"
+        assert info.variant == pf.PF_VARIANT_T_ROWS
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_transpose_fused_with_elementwise(dtype):
+    # (K [B, 197, 72] + bias [72]) * 0.125 -> [B, 72, 197]: ragged output rows; and element-wise work on the output side
+    b, sq, d = 3, 197, 72
+    k = wl.random_tensor((b, sq, d), dtype, 2121, dist="uniform")
+    bias = wl.random_tensor((d,), dtype, 2122, dist="uniform")
+    s = wl.ChainSpec(inputs=[(dtype, (b, sq, d)), (dtype, (d,))])
+    s.out(s.op("permute", s.op("scale", s.op("add", 0, 1), f=[0.125]), i=[0, 2, 1]), dtype)
+    check_chain(s, [k, bias], what=f"ragged bias + scale + transpose {dtype}")
+    col = wl.random_tensor((sq,), dtype, 2123, dist="uniform")
+    s = wl.ChainSpec(inputs=[(dtype, (b, sq, d)), (dtype, (sq,))])
+    s.out(s.op("add", s.op("permute", 0, i=[0, 2, 1]), 1), dtype)
+    check_chain(s, [k, col], what=f"ragged transpose + bias on the output side {dtype}")
+    # a kept ragged innermost dimension with a bias along it
+    x = wl.random_tensor((4, 6, 197), dtype, 2124, dist="uniform")
+    bias = wl.random_tensor((197,), dtype, 2125, dist="uniform")
+    s = wl.ChainSpec(inputs=[(dtype, (4, 6, 197)), (dtype, (197,))])
+    s.out(s.op("permute", s.op("add", 0, 1), i=[1, 0, 2]), dtype)
+    check_chain(s, [x, bias], what=f"ragged rows moved with a bias {dtype}")

@@ -501,16 +501,17 @@ def random_attention_chain(seed: int):
 
 
 def random_permute_chain(seed: int):
-    """(x [+ bias] [* scale]) -> random permutation of 2 to 5 dimensions whose extents are multiples of a vector
-    wherever the kernels need whole vectors (the innermost dimensions of both layouts)."""
+    """(x [+ bias] [* scale]) -> random permutation of 2 to 5 dimensions; the innermost extents of both layouts are
+    whole 16-byte vectors in half of the chains and arbitrary in the other half."""
     g = np.random.default_rng(BASE_SEED * 29 + seed)
     dtype = str(g.choice(["f16", "bf16", "f32"]))
     vec = 4 if dtype == "f32" else 8
     rank = int(g.integers(2, 6))
     perm = [int(p) for p in g.permutation(rank)]
     shape = [int(g.integers(1, 9)) for _ in range(rank)]
-    shape[rank - 1] = vec * int(g.integers(1, 13))           # innermost of the input
-    shape[perm[rank - 1]] = vec * int(g.integers(1, 13))     # innermost of the output
+    ragged = bool(g.random() < 0.5)                          # extents that are not whole 16-byte vectors
+    shape[rank - 1] = int(g.integers(2, 98)) if ragged else vec * int(g.integers(1, 13))           # innermost of the input
+    shape[perm[rank - 1]] = int(g.integers(2, 98)) if ragged else vec * int(g.integers(1, 13))     # innermost of the output
     shape = tuple(shape)
     ins, tensors = [(dtype, shape)], [random_tensor(shape, dtype, 700 * seed, dist="uniform")]
     s = ChainSpec(inputs=ins)
