@@ -40,7 +40,11 @@ def causal_needed_read_bytes(b, h, s, s_k, esize):
 def full_size_chain(name):
     """(spec, inputs, algorithmic bytes, nominal bytes, label) at the benchmark's full size."""
     import workloads as wl
-    spec, ins = wl.CONFIGS[name]()
+    if name == "C1x256":
+        # the C1 chain and kernel with 256 times the rows: what that kernel does when it is not launch-bound
+        spec, ins = wl.c1_bias_res_layernorm_gelu(rows=65536)
+    else:
+        spec, ins = wl.CONFIGS[name]()
     esz = {"f32": 4, "f16": 2, "bf16": 2}
     nominal = sum(t.numel() * t.element_size() for t in ins)
     out_bytes = 0
@@ -57,6 +61,7 @@ def full_size_chain(name):
         algorithmic = causal_needed_read_bytes(b, h, s, s_k, 2) + out_bytes
     labels = {
         "C1": "C1 fp32 x+res+bias -> LayerNorm -> GELU(erf) [256x768]",
+        "C1x256": "the C1 chain at [65536x768] (same kernel, 256 x the rows: its bandwidth when not launch-bound; not a BASELINE config)",
         "C2": "C2 fp16 scale -> causal mask -> softmax [8,12,512,512]",
         "C3": "C3 fp16 x+bias+res -> LayerNorm [16384x1024]",
         "C4": "C4 bf16 (Q+bias)*0.125 -> permute [32,512,16,64]->[32,16,512,64]",
@@ -261,7 +266,7 @@ def main():
         result["config"]["hot_us_per_call"] = round(hot[0] * 1e3, 3)
     if not args.no_context:
         chains = {}
-        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C3", "C4", "C5", "X1", "X2", "X3", "X4"]) if c]
+        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C1x256", "C3", "C4", "C5", "X1", "X2", "X3", "X4"]) if c]
         forced = dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.variant.split(",") if "=" in kv)
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
