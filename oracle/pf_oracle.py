@@ -189,6 +189,22 @@ def reduce_last(name: str, x: np.ndarray) -> np.ndarray:
     return out
 
 
+def reduce_axes(name: str, x: np.ndarray, axes) -> np.ndarray:
+    """The reduce basic operator (section 6) over any set of dimensions, extents kept as 1: the reduced
+    dimensions are moved behind the others (a transposition: data movement only), flattened, and reduced by the
+    same routine as a reduction over the last dimension."""
+    x = _f64(x)
+    axes = sorted(int(a) for a in axes)
+    if not axes or len(set(axes)) != len(axes) or axes[0] < 0 or axes[-1] >= x.ndim:
+        raise ValueError(f"oracle: reduce axes {axes} for rank {x.ndim}")
+    kept = [d for d in range(x.ndim) if d not in axes]
+    moved = np.ascontiguousarray(np.transpose(x, kept + axes))
+    n = int(np.prod([x.shape[d] for d in axes], dtype=np.int64))
+    flat = moved.reshape(tuple(x.shape[d] for d in kept) + (n,))
+    red = reduce_last(name, flat)                       # [kept..., 1]
+    return np.ascontiguousarray(red.reshape(tuple(1 if d in axes else x.shape[d] for d in range(x.ndim))))
+
+
 def dwconv2d_nhwc(x: np.ndarray, wgt: np.ndarray, stride: int = 1) -> np.ndarray:
     """Depthwise convolution (cross-correlation, zero padding of half the kernel extent on every side, the same
     stride along both axes) of channels-last x [n, h, w, c] with per-channel kernels wgt [kh, kw, c]
@@ -355,7 +371,7 @@ def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
     if name == "causal_mask":
         return causal_mask(a[0])
     if name in _REDUCE:
-        return reduce_last(name, a[0])
+        return reduce_axes(name, a[0], op.i) if len(op.i) else reduce_last(name, a[0])
     if name == "softmax":
         return softmax(a[0])
     if name == "dwconv2d":

@@ -641,6 +641,38 @@ def test_strided_depthwise_convolution():
     np.testing.assert_array_equal(got, orc.dwconv2d_nhwc(np.maximum(x, 0.0), k, stride=2))
 
 
+def test_reduction_over_other_dimensions():
+    # spatial pooling of a channels-last tensor: reduce over H and W, keep N and C
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((2, 3, 4, 5))
+    s = orc.reduce_axes("reduce_sum", x, [1, 2])
+    assert s.shape == (2, 1, 1, 5)
+    for n in range(2):
+        for c in range(5):
+            acc = 0.0
+            for h in range(3):
+                for w in range(4):
+                    acc += x[n, h, w, c]
+            assert abs(s[n, 0, 0, c] - acc) < 1e-13
+    np.testing.assert_allclose(orc.reduce_axes("reduce_mean", x, [1, 2]), x.mean(axis=(1, 2), keepdims=True), rtol=0, atol=1e-14)
+    np.testing.assert_array_equal(orc.reduce_axes("reduce_max", x, [2, 1]), x.max(axis=(1, 2), keepdims=True))
+    # a single middle dimension, and the last dimension named explicitly (equals the default)
+    np.testing.assert_allclose(orc.reduce_axes("reduce_sum", x, [2]), x.sum(axis=2, keepdims=True), rtol=0, atol=1e-14)
+    np.testing.assert_array_equal(orc.reduce_axes("reduce_mean", x, [3]), orc.reduce_last("reduce_mean", x))
+    # the mean of a tensor that is constant along the pooled dimensions is that constant, for every channel
+    y = np.broadcast_to(np.arange(5.0), (2, 3, 4, 5))
+    np.testing.assert_array_equal(orc.reduce_axes("reduce_mean", y, [1, 2])[1, 0, 0], np.arange(5.0))
+    with pytest.raises(ValueError):
+        orc.reduce_axes("reduce_sum", x, [1, 1])
+    with pytest.raises(ValueError):
+        orc.reduce_axes("reduce_sum", x, [4])
+    # through the chain walker: i = the dimensions to reduce
+    spec = wl.ChainSpec(inputs=[("f32", (2, 3, 4, 5))])
+    spec.out(spec.op("reduce_mean", spec.op("relu", 0), i=[1, 2]), "f32")
+    (got,) = orc.evaluate_outputs(spec, [x])
+    np.testing.assert_allclose(got, np.maximum(x, 0).mean(axis=(1, 2), keepdims=True), rtol=0, atol=1e-14)
+
+
 # ---- the broadcast basic operator with extents of 1 anywhere (paper section 6)
 
 def test_broadcast_to_against_explicit_loops():
