@@ -72,7 +72,9 @@ typedef enum {
     PF_EXP = 14,
     PF_RSQRT = 15,      /* 1 / sqrt(x)                                */
     PF_CAUSAL_MASK = 16,/* last two dims (i, j): j > i -> -inf, else x; the mask is implicit, never stored */
-    /* reduce over the last dimension, result keeps that dimension with extent 1 */
+    /* reduce; the result keeps every reduced dimension with extent 1.  n_i = 0: over the last dimension.
+       n_i >= 1: over the dimensions i[0] < i[1] < ...; implemented besides {last}: every dimension between the
+       first and the last (global pooling of a channels-last tensor [n, spatial.., c] into [n, 1.., c])       */
     PF_REDUCE_SUM = 17, PF_REDUCE_MAX = 18, PF_REDUCE_MEAN = 19,
     /* reduce-then-broadcast composites over the last dimension */
     PF_SOFTMAX = 20,    /* exp(x - max) / sum exp(x - max); exp(-inf) = 0; an all -inf row gives NaN        */
@@ -147,6 +149,8 @@ typedef enum {
     PF_FAMILY_STENCIL = 6,     /* depthwise convolution: overlapping reads kept on chip in a register window         */
     PF_FAMILY_GATHER = 5,      /* layout-only chains (concat / slice / permute / reshape): a copy driven by a table
                                   of contiguous runs computed when the plan is made                          */
+    PF_FAMILY_POOL = 7,        /* reduction over the positions of a channels-last tensor (global pooling): partial
+                                  results per workgroup, merged by the last workgroup of a sample to arrive      */
     PF_FAMILY_ATTENTION = 4    /* one-token attention: a head's rows span workgroups, partial results are
                                   merged by the last workgroup to arrive                                     */
 } pf_family;
@@ -235,7 +239,7 @@ pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
  * No allocation, no host synchronisation, no host work proportional to tensor size.
  * An output may be the same buffer as an input of identical shape and dtype in the element-wise, row and
  * group families (each element is read before it is written by the same lane); the other families
- * return PF_ERR_ALIAS for any overlap.  A plan with workspace (group, attention families) must not run on
+ * return PF_ERR_ALIAS for any overlap.  A plan with workspace (group, attention, pool families) must not run on
  * two streams at the same time.
  * The launches may be recorded into a HIP graph (stream capture) and replayed, except those of the one-launch
  * GroupNorm variant (PF_ERR_UNSUPPORTED while the stream is capturing; plan PF_VARIANT_GROUP_TWO_PASS instead).
@@ -243,7 +247,7 @@ pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
 pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *const *outputs, void *stream);
 
 /*
- * Kernels that wait for other workgroups (the fused GroupNorm variant) bound every wait; when a wait runs
+ * Kernels that wait for other workgroups (the fused GroupNorm variant, the merging workgroup of a pooling) bound every wait; when a wait runs
  * out they set an error word in the plan's workspace and carry on, so a launch always terminates.  This call
  * synchronises with the device (hipMemcpy), stores the word in *flag (0 = no wait ever gave up since the
  * plan was made) and clears it.  Plans without workspace always report 0.

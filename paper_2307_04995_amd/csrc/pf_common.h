@@ -111,6 +111,7 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
     CORE_PERMUTE = 8,
+    CORE_POOL = 13,         // reduction over the positions of a channels-last tensor (pool family)
     CORE_DWCONV = 12,       // depthwise convolution (stencil family); core_vec[0] = slot of the kernels
     CORE_GATHER = 11,       // layout-only chain with concatenations / slices
     CORE_ATTN_DECODE = 10,  // concat -> matrix-vector -> softmax -> concat -> vector-matrix (one-token attention)
@@ -166,6 +167,24 @@ struct GroupGeom {
     // groups of any width (GEN kernels): channels per group, its divider, and the most groups one vector touches
     uint32_t cpg, parts;
     FastDiv div_cpg;
+};
+
+// Pool family (reduction over the positions of a channels-last tensor) geometry.
+struct PoolGeom {
+    uint32_t samples, hw, channels;
+    uint32_t cv;                 // 16-byte vectors per position (channels / VEC)
+    uint32_t pos_per_step;       // positions a workgroup covers per step (512 / cv)
+    uint32_t pos_per_block;      // positions one workgroup owns
+    uint32_t blocks_per_sample;
+    uint32_t chunks;             // chunks (of NV position steps) a workgroup walks
+    uint32_t epi_full_mask, epi_vec_mask;  // operands that belong to the epilogue (read in the result's layout)
+    float inv_hw;                // 1 / positions (mean)
+    float* ws_partial;           // [samples][blocks_per_sample][channels] partial results (more than one block per sample)
+    uint32_t* ws_flags;          // [samples][blocks_per_sample] 1 = the slice's partial result is published (lowered by the merger)
+    uint32_t* ws_error;          // set to 1 if a wait ran out
+    uint32_t spin_limit;         // polling rounds before a wait gives up
+    uint32_t pad;
+    FastDiv div_cv;
 };
 
 // Attention family (one new token against cached keys and values); all tensors of one storage type.

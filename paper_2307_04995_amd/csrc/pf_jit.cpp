@@ -187,6 +187,12 @@ hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, con
     return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
 }
 
+hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err) {
+    std::ostringstream name;
+    name << "pf::pool_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << op << ">";
+    return compile(device, "#include \"pf_pool_kernels.hpp\"\n", name.str(), err);
+}
+
 int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes) {
     int n = 0;
     if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, block_threads, lds_bytes) != hipSuccess) return 0;

@@ -103,3 +103,8 @@ def test_random_layout_chains_are_bit_exact(block):
             assert np.array_equal(wl.raw_bits(o), w), f"{desc}: output {k} differs"
         ran += 1
     assert ran >= 12
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_pooling_chains_match_the_oracle(block):
+    assert _run_random(wl.random_pool_chain, range(block * 12, block * 12 + 12)) == 12

@@ -601,3 +601,42 @@ def random_layout_chain(seed: int):
                       ops=[OpSpec(o.name, tuple(fix(x) for x in o.src), o.f, o.i) for o in s.ops],
                       outputs=[(fix(x), dt) for x, dt in s.outputs])
     return s, f"seed {seed}: {dtype} {tuple(shape)} x{len(s.inputs)} steps={steps} outputs={len(s.outputs)}"
+
+
+def random_pool_chain(seed: int):
+    """A random pooling chain: [element-wise] -> reduce_sum / max / mean over the positions of a channels-last tensor
+    -> [element-wise]; random sample count, 1 to 3 spatial dimensions, channel count, storage type."""
+    g = np.random.default_rng(BASE_SEED * 37 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    vec = 4 if dtype == "f32" else 8
+    c = vec * int(g.integers(1, 65))
+    n = int(g.integers(1, 6))
+    spatial = [int(g.integers(1, 48)) for _ in range(int(g.integers(1, 4)))]
+    shape = tuple([n] + spatial + [c])
+    positions = int(np.prod(spatial))
+    op = str(g.choice(["reduce_sum", "reduce_max", "reduce_mean"]))
+    # (sums are kept O(1): a 16-bit result of magnitude 16 is rounded by more than the absolute bar allows)
+    x = random_tensor(shape, dtype, 900 * seed, scale=2.0 / positions if op == "reduce_sum" else 0.8)
+    s = ChainSpec(inputs=[(dtype, shape)])
+    tensors = [x]
+    pre = str(g.choice(["none", "relu", "silu", "bias"]))
+    post = str(g.choice(["none", "sigmoid", "bias", "sample_bias"]))
+    if pre == "bias":
+        s.inputs.append((dtype, (c,)))
+        tensors.append(random_tensor((c,), dtype, 900 * seed + 1, scale=0.3 / (positions if op == "reduce_sum" else 1.0)))
+    if post in ("bias", "sample_bias"):
+        shp = (c,) if post == "bias" else tuple([n] + [1] * len(spatial) + [c])
+        s.inputs.append((dtype, shp))
+        tensors.append(random_tensor(shp, dtype, 900 * seed + 2, scale=0.3))
+    v = 0
+    if pre == "bias":
+        v = s.op("add", v, 1)
+    elif pre != "none":
+        v = s.op(pre, v)
+    v = s.op(op, v, i=list(range(1, len(shape) - 1)))
+    if post in ("bias", "sample_bias"):
+        v = s.op("add", v, len(s.inputs) - 1)
+    elif post == "sigmoid":
+        v = s.op("sigmoid", v)
+    s.out(v, dtype)
+    return s, tensors, f"seed {seed}: {dtype} {shape} {op} pre={pre} post={post}"
