@@ -2143,16 +2143,15 @@ pf_status plan_pool(pf_plan_s* p) {
     for (int v = 0; v < L.n_vec; ++v)
         if (L.vec_is_epi[v]) g.epi_vec_mask |= 1u << v;
     // A workgroup walks `chunks` chunks of nv position steps.  Slices are cut so that the device gets about four
-    // workgroups per compute unit, but never more than 16 per sample: partial results travel as device-coherent
-    // 4-byte stores, and those are dear (measured on [16, 64, 64, 512] fp16: 64 slices per sample 69 us, 32: 29 us,
-    // 16: 21 us, 8: 21 us, 4: 30 us).
+    // workgroups per compute unit, at most 32 per sample (measured on [16, 64, 64, 512] fp16: 64 slices per sample
+    // 21 us, 32: 17.7 us, 16: 17.1 us, 8: 19.5 us, 4: 28 us; with SiLU in front 32 slices are best).
     int nv = 8;
     while (nv > 1 && (int64_t)(nv / 2) * g.pos_per_step >= hw) nv /= 2;
     const int forced_nv = env_int("PF_POOL_NV", 0);
     if (forced_nv == 1 || forced_nv == 2 || forced_nv == 4 || forced_nv == 8) nv = forced_nv;
     const int64_t chunk_pos = (int64_t)nv * g.pos_per_step;
     const int64_t all_chunks = (hw + chunk_pos - 1) / chunk_pos;
-    const int64_t want_bps = std::max<int64_t>(1, std::min<int64_t>(all_chunks, std::min<int64_t>(16, (4 * (int64_t)n_cu + n - 1) / n)));
+    const int64_t want_bps = std::max<int64_t>(1, std::min<int64_t>(all_chunks, std::min<int64_t>(32, (4 * (int64_t)n_cu + n - 1) / n)));
     int64_t chunks = (all_chunks + want_bps - 1) / want_bps;
     const int forced_chunks = env_int("PF_POOL_CHUNKS", 0);
     if (forced_chunks > 0) chunks = forced_chunks;

@@ -101,14 +101,17 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
 
     if (g.blocks_per_sample > 1u) {
         // ---- publish the slice's partial result, then raise the slice's flag.  The sample's LAST slice (dispatched
-        // after the others) waits for all flags, merges, and lowers the flags again for the next launch.  Counting
-        // arrivals instead costs a device-scope read-modify-write per workgroup, and those to one address are
-        // served one after the other, about a microsecond each: 64 slices per sample took 64 us that way.
-        float* part = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + bx) * g.cv + t) * VEC;
+        // after the others) waits for all flags, merges, and lowers the flags again for the next launch.
+        // (the slice's result goes through LDS once more so that consecutive lanes store consecutive words: a wave
+        // then writes 256 contiguous bytes instead of 64 separate words)
+        __syncthreads();
         if (owner) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) __hip_atomic_store(part + e, acc[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int e = 0; e < VEC; ++e) lds[t * VEC + e] = acc[e];
         }
+        __syncthreads();
+        float* part = g.ws_partial + (uint64_t)(sample * g.blocks_per_sample + bx) * g.channels;
+        for (uint32_t idx = t; idx < g.channels; idx += 512u) __hip_atomic_store(part + idx, lds[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
         __syncthreads();
         uint32_t* flags = g.ws_flags + (uint64_t)sample * g.blocks_per_sample;
@@ -127,35 +130,28 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
             __builtin_amdgcn_s_sleep(8);
         }
         for (uint32_t b = t; b < g.blocks_per_sample; b += 512u) __hip_atomic_store(flags + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // every lane takes part: lane (pstep, channel vector) merges slices pstep, pstep + pos_per_step, ...,
-        // four loads in flight at a time; the position steps are then merged through LDS as above
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = pool_identity<OP>();
-        if (active) {
-            for (uint32_t b0 = pstep; b0 < g.blocks_per_sample; b0 += 4u * g.pos_per_step) {
-                float part[4][VEC];
+        // one channel per lane (consecutive lanes, consecutive words), four slices in flight at a time
+        const float* base = g.ws_partial + (uint64_t)sample * g.blocks_per_sample * g.channels;
+        __syncthreads();
+        for (uint32_t idx = t; idx < g.channels; idx += 512u) {
+            float m = pool_identity<OP>();
+            for (uint32_t b0 = 0; b0 < g.blocks_per_sample; b0 += 4u) {
+                float part4[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const uint32_t b = b0 + (uint32_t)u * g.pos_per_step;
-                    const float* p = g.ws_partial + ((uint64_t)(sample * g.blocks_per_sample + (b < g.blocks_per_sample ? b : 0u)) * g.cv + cvi) * VEC;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e)
-                        part[u][e] = b < g.blocks_per_sample ? __hip_atomic_load(p + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : pool_identity<OP>();
+                    const uint32_t b = b0 + (uint32_t)u;
+                    part4[u] = b < g.blocks_per_sample ? __hip_atomic_load(base + (uint64_t)b * g.channels + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                                       : pool_identity<OP>();
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc[e] = pool_combine<OP>(acc[e], part[u][e]);
+                for (int u = 0; u < 4; ++u) m = pool_combine<OP>(m, part4[u]);
             }
+            lds[idx] = m;
         }
-        __syncthreads();  // (the first pass through LDS has been read by now)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) lds[t * VEC + e] = acc[e];
         __syncthreads();
         if (owner) {
-            for (uint32_t q = 1; q < g.pos_per_step; ++q)
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = pool_combine<OP>(acc[e], lds[(q * g.cv + t) * VEC + e]);
+            for (int e = 0; e < VEC; ++e) acc[e] = lds[t * VEC + e];
         }
     }
     if (!owner) return;
