@@ -59,7 +59,7 @@ def test_full_size_chain_matches_oracle(name):
         assert info.variant == pf.PF_VARIANT_GROUP_RESIDENT
 
 
-@pytest.mark.parametrize("name", ["X2", "X4"])
+@pytest.mark.parametrize("name", ["X2", "X4", "X5", "X6"])
 def test_full_size_extra_chains_match_oracle(name):
     # the attention and depthwise-convolution chains bench.py times for context, every element
     from paper_2307_04995_amd import binding as pf

@@ -247,6 +247,22 @@ def x3_channel_shuffle(n: int = 128, c: int = 232, h: int = 28, w: int = 28, gro
     return s, [quantise(a, dtype), quantise(b, dtype)]
 
 
+def x5_groupnorm_silu_wide_groups(n: int = 16, h: int = 64, w: int = 64, ch: int = 320, groups: int = 32, dtype: str = "f16"):
+    """GroupNorm + SiLU with 10 channels per group (not a BASELINE config): a group is not a whole number of
+    16-byte vectors, so the general-width kernels run."""
+    return c5_groupnorm_silu(n=n, h=h, w=w, ch=ch, groups=groups, dtype=dtype, salt=3)
+
+
+def x6_silu_global_mean(n: int = 32, h: int = 56, w: int = 56, c: int = 240, dtype: str = "f16"):
+    """SiLU -> mean over H and W of channels-last x [n, h, w, c] (not a BASELINE config; the squeeze step of a
+    squeeze-and-excite block with the activation in front of it)."""
+    g = _rng(11, 0)
+    x = g.standard_normal((n, h, w, c), dtype=np.float32)
+    s = ChainSpec(inputs=[(dtype, (n, h, w, c))])
+    s.out(s.op("reduce_mean", s.op("silu", 0), i=[1, 2]), dtype)
+    return s, [quantise(x, dtype)]
+
+
 CONFIGS = {
     "C1": c1_bias_res_layernorm_gelu,
     "C2": c2_causal_softmax,
@@ -257,6 +273,8 @@ CONFIGS = {
     "X4": x4_relu_dwconv,               # not a BASELINE config: activation + depthwise convolution
     "X3": x3_channel_shuffle,           # not a BASELINE config: concat -> channel shuffle -> split
     "X2": x2_decode_attention,          # not a BASELINE config: one-token attention against a key-value cache
+    "X5": x5_groupnorm_silu_wide_groups,  # not a BASELINE config: GroupNorm with groups of 10 channels
+    "X6": x6_silu_global_mean,          # not a BASELINE config: activation + global average pooling
 }
 
 
