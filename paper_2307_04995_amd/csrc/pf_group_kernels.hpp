@@ -258,6 +258,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     constexpr int VEC = S::VEC;
     // kLean: 16-bit storage and nothing but the load in front of the normalisation
     constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32 && !GEN;
+    // GEN == 2: the same for the general kernels, planned when a group holds an even number of channels
+    constexpr bool kLeanGen = GEN == 2 && Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
     __shared__ float lds_part[GEN ? 1 : 512 * 3];
     __shared__ float lds_stat[512 * 2];
     extern __shared__ float lds_gen[];  // GEN: [lane][part] (count, mean, M2)
@@ -342,7 +344,53 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             else run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
         };
 
-        if (PHASE != 2 && GEN) {
+        if (PHASE != 2 && GEN && kLeanGen) {
+            // ---- partial statistics straight from the packed values: plain sums per PAIR of elements (a pair never
+            // straddles groups when a group holds an even number of channels), two dot-product instructions per pair
+            float npos = 0.0f, sp[4], ssp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sp[j] = ssp[j] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                if (!valid_of(i)) continue;
+                npos += 1.0f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t w = raw[i][j];
+                    if (DT == DT_F16) {
+                        const f16x2 x = __builtin_bit_cast(f16x2, w), ones = {(_Float16)1.0f, (_Float16)1.0f};
+                        sp[j] = __builtin_amdgcn_fdot2(x, ones, sp[j], false);
+                        ssp[j] = __builtin_amdgcn_fdot2(x, x, ssp[j], false);
+                    } else {
+                        const bf16x2 x = __builtin_bit_cast(bf16x2, w), ones = {(__bf16)1.0f, (__bf16)1.0f};
+                        sp[j] = __builtin_amdgcn_fdot2_f32_bf16(x, ones, sp[j], false);
+                        ssp[j] = __builtin_amdgcn_fdot2_f32_bf16(x, x, ssp[j], false);
+                    }
+                }
+            }
+            const float n_pair = active ? 2.0f * npos : 0.0f;
+            const float inv = n_pair > 0.0f ? 1.0f / n_pair : 0.0f;
+            auto pair_stat = [&](int j) { return Stat{n_pair, sp[j] * inv, fmaxf(ssp[j] - sp[j] * sp[j] * inv, 0.0f)}; };
+            Stat cur = pair_stat(0);
+#pragma unroll
+            for (int j = 1; j <= 4; ++j) {
+                const bool flush = j == 4 || part_of(2 * (j % 4)) != part_of(2 * (j - 1));
+                if (flush) {
+                    float* q = lds_gen + (t * g.parts + part_of(2 * (j - 1))) * 3u;
+                    q[0] = cur.n;
+                    q[1] = cur.mean;
+                    q[2] = cur.m2;
+                }
+                if (j < 4) cur = flush ? pair_stat(j % 4) : stat_merge(cur, pair_stat(j % 4));
+            }
+            for (uint32_t part = part_of(VEC - 1) + 1u; part < g.parts; ++part) {
+                float* q = lds_gen + (t * g.parts + part) * 3u;
+                q[0] = 0.0f;
+                q[1] = 0.0f;
+                q[2] = 0.0f;
+            }
+        }
+        if (PHASE != 2 && GEN && !kLeanGen) {
             // ---- partial statistics: a running (mean, M2) per element slot over the lane's positions (one shared
             // count), then the slots of each part merged into one (count, mean, M2) triple per part in LDS
             float npos = 0.0f, mean_e[VEC], m2_e[VEC];
@@ -386,6 +434,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 q[1] = 0.0f;
                 q[2] = 0.0f;
             }
+        }
+        if (PHASE != 2 && GEN) {
             __syncthreads();
             uint32_t grp;
             Stat acc;
@@ -450,7 +500,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             __syncthreads();
         }
 
-        if (PHASE == 0 && !kLean) {
+        if (PHASE == 0 && !kLean && !kLeanGen) {
             // The prologue is run again on the packed values below.  Without this fence the compiler keeps the
             // widened values of the statistics pass alive across the exchange instead (NV * VEC more registers).
 #pragma unroll

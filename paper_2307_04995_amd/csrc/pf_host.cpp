@@ -1721,7 +1721,9 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     for (int64_t v = 0; v < cv; ++v) g.parts = std::max<uint32_t>(g.parts, (uint32_t)((v * vec + vec - 1) / cpg - (v * vec) / cpg + 1));
     const uint32_t gen_lds = general ? 512u * g.parts * 3u * (uint32_t)sizeof(float) : 0u;
     p->group_general = general;
-    const int gen_parts = general ? 1 : 0;
+    // 2: statistics straight from the packed 16-bit pairs (needs pairs that never straddle groups and nothing but the
+    // load in front of the normalisation; the kernel checks the rest at compile time)
+    const int gen_parts = !general ? 0 : ((cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);
@@ -1746,17 +1748,23 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
         const uint32_t ppb = (uint32_t)nv_c * g.pos_per_step;
         *bps_out = (uint32_t)((hw + ppb - 1) / ppb);
     };
-    // the largest tile that still gives every compute unit two workgroups
+    // The largest tile that still leaves enough workgroups.  The two-launch variant wants two per compute unit.  The
+    // one-launch variant does better with fewer, larger tiles, down to about two for every three compute units: all
+    // of them are resident at once, and fewer tiles mean fewer words in the exchange (measured: [16,32,32,640]
+    // 24.6 us with 688 tiles of 4 steps, 16.9 us with 176 of 16; [16,64,64,128] 16.5 -> 13.2 us).
+    const bool fused_candidate = L.n_full == 1 && g.vec_per_channel && forced_variant != PF_VARIANT_GROUP_TWO_PASS &&
+                                 (p->spec_id != 0 || jit_possible(p->device));
+    const uint64_t min_tiles = fused_candidate ? ((uint64_t)n_cu * 2 + 2) / 3 : 2 * (uint64_t)n_cu;
     const int cands[3] = {16, 8, 4};
     const int forced_nv = env_int("PF_GROUP_NV", 0);
     int nv = 0;
     uint32_t bps = 0;
     for (int ci = 0; ci < 3 && nv == 0; ++ci) {
         if (forced_nv && cands[ci] != forced_nv) continue;
-        if (general && cands[ci] == 16 && !forced_nv) continue;  // (the general kernels' registers hold 8 vectors at most)
+        if (general && !(gen_parts == 2 && jit_possible(p->device)) && cands[ci] == 16 && !forced_nv) continue;  // (16 vectors fit the general kernels' registers only with packed statistics)
         uint32_t b;
         tiling(cands[ci], &b);
-        if ((uint64_t)b * samples >= 2 * (uint64_t)n_cu || ci == 2 || forced_nv) {
+        if ((uint64_t)b * samples >= min_tiles || ci == 2 || forced_nv) {
             nv = cands[ci];
             bps = b;
         }
