@@ -274,7 +274,9 @@ PF_DEVICE Stat stat_merge(Stat a, Stat b) {
     const float delta = b.mean - a.mean;
     Stat r;
     r.n = n;
-    r.mean = a.mean + delta * (b.n * inv);
+    // (merging with an empty side must return the other side's mean bit for bit: the reciprocal is approximate, and a
+    // group of one element has to come out with zero deviation exactly)
+    r.mean = a.n == 0.0f ? b.mean : (b.n == 0.0f ? a.mean : a.mean + delta * (b.n * inv));
     r.m2 = a.m2 + b.m2 + delta * delta * (a.n * b.n * inv);
     return r;
 }

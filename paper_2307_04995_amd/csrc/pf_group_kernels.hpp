@@ -516,7 +516,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         // channel, so each element costs one fused multiply-add (taken directly from the fp16 value)
         const uint32_t my_grp = GEN ? first_grp : cvi >> g.log2_vpg;
         const float mean = lds_stat[my_grp * 2u], rstd = lds_stat[my_grp * 2u + 1u];
-        float A[VEC], B[VEC];
+        // fp32 chains subtract the mean first ((x - mean) * A + beta): folded into one multiply-add, a group whose
+        // spread is tiny against its mean loses eps_fp32 * |mean| * rstd, up to 3e-5 per unit of mean at rstd = 1 / sqrt(eps)
+        constexpr bool kCentre = DT == DT_F32;
+        float A[VEC], B[VEC], M[kCentre ? VEC : 1];
         auto affine = [&]() {
             float gm[VEC], bt[VEC];
 #pragma unroll
@@ -532,7 +535,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 const float r = GEN ? lds_stat[(my_grp + part_of(e)) * 2u + 1u] : rstd;
                 const float m = GEN ? lds_stat[(my_grp + part_of(e)) * 2u] : mean;
                 A[e] = r * gm[e];
-                B[e] = bt[e] - m * A[e];
+                B[e] = kCentre ? bt[e] : bt[e] - m * A[e];
+                if (kCentre) M[e % (kCentre ? VEC : 1)] = m;
             }
         };
         if (vec_per_channel) affine();
@@ -542,7 +546,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             prologue(i);
             if (!vec_per_channel) affine();
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(s.acc[e], A[e], B[e]);
+            for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(kCentre ? s.acc[e] - M[e % (kCentre ? VEC : 1)] : s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
             if (valid_of(i)) store_stream(out_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
         }

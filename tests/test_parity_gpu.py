@@ -142,6 +142,20 @@ def test_groupnorm_groups_of_any_width(n, h, w, c, g, dtype, variant):
     assert info.n_launches == (2 if variant == 0 else 1)
 
 
+def test_groupnorm_of_single_element_groups_returns_beta_exactly():
+    # one position, one channel per group: every deviation is exactly zero, the result is beta (1 / sqrt(eps) would
+    # amplify a one-ulp error of the mean to 3e-5)
+    c = 148
+    x = wl.random_tensor((1, 1, c), "f32", 1801, scale=2.0)
+    gamma = wl.random_tensor((c,), "f32", 1802, dist="positive")
+    beta = wl.random_tensor((c,), "f32", 1803)
+    s = wl.ChainSpec(inputs=[("f32", (1, 1, c)), ("f32", (c,)), ("f32", (c,))])
+    s.out(s.op("groupnorm", 0, 1, 2, f=[1e-5], i=[c]), "f32")
+    for variant in (0, 1):
+        outs, _, _ = check_chain(s, [x, gamma, beta], variant=variant, what=f"single-element groups, variant {variant}")
+        assert torch.equal(outs[0].reshape(-1), beta)
+
+
 @pytest.mark.parametrize("c,g", [(64, 8), (320, 32)])
 def test_groupnorm_with_residuals_on_both_sides(c, g):
     # GroupNorm(x + res) + skip: two full-shape operands in front, one behind (two-launch variant: the fused one
