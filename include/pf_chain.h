@@ -222,6 +222,10 @@ pf_status pf_chain_recompose(const pf_chain_desc *desc, pf_chain_desc *out, int3
  * a GIR template are parameters chosen before code is produced; here they are chosen once per plan).
  * `device` is a HIP device ordinal.  May allocate plan-owned device workspace; launches no kernel.
  * On success *out is a new plan the caller must release with pf_chain_plan_destroy.
+ * Limits of the kernels (PF_ERR_UNSUPPORTED beyond them): a chain outside the layout-only family reads at most 3
+ * inputs of the full shape and 4 broadcast inputs, keeps at most 2 intermediate values alive besides the one being
+ * computed (4 per-row values in chains with in-line reductions), runs at most 24 element-wise steps on either side
+ * of its reduce / normalise / permute step, and holds one such step.
  * The environment variable PF_FORCE_VARIANT=<int> overrides the variant choice where that variant is
  * legal for the chain (for A/B measurements); PF_LOG=1 prints the decision to stderr.
  */
