@@ -34,7 +34,7 @@ PF_DEVICE void finish_slice(const AttnArgs& a, uint32_t head, uint32_t split, fl
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t d = a.d;
     const uint32_t n_split = gridDim.x;
-    float* part = a.ws_partial + ((uint64_t)head * n_split + split) * (d + 2u);
+    float* part = a.ws_partial + ((uint64_t)head * n_split + split) * a.part_stride;
     if (n_split == 1u) {
         if (tid < d) {
             const float r = PR ? o_mine / l_blk : o_mine * __builtin_amdgcn_rcpf(l_blk);
@@ -68,17 +68,17 @@ PF_DEVICE void finish_slice(const AttnArgs& a, uint32_t head, uint32_t split, fl
     // All 256 threads take part: thread (g, c) sums column c over the slices s = g, g + G, ... (G = 256 / d'
     // groups, d' = d rounded up to a power of two), so the loads of many slices are in flight together; the
     // groups are then combined through LDS.
-    const float* base = a.ws_partial + (uint64_t)head * n_split * (d + 2u);
+    const float* base = a.ws_partial + (uint64_t)head * n_split * a.part_stride;
     uint32_t dp = 1;
     while (dp < d) dp <<= 1;
     const uint32_t groups = 256u / dp, g = tid / dp, c = tid - g * dp;
     float big = -__builtin_inff();
     for (uint32_t s = lane; s < n_split; s += 64u)
-        big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * (d + 2u) + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        big = fmaxf(big, __hip_atomic_load(base + (uint64_t)s * a.part_stride + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     for (int msk = 1; msk < 64; msk <<= 1) big = fmaxf(big, shfl_xor_f(big, msk));  // every wave finds the same maximum
     float num = 0.0f, den = 0.0f;
     for (uint32_t s = g; s < n_split; s += groups) {
-        const float* ps = base + (uint64_t)s * (d + 2u);
+        const float* ps = base + (uint64_t)s * a.part_stride;
         const float ms = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const float ls = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const float os = c < d ? __hip_atomic_load(ps + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;

@@ -197,13 +197,15 @@ struct AttnArgs {
     void* o;              // [heads, d]
     void* k_out;          // [heads, t_total, d] grown caches, or null when they are not outputs
     void* v_out;
-    float* ws_partial;    // [heads][splits][d + 2]: weighted value sum, maximum, sum of exponentials
+    float* ws_partial;    // [heads][splits][part_stride]: weighted value sum (d), maximum, sum of exponentials
     uint32_t* ws_counter; // [heads] arrivals of the current launch (re-armed by the last arrival)
     uint32_t t, t_total;  // cached rows; rows after the concatenation (t or t + 1)
     uint32_t d;           // head dimension (elements), at most 256
     uint32_t lanes_per_row, log2_lpr;
     float scale;
     uint32_t chunks;      // streaming variant: chunks (of NV steps of 256 / lanes_per_row rows) a workgroup walks
+    uint32_t part_stride; // floats between the partial results of two slices: d + 2 rounded up to whole 128-byte lines, so
+                          // that no two workgroups publish (device-coherent stores) into one memory line
 };
 
 // Stencil family (depthwise 3 x 3 convolution on a channels-last tensor) geometry.

@@ -2267,7 +2267,8 @@ pf_status plan_attn(pf_plan_s* p, int forced_variant) {
     p->grid = dim3((uint32_t)splits, (uint32_t)heads);
     p->lds_bytes = (8 + 4 * 256 + 1) * 4;
     p->n_launches = 1;
-    const uint64_t part_bytes = ((uint64_t)heads * splits * (d + 2) * sizeof(float) + 255) / 256 * 256;
+    a.part_stride = (uint32_t)((d + 2 + 31) / 32 * 32);
+    const uint64_t part_bytes = ((uint64_t)heads * splits * a.part_stride * sizeof(float) + 255) / 256 * 256;
     const uint64_t cnt_bytes = ((uint64_t)heads * sizeof(uint32_t) + 255) / 256 * 256;
     p->workspace_bytes = part_bytes + cnt_bytes;
     if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
