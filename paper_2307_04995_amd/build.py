@@ -17,9 +17,9 @@ LIBDIR = os.path.join(HERE, "lib")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(LIBDIR, "libpf_chain.so")
 
-SOURCES = ["pf_host.cpp", "pf_jit.cpp", "pf_row_generic.hip", "pf_row_stream.hip", "pf_row_static.hip", "pf_row_static_f32.hip", "pf_row_static_f16.hip",
+SOURCES = ["pf_host.cpp", "pf_check.cpp", "pf_recompose.cpp", "pf_lower.cpp", "pf_plan.cpp", "pf_jit.cpp", "pf_row_generic.hip", "pf_row_stream.hip", "pf_row_static.hip", "pf_row_static_f32.hip", "pf_row_static_f16.hip",
            "pf_row_static_bf16.hip", "pf_perm.hip", "pf_group.hip", "pf_attn.hip", "pf_gather.hip", "pf_stencil.hip", "pf_pool.hip"]
-HEADERS = ["pf_common.h", "pf_device.hpp", "pf_jit.h", "pf_launch.h", "pf_row_kernels.hpp", "pf_row_stream.hpp", "pf_perm_kernels.hpp", "pf_group_kernels.hpp", "pf_stencil_kernels.hpp", "pf_pool_kernels.hpp", "pf_specs.h", "pf_row_static.inc",
+HEADERS = ["pf_common.h", "pf_host_internal.h", "pf_chain.map", "pf_device.hpp", "pf_jit.h", "pf_launch.h", "pf_row_kernels.hpp", "pf_row_stream.hpp", "pf_perm_kernels.hpp", "pf_group_kernels.hpp", "pf_stencil_kernels.hpp", "pf_pool_kernels.hpp", "pf_specs.h", "pf_row_static.inc",
            os.path.join("..", "..", "include", "pf_chain.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-pass-failed",
@@ -68,7 +68,7 @@ def build(force: bool = True, verbose: bool = False, jobs: int | None = None) ->
 
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs + ["-lhiprtc", "-ldl"]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,--version-script=" + os.path.join(CSRC, "pf_chain.map"), "-o", LIB] + objs + ["-lhiprtc", "-ldl"]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,0 +1,152 @@
+// Declarations shared by the host-side translation units of the fused-chain library: description checking
+// (pf_check.cpp), recomposition of basic operators (pf_recompose.cpp), lowering to micro-programs (pf_lower.cpp),
+// kernel-family planning (pf_plan.cpp) and the C ABI with the launch path (pf_host.cpp).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pf_chain.h"
+#include "pf_common.h"
+#include "pf_jit.h"
+#include "pf_launch.h"
+
+namespace pfh {
+
+// ---- errors: the message is kept per thread for pf_last_error ----
+pf_status fail(pf_status s, const char* fmt, ...);
+const char* last_error();
+
+// ---- operator table and shapes ----
+enum OpClass { OC_BINARY, OC_UNARY, OC_MASK, OC_REDUCE, OC_SOFTMAX, OC_LAYERNORM, OC_RMSNORM, OC_GROUPNORM, OC_PERMUTE, OC_RESHAPE,
+               OC_CONCAT_ROWS, OC_MATVEC, OC_VECMAT, OC_CONCAT, OC_SLICE, OC_DWCONV };
+
+struct OpTraits {
+    OpClass cls;
+    int arity;
+    const char* name;
+};
+
+extern const OpTraits kOps[PF_OP_COUNT_];
+
+inline bool is_elementwise(OpClass c) { return c == OC_BINARY || c == OC_UNARY || c == OC_MASK; }
+
+typedef std::vector<int64_t> Shape;
+
+int64_t numel(const Shape& s);
+bool is_trailing(const Shape& small_in, const Shape& big);
+bool is_row_value_of(const Shape& small, const Shape& big);
+bool broadcasts_onto(const Shape& small, const Shape& big);
+inline int dtype_size(int dt) { return dt == PF_F32 ? 4 : 2; }
+
+// A REDUCE_* operator with integer attributes names the dimensions it reduces; without, or with just the last
+// dimension, it is the row reduction.
+inline bool reduces_other_dims(const pf_op_desc& o, size_t rank) { return o.n_i > 1 || (o.n_i == 1 && o.i[0] != (int64_t)rank - 1); }
+
+struct Checked {
+    std::vector<Shape> shape;  // per value id
+};
+
+// Full structural and shape check of a chain description; fills the shape of every value.
+pf_status check_desc(const pf_chain_desc* d, Checked* out);
+
+// Rewrites sub-graphs of basic operators that spell a softmax, a layer normalisation or an RMS normalisation over the
+// last dimension into that operator.  Returns false (out untouched or partial) when nothing matched.
+bool recompose_chain(const pf_chain_desc* d, const Checked& c, pf_chain_desc* out);
+
+// ---- lowering ----
+struct Lowered {
+    int main_dtype = PF_F32;
+    int core_op = -1;         // index into desc->ops, -1 = none
+    int pool_op = 0;          // CORE_POOL: 0 sum, 1 maximum, 2 mean
+    int core = pf::CORE_NONE;
+    float eps = 0.0f;
+    int n_full = 0, n_vec = 0, n_tmp = 0;
+    int full_input[PF_DEV_MAX_FULL];  // chain input index per full slot
+    bool full_is_epi[PF_DEV_MAX_FULL];
+    int vec_input[PF_DEV_MAX_VEC];
+    bool vec_is_epi[PF_DEV_MAX_VEC];
+    bool general_bcast = false;         // some broadcast input needs the general (term-based) addressing
+    Shape vec_partner[PF_DEV_MAX_VEC];  // shape of the value the operand is broadcast against (where it is first used)
+    int core_vec[2] = {-1, -1};
+    pf::Program pro, epi;
+    uint32_t mask_si = 0;     // load skipping allowed for a causal mask of this extent
+    uint32_t core_mask = 0;   // the mask is applied inside the softmax core
+    float core_scale = 1.0f;  // scale folded into the softmax core
+    int out_slot_to_user[PF_MAX_OUTPUTS];  // args.out[slot] <- user outputs[...]
+    int n_out = 1;
+    Shape pre_shape;          // shape of the value entering the core (or the final value if no core)
+    Shape post_shape;         // shape of the value leaving the core
+    int64_t groups = 0;
+    int perm[PF_MAX_RANK];
+    // one-token attention: chain input index of q, new key row, new value row, key cache, value cache (-1: the
+    // caches already hold the new rows); user output index of o, grown key cache, grown value cache (-1: not an output)
+    int attn_in[5] = {-1, -1, -1, -1, -1};
+    int attn_out[3] = {-1, -1, -1};
+    float attn_scale = 1.0f;
+};
+
+// Lowers a checked chain: prologue and epilogue micro-programs around at most one core, operand slots, output slots.
+pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L);
+
+}  // namespace pfh
+
+// ---------------------------------------------------------------------------------------------
+// the plan
+// ---------------------------------------------------------------------------------------------
+struct pf_plan_s {
+    pf_chain_desc desc;
+    pfh::Lowered low;
+    int device = 0;
+    int family = 0, variant = 0;
+    int spec_id = 0;          // 0 = generic interpreter
+    int k = 1;                // 16-byte vectors per lane
+    bool reduce_only = false;
+    hipFunction_t jit_fn2 = nullptr; // second launch of a two-launch plan
+    hipFunction_t jit_fn = nullptr;  // kernel specialised for this chain's structure when the plan was made (spec_id == kSpecJit)
+    bool ragged = false;      // rows or broadcast operands that are not whole 16-byte vectors: element-granular kernels
+    pf::ChainArgs args;       // pointers are filled per run
+    pf::RowGeom row;
+    pf::GroupGeom group;
+    pf::PermGeom permg;
+    pf::AttnArgs attn;
+    pf::GatherArgs gather;
+    pf::StencilGeom stencil;
+    pf::PoolGeom pool;
+    int stencil_ks = 3;       // kernel extent of the depthwise convolution
+    int row_log2l = 6;        // row family: log2 of the lanes of a wave that share a row
+    pf::BcastTerm bcast_host[PF_DEV_MAX_VEC][PF_DEV_MAX_BCAST_TERMS];  // general broadcasting terms, staged on the host
+    void* bcast_dev = nullptr;  // ... and their copy in device memory
+    bool group_general = false; // group family: groups of any width (general kernels)
+    uint32_t dyn_lds = 0;     // group family: dynamic LDS bytes of each launch
+    uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
+    dim3 grid, block;
+    dim3 grid2, block2;       // second launch (two-pass group variant)
+    uint32_t lds_bytes = 0;
+    void* workspace = nullptr;
+    uint32_t* ws_error = nullptr;  // device word a kernel sets when one of its bounded waits ran out
+    uint64_t workspace_bytes = 0;
+    uint64_t in_bytes[PF_MAX_INPUTS];
+    uint64_t out_bytes[PF_MAX_OUTPUTS];
+    pfh::Shape out_shape[PF_MAX_OUTPUTS];
+    int n_launches = 1;
+    mutable uint32_t epoch = 0;
+};
+
+namespace pfh {
+
+// ---- planning ----
+int env_int(const char* name, int dflt);
+pf::FastDiv make_fastdiv(uint32_t d);
+// Checks, lowers and plans one description as it stands (no recomposition).
+pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out);
+
+}  // namespace pfh
