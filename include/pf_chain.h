@@ -168,7 +168,18 @@ typedef struct {
     int32_t spec_id;                   /* 0: run-time interpreted kernel; 1..254: built-in catalogue entry;
                                           PF_SPEC_JIT: specialised for this chain when the plan was made      */
     int32_t vectors_per_lane;          /* 16-byte vectors each lane keeps in registers */
+    int32_t n_kernels;                 /* 1, or the number of kernels a chain was split into (pf_chain_partition);
+                                          family, variant, grid, block, spec_id and vectors_per_lane are then the
+                                          first kernel's, workspace_bytes includes the tensors between kernels    */
 } pf_plan_info;
+
+/* A split of a chain into kernels: kernel k runs ops[first_op[k]] .. ops[first_op[k + 1] - 1]. */
+typedef struct {
+    int32_t n_parts;
+    int32_t first_op[PF_MAX_OPS + 1];
+    double predicted_us[PF_MAX_OPS]; /* the performance model's time for each kernel, microseconds */
+    uint64_t bytes[PF_MAX_OPS];      /* bytes each kernel reads and writes                           */
+} pf_partition;
 
 #define PF_VARIANT_EW_FLAT 0          /* element-wise: one 16-byte vector per lane per step                  */
 #define PF_SPEC_JIT 255               /* pf_plan_info.spec_id of a plan-time specialised kernel                */
@@ -216,6 +227,21 @@ pf_status pf_chain_infer_shape(const pf_chain_desc *desc, int32_t value, pf_tens
  * cannot be planned); PF_RECOMPOSE=0 in the environment switches that off.
  */
 pf_status pf_chain_recompose(const pf_chain_desc *desc, pf_chain_desc *out, int32_t *changed);
+
+/*
+ * Merge plan of a chain (host only; section 6, graph merging with a performance model).  One kernel holds one
+ * exchange wider than a lane; a chain with several (a layout change, then a normalisation, then another layout
+ * change; a normalisation followed by a pooling) runs as several kernels, and the element-wise operators between
+ * two exchanges can go with either neighbour.  The model prices a kernel at a launch cost plus the bytes it reads
+ * and writes over the rate its kernel family reaches; pf_chain_partition returns the split with the smallest
+ * total, pf_chain_segment_cost the price of operators first_op .. last_op - 1 as one kernel (an error status when
+ * they are not one kernel; us and bytes may be NULL).  Values that cross from one kernel to the next are stored in
+ * out_dtype[0].  pf_chain_plan applies the split by itself when a chain is not one kernel (PF_PARTITION=0 in the
+ * environment: PF_ERR_UNSUPPORTED instead); such a plan owns the tensors between its kernels, must not run on
+ * two streams at the same time, and returns PF_ERR_ALIAS when an output overlaps an input.
+ */
+pf_status pf_chain_partition(const pf_chain_desc *desc, pf_partition *out);
+pf_status pf_chain_segment_cost(const pf_chain_desc *desc, int32_t first_op, int32_t last_op, double *us, uint64_t *bytes);
 
 /*
  * Map the chain onto a kernel family and fix launch geometry (section 6: the parallelism and tile size of

@@ -60,13 +60,19 @@ class pf_plan_info(C.Structure):
                 ("lds_bytes", C.c_uint32), ("workspace_bytes", C.c_uint64),
                 ("compulsory_read_bytes", C.c_uint64), ("compulsory_write_bytes", C.c_uint64),
                 ("n_launches", C.c_int32), ("n_micro_ops", C.c_int32), ("spec_id", C.c_int32),
-                ("vectors_per_lane", C.c_int32)]
+                ("vectors_per_lane", C.c_int32), ("n_kernels", C.c_int32)]
+
+
+class pf_partition(C.Structure):
+    _fields_ = [("n_parts", C.c_int32), ("first_op", C.c_int32 * (PF_MAX_OPS + 1)),
+                ("predicted_us", C.c_double * PF_MAX_OPS), ("bytes", C.c_uint64 * PF_MAX_OPS)]
 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
-           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose"]
+           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose",
+           "pf_chain_partition", "pf_chain_segment_cost"]
 
 
 def _load() -> C.CDLL:
@@ -91,6 +97,8 @@ def _load() -> C.CDLL:
     lib.pf_last_error.restype = C.c_char_p
     lib.pf_copy_probe.argtypes = [vp, vp, C.c_uint64, C.c_int32, vp]
     lib.pf_chain_recompose.argtypes = [C.POINTER(pf_chain_desc), C.POINTER(pf_chain_desc), C.POINTER(C.c_int32)]
+    lib.pf_chain_partition.argtypes = [C.POINTER(pf_chain_desc), C.POINTER(pf_partition)]
+    lib.pf_chain_segment_cost.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     lib.pf_jit_compile_count.argtypes = []
     lib.pf_jit_compile_count.restype = C.c_uint64
     for name in EXPORTS:
@@ -179,6 +187,23 @@ def pf_chain_recompose(desc: pf_chain_desc):
     changed = C.c_int32(0)
     st = _lib.pf_chain_recompose(C.byref(desc), C.byref(out), C.byref(changed))
     return st, (out if st == PF_OK else None), bool(changed.value)
+
+
+def pf_chain_partition(desc: pf_chain_desc):
+    """(status, [(first_op, last_op, predicted_us, bytes), ...]) of the cheapest split into kernels."""
+    out = pf_partition()
+    st = _lib.pf_chain_partition(C.byref(desc), C.byref(out))
+    if st != PF_OK:
+        return st, None
+    return st, [(out.first_op[k], out.first_op[k + 1], out.predicted_us[k], out.bytes[k]) for k in range(out.n_parts)]
+
+
+def pf_chain_segment_cost(desc: pf_chain_desc, first_op: int, last_op: int):
+    """(status, predicted_us, bytes) of operators first_op .. last_op - 1 run as one kernel."""
+    us = C.c_double(0.0)
+    nbytes = C.c_uint64(0)
+    st = _lib.pf_chain_segment_cost(C.byref(desc), C.c_int32(first_op), C.c_int32(last_op), C.byref(us), C.byref(nbytes))
+    return st, us.value, nbytes.value
 
 
 def pf_jit_compile_count() -> int:

@@ -42,15 +42,28 @@ pf_status pf_chain_infer_shape(const pf_chain_desc* desc, int32_t value, pf_tens
 
 pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out) {
     if (!out) return fail(PF_ERR_INVALID_ARG, "out is null");
+    pf_status s = plan_one_kernel(desc, device, variant, out);
+    // more than one exchange wider than a lane (or one a single kernel cannot hold): several kernels, split where the
+    // performance model says the bytes are fewest
+    if (s == PF_ERR_UNSUPPORTED && variant < 0 && desc->n_ops > 1 && env_int("PF_PARTITION", 1) != 0) {
+        const std::string single = last_error();
+        if (plan_partitioned(desc, device, out) == PF_OK) return PF_OK;
+        const std::string split = last_error();
+        return fail(s, "%s; as several kernels: %s", single.c_str(), split.c_str());
+    }
+    return s;
+}
+
+pf_status pf_chain_partition(const pf_chain_desc* desc, pf_partition* out) {
     Checked c;
     pf_status s = check_desc(desc, &c);
     if (s != PF_OK) return s;
-    // a chain that spells a composite operator in basic operators is planned as that operator when that works
-    if (env_int("PF_RECOMPOSE", 1) != 0) {
-        pf_chain_desc composite;
-        if (recompose_chain(desc, c, &composite) && plan_checked_desc(&composite, device, variant, out) == PF_OK) return PF_OK;
-    }
-    return plan_checked_desc(desc, device, variant, out);
+    if (!out) return fail(PF_ERR_INVALID_ARG, "out is null");
+    return partition_chain(desc, c, std::vector<std::pair<int, int>>(), out);
+}
+
+pf_status pf_chain_segment_cost(const pf_chain_desc* desc, int32_t first_op, int32_t last_op, double* us, uint64_t* bytes) {
+    return segment_cost(desc, first_op, last_op, us, bytes);
 }
 
 }  // extern "C"
@@ -76,6 +89,22 @@ pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
     info->n_micro_ops = plan->low.pro.n + plan->low.epi.n;
     info->spec_id = plan->spec_id;
     info->vectors_per_lane = plan->k;
+    info->n_kernels = 1;
+    if (plan->composite) {  // family, variant, grid and block are the first kernel's; the sums are the chain's
+        info->n_kernels = (int32_t)plan->parts.size();
+        info->workspace_bytes = plan->arena_bytes;
+        info->n_micro_ops = 0;
+        pf_plan_info sub;
+        for (const pf_plan_s::Part& pp : plan->parts) {
+            pf_chain_plan_get_info(pp.plan, &sub);
+            info->workspace_bytes += sub.workspace_bytes;
+            info->n_micro_ops += sub.n_micro_ops;
+            info->lds_bytes = std::max(info->lds_bytes, sub.lds_bytes);
+        }
+        pf_chain_plan_get_info(plan->parts[0].plan, &sub);
+        info->spec_id = sub.spec_id;
+        info->vectors_per_lane = sub.vectors_per_lane;
+    }
     return PF_OK;
 }
 
@@ -104,6 +133,25 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             const uintptr_t jb = (uintptr_t)outputs[j], je = jb + plan->out_bytes[j];
             if (ob < je && jb < oe) return fail(PF_ERR_ALIAS, "outputs %d and %d overlap", j, o);
         }
+    }
+    if (plan->composite) {
+        // a value written by one kernel and read by the next may not share memory with anything the caller passed
+        for (int o = 0; o < d.n_outputs; ++o)
+            for (int k = 0; k < d.n_inputs; ++k) {
+                const uintptr_t ob = (uintptr_t)outputs[o], oe = ob + plan->out_bytes[o], ib = (uintptr_t)inputs[k], ie = ib + plan->in_bytes[k];
+                if (ob < ie && ib < oe) return fail(PF_ERR_ALIAS, "output %d overlaps input %d (the chain runs as several kernels)", o, k);
+            }
+        for (const pf_plan_s::Part& pp : plan->parts) {
+            const void* in[PF_MAX_INPUTS];
+            void* outp[PF_MAX_OUTPUTS];
+            for (int i = 0; i < pp.n_in; ++i)
+                in[i] = pp.in_kind[i] == 0 ? inputs[pp.in_index[i]] : pp.in_kind[i] == 1 ? (const void*)outputs[pp.in_index[i]] : (const void*)((const char*)plan->arena + plan->arena_offset[pp.in_index[i]]);
+            for (int o = 0; o < pp.n_out; ++o)
+                outp[o] = pp.out_kind[o] == 1 ? outputs[pp.out_index[o]] : (void*)((char*)plan->arena + plan->arena_offset[pp.out_index[o]]);
+            const pf_status ps = pf_chain_run(pp.plan, in, outp, stream);
+            if (ps != PF_OK) return ps;
+        }
+        return PF_OK;
     }
     const Lowered& L = plan->low;
     if (plan->family == PF_FAMILY_ATTENTION) {
@@ -223,6 +271,15 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
 pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
     if (!plan || !flag) return fail(PF_ERR_INVALID_ARG, "null argument");
     *flag = 0;
+    if (plan->composite) {
+        for (const pf_plan_s::Part& pp : plan->parts) {
+            int32_t f = 0;
+            const pf_status ps = pf_chain_plan_poll_error(pp.plan, &f);
+            if (ps != PF_OK) return ps;
+            *flag |= f;
+        }
+        return PF_OK;
+    }
     uint32_t* err = plan->family == PF_FAMILY_GROUP ? plan->group.ws_error : plan->ws_error;
     if (!err) return PF_OK;
     uint32_t word = 0;
@@ -237,6 +294,8 @@ void pf_chain_plan_destroy(pf_plan* plan) {
     if (!plan) return;
     if (plan->workspace) (void)hipFree(plan->workspace);
     if (plan->bcast_dev) (void)hipFree(plan->bcast_dev);
+    for (pf_plan_s::Part& pp : plan->parts) pf_chain_plan_destroy(pp.plan);
+    if (plan->arena) (void)hipFree(plan->arena);
     delete plan;
 }
 

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/pf_chain.h"
@@ -139,6 +140,18 @@ struct pf_plan_s {
     pfh::Shape out_shape[PF_MAX_OUTPUTS];
     int n_launches = 1;
     mutable uint32_t epoch = 0;
+    // a chain split into several kernels: one plan per kernel, run in order on the caller's stream
+    struct Part {
+        pf_plan_s* plan = nullptr;
+        int n_in = 0, n_out = 0;
+        int in_kind[PF_MAX_INPUTS], in_index[PF_MAX_INPUTS];     // kind 0: the caller's input, 1: the caller's output, 2: tensor in the arena
+        int out_kind[PF_MAX_OUTPUTS], out_index[PF_MAX_OUTPUTS];
+    };
+    bool composite = false;
+    std::vector<Part> parts;
+    void* arena = nullptr;                // tensors that cross from one kernel to the next
+    uint64_t arena_bytes = 0;
+    std::vector<uint64_t> arena_offset;
 };
 
 namespace pfh {
@@ -148,5 +161,15 @@ int env_int(const char* name, int dflt);
 pf::FastDiv make_fastdiv(uint32_t d);
 // Checks, lowers and plans one description as it stands (no recomposition).
 pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out);
+// One kernel for the whole chain: as its composite operators when it spells them in basic operators, else as written.
+pf_status plan_one_kernel(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out);
+
+// ---- chains of several kernels (pf_partition.cpp) ----
+// Modelled time and bytes of operators [first, last) run as one kernel; an error status when they are not one kernel.
+pf_status segment_cost(const pf_chain_desc* d, int first, int last, double* us, uint64_t* bytes);
+// The cheapest split under the model that uses no segment of `blocked`.
+pf_status partition_chain(const pf_chain_desc* d, const Checked& c, const std::vector<std::pair<int, int>>& blocked, pf_partition* out);
+// A plan of several kernels for a chain that is not one kernel.
+pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out);
 
 }  // namespace pfh

@@ -1221,4 +1221,16 @@ pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t v
     return s;
 }
 
+pf_status plan_one_kernel(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out) {
+    Checked c;
+    pf_status s = check_desc(desc, &c);
+    if (s != PF_OK) return s;
+    // a chain that spells a composite operator in basic operators is planned as that operator when that works
+    if (env_int("PF_RECOMPOSE", 1) != 0) {
+        pf_chain_desc composite;
+        if (recompose_chain(desc, c, &composite) && plan_checked_desc(&composite, device, variant, out) == PF_OK) return PF_OK;
+    }
+    return plan_checked_desc(desc, device, variant, out);
+}
+
 }  // namespace pfh

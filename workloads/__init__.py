@@ -658,3 +658,85 @@ def random_pool_chain(seed: int):
         v = s.op("sigmoid", v)
     s.out(v, dtype)
     return s, tensors, f"seed {seed}: {dtype} {shape} {op} pre={pre} post={post}"
+
+
+def random_multi_kernel_chain(seed: int):
+    """A random chain with two to four exchanges wider than a lane (softmax, layer / RMS normalisation, a reduction
+    over the last dimension used as a row statistic, a permutation of the leading dimensions, a transposition of the
+    last two) and random element-wise steps between them: more than one kernel by construction."""
+    g = np.random.default_rng(BASE_SEED * 41 + seed)
+    dtype = str(g.choice(["f16", "bf16", "f32"]))
+    shape = [int(g.integers(2, 6)), int(g.choice([3, 8, 17, 32])), int(g.choice([16, 24, 40, 64, 128, 200, 256]))]  # (no extents of 1: a permutation that makes one innermost is refused)
+    s = ChainSpec(inputs=[(dtype, tuple(shape))])
+    tensors = [random_tensor(tuple(shape), dtype, 1100 * seed)]
+    names = []
+
+    def operand(shp, scale, dist="normal"):
+        s.inputs.append((dtype, tuple(shp)))
+        tensors.append(random_tensor(tuple(shp), dtype, 1100 * seed + len(tensors), dist=dist, scale=scale))
+        return len(s.inputs) - 1
+
+    # inputs must be declared before operators use value ids: collect the stages first, then number the values
+    stages = []
+    after_softmax = False
+    for _ in range(int(g.integers(2, 5))):
+        st = str(g.choice(["softmax", "layernorm", "rmsnorm", "swap_leading", "transpose_inner", "centre"]))
+        # (probabilities are not centred: their differences from the row mean cancel, which turns the one-ulp
+        # difference a stored 16-bit tensor may have from the oracle's into a relative error above the bar)
+        if after_softmax and st in ("layernorm", "centre"):
+            st = "rmsnorm"
+        if st in ("softmax", "layernorm", "rmsnorm", "centre"):
+            after_softmax = st == "softmax"
+        stages.append(st)
+        for _ in range(int(g.integers(0, 3))):
+            stages.append(str(g.choice(["ew_silu", "ew_bias", "ew_full", "ew_scale", "ew_tanh"])))
+    plan = []
+    cur = list(shape)
+    for st in stages:
+        if len(s.inputs) + 2 > 8:  # the description holds eight inputs
+            st = {"layernorm": "softmax", "rmsnorm": "softmax", "ew_bias": "ew_silu", "ew_full": "ew_tanh"}.get(st, st)
+        if st in ("layernorm", "rmsnorm"):
+            gam = operand((cur[-1],), 1.0, "positive")
+            bet = operand((cur[-1],), 0.3) if st == "layernorm" else None
+            plan.append((st, gam, bet))
+        elif st == "swap_leading":
+            plan.append((st,))
+            cur = [cur[1], cur[0], cur[2]]
+        elif st == "transpose_inner":
+            plan.append((st,))
+            cur = [cur[0], cur[2], cur[1]]
+        elif st == "ew_bias":
+            plan.append((st, operand((cur[-1],), 0.3)))
+        elif st == "ew_full":
+            plan.append((st, operand(tuple(cur), 0.5)))
+        else:
+            plan.append((st,))
+    n_in = len(s.inputs)
+    # ChainSpec numbers operator results after the inputs that exist when op() is called, so all inputs are in place now
+    v = 0
+    for item in plan:
+        st = item[0]
+        names.append(st)
+        if st == "softmax":
+            v = s.op("softmax", v)
+        elif st == "layernorm":
+            v = s.op("layernorm", v, item[1], item[2], f=[2.0 ** -16])
+        elif st == "rmsnorm":
+            v = s.op("rmsnorm", v, item[1], f=[2.0 ** -16])
+        elif st == "swap_leading":
+            v = s.op("permute", v, i=[1, 0, 2])
+        elif st == "transpose_inner":
+            v = s.op("permute", v, i=[0, 2, 1])
+        elif st == "centre":
+            v = s.op("sub", v, s.op("reduce_mean", v))
+        elif st == "ew_silu":
+            v = s.op("silu", v)
+        elif st == "ew_tanh":
+            v = s.op("tanh", v)
+        elif st == "ew_scale":
+            v = s.op("scale", v, f=[0.5])
+        else:
+            v = s.op("add", v, item[1])
+    assert len(s.inputs) == n_in
+    s.out(v, dtype)
+    return s, tensors, f"seed {seed}: {dtype} {tuple(shape)} " + " > ".join(names)
