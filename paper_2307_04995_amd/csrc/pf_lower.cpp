@@ -187,10 +187,25 @@ struct Lowerer {
 
     int final_value = -1;
 
+    // A result computed from broadcast inputs alone (sigmoid of a per-row scale, say) is still smaller than the value
+    // the kernel walks over; its inputs are addressed against the first full-size value it flows into.
+    int partner_value(int id) const {
+        int v = id;
+        for (int hop = 0; hop < d->n_ops && numel(c->shape[v]) != region_numel; ++hop) {
+            int next = -1;
+            for (int k = v - d->n_inputs + 1; k < d->n_ops && next < 0; ++k)
+                for (int j = 0; j < d->ops[k].n_src; ++j)
+                    if (d->ops[k].src[j] == v) next = d->n_inputs + k;
+            if (next < 0) break;
+            v = next;
+        }
+        return v;
+    }
+
     bool lower_elementwise_op(int k) {
         const pf_op_desc& o = d->ops[k];
         const int id = d->n_inputs + k;
-        cur_result_shape = c->shape[id];
+        cur_result_shape = c->shape[partner_value(id)];
         const OpTraits& tr = kOps[o.op];
         if (tr.cls == OC_RESHAPE) return true;  // alias only
         if (tr.cls == OC_REDUCE) {

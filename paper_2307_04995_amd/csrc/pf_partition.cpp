@@ -186,11 +186,11 @@ pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out
     pf_status st = check_desc(d, &c);
     if (st != PF_OK) return st;
     std::vector<std::pair<int, int>> blocked;
+    blocked.push_back(std::make_pair(0, (int)d->n_ops));  // the caller has tried the whole chain as one kernel
     for (int attempt = 0; attempt < 64; ++attempt) {
         pf_partition part;
         st = partition_chain(d, c, blocked, &part);
         if (st != PF_OK) return st;
-        if (part.n_parts < 2) return fail(PF_ERR_UNSUPPORTED, "the chain is one kernel under the model but its planning failed");
         pf_plan_s* p = new (std::nothrow) pf_plan_s();
         if (!p) return fail(PF_ERR_NOMEM, "out of host memory");
         p->desc = *d;

@@ -97,3 +97,21 @@ def test_shapes_that_do_not_broadcast_are_refused():
     s = wl.ChainSpec(inputs=[("f32", (2, 3, 8, 8)), ("f32", (2, 2, 1, 8))])
     s.out(s.op("add", 0, 1), "f32")
     assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("small", [(6, 1), (1, 200), (200,), (1, 1)])
+def test_a_value_computed_from_broadcast_inputs_alone(small, dtype):
+    # x / (m + 1), x * sigmoid(g) * (a + b): the small operands are transformed before they meet the full-size value;
+    # they are addressed against that value, not against their own shape
+    shape = (6, 200)
+    x = wl.random_tensor(shape, dtype, 5601)
+    m = wl.random_tensor(small, dtype, 5602, dist="positive")
+    g = wl.random_tensor(small, dtype, 5603)
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, small)])
+    s.out(s.op("div", 0, s.op("addc", 1, f=[1.0])), dtype)
+    check_chain(s, [x, m], what=f"x / (m{small} + 1) {dtype}")
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, small), (dtype, small)])
+    v = s.op("mul", s.op("sigmoid", 2), s.op("add", 1, 2))
+    s.out(s.op("softmax", s.op("mul", 0, v)), dtype)
+    check_chain(s, [x, m, g], what=f"softmax(x * sigmoid(g) * (m + g)) {small} {dtype}")

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as wl
-from pf_testlib import gpu_run
+from pf_testlib import check_chain, env, gpu_run
 
 pytestmark = pytest.mark.gpu
 
@@ -91,8 +91,13 @@ def test_arithmetic_next_to_concat_is_refused():
     pf = _pf()
     s = wl.ChainSpec(inputs=[("f16", (4, 8)), ("f16", (4, 8))])
     s.out(s.op("relu", s.op("concat", 0, 1, i=[1])), "f16")
-    st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
-    assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    with env(PF_PARTITION="0"):  # not one kernel ...
+        st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
+        assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    # ... so it runs as two: the index-map copy, then the element-wise kernel
+    a, b = wl.random_tensor((4, 8), "f16", 4501), wl.random_tensor((4, 8), "f16", 4502)
+    _, info, _ = check_chain(s, [a, b], what="concat > relu")
+    assert info.n_kernels == 2
     s = wl.ChainSpec(inputs=[("f16", (4, 8)), ("f16", (4, 9))])
     s.out(s.op("concat", 0, 1, i=[0]), "f16")
     assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE

@@ -128,13 +128,20 @@ def test_in_line_reductions_need_rows_that_fit_a_workgroup():
     pf = _pf()
     s = wl.ChainSpec(inputs=[("f32", (2, 70000))])
     s.out(s.op("div", 0, s.op("addc", s.op("reduce_max", 0), f=[1.0])), "f32")
-    st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
-    assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    with env(PF_PARTITION="0"):
+        st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
+        assert st == pf.PF_ERR_UNSUPPORTED and h is None
+    # as two kernels it runs: the reduction alone has a streaming variant, the division reads one value per row
+    _, info, _ = check_chain(s, [wl.random_tensor((2, 70000), "f32", 1060, scale=2.0)], what="long rows, reduction and use in two kernels")
+    assert info.n_kernels == 2
     # a softmax spelled in basic operators is planned as the operator, whose streaming variant has no such limit
-    with env(PF_RECOMPOSE="0"):
+    with env(PF_RECOMPOSE="0", PF_PARTITION="0"):
         st, h = pf.pf_chain_plan(pf.make_desc(_softmax_chain("f32", (2, 70000))), 0)
         assert st == pf.PF_ERR_UNSUPPORTED and h is None
     x = wl.random_tensor((2, 70000), "f32", 1061, scale=2.0)
+    with env(PF_RECOMPOSE="0"):  # without the rewrite: one kernel per reduction, each streaming over the row
+        _, info, _ = check_chain(_softmax_chain("f32", (2, 70000)), [x], what="long softmax in basic operators, several kernels")
+        assert info.n_kernels >= 2
     _, info, _ = check_chain(_softmax_chain("f32", (2, 70000)), [x], what="long softmax in basic operators")
     assert info.variant == pf.PF_VARIANT_ROW_STREAM
 
