@@ -27,6 +27,22 @@ def test_random_chains_match_the_oracle(block):
 
 
 @pytest.mark.parametrize("block", range(6))
+def test_random_chains_with_transformed_broadcast_operands(block):
+    # the same chains, with about half of the broadcast operands passed through an operator of their own first
+    from paper_2307_04995_amd import binding as pf
+    ran = 0
+    for seed in range(block * 12, block * 12 + 12):
+        spec, ins, desc = wl.random_chain(seed, transform_operands=True)
+        try:
+            check_chain(spec, ins, what=desc + " (operands transformed)")
+            ran += 1
+        except pf.PfError as e:
+            assert e.status in (pf.PF_ERR_UNSUPPORTED, pf.PF_ERR_ALIGNMENT), f"{desc}: {e}"
+            print(f"refused ({pf.pf_status_str(e.status)}): {desc}: {e}")
+    assert ran >= 8
+
+
+@pytest.mark.parametrize("block", range(6))
 def test_random_groupnorm_chains_match_the_oracle(block):
     # groups of any width, small and large tiles, one or several workgroups per sample; both variants
     from paper_2307_04995_amd import binding as pf

@@ -308,11 +308,14 @@ def random_tensor(shape, dtype: str, seed: int, dist: str = "normal", scale: flo
 # which shapes); values stay O(1) so that the absolute fp32 bar is meaningful.
 # ---------------------------------------------------------------------------------------------
 
-def random_chain(seed: int):
+def random_chain(seed: int, transform_operands: bool = False):
     """A random chain of the canonical form `element-wise* -> [core] -> element-wise*` with random shapes,
     operand kinds (full shape, trailing broadcast, broadcast with extents of 1, scalar) and dtypes.
+    With transform_operands, about half of the broadcast operands go through an operator of their own (sigmoid,
+    addc, scale) before they meet the running value; the chain is otherwise the same as without.
     Returns (ChainSpec, inputs, description)."""
     g = np.random.default_rng(BASE_SEED * 13 + seed)
+    g2 = np.random.default_rng(BASE_SEED * 43 + seed)  # decisions of transform_operands only: the other draws stay as they are
     dtype = str(g.choice(["f16", "bf16", "f32"]))
     inner = int(g.choice([8, 24, 64, 96, 197, 200, 512, 1000, 2048]))
     rank = int(g.integers(2, 5))
@@ -357,7 +360,11 @@ def random_chain(seed: int):
             if name in ("add", "sub", "mul", "max", "min"):
                 # (a clamp against one value per row or per tensor can make whole rows constant, where a
                 # normalisation amplifies fp32 rounding of the mean by 1 / sqrt(eps): not what is tested here)
+                n_before = len(inputs)
                 o = operand_for(cur_shape) if name not in ("max", "min") else operand_for(cur_shape, ("full", "trailing", "ones"))
+                if transform_operands and len(inputs) > n_before and inputs[-1][1] != tuple(cur_shape) and g2.random() < 0.5:
+                    how = str(g2.choice(["sigmoid", "addc", "scale"]))
+                    o = emit(how, o, f=[0.5] if how != "sigmoid" else ())
                 v = emit(name, v, o) if g.random() < 0.7 else emit(name, o, v)
                 if name == "mul":
                     v = emit("tanh", v)          # keeps magnitudes bounded
