@@ -224,8 +224,10 @@ PF_DEVICE void transpose_block(const u32x4 (&in)[Storage<DT>::VEC], u32x4 (&out)
 
 // RAGGED: the two transposed extents need not be whole vectors: a lane's block is ni x no elements (0 .. VEC
 // each), rows and columns beyond that are neither loaded nor stored, and every access is element-aligned.
+// (Left to itself the compiler interleaves the eight rows' conversions of a specialised fp16 chain and ends up at 234
+// registers, two waves per SIMD and 2.9 TB/s; held to four waves per SIMD it needs 93 and no scratch.)
 template <int DT, class Spec, bool RAGGED = false>
-__global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const PermGeom g) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Spec::kStatic ? 4 : 2))) perm_tile_kernel(const ChainArgs a, const PermGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     constexpr uint32_t TE = 8u * VEC;  // tile edge in elements
@@ -244,7 +246,11 @@ __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const
 
     LaneState<DT, 1, Spec> s;
     u32x4 blk[VEC], outv[VEC];
-    const bool pro_trivial = a.pro.n == 1;  // nothing but the load
+    // nothing but the load / nothing after the transposition: known when the kernel is compiled for a static chain
+    using ProL = typename Spec::Pro;
+    using EpiL = typename Spec::Epi;
+    const bool pro_trivial = ProL::kDynamic ? a.pro.n == 1 : ProL::n == 1;
+    const bool has_epi = EpiL::kDynamic ? a.epi.n != 0 : EpiL::n != 0;
     uint32_t in_off[VEC];
 #pragma unroll
     for (int r = 0; r < VEC; ++r) {
@@ -273,7 +279,7 @@ __global__ void __launch_bounds__(256) perm_tile_kernel(const ChainArgs a, const
     for (int c = 0; c < VEC; ++c) {
         const uint32_t out_off = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
         const bool row_ok = valid && (!RAGGED || (uint32_t)c < ni);
-        if (a.epi.n != 0) {
+        if (has_epi) {
             const uint32_t zero = 0u;
             perm_load_operands<DT, 1, Spec, 2, RAGGED>(a, g, s, &zero, &out_off, &row_ok, &no);
             S::unpack(outv[c], s.acc);
