@@ -19,7 +19,7 @@ namespace {
 // Performance model.  Launch cost and streaming rate are those of a plain copy kernel on this device
 // (2.8 us + bytes / 6.7 TB/s); the family factors are the fractions of that rate the families' kernels reach on
 // tensors of 75 to 170 MB (measured: element-wise 1.0, row normalisations 0.76 - 0.80, permutations that keep the
-// innermost dimension 0.87, those that change it 0.37, group normalisation 0.65, pooling 0.6).
+// innermost dimension 0.87, those that change it 0.7 - 0.8, group normalisation 0.65, pooling 0.6).
 constexpr double kLaunchUs = 2.8;
 constexpr double kCopyBytesPerUs = 6.7e6;
 
@@ -28,7 +28,7 @@ double family_factor(const Lowered& low) {
         case pf::CORE_NONE: return 0.97;
         case pf::CORE_PERMUTE: {
             const int rank = (int)low.pre_shape.size();
-            return rank > 0 && low.perm[rank - 1] != rank - 1 ? 0.37 : 0.85;
+            return rank > 0 && low.perm[rank - 1] != rank - 1 ? 0.72 : 0.85;
         }
         case pf::CORE_GATHER: return 0.80;
         case pf::CORE_GROUPNORM: return 0.65;
