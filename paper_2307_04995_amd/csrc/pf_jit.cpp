@@ -119,6 +119,15 @@ hipFunction_t compile(int device, const std::string& source, const std::string& 
     if (hipModuleLoadData(&mod, code.data()) != hipSuccess) return fail("hipModuleLoadData failed");
     if (hipModuleGetFunction(&fn, mod, symbol.c_str()) != hipSuccess) return fail("hipModuleGetFunction failed");
     ++g_compiles;
+    {
+        const char* lg = getenv("PF_LOG");
+        if (lg && atoi(lg) != 0) {  // registers and scratch of the new kernel: what decides how many waves a SIMD holds
+            int regs = 0, scratch = 0;
+            (void)hipFuncGetAttribute(&regs, HIP_FUNC_ATTRIBUTE_NUM_REGS, fn);
+            (void)hipFuncGetAttribute(&scratch, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, fn);
+            fprintf(stderr, "[pf_jit] %s: %d registers, %d bytes of scratch per lane\n", name_expr.c_str(), regs, scratch);
+        }
+    }
     g_cache[key] = fn;  // the module stays loaded until the process ends
     return fn;
 }
