@@ -419,7 +419,31 @@ pf_status lower_attention(const pf_chain_desc* d, const Checked& c, Lowered* L) 
     return PF_OK;
 }
 
-pf_status lower_chain(const pf_chain_desc* d, const Checked& c, Lowered* L) {
+pf_status lower_chain(const pf_chain_desc* d_in, const Checked& c, Lowered* L) {
+    // A permutation that only moves extents of 1 leaves the order of the elements alone: it is a reshape (free),
+    // not a layout change that needs a kernel of the transpose family.
+    pf_chain_desc local = *d_in;
+    for (int k = 0; k < local.n_ops; ++k) {
+        pf_op_desc& o = local.ops[k];
+        if (kOps[o.op].cls != OC_PERMUTE) continue;
+        const Shape& in = c.shape[o.src[0]];
+        const Shape& out = c.shape[local.n_inputs + k];
+        int64_t last = -1;
+        bool keeps_order = true;
+        for (int q = 0; q < o.n_i; ++q) {
+            if (in[o.i[q]] == 1) continue;
+            keeps_order &= o.i[q] > last;
+            last = o.i[q];
+        }
+        if (!keeps_order) continue;
+        o.op = PF_RESHAPE;
+        o.n_i = (int32_t)out.size();
+        for (size_t q = 0; q < out.size(); ++q) o.i[q] = out[q];
+    }
+    // (a chain of nothing else stays a copy: a caller who asks for a permuted tensor gets one)
+    bool computes = false;
+    for (int k = 0; k < local.n_ops; ++k) computes |= kOps[local.ops[k].op].cls != OC_RESHAPE;
+    const pf_chain_desc* d = computes ? &local : d_in;
     const int n_in = d->n_inputs, n_val = d->n_inputs + d->n_ops;
     for (int k = 0; k < d->n_ops; ++k) {
         const OpClass cls = kOps[d->ops[k].op].cls;

@@ -159,3 +159,21 @@ def test_ragged_transpose_fused_with_elementwise(dtype):
     s = wl.ChainSpec(inputs=[(dtype, (4, 6, 197)), (dtype, (197,))])
     s.out(s.op("permute", s.op("add", 0, 1), i=[1, 0, 2]), dtype)
     check_chain(s, [x, bias], what=f"ragged rows moved with a bias {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((17, 1, 256), (0, 2, 1)), ((1, 5, 40), (1, 2, 0)), ((3, 1, 1, 24), (1, 0, 2, 3)), ((6, 1, 33), (1, 0, 2))])
+def test_a_permutation_that_only_moves_extents_of_1_is_a_reshape(shape, perm, dtype):
+    # the order of the elements does not change: no transpose kernel, element-wise work on both sides in one launch
+    from paper_2307_04995_amd import binding as pf
+    out_shape = tuple(shape[p] for p in perm)
+    keeps = [p for p in perm if shape[p] != 1]
+    if keeps != sorted(keeps):
+        pytest.skip("moves data")
+    x = wl.random_tensor(shape, dtype, 6101)
+    b = wl.random_tensor((shape[-1],), dtype, 6102, scale=0.3)
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, (shape[-1],))])
+    v = s.op("permute", s.op("silu", s.op("add", 0, 1)), i=list(perm))
+    s.out(s.op("scale", v, f=[0.5]), dtype)
+    outs, info, _ = check_chain(s, [x, b], what=f"{shape} perm {perm} {dtype}")
+    assert info.family == pf.PF_FAMILY_ELEMENTWISE and tuple(outs[0].shape) == out_shape
