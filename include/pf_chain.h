@@ -263,6 +263,13 @@ pf_status pf_chain_plan_variant(const pf_chain_desc *desc, int32_t device, int32
 pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
 
 /*
+ * The split a plan runs with: one part for a chain that is one kernel, else the cut points pf_chain_plan settled
+ * on (those of pf_chain_partition unless the device-side planning refused one of its segments and the search ran
+ * again without it).  predicted_us and bytes are the model's figures for the parts.
+ */
+pf_status pf_chain_plan_get_partition(const pf_plan *plan, pf_partition *out);
+
+/*
  * Enqueue the fused kernel on `stream` (a hipStream_t, passed as void*; NULL = the default stream) and
  * return without waiting.  inputs[k] / outputs[k] are device pointers to contiguous tensors of exactly
  * the shapes and dtypes of the description, 16-byte aligned, owned by the caller and not retained.

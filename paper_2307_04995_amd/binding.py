@@ -72,7 +72,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libp
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
            "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose",
-           "pf_chain_partition", "pf_chain_segment_cost"]
+           "pf_chain_partition", "pf_chain_segment_cost", "pf_chain_plan_get_partition"]
 
 
 def _load() -> C.CDLL:
@@ -98,6 +98,7 @@ def _load() -> C.CDLL:
     lib.pf_copy_probe.argtypes = [vp, vp, C.c_uint64, C.c_int32, vp]
     lib.pf_chain_recompose.argtypes = [C.POINTER(pf_chain_desc), C.POINTER(pf_chain_desc), C.POINTER(C.c_int32)]
     lib.pf_chain_partition.argtypes = [C.POINTER(pf_chain_desc), C.POINTER(pf_partition)]
+    lib.pf_chain_plan_get_partition.argtypes = [vp, C.POINTER(pf_partition)]
     lib.pf_chain_segment_cost.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     lib.pf_jit_compile_count.argtypes = []
     lib.pf_jit_compile_count.restype = C.c_uint64
@@ -275,6 +276,14 @@ class Plan:
 
     def info(self) -> pf_plan_info:
         return pf_chain_plan_get_info(self.handle)
+
+    def partition(self):
+        """[(first_op, last_op, predicted_us, bytes), ...] of the kernels this plan runs."""
+        out = pf_partition()
+        st = _lib.pf_chain_plan_get_partition(self.handle, C.byref(out))
+        if st != PF_OK:
+            raise PfError(st, pf_last_error())
+        return [(out.first_op[k], out.first_op[k + 1], out.predicted_us[k], out.bytes[k]) for k in range(out.n_parts)]
 
     def output_shapes(self) -> List[tuple]:
         shapes = []

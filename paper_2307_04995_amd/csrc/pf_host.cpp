@@ -108,6 +108,22 @@ pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
     return PF_OK;
 }
 
+pf_status pf_chain_plan_get_partition(const pf_plan* plan, pf_partition* out) {
+    if (!plan || !out) return fail(PF_ERR_INVALID_ARG, "null argument");
+    if (plan->composite) {
+        *out = plan->partition;
+        return PF_OK;
+    }
+    memset(out, 0, sizeof(*out));
+    out->n_parts = 1;
+    out->first_op[0] = 0;
+    out->first_op[1] = plan->desc.n_ops;
+    double us = 0.0;
+    uint64_t bytes = 0;
+    if (segment_cost(&plan->desc, 0, plan->desc.n_ops, &us, &bytes) == PF_OK) out->predicted_us[0] = us, out->bytes[0] = bytes;
+    return PF_OK;
+}
+
 pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* const* outputs, void* stream) {
     if (!plan || !inputs || !outputs) return fail(PF_ERR_INVALID_ARG, "null argument");
     const pf_chain_desc& d = plan->desc;

@@ -149,6 +149,7 @@ struct pf_plan_s {
     };
     bool composite = false;
     std::vector<Part> parts;
+    pf_partition partition;               // the cut points in use (composite plans)
     void* arena = nullptr;                // tensors that cross from one kernel to the next
     uint64_t arena_bytes = 0;
     std::vector<uint64_t> arena_offset;

@@ -253,6 +253,7 @@ pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out
             }
             p->arena_bytes = arena_bytes;
             p->arena_offset = arena_offset;
+            p->partition = part;
             p->family = p->parts[0].plan->family;
             p->variant = p->parts[0].plan->variant;
             p->grid = p->parts[0].plan->grid;

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import workloads as wl
-from pf_testlib import TORCH_DT, compare, env, gpu_run, oracle_run
+from pf_testlib import check_chain, env, oracle_with_storage, compare
 
 pytestmark = pytest.mark.gpu
 
@@ -17,81 +17,10 @@ def _pf():
     return pf
 
 
-def _crossing_values(spec, parts):
-    """Value ids produced in one part and used in a later one."""
-    n_in = len(spec.inputs)
-    part_of = {}
-    for k, (a, b, _, _) in enumerate(parts):
-        for op in range(a, b):
-            part_of[n_in + op] = k
-    crossing = set()
-    for k, op in enumerate(spec.ops):
-        for v in op.src:
-            if v >= n_in and part_of[v] != part_of[n_in + k]:
-                crossing.add(v)
-    return crossing
-
-
-def _round_to(dtype, nudge_seed=None):
-    """Rounding of a float64 array to the storage type; with a seed, every value is then moved one unit in the last
-    place up or down at random (what a stored tensor may differ by when it was computed in fp32 instead of fp64)."""
-    if dtype == "f32":
-        return lambda a: a.astype(np.float32)
-
-    def rnd(a):
-        t = torch.from_numpy(np.ascontiguousarray(a)).to(TORCH_DT[dtype])
-        if nudge_seed is not None:
-            g = np.random.default_rng(nudge_seed + a.size)
-            step = torch.from_numpy(g.choice(np.array([-1, 1], dtype=np.int16), size=a.shape))
-            bits = t.view(torch.int16)
-            ok = torch.isfinite(t) & ((bits & 0x7fff) > 1)
-            t = torch.where(ok, bits + step, bits).view(TORCH_DT[dtype])
-        return t.to(torch.float64).numpy()
-    return rnd
-
-
-def _oracle_with_storage(spec, inputs, dtype, nudge_seed=None):
-    from oracle import pf_oracle as orc
-    pf = _pf()
-    st, parts = pf.pf_chain_partition(pf.make_desc(spec))
-    assert st == pf.PF_OK
-    rnd = _round_to(dtype, nudge_seed)
-    stored = {v: rnd for v in _crossing_values(spec, parts)}
-    return orc.evaluate_outputs(spec, [wl.widen(t) for t in inputs], stored), parts
-
-
-def _compare_16bit(got, want, nudged, dtype, what):
-    """The 16-bit bars.  A tensor stored between two kernels may differ by one unit in the last place from the
-    oracle's (fp32 against fp64 arithmetic before the rounding); where later operators amplify that (differences of
-    nearly equal values), no implementation can meet the relative bar.  Such elements are recognised by the oracle
-    itself: its result with every stored value moved one unit up or down at random.  An element passes with a
-    relative error within the bar, or an error within twice what that perturbation does to it; the absolute bar
-    holds everywhere, and the plain relative bar on at least 95 % of the elements."""
-    from pf_testlib import H_ABS, H_REL, REL_FLOOR
-    g = wl.widen(got)
-    assert g.shape == want.shape and np.all(np.isfinite(want)) and np.all(np.isfinite(g)), what
-    diff = np.abs(g - want)
-    assert diff.max() <= H_ABS, f"{what}: max-abs {diff.max():.3e} > {H_ABS}"
-    big = np.abs(want) >= REL_FLOOR
-    within = diff <= H_REL * np.abs(want)
-    explained = diff <= 2.0 * np.abs(nudged - want)
-    bad = big & ~within & ~explained
-    assert not bad.any(), f"{what}: {bad.sum()} elements beyond the relative bar that stored rounding does not explain (worst {(diff[bad] / np.abs(want[bad])).max():.3e})"
-    assert (big & within).sum() >= 0.95 * big.sum(), f"{what}: only {(big & within).sum()} of {big.sum()} elements within the relative bar"
-
-
 def _check(spec, inputs, dtype, what):
-    outs, info = gpu_run(spec, inputs)
-    wants, parts = _oracle_with_storage(spec, inputs, dtype)
-    assert info.n_kernels == len(parts) and info.n_launches >= info.n_kernels, what
-    if dtype == "f32":  # fp32 storage: also within the bar of the chain evaluated without any rounding
-        for o, w, u in zip(outs, wants, oracle_run(spec, inputs)):
-            compare(o, w, "f32", what)
-            compare(o, u, "f32", what + " (unrounded)")
-    else:
-        nudged, _ = _oracle_with_storage(spec, inputs, dtype, nudge_seed=977)
-        for o, w, nd in zip(outs, wants, nudged):
-            _compare_16bit(o, w, nd, dtype, what)
+    outs, info, _ = check_chain(spec, inputs, what=what)  # several kernels: the storage-aware comparison
+    assert info.n_kernels == len(info.parts) >= 1 and info.n_launches >= info.n_kernels, what  # (two row statistics alone are one row program)
+    assert info.parts[0][0] == 0 and info.parts[-1][1] == len(spec.ops), what
     return outs, info
 
 
@@ -186,7 +115,7 @@ def test_plan_properties_repeated_runs_and_refusals():
         xd = x.cuda()
         plan.run_ptrs([xd.data_ptr(), gam.data_ptr(), bet.data_ptr()], [out.data_ptr()], stream)
         torch.cuda.synchronize()
-        wants, _ = _oracle_with_storage(s, [x, gam.cpu(), bet.cpu()], "f16")
+        wants = oracle_with_storage(s, [x, gam.cpu(), bet.cpu()], "f16")
         compare(out.cpu(), wants[0], "f16", f"run {rep}")
     # in place is refused: the first kernel's output would be read by the second while the input is gone
     with pytest.raises(pf.PfError) as e:

@@ -670,7 +670,7 @@ def random_pool_chain(seed: int):
 def random_multi_kernel_chain(seed: int):
     """A random chain with two to four exchanges wider than a lane (softmax, layer / RMS normalisation, a reduction
     over the last dimension used as a row statistic, a permutation of the leading dimensions, a transposition of the
-    last two) and random element-wise steps between them: more than one kernel by construction."""
+    last two) and random element-wise steps between them: more than one kernel in nearly every case."""
     g = np.random.default_rng(BASE_SEED * 41 + seed)
     dtype = str(g.choice(["f16", "bf16", "f32"]))
     shape = [int(g.integers(2, 6)), int(g.choice([3, 8, 17, 32])), int(g.choice([16, 24, 40, 64, 128, 200, 256]))]  # (no extents of 1: a permutation that makes one innermost is refused)
