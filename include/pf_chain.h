@@ -151,6 +151,9 @@ typedef enum {
                                   of contiguous runs computed when the plan is made                          */
     PF_FAMILY_POOL = 7,        /* reduction over the positions of a channels-last tensor (global pooling): partial
                                   results per workgroup, merged by the last workgroup of a sample to arrive      */
+    PF_FAMILY_COLUMN = 8,      /* layer / RMS normalisation over a dimension that is not the innermost (move it to the
+                                  end, normalise, move it back: the two layout changes cancel): a workgroup keeps a slab
+                                  [c, 64 positions] in registers, statistics cross lanes and waves, nothing is transposed */
     PF_FAMILY_ATTENTION = 4    /* one-token attention: a head's rows span workgroups, partial results are
                                   merged by the last workgroup to arrive                                     */
 } pf_family;

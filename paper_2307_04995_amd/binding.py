@@ -29,7 +29,7 @@ OP_CODE = {name: i for i, name in enumerate([
     "tanh", "exp", "rsqrt", "causal_mask", "reduce_sum", "reduce_max", "reduce_mean", "softmax", "layernorm",
     "rmsnorm", "groupnorm", "permute", "reshape", "concat_rows", "matvec", "vecmat", "concat", "slice", "dwconv2d"])}
 # pf_family
-PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE, PF_FAMILY_ATTENTION, PF_FAMILY_GATHER, PF_FAMILY_STENCIL, PF_FAMILY_POOL = range(8)
+PF_FAMILY_ELEMENTWISE, PF_FAMILY_ROW, PF_FAMILY_GROUP, PF_FAMILY_TRANSPOSE, PF_FAMILY_ATTENTION, PF_FAMILY_GATHER, PF_FAMILY_STENCIL, PF_FAMILY_POOL, PF_FAMILY_COLUMN = range(9)
 PF_VARIANT_ROW_WAVE, PF_VARIANT_ROW_BLOCK, PF_VARIANT_ROW_STREAM = 0, 1, 2
 PF_SPEC_GENERIC, PF_SPEC_JIT = 0, 255
 PF_VARIANT_STENCIL_DIRECT, PF_VARIANT_STENCIL_STAGED, PF_VARIANT_STENCIL_STRIDED = 0, 1, 2

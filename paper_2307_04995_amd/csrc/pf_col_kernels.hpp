@@ -1,0 +1,138 @@
+// Column family: layer / RMS normalisation over a dimension that is NOT the innermost one.
+//
+// A channels-first tensor [outer, C, S] (S = everything after the normalised dimension, contiguous) normalised
+// over C is usually written as: move C to the end, normalise rows, move it back -- three kernels and three times
+// the bytes when each step is a kernel of its own.  The paper's rewriting (section 5: operators swapped across
+// data movement until reads and writes of the same slice merge) removes both layout changes: the reduction runs
+// over a strided dimension instead.  Here a workgroup owns a slab [C, 8 vectors of S]: lane (row group rg = tid / 8,
+// column col = tid % 8) loads the 16-byte vectors of rows rg, rg + 32, ... at column col -- every load instruction
+// of a wave reads 8 rows x 128 contiguous bytes, like the tile transposition -- and keeps them in registers (KC
+// vectors per lane, so C <= 32 * KC).  The statistics of one position are spread over the 32 row groups: three
+// lane exchanges inside a wave (lanes 8, 16, 32 apart hold the same column), then one LDS exchange between the
+// four waves.  Mean first (as differences from a pivot row), then centred squares: no cancellation; RMS needs one
+// exchange.  Every input
+// element is read once and every output element written once; nothing is transposed.
+#pragma once
+#include "pf_device.hpp"
+
+namespace pf {
+
+template <int VEC>
+PF_DEVICE void col_all_reduce(float (&v)[VEC], float* lds, uint32_t wave, uint32_t col, uint32_t lane) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        v[j] += __shfl_xor(v[j], 8, 64);
+        v[j] += __shfl_xor(v[j], 16, 64);
+        v[j] += __shfl_xor(v[j], 32, 64);
+    }
+    __syncthreads();  // the previous exchange's readers are done
+    if (lane < 8u) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) lds[(wave * 8u + col) * VEC + j] = v[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < VEC; ++j)
+        v[j] = (lds[(0u * 8u + col) * VEC + j] + lds[(1u * 8u + col) * VEC + j]) + (lds[(2u * 8u + col) * VEC + j] + lds[(3u * 8u + col) * VEC + j]);
+}
+
+// The slab stays in registers in its storage form between the passes: the compiler may not keep the unpacked values
+// of one pass alive for the next.
+template <int KC>
+PF_DEVICE void keep_packed(u32x4 (&raw)[KC]) {
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t w = raw[k][i];
+            asm volatile("" : "+v"(w));
+            raw[k][i] = w;
+        }
+}
+
+template <int DT, int KC, bool RMS>
+__global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    __shared__ float lds[4 * 8 * VEC];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, col = tid & 7u, rg = tid >> 3;
+    const uint32_t o = blockIdx.x / a.tiles_per_outer, t = blockIdx.x - o * a.tiles_per_outer;
+    const uint32_t sv = t * 8u + col;
+    const bool col_ok = sv < a.s_vecs;
+    const uint64_t base = ((uint64_t)o * a.c) * a.s + (uint64_t)sv * VEC;  // element offset of row 0 at this column
+
+    u32x4 raw[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const uint32_t c = rg + 32u * (uint32_t)k;
+        raw[k] = u32x4{0u, 0u, 0u, 0u};
+        if (col_ok && c < a.c) raw[k] = load_stream(a.x, (base + (uint64_t)c * a.s) * S::ESIZE);
+    }
+    // mean = piv + mean[]: kept as a pivot (row 0 of the same position) plus the mean of the differences from it, so
+    // that a large common offset of the values eats the digits neither of the sum nor of x - mean
+    float piv[VEC], mean[VEC], acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) piv[j] = 0.0f, mean[j] = 0.0f, acc[j] = 0.0f;
+    if (!RMS) {
+        if (rg == 0u) {
+            S::unpack(raw[0], piv);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) lds[col * VEC + j] = piv[j];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) piv[j] = lds[col * VEC + j];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            if (rg + 32u * (uint32_t)k < a.c) {
+                float x[VEC];
+                S::unpack(raw[k], x);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) mean[j] += x[j] - piv[j];
+            }
+        }
+        col_all_reduce<VEC>(mean, lds, wave, col, lane);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mean[j] *= a.inv_c;
+        keep_packed<KC>(raw);
+    }
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const uint32_t c = rg + 32u * (uint32_t)k;
+        if (c < a.c) {
+            float x[VEC];
+            S::unpack(raw[k], x);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float d = (x[j] - piv[j]) - mean[j];
+                acc[j] = fmaf(d, d, acc[j]);
+            }
+        }
+    }
+    col_all_reduce<VEC>(acc, lds, wave, col, lane);
+    keep_packed<KC>(raw);
+    float rstd[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) rstd[j] = pf_rsqrt<S::PRECISE>(fmaf(acc[j], a.inv_c, a.eps));
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const uint32_t c = rg + 32u * (uint32_t)k;
+        if (!(col_ok && c < a.c)) continue;
+        float x[VEC], gam, bet = 0.0f;
+        {
+            float tmp[VEC];  // one element of the parameter vectors: the same for the whole row
+            S::unpack(S::splat(static_cast<const char*>(a.gamma) + (uint64_t)c * S::ESIZE), tmp);
+            gam = tmp[0];
+            if (a.beta) {
+                S::unpack(S::splat(static_cast<const char*>(a.beta) + (uint64_t)c * S::ESIZE), tmp);
+                bet = tmp[0];
+            }
+        }
+        S::unpack(raw[k], x);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) x[j] = fmaf(((x[j] - piv[j]) - mean[j]) * rstd[j], gam, bet);
+        store_stream(a.out, (base + (uint64_t)c * a.s) * S::ESIZE, S::pack(x));
+    }
+}
+
+}  // namespace pf

@@ -111,6 +111,7 @@ enum CoreKind : int32_t {
     CORE_REDUCE_MEAN = 6,
     CORE_GROUPNORM = 7,
     CORE_PERMUTE = 8,
+    CORE_COLNORM = 14,      // layer / RMS normalisation over a dimension that is not the innermost (column family)
     CORE_POOL = 13,         // reduction over the positions of a channels-last tensor (pool family)
     CORE_DWCONV = 12,       // depthwise convolution (stencil family); core_vec[0] = slot of the kernels
     CORE_GATHER = 11,       // layout-only chain with concatenations / slices
@@ -185,6 +186,18 @@ struct PoolGeom {
     uint32_t spin_limit;         // polling rounds before a wait gives up
     uint32_t pad;
     FastDiv div_cv;
+};
+
+// Column family: normalisation of [outer, c, s] over c (s contiguous); all tensors of one storage type.
+struct ColArgs {
+    const void* x;
+    void* out;
+    const void* gamma;        // [c]
+    const void* beta;         // [c], or null (RMS normalisation)
+    uint32_t c, s;            // normalised extent; elements after it
+    uint32_t s_vecs;          // s in 16-byte vectors
+    uint32_t tiles_per_outer; // workgroups per outer index: ceil(s_vecs / 8)
+    float inv_c, eps;
 };
 
 // Attention family (one new token against cached keys and values); all tensors of one storage type.

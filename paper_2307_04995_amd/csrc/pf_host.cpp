@@ -184,6 +184,16 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
         if (ea != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ea));
         return PF_OK;
     }
+    if (plan->family == PF_FAMILY_COLUMN) {
+        pf::ColArgs ca = plan->col;
+        ca.x = inputs[L.col_in[0]];
+        ca.gamma = inputs[L.col_in[1]];
+        ca.beta = L.col_in[2] >= 0 ? inputs[L.col_in[2]] : nullptr;
+        ca.out = outputs[0];
+        const hipError_t ec = pf::launch_colnorm(L.main_dtype, ca, plan->k, L.col_in[2] < 0, plan->grid, (hipStream_t)stream);
+        if (ec != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ec));
+        return PF_OK;
+    }
     if (plan->family == PF_FAMILY_GATHER) {
         pf::GatherArgs ga = plan->gather;
         for (int k = 0; k < plan->desc.n_inputs; ++k) ga.in[k] = inputs[k];

@@ -93,6 +93,9 @@ struct Lowered {
     int attn_in[5] = {-1, -1, -1, -1, -1};
     int attn_out[3] = {-1, -1, -1};
     float attn_scale = 1.0f;
+    // column family: chain input index of x, gamma, beta (-1: RMS normalisation); [outer, c, s] view of x
+    int col_in[3] = {-1, -1, -1};
+    int64_t col_outer = 0, col_c = 0, col_s = 0;
 };
 
 // Lowers a checked chain: prologue and epilogue micro-programs around at most one core, operand slots, output slots.
@@ -122,6 +125,7 @@ struct pf_plan_s {
     pf::GatherArgs gather;
     pf::StencilGeom stencil;
     pf::PoolGeom pool;
+    pf::ColArgs col;
     int stencil_ks = 3;       // kernel extent of the depthwise convolution
     int row_log2l = 6;        // row family: log2 of the lanes of a wave that share a row
     pf::BcastTerm bcast_host[PF_DEV_MAX_VEC][PF_DEV_MAX_BCAST_TERMS];  // general broadcasting terms, staged on the host

@@ -419,6 +419,49 @@ pf_status lower_attention(const pf_chain_desc* d, const Checked& c, Lowered* L) 
     return PF_OK;
 }
 
+// Column family: move a dimension to the end, layer / RMS normalisation, move it back -- exactly these three
+// operators on chain inputs, one output.  Swapping the normalisation across the two layout changes (section 5,
+// operator swapping) leaves a normalisation over a strided dimension and no layout change at all.
+static bool lower_column_norm(const pf_chain_desc* d, const Checked& c, Lowered* L) {
+    if (d->n_ops != 3 || d->n_outputs != 1) return false;
+    const int n_in = d->n_inputs;
+    const pf_op_desc &p1 = d->ops[0], &nm = d->ops[1], &p2 = d->ops[2];
+    if (kOps[p1.op].cls != OC_PERMUTE || kOps[p2.op].cls != OC_PERMUTE) return false;
+    if (nm.op != PF_LAYERNORM && nm.op != PF_RMSNORM) return false;
+    if (p1.src[0] >= n_in || nm.src[0] != n_in || p2.src[0] != n_in + 1 || d->out_value[0] != n_in + 2) return false;
+    const Shape& in = c.shape[p1.src[0]];
+    const int rank = (int)in.size();
+    if (rank < 2 || p1.n_i != rank || p2.n_i != rank) return false;
+    const int axis = (int)p1.i[rank - 1];
+    if (axis >= rank - 1) return false;
+    for (int q = 0; q < rank - 1; ++q)
+        if (p1.i[q] != (q < axis ? q : q + 1)) return false;  // every other dimension keeps its place in the order
+    for (int q = 0; q < rank; ++q)
+        if (p1.i[p2.i[q]] != q) return false;  // the second permutation undoes the first
+    const int gamma = nm.src[1], beta = nm.op == PF_LAYERNORM ? nm.src[2] : -1;
+    if (gamma >= n_in || beta >= n_in) return false;
+    const int dt = d->out_dtype[0];
+    if (d->inputs[p1.src[0]].dtype != dt || d->inputs[gamma].dtype != dt || (beta >= 0 && d->inputs[beta].dtype != dt)) return false;
+    if (c.shape[gamma].size() != 1 || c.shape[gamma][0] != in[axis]) return false;
+    if (beta >= 0 && (c.shape[beta].size() != 1 || c.shape[beta][0] != in[axis])) return false;
+    if (!std::isfinite(nm.f[0]) || nm.f[0] < 0.0f) return false;
+    *L = Lowered();
+    L->main_dtype = dt;
+    L->core = pf::CORE_COLNORM;
+    L->core_op = 1;
+    L->eps = nm.f[0];
+    L->col_in[0] = p1.src[0], L->col_in[1] = gamma, L->col_in[2] = beta;
+    L->col_outer = 1, L->col_s = 1;
+    for (int q = 0; q < axis; ++q) L->col_outer *= in[q];
+    for (int q = axis + 1; q < rank; ++q) L->col_s *= in[q];
+    L->col_c = in[axis];
+    L->pre_shape = in;
+    L->post_shape = in;
+    L->n_out = 1;
+    L->out_slot_to_user[0] = 0;
+    return true;
+}
+
 pf_status lower_chain(const pf_chain_desc* d_in, const Checked& c, Lowered* L) {
     // A permutation that only moves extents of 1 leaves the order of the elements alone: it is a reshape (free),
     // not a layout change that needs a kernel of the transpose family.
@@ -445,6 +488,7 @@ pf_status lower_chain(const pf_chain_desc* d_in, const Checked& c, Lowered* L) {
     for (int k = 0; k < local.n_ops; ++k) computes |= kOps[local.ops[k].op].cls != OC_RESHAPE;
     const pf_chain_desc* d = computes ? &local : d_in;
     const int n_in = d->n_inputs, n_val = d->n_inputs + d->n_ops;
+    if (lower_column_norm(d, c, L)) return PF_OK;
     for (int k = 0; k < d->n_ops; ++k) {
         const OpClass cls = kOps[d->ops[k].op].cls;
         if (cls == OC_CONCAT_ROWS || cls == OC_MATVEC || cls == OC_VECMAT) return lower_attention(d, c, L);

@@ -33,6 +33,7 @@ double family_factor(const Lowered& low) {
         case pf::CORE_GATHER: return 0.80;
         case pf::CORE_GROUPNORM: return 0.65;
         case pf::CORE_POOL: return 0.60;
+        case pf::CORE_COLNORM: return 0.75;
         case pf::CORE_DWCONV: return 0.35;
         case pf::CORE_ATTN_DECODE: return 0.70;
         default: return 0.78;  // the row family's cores and row programs

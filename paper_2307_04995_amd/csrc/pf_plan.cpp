@@ -1082,6 +1082,33 @@ pf_status plan_pool(pf_plan_s* p) {
     return PF_OK;
 }
 
+// ---- column family
+pf_status plan_column(pf_plan_s* p) {
+    const Lowered& L = p->low;
+    const int es = dtype_size(L.main_dtype), vec = 16 / es;
+    if (L.col_s % vec != 0) return fail(PF_ERR_UNSUPPORTED, "normalisation over a strided dimension needs %d-element multiples after it (got %lld)", vec, (long long)L.col_s);
+    if (L.col_c > 1024) return fail(PF_ERR_UNSUPPORTED, "normalisation over a strided dimension holds at most 1024 values per position in registers (got %lld)", (long long)L.col_c);
+    const int64_t s_vecs = L.col_s / vec, tiles = (s_vecs + 7) / 8;
+    if (L.col_outer * tiles > 0x7fffffffLL || L.col_outer * L.col_c * L.col_s > 0xffffffffLL * 4) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the column family");
+    pf::ColArgs& a = p->col;
+    memset(&a, 0, sizeof(a));
+    a.c = (uint32_t)L.col_c;
+    a.s = (uint32_t)L.col_s;
+    a.s_vecs = (uint32_t)s_vecs;
+    a.tiles_per_outer = (uint32_t)tiles;
+    a.inv_c = 1.0f / (float)L.col_c;
+    a.eps = L.eps;
+    p->k = L.col_c <= 32 ? 1 : L.col_c <= 64 ? 2 : L.col_c <= 128 ? 4 : L.col_c <= 512 ? 16 : 32;
+    p->family = PF_FAMILY_COLUMN;
+    p->variant = 0;
+    p->spec_id = 0;
+    p->grid = dim3((uint32_t)(L.col_outer * tiles));
+    p->block = dim3(256);
+    p->lds_bytes = 4 * 8 * (uint32_t)vec * 4;
+    p->n_launches = 1;
+    return PF_OK;
+}
+
 pf_status plan_attn(pf_plan_s* p, int forced_variant) {
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype);
@@ -1174,7 +1201,7 @@ pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t v
     memset(&p->permg, 0, sizeof(p->permg));
     memset(&p->attn, 0, sizeof(p->attn));
     s = lower_chain(desc, c, &p->low);
-    if (s == PF_OK && p->low.core != pf::CORE_ATTN_DECODE && p->low.core != pf::CORE_GATHER) {
+    if (s == PF_OK && p->low.core != pf::CORE_ATTN_DECODE && p->low.core != pf::CORE_GATHER && p->low.core != pf::CORE_COLNORM) {
         const Lowered& L = p->low;
         p->args.n_full = L.n_full;
         p->args.n_vec = L.n_vec;
@@ -1201,6 +1228,7 @@ pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t v
             case pf::CORE_GATHER: s = plan_gather(p, c); break;
             case pf::CORE_DWCONV: s = plan_stencil(p, c, variant); break;
             case pf::CORE_POOL: s = plan_pool(p); break;
+            case pf::CORE_COLNORM: s = plan_column(p); break;
             default: s = plan_row(p, variant); break;
         }
     }

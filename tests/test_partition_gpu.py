@@ -38,7 +38,9 @@ def test_layout_change_around_a_layer_normalisation(shape, dtype):
     gam = wl.random_tensor((c,), dtype, 3102, dist="positive")
     bet = wl.random_tensor((c,), dtype, 3103, scale=0.3)
     outs, info = _check(s, [x, gam, bet], dtype, f"permute > layernorm > permute {shape} {dtype}")
-    assert info.n_kernels == 3 and tuple(outs[0].shape) == shape
+    # (positions that are whole 16-byte vectors: one kernel of the column family; else three kernels)
+    whole = (h * w) % (4 if dtype == "f32" else 8) == 0
+    assert info.n_kernels == (1 if whole else 3) and tuple(outs[0].shape) == shape
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
