@@ -72,6 +72,7 @@ def full_size_chain(name):
         "X2": "X2 fp16 one-token attention, 8x25 heads, 1023 cached rows + 1, d=64 (not a BASELINE config)",
         "X5": "X5 fp16 NHWC GroupNorm(32)+SiLU [16,64,64,320], 10 channels per group (not a BASELINE config)",
         "X6": "X6 fp16 SiLU -> mean over H, W, NHWC [32,56,56,240] (not a BASELINE config)",
+        "X7": "X7 fp16 LayerNorm over the channels of NCHW [64,96,56,56], written permute -> LayerNorm -> permute (not a BASELINE config)",
     }
     return spec, ins, algorithmic, nominal, labels[name]
 
@@ -268,7 +269,7 @@ def main():
         result["config"]["hot_us_per_call"] = round(hot[0] * 1e3, 3)
     if not args.no_context:
         chains = {}
-        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C1x256", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6"]) if c]
+        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C1x256", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7"]) if c]
         forced = dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.variant.split(",") if "=" in kv)
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)

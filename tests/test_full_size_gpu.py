@@ -59,7 +59,7 @@ def test_full_size_chain_matches_oracle(name):
         assert info.variant == pf.PF_VARIANT_GROUP_RESIDENT
 
 
-@pytest.mark.parametrize("name", ["X2", "X4", "X5", "X6"])
+@pytest.mark.parametrize("name", ["X2", "X4", "X5", "X6", "X7"])
 def test_full_size_extra_chains_match_oracle(name):
     # the attention and depthwise-convolution chains bench.py times for context, every element
     from paper_2307_04995_amd import binding as pf
@@ -70,6 +70,8 @@ def test_full_size_extra_chains_match_oracle(name):
     _report_ulps(name, outs[0], want[0], spec.outputs[0][1])
     print(f"{name}: family {info.family} variant {info.variant} spec {info.spec_id} max-abs {max_abs:.3e} max-rel {max_rel:.3e}")
     assert info.n_launches == 1
+    if name == "X7":
+        assert info.family == pf.PF_FAMILY_COLUMN
     if name == "X4":
         assert info.variant == pf.PF_VARIANT_STENCIL_STAGED and info.spec_id == pf.PF_SPEC_JIT
 

@@ -263,6 +263,21 @@ def x6_silu_global_mean(n: int = 32, h: int = 56, w: int = 56, c: int = 240, dty
     return s, [quantise(x, dtype)]
 
 
+def x7_channels_first_layernorm(n: int = 64, c: int = 96, h: int = 56, w: int = 56, dtype: str = "f16"):
+    """LayerNorm over the channels of a channels-first x [n, c, h, w], written as move the channels to the end ->
+    LayerNorm -> move them back (not a BASELINE config; the normalisation of a convolutional network's
+    down-sampling layers)."""
+    g = _rng(12, 0)
+    x = g.standard_normal((n, c, h, w), dtype=np.float32)
+    gamma = g.uniform(0.5, 1.5, c).astype(np.float32)
+    beta = g.uniform(-0.5, 0.5, c).astype(np.float32)
+    s = ChainSpec(inputs=[(dtype, (n, c, h, w)), (dtype, (c,)), (dtype, (c,))])
+    v = s.op("permute", 0, i=[0, 2, 3, 1])
+    v = s.op("layernorm", v, 1, 2, f=[1e-6])
+    s.out(s.op("permute", v, i=[0, 3, 1, 2]), dtype)
+    return s, [quantise(x, dtype), quantise(gamma, dtype), quantise(beta, dtype)]
+
+
 CONFIGS = {
     "C1": c1_bias_res_layernorm_gelu,
     "C2": c2_causal_softmax,
@@ -275,6 +290,7 @@ CONFIGS = {
     "X2": x2_decode_attention,          # not a BASELINE config: one-token attention against a key-value cache
     "X5": x5_groupnorm_silu_wide_groups,  # not a BASELINE config: GroupNorm with groups of 10 channels
     "X6": x6_silu_global_mean,          # not a BASELINE config: activation + global average pooling
+    "X7": x7_channels_first_layernorm,  # not a BASELINE config: normalisation over a strided dimension
 }
 
 
