@@ -9,7 +9,7 @@
 // of a wave reads 8 rows x 128 contiguous bytes, like the tile transposition -- and keeps them in registers (KC
 // vectors per lane, so C <= 32 * KC).  The statistics of one position are spread over the 32 row groups: three
 // lane exchanges inside a wave (lanes 8, 16, 32 apart hold the same column), then one LDS exchange between the
-// four waves.  Mean first (as differences from a pivot row), then centred squares: no cancellation; RMS needs one
+// four waves (one barrier each).  Mean first (as differences from a pivot row), then centred squares: no cancellation; RMS needs one
 // exchange.  Every input
 // element is read once and every output element written once; nothing is transposed.
 #pragma once
@@ -25,8 +25,7 @@ PF_DEVICE void col_all_reduce(float (&v)[VEC], float* lds, uint32_t wave, uint32
         v[j] += __shfl_xor(v[j], 16, 64);
         v[j] += __shfl_xor(v[j], 32, 64);
     }
-    __syncthreads();  // the previous exchange's readers are done
-    if (lane < 8u) {
+    if (lane < 8u) {  // (each exchange of a kernel has an LDS area of its own: no barrier in front)
 #pragma unroll
         for (int j = 0; j < VEC; ++j) lds[(wave * 8u + col) * VEC + j] = v[j];
     }
@@ -54,7 +53,7 @@ template <int DT, int KC, bool RMS>
 __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
-    __shared__ float lds[4 * 8 * VEC];
+    __shared__ float lds[2][4 * 8 * VEC];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, col = tid & 7u, rg = tid >> 3;
     const uint32_t o = blockIdx.x / a.tiles_per_outer, t = blockIdx.x - o * a.tiles_per_outer;
     const uint32_t sv = t * 8u + col;
@@ -70,18 +69,15 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     }
     // mean = piv + mean[]: kept as a pivot (row 0 of the same position) plus the mean of the differences from it, so
     // that a large common offset of the values eats the digits neither of the sum nor of x - mean
+    // (every lane fetches the pivot row itself: the 32 row groups of a column read the same 16 bytes, which the cache
+    // serves, and no barrier is needed to share them)
+    u32x4 piv_raw = u32x4{0u, 0u, 0u, 0u};
+    if (!RMS && col_ok) piv_raw = load_cached(a.x, base * S::ESIZE);
     float piv[VEC], mean[VEC], acc[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) piv[j] = 0.0f, mean[j] = 0.0f, acc[j] = 0.0f;
     if (!RMS) {
-        if (rg == 0u) {
-            S::unpack(raw[0], piv);
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) lds[col * VEC + j] = piv[j];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) piv[j] = lds[col * VEC + j];
+        S::unpack(piv_raw, piv);
 #pragma unroll
         for (int k = 0; k < KC; ++k) {
             if (rg + 32u * (uint32_t)k < a.c) {
@@ -91,7 +87,7 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
                 for (int j = 0; j < VEC; ++j) mean[j] += x[j] - piv[j];
             }
         }
-        col_all_reduce<VEC>(mean, lds, wave, col, lane);
+        col_all_reduce<VEC>(mean, lds[0], wave, col, lane);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) mean[j] *= a.inv_c;
         keep_packed<KC>(raw);
@@ -109,7 +105,7 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
             }
         }
     }
-    col_all_reduce<VEC>(acc, lds, wave, col, lane);
+    col_all_reduce<VEC>(acc, lds[1], wave, col, lane);
     keep_packed<KC>(raw);
     float rstd[VEC];
 #pragma unroll
