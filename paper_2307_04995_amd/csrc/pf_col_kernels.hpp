@@ -49,7 +49,9 @@ PF_DEVICE void keep_packed(u32x4 (&raw)[KC]) {
         }
 }
 
-template <int DT, int KC, bool RMS>
+// RAGGED: the extent after the normalised dimension is not a whole number of 16-byte vectors (7 x 7 or 14 x 14
+// positions of 16-bit data): rows start at element alignment and the last vector of a row is partial.
+template <int DT, int KC, bool RMS, bool RAGGED = false>
 __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -58,6 +60,7 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     const uint32_t o = blockIdx.x / a.tiles_per_outer, t = blockIdx.x - o * a.tiles_per_outer;
     const uint32_t sv = t * 8u + col;
     const bool col_ok = sv < a.s_vecs;
+    const uint32_t cnt = RAGGED ? elems_below<VEC>(sv * VEC, a.s) : (uint32_t)VEC;  // elements of this lane's vector inside the row
     const uint64_t base = ((uint64_t)o * a.c) * a.s + (uint64_t)sv * VEC;  // element offset of row 0 at this column
 
     u32x4 raw[KC];
@@ -65,14 +68,17 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     for (int k = 0; k < KC; ++k) {
         const uint32_t c = rg + 32u * (uint32_t)k;
         raw[k] = u32x4{0u, 0u, 0u, 0u};
-        if (col_ok && c < a.c) raw[k] = load_stream(a.x, (base + (uint64_t)c * a.s) * S::ESIZE);
+        if (col_ok && c < a.c) {
+            if (RAGGED) raw[k] = load_elems<DT>(a.x, base + (uint64_t)c * a.s, cnt, 0u);
+            else raw[k] = load_stream(a.x, (base + (uint64_t)c * a.s) * S::ESIZE);
+        }
     }
     // mean = piv + mean[]: kept as a pivot (row 0 of the same position) plus the mean of the differences from it, so
     // that a large common offset of the values eats the digits neither of the sum nor of x - mean
     // (every lane fetches the pivot row itself: the 32 row groups of a column read the same 16 bytes, which the cache
     // serves, and no barrier is needed to share them)
     u32x4 piv_raw = u32x4{0u, 0u, 0u, 0u};
-    if (!RMS && col_ok) piv_raw = load_cached(a.x, base * S::ESIZE);
+    if (!RMS && col_ok) piv_raw = RAGGED ? load_elems<DT>(a.x, base, cnt, 0u) : load_cached(a.x, base * S::ESIZE);
     float piv[VEC], mean[VEC], acc[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) piv[j] = 0.0f, mean[j] = 0.0f, acc[j] = 0.0f;
@@ -127,7 +133,8 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
         S::unpack(raw[k], x);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) x[j] = fmaf(((x[j] - piv[j]) - mean[j]) * rstd[j], gam, bet);
-        store_stream(a.out, (base + (uint64_t)c * a.s) * S::ESIZE, S::pack(x));
+        if (RAGGED) store_elems<DT>(a.out, base + (uint64_t)c * a.s, cnt, S::pack(x));
+        else store_stream(a.out, (base + (uint64_t)c * a.s) * S::ESIZE, S::pack(x));
     }
 }
 

@@ -190,7 +190,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
         ca.gamma = inputs[L.col_in[1]];
         ca.beta = L.col_in[2] >= 0 ? inputs[L.col_in[2]] : nullptr;
         ca.out = outputs[0];
-        const hipError_t ec = pf::launch_colnorm(L.main_dtype, ca, plan->k, L.col_in[2] < 0, plan->grid, (hipStream_t)stream);
+        const hipError_t ec = pf::launch_colnorm(L.main_dtype, ca, plan->k, L.col_in[2] < 0, plan->ragged, plan->grid, (hipStream_t)stream);
         if (ec != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ec));
         return PF_OK;
     }

@@ -1086,9 +1086,9 @@ pf_status plan_pool(pf_plan_s* p) {
 pf_status plan_column(pf_plan_s* p) {
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype), vec = 16 / es;
-    if (L.col_s % vec != 0) return fail(PF_ERR_UNSUPPORTED, "normalisation over a strided dimension needs %d-element multiples after it (got %lld)", vec, (long long)L.col_s);
     if (L.col_c > 1024) return fail(PF_ERR_UNSUPPORTED, "normalisation over a strided dimension holds at most 1024 values per position in registers (got %lld)", (long long)L.col_c);
-    const int64_t s_vecs = L.col_s / vec, tiles = (s_vecs + 7) / 8;
+    const int64_t s_vecs = (L.col_s + vec - 1) / vec, tiles = (s_vecs + 7) / 8;
+    p->ragged = L.col_s % vec != 0;  // rows at element alignment, partial last vector
     if (L.col_outer * tiles > 0x7fffffffLL || L.col_outer * L.col_c * L.col_s > 0xffffffffLL * 4) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the column family");
     pf::ColArgs& a = p->col;
     memset(&a, 0, sizeof(a));

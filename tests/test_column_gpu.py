@@ -38,7 +38,8 @@ def _inputs(dtype, shape, axis, kind, seed):
 
 # channel counts on both sides of every registers-per-lane step (32, 64, 128, 512, 1024), positions with a partial
 # last tile (the slab is 64 positions of 16-bit data, 32 of fp32), several outer indices, rank 3 to 5
-SHAPES = [((2, 96, 56, 56), 1), ((3, 32, 8, 8), 1), ((1, 33, 72), 1), ((2, 64, 136), 1), ((2, 65, 40), 1), ((1, 128, 200), 1),
+SHAPES = [((2, 96, 7, 7), 1), ((1, 40, 14, 14), 1), ((3, 17, 5, 3), 1), ((2, 200, 6, 9), 1), ((2, 5, 3, 1), 1),  # positions that are not whole vectors
+          ((2, 96, 56, 56), 1), ((3, 32, 8, 8), 1), ((1, 33, 72), 1), ((2, 64, 136), 1), ((2, 65, 40), 1), ((1, 128, 200), 1),
           ((1, 129, 64), 1), ((2, 320, 24), 1), ((1, 512, 16), 1), ((1, 513, 8), 1), ((1, 1024, 8), 1), ((2, 2, 64), 1),
           ((2, 3, 5, 7, 16), 2), ((4, 5, 6, 8), 0), ((2, 2, 24, 4, 4), 2)]
 
@@ -58,16 +59,14 @@ def test_normalisation_over_a_strided_dimension(shape, axis, dtype, kind):
 
 def test_what_the_one_kernel_form_does_not_take_runs_as_three_kernels():
     pf = _pf()
-    # positions that are not whole 16-byte vectors; more than 1024 values per position
-    for shape in ((2, 24, 6, 9), (1, 1100, 16)):
-        s = _chain("f16", shape, 1, "layernorm")
-        _, info, _ = check_chain(s, _inputs("f16", shape, 1, "layernorm", 7200), what=f"{shape}")
-        assert info.n_kernels == 3
-    # with the split switched off the refusal names the reason
-    with env(PF_PARTITION="0"):
+    shape = (1, 1100, 16)  # more than 1024 values per position
+    s = _chain("f16", shape, 1, "layernorm")
+    _, info, _ = check_chain(s, _inputs("f16", shape, 1, "layernorm", 7200), what=f"{shape}")
+    assert info.n_kernels == 3
+    with env(PF_PARTITION="0"):  # with the split switched off the refusal names the reason
         with pytest.raises(pf.PfError) as e:
-            pf.Plan(_chain("f16", (2, 24, 6, 9), 1, "layernorm"), 0)
-        assert e.value.status == pf.PF_ERR_UNSUPPORTED
+            pf.Plan(s, 0)
+        assert e.value.status == pf.PF_ERR_UNSUPPORTED and "1024" in str(e.value)
 
 
 def test_constant_positions_and_large_offsets():

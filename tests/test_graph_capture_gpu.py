@@ -97,9 +97,10 @@ def test_fused_groupnorm_refuses_capture_and_the_two_launch_variant_replays():
 
 def test_a_chain_of_several_kernels_replays_from_a_graph():
     # three kernels per run, tensors between them in the plan's arena: nine kernel nodes per replay
-    n, c, h, w = 2, 24, 6, 9  # (54 positions: not whole vectors, so not the one-kernel column family)
+    n, c, h, w = 2, 24, 6, 10
     spec = wl.ChainSpec(inputs=[("f32", (n, c, h, w)), ("f32", (c,)), ("f32", (c,))])
-    v = spec.op("permute", spec.op("layernorm", spec.op("permute", 0, i=[0, 2, 3, 1]), 1, 2, f=[2.0 ** -20]), i=[0, 3, 1, 2])
+    # (the activation keeps the chain from being the one-kernel form of the column family)
+    v = spec.op("permute", spec.op("layernorm", spec.op("silu", spec.op("permute", 0, i=[0, 2, 3, 1])), 1, 2, f=[2.0 ** -20]), i=[0, 3, 1, 2])
     spec.out(v, "f32")
     ins = [wl.random_tensor((n, c, h, w), "f32", 1411), wl.random_tensor((c,), "f32", 1412, dist="positive"), wl.random_tensor((c,), "f32", 1413, scale=0.3)]
     _capture_and_replay(spec, ins, "channels-first layer normalisation in a graph")
