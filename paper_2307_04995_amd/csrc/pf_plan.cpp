@@ -378,14 +378,20 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     int64_t acc = 1;
     for (int k = rank - 1; k >= 0; --k) { istr[k] = acc; acc *= in[k]; }
     // output dims in order, dropping extent-1 dims and merging dims that stay adjacent
+    bool uses_positions = L.n_vec != 0 || L.mask_si != 0 || L.core_mask != 0;
+    for (int i = 0; i < L.pro.n; ++i) uses_positions |= L.pro.u[i].code == pf::U_MASK_CAUSAL;
+    for (int i = 0; i < L.epi.n; ++i) uses_positions |= L.epi.u[i].code == pf::U_MASK_CAUSAL;
+    const bool merge_ragged = ragged && !uses_positions && L.perm[rank - 1] != rank - 1 && env_int("PF_PERM_MERGE_RAGGED", 1) != 0;
     struct Dim { int64_t extent, in_stride; };
     std::vector<Dim> od;
     for (int q = 0; q < rank; ++q) {
         const int src = L.perm[q];
         if (in[src] == 1) continue;
         // (ragged: dimensions are not merged, so that the innermost dimension of each side is one the vectors of
-        // broadcast operands and the partial last vector can be told from)
-        if (!ragged && !od.empty() && od.back().in_stride == in[src] * istr[src]) {
+        // broadcast operands and the partial last vector can be told from -- unless nothing in the chain looks at
+        // positions: an innermost-changing permutation without broadcast operands or mask, where merging h and w of
+        // a 7 x 7 feature map makes the transposed extent 49 instead of 7)
+        if ((!ragged || merge_ragged) && !od.empty() && od.back().in_stride == in[src] * istr[src]) {
             od.back().extent *= in[src];
             od.back().in_stride = istr[src];
         } else {

@@ -177,3 +177,22 @@ def test_a_permutation_that_only_moves_extents_of_1_is_a_reshape(shape, perm, dt
     s.out(s.op("scale", v, f=[0.5]), dtype)
     outs, info, _ = check_chain(s, [x, b], what=f"{shape} perm {perm} {dtype}")
     assert info.family == pf.PF_FAMILY_ELEMENTWISE and tuple(outs[0].shape) == out_shape
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((3, 40, 7, 7), (0, 2, 3, 1)), ((3, 7, 7, 40), (0, 3, 1, 2)), ((2, 24, 14, 14), (0, 2, 3, 1)),
+                                        ((2, 5, 3, 9, 16), (0, 4, 1, 2, 3)), ((2, 17, 3, 5), (0, 2, 3, 1))])
+def test_channels_first_to_channels_last_with_few_positions(shape, perm, dtype):
+    # h and w stay adjacent and in order: they transpose as one extent of h * w (49, 196) although that is not a whole
+    # number of vectors; nothing in the chain looks at positions (no broadcast operand, no mask)
+    from paper_2307_04995_amd import binding as pf
+    x = wl.random_tensor(shape, dtype, 6201)
+    s = wl.ChainSpec(inputs=[(dtype, shape)])
+    s.out(s.op("scale", s.op("permute", s.op("silu", 0) if dtype == "f32" else 0, i=list(perm)), f=[0.5]), dtype)
+    outs, info, _ = check_chain(s, [x], what=f"{shape} perm {perm} {dtype}")
+    assert info.family == pf.PF_FAMILY_TRANSPOSE and info.variant == pf.PF_VARIANT_T_TILE
+    # with a broadcast operand the extents stay apart (its vectors are told from the innermost extent)
+    b = wl.random_tensor((shape[perm[-1]],), dtype, 6202, scale=0.3)
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, (shape[perm[-1]],))])
+    s.out(s.op("add", s.op("permute", 0, i=list(perm)), 1), dtype)
+    check_chain(s, [x, b], what=f"{shape} perm {perm} {dtype} + bias")
