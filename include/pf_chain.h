@@ -277,8 +277,8 @@ pf_status pf_chain_plan_get_partition(const pf_plan *plan, pf_partition *out);
  * return without waiting.  inputs[k] / outputs[k] are device pointers to contiguous tensors of exactly
  * the shapes and dtypes of the description, 16-byte aligned, owned by the caller and not retained.
  * No allocation, no host synchronisation, no host work proportional to tensor size.
- * An output may be the same buffer as an input of identical shape and dtype in the element-wise, row and
- * group families (each element is read before it is written by the same lane); the other families
+ * An output may be the same buffer as an input of identical shape and dtype in the element-wise, row, group and
+ * column families (each element is read before it is written, by the same lane or workgroup); the other families
  * return PF_ERR_ALIAS for any overlap.  A plan with workspace (group, attention, pool families) must not run on
  * two streams at the same time.
  * The launches may be recorded into a HIP graph (stream capture) and replayed, except those of the one-launch

@@ -140,7 +140,9 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             if (ob < ie && ib < oe) {
                 const bool same = ob == ib && plan->out_bytes[o] == plan->in_bytes[k];
                 // in place only where every element is read before it is written by the same lane
-                const bool in_place_ok = plan->family == PF_FAMILY_ELEMENTWISE || plan->family == PF_FAMILY_ROW || plan->family == PF_FAMILY_GROUP;
+                // (column family: a workgroup has its whole slab in registers before it stores any of it, and slabs are disjoint)
+                const bool in_place_ok = plan->family == PF_FAMILY_ELEMENTWISE || plan->family == PF_FAMILY_ROW || plan->family == PF_FAMILY_GROUP ||
+                                         plan->family == PF_FAMILY_COLUMN;
                 if (!same || !in_place_ok)
                     return fail(PF_ERR_ALIAS, "output %d overlaps input %d", o, k);
             }

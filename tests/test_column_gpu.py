@@ -81,7 +81,7 @@ def test_constant_positions_and_large_offsets():
     assert torch.equal(outs[0][0], bet.reshape(48, 1).expand(48, 64))
 
 
-def test_repeated_runs_and_in_place_refusal():
+def test_repeated_runs_and_in_place():
     pf = _pf()
     shape = (2, 40, 4, 16)
     s = _chain("f16", shape, 1, "rmsnorm")
@@ -96,7 +96,15 @@ def test_repeated_runs_and_in_place_refusal():
         plan.run_ptrs([xd.data_ptr(), gam.data_ptr()], [out.data_ptr()], stream)
         torch.cuda.synchronize()
         compare(out.cpu(), oracle_run(s, [x, gam.cpu()])[0], "f16", f"run {rep}")
+    # in place: a workgroup holds its whole slab before it stores any of it
+    x = wl.random_tensor(shape, "f16", 7420)
+    buf = x.cuda()
+    plan.run_ptrs([buf.data_ptr(), gam.data_ptr()], [buf.data_ptr()], stream)
+    torch.cuda.synchronize()
+    compare(buf.cpu(), oracle_run(s, [x, gam.cpu()])[0], "f16", "in place")
+    # a partial overlap is refused
+    big = torch.empty(int(np.prod(shape)) + 64, dtype=torch.float16, device="cuda")
     with pytest.raises(pf.PfError) as e:
-        plan.run_ptrs([out.data_ptr(), gam.data_ptr()], [out.data_ptr()], stream)
+        plan.run_ptrs([big.data_ptr(), gam.data_ptr()], [big.data_ptr() + 64], stream)
     assert e.value.status == pf.PF_ERR_ALIAS
     plan.close()
