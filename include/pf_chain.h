@@ -82,7 +82,9 @@ typedef enum {
     PF_RMSNORM = 22,    /* src = x, gamma;       f[0] = eps; x / sqrt(mean(x^2)+eps) * gamma                */
     PF_GROUPNORM = 23,  /* channels-last x [N, spatial.., C]; src = x, gamma, beta; i[0] = groups; f[0]=eps */
     /* layout */
-    PF_PERMUTE = 24,    /* i[0..rank-1] = perm; output dim k is input dim perm[k]                           */
+    PF_PERMUTE = 24,    /* i[0..rank-1] = perm; output dim k is input dim perm[k].  A permutation that only moves
+                           extents of 1 is lowered as a reshape; "move a dimension to the end -> LAYERNORM / RMSNORM
+                           -> move it back" on chain inputs is one kernel without a layout change (column family) */
     PF_RESHAPE = 25,    /* i[0..n_i-1] = new shape with the same element count; contiguous data is
                            reinterpreted, nothing moves                                                     */
     /* one-token attention against cached keys and values (section 8, GPT-2 case study).  These three are
