@@ -296,6 +296,27 @@ pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *con
  */
 pf_status pf_chain_plan_poll_error(const pf_plan *plan, int32_t *flag);
 
+/*
+ * pf_chain_plan + pf_chain_run + pf_chain_plan_destroy in one call that allocates nothing on the device.  For
+ * callers that cannot call hipMalloc where they run a chain: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  The device memory a chain's kernels need beyond its inputs and outputs (partial
+ * GroupNorm statistics per workgroup; partial results and arrival counters of the one-token attention) comes from a
+ * static device array of PF_STATIC_SCRATCH_BYTES that every device the library runs on holds until the process
+ * ends.  A chain that needs more returns PF_ERR_NOMEM and nothing is launched.
+ * Also refused, with PF_ERR_UNSUPPORTED (all of these need memory or code put on the device when a plan is made):
+ * chains that run as several kernels, layout-only chains with CONCAT / SLICE, broadcast inputs with extents of 1
+ * inside their shape, poolings split over several workgroups per sample.  Kernels are the library's built-in ones
+ * (nothing is compiled: a chain outside the catalogue runs on the run-time-interpreted kernels), GroupNorm runs as
+ * its two-launch variant, which waits for no other workgroup.
+ * desc, inputs, outputs, stream: as for pf_chain_plan and pf_chain_run; `device` is made current for the call and the
+ * caller's current device restored.  The parts of the array that must start at a value are rewritten by a small fill
+ * kernel enqueued on `stream` ahead of the chain's kernels (no memset, so the launches can be recorded into a graph).
+ * All calls on one device share the array: calls that overlap in time on one device (two streams, two threads)
+ * race; order them on one stream or with events.
+ */
+#define PF_STATIC_SCRATCH_BYTES (2u << 20)
+pf_status pf_chain_run_static(const pf_chain_desc *desc, int32_t device, const void *const *inputs, void *const *outputs, void *stream);
+
 void pf_chain_plan_destroy(pf_plan *plan);
 
 const char *pf_status_str(pf_status s);

@@ -72,7 +72,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libp
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
            "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose",
-           "pf_chain_partition", "pf_chain_segment_cost", "pf_chain_plan_get_partition"]
+           "pf_chain_partition", "pf_chain_segment_cost", "pf_chain_plan_get_partition", "pf_chain_run_static"]
 
 
 def _load() -> C.CDLL:
@@ -88,6 +88,7 @@ def _load() -> C.CDLL:
     lib.pf_chain_plan_variant.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.c_int32, C.POINTER(vp)]
     lib.pf_chain_plan_get_info.argtypes = [vp, C.POINTER(pf_plan_info)]
     lib.pf_chain_run.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.pf_chain_run_static.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.POINTER(vp), C.POINTER(vp), vp]
     lib.pf_chain_plan_poll_error.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.pf_chain_plan_destroy.argtypes = [vp]
     lib.pf_chain_plan_destroy.restype = None
@@ -164,6 +165,15 @@ def pf_chain_run(plan, input_ptrs: Sequence[int], output_ptrs: Sequence[int], st
     ins = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
     outs = (C.c_void_p * len(output_ptrs))(*[C.c_void_p(int(p)) for p in output_ptrs])
     return _lib.pf_chain_run(plan, ins, outs, C.c_void_p(int(stream)))
+
+
+PF_STATIC_SCRATCH_BYTES = 2 << 20
+
+
+def pf_chain_run_static(desc: pf_chain_desc, device: int, input_ptrs: Sequence[int], output_ptrs: Sequence[int], stream: int = 0) -> int:
+    ins = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
+    outs = (C.c_void_p * len(output_ptrs))(*[C.c_void_p(int(p)) for p in output_ptrs])
+    return _lib.pf_chain_run_static(C.byref(desc), int(device), ins, outs, C.c_void_p(int(stream)))
 
 
 def pf_chain_plan_poll_error(plan):

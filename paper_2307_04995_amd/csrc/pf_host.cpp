@@ -42,6 +42,14 @@ pf_status pf_chain_infer_shape(const pf_chain_desc* desc, int32_t value, pf_tens
 
 pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out) {
     if (!out) return fail(PF_ERR_INVALID_ARG, "out is null");
+    // planning makes `device` current (allocations, the run-time compiler); the caller's current device is put back
+    struct DeviceRestore {
+        int prev = -1;
+        ~DeviceRestore() {
+            if (prev >= 0) (void)hipSetDevice(prev);
+        }
+    } restore;
+    if (hipGetDevice(&restore.prev) != hipSuccess) restore.prev = -1;
     pf_status s = plan_one_kernel(desc, device, variant, out);
     // more than one exchange wider than a lane (or one a single kernel cannot hold): several kernels, split where the
     // performance model says the bytes are fewest
@@ -320,7 +328,7 @@ pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
 
 void pf_chain_plan_destroy(pf_plan* plan) {
     if (!plan) return;
-    if (plan->workspace) (void)hipFree(plan->workspace);
+    if (plan->workspace && !plan->workspace_borrowed) (void)hipFree(plan->workspace);
     if (plan->bcast_dev) (void)hipFree(plan->bcast_dev);
     for (pf_plan_s::Part& pp : plan->parts) pf_chain_plan_destroy(pp.plan);
     if (plan->arena) (void)hipFree(plan->arena);

@@ -137,6 +137,13 @@ struct pf_plan_s {
     dim3 grid2, block2;       // second launch (two-pass group variant)
     uint32_t lds_bytes = 0;
     void* workspace = nullptr;
+    bool workspace_borrowed = false;  // the workspace lies in the library's static scratch array: nothing to free
+    struct Fill {                     // ... and these parts of it must hold `byte` when the kernels start
+        void* ptr;
+        uint64_t bytes;
+        int byte;
+    };
+    std::vector<Fill> fills;
     uint32_t* ws_error = nullptr;  // device word a kernel sets when one of its bounded waits ran out
     uint64_t workspace_bytes = 0;
     uint64_t in_bytes[PF_MAX_INPUTS];
@@ -163,6 +170,22 @@ namespace pfh {
 
 // ---- planning ----
 int env_int(const char* name, int dflt);
+
+// Where a plan's device memory comes from.  Ordinary plans allocate it.  While pf_chain_run_static plans (tls_scratch is
+// set on that thread) it is carved out of the library's static scratch array instead, nothing is allocated, compiled
+// or uploaded, and whatever must start at a given value is recorded in the plan (pf_plan_s::fills) for a fill kernel
+// on the caller's stream.
+struct ScratchArena {
+    char* base;
+    uint64_t cap, used;
+};
+extern thread_local ScratchArena* tls_scratch;
+inline bool planning_static() { return tls_scratch != nullptr; }
+// `bytes` of device memory for the plan's workspace (p->workspace, p->workspace_bytes); the device must be current.
+pf_status plan_workspace_alloc(pf_plan_s* p, uint64_t bytes, const char* what);
+// Sets `bytes` bytes at `ptr` to `byte`.  must_hold: the kernels rely on the value (flags, counters, error words);
+// otherwise the clear is hygiene and a plan on the static scratch array skips it.
+pf_status plan_workspace_fill(pf_plan_s* p, void* ptr, int byte, uint64_t bytes, bool must_hold);
 pf::FastDiv make_fastdiv(uint32_t d);
 // Checks, lowers and plans one description as it stands (no recomposition).
 pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t variant, pf_plan** out);

@@ -83,9 +83,37 @@ pf::JitSpec make_jit_spec(const Lowered& L) {
     return j;
 }
 
+thread_local ScratchArena* tls_scratch = nullptr;
+
+pf_status plan_workspace_alloc(pf_plan_s* p, uint64_t bytes, const char* what) {
+    p->workspace_bytes = bytes;
+    if (ScratchArena* a = tls_scratch) {
+        const uint64_t at = (a->used + 255) / 256 * 256;
+        if (at + bytes > a->cap)
+            return fail(PF_ERR_NOMEM, "%s of %llu bytes does not fit the static scratch array (%llu bytes, %llu in use): use pf_chain_plan + pf_chain_run",
+                        what, (unsigned long long)bytes, (unsigned long long)a->cap, (unsigned long long)at);
+        p->workspace = a->base + at;
+        p->workspace_borrowed = true;
+        a->used = at + bytes;
+        return PF_OK;
+    }
+    if (hipMalloc(&p->workspace, bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "%s of %llu bytes failed", what, (unsigned long long)bytes);
+    return PF_OK;
+}
+
+pf_status plan_workspace_fill(pf_plan_s* p, void* ptr, int byte, uint64_t bytes, bool must_hold) {
+    if (bytes == 0) return PF_OK;
+    if (planning_static()) {
+        if (must_hold) p->fills.push_back(pf_plan_s::Fill{ptr, bytes, byte});
+        return PF_OK;
+    }
+    if (hipMemset(ptr, byte, bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
+    return PF_OK;
+}
+
 // Plan-time specialisation needs the device (the compiled kernel is loaded onto it).
 bool jit_possible(int device) {
-    if (!pf::jit_enabled()) return false;
+    if (!pf::jit_enabled() || planning_static()) return false;
     int n = 0;
     if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return false;
     return hipSetDevice(device) == hipSuccess;
@@ -167,6 +195,8 @@ pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
         }
     }
     if (L.general_bcast) {
+        if (planning_static())
+            return fail(PF_ERR_UNSUPPORTED, "broadcast inputs with extents of 1 inside their shape need a table in device memory: use pf_chain_plan + pf_chain_run");
         if (hipSetDevice(p->device) != hipSuccess || hipMalloc(&p->bcast_dev, sizeof(p->bcast_host)) != hipSuccess)
             return fail(PF_ERR_NOMEM, "device memory for broadcast terms");
         if (hipMemcpy(p->bcast_dev, p->bcast_host, sizeof(p->bcast_host), hipMemcpyHostToDevice) != hipSuccess)
@@ -572,6 +602,8 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
 
 // ---- group family
 pf_status plan_group(pf_plan_s* p, int forced_variant) {
+    // on the static scratch array: the two-launch variant, which waits for nobody and so has no failed wait to report
+    if (planning_static()) forced_variant = PF_VARIANT_GROUP_TWO_PASS;
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype);
     const int vec = 16 / es;
@@ -720,11 +752,12 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     const uint64_t part_bytes = variant == PF_VARIANT_GROUP_RESIDENT ? 0 : (uint64_t)samples * g.blocks_per_sample * g.groups * 4 * sizeof(float);
     const uint64_t gather_bytes =
         variant == PF_VARIANT_GROUP_RESIDENT ? (((uint64_t)2 * samples * g.groups * g.blocks_per_sample * sizeof(uint64_t)) + 255) / 256 * 256 : 0;
-    p->workspace_bytes = part_bytes + gather_bytes + 256;
-    if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
+    pf_status ws_st = plan_workspace_alloc(p, part_bytes + gather_bytes + 256, "workspace allocation");
+    if (ws_st != PF_OK) return ws_st;
     char* ws = static_cast<char*>(p->workspace);
-    if (hipMemset(ws, 0, p->workspace_bytes) != hipSuccess || (gather_bytes && hipMemset(ws + part_bytes, 0xff, gather_bytes) != hipSuccess))
-        return fail(PF_ERR_HIP, "workspace clear failed");
+    if ((ws_st = plan_workspace_fill(p, ws, 0, part_bytes, false)) != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, ws + part_bytes, 0xff, gather_bytes, true)) != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, ws + part_bytes + gather_bytes, 0, 256, true)) != PF_OK) return ws_st;
     g.ws_partial = part_bytes ? reinterpret_cast<float*>(ws) : nullptr;
     g.ws_gather = gather_bytes ? reinterpret_cast<uint64_t*>(ws + part_bytes) : nullptr;
     g.ws_error = reinterpret_cast<uint32_t*>(ws + part_bytes + gather_bytes);
@@ -979,6 +1012,8 @@ pf_status plan_gather(pf_plan_s* p, const Checked& c) {
             r.pad = 0;
         }
     }
+    if (planning_static())
+        return fail(PF_ERR_UNSUPPORTED, "layout-only chains with concat / slice need a run table in device memory: use pf_chain_plan + pf_chain_run");
     if (hipSetDevice(p->device) != hipSuccess) return fail(PF_ERR_HIP, "cannot select device %d", p->device);
     p->workspace_bytes = (uint64_t)n_runs * sizeof(pf::GatherRun);
     if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "run table allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
@@ -1069,10 +1104,13 @@ pf_status plan_pool(pf_plan_s* p) {
     if (g.blocks_per_sample > 1) {
         const uint64_t part_bytes = ((uint64_t)blocks * ch * sizeof(float) + 255) / 256 * 256;
         const uint64_t flag_bytes = ((uint64_t)blocks * sizeof(uint32_t) + 255) / 256 * 256;
-        p->workspace_bytes = part_bytes + flag_bytes + 256;
-        if (hipSetDevice(p->device) != hipSuccess || hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess)
-            return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
-        if (hipMemset(p->workspace, 0, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
+        if (planning_static())
+            return fail(PF_ERR_UNSUPPORTED, "a pooling split over several workgroups per sample waits on the device, and a wait that gives up is reported "
+                                            "through the plan: use pf_chain_plan + pf_chain_run");
+        if (hipSetDevice(p->device) != hipSuccess) return fail(PF_ERR_HIP, "cannot select device %d", p->device);
+        pf_status ws_st = plan_workspace_alloc(p, part_bytes + flag_bytes + 256, "workspace allocation");
+        if (ws_st != PF_OK) return ws_st;
+        if ((ws_st = plan_workspace_fill(p, p->workspace, 0, p->workspace_bytes, true)) != PF_OK) return ws_st;
         g.ws_partial = reinterpret_cast<float*>(p->workspace);
         g.ws_flags = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
         g.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes + flag_bytes);
@@ -1185,9 +1223,10 @@ pf_status plan_attn(pf_plan_s* p, int forced_variant) {
     a.part_stride = (uint32_t)((d + 2 + 31) / 32 * 32);
     const uint64_t part_bytes = ((uint64_t)heads * splits * a.part_stride * sizeof(float) + 255) / 256 * 256;
     const uint64_t cnt_bytes = ((uint64_t)heads * sizeof(uint32_t) + 255) / 256 * 256;
-    p->workspace_bytes = part_bytes + cnt_bytes;
-    if (hipMalloc(&p->workspace, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_NOMEM, "workspace allocation of %llu bytes failed", (unsigned long long)p->workspace_bytes);
-    if (hipMemset(p->workspace, 0, p->workspace_bytes) != hipSuccess) return fail(PF_ERR_HIP, "workspace clear failed");
+    pf_status ws_st = plan_workspace_alloc(p, part_bytes + cnt_bytes, "workspace allocation");
+    if (ws_st != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, p->workspace, 0, part_bytes, false)) != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, static_cast<char*>(p->workspace) + part_bytes, 0, cnt_bytes, true)) != PF_OK) return ws_st;
     a.ws_partial = reinterpret_cast<float*>(p->workspace);
     a.ws_counter = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
     return PF_OK;
@@ -1199,6 +1238,7 @@ pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t v
     if (s != PF_OK) return s;
     pf_plan_s* p = new (std::nothrow) pf_plan_s();
     if (!p) return fail(PF_ERR_NOMEM, "out of host memory");
+    const uint64_t scratch_used_before = tls_scratch ? tls_scratch->used : 0;
     p->desc = *desc;
     p->device = device;
     memset(&p->args, 0, sizeof(p->args));
@@ -1252,6 +1292,7 @@ pf_status plan_checked_desc(const pf_chain_desc* desc, int32_t device, int32_t v
         return PF_OK;
     }
     pf_chain_plan_destroy(p);
+    if (tls_scratch) tls_scratch->used = scratch_used_before;  // a plan that failed gives its share of the scratch array back
     return s;
 }
 
