@@ -396,6 +396,7 @@ struct ProgView {
 struct GenericSpec {
     static constexpr bool kStatic = false;
     static constexpr bool kBcast = true;  // general broadcasting of operands is a run-time property here
+    static constexpr int kVecMode = 3;    // ... and so is a broadcast operand with a single element
     static constexpr int NF = 3, NV = 4, NT = PF_DEV_MAX_TMP;
     using Pro = DynList;
     using Epi = DynList;
@@ -406,11 +407,15 @@ struct GenericSpec {
     static PF_DEVICE int beta(const ChainArgs& a) { return a.core_vec[1]; }
 };
 
-// FLAGS_: bit 0 = some operand broadcasts the general way (extents of 1 anywhere)
+// FLAGS_: bit 0 = some operand broadcasts the general way (extents of 1 anywhere); bit 1 = some broadcast operand has a
+// single element.  Kernels built without a bit carry none of that case's code: the one-element case in particular
+// costs more than its branch, because the compiler issues its 2-byte load next to the 16-byte one and waits for both
+// before it goes on, which turns the operand loads of a kernel into one memory round trip after the other.
 template <int NF_, int NV_, int NT_, int CORE_, int GAMMA_, int BETA_, class ProL, class EpiL, int FLAGS_ = 0>
 struct StaticSpec {
     static constexpr bool kStatic = true;
     static constexpr bool kBcast = (FLAGS_ & 1) != 0;
+    static constexpr int kVecMode = FLAGS_ & 3;
     static constexpr int NF = NF_, NV = NV_, NT = NT_;
     using Pro = ProL;
     using Epi = EpiL;
@@ -485,19 +490,22 @@ PF_DEVICE uint32_t vec_offset(const VecArg& va, uint32_t row, uint32_t col, uint
     return col % va.numel;
 }
 
-template <int DT, bool BC = true>
+// VM: which of the cases above the kernel was built for (bit 0: general broadcasting, bit 1: one-element operands)
+template <int DT, int VM = 3>
 PF_DEVICE u32x4 load_vec_operand(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner) {
-    if (va.numel == 1) return Storage<DT>::splat(va.ptr);
+    constexpr bool BC = (VM & 1) != 0;
+    if ((VM & 2) && va.numel == 1) return Storage<DT>::splat(va.ptr);
     const uint32_t off = vec_offset<BC>(va, row, col, n_inner);
     if (BC && va.n_terms != 0u && va.col_bcast) return Storage<DT>::splat(static_cast<const char*>(va.ptr) + (uint64_t)off * Storage<DT>::ESIZE);
     return load_cached(va.ptr, (uint64_t)off * Storage<DT>::ESIZE);
 }
 
 // The same for a position whose vector may be unaligned or partial: gathered element by element.
-template <int DT, bool BC = true>
+template <int DT, int VM = 3>
 PF_DEVICE u32x4 load_vec_operand_elems(const VecArg& va, uint32_t row, uint32_t col, uint32_t n_inner, uint32_t count) {
     using S = Storage<DT>;
-    if (va.numel == 1) return S::splat(va.ptr);
+    constexpr bool BC = (VM & 1) != 0;
+    if ((VM & 2) && va.numel == 1) return S::splat(va.ptr);
     if (BC && va.n_terms != 0u && va.col_bcast) return S::splat(static_cast<const char*>(va.ptr) + (uint64_t)vec_offset<BC>(va, row, col, n_inner) * S::ESIZE);
     u32x4 r = {0u, 0u, 0u, 0u};
     if (DT == DT_F32) {

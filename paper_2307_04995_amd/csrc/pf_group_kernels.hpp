@@ -290,7 +290,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         for (int v = 0; v < Spec::NV; ++v) {
             if (v < Spec::n_vec(a)) {
                 s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                if (active) s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], 0u, s.col[0], g.channels);
+                if (active) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], 0u, s.col[0], g.channels);
             }
         }
     }
@@ -336,7 +336,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 for (int v = 0; v < Spec::NV; ++v) {
                     if (v < Spec::n_vec(a)) {
                         s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                        if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], s.row[0], s.col[0], g.channels);
+                        if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.channels);
                     }
                 }
             }

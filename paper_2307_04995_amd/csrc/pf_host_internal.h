@@ -76,6 +76,7 @@ struct Lowered {
     int vec_input[PF_DEV_MAX_VEC];
     bool vec_is_epi[PF_DEV_MAX_VEC];
     bool general_bcast = false;         // some broadcast input needs the general (term-based) addressing
+    bool scalar_vec = false;            // some broadcast input has a single element
     Shape vec_partner[PF_DEV_MAX_VEC];  // shape of the value the operand is broadcast against (where it is first used)
     int core_vec[2] = {-1, -1};
     pf::Program pro, epi;

@@ -72,8 +72,8 @@ PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneSta
                 if (valid[k]) {
                     const uint32_t off = epi ? out_off[k] : in_off[k];
                     const uint32_t row = fast_div(off, epi ? g.div_out_inner : g.div_in_inner);
-                    if (RAGGED) s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner, cnt[k]);
-                    else s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, off - row * inner, inner);
+                    if (RAGGED) s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, off - row * inner, inner, cnt[k]);
+                    else s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, off - row * inner, inner);
                 }
             }
         }

@@ -45,7 +45,8 @@ bool list_equal(const pf::Program& p, const uint32_t* list, int n) {
 }
 
 int match_spec(const std::vector<pf::SpecDesc>& table, const Lowered& L) {
-    if (L.general_bcast) return 0;  // catalogue kernels are built without the general broadcast addressing
+    if (L.general_bcast || L.scalar_vec) return 0;  // catalogue kernels are built without the general broadcast addressing
+                                                    // and without the one-element operand case
     if (L.n_out != 1) return 0;
     for (const pf::SpecDesc& s : table) {
         if (s.nf != L.n_full || s.nv != L.n_vec || s.nt != L.n_tmp || s.core != L.core) continue;
@@ -75,7 +76,7 @@ pf::JitSpec make_jit_spec(const Lowered& L) {
     j.core = L.core;
     j.gamma = L.core_vec[0];
     j.beta = L.core_vec[1];
-    j.flags = L.general_bcast ? 1 : 0;
+    j.flags = (L.general_bcast ? 1 : 0) | (L.scalar_vec ? 2 : 0);
     for (int i = 0; i < L.pro.n; ++i)
         j.pro.push_back((uint32_t)L.pro.u[i].code | ((uint32_t)L.pro.u[i].kind << 8) | ((uint32_t)L.pro.u[i].slot << 16));
     for (int i = 0; i < L.epi.n; ++i)
@@ -137,7 +138,10 @@ pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
         va.period_rows = 1;
         va.n_terms = 0;
         va.col_bcast = 0;
-        if (n == 1) continue;
+        if (n == 1) {
+            p->low.scalar_vec = true;
+            continue;
+        }
         const Shape& os = c.shape[in];
         const Shape& ps = L.vec_partner[v];
         if (!ps.empty() && !is_trailing(os, ps)) {

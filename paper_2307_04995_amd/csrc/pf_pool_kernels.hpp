@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
             for (int v = 0; v < Spec::NV; ++v)
                 if (v < Spec::n_vec(a) && ((pro_vec >> v) & 1u)) {
                     s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                    if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos, s.col[0], g.channels);
+                    if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.channels);
                 }
             run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
             if (valid_of(i)) {
@@ -169,7 +169,7 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
         if (f < Spec::n_full(a) && ((epi_full >> f) & 1u)) s.fraw[f][0] = load_cached(a.full[f], out_off);
 #pragma unroll
     for (int v = 0; v < Spec::NV; ++v)
-        if (v < Spec::n_vec(a) && ((epi_vec >> v) & 1u)) s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], sample, s.col[0], g.channels);
+        if (v < Spec::n_vec(a) && ((epi_vec >> v) & 1u)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], sample, s.col[0], g.channels);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
     run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});

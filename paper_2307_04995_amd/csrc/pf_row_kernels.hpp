@@ -172,8 +172,8 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                 const int k = k0 + c;
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
                 if (RAGGED)
-                    s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kBcast>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
-                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], row, s.col[k], a.n_inner);
+                    s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
+                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner);
             }
         }
     }
@@ -534,7 +534,7 @@ __global__ void __launch_bounds__(256) ew_kernel(const ChainArgs a, const uint32
                                                  bits[4 % VEC] | (bits[5 % VEC] << 16), bits[6 % VEC] | (bits[7 % VEC] << 16)};
                     }
                 } else if (cnt[k] != 0u) {
-                    s.vraw[v][k] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], s.row[k], s.col[k], a.n_inner);
+                    s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[k], s.col[k], a.n_inner);
                 }
             }
         }

@@ -60,7 +60,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos, s.col[0], g.c);
+                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
     };
 
     uint32_t win[3][3][WE];  // activated values (fp32 bits, or packed): window row (input row mod 3), column -1 / 0 / +1
@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
             for (int v = 0; v < Spec::NV; ++v)
                 if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                    pend_v[dw][v] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos, s.col[0], g.c);
+                    pend_v[dw][v] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
         }
     };
     auto admit_row = [&](int r, int slot) {
@@ -229,7 +229,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v)
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                        s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], s.row[0], s.col[0], g.c);
+                        s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.c);
                 run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
             }
             u32x4* dst = tile + ((uint32_t)r * tw + j) * EV;
@@ -325,7 +325,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos, s.col[0], g.c);
+                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
@@ -393,7 +393,7 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v)
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                        pend_v[dw][v] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], pos[dw], s.col[0], g.c);
+                        pend_v[dw][v] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos[dw], s.col[0], g.c);
             }
 #pragma unroll
             for (int dw = 0; dw < KS; ++dw) {
@@ -421,7 +421,7 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kBcast>(a.vec[v], opos, s.col[0], g.c);
+                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], opos, s.col[0], g.c);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
