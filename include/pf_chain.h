@@ -241,9 +241,12 @@ pf_status pf_chain_recompose(const pf_chain_desc *desc, pf_chain_desc *out, int3
  * and writes over the rate its kernel family reaches; pf_chain_partition returns the split with the smallest
  * total, pf_chain_segment_cost the price of operators first_op .. last_op - 1 as one kernel (an error status when
  * they are not one kernel; us and bytes may be NULL).  Values that cross from one kernel to the next are stored in
- * out_dtype[0].  pf_chain_plan applies the split by itself when a chain is not one kernel (PF_PARTITION=0 in the
- * environment: PF_ERR_UNSUPPORTED instead); such a plan owns the tensors between its kernels, must not run on
- * two streams at the same time, and returns PF_ERR_ALIAS when an output overlaps an input.
+ * fp32 whatever the storage type, so that a chain of several kernels still computes in fp32 from its first load to
+ * its last store and rounds once: on 16-bit storage its inputs are widened and its outputs rounded by conversion
+ * copies around the kernels, priced with the first and the last kernel.  pf_chain_plan applies the split by itself
+ * when a chain is not one kernel (PF_PARTITION=0 in the environment: PF_ERR_UNSUPPORTED instead); such a plan owns
+ * the tensors between its kernels, must not run on two streams at the same time, and returns PF_ERR_ALIAS when an
+ * output overlaps an input.
  */
 pf_status pf_chain_partition(const pf_chain_desc *desc, pf_partition *out);
 pf_status pf_chain_segment_cost(const pf_chain_desc *desc, int32_t first_op, int32_t last_op, double *us, uint64_t *bytes);

@@ -399,12 +399,9 @@ def _eval_op(op, vals: List[np.ndarray]) -> np.ndarray:
     raise KeyError(f"oracle: unknown op {name}")
 
 
-def evaluate(spec, inputs: Sequence[np.ndarray], stored=None) -> List[np.ndarray]:
-    """Evaluate the chain on float64 inputs.  Returns every value (inputs first, then one per op).
-
-    `stored` maps value ids to a rounding function: those values are kept in a tensor of the storage type between
-    two kernels (section 6: merged graphs exchange tensors through global memory), so operators after them see the
-    rounded value, as they would between two operators of an unfused framework.  Without it nothing is rounded."""
+def evaluate(spec, inputs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Evaluate the chain on float64 inputs.  Returns every value (inputs first, then one per op); nothing is
+    rounded anywhere."""
     if len(inputs) != len(spec.inputs):
         raise ValueError("oracle: wrong number of inputs")
     vals: List[np.ndarray] = []
@@ -414,15 +411,12 @@ def evaluate(spec, inputs: Sequence[np.ndarray], stored=None) -> List[np.ndarray
             raise ValueError(f"oracle: input shape {arr.shape} != declared {shape}")
         vals.append(arr)
     for op in spec.ops:
-        r = _eval_op(op, vals)
-        if stored and len(vals) in stored:
-            r = _f64(stored[len(vals)](r))
-        vals.append(r)
+        vals.append(_eval_op(op, vals))
     return vals
 
 
-def evaluate_outputs(spec, inputs: Sequence[np.ndarray], stored=None) -> List[np.ndarray]:
-    vals = evaluate(spec, inputs, stored)
+def evaluate_outputs(spec, inputs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    vals = evaluate(spec, inputs)
     return [vals[v] for v, _ in spec.outputs]
 
 

@@ -18,7 +18,7 @@ OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(LIBDIR, "libpf_chain.so")
 
 SOURCES = ["pf_host.cpp", "pf_check.cpp", "pf_recompose.cpp", "pf_lower.cpp", "pf_plan.cpp", "pf_partition.cpp", "pf_jit.cpp", "pf_run_static.cpp", "pf_row_generic.hip", "pf_row_stream.hip", "pf_row_static.hip", "pf_row_static_f32.hip", "pf_row_static_f16.hip",
-           "pf_row_static_bf16.hip", "pf_perm.hip", "pf_group.hip", "pf_attn.hip", "pf_gather.hip", "pf_stencil.hip", "pf_pool.hip", "pf_col.hip"]
+           "pf_row_static_bf16.hip", "pf_perm.hip", "pf_group.hip", "pf_attn.hip", "pf_gather.hip", "pf_stencil.hip", "pf_pool.hip", "pf_col.hip", "pf_cast.hip"]
 HEADERS = ["pf_common.h", "pf_host_internal.h", "pf_chain.map", "pf_device.hpp", "pf_jit.h", "pf_launch.h", "pf_row_kernels.hpp", "pf_row_stream.hpp", "pf_perm_kernels.hpp", "pf_group_kernels.hpp", "pf_stencil_kernels.hpp", "pf_pool_kernels.hpp", "pf_col_kernels.hpp", "pf_specs.h", "pf_row_static.inc",
            os.path.join("..", "..", "include", "pf_chain.h")]
 

@@ -167,6 +167,10 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
                 const uintptr_t ob = (uintptr_t)outputs[o], oe = ob + plan->out_bytes[o], ib = (uintptr_t)inputs[k], ie = ib + plan->in_bytes[k];
                 if (ob < ie && ib < oe) return fail(PF_ERR_ALIAS, "output %d overlaps input %d (the chain runs as several kernels)", o, k);
             }
+        for (const pf_plan_s::Cast& w : plan->widen_in) {
+            const hipError_t ew = pf::launch_cast(d.inputs[w.user].dtype, PF_F32, inputs[w.user], (char*)plan->arena + plan->arena_offset[w.slot], w.numel, (hipStream_t)stream);
+            if (ew != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(ew));
+        }
         for (const pf_plan_s::Part& pp : plan->parts) {
             const void* in[PF_MAX_INPUTS];
             void* outp[PF_MAX_OUTPUTS];
@@ -176,6 +180,10 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
                 outp[o] = pp.out_kind[o] == 1 ? outputs[pp.out_index[o]] : (void*)((char*)plan->arena + plan->arena_offset[pp.out_index[o]]);
             const pf_status ps = pf_chain_run(pp.plan, in, outp, stream);
             if (ps != PF_OK) return ps;
+        }
+        for (const pf_plan_s::Cast& r : plan->round_out) {
+            const hipError_t er = pf::launch_cast(PF_F32, d.out_dtype[r.user], (const char*)plan->arena + plan->arena_offset[r.slot], outputs[r.user], r.numel, (hipStream_t)stream);
+            if (er != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(er));
         }
         return PF_OK;
     }

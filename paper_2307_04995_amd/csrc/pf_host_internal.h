@@ -159,6 +159,15 @@ struct pf_plan_s {
         int in_kind[PF_MAX_INPUTS], in_index[PF_MAX_INPUTS];     // kind 0: the caller's input, 1: the caller's output, 2: tensor in the arena
         int out_kind[PF_MAX_OUTPUTS], out_index[PF_MAX_OUTPUTS];
     };
+    // a chain of several kernels on 16-bit storage runs in fp32 between its first load and its last store: inputs are
+    // widened into the arena before the first kernel, outputs rounded from the arena after the last
+    struct Cast {
+        int user = 0;          // index of the caller's input / output
+        int slot = 0;          // index into arena_offset
+        uint64_t numel = 0;
+    };
+    std::vector<Cast> widen_in, round_out;
+    int storage_dtype = PF_F32;
     bool composite = false;
     std::vector<Part> parts;
     pf_partition partition;               // the cut points in use (composite plans)

@@ -27,6 +27,8 @@ hipError_t launch_pool(int dtype, const ChainArgs& a, const PoolGeom& g, int op,
 hipError_t launch_colnorm(int dtype, const ColArgs& a, int kc, bool rms, bool ragged, dim3 grid, hipStream_t st);
 hipError_t launch_gather(int dtype, const GatherArgs& a, dim3 grid, hipStream_t st);
 int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads);
+// whole-tensor storage conversion, 16-bit <-> fp32 (n elements)
+hipError_t launch_cast(int src_dtype, int dst_dtype, const void* src, void* dst, uint64_t n, hipStream_t st);
 hipError_t launch_copy_probe(const void* src, void* dst, uint64_t bytes, int variant, hipStream_t st);
 
 }  // namespace pf

@@ -5,8 +5,10 @@
 // exchanges could go to either side.  The paper generates the candidate merge plans and picks one with a
 // performance model that predicts a merged graph's time from its regular data movement (section 6, graph
 // merging).  Here a merge plan is a set of cut points in the chain's operator order; the values that cross a cut
-// are stored in device memory in the chain's storage dtype, like the tensors between two operators of an unfused
-// framework.  Every segment must lower to one kernel on its own; the model prices a segment at a launch cost plus
+// are stored in device memory in fp32, whatever the chain's storage type: a chain computes in fp32 from its first
+// load to its last store and rounds once, whether it is one kernel or several (a 16-bit chain of several kernels has
+// its inputs widened and its outputs rounded by two conversion copies around the kernels, which the model prices).
+// Every segment must lower to one kernel on its own; the model prices a segment at a launch cost plus
 // the bytes it reads and writes over the bandwidth its kernel family reaches, and a dynamic programme over the
 // cut points returns the cheapest plan under that model (the full search the paper prunes is tractable here
 // because a chain has one operator order).
@@ -48,6 +50,31 @@ struct Segment {
     uint64_t bytes = 0;
     double us = 0.0;
 };
+
+// The fp32 twin of a chain on 16-bit storage (same operators, every input and output fp32); false when the chain is
+// fp32 already.
+bool widened_twin(const pf_chain_desc* d, pf_chain_desc* twin) {
+    if (d->n_outputs < 1 || d->out_dtype[0] == PF_F32) return false;
+    *twin = *d;
+    for (int k = 0; k < twin->n_inputs; ++k) twin->inputs[k].dtype = PF_F32;
+    for (int o = 0; o < twin->n_outputs; ++o) twin->out_dtype[o] = PF_F32;
+    return true;
+}
+
+// what the two conversion copies around the kernels of such a chain move
+void cast_costs(const pf_chain_desc* d, const Checked& c, uint64_t* in_bytes, uint64_t* out_bytes) {
+    *in_bytes = *out_bytes = 0;
+    for (int k = 0; k < d->n_inputs; ++k) *in_bytes += (uint64_t)numel(c.shape[k]) * (dtype_size(d->inputs[k].dtype) + 4);
+    for (int o = 0; o < d->n_outputs; ++o) *out_bytes += (uint64_t)numel(c.shape[d->out_value[o]]) * (dtype_size(d->out_dtype[o]) + 4);
+}
+
+// The conversion copies of a split chain on 16-bit storage are priced with its first and its last kernel.
+void add_cast_costs(const pf_chain_desc* user, const Checked& c, int first, int last, uint64_t* bytes, double* us) {
+    uint64_t in_bytes, out_bytes;
+    cast_costs(user, c, &in_bytes, &out_bytes);
+    if (first == 0) *bytes += in_bytes, *us += user->n_inputs * kLaunchUs + (double)in_bytes / (kCopyBytesPerUs * 0.97);
+    if (last == user->n_ops) *bytes += out_bytes, *us += user->n_outputs * kLaunchUs + (double)out_bytes / (kCopyBytesPerUs * 0.97);
+}
 
 }  // namespace
 
@@ -133,16 +160,25 @@ pf_status segment_cost(const pf_chain_desc* d, int first, int last, double* us, 
     pf_status st = check_desc(d, &c);
     if (st != PF_OK) return st;
     if (first < 0 || last > d->n_ops || first >= last) return fail(PF_ERR_INVALID_ARG, "operator range [%d, %d) is empty or outside the chain", first, last);
+    // (a chain on 16-bit storage that is split runs as its fp32 twin: that is what a segment of it costs)
+    pf_chain_desc twin;
+    const bool whole = first == 0 && last == d->n_ops;
+    const pf_chain_desc* dd = (!whole && widened_twin(d, &twin)) ? &twin : d;
     Segment seg;
-    st = build_segment(d, c, first, last, &seg);
+    st = build_segment(dd, c, first, last, &seg);
     if (st != PF_OK) return st;
+    if (dd != d) add_cast_costs(d, c, first, last, &seg.bytes, &seg.us);
     if (us) *us = seg.us;
     if (bytes) *bytes = seg.bytes;
     return PF_OK;
 }
 
 // The cheapest set of cuts under the model, never using a segment listed in `blocked` (pairs first, last).
-pf_status partition_chain(const pf_chain_desc* d, const Checked& c, const std::vector<std::pair<int, int>>& blocked, pf_partition* out) {
+pf_status partition_chain(const pf_chain_desc* user, const Checked& c, const std::vector<std::pair<int, int>>& blocked, pf_partition* out) {
+    // a chain on 16-bit storage is split as its fp32 twin
+    pf_chain_desc twin;
+    const bool widen = widened_twin(user, &twin);
+    const pf_chain_desc* d = widen ? &twin : user;
     const int n = d->n_ops;
     const double inf = 1e300;
     std::vector<double> best(n + 1, inf), seg_us((size_t)(n + 1) * (n + 1), 0.0);
@@ -155,10 +191,12 @@ pf_status partition_chain(const pf_chain_desc* d, const Checked& c, const std::v
             if (best[first] >= inf) continue;
             if (std::find(blocked.begin(), blocked.end(), std::make_pair(first, last)) != blocked.end()) continue;
             Segment seg;
-            if (build_segment(d, c, first, last, &seg) != PF_OK) {
+            const bool whole = first == 0 && last == n;  // (the chain as one kernel runs on its own storage type)
+            if (build_segment(whole ? user : d, c, first, last, &seg) != PF_OK) {
                 if (first_error.empty()) first_error = last_error();
                 continue;
             }
+            if (widen && !whole) add_cast_costs(user, c, first, last, &seg.bytes, &seg.us);
             seg_us[(size_t)first * (n + 1) + last] = seg.us;
             seg_bytes[(size_t)first * (n + 1) + last] = seg.bytes;
             const double t = best[first] + seg.us;
@@ -182,25 +220,45 @@ pf_status partition_chain(const pf_chain_desc* d, const Checked& c, const std::v
 
 // Plans every segment of the cheapest partition; a segment the device-side planning refuses is struck out and the
 // search runs again.
-pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out) {
+pf_status plan_partitioned(const pf_chain_desc* user, int32_t device, pf_plan** out) {
     Checked c;
-    pf_status st = check_desc(d, &c);
+    pf_status st = check_desc(user, &c);
     if (st != PF_OK) return st;
+    // kernels are planned for the fp32 twin of a chain on 16-bit storage; the plan widens and rounds around them
+    pf_chain_desc twin;
+    const bool widen = widened_twin(user, &twin);
+    const pf_chain_desc* d = widen ? &twin : user;
     std::vector<std::pair<int, int>> blocked;
     blocked.push_back(std::make_pair(0, (int)d->n_ops));  // the caller has tried the whole chain as one kernel
     for (int attempt = 0; attempt < 64; ++attempt) {
         pf_partition part;
-        st = partition_chain(d, c, blocked, &part);
+        st = partition_chain(user, c, blocked, &part);
         if (st != PF_OK) return st;
         pf_plan_s* p = new (std::nothrow) pf_plan_s();
         if (!p) return fail(PF_ERR_NOMEM, "out of host memory");
-        p->desc = *d;
+        p->desc = *user;
         p->device = device;
         p->composite = true;
-        // values that cross a cut and are not chain outputs live in one arena the plan owns
+        p->storage_dtype = user->out_dtype[0];
+        // Tensors the plan owns live in one arena: values that cross a cut and are not chain outputs and, for a chain
+        // on 16-bit storage, the fp32 copies of its inputs and outputs.
         std::vector<int> where(d->n_inputs + d->n_ops, -1);  // value id -> index into arena_offset
         std::vector<uint64_t> arena_offset;
         uint64_t arena_bytes = 0;
+        auto arena_add = [&](int v) {
+            where[v] = (int)arena_offset.size();
+            arena_offset.push_back(arena_bytes);
+            arena_bytes += ((uint64_t)numel(c.shape[v]) * sizeof(float) + 255) / 256 * 256;
+            return where[v];
+        };
+        if (widen) {
+            for (int k = 0; k < d->n_inputs; ++k) p->widen_in.push_back(pf_plan_s::Cast{k, arena_add(k), (uint64_t)numel(c.shape[k])});
+            for (int o = 0; o < d->n_outputs; ++o) {
+                const int v = d->out_value[o];
+                if (where[v] < 0) arena_add(v);  // (two outputs may name one value)
+                p->round_out.push_back(pf_plan_s::Cast{o, where[v], (uint64_t)numel(c.shape[v])});
+            }
+        }
         bool ok = true;
         for (int k = 0; k < part.n_parts && ok; ++k) {
             Segment seg;
@@ -219,26 +277,25 @@ pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out
             for (int i = 0; i < seg.n_in; ++i) {
                 const int v = seg.in_value[i];
                 if (v < d->n_inputs) {
-                    pp.in_kind[i] = 0, pp.in_index[i] = v;
+                    if (widen) pp.in_kind[i] = 2, pp.in_index[i] = where[v];
+                    else pp.in_kind[i] = 0, pp.in_index[i] = v;
                     continue;
                 }
-                int user = -1;
+                int user_out = -1;
                 for (int o = 0; o < d->n_outputs; ++o)
-                    if (d->out_value[o] == v) user = o;
-                if (user >= 0) pp.in_kind[i] = 1, pp.in_index[i] = user;
+                    if (d->out_value[o] == v) user_out = o;
+                if (user_out >= 0 && !widen) pp.in_kind[i] = 1, pp.in_index[i] = user_out;
                 else pp.in_kind[i] = 2, pp.in_index[i] = where[v];
             }
             for (int o = 0; o < seg.n_out; ++o) {
                 const int v = seg.out_value[o];
-                int user = -1;
+                int user_out = -1;
                 for (int u = 0; u < d->n_outputs; ++u)
-                    if (d->out_value[u] == v) user = u;
-                if (user >= 0) {
-                    pp.out_kind[o] = 1, pp.out_index[o] = user;
+                    if (d->out_value[u] == v) user_out = u;
+                if (user_out >= 0 && !widen) {
+                    pp.out_kind[o] = 1, pp.out_index[o] = user_out;
                 } else {
-                    where[v] = (int)arena_offset.size();
-                    arena_offset.push_back(arena_bytes);
-                    arena_bytes += ((uint64_t)numel(c.shape[v]) * dtype_size(d->out_dtype[0]) + 255) / 256 * 256;
+                    if (where[v] < 0) arena_add(v);
                     pp.out_kind[o] = 2, pp.out_index[o] = where[v];
                 }
             }
@@ -259,12 +316,12 @@ pf_status plan_partitioned(const pf_chain_desc* d, int32_t device, pf_plan** out
             p->variant = p->parts[0].plan->variant;
             p->grid = p->parts[0].plan->grid;
             p->block = p->parts[0].plan->block;
-            p->n_launches = 0;
+            p->n_launches = (int)(p->widen_in.size() + p->round_out.size());
             for (const pf_plan_s::Part& pp : p->parts) p->n_launches += pp.plan->n_launches;
-            for (int k = 0; k < d->n_inputs; ++k) p->in_bytes[k] = (uint64_t)numel(c.shape[k]) * dtype_size(d->inputs[k].dtype);
+            for (int k = 0; k < d->n_inputs; ++k) p->in_bytes[k] = (uint64_t)numel(c.shape[k]) * dtype_size(user->inputs[k].dtype);
             for (int o = 0; o < d->n_outputs; ++o) {
                 p->out_shape[o] = c.shape[d->out_value[o]];
-                p->out_bytes[o] = (uint64_t)numel(p->out_shape[o]) * dtype_size(d->out_dtype[o]);
+                p->out_bytes[o] = (uint64_t)numel(p->out_shape[o]) * dtype_size(user->out_dtype[o]);
             }
             if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf_chain] %d kernels, %llu bytes between them\n", (int)p->parts.size(), (unsigned long long)arena_bytes);
             *out = p;

@@ -108,104 +108,14 @@ def ulp_histogram(got: torch.Tensor, want: np.ndarray, dtype: str):
             ">8": int(counts[5]), "max": int(d.max()) if d.size else 0, "elements": int(d.size)}
 
 
-# ---- chains that run as several kernels: the tensors between kernels are stored in the chain's storage type ----
-
-def crossing_values(spec, parts):
-    """Value ids produced in one part of a split chain and used in a later one."""
-    n_in = len(spec.inputs)
-    part_of = {}
-    for k, (a, b, _, _) in enumerate(parts):
-        for op in range(a, b):
-            part_of[n_in + op] = k
-    crossing = set()
-    for k, op in enumerate(spec.ops):
-        for v in op.src:
-            if v >= n_in and part_of[v] != part_of[n_in + k]:
-                crossing.add(v)
-    return sorted(crossing)
-
-
-def round_to(dtype, nudge_seed=None):
-    """Rounding of a float64 array to the storage type; with a seed, every value is then moved one unit in the last
-    place up or down at random (what a stored tensor may differ by when it was computed in fp32 instead of fp64)."""
-    if dtype == "f32":
-        return lambda a: a.astype(np.float32)
-
-    def rnd(a):
-        t = torch.from_numpy(np.ascontiguousarray(a)).to(TORCH_DT[dtype])
-        if nudge_seed is not None:
-            g = np.random.default_rng(nudge_seed + a.size)
-            step = torch.from_numpy(g.choice(np.array([-1, 1], dtype=np.int16), size=a.shape))
-            bits = t.view(torch.int16)
-            ok = torch.isfinite(t) & ((bits & 0x7fff) > 1)
-            t = torch.where(ok, bits + step, bits).view(TORCH_DT[dtype])
-        return t.to(torch.float64).numpy()
-    return rnd
-
-
-def oracle_with_storage(spec, inputs, dtype, nudge=None, parts=None):
-    """The oracle with the values that cross between the kernels of a split rounded to the storage type.  `parts` is
-    the split (structure only: which operators each kernel runs; a plan reports its own), by default the one
-    pf_chain_partition returns.  nudge = (value id, seed): that stored tensor is also moved by one unit in the last
-    place per element."""
-    from oracle import pf_oracle as orc
-    if parts is None:
-        from paper_2307_04995_amd import binding as pf
-        st, parts = pf.pf_chain_partition(pf.make_desc(spec))
-        assert st == pf.PF_OK
-    stored = {v: round_to(dtype) for v in crossing_values(spec, parts)}
-    if nudge is not None:
-        stored[nudge[0]] = round_to(dtype, nudge[1])
-    return orc.evaluate_outputs(spec, [wl.widen(t) for t in inputs], stored)
-
-
-def compare_split_16bit(spec, inputs, outs, dtype, what, parts):
-    """The 16-bit bars for a chain that ran as several kernels.  A tensor stored between two kernels may differ by
-    one unit in the last place from the oracle's (fp32 against fp64 arithmetic before the rounding); where later
-    operators amplify that (differences of nearly equal values), no implementation can meet the relative bar.
-    Such elements are recognised by the oracle itself: for every stored tensor in turn, its result with that
-    tensor's values moved one unit up or down at random (two draws), and the largest effects summed over the
-    tensors.  An element passes with a relative error within the bar, or an error within twice that sum; the
-    absolute bar holds everywhere, and the plain relative bar on at least 95 % of the elements."""
-    wants = oracle_with_storage(spec, inputs, dtype, parts=parts)
-    effect = [np.zeros_like(w) for w in wants]
-    for v in crossing_values(spec, parts):
-        worst = [np.zeros_like(w) for w in wants]
-        for seed in (977, 1979):
-            nudged = oracle_with_storage(spec, inputs, dtype, nudge=(v, seed), parts=parts)
-            worst = [np.maximum(a, np.abs(n - w)) for a, n, w in zip(worst, nudged, wants)]
-        effect = [e + a for e, a in zip(effect, worst)]
-    for got, want, eff in zip(outs, wants, effect):
-        g = wl.widen(got)
-        assert g.shape == want.shape and np.all(np.isfinite(want)) and np.all(np.isfinite(g)), what
-        diff = np.abs(g - want)
-        assert diff.max() <= H_ABS, f"{what}: max-abs {diff.max():.3e} > {H_ABS}"
-        big = np.abs(want) >= REL_FLOOR
-        within = diff <= H_REL * np.abs(want)
-        explained = diff <= 2.0 * eff
-        bad = big & ~within & ~explained
-        assert not bad.any(), (f"{what}: {bad.sum()} elements beyond the relative bar that stored rounding does not explain "
-                               f"(worst {(diff[bad] / np.abs(want[bad])).max():.3e})")
-        assert (big & within).sum() >= 0.95 * big.sum(), f"{what}: only {(big & within).sum()} of {big.sum()} elements within the relative bar"
-
-
-
 SPEC_JIT = 255   # plan info spec_id of a kernel specialised for the chain when the plan was made
 
 
 def check_chain(spec, inputs, variant=None, generic=False, what=""):
+    """Run the chain as planned and compare every output with the oracle at the bars above: one comparison for every
+    chain, whether it runs as one kernel or as several."""
     outs, info = gpu_run(spec, inputs, variant=variant, generic=generic)
     stats = []
-    if info.n_kernels > 1:
-        # several kernels: the tensors between them are rounded to the storage type, and so are the oracle's
-        dt0 = spec.outputs[0][1]
-        if dt0 == "f32":
-            for o, w, u in zip(outs, oracle_with_storage(spec, inputs, dt0, parts=info.parts), oracle_run(spec, inputs)):
-                stats.append(compare(o, w, "f32", what))
-                compare(o, u, "f32", what + " (unrounded)")
-        else:
-            compare_split_16bit(spec, inputs, outs, dt0, what, info.parts)
-        return outs, info, stats
     wants = oracle_run(spec, inputs)
     for o, w, (_, dt) in zip(outs, wants, spec.outputs):
         stats.append(compare(o, w, dt, what))

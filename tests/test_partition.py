@@ -36,14 +36,22 @@ def _brute_force(desc, n_ops):
     return best
 
 
-def test_layout_norm_layout_is_three_kernels_with_the_bytes_of_its_tensors():
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_layout_norm_layout_is_three_kernels_with_the_bytes_of_its_tensors(dtype):
     n, c, h, w = 8, 96, 56, 56
-    d = pf.make_desc(_convnext_norm(n, c, h, w, "f16"))
+    d = pf.make_desc(_convnext_norm(n, c, h, w, dtype))
     st, parts = pf.pf_chain_partition(d)
     assert st == pf.PF_OK
     assert [(a, b) for a, b, _, _ in parts] in ([(0, 2), (2, 3), (3, 4)], [(0, 1), (1, 3), (3, 4)])  # the activation goes with either neighbour
-    t = n * c * h * w * 2
-    assert [nb for _, _, _, nb in parts] == [2 * t, 2 * t + 2 * c * 2, 2 * t]
+    # every kernel moves fp32 tensors, whatever the storage type: a split chain rounds once, at its end
+    t = n * c * h * w * 4
+    want = [2 * t, 2 * t + 2 * c * 4, 2 * t]
+    if dtype == "f16":
+        # ... and the copies that widen the inputs (2 bytes read, 4 written per element) and round the output are
+        # priced with the first and the last kernel
+        want[0] += (n * c * h * w + 2 * c) * 6
+        want[2] += n * c * h * w * 6
+    assert [nb for _, _, _, nb in parts] == want
     for a, b, us, nb in parts:
         st, us2, nb2 = pf.pf_chain_segment_cost(d, a, b)
         assert st == pf.PF_OK and us2 == us and nb2 == nb
