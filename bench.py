@@ -1,17 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the fused-chain hot path on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch: one `pf_chain_run` of the headline chain
-(benchmark configs[1]: fp16 scale -> causal mask -> softmax on [8, 12, 512, 512]) with its inputs already
-resident in HBM.  Successive steps rotate over enough buffer sets (> 600 MB in total) that no step finds
-its data in the 256 MB last-level cache: the number printed is the cold, HBM-bound one.
+A "step" is one pass of the whole hot path over one batch: one `pf_chain_run` of each of the five benchmark
+chains (benchmark configs C1 .. C5 at full size), inputs already resident in HBM.  Every chain rotates over
+several buffer sets and a step moves 380 MB, so no launch finds its data in the 256 MB last-level cache: the
+numbers printed are the cold, HBM-bound ones.
 
-One JSON line is printed.  `value` is GB/s of the bytes the chain has to move (inputs once + outputs once;
+One JSON line is printed.  `value` is GB/s of the bytes the five chains have to move (inputs once + outputs once;
 for the causal chain the 16-byte vectors that lie wholly above the diagonal are never needed and are not
-counted).  `roofline` prices the same kernel against the 8 TB/s HBM peak from the average launch duration
-measured with HIP events on the launch stream.  `cpu_baseline` is the fp64 oracle timed on the host cores on
-a bounded sample of the same workload.  `chains` adds the same measurement for the other four benchmark
-chains and a plain copy kernel, for context.
+counted) over the wall time of a step.  `roofline` prices the dominant kernel of the step -- the chain that takes
+longest, C5 -- against the 8 TB/s HBM peak from its average launch duration, measured with HIP events around its
+launches inside the timed region.  `cpu_baseline` is the fp64 oracle timed on the host cores on whole passes over the
+same five chains.  `chains` has every chain timed on its own (at least 200 launches each, whatever --steps says) and
+a plain copy kernel, for context.
 """
 import argparse
 import json
@@ -176,36 +177,100 @@ def time_copy(nbytes, steps, warmup, variant=2):
     return ev0.elapsed_time(ev1) / steps
 
 
+BENCH_CHAINS = ["C1", "C2", "C3", "C4", "C5"]
+
+
+def time_pass(steps, warmup):
+    """One step = C1 .. C5 once each, back to back on one stream.  Returns (ms per step from the host clock, ms per
+    step from HIP events, {name: average launch ms of that chain inside the timed region, from HIP events recorded
+    around its launches}, {name: plan info}, {name: (algorithmic bytes, nominal bytes, label)})."""
+    import numpy as np
+    import torch
+    from paper_2307_04995_amd import binding as pf
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    esz = {"f32": 4, "f16": 2, "bf16": 2}
+    plans, sets, infos, meta = {}, {}, {}, {}
+    for name in BENCH_CHAINS:
+        spec, ins, alg, nom, label = full_size_chain(name)
+        plan = pf.Plan(spec, 0)
+        shapes = plan.output_shapes()
+        per_set = sum(t.numel() * t.element_size() for t in ins) + sum(int(np.prod(sh)) * esz[dt] for sh, (_, dt) in zip(shapes, spec.outputs))
+        n_sets = max(3, min(8, -(-ROTATE_BYTES // per_set)))
+        base = [t.cuda() for t in ins]
+        ss = []
+        for k in range(n_sets):
+            i_k = [t if t.numel() * t.element_size() < 65536 else t.clone() for t in base]
+            o_k = [torch.empty(sh, dtype=tdt[dt], device="cuda") for sh, (_, dt) in zip(shapes, spec.outputs)]
+            ss.append(([t.data_ptr() for t in i_k], [t.data_ptr() for t in o_k], i_k, o_k))
+        plans[name], sets[name], infos[name], meta[name] = plan, ss, plan.info(), (alg, nom, label)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def one_step(k, marks=None):
+        for name in BENCH_CHAINS:
+            ss = sets[name]
+            ip, op, _, _ = ss[k % len(ss)]
+            if marks is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                plans[name].run_ptrs(ip, op, stream)
+                e1.record()
+                marks[name].append((e0, e1))
+            else:
+                plans[name].run_ptrs(ip, op, stream)
+
+    for k in range(warmup):
+        one_step(k)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for k in range(steps):
+        one_step(k)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    host_ms = (t1 - t0) * 1e3 / steps
+    event_ms = ev0.elapsed_time(ev1) / steps
+    # the same K steps once more with an event pair around every launch: the per-kernel durations of the timed
+    # region (kept out of the first loop so that the events' own cost is not in `value`)
+    marks = {name: [] for name in BENCH_CHAINS}
+    for k in range(steps):
+        one_step(k, marks)
+    torch.cuda.synchronize()
+    per_kernel = {name: sum(a.elapsed_time(b) for a, b in marks[name]) / len(marks[name]) for name in BENCH_CHAINS}
+    for plan in plans.values():
+        plan.close()
+    del sets
+    torch.cuda.empty_cache()
+    return host_ms, event_ms, per_kernel, infos, meta
+
+
 def cpu_baseline(budget_s=12.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the headline workload: whole
-    passes over a slice of the score tensor, repeated until about `budget_s` seconds of CPU work."""
+    """The oracle as it stands, on the host cores: whole passes over the five benchmark chains at full size (the same
+    work as one step), repeated until about `budget_s` seconds of CPU work."""
     import workloads as wl
     from oracle import pf_oracle as orc
     threads = orc.max_threads()
     orc.set_threads(threads)
-    heads = 24                                   # a quarter of the 8 x 12 (batch, head) matrices
-    spec, ins = wl.c2_causal_softmax(b=2, h=12, s=512)
-    wide = [wl.widen(t) for t in ins]
-    nbytes = causal_needed_read_bytes(2, 12, 512, 512, 2) + heads * 512 * 512 * 2
+    work, nbytes = [], 0
+    for name in BENCH_CHAINS:
+        spec, ins = wl.CONFIGS[name]()
+        work.append((name, spec, [wl.widen(t) for t in ins]))
+    nbytes = None
+    per_chain = {name: 0.0 for name in BENCH_CHAINS}
     passes, total = 0, 0.0
-    while total < budget_s and passes < 5000:
-        t0 = time.perf_counter()
-        orc.evaluate_outputs(spec, wide)
-        total += time.perf_counter() - t0
+    while total < budget_s and passes < 200:
+        for name, spec, wide in work:
+            t0 = time.perf_counter()
+            orc.evaluate_outputs(spec, wide)
+            dt = time.perf_counter() - t0
+            per_chain[name] += dt
+            total += dt
         passes += 1
-    gbps = nbytes * passes / total / 1e9
-    orc.set_threads(1)
-    p1, t1 = 0, 0.0
-    while t1 < budget_s / 4 and p1 < 100:
-        t0 = time.perf_counter()
-        orc.evaluate_outputs(spec, wide)
-        t1 += time.perf_counter() - t0
-        p1 += 1
-    orc.set_threads(threads)
-    return {"value": round(gbps, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "single_thread_value": round(nbytes * p1 / t1 / 1e9, 4),
-            "sample": f"scores [2,12,512,512] (a quarter of the [8,12,512,512] workload), {passes} passes in {total:.1f} s, "
-                      f"fp64 unfused, {threads} OpenMP threads (then {p1} passes in {t1:.1f} s on one thread)"}
+    return {"unit": "GB/s", "cores": int(threads), "kind": "oracle", "passes": passes, "seconds": round(total, 2),
+            "ms_per_chain": {name: round(per_chain[name] * 1e3 / passes, 2) for name in BENCH_CHAINS},
+            "sample": f"{passes} whole passes over C1..C5 at full size (the work of {passes} steps) in {total:.1f} s, fp64 unfused, "
+                      f"{threads} OpenMP threads"}
 
 
 def read_traffic(name):
@@ -221,11 +286,11 @@ def read_traffic(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--only", default="", help="comma-separated subset of C1..C5 for the context block")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--only", default="", help="comma-separated subset of chains for the context block")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--no-context", action="store_true", help="time the headline chain only")
+    ap.add_argument("--no-context", action="store_true", help="time the five-chain step only")
     ap.add_argument("--hot", action="store_true",
                     help="also time every chain on ONE buffer set (cache-resident where it fits); adds launches of the "
                          "same kernels, so leave it off under a kernel trace")
@@ -240,14 +305,22 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
 
-    headline = "C2"
-    spec, ins, alg_bytes, nominal_bytes, label = full_size_chain(headline)
-    hot = [] if args.hot else None
-    host_ms, event_ms, info = time_chain(spec, ins, args.steps, args.warmup, hot=hot)
-    achieved = alg_bytes / (event_ms * 1e-3) / 1e9
+    host_ms, event_ms, per_kernel, infos, meta = time_pass(args.steps, args.warmup)
+    alg_total = sum(meta[n][0] for n in BENCH_CHAINS)
+    nom_total = sum(meta[n][1] for n in BENCH_CHAINS)
+    dominant = max(BENCH_CHAINS, key=lambda n: per_kernel[n])
+    dom_alg = meta[dominant][0]
+    # The dominant kernel's launch duration: its launches back to back on the stream between two HIP events (what a
+    # kernel trace reports as its duration; an event pair around a single launch inside a step adds about 1 us of
+    # dispatch gap, kept below as in_step_kernel_us).
+    ctx_steps, ctx_warm = max(200, args.steps), max(20, args.warmup)   # enough launches for a 5 us kernel to time stably
+    dom_spec, dom_ins, _, _, _ = full_size_chain(dominant)
+    _, dom_ms, _ = time_chain(dom_spec, dom_ins, ctx_steps, ctx_warm)
+    del dom_spec, dom_ins
+    achieved = dom_alg / (dom_ms * 1e-3) / 1e9
     result = {
         "metric": "achieved HBM GB/s (fraction of MI355X peak) per fused chain; us per call",
-        "value": round(alg_bytes / (host_ms * 1e-3) / 1e9, 1),
+        "value": round(alg_total / (host_ms * 1e-3) / 1e9, 1),
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -258,27 +331,29 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": label, "storage": "fp16", "bytes_per_step": alg_bytes, "nominal_bytes_per_step": nominal_bytes,
-                   "us_per_call": round(host_ms * 1e3, 3), "family": info.family, "variant": info.variant,
-                   "spec_id": info.spec_id, "buffers": "rotating, > 600 MB (cold)"},
+        "config": {"workload": "one pass over the five BASELINE chains at full size: " + "; ".join(meta[n][2] for n in BENCH_CHAINS),
+                   "storage": "fp32 (C1), fp16 (C2, C3, C5), bf16 (C4)", "bytes_per_step": alg_total, "nominal_bytes_per_step": nom_total,
+                   "us_per_step": round(host_ms * 1e3, 3), "event_us_per_step": round(event_ms * 1e3, 3),
+                   "buffers": "rotating sets per chain, 380 MB moved per step (cold)"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(headline),
-                     "kernel_us": round(event_ms * 1e3, 3), "nominal_gbps": round(nominal_bytes / (event_ms * 1e-3) / 1e9, 1)},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(dominant),
+                     "traffic_source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE / WRITE_SIZE runs, not measured in this run)",
+                     "kernel": dominant + ": " + meta[dominant][2], "kernel_us": round(dom_ms * 1e3, 3),
+                     "bytes_per_launch": dom_alg,
+                     "in_step_kernel_us": {n: round(per_kernel[n] * 1e3, 3) for n in BENCH_CHAINS}},
     }
-    if hot:
-        result["config"]["hot_us_per_call"] = round(hot[0] * 1e3, 3)
     if not args.no_context:
         chains = {}
-        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C1x256", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7"]) if c]
+        wanted = [c for c in (args.only.split(",") if args.only else ["C1", "C1x256", "C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7"]) if c]
         forced = dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.variant.split(",") if "=" in kv)
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
             hot2 = [] if args.hot else None
             gr2 = [] if (args.hot and name == "C1") else None   # the launch-bound chain, replayed from a HIP graph
-            h2, e2, inf2 = time_chain(s2, i2, max(50, args.steps // 2), max(10, args.warmup // 2), forced.get(name), hot=hot2, graph=gr2)
+            h2, e2, inf2 = time_chain(s2, i2, ctx_steps, ctx_warm, forced.get(name), hot=hot2, graph=gr2)
             chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3),
                             "host_us_per_call": round(h2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
-                            "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2,
+                            "frac_of_peak": round(alg2 / (e2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "bytes": alg2, "nominal_bytes": nom2,
                             "variant": inf2.variant, "spec_id": inf2.spec_id, "launches": inf2.n_launches,
                             "traffic": read_traffic(name)}
             if hot2:
@@ -298,7 +373,9 @@ def main():
                                 "unroll": best[1]}
         result["chains"] = chains
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline()
+        cb = cpu_baseline()
+        cb["value"] = round(alg_total * cb["passes"] / cb["seconds"] / 1e9, 4)
+        result["cpu_baseline"] = cb
     print(json.dumps(result), flush=True)
 
 

@@ -203,18 +203,23 @@ typedef struct {
 #define PF_VARIANT_T_TILE 2           /* transpose family: innermost dim changes, square tiles, blocks of elements
                                          transposed in registers                                               */
 
-typedef struct pf_plan_s pf_plan; /* opaque plan object, owned by the library */
+/* Opaque plan object, owned by the library.  (Not called pf_chain_plan: in C a typedef and the function of that
+ * name cannot coexist.) */
+typedef struct pf_plan_s pf_plan;
 
 /*
  * Check a chain description on the host (no GPU needed): structure, value ids, arities, attributes,
  * shape compatibility of every operator.  Returns PF_OK or the first problem found.
+ * The rules are those of the four basic operator kinds the method splits a subgraph into (section 6, "GIR-Graph
+ * generation": element-wise, broadcast, reduce, transpose) and of the composites built from them.
  */
 pf_status pf_chain_validate(const pf_chain_desc *desc);
 
 /*
  * Shape and (for inputs) dtype of any value of the chain (host only).  `value` is a value id.  For
  * operator results the dtype field is PF_F32, the type intermediates are computed in.  `out` is written
- * only on success.
+ * only on success.  (Section 6: every basic operator kind fixes the shape of its result from its operands' --
+ * element-wise keeps it, broadcast extends it, reduce keeps reduced extents as 1, transpose permutes it.)
  */
 pf_status pf_chain_infer_shape(const pf_chain_desc *desc, int32_t value, pf_tensor_desc *out);
 
@@ -268,6 +273,12 @@ pf_status pf_chain_plan(const pf_chain_desc *desc, int32_t device, pf_plan **out
 /* Same as pf_chain_plan but with an explicit variant (-1 = choose automatically). */
 pf_status pf_chain_plan_variant(const pf_chain_desc *desc, int32_t device, int32_t variant, pf_plan **out);
 
+/*
+ * What the planner decided: kernel family (the synchronisation scope of section 5.1 the chain needs), variant,
+ * launch geometry, LDS and workspace sizes, the bytes the chain has to move (every input and output once: what is
+ * left after the merging rules of section 5.1 have removed every DRAM round trip between operators), launches per
+ * run.  `info` is written only on success; PF_ERR_INVALID_ARG for null arguments.
+ */
 pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
 
 /*
@@ -278,6 +289,9 @@ pf_status pf_chain_plan_get_info(const pf_plan *plan, pf_plan_info *info);
 pf_status pf_chain_plan_get_partition(const pf_plan *plan, pf_partition *out);
 
 /*
+ * Run the chain: the device side of the optimised GIR-Graph (section 4: data-movement gOperators DRAM -> registers,
+ * computation gOperators in registers, at most one synchronisation whose scope picked the kernel family, data movement
+ * registers -> DRAM), launched with the parameters fixed when the plan was made (section 7, code generation).
  * Enqueue the fused kernel on `stream` (a hipStream_t, passed as void*; NULL = the default stream) and
  * return without waiting.  inputs[k] / outputs[k] are device pointers to contiguous tensors of exactly
  * the shapes and dtypes of the description, 16-byte aligned, owned by the caller and not retained.
@@ -320,10 +334,23 @@ pf_status pf_chain_plan_poll_error(const pf_plan *plan, int32_t *flag);
 #define PF_STATIC_SCRATCH_BYTES (2u << 20)
 pf_status pf_chain_run_static(const pf_chain_desc *desc, int32_t device, const void *const *inputs, void *const *outputs, void *stream);
 
+/*
+ * Release a plan and the device memory it owns (workspace, tables, tensors between the kernels of a split chain).
+ * The caller makes sure no launch of the plan is still running.  NULL is ignored.  (Section 6: a generated kernel
+ * lives as long as the subgraph it was made for; here that lifetime is the caller's.)
+ */
 void pf_chain_plan_destroy(pf_plan *plan);
 
+/*
+ * Error reporting of the boundary: every entry point returns a pf_status; these turn it into text.  The paper's
+ * system hands what it does not optimise to the vendor's DNN library (section 6, compute-bound operators); this
+ * library has no such fallback, so a chain it cannot run as fused kernels is an explicit PF_ERR_UNSUPPORTED with the
+ * reason here.
+ * pf_status_str: the name of a status code (static storage).  pf_last_error: detail of the last failing call on the
+ * calling thread (thread-local storage, valid until that thread's next failing call; empty string if none).
+ */
 const char *pf_status_str(pf_status s);
-const char *pf_last_error(void); /* thread-local, valid until the next failing call on this thread */
+const char *pf_last_error(void);
 
 /*
  * Measurement aid, not part of a chain: a plain 16-byte-per-lane device copy of `bytes` bytes
