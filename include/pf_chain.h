@@ -38,7 +38,8 @@ typedef enum {
                                in the group and stencil families                                          */
     PF_ERR_ALIAS = 6,       /* an output overlaps an input in a family that cannot run in place            */
     PF_ERR_NOMEM = 7,       /* host or device allocation failed                                            */
-    PF_ERR_HIP = 8          /* a HIP runtime call failed; pf_last_error holds hipGetErrorString            */
+    PF_ERR_HIP = 8,         /* a HIP runtime call failed; pf_last_error holds hipGetErrorString            */
+    PF_STATUS_FORCE_INT32_ = 0x7fffffff /* (any non-negative int is a representable value: pf_status_str takes what it is given) */
 } pf_status;
 
 typedef enum { PF_F32 = 0, PF_F16 = 1, PF_BF16 = 2 } pf_dtype;
@@ -176,6 +177,11 @@ typedef struct {
     int32_t n_kernels;                 /* 1, or the number of kernels a chain was split into (pf_chain_partition);
                                           family, variant, grid, block, spec_id and vectors_per_lane are then the
                                           first kernel's, workspace_bytes includes the tensors between kernels    */
+    int32_t interpreter_fallback;      /* 1: a kernel specialised for this chain was wanted when the plan was made and
+                                          could not be produced (kernel headers or run-time compiler missing, compile
+                                          error): the run-time-interpreted kernels run instead, correct but several
+                                          times slower.  pf_chain_plan still returns PF_OK; pf_last_error holds the
+                                          reason right after it.  0 also when PF_JIT=0 asked for the interpreter.   */
 } pf_plan_info;
 
 /* A split of a chain into kernels: kernel k runs ops[first_op[k]] .. ops[first_op[k + 1] - 1]. */
@@ -308,8 +314,14 @@ pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *con
 /*
  * Kernels that wait for other workgroups (the fused GroupNorm variant, the merging workgroup of a pooling) bound every wait; when a wait runs
  * out they set an error word in the plan's workspace and carry on, so a launch always terminates.  This call
- * synchronises with the device (hipMemcpy), stores the word in *flag (0 = no wait ever gave up since the
- * plan was made) and clears it.  Plans without workspace always report 0.
+ * synchronises with the device (hipMemcpy), stores the word in *flag (0 = no wait gave up since the last poll)
+ * and clears it.  A non-zero flag means that the outputs of the plan's launches since the last poll are invalid;
+ * the call then also puts the plan's exchange words back into their initial state, so the caller must have
+ * synchronised with every stream the plan ran on.  Plans without workspace always report 0.
+ * Such waits end because the workgroups waited for are running: the grids are sized to what an otherwise idle
+ * device holds at once.  A plan of the one-launch GroupNorm variant or of a pooling split over several workgroups
+ * should therefore not share the device with other long-running kernels (plan PF_VARIANT_GROUP_TWO_PASS where
+ * streams run concurrently).
  */
 pf_status pf_chain_plan_poll_error(const pf_plan *plan, int32_t *flag);
 

@@ -41,8 +41,8 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        # (PF_ORACLE_LIB names another build of the same C file: the one instrumented by the host sanitizers)
+        lib = ctypes.CDLL(os.environ["PF_ORACLE_LIB"]) if os.environ.get("PF_ORACLE_LIB") else ctypes.CDLL(build())
         dp = ctypes.POINTER(ctypes.c_double)
         i64 = ctypes.c_int64
         lib.orc_set_threads.argtypes = [ctypes.c_int]

@@ -60,7 +60,7 @@ class pf_plan_info(C.Structure):
                 ("lds_bytes", C.c_uint32), ("workspace_bytes", C.c_uint64),
                 ("compulsory_read_bytes", C.c_uint64), ("compulsory_write_bytes", C.c_uint64),
                 ("n_launches", C.c_int32), ("n_micro_ops", C.c_int32), ("spec_id", C.c_int32),
-                ("vectors_per_lane", C.c_int32), ("n_kernels", C.c_int32)]
+                ("vectors_per_lane", C.c_int32), ("n_kernels", C.c_int32), ("interpreter_fallback", C.c_int32)]
 
 
 class pf_partition(C.Structure):
@@ -68,7 +68,8 @@ class pf_partition(C.Structure):
                 ("predicted_us", C.c_double * PF_MAX_OPS), ("bytes", C.c_uint64 * PF_MAX_OPS)]
 
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
+# (PF_CHAIN_LIB names another build of the same library: the one with sanitized host code, see build.py --sanitize)
+LIB_PATH = os.environ.get("PF_CHAIN_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
            "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose",

@@ -52,7 +52,11 @@ PF_DEVICE void finish_slice(const AttnArgs& a, uint32_t head, uint32_t split, fl
         __hip_atomic_store(part + d, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(part + d + 1u, l_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+    // The arrival below must not become visible before these words: every wave waits until its device-coherent
+    // (write-through) stores have been acknowledged, then the barrier lets lane 0 count the slice in.  (A
+    // workgroup-scope release does not wait for outstanding stores on this device; an agent-scope one would write
+    // back the whole L2.)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
         const uint32_t before = __hip_atomic_fetch_add(a.ws_counter + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

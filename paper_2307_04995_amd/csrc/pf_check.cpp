@@ -31,6 +31,8 @@ const OpTraits kOps[PF_OP_COUNT_] = {
 
 
 
+constexpr int64_t kMaxElements = (int64_t)1 << 40;  // of any one tensor of a chain
+
 int64_t numel(const Shape& s) {
     int64_t n = 1;
     for (int64_t d : s) n *= d;
@@ -79,8 +81,14 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
         if (t.dtype < PF_F32 || t.dtype > PF_BF16) return fail(PF_ERR_DTYPE, "input %d: unknown dtype %d", k, t.dtype);
         if (t.rank < 1 || t.rank > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "input %d: rank %d out of range", k, t.rank);
         Shape s(t.shape, t.shape + t.rank);
-        for (int64_t e : s)
+        // extents are positive and their product stays far from the range of a 64-bit integer (every later size
+        // computation -- bytes, rows, vectors -- multiplies it by small factors only)
+        int64_t n = 1;
+        for (int64_t e : s) {
             if (e <= 0) return fail(PF_ERR_SHAPE, "input %d: non-positive extent", k);
+            if (e > kMaxElements / n) return fail(PF_ERR_SHAPE, "input %d: more than 2^40 elements", k);
+            n *= e;
+        }
         sh.push_back(s);
     }
     for (int k = 0; k < d->n_ops; ++k) {
@@ -91,6 +99,7 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
         if (o.n_src != tr.arity) return fail(PF_ERR_INVALID_ARG, "op %d (%s): n_src %d, expected %d", k, tr.name, o.n_src, tr.arity);
         for (int s = 0; s < o.n_src; ++s)
             if (o.src[s] < 0 || o.src[s] >= id) return fail(PF_ERR_INVALID_ARG, "op %d (%s): operand id %d out of range", k, tr.name, o.src[s]);
+        if (o.n_i < 0 || o.n_i > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "op %d (%s): n_i %d out of range", k, tr.name, o.n_i);
         const Shape& a = sh[o.src[0]];
         Shape r;
         switch (tr.cls) {
@@ -216,9 +225,13 @@ pf_status check_desc(const pf_chain_desc* d, Checked* out) {
             case OC_RESHAPE: {
                 if (o.n_i < 1 || o.n_i > PF_MAX_RANK) return fail(PF_ERR_INVALID_ARG, "op %d (reshape): n_i out of range", k);
                 r.assign(o.i, o.i + o.n_i);
-                for (int64_t e : r)
+                int64_t n_new = 1;
+                for (int64_t e : r) {
                     if (e <= 0) return fail(PF_ERR_SHAPE, "op %d (reshape): non-positive extent", k);
-                if (numel(r) != numel(a)) return fail(PF_ERR_SHAPE, "op %d (reshape): element count changes", k);
+                    if (e > kMaxElements / n_new) return fail(PF_ERR_SHAPE, "op %d (reshape): element count changes", k);
+                    n_new *= e;
+                }
+                if (n_new != numel(a)) return fail(PF_ERR_SHAPE, "op %d (reshape): element count changes", k);
                 break;
             }
         }

@@ -51,6 +51,8 @@ pf_status pf_chain_plan_variant(const pf_chain_desc* desc, int32_t device, int32
     } restore;
     if (hipGetDevice(&restore.prev) != hipSuccess) restore.prev = -1;
     pf_status s = plan_one_kernel(desc, device, variant, out);
+    if (s == PF_OK && (*out)->interpreter_fallback)  // PF_OK, but the caller can see why the plan is slow
+        (void)fail(PF_OK, "plan-time specialisation unavailable, the run-time-interpreted kernels run: %s", (*out)->fallback_reason.c_str());
     // more than one exchange wider than a lane (or one a single kernel cannot hold): several kernels, split where the
     // performance model says the bytes are fewest
     if (s == PF_ERR_UNSUPPORTED && variant < 0 && desc->n_ops > 1 && env_int("PF_PARTITION", 1) != 0) {
@@ -98,6 +100,7 @@ pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
     info->spec_id = plan->spec_id;
     info->vectors_per_lane = plan->k;
     info->n_kernels = 1;
+    info->interpreter_fallback = plan->interpreter_fallback ? 1 : 0;
     if (plan->composite) {  // family, variant, grid and block are the first kernel's; the sums are the chain's
         info->n_kernels = (int32_t)plan->parts.size();
         info->workspace_bytes = plan->arena_bytes;
@@ -108,6 +111,7 @@ pf_status pf_chain_plan_get_info(const pf_plan* plan, pf_plan_info* info) {
             info->workspace_bytes += sub.workspace_bytes;
             info->n_micro_ops += sub.n_micro_ops;
             info->lds_bytes = std::max(info->lds_bytes, sub.lds_bytes);
+            info->interpreter_fallback |= sub.interpreter_fallback;
         }
         pf_chain_plan_get_info(plan->parts[0].plan, &sub);
         info->spec_id = sub.spec_id;
@@ -260,7 +264,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
                     return fail(PF_ERR_UNSUPPORTED, "the one-launch GroupNorm variant cannot be recorded into a graph; plan the two-launch variant for that");
             }
             pf::GroupGeom g = plan->group;
-            g.epoch = ++plan->epoch;
+            g.epoch = plan->epoch + 1;  // (counted below, once the launch has been accepted: a failed launch must not flip the slots' parity)
             const uint32_t tiles = g.samples * g.blocks_per_sample;
             if (plan->spec_id == pf::kSpecJit) {
                 uint32_t t = tiles;
@@ -276,6 +280,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
             } else {
                 e = pf::launch_group(0, false, plan->spec_id, L.main_dtype, a, g, plan->k, tiles, plan->grid, plan->block, 0, st);
             }
+            if (e == hipSuccess) plan->epoch = g.epoch;
             break;
         }
         case PF_FAMILY_POOL:
@@ -329,7 +334,19 @@ pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
     uint32_t word = 0;
     if (hipMemcpy(&word, err, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
         return fail(PF_ERR_HIP, "cannot read the error word");
-    if (word != 0u && hipMemset(err, 0, sizeof(word)) != hipSuccess) return fail(PF_ERR_HIP, "cannot clear the error word");
+    if (word != 0u) {
+        // A wait gave up: the launch's outputs are invalid, and the exchange words may be in a state the next launch
+        // does not expect (slots of the wrong parity still filled, flags of late slices still raised).  Put the
+        // workspace back the way the planner left it.  (The caller has synchronised: nothing of this plan is running.)
+        bool ok = hipMemset(err, 0, sizeof(word)) == hipSuccess;
+        if (plan->family == PF_FAMILY_GROUP && plan->group.ws_gather) {
+            const pf::GroupGeom& g = plan->group;
+            ok = ok && hipMemset(g.ws_gather, 0xff, (size_t)2 * g.samples * g.groups * g.blocks_per_sample * sizeof(uint64_t)) == hipSuccess;
+        }
+        if (plan->family == PF_FAMILY_POOL && plan->pool.ws_flags)
+            ok = ok && hipMemset(plan->pool.ws_flags, 0, (size_t)plan->pool.samples * plan->pool.blocks_per_sample * sizeof(uint32_t)) == hipSuccess;
+        if (!ok) return fail(PF_ERR_HIP, "cannot re-arm the workspace");
+    }
     *flag = (int32_t)word;
     return PF_OK;
 }

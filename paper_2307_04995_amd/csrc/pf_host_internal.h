@@ -132,6 +132,8 @@ struct pf_plan_s {
     pf::BcastTerm bcast_host[PF_DEV_MAX_VEC][PF_DEV_MAX_BCAST_TERMS];  // general broadcasting terms, staged on the host
     void* bcast_dev = nullptr;  // ... and their copy in device memory
     bool group_general = false; // group family: groups of any width (general kernels)
+    bool interpreter_fallback = false;  // a specialised kernel was wanted and could not be produced: the interpreter runs
+    std::string fallback_reason;
     uint32_t dyn_lds = 0;     // group family: dynamic LDS bytes of each launch
     uint32_t ew_total_vecs = 0, ew_vecs_per_row = 0;
     dim3 grid, block;
@@ -180,6 +182,7 @@ namespace pfh {
 
 // ---- planning ----
 int env_int(const char* name, int dflt);
+void note_interpreter_fallback(pf_plan_s* p, const std::string& why);
 
 // Where a plan's device memory comes from.  Ordinary plans allocate it.  While pf_chain_run_static plans (tls_scratch is
 // set on that thread) it is carved out of the library's static scratch array instead, nothing is allocated, compiled

@@ -73,9 +73,12 @@ hipFunction_t compile(int device, const std::string& source, const std::string& 
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_cache.find(key);
     if (it != g_cache.end()) return it->second;
-    auto fail = [&](const std::string& what) -> hipFunction_t {
+    // Only a compile error is remembered (the same source fails the same way every time); missing headers or a module
+    // that does not load may be a passing condition, and remembering it would keep this structure on the interpreter
+    // for the life of the process.
+    auto fail = [&](const std::string& what, bool remember = false) -> hipFunction_t {
         if (err) *err = what;
-        g_cache[key] = nullptr;  // do not try again for this structure
+        if (remember) g_cache[key] = nullptr;
         return nullptr;
     };
     const std::string inc = include_dir();
@@ -98,7 +101,7 @@ hipFunction_t compile(int device, const std::string& source, const std::string& 
             hiprtcGetProgramLog(prog, &log[0]);
         }
         hiprtcDestroyProgram(&prog);
-        return fail("run-time compilation failed: " + log.substr(0, 2000));
+        return fail("run-time compilation failed: " + log.substr(0, 2000), true);
     }
     const char* lowered = nullptr;
     if (hiprtcGetLoweredName(prog, name_expr.c_str(), &lowered) != HIPRTC_SUCCESS || !lowered) {

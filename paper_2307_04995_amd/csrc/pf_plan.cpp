@@ -112,6 +112,15 @@ pf_status plan_workspace_fill(pf_plan_s* p, void* ptr, int byte, uint64_t bytes,
     return PF_OK;
 }
 
+// A plan that should have got a kernel specialised for its chain runs on the run-time-interpreted kernels instead (the
+// run-time compiler or the kernel headers are missing, or the compilation failed): several times slower, so the plan
+// says so (pf_plan_info.interpreter_fallback) and keeps the reason for pf_last_error.
+void note_interpreter_fallback(pf_plan_s* p, const std::string& why) {
+    p->interpreter_fallback = true;
+    p->fallback_reason = why;
+    if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", why.c_str());
+}
+
 // Plan-time specialisation needs the device (the compiled kernel is loaded onto it).
 bool jit_possible(int device) {
     if (!pf::jit_enabled() || planning_static()) return false;
@@ -288,7 +297,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
             std::string err;
             p->jit_fn = pf::jit_row_stream_kernel(p->device, L.main_dtype, p->ragged, make_jit_spec(L), &err);
             if (p->jit_fn) p->spec_id = pf::kSpecJit;
-            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+            else note_interpreter_fallback(p, err);
         }
         return PF_OK;
     }
@@ -329,7 +338,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         else p->jit_fn = pf::jit_row_kernel(p->device, L.main_dtype, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->ragged,
                                        p->block.x <= 256 ? 256 : 1024, log2l, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
-        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        else note_interpreter_fallback(p, err);
     }
     if (!p->spec_id) {
         p->row.rows_per_wave = 1;
@@ -369,7 +378,7 @@ pf_status plan_ew(pf_plan_s* p) {
         std::string err;
         p->jit_fn = pf::jit_ew_kernel(p->device, L.main_dtype, p->k, p->ragged, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
-        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        else note_interpreter_fallback(p, err);
     }
     return PF_OK;
 }
@@ -506,7 +515,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
             std::string err;
             p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, ragged, make_jit_spec(L), &err);
             if (p->jit_fn) p->spec_id = pf::kSpecJit;
-            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+            else note_interpreter_fallback(p, err);
         }
         return PF_OK;
     }
@@ -599,7 +608,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         std::string err;
         p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, ragged, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
-        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        else note_interpreter_fallback(p, err);
     }
     return PF_OK;
 }
@@ -747,8 +756,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
             if (p->jit_fn && p->jit_fn2) p->spec_id = pf::kSpecJit;
         }
     }
-    if (jit_ok && p->spec_id == 0 && env_int("PF_LOG", 0))
-        fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", jit_err.c_str());
+    if (jit_ok && p->spec_id == 0) note_interpreter_fallback(p, jit_err);
     p->lds_bytes = general ? gen_lds + 512 * 2 * 4 + 4 : 512 * 3 * 4 + 512 * 2 * 4 + 4;
     p->dyn_lds = gen_lds;
     // workspace: partials of the two-launch variant, or two parities of exchange words (all-ones = empty) of the
@@ -839,7 +847,7 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
             std::string err;
             p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, p->variant, ksz, make_jit_spec(L), &err);
             if (p->jit_fn) p->spec_id = pf::kSpecJit;
-            else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+            else note_interpreter_fallback(p, err);
         }
         return PF_OK;
     }
@@ -884,7 +892,7 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
         p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, ksz, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else {
-            if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+            note_interpreter_fallback(p, err);
             // the interpreted kernel never packs its tile
             if (variant == PF_VARIANT_STENCIL_STAGED && entry_bytes == 16u && L.main_dtype != PF_F32) {
                 const uint64_t big = tile_bytes * 2;
@@ -1125,7 +1133,7 @@ pf_status plan_pool(pf_plan_s* p) {
         std::string err;
         p->jit_fn = pf::jit_pool_kernel(p->device, L.main_dtype, nv, L.pool_op, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
-        else if (env_int("PF_LOG", 0)) fprintf(stderr, "[pf] plan-time specialisation unavailable, using the interpreter: %s\n", err.c_str());
+        else note_interpreter_fallback(p, err);
     }
     return PF_OK;
 }

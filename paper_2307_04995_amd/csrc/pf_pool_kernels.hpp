@@ -112,7 +112,12 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
         __syncthreads();
         float* part = g.ws_partial + (uint64_t)(sample * g.blocks_per_sample + bx) * g.channels;
         for (uint32_t idx = t; idx < g.channels; idx += 512u) __hip_atomic_store(part + idx, lds[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+        // The flag below must not become visible before these words.  They are device-coherent write-through stores,
+        // so nothing has to be written back; what is needed is that every wave's stores have been acknowledged before
+        // the barrier lets lane 0 raise the flag.  A workgroup-scope release does not wait for outstanding stores on
+        // this device (a workgroup never leaves its compute unit), and an agent-scope one would write back the whole
+        // L2: the wait is spelled out instead.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         uint32_t* flags = g.ws_flags + (uint64_t)sample * g.blocks_per_sample;
         if (t == 0) __hip_atomic_store(flags + bx, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

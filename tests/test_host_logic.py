@@ -336,6 +336,30 @@ def test_empty_and_oversized_tensors_are_refused_cleanly():
     assert _plan_status(s) == pf.PF_ERR_UNSUPPORTED
 
 
+def test_crafted_descriptions_cannot_wrap_a_size_or_hide_a_reduction():
+    # extents whose product does not fit 64 bits (2^21 * 2^21 * 2^22 = 2^64 wraps to 0): refused when the shapes are
+    # checked, before any size is computed from them
+    s = wl.ChainSpec(inputs=[("f16", (1 << 21, 1 << 21, 1 << 22))])
+    s.out(s.op("relu", 0), "f16")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+    assert "2^40" in pf.pf_last_error()
+    s = wl.ChainSpec(inputs=[("f32", (1 << 20, 1 << 21))])  # 2^41 elements: over the limit without wrapping anything
+    s.out(s.op("relu", 0), "f32")
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+    # a reshape to extents that wrap back to the right count
+    s = wl.ChainSpec(inputs=[("f16", (4, 16))])
+    s.out(s.op("reshape", 0, i=[1 << 33, 1 << 33, 64]), "f16")  # 2^72 = 64 mod 2^64 ... and not 64 elements
+    assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+    # a negative count of integer attributes is no reduction that reduces nothing
+    s = wl.ChainSpec(inputs=[("f16", (4, 16))])
+    s.out(s.op("reduce_sum", 0), "f16")
+    d = pf.make_desc(s)
+    d.ops[0].n_i = -1
+    assert pf.pf_chain_validate(d) == pf.PF_ERR_INVALID_ARG
+    d.ops[0].n_i = 7
+    assert pf.pf_chain_validate(d) == pf.PF_ERR_INVALID_ARG
+
+
 # ---- recomposition of basic operators into composite ones (host only)
 
 def _recompose(spec):

@@ -142,3 +142,28 @@ def test_short_causal_rows_side_by_side():
     assert info.spec_id == SPEC_JIT
     spec, ins = wl.c2_causal_softmax(b=1, h=3, s=100, s_k=197, dtype="bf16")
     check_chain(spec, ins, what="short ragged causal rows")
+
+
+def test_a_plan_that_falls_back_to_the_interpreter_says_so(tmp_path):
+    """With the kernel headers out of reach the chain cannot be specialised: the plan is still made and still right,
+    but it reports that it runs on the interpreted kernels, and why."""
+    from paper_2307_04995_amd import binding as pf
+    # (a structure of its own, so that no kernel made for another test is waiting in the cache)
+    spec = wl.ChainSpec(inputs=[("f16", (21, 384)), ("f16", (384,))])
+    spec.out(spec.op("neg", spec.op("softmax", spec.op("tanh", spec.op("sub", 0, 1)))), "f16")
+    ins = [wl.random_tensor((21, 384), "f16", 911), wl.random_tensor((384,), "f16", 912)]
+    with env(PF_JIT_INCLUDE=str(tmp_path)):
+        plan = pf.Plan(spec, 0)
+        reason = pf.pf_last_error()
+        info = plan.info()
+        plan.close()
+        assert info.spec_id == 0 and info.interpreter_fallback == 1
+        assert "headers not found" in reason
+        check_chain(spec, ins, what="interpreter fallback")
+    # a passing condition is not remembered: with the headers back, the same chain gets its kernel
+    _, info2, _ = check_chain(spec, ins, what="specialised after the headers came back")
+    assert info2.spec_id == SPEC_JIT and info2.interpreter_fallback == 0
+    # asking for the interpreter is no fallback
+    with env(PF_JIT="0"):
+        _, info3 = gpu_run(spec, ins)
+    assert info3.spec_id == 0 and info3.interpreter_fallback == 0
