@@ -102,16 +102,18 @@ def time_chain(spec, ins, steps, warmup, variant=None, hot=None, graph=None):
         o_k = [torch.empty(s, dtype=tdt[dt], device="cuda") for s, (_, dt) in zip(shapes, spec.outputs)]
         sets.append(([t.data_ptr() for t in i_k], [t.data_ptr() for t in o_k], i_k, o_k))
     stream = torch.cuda.current_stream().cuda_stream
+    # the pointer arrays of every buffer set are marshalled once: the timed loop is one foreign call per launch
+    import ctypes
+    cstream = ctypes.c_void_p(stream)
+    psets = [pf.PointerSet(ip, op) for ip, op, _, _ in sets]
     for k in range(warmup):
-        ip, op, _, _ = sets[k % n_sets]
-        plan.run_ptrs(ip, op, stream)
+        plan.run_set(psets[k % n_sets], cstream)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
     for k in range(steps):
-        ip, op, _, _ = sets[k % n_sets]
-        plan.run_ptrs(ip, op, stream)
+        plan.run_set(psets[k % n_sets], cstream)
     ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -152,14 +154,37 @@ def time_chain(spec, ins, steps, warmup, variant=None, hot=None, graph=None):
     return host_ms, event_ms, info
 
 
-def time_copy(nbytes, steps, warmup, variant=2):
+def time_copy(nbytes, steps, warmup, variant=2, graph=False):
+    """Average duration of a launch of the library's plain copy kernel over rotating buffers, launched back to back
+    from Python, or (graph=True) replayed from a HIP graph, where the host's launch rate plays no part."""
     import torch
     from paper_2307_04995_amd import binding as pf
-    n_sets = max(3, -(-ROTATE_BYTES // (2 * nbytes)))
+    n_sets = min(64 if graph else 512, max(3, -(-ROTATE_BYTES // (2 * nbytes))))
     bufs = [(torch.empty(nbytes, dtype=torch.uint8, device="cuda"), torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
             for _ in range(n_sets)]
     for a, _ in bufs:
         a.fill_(1)
+    if graph:
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            pf.pf_copy_probe(bufs[0][0].data_ptr(), bufs[0][1].data_ptr(), nbytes, variant, side.cuda_stream)
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                cs = torch.cuda.current_stream().cuda_stream
+                for a, b in bufs:
+                    if pf.pf_copy_probe(a.data_ptr(), b.data_ptr(), nbytes, variant, cs) != 0:
+                        raise RuntimeError(pf.pf_last_error())
+        reps = max(1, steps // n_sets)
+        g.replay()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(reps):
+            g.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / (reps * n_sets)
     stream = torch.cuda.current_stream().cuda_stream
     for k in range(warmup):
         a, b = bufs[k % n_sets]
@@ -201,22 +226,23 @@ def time_pass(steps, warmup):
         for k in range(n_sets):
             i_k = [t if t.numel() * t.element_size() < 65536 else t.clone() for t in base]
             o_k = [torch.empty(sh, dtype=tdt[dt], device="cuda") for sh, (_, dt) in zip(shapes, spec.outputs)]
-            ss.append(([t.data_ptr() for t in i_k], [t.data_ptr() for t in o_k], i_k, o_k))
+            ss.append((pf.PointerSet([t.data_ptr() for t in i_k], [t.data_ptr() for t in o_k]), i_k, o_k))
         plans[name], sets[name], infos[name], meta[name] = plan, ss, plan.info(), (alg, nom, label)
-    stream = torch.cuda.current_stream().cuda_stream
+    import ctypes
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
     def one_step(k, marks=None):
         for name in BENCH_CHAINS:
             ss = sets[name]
-            ip, op, _, _ = ss[k % len(ss)]
+            ps = ss[k % len(ss)][0]
             if marks is not None:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                plans[name].run_ptrs(ip, op, stream)
+                plans[name].run_set(ps, stream)
                 e1.record()
                 marks[name].append((e0, e1))
             else:
-                plans[name].run_ptrs(ip, op, stream)
+                plans[name].run_set(ps, stream)
 
     for k in range(warmup):
         one_step(k)
@@ -349,7 +375,7 @@ def main():
         for name in wanted:
             s2, i2, alg2, nom2, lab2 = full_size_chain(name)
             hot2 = [] if args.hot else None
-            gr2 = [] if (args.hot and name == "C1") else None   # the launch-bound chain, replayed from a HIP graph
+            gr2 = [] if name == "C1" else None   # the launch-bound chain, also replayed from a HIP graph
             h2, e2, inf2 = time_chain(s2, i2, ctx_steps, ctx_warm, forced.get(name), hot=hot2, graph=gr2)
             chains[name] = {"workload": lab2, "us_per_call": round(e2 * 1e3, 3),
                             "host_us_per_call": round(h2 * 1e3, 3), "gbps": round(alg2 / (e2 * 1e-3) / 1e9, 1),
@@ -368,6 +394,15 @@ def main():
             g = 2 * nbytes / (ms * 1e-3) / 1e9
             if best is None or g > best[0]:
                 best = (g, variant, ms)
+        # what a launch costs before it moves anything, and what a plain copy of C1's 2.4 MB costs: the floor under
+        # the launch-bound chain (a 16-byte write-only launch stands in for an empty kernel)
+        small = 1184256  # bytes in (and out): C1's algorithmic 2 368 512 bytes
+        chains["launch_floor"] = {"workload": "one-wave 16-byte store / plain copy 1.18 MB in + 1.18 MB out; launched from Python "
+                                              "back to back, and replayed from a HIP graph (no host in the loop)",
+                                  "null_us_per_call": round(time_copy(16, 400, 40, 64 | 1) * 1e3, 3),
+                                  "copy_2p4MB_us_per_call": round(min(time_copy(small, 400, 40, v) for v in (1, 2)) * 1e3, 3),
+                                  "null_graph_replay_us_per_call": round(time_copy(16, 640, 0, 64 | 1, graph=True) * 1e3, 3),
+                                  "copy_2p4MB_graph_replay_us_per_call": round(min(time_copy(small, 640, 0, v, graph=True) for v in (1, 2)) * 1e3, 3)}
         chains["copy_probe"] = {"workload": "plain 16-byte copy, 64 MiB in + 64 MiB out", "gbps": round(best[0], 1),
                                 "frac_of_peak": round(best[0] / HBM_PEAK_GBPS, 4), "us_per_call": round(best[2] * 1e3, 3),
                                 "unroll": best[1]}

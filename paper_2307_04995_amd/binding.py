@@ -168,6 +168,23 @@ def pf_chain_run(plan, input_ptrs: Sequence[int], output_ptrs: Sequence[int], st
     return _lib.pf_chain_run(plan, ins, outs, C.c_void_p(int(stream)))
 
 
+class PointerSet:
+    """The pointer arrays of one call of pf_chain_run, marshalled once: a caller that launches the same buffers again
+    and again (a serving loop, a benchmark) passes this instead of two Python sequences, and the call then costs one
+    foreign-function call instead of rebuilding two arrays."""
+
+    __slots__ = ("ins", "outs")
+
+    def __init__(self, input_ptrs: Sequence[int], output_ptrs: Sequence[int]):
+        self.ins = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
+        self.outs = (C.c_void_p * len(output_ptrs))(*[C.c_void_p(int(p)) for p in output_ptrs])
+
+
+def pf_chain_run_set(plan, ptrs: PointerSet, stream) -> int:
+    """pf_chain_run on pointer arrays marshalled beforehand; `stream` is a ctypes.c_void_p (or None)."""
+    return _lib.pf_chain_run(plan, ptrs.ins, ptrs.outs, stream)
+
+
 PF_STATIC_SCRATCH_BYTES = 2 << 20
 
 
@@ -307,6 +324,12 @@ class Plan:
 
     def run_ptrs(self, input_ptrs: Sequence[int], output_ptrs: Sequence[int], stream: int = 0) -> None:
         st = pf_chain_run(self.handle, input_ptrs, output_ptrs, stream)
+        if st != PF_OK:
+            raise PfError(st, pf_last_error())
+
+    def run_set(self, ptrs: "PointerSet", stream: "C.c_void_p") -> None:
+        """run_ptrs on a PointerSet built beforehand; `stream` as ctypes.c_void_p (also built beforehand)."""
+        st = _lib.pf_chain_run(self.handle, ptrs.ins, ptrs.outs, stream)
         if st != PF_OK:
             raise PfError(st, pf_last_error())
 

@@ -134,7 +134,7 @@ struct ChainArgs {
     float core_scale;        // softmax: the input is multiplied by this (> 0) inside the core (folded SCALE step)
     uint32_t core_mask;      // softmax: the causal mask (extent mask_si) is applied inside the core; 1 = element by
                              // element, 2 = skipped vectors read as -inf and only the diagonal vector is masked
-    uint32_t pad0;
+    uint32_t vec_plain_all;  // 1: every broadcast operand is one vector of n_inner elements, indexed by column alone
     FastDiv mask_div;        // division by mask_si
     uint64_t rows;           // number of rows (product of the other extents)
     Program pro, epi;

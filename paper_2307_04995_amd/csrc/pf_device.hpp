@@ -116,6 +116,27 @@ PF_DEVICE u32x4 load_cached(const void* base, uint64_t byte_off) {
     return *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off);
 }
 
+// Kernel arguments live in memory and the scalar loads that read them are issued where a value is first needed, so a
+// kernel whose control flow depends on them pays one memory round trip per dependent step: several in a row before
+// the first data load on a workgroup that is alone on its compute unit (a launch of a few hundred workgroups).
+// Touching every 64-byte line of the first `BYTES` bytes of the argument block once, up front and in one batch,
+// leaves those later loads to the scalar cache.  (Reads only.)
+// ALSO: offset of one more argument to touch (the family's geometry, which follows the chain arguments).
+template <uint32_t BYTES, uint32_t ALSO>
+PF_DEVICE void warm_kernel_arguments() {
+    typedef const __attribute__((address_space(4))) uint32_t* karg_ptr;
+    karg_ptr k = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t acc = k[ALSO / 4u];
+#pragma unroll
+    for (uint32_t off = 0; off < BYTES; off += 64u) acc |= k[off / 4u];
+    asm volatile("" ::"s"(acc));
+}
+// for kernels whose arguments are (ChainArgs, geometry): a specialised kernel never reads the two programs
+template <class Spec>
+PF_DEVICE void warm_chain_arguments() {
+    warm_kernel_arguments<Spec::kStatic ? (uint32_t)__builtin_offsetof(ChainArgs, pro) : (uint32_t)sizeof(ChainArgs), (uint32_t)sizeof(ChainArgs)>();
+}
+
 // Element-granular access, for rows whose byte length is not a multiple of 16: their vectors are not
 // 16-byte aligned and the last one is partial.  The first `count` elements of the vector are touched; the
 // others read as the matching half of `fill` and are not stored.
@@ -208,6 +229,7 @@ PF_DEVICE int32_t float_to_key(float f) {
 PF_DEVICE float key_to_float(int32_t k) { return __builtin_bit_cast(float, k ^ ((k >> 31) & 0x7fffffff)); }
 
 struct OpSum {
+    static PF_DEVICE float identity() { return 0.0f; }
     static PF_DEVICE float apply(float a, float b) { return a + b; }
     static PF_DEVICE float wave(float v) {
         v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
@@ -220,6 +242,7 @@ struct OpSum {
     }
 };
 struct OpMax {
+    static PF_DEVICE float identity() { return -__builtin_inff(); }
     static PF_DEVICE float apply(float a, float b) { return fmaxf(a, b); }
     static PF_DEVICE float wave(float f) {
         int32_t v = float_to_key(f);
@@ -351,7 +374,22 @@ PF_DEVICE float pf_tanh(float x) {
     if (PRECISE) return tanhf(x);
     return 2.0f * pf_sigmoid<false>(2.0f * x) - 1.0f;
 }
-PF_DEVICE float pf_gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// GELU(x) = x * Phi(x), Phi(x) = (1 + erf(x / sqrt 2)) / 2.  The tail Q = erfc(|x| / sqrt 2) / 2 comes from the rational
+// approximation 7.1.26 of Abramowitz & Stegun's handbook, erfc(z) = (a1 t + ... + a5 t^5) exp(-z^2) with
+// t = 1 / (1 + p z), whose absolute error is below 1.5e-7; Phi is Q left of zero and 1 - Q right of it, so the left
+// tail has no cancellation.  The result is within 3e-7 * |x| of the exact value (the library erff costs six times the
+// instructions and made the fp32 chain arithmetic-bound).
+PF_DEVICE float pf_gelu_erf(float x) {
+    const float z = __builtin_fabsf(x) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+    float poly = 1.061405429f;
+    poly = __builtin_fmaf(poly, t, -1.453152027f);
+    poly = __builtin_fmaf(poly, t, 1.421413741f);
+    poly = __builtin_fmaf(poly, t, -0.284496736f);
+    poly = __builtin_fmaf(poly, t, 0.254829592f);
+    const float q = 0.5f * poly * t * __builtin_amdgcn_exp2f(-z * z * kLog2e);
+    return x * (x < 0.0f ? q : 1.0f - q);
+}
 PF_DEVICE float pf_max_nan(float a, float b) {
     float r = fmaxf(a, b);
     return (a != a || b != b) ? __builtin_nanf("") : r;

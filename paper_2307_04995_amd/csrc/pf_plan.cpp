@@ -133,10 +133,12 @@ bool jit_possible(int device) {
 pf_status fill_vec_args(pf_plan_s* p, const Checked& c) {
     const Lowered& L = p->low;
     const int es = dtype_size(L.main_dtype);
+    p->args.vec_plain_all = 1;
     for (int v = 0; v < L.n_vec; ++v) {
         const int in = L.vec_input[v];
         const int64_t n = numel(c.shape[in]);
         const int64_t inner = (L.vec_is_epi[v] ? L.post_shape : L.pre_shape).back();
+        if (n != inner || c.shape[in].empty() || c.shape[in].back() != inner || (n * es) % 16 != 0) p->args.vec_plain_all = 0;
         pf::VecArg& va = p->args.vec[v];
         va.ptr = nullptr;
         va.dtype = L.main_dtype;
@@ -255,6 +257,11 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         const double waste = 1.0 - (double)vpr / (double)(wpr * 64 * k);
         const unsigned threads = 64u * (unsigned)wpr * (wpr >= 4 ? 1u : (unsigned)(4 / wpr));
         long score = (waste > 0.26 ? 4000 : (waste > 0.13 ? 2000 : 0)) + (wpr > 4 ? 1000 : 0) + (wpr > 1 ? 100 : 0) + k;
+        // With rows to spare, a wave that owns its row and idles through up to a quarter of its vector slots (they are
+        // never loaded) still beats waves that share a row through LDS and barriers (768 fp32 columns, 65 536 rows:
+        // 98.4 us against 106.6 us); with few rows the shared row wins, its lanes each doing a third of the arithmetic
+        // (256 rows, replayed from a graph: 3.0 us against 3.6 us).
+        if (wpr == 1 && rows >= 8192 && waste <= 0.26) score = k;
         if ((matched || jit_ok) && !have_static(k, 1, wpr == 1, threads)) score += 500;
         if (best_score < 0 || score < best_score) {
             best_score = score;

@@ -59,15 +59,16 @@ struct FlatStore {
 // staging area no earlier reduction of this workgroup may still be reading.
 // LOG2L < 6: a row occupies an aligned segment of 2^LOG2L lanes of one wave (waves_per_row is then 1).
 template <class Op, int LOG2L = 6>
-PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, uint32_t lane, float* red) {
+PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, uint32_t first_wave, uint32_t lane, float* red) {
     v = seg_allreduce<Op, LOG2L>(v);
     if (waves_per_row == 1) return v;
     if (lane == 0) red[wave] = v;
     __syncthreads();
-    const uint32_t first = (wave / waves_per_row) * waves_per_row;
-    float r = red[first];
-    for (uint32_t i = 1; i < waves_per_row; ++i) r = Op::apply(r, red[first + i]);
-    return r;
+    // at most 16 waves share a row (first_wave is the first of them): lane j of every 16 lanes reads the partial of the
+    // row's wave j, and four lane permutations leave the row's value in every lane -- one LDS read, no loop
+    const uint32_t j = lane & 15u;
+    const float p = j < waves_per_row ? red[first_wave + j] : Op::identity();
+    return subrow_allreduce<Op, 4>(p);
 }
 
 // What the interpreter calls back into from inside the row kernel: secondary-output stores, and the row
@@ -78,7 +79,7 @@ PF_DEVICE float row_allreduce(float v, uint32_t waves_per_row, uint32_t wave, ui
 template <bool RAGGED, int KC, int RPW, int LOG2L = 6>
 struct RowHooks {
     RowStore<RAGGED> store;
-    uint32_t wpr, wave, lane;
+    uint32_t wpr, wave, first_wave, lane;
     const uint32_t* limit;  // [RPW] row lengths (0 for rows past the end)
     float inv_n;
     float (*red)[16];
@@ -116,8 +117,8 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, 
                 // the wave reduction runs on order-preserving integer keys in which a positive NaN ranks above +inf
                 v = wave_allreduce<OpMax>(nan_seen > 0.0f ? __builtin_nanf("") : m);
             } else {
-                m = row_allreduce<OpMax, LOG2L>(m, h.wpr, h.wave, h.lane, stage);
-                nan_seen = row_allreduce<OpMax, LOG2L>(nan_seen, h.wpr, h.wave, h.lane, h.red[*h.flip & 1u]);
+                m = row_allreduce<OpMax, LOG2L>(m, h.wpr, h.wave, h.first_wave, h.lane, stage);
+                nan_seen = row_allreduce<OpMax, LOG2L>(nan_seen, h.wpr, h.wave, h.first_wave, h.lane, h.red[*h.flip & 1u]);
                 *h.flip += 1u;
                 v = nan_seen > 0.0f ? __builtin_nanf("") : m;
             }
@@ -131,7 +132,7 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, 
                     const bool valid = RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit;
                     sum += valid ? s.acc[k * VEC + e] : 0.0f;
                 }
-            v = row_allreduce<OpSum, LOG2L>(sum, h.wpr, h.wave, h.lane, stage);
+            v = row_allreduce<OpSum, LOG2L>(sum, h.wpr, h.wave, h.first_wave, h.lane, stage);
             if (code == U_RED_MEAN) v *= h.inv_n;
         }
 #pragma unroll
@@ -147,10 +148,14 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, 
 // so each load is a scalar base plus a 32-bit lane offset.  Vectors that are not loaded read as `fill`.
 // The KC vectors starting at k0 belong to the row at `row_byte`.
 // RAGGED: the row's byte length is not a multiple of 16; its vectors are gathered element by element.
-template <int DT, int K, int KC, class Spec, bool RAGGED = false>
+// WHOLE: every vector of the tile lies inside its row, nothing is skipped and every broadcast operand is a vector of the
+// row's length, so the loads carry no condition and no index arithmetic: they are issued back to back, and no register has to be merged with a fill value (a merge the compiler resolves by
+// waiting for the load).
+template <int DT, int K, int KC, class Spec, bool RAGGED = false, bool WHOLE = false>
 PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, int k0, uint64_t row_byte, uint32_t row,
                                  uint32_t load_limit, uint32_t limit, uint32_t fill) {
     using S = Storage<DT>;
+    static_assert(!(RAGGED && WHOLE), "a ragged row has a partial vector");
 #pragma unroll
     for (int f = 0; f < Spec::NF; ++f) {
         if (f < Spec::n_full(a)) {
@@ -158,6 +163,10 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 #pragma unroll
             for (int c = 0; c < KC; ++c) {
                 const int k = k0 + c;
+                if (WHOLE) {
+                    s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
+                    continue;
+                }
                 s.fraw[f][k] = u32x4{fill, fill, fill, fill};
                 if (RAGGED) s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill);
                 else if (s.col[k] < load_limit) s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
@@ -170,6 +179,10 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 #pragma unroll
             for (int c = 0; c < KC; ++c) {
                 const int k = k0 + c;
+                if (WHOLE) {
+                    s.vraw[v][k] = load_cached(a.vec[v].ptr, (uint64_t)s.col[k] * S::ESIZE);  // (a vector of the row's length)
+                    continue;
+                }
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
                 if (RAGGED)
                     s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
@@ -201,12 +214,14 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     constexpr uint32_t LPR = 1u << LOG2L;   // lanes per row inside a wave
     constexpr uint32_t SUB = 64u >> LOG2L;  // rows side by side in a wave
     __shared__ float red[2][16];
+    warm_chain_arguments<Spec>();
 
     const uint32_t lane = threadIdx.x & 63u;
     // the wave index is the same for all 64 lanes: keep it, and everything derived from it, in scalar registers
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t wpr = WPR1 ? 1u : g.waves_per_row;
-    const uint32_t slot_in_block = WPR1 ? wave : wave / wpr;
+    const uint32_t slot_in_block = WPR1 ? wave : (g.rows_per_block == 1u ? 0u : wave / wpr);
+    const uint32_t first_wave = WPR1 ? wave : slot_in_block * wpr;  // first of the waves that share this wave's row
     const uint64_t row0 = ((uint64_t)blockIdx.x * g.rows_per_block + slot_in_block) * (RPW * SUB);
     if (WPR1 && row0 >= a.rows) return;  // wave-uniform; this configuration has no barrier
     const uint32_t n = a.n_inner;
@@ -218,6 +233,23 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     uint64_t row_byte[RPW];
     const bool fill_inf = a.core_mask == 2u;
     const uint32_t fill = fill_inf ? (DT == DT_F32 ? 0xff800000u : (DT == DT_F16 ? 0xfc00fc00u : 0xff80ff80u)) : 0u;
+    // the usual tile: rows that fill the lanes exactly, all of them inside the tensor, no causal skipping
+    const bool whole_tile = !RAGGED && n == LPR * wpr * (uint32_t)EC && a.mask_si == 0u && a.vec_plain_all != 0u && row0 + (uint64_t)(RPW * SUB) <= a.rows;
+    if (!RAGGED && whole_tile) {
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const uint64_t row64 = row0 + (uint32_t)r * SUB + sub;
+            limit[r] = n;
+            i_row[r] = 0;
+#pragma unroll
+            for (int c = 0; c < KC; ++c) {
+                s.row[r * KC + c] = (uint32_t)row64;
+                s.col[r * KC + c] = (lane_in_row + LPR * wpr * c) * VEC;
+            }
+            row_byte[r] = row64 * n * S::ESIZE;
+            load_row_operands<DT, K, KC, Spec, false, !RAGGED>(a, s, r * KC, row_byte[r], (uint32_t)row64, n, n, fill);
+        }
+    } else
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const uint64_t row64 = row0 + (uint32_t)r * SUB + sub;
@@ -243,7 +275,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
     const float inv_n = 1.0f / (float)n;
     uint32_t flip = 0;
-    const RowHooks<RAGGED, KC, RPW, LOG2L> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, lane, limit, inv_n, red, &flip};
+    const RowHooks<RAGGED, KC, RPW, LOG2L> store_fn{RowStore<RAGGED>{a.out[0], a.out[1], row_byte[0], limit[0]}, wpr, wave, first_wave, lane, limit, inv_n, red, &flip};
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, store_fn);
 
     // Lanes past the end of a row that does not fill the lanes exactly must not disturb the reductions.
@@ -291,7 +323,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             float m = acc[0];
 #pragma unroll
             for (int e = 1; e < EC; ++e) m = fmaxf(m, acc[e]);
-            m = row_allreduce<OpMax, LOG2L>(m, wpr, wave, lane, red[0]);
+            m = row_allreduce<OpMax, LOG2L>(m, wpr, wave, first_wave, lane, red[0]);
             // exp(c * (x - m)); c is the folded scale (1 when there is none).  -inf - m = -inf -> 0; an all
             // -inf row gives -inf - -inf = NaN, as the definition does.
             const float cs = a.core_scale;
@@ -311,7 +343,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                     sum += acc[e];
                 }
             }
-            sum = row_allreduce<OpSum, LOG2L>(sum, wpr, wave, lane, red[1]);
+            sum = row_allreduce<OpSum, LOG2L>(sum, wpr, wave, first_wave, lane, red[1]);
             const float inv = pf_rcp<PR>(sum);
 #pragma unroll
             for (int e = 0; e < EC; ++e) acc[e] *= inv;
@@ -325,7 +357,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             float s1 = 0.0f;
 #pragma unroll
             for (int e = 0; e < EC; ++e) s1 += acc[e];
-            const float mean = row_allreduce<OpSum, LOG2L>(s1, wpr, wave, lane, red[0]) * inv_n;
+            const float mean = row_allreduce<OpSum, LOG2L>(s1, wpr, wave, first_wave, lane, red[0]) * inv_n;
             float s2 = 0.0f;
 #pragma unroll
             for (int c = 0; c < KC; ++c)
@@ -335,7 +367,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                     acc[c * VEC + e] = d;
                     s2 += (all_valid || valid_elem(c, e)) ? d * d : 0.0f;
                 }
-            const float var = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, lane, red[1]) * inv_n;
+            const float var = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, first_wave, lane, red[1]) * inv_n;
             const float rstd = pf_rsqrt<PR>(var + a.eps);
             float gm[EC], bt[EC];
 #pragma unroll
@@ -353,7 +385,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             for (int c = 0; c < KC; ++c)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) s2 += (all_valid || valid_elem(c, e)) ? acc[c * VEC + e] * acc[c * VEC + e] : 0.0f;
-            const float ms = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, lane, red[0]) * inv_n;
+            const float ms = row_allreduce<OpSum, LOG2L>(s2, wpr, wave, first_wave, lane, red[0]) * inv_n;
             const float rstd = pf_rsqrt<PR>(ms + a.eps);
             float gm[EC];
 #pragma unroll
@@ -394,7 +426,8 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
     const uint32_t row = (uint32_t)row64;
     const uint32_t n = a.n_inner;
     LaneState<DT, K, Spec> s;
-    const uint32_t lane_in_row = (wave % wpr) * 64u + lane;
+    const uint32_t first_wave = wave / wpr * wpr;
+    const uint32_t lane_in_row = (wave - first_wave) * 64u + lane;
     const uint32_t limit = row_ok ? n : 0u;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -419,8 +452,8 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
                     nan_seen = (x != x) ? 1.0f : nan_seen;
                 }
             }
-        m = row_allreduce<OpMax>(m, wpr, wave, lane, red[0]);
-        nan_seen = row_allreduce<OpMax>(nan_seen, wpr, wave, lane, red[1]);
+        m = row_allreduce<OpMax>(m, wpr, wave, first_wave, lane, red[0]);
+        nan_seen = row_allreduce<OpMax>(nan_seen, wpr, wave, first_wave, lane, red[1]);
         r = nan_seen > 0.0f ? __builtin_nanf("") : m;
     } else {
         float sum = 0.0f;
@@ -428,7 +461,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
         for (int k = 0; k < K; ++k)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) sum += valid_elem(k, e) ? s.acc[k * VEC + e] : 0.0f;
-        r = row_allreduce<OpSum>(sum, wpr, wave, lane, red[0]);
+        r = row_allreduce<OpSum>(sum, wpr, wave, first_wave, lane, red[0]);
         if (Spec::core(a) == CORE_REDUCE_MEAN) r = r / (float)n;
     }
     // epilogue on the row value: immediates and unary steps only (the planner guarantees it)

@@ -151,23 +151,23 @@ __global__ void __launch_bounds__(kStreamThreads) row_stream_kernel(const ChainA
     // ---- block-scope exchange
     float row_max = 0.0f, row_inv = 0.0f, mean = 0.0f, rstd = 0.0f, value = 0.0f;
     if (core == CORE_SOFTMAX) {
-        row_max = row_allreduce<OpMax>(run_max, kStreamWaves, wave, lane, red[0]);
+        row_max = row_allreduce<OpMax>(run_max, kStreamWaves, wave, 0u, lane, red[0]);
         if (run_max != row_max) run_sum *= PR ? expf((run_max - row_max) * cs) : __builtin_amdgcn_exp2f((run_max - row_max) * c2);
-        const float sum = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, lane, red[1]);
+        const float sum = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, 0u, lane, red[1]);
         row_inv = pf_rcp<PR>(sum);
     } else if (core == CORE_LAYERNORM) {
         const Stat st = block_merge_stat(la.finish(), wave, lane, lds_stat);
         mean = st.mean;
         rstd = pf_rsqrt<PR>(st.m2 / (float)n + a.eps);
     } else if (core == CORE_RMSNORM) {
-        const float ss = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, lane, red[0]);
+        const float ss = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, 0u, lane, red[0]);
         rstd = pf_rsqrt<PR>(ss / (float)n + a.eps);
     } else if (core == CORE_REDUCE_MAX) {
-        const float m = row_allreduce<OpMax>(run_max, kStreamWaves, wave, lane, red[0]);
-        const float ns = row_allreduce<OpMax>(nan_seen, kStreamWaves, wave, lane, red[1]);
+        const float m = row_allreduce<OpMax>(run_max, kStreamWaves, wave, 0u, lane, red[0]);
+        const float ns = row_allreduce<OpMax>(nan_seen, kStreamWaves, wave, 0u, lane, red[1]);
         value = ns > 0.0f ? __builtin_nanf("") : m;
     } else {
-        value = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, lane, red[0]);
+        value = row_allreduce<OpSum>(run_sum, kStreamWaves, wave, 0u, lane, red[0]);
         if (core == CORE_REDUCE_MEAN) value = value / (float)n;
     }
 

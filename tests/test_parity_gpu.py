@@ -462,3 +462,22 @@ def test_non_default_stream_and_repeated_runs():
     stream.synchronize()
     compare(out.cpu(), want, "f16", "repeated runs")
     plan.close()
+
+
+def test_pointer_arrays_marshalled_once_give_the_same_result():
+    # Plan.run_set: the pointer arrays are built once and passed to the same C entry point
+    import ctypes
+    pf = _pf()
+    spec, ins = wl.c1_bias_res_layernorm_gelu(rows=37, n=768, dtype="f32")
+    dev = [t.cuda() for t in ins]
+    plan = pf.Plan(spec, 0)
+    a, b = torch.empty_like(dev[0]), torch.empty_like(dev[0])
+    stream = torch.cuda.current_stream().cuda_stream
+    plan.run_ptrs([t.data_ptr() for t in dev], [a.data_ptr()], stream)
+    ptrs = pf.PointerSet([t.data_ptr() for t in dev], [b.data_ptr()])
+    for _ in range(3):
+        plan.run_set(ptrs, ctypes.c_void_p(stream))
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    compare(b.cpu(), oracle_run(spec, ins)[0], "f32", "run_set")
+    plan.close()
