@@ -210,7 +210,9 @@ def test_normalisation_of_a_single_row(dtype, n):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape,perm", [((2, 24, 16, 64), (0, 2, 1, 3)), ((6, 5, 32), (1, 0, 2)), ((2, 3, 4, 5, 16), (3, 0, 2, 1, 4)),
-                                        ((4, 8, 8), (0, 1, 2))])
+                                        ((4, 8, 8), (0, 1, 2)),
+                                        # two swapped dimensions around a short kept run: walked in blocks (4 x 4, 2 x 4, 8 x 2, none)
+                                        ((3, 12, 6, 64), (0, 2, 1, 3)), ((40, 24, 8), (1, 0, 2)), ((2, 7, 9, 32), (0, 2, 1, 3))])
 def test_permute_only_bit_exact(shape, perm, dtype):
     from oracle import pf_oracle as orc
     g = np.random.default_rng(99)
