@@ -211,6 +211,12 @@ int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes) {
     return n;
 }
 
+int jit_scratch_bytes(hipFunction_t fn) {
+    int n = 0;
+    if (hipFuncGetAttribute(&n, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, fn) != hipSuccess) return 0;
+    return n;
+}
+
 hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, uint32_t lds_bytes, void** params, hipStream_t st) {
     return hipModuleLaunchKernel(fn, grid.x, grid.y, grid.z, block.x, block.y, block.z, lds_bytes, st, params, nullptr);
 }

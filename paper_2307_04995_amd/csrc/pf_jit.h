@@ -42,6 +42,8 @@ hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, con
 // workgroups of `block_threads` threads one compute unit holds at once
 hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err);
 int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes = 0);
+// bytes of per-lane scratch memory the compiled kernel uses (register spills); 0 when it keeps everything in registers
+int jit_scratch_bytes(hipFunction_t fn);
 
 // params: addresses of the kernel's arguments, in order; lds_bytes: dynamic LDS
 hipError_t jit_launch(hipFunction_t fn, dim3 grid, dim3 block, uint32_t lds_bytes, void** params, hipStream_t st);

@@ -747,9 +747,6 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
         }
     }
     if (nv == 0) return fail(PF_ERR_INVALID_ARG, "PF_GROUP_NV must be 4, 8 or 16");
-    const uint64_t tiles = (uint64_t)bps * samples;
-    if (tiles > 0x7fffffffull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
-
     // resident variant: catalogue entry, one full operand, per-channel broadcast operands only, and a grid the
     // device holds at once
     const bool jit_ok = p->spec_id == 0 && jit_possible(p->device);
@@ -760,8 +757,23 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     if (resident_ok && p->spec_id == 0) {
         // not in the catalogue: the fused kernel exists only if it can be specialised now
         fused_fn = jit_ok ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 0, gen_parts, jspec, &jit_err) : nullptr;
+        if (fused_fn && nv == 16 && !forced_nv && pf::jit_scratch_bytes(fused_fn) > 0) {
+            // The kernel of 16 vectors per lane does not fit the registers for this chain: what it spills goes through
+            // memory once per workgroup (measured on [16,64,64,320] with groups of 10: 16 KiB per workgroup, traffic 1.16 x
+            // the tensor).  Tiles of 12 steps do fit.
+            uint32_t b12;
+            tiling(12, &b12);
+            hipFunction_t fn12 = pf::jit_group_kernel(p->device, L.main_dtype, 12, 0, gen_parts, jspec, &jit_err);
+            if (fn12 && pf::jit_scratch_bytes(fn12) == 0) {
+                fused_fn = fn12;
+                nv = 12;
+                bps = b12;
+            }
+        }
         if (!fused_fn) resident_ok = false;
     }
+    const uint64_t tiles = (uint64_t)bps * samples;
+    if (tiles > 0x7fffffffull) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
     uint32_t res_grid = 0;
     if (resident_ok) {
         const int per_cu = fused_fn ? pf::jit_blocks_per_cu(fused_fn, (int)threads, gen_lds)
@@ -799,6 +811,8 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
             p->jit_fn2 = p->jit_fn ? pf::jit_group_kernel(p->device, L.main_dtype, nv, 2, gen_parts, jspec, &jit_err) : nullptr;
             if (p->jit_fn && p->jit_fn2) p->spec_id = pf::kSpecJit;
         }
+        // (tiles of 12 steps exist in plan-time specialised form only)
+        if (nv == 12 && p->spec_id != pf::kSpecJit) return fail(PF_ERR_UNSUPPORTED, "plan-time specialisation failed for the two-launch kernels: %s", jit_err.c_str());
     }
     if (jit_ok && p->spec_id == 0) note_interpreter_fallback(p, jit_err);
     p->lds_bytes = general ? gen_lds + 512 * 2 * 4 + 4 : 512 * 3 * 4 + 512 * 2 * 4 + 4;
