@@ -168,6 +168,8 @@ struct GroupGeom {
     // groups of any width (GEN kernels): channels per group, its divider, and the most groups one vector touches
     uint32_t cpg, parts;
     FastDiv div_cpg;
+    uint32_t ragged;             // 1: channels is not a whole number of 16-byte vectors (general kernels only): positions
+                                 // are not vector-aligned and the last vector of each is partial
 };
 
 // Pool family (reduction over the positions of a channels-last tensor) geometry.

@@ -270,10 +270,18 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     // GEN: the part (group, relative to the lane's first group) each element of the lane's vector belongs to,
     // four bits per element
     uint32_t part_code = 0, first_grp = 0;
+    // GEN == 1 kernels also serve channel counts that are not whole vectors: a position then starts at element
+    // alignment and its last vector holds `cnt` channels (elements past them are never read, counted or stored)
+    constexpr bool kRag = GEN == 1;
+    const bool ragged = kRag && g.ragged != 0u;
+    const uint32_t cnt = ragged ? elems_below<VEC>(cvi * (uint32_t)VEC, g.channels) : (uint32_t)VEC;
     if (GEN) {
         first_grp = fast_div(cvi * (uint32_t)VEC, g.div_cpg);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) part_code |= (fast_div(cvi * (uint32_t)VEC + (uint32_t)e, g.div_cpg) - first_grp) << (4 * e);
+        for (int e = 0; e < VEC; ++e) {
+            const uint32_t ch = min(cvi * (uint32_t)VEC + (uint32_t)e, g.channels - 1u);  // (slots past the last channel: its part, count 0)
+            part_code |= (fast_div(ch, g.div_cpg) - first_grp) << (4 * e);
+        }
     }
     auto part_of = [&](int e) { return (part_code >> (4 * e)) & 15u; };
 
@@ -290,7 +298,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         for (int v = 0; v < Spec::NV; ++v) {
             if (v < Spec::n_vec(a)) {
                 s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                if (active) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], 0u, s.col[0], g.channels);
+                if (active)
+                    s.vraw[v][0] = ragged ? load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], 0u, s.col[0], g.channels, cnt)
+                                          : load_vec_operand<DT, Spec::kVecMode>(a.vec[v], 0u, s.col[0], g.channels);
             }
         }
     }
@@ -312,7 +322,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid_of(i)) raw[i] = load_stream(in_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
+            if (valid_of(i)) {
+                if (ragged) raw[i] = load_elems<DT>(in_base, rel_of(i) * g.channels + cvi * VEC, cnt, 0u);
+                else raw[i] = load_stream(in_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
+            }
         }
 
         // Run the prologue on slice i (lean chains have none).
@@ -326,8 +339,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 for (int f = 1; f < Spec::NF; ++f) {
                     if (f < Spec::n_full(a)) {
                         s.fraw[f][0] = u32x4{0u, 0u, 0u, 0u};
-                        if (valid_of(i))
-                            s.fraw[f][0] = load_stream(a.full[f], (((uint64_t)sample * g.hw + p_begin + rel_of(i)) * g.channels + cvi * VEC) * S::ESIZE);
+                        if (valid_of(i)) {
+                            const uint64_t elem = ((uint64_t)sample * g.hw + p_begin + rel_of(i)) * g.channels + cvi * VEC;
+                            s.fraw[f][0] = ragged ? load_elems<DT>(a.full[f], elem, cnt, 0u) : load_stream(a.full[f], elem * S::ESIZE);
+                        }
                     }
                 }
             }
@@ -336,7 +351,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 for (int v = 0; v < Spec::NV; ++v) {
                     if (v < Spec::n_vec(a)) {
                         s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                        if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.channels);
+                        if (valid_of(i))
+                            s.vraw[v][0] = ragged ? load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.channels, cnt)
+                                                  : load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.channels);
                     }
                 }
             }
@@ -411,8 +428,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 }
             }
             // slots of one part are adjacent: walk them once, flushing a part when the next one begins
-            const float n_slot = active ? npos : 0.0f;
-            Stat cur = {n_slot, mean_e[0], m2_e[0]};
+            const float n_lane = active ? npos : 0.0f;
+            auto n_of = [&](int e) { return (uint32_t)e < cnt ? n_lane : 0.0f; };
+            Stat cur = {n_of(0), mean_e[0], m2_e[0]};
 #pragma unroll
             for (int e = 1; e <= VEC; ++e) {
                 const bool flush = e == VEC || part_of(e % VEC) != part_of(e - 1);
@@ -423,7 +441,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                     q[2] = cur.m2;
                 }
                 if (e < VEC) {
-                    const Stat slot = {n_slot, mean_e[e % VEC], m2_e[e % VEC]};
+                    const Stat slot = {n_of(e % VEC), mean_e[e % VEC], m2_e[e % VEC]};
                     cur = flush ? slot : stat_merge(cur, slot);
                 }
             }
@@ -548,7 +566,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 #pragma unroll
             for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(kCentre ? s.acc[e] - M[e % (kCentre ? VEC : 1)] : s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-            if (valid_of(i)) store_stream(out_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
+            if (valid_of(i)) {
+                if (ragged) store_elems<DT>(out_base, rel_of(i) * g.channels + cvi * VEC, cnt, S::pack(s.acc));
+                else store_stream(out_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
+            }
         }
         __syncthreads();  // LDS staging is reused by the next tile
     }

@@ -668,13 +668,15 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     const int64_t samples = sh[0], C = sh.back();
     const int64_t hw = numel(sh) / (samples * C);
     const int64_t G = L.groups;
-    if ((C * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)C);
-    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the group family is not a multiple of 16 bytes");
+    // A channel count that is not a whole number of vectors: positions start at element alignment and end in a partial
+    // vector.  The general kernels (interpreted or specialised now) read and write such vectors element by element.
+    const bool ragged_c = (C * es) % 16 != 0;
+    if (p->ragged && !ragged_c) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the group family is not a multiple of 16 bytes");
     const int64_t cpg = C / G;
-    const int64_t vpg = cpg / vec, cv = C / vec;
+    const int64_t vpg = cpg / vec, cv = (C + vec - 1) / vec;
     // Groups that are a power-of-two number of whole vectors take the kernels' shuffle-tree path; any other width
     // takes the general one (per-element sums, parts merged through LDS).
-    const bool general = cpg % vec != 0 || (vpg & (vpg - 1)) != 0 || vpg > 64 || env_int("PF_GROUP_GENERAL", 0) != 0;
+    const bool general = ragged_c || cpg % vec != 0 || (vpg & (vpg - 1)) != 0 || vpg > 64 || env_int("PF_GROUP_GENERAL", 0) != 0;
     if (general && G > 512) return fail(PF_ERR_UNSUPPORTED, "more than 512 groups");
     if (samples * hw > 0xffffffffLL || samples > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the group family");
     for (int i = 0; i < L.pro.n; ++i)
@@ -695,12 +697,13 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     g.cpg = (uint32_t)cpg;
     g.div_cpg = make_fastdiv(g.cpg);
     g.parts = 1;
-    for (int64_t v = 0; v < cv; ++v) g.parts = std::max<uint32_t>(g.parts, (uint32_t)((v * vec + vec - 1) / cpg - (v * vec) / cpg + 1));
+    for (int64_t v = 0; v < cv; ++v) g.parts = std::max<uint32_t>(g.parts, (uint32_t)(std::min<int64_t>(v * vec + vec - 1, C - 1) / cpg - (v * vec) / cpg + 1));
+    g.ragged = ragged_c ? 1u : 0u;
     const uint32_t gen_lds = general ? 512u * g.parts * 3u * (uint32_t)sizeof(float) : 0u;
     p->group_general = general;
     // 2: statistics straight from the packed 16-bit pairs (needs pairs that never straddle groups and nothing but the
     // load in front of the normalisation; the kernel checks the rest at compile time)
-    const int gen_parts = !general ? 0 : ((cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
+    const int gen_parts = !general ? 0 : ((!ragged_c && cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);

@@ -142,6 +142,41 @@ def test_groupnorm_groups_of_any_width(n, h, w, c, g, dtype, variant):
     assert info.n_launches == (2 if variant == 0 else 1)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("n,h,w,c,g,dtype", [
+    (2, 6, 6, 12, 3, "f16"),        # 24 bytes per position: one whole vector and one of four channels
+    (2, 9, 7, 100, 4, "f16"),       # 25 channels per group, last vector of four
+    (3, 5, 5, 6, 2, "f32"),         # fp32, 24 bytes per position
+    (1, 20, 20, 36, 36, "bf16"),    # one channel per group
+    (2, 33, 33, 50, 1, "f16"),      # one group, several workgroups per sample
+    (2, 4, 4, 3, 1, "f16"),         # fewer channels than one vector
+])
+def test_groupnorm_channel_counts_that_are_not_whole_vectors(n, h, w, c, g, dtype, variant):
+    pf = _pf()
+    spec, ins = wl.c5_groupnorm_silu(n=n, h=h, w=w, ch=c, groups=g, dtype=dtype, salt=13)
+    _, info, _ = check_chain(spec, ins, variant=variant, what=f"GroupNorm {c} channels (ragged) / {g} groups {dtype} v{variant}")
+    assert info.family == pf.PF_FAMILY_GROUP and info.variant == variant
+    assert info.n_launches == (2 if variant == 0 else 1)
+
+
+@pytest.mark.parametrize("c,g,dtype", [(12, 3, "f16"), (6, 2, "f32"), (100, 4, "bf16")])
+def test_groupnorm_ragged_channels_on_the_interpreted_kernels(c, g, dtype):
+    spec, ins = wl.c5_groupnorm_silu(n=2, h=9, w=7, ch=c, groups=g, dtype=dtype, salt=14)
+    _, info, _ = check_chain(spec, ins, variant=0, generic=True, what=f"GroupNorm {c} channels (ragged), interpreted")
+    assert info.spec_id == 0 and info.n_launches == 2
+
+
+def test_groupnorm_with_residual_on_a_ragged_channel_count():
+    # a second full-shape operand and a per-sample operand in front of the normalisation, 20 bytes per position
+    c = 10
+    shape = (3, 7, 5, c)
+    x, res = wl.random_tensor(shape, "f16", 1901), wl.random_tensor(shape, "f16", 1902)
+    gamma, beta = wl.random_tensor((c,), "f16", 1903, dist="positive"), wl.random_tensor((c,), "f16", 1904, scale=0.3)
+    s = wl.ChainSpec(inputs=[("f16", shape), ("f16", shape), ("f16", (c,)), ("f16", (c,))])
+    s.out(s.op("relu", s.op("groupnorm", s.op("add", 0, 1), 2, 3, f=[1e-5], i=[2])), "f16")
+    check_chain(s, [x, res, gamma, beta], what="GroupNorm(x + res) on 10 channels")
+
+
 def test_groupnorm_of_single_element_groups_returns_beta_exactly():
     # one position, one channel per group: every deviation is exactly zero, the result is beta (1 / sqrt(eps) would
     # amplify a one-ulp error of the mean to 3e-5)
