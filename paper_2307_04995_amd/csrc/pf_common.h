@@ -234,6 +234,7 @@ struct StencilGeom {
     FastDiv div_cv;
     uint32_t stride, oh, ow, out_row_vecs; // strided variant: stride along both axes, output extents, ow * cv
     uint32_t strip_rows;                   // strided variant: output rows per workgroup
+    uint32_t ragged;                       // 1: c is not a whole number of 16-byte vectors (cv counts the partial one)
 };
 
 // Gather family: layout-only chains as a copy of contiguous runs.  Run k of the table moves run_elems elements

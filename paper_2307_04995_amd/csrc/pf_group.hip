@@ -41,6 +41,10 @@ static hipError_t launch_group_dt(int phase, bool general, const ChainArgs& a, c
         // groups of any width: built in the run-time-interpreted, two-launch form only (the rest is specialised when
         // the plan is made)
         if constexpr (ID == 0) {
+            if (g.ragged) {
+                if (phase == 1) return launch_group_nv<0, DT, 1, 3>(a, g, nv, tiles, grid, block, lds, st);
+                if (phase == 2) return launch_group_nv<0, DT, 2, 3>(a, g, nv, tiles, grid, block, lds, st);
+            }
             if (phase == 1) return launch_group_nv<0, DT, 1, 1>(a, g, nv, tiles, grid, block, lds, st);
             if (phase == 2) return launch_group_nv<0, DT, 2, 1>(a, g, nv, tiles, grid, block, lds, st);
         }

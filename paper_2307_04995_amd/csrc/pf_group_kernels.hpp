@@ -250,7 +250,7 @@ PF_DEVICE bool merge_parts_of_block(const GroupGeom& g, const float* lds_gen, ui
 // (agent-scope atomic) accesses, so no cache write-back or invalidate is needed around them -- a write-back
 // here would wait for every output line other workgroups have just stored.
 //
-// GEN != 0: groups of any width (see merge_parts_of_block); needs 512 * parts * 12 bytes of dynamic LDS, `parts`
+// GEN != 0: groups of any width (see merge_parts_of_block; 2 and 3 are described at their use); needs 512 * parts * 12 bytes of dynamic LDS, `parts`
 // being the most groups one vector touches.
 template <int DT, int NV, class Spec, int PHASE, int GEN = 0>
 __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles) {
@@ -270,10 +270,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     // GEN: the part (group, relative to the lane's first group) each element of the lane's vector belongs to,
     // four bits per element
     uint32_t part_code = 0, first_grp = 0;
-    // GEN == 1 kernels also serve channel counts that are not whole vectors: a position then starts at element
+    // GEN == 3: general kernels for channel counts that are not whole vectors: a position then starts at element
     // alignment and its last vector holds `cnt` channels (elements past them are never read, counted or stored)
-    constexpr bool kRag = GEN == 1;
-    const bool ragged = kRag && g.ragged != 0u;
+    constexpr bool ragged = GEN == 3;
     const uint32_t cnt = ragged ? elems_below<VEC>(cvi * (uint32_t)VEC, g.channels) : (uint32_t)VEC;
     if (GEN) {
         first_grp = fast_div(cvi * (uint32_t)VEC, g.div_cpg);

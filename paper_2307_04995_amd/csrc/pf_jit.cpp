@@ -191,11 +191,12 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int gen
     return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
 }
 
-hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, const JitSpec& spec, std::string* err) {
+hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
-    if (variant == 2) name << "pf::dwconv_strided_kernel<" << dtype << ", " << spec_text(spec) << ", " << ks << ">";
-    else if (variant == 1) name << "pf::dwconv_staged_kernel<" << dtype << ", " << spec_text(spec) << ", " << ks << ">";
-    else name << "pf::dwconv3x3_kernel<" << dtype << ", " << spec_text(spec) << ">";
+    const char* rg = ragged ? ", true>" : ", false>";
+    if (variant == 2) name << "pf::dwconv_strided_kernel<" << dtype << ", " << spec_text(spec) << ", " << ks << rg;
+    else if (variant == 1) name << "pf::dwconv_staged_kernel<" << dtype << ", " << spec_text(spec) << ", " << ks << rg;
+    else name << "pf::dwconv3x3_kernel<" << dtype << ", " << spec_text(spec) << rg;
     return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
 }
 

@@ -38,7 +38,7 @@ hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, bool ra
 // group family: phase 0 fused, 1 statistics, 2 normalisation
 hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err);
 // stencil family (depthwise 3 x 3 convolution)
-hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, const JitSpec& spec, std::string* err);
+hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err);
 // workgroups of `block_threads` threads one compute unit holds at once
 hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err);
 int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes = 0);

@@ -703,7 +703,8 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     p->group_general = general;
     // 2: statistics straight from the packed 16-bit pairs (needs pairs that never straddle groups and nothing but the
     // load in front of the normalisation; the kernel checks the rest at compile time)
-    const int gen_parts = !general ? 0 : ((!ragged_c && cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
+    // 3: channel counts that are not whole vectors
+    const int gen_parts = !general ? 0 : ragged_c ? 3 : ((cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);
@@ -851,8 +852,9 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     const int ksz = (int)ks[0];
     const int out_rows = ksz == 3 ? kStencilRowsHost : kStencilRows5Host;
     const int64_t n = xs[0], h = xs[1], w = xs[2], ch = xs[3];
-    if ((ch * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)ch);
-    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the stencil family is not a multiple of 16 bytes");
+    // a channel count that is not a whole number of vectors: element-aligned positions, a partial last vector
+    const bool ragged_c = (ch * es) % 16 != 0;
+    if (p->ragged && !ragged_c) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the stencil family is not a multiple of 16 bytes");
     if (n * h * w > 0xffffffffLL || n > 65535 || (h + out_rows - 1) / out_rows > 65535) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the stencil family");
     if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the stencil family");
     for (int i = 0; i < L.pro.n; ++i)
@@ -865,7 +867,8 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     g.h = (uint32_t)h;
     g.w = (uint32_t)w;
     g.c = (uint32_t)ch;
-    g.cv = (uint32_t)(ch / vec);
+    g.cv = (uint32_t)((ch + vec - 1) / vec);
+    g.ragged = ragged_c ? 1u : 0u;
     g.row_vecs = (uint32_t)(w * g.cv);
     g.div_cv = make_fastdiv(g.cv);
     for (int f = 0; f < L.n_full; ++f)
@@ -906,7 +909,7 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
         p->grid = dim3((uint32_t)tiles_x, (uint32_t)((oh + strip - 1) / strip), (uint32_t)n);
         if (jit_possible(p->device)) {
             std::string err;
-            p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, p->variant, ksz, make_jit_spec(L), &err);
+            p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, p->variant, ksz, ragged_c, make_jit_spec(L), &err);
             if (p->jit_fn) p->spec_id = pf::kSpecJit;
             else note_interpreter_fallback(p, err);
         }
@@ -950,7 +953,7 @@ pf_status plan_stencil(pf_plan_s* p, const Checked& c, int forced_variant) {
     }
     if (jit_ok) {
         std::string err;
-        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, ksz, make_jit_spec(L), &err);
+        p->jit_fn = pf::jit_stencil_kernel(p->device, L.main_dtype, variant, ksz, ragged_c, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else {
             note_interpreter_fallback(p, err);

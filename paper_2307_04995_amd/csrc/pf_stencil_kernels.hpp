@@ -17,10 +17,28 @@
 
 namespace pf {
 
+// Memory access of the family.  ragged (a compile-time fact of the kernel: a run-time test at every load costs the
+// aligned kernels a third of their speed): the channel count is not a whole number of vectors, so a position starts at
+// element alignment and its last vector holds `cnt` channels; the rest of that vector reads as zero (and contributes
+// zero to every tap) and is not stored.
+template <int DT>
+PF_DEVICE u32x4 stencil_load(const void* base, uint64_t elem, bool ragged, uint32_t cnt) {
+    return ragged ? load_elems<DT>(base, elem, cnt, 0u) : load_cached(base, elem * Storage<DT>::ESIZE);
+}
+template <int DT>
+PF_DEVICE void stencil_store(void* base, uint64_t elem, bool ragged, uint32_t cnt, u32x4 v) {
+    if (ragged) store_elems<DT>(base, elem, cnt, v);
+    else store_stream(base, elem * Storage<DT>::ESIZE, v);
+}
+template <int DT, int VM>
+PF_DEVICE u32x4 stencil_load_vec(const VecArg& va, uint32_t row, uint32_t col, uint32_t n, bool ragged, uint32_t cnt) {
+    return ragged ? load_vec_operand_elems<DT, VM>(va, row, col, n, cnt) : load_vec_operand<DT, VM>(va, row, col, n);
+}
+
 constexpr int kStencilRows = 6;   // output rows per strip, 3 x 3 kernels (8 input rows are read for them)
 constexpr int kStencilRows5 = 4;  // output rows per strip, 5 x 5 kernels (staged variant only; 8 input rows as well)
 
-template <int DT, class Spec>
+template <int DT, class Spec, bool RAGGED = false>
 __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const StencilGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -28,6 +46,8 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
     if (t >= g.row_vecs) return;
     const uint32_t wcol = fast_div(t, g.div_cv);
     const uint32_t cvi = t - wcol * g.cv;
+    constexpr bool ragged = RAGGED;
+    const uint32_t cnt = ragged ? elems_below<Storage<DT>::VEC>(cvi * (uint32_t)Storage<DT>::VEC, g.c) : (uint32_t)Storage<DT>::VEC;
     const uint32_t sample = blockIdx.z;
     const uint32_t h0 = blockIdx.y * (uint32_t)kStencilRows;
     const int wslot = Spec::gamma(a);  // broadcast slot that holds the kernels [3, 3, channels]
@@ -36,7 +56,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
     u32x4 wraw[9];
 #pragma unroll
     for (int k = 0; k < 9; ++k)
-        wraw[k] = load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE);
+        wraw[k] = stencil_load<DT>(a.vec[wslot].ptr, (uint64_t)k * g.c + cvi * VEC, ragged, cnt);
 
     // which operands each side of the convolution reads: known at compile time for a specialised kernel
     const uint32_t pro_full = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_FULL) : ~g.epi_full_mask;
@@ -56,11 +76,11 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
         for (int f = 0; f < Spec::NF; ++f)
             if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
-                s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+                s.fraw[f][0] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
+                s.vraw[v][0] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c, ragged, cnt);
     };
 
     uint32_t win[3][3][WE];  // activated values (fp32 bits, or packed): window row (input row mod 3), column -1 / 0 / +1
@@ -79,11 +99,11 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
             for (int f = 0; f < Spec::NF; ++f)
                 if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
-                    pend_f[dw][f] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+                    pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
 #pragma unroll
             for (int v = 0; v < Spec::NV; ++v)
                 if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                    pend_v[dw][v] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
+                    pend_v[dw][v] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c, ragged, cnt);
         }
     };
     auto admit_row = [&](int r, int slot) {
@@ -148,7 +168,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-        store_stream(a.out[0], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE, S::pack(s.acc));
+        stencil_store<DT>(a.out[0], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt, S::pack(s.acc));
     }
 }
 
@@ -163,7 +183,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 //
 // LDS layout: tile[input row 0..7][staging lane 0 .. 256 + 2 cv), entries of 16 bytes (packed storage type, when
 // the prologue keeps storage precision) or 32 bytes (fp32).  Lanes read consecutive entries: no bank conflicts.
-template <int DT, class Spec, int KS>
+template <int DT, class Spec, int KS, bool RAGGED = false>
 __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, const StencilGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -203,6 +223,8 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
         const uint32_t lp = lane_ok ? (uint32_t)lane_pos : 0u;
         const uint32_t wcol = fast_div(lp, g.div_cv);
         const uint32_t cvi = lp - wcol * cv;
+        constexpr bool ragged = RAGGED;
+        const uint32_t cnt = ragged ? elems_below<Storage<DT>::VEC>(cvi * (uint32_t)Storage<DT>::VEC, g.c) : (uint32_t)Storage<DT>::VEC;
         s.col[0] = cvi * VEC;
         u32x4 pend_f[kRows][at_least_1(Spec::NF)];
 #pragma unroll
@@ -214,7 +236,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
             for (int f = 0; f < Spec::NF; ++f) {
                 pend_f[r][f] = u32x4{0u, 0u, 0u, 0u};
                 if (f < Spec::n_full(a) && ((pro_full >> f) & 1u) && ok)
-                    pend_f[r][f] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+                    pend_f[r][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
             }
         }
 #pragma unroll
@@ -229,7 +251,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v)
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                        s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.c);
+                        s.vraw[v][0] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], s.row[0], s.col[0], g.c, ragged, cnt);
                 run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
             }
             u32x4* dst = tile + ((uint32_t)r * tw + j) * EV;
@@ -253,6 +275,8 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
     if (t >= g.row_vecs) return;
     const uint32_t wcol = fast_div(t, g.div_cv);
     const uint32_t cvi = t - wcol * cv;
+    constexpr bool ragged = RAGGED;
+    const uint32_t cnt = ragged ? elems_below<Storage<DT>::VEC>(cvi * (uint32_t)Storage<DT>::VEC, g.c) : (uint32_t)Storage<DT>::VEC;
     s.col[0] = cvi * VEC;
     // fp16 tile entries meet fp16 kernels: the multiply-add takes both halves of the packed registers directly
     // (v_fma_mix_f32 widens them on the fly), so nothing is unpacked in the inner loop
@@ -262,7 +286,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
     constexpr int NW = kKeepW ? KS * KS : 1;
     u32x4 wraw[NW];
     float wf[(kMix || !kKeepW) ? 1 : NW][VEC];
-    auto load_w = [&](int k) { return load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE); };
+    auto load_w = [&](int k) { return stencil_load<DT>(a.vec[wslot].ptr, (uint64_t)k * g.c + cvi * VEC, ragged, cnt); };
     if (kKeepW) {
 #pragma unroll
         for (int k = 0; k < NW; ++k) {
@@ -321,15 +345,15 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
 #pragma unroll
         for (int f = 0; f < Spec::NF; ++f)
             if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
-                s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE);
+                s.fraw[f][0] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c);
+                s.vraw[v][0] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.c, ragged, cnt);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-        store_stream(a.out[0], ((uint64_t)pos * g.c + cvi * VEC) * S::ESIZE, S::pack(s.acc));
+        stencil_store<DT>(a.out[0], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt, S::pack(s.acc));
     }
 }
 
@@ -339,7 +363,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
 // taps of an output are loaded where they are used, one kernel row's loads in flight together, and what
 // neighbouring lanes and rows read twice comes from the first-level cache.  The prologue runs on every tap.
 
-template <int DT, class Spec, int KS>
+template <int DT, class Spec, int KS, bool RAGGED = false>
 __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, const StencilGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -349,6 +373,8 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
     if (t >= g.out_row_vecs) return;
     const uint32_t ocol = fast_div(t, g.div_cv);
     const uint32_t cvi = t - ocol * g.cv;
+    constexpr bool ragged = RAGGED;
+    const uint32_t cnt = ragged ? elems_below<Storage<DT>::VEC>(cvi * (uint32_t)Storage<DT>::VEC, g.c) : (uint32_t)Storage<DT>::VEC;
     const uint32_t sample = blockIdx.z;
     const uint32_t i0 = blockIdx.y * g.strip_rows;  // strip_rows output rows per workgroup (the planner keeps the grid large)
     const int wslot = Spec::gamma(a);
@@ -356,7 +382,7 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
     const uint32_t pro_vec = Spec::kStatic ? list_operand_mask<typename Spec::Pro>(K_VEC) : ~g.epi_vec_mask;
     const uint32_t epi_full = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_FULL) : g.epi_full_mask;
     const uint32_t epi_vec = Spec::kStatic ? list_operand_mask<typename Spec::Epi>(K_VEC) : g.epi_vec_mask;
-    auto load_w = [&](int k) { return load_cached(a.vec[wslot].ptr, ((uint64_t)k * g.c + cvi * VEC) * S::ESIZE); };
+    auto load_w = [&](int k) { return stencil_load<DT>(a.vec[wslot].ptr, (uint64_t)k * g.c + cvi * VEC, ragged, cnt); };
     // 3 x 3: the nine kernel vectors stay in registers; 5 x 5: read where they are used (first-level cache)
     constexpr bool kKeepW = KS == 3;
     u32x4 wraw[kKeepW ? KS * KS : 1];
@@ -389,11 +415,11 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
 #pragma unroll
                 for (int f = 0; f < Spec::NF; ++f)
                     if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
-                        pend_f[dw][f] = load_cached(a.full[f], ((uint64_t)pos[dw] * g.c + cvi * VEC) * S::ESIZE);
+                        pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos[dw] * g.c + cvi * VEC, ragged, cnt);
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v)
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
-                        pend_v[dw][v] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos[dw], s.col[0], g.c);
+                        pend_v[dw][v] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], pos[dw], s.col[0], g.c, ragged, cnt);
             }
 #pragma unroll
             for (int dw = 0; dw < KS; ++dw) {
@@ -417,15 +443,15 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
 #pragma unroll
         for (int f = 0; f < Spec::NF; ++f)
             if (f < Spec::n_full(a) && ((epi_full >> f) & 1u))
-                s.fraw[f][0] = load_cached(a.full[f], ((uint64_t)opos * g.c + cvi * VEC) * S::ESIZE);
+                s.fraw[f][0] = stencil_load<DT>(a.full[f], (uint64_t)opos * g.c + cvi * VEC, ragged, cnt);
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v)
             if (v < Spec::n_vec(a) && v != wslot && ((epi_vec >> v) & 1u))
-                s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], opos, s.col[0], g.c);
+                s.vraw[v][0] = stencil_load_vec<DT, Spec::kVecMode>(a.vec[v], opos, s.col[0], g.c, ragged, cnt);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
         run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-        store_stream(a.out[0], ((uint64_t)opos * g.c + cvi * VEC) * S::ESIZE, S::pack(s.acc));
+        stencil_store<DT>(a.out[0], (uint64_t)opos * g.c + cvi * VEC, ragged, cnt, S::pack(s.acc));
     }
 }
 

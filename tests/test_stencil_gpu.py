@@ -25,6 +25,29 @@ def test_relu_depthwise_conv_bias(n, h, w, c, dtype, variant):
     assert info.spec_id == SPEC_JIT
 
 
+@pytest.mark.parametrize("n,h,w,c,k,stride,dtype", [
+    (2, 9, 11, 12, 3, 1, "f16"),     # 24 bytes per position: one whole vector and one of four channels
+    (1, 7, 7, 100, 3, 1, "bf16"),    # last vector of four
+    (2, 6, 5, 6, 3, 1, "f32"),       # fp32, 24 bytes per position
+    (1, 10, 9, 20, 5, 1, "f16"),     # 5 x 5 kernel (staged variant)
+    (2, 11, 13, 36, 3, 2, "f16"),    # down-sampling convolution
+    (1, 5, 5, 3, 3, 1, "f16"),       # fewer channels than one vector
+])
+def test_convolution_on_channel_counts_that_are_not_whole_vectors(n, h, w, c, k, stride, dtype):
+    pf = _pf()
+    spec, ins = wl.x4_relu_dwconv(n=n, h=h, w=w, c=c, k=k, dtype=dtype, stride=stride, salt=3)
+    variants = (None,) if (k == 5 or stride != 1) else (0, 1)
+    for variant in variants:
+        _, info, _ = check_chain(spec, ins, variant=variant, what=f"relu -> dwconv {k}x{k}/{stride} -> bias, {c} channels (ragged) {dtype} variant {variant}")
+        assert info.family == pf.PF_FAMILY_STENCIL and info.n_launches == 1
+
+
+def test_convolution_on_ragged_channels_interpreted():
+    spec, ins = wl.x4_relu_dwconv(n=1, h=6, w=7, c=12, dtype="f16", salt=4)
+    _, info, _ = check_chain(spec, ins, generic=True, what="relu -> dwconv -> bias, 12 channels, interpreted kernel")
+    assert info.spec_id == 0
+
+
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_convolution_alone_and_asymmetric_kernel(dtype):
     # distinct weights in all nine taps, no other operator: tap order and padding show directly
