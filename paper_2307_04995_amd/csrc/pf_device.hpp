@@ -37,7 +37,7 @@ template <>
 struct Storage<DT_F32> {
     static constexpr int VEC = 4;      // elements per 16-byte vector
     static constexpr int ESIZE = 4;
-    static constexpr bool PRECISE = true;  // fp32 results are held to 1e-5: use correctly rounded math
+    static constexpr bool PRECISE = true;  // fp32 results are held to 1e-5: correctly rounded exp, division, square root (GELU: see pf_gelu_erf)
     static PF_DEVICE void unpack(u32x4 raw, float* out) {
         f32x4 v = __builtin_bit_cast(f32x4, raw);
         out[0] = v[0]; out[1] = v[1]; out[2] = v[2]; out[3] = v[3];

@@ -180,7 +180,9 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
             for (int c = 0; c < KC; ++c) {
                 const int k = k0 + c;
                 if (WHOLE) {
-                    s.vraw[v][k] = load_cached(a.vec[v].ptr, (uint64_t)s.col[k] * S::ESIZE);  // (a vector of the row's length)
+                    // a vector of the row's length: the same for every row the wave holds, loaded for the first only
+                    if (k0 > 0) s.vraw[v][k] = s.vraw[v][c];
+                    else s.vraw[v][k] = load_cached(a.vec[v].ptr, (uint64_t)s.col[k] * S::ESIZE);
                     continue;
                 }
                 s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
