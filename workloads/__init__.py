@@ -736,9 +736,9 @@ def random_multi_kernel_chain(seed: int):
         if st == "softmax":
             v = s.op("softmax", v)
         elif st == "layernorm":
-            v = s.op("layernorm", v, item[1], item[2], f=[2.0 ** -16])
+            v = s.op("layernorm", v, item[1], item[2], f=[1e-5])
         elif st == "rmsnorm":
-            v = s.op("rmsnorm", v, item[1], f=[2.0 ** -16])
+            v = s.op("rmsnorm", v, item[1], f=[1e-5])
         elif st == "swap_leading":
             v = s.op("permute", v, i=[1, 0, 2])
         elif st == "transpose_inner":
