@@ -167,9 +167,25 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                     s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
                     continue;
                 }
-                s.fraw[f][k] = u32x4{fill, fill, fill, fill};
-                if (RAGGED) s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill);
-                else if (s.col[k] < load_limit) s.fraw[f][k] = load_stream(base, s.col[k] * (uint32_t)S::ESIZE);
+                if (RAGGED) {
+                    s.fraw[f][k] = u32x4{fill, fill, fill, fill};
+                    s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill);
+                } else {
+                    // No branch around the load: a lane past the limit reads the last vector inside it (the same
+                    // memory line as its neighbour: no extra traffic; `row_byte` always addresses a row that
+                    // exists) and the fill value is selected afterwards.  A guarded load would merge with the fill
+                    // value at the join, which the compiler resolves by waiting for the load: every later load of
+                    // the wave would then be issued one memory round trip late.
+                    const uint32_t lim = load_limit != 0u ? load_limit : a.n_inner;
+                    const uint32_t colc = min(s.col[k], lim - (uint32_t)S::VEC);
+                    const u32x4 got = load_stream(base, colc * (uint32_t)S::ESIZE);
+                    const bool keep = s.col[k] < load_limit;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t w = got[j];
+                        s.fraw[f][k][j] = keep ? w : fill;
+                    }
+                }
             }
         }
     }
@@ -185,10 +201,14 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                     else s.vraw[v][k] = load_cached(a.vec[v].ptr, (uint64_t)s.col[k] * S::ESIZE);
                     continue;
                 }
-                s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
-                if (RAGGED)
+                if (RAGGED) {
+                    s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
                     s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
-                else if (s.col[k] < limit) s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner);
+                } else {
+                    // (as above; values of lanes past the row's end are never used)
+                    const uint32_t colc = min(s.col[k], a.n_inner - (uint32_t)S::VEC);
+                    s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, colc, a.n_inner);
+                }
             }
         }
     }
@@ -271,7 +291,9 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
             s.col[r * KC + c] = (lane_in_row + LPR * wpr * c) * VEC;
         }
         row_byte[r] = row64 * n * S::ESIZE;
-        load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_byte[r], row, load_limit, limit[r], fill);
+        // (loads of a row past the end of the tensor are aimed at the last row and discarded)
+        const uint64_t row_in = RAGGED ? row64 : min(row64, a.rows - 1u);
+        load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_in * n * S::ESIZE, (uint32_t)row_in, load_limit, limit[r], fill);
     }
 
     // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
@@ -436,8 +458,8 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
         s.row[k] = row;
         s.col[k] = (lane_in_row + 64u * wpr * k) * VEC;
     }
-    const uint64_t row_byte = row64 * n * S::ESIZE;
-    load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_byte, row, limit, limit, 0u);
+    const uint64_t row_in = RAGGED ? row64 : min(row64, a.rows - 1u);  // (a row past the end: loads aimed at the last row, discarded)
+    load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_in * n * S::ESIZE, (uint32_t)row_in, limit, limit, 0u);
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
     auto valid_elem = [&](int k, int e) { return RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit; };
     float r;
