@@ -185,6 +185,34 @@ hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, bool ra
     return compile(device, "#include \"pf_perm_kernels.hpp\"\n", name.str(), err);
 }
 
+// The row-permutation kernel with this launch's geometry as constants: a generated type in front of the kernel's
+// name, named by a hash of its contents (the cache key is the name expression).
+hipFunction_t jit_perm_rows_const(int device, int dtype, int k, const JitSpec& spec, const PermGeom& g, const uint32_t* vec_numel,
+                                  const uint32_t* vec_period, std::string* err) {
+    std::ostringstream body;
+    auto list = [&](const char* what, const uint32_t* v, int n) {
+        body << "    static constexpr unsigned " << what << "[" << n << "] = {";
+        for (int i = 0; i < n; ++i) body << (i ? ", " : "") << v[i] << "u";
+        body << "};\n";
+    };
+    body << "    static constexpr bool kConst = true;\n    static constexpr int rank = " << g.rank << ";\n";
+    list("extent", g.extent, PF_DEV_MAX_RANK);
+    list("in_stride", g.in_stride, PF_DEV_MAX_RANK);
+    list("out_stride", g.out_stride, PF_DEV_MAX_RANK);
+    list("vec_numel", vec_numel, PF_DEV_MAX_VEC);
+    list("vec_period", vec_period, PF_DEV_MAX_VEC);
+    body << "    static constexpr unsigned in_n_inner = " << g.in_n_inner << "u, out_n_inner = " << g.out_n_inner << "u, total_vecs = " << g.total_vecs
+         << "u, epi_full_mask = " << g.epi_full_mask << "u, epi_vec_mask = " << g.epi_vec_mask << "u;\n";
+    const std::string text = body.str();
+    uint64_t h = 1469598103934665603ull;  // FNV-1a
+    for (unsigned char c : text) h = (h ^ c) * 1099511628211ull;
+    std::ostringstream type, source, name;
+    type << "PfPermGeom_" << std::hex << h;
+    source << "#include \"pf_perm_kernels.hpp\"\nstruct " << type.str() << " {\n" << text << "};\n";
+    name << "pf::perm_rows_kernel<" << dtype << ", " << k << ", " << spec_text(spec) << ", false, " << type.str() << ">";
+    return compile(device, source.str(), name.str(), err);
+}
+
 hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
     name << "pf::group_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << phase << ", " << general_parts << ">";

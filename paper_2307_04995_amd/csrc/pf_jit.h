@@ -35,6 +35,10 @@ hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const Jit
 
 // transpose family: variant 0 rows (k vectors per lane), 1 LDS-staged rows, 2 register-transposed tiles
 hipFunction_t jit_perm_kernel(int device, int dtype, int variant, int k, bool ragged, const JitSpec& spec, std::string* err);
+// the rows variant with the geometry of one launch shape as compile-time constants (vec_numel / vec_period: element
+// count and row period of each broadcast operand, PF_DEV_MAX_VEC entries)
+hipFunction_t jit_perm_rows_const(int device, int dtype, int k, const JitSpec& spec, const PermGeom& g, const uint32_t* vec_numel,
+                                  const uint32_t* vec_period, std::string* err);
 // group family: phase 0 fused, 1 statistics, 2 normalisation
 hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err);
 // stencil family (depthwise 3 x 3 convolution)

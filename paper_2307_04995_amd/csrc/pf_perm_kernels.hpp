@@ -40,12 +40,78 @@ PF_DEVICE void perm_offsets(const PermGeom& g, uint32_t v, uint32_t vec, uint32_
     *out_off = oo;
 }
 
+// Geometry as a compile-time fact.  Splitting an index over up to six dimensions whose extents are kernel arguments
+// costs a lane a dozen 32-bit multiplications per vector, more instructions than the rest of a permutation kernel
+// together.  For large tensors the planner therefore hands the run-time compiler a type that holds the geometry as
+// constants (same members as below, kConst = true, plus what it knows about the broadcast operands): divisions by
+// powers of two become shifts, the others multiplications by constants, and nothing is loaded or branched on.
+// RuntimePermGeom stands for "read the PermGeom argument".
+struct RuntimePermGeom {
+    static constexpr bool kConst = false;
+};
+
+template <class CG>
+PF_DEVICE void perm_offsets_t(const PermGeom& g, uint32_t v, uint32_t vec, uint32_t* in_off, uint32_t* out_off) {
+    if constexpr (!CG::kConst) {
+        perm_offsets(g, v, vec, in_off, out_off);
+    } else {
+        uint32_t io = 0, oo = 0, rem = v;
+#pragma unroll
+        for (int q = CG::rank - 1; q >= 0; --q) {
+            const uint32_t quo = (q == 0) ? 0u : rem / CG::extent[q];
+            const uint32_t idx = (q == 0) ? rem : rem - quo * CG::extent[q];
+            const uint32_t scale = (q == CG::rank - 1) ? vec : 1u;
+            io += idx * (scale * CG::in_stride[q]);
+            oo += idx * (scale * CG::out_stride[q]);
+            rem = quo;
+        }
+        *in_off = io;
+        *out_off = oo;
+    }
+}
+
 // SIDES: 3 = operands of both programs, 1 = prologue operands only (input layout), 2 = epilogue operands only
 // RAGGED: vectors may start at any element and hold fewer than VEC elements (cnt[k] of them; 0 = none)
-template <int DT, int K, class Spec, int SIDES = 3, bool RAGGED = false>
+template <int DT, int K, class Spec, int SIDES = 3, bool RAGGED = false, class CG = RuntimePermGeom>
 PF_DEVICE void perm_load_operands(const ChainArgs& a, const PermGeom& g, LaneState<DT, K, Spec>& s, const uint32_t* in_off,
                                   const uint32_t* out_off, const bool* valid, const uint32_t* cnt = nullptr) {
     using S = Storage<DT>;
+    if constexpr (CG::kConst && !RAGGED && (Spec::kVecMode & 1) == 0) {
+        // every mask, extent and operand length is a constant: plain address arithmetic, no division at run time
+#pragma unroll
+        for (int f = 0; f < Spec::NF; ++f) {
+            const bool epi = (CG::epi_full_mask >> f) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.fraw[f][k] = u32x4{0u, 0u, 0u, 0u};
+                if (valid[k]) s.fraw[f][k] = load_stream(a.full[f], (uint64_t)(epi ? out_off[k] : in_off[k]) * S::ESIZE);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < Spec::NV; ++v) {
+            const bool epi = (CG::epi_vec_mask >> v) & 1u;
+            if ((epi && !(SIDES & 2)) || (!epi && !(SIDES & 1))) continue;
+            constexpr uint32_t in_inner = CG::in_n_inner, out_inner = CG::out_n_inner;
+            const uint32_t inner = epi ? out_inner : in_inner;
+            const uint32_t numel = CG::vec_numel[v], period = CG::vec_period[v];
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
+                if (!valid[k]) continue;
+                const uint32_t off = epi ? out_off[k] : in_off[k];
+                if ((Spec::kVecMode & 2) && numel == 1u) {
+                    s.vraw[v][k] = S::splat(a.vec[v].ptr);
+                    continue;
+                }
+                const uint32_t row = epi ? off / out_inner : off / in_inner;
+                const uint32_t col = off - row * inner;
+                const uint32_t o = numel >= inner ? (period == 1u ? 0u : row % period) * inner + col : col % numel;
+                s.vraw[v][k] = load_cached(a.vec[v].ptr, (uint64_t)o * S::ESIZE);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int f = 0; f < Spec::NF; ++f) {
         if (f < Spec::n_full(a)) {
@@ -89,12 +155,23 @@ PF_DEVICE void set_positions(LaneState<DT, K, Spec>& s, const uint32_t* off, con
     }
 }
 
+template <int DT, int K, class Spec, uint32_t INNER>
+PF_DEVICE void set_positions_c(LaneState<DT, K, Spec>& s, const uint32_t* off) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        s.row[k] = off[k] / INNER;
+        s.col[k] = off[k] - s.row[k] * INNER;
+    }
+}
+
 // RAGGED: the innermost extent (kept by the permutation) is not a whole number of vectors; the last vector of
 // every innermost run is partial and all of them start at element alignment.
-template <int DT, int K, class Spec, bool RAGGED = false>
+// CG: RuntimePermGeom, or a type that holds this launch's geometry as constants (see above).
+template <int DT, int K, class Spec, bool RAGGED = false, class CG = RuntimePermGeom>
 __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const PermGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
+    static_assert(!(CG::kConst && RAGGED), "constant geometry is for whole vectors");
     LaneState<DT, K, Spec> s;
     uint32_t in_off[K], out_off[K], cnt[K];
     bool valid[K];
@@ -102,8 +179,9 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t v = base + 256u * k;
-        valid[k] = v < g.total_vecs;
-        perm_offsets(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
+        if constexpr (CG::kConst) valid[k] = v < CG::total_vecs;
+        else valid[k] = v < g.total_vecs;
+        perm_offsets_t<CG>(g, valid[k] ? v : 0u, VEC, &in_off[k], &out_off[k]);
         cnt[k] = (uint32_t)VEC;
         if (RAGGED) {
             // position inside the innermost run (tile_a elements long here): the last iteration dimension counts its vectors
@@ -112,7 +190,7 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
             cnt[k] = elems_below<VEC>(iv * (uint32_t)VEC, g.tile_a);
         }
     }
-    perm_load_operands<DT, K, Spec, 3, RAGGED>(a, g, s, in_off, out_off, valid, cnt);
+    perm_load_operands<DT, K, Spec, 3, RAGGED, CG>(a, g, s, in_off, out_off, valid, cnt);
     auto store = [&](int k, u32x4 v) {
         if (RAGGED) store_elems<DT>(a.out[0], out_off[k], cnt[k], v);
         else store_stream(a.out[0], (uint64_t)out_off[k] * S::ESIZE, v);
@@ -124,9 +202,11 @@ __global__ void __launch_bounds__(256) perm_rows_kernel(const ChainArgs a, const
             if (valid[k]) store(k, s.fraw[0][k]);
         return;
     }
-    set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
+    if constexpr (CG::kConst) set_positions_c<DT, K, Spec, CG::in_n_inner>(s, in_off);
+    else set_positions<DT, K, Spec>(s, in_off, g.div_in_inner, g.in_n_inner);
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
-    set_positions<DT, K, Spec>(s, out_off, g.div_out_inner, g.out_n_inner);
+    if constexpr (CG::kConst) set_positions_c<DT, K, Spec, CG::out_n_inner>(s, out_off);
+    else set_positions<DT, K, Spec>(s, out_off, g.div_out_inner, g.out_n_inner);
     run_program<DT, K, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
 #pragma unroll
     for (int k = 0; k < K; ++k)

@@ -648,6 +648,23 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
         p->lds_bytes = 0;
     }
+    // Large tensors on the rows variant: the kernel is compiled for this geometry (index arithmetic on constants).  Worth
+    // a compilation per shape only where the launch is long enough to notice; smaller ones keep the run-time geometry.
+    if (p->variant == PF_VARIANT_T_ROWS && !ragged && !L.general_bcast && g.total_vecs >= (1u << 20) && jit_possible(p->device) &&
+        env_int("PF_PERM_CONST", 1) != 0) {
+        uint32_t numel[PF_DEV_MAX_VEC] = {1, 1, 1, 1}, period[PF_DEV_MAX_VEC] = {1, 1, 1, 1};
+        for (int v = 0; v < L.n_vec; ++v) {
+            numel[v] = p->args.vec[v].numel;
+            period[v] = p->args.vec[v].period_rows;
+        }
+        std::string err;
+        hipFunction_t fn = pf::jit_perm_rows_const(p->device, L.main_dtype, p->k, make_jit_spec(L), g, numel, period, &err);
+        if (fn) {
+            p->jit_fn = fn;
+            p->spec_id = pf::kSpecJit;
+            return PF_OK;
+        }
+    }
     if (!p->spec_id && jit_possible(p->device)) {
         std::string err;
         p->jit_fn = pf::jit_perm_kernel(p->device, L.main_dtype, p->variant, p->k, ragged, make_jit_spec(L), &err);
