@@ -158,6 +158,25 @@ hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_r
     return compile(device, "#include \"pf_row_kernels.hpp\"\n", name.str(), err);
 }
 
+// The row kernel with the shape of one launch as constants (a generated type, named by a hash of its contents).
+hipFunction_t jit_row_kernel_const(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads, int log2_lanes,
+                                   const JitSpec& spec, const RowShapeConst& sh, std::string* err) {
+    std::ostringstream body;
+    body << "    static constexpr bool kConst = true;\n"
+         << "    static constexpr unsigned n_inner = " << sh.n_inner << "u, mask_si = " << sh.mask_si << "u, core_mask = " << sh.core_mask
+         << "u, vec_plain_all = " << sh.vec_plain_all << "u, waves_per_row = " << sh.waves_per_row << "u, rows_per_block = " << sh.rows_per_block
+         << "u;\n    static constexpr unsigned long long rows = " << sh.rows << "ull;\n";
+    const std::string text = body.str();
+    uint64_t h = 1469598103934665603ull;  // FNV-1a
+    for (unsigned char c : text) h = (h ^ c) * 1099511628211ull;
+    std::ostringstream type, source, name;
+    type << "PfRowShape_" << std::hex << h;
+    source << "#include \"pf_row_kernels.hpp\"\nstruct " << type.str() << " {\n" << text << "};\n";
+    name << "pf::row_kernel<" << dtype << ", " << kc << ", " << rpw << ", " << spec_text(spec) << ", " << max_threads << ", "
+         << (wave_rows ? "true" : "false") << ", " << (ragged ? "true" : "false") << ", " << log2_lanes << ", " << type.str() << ">";
+    return compile(device, source.str(), name.str(), err);
+}
+
 hipFunction_t jit_row_reduce_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
     name << "pf::row_reduce_kernel<" << dtype << ", " << k << ", " << (ragged ? "true" : "false") << ", " << spec_text(spec) << ">";

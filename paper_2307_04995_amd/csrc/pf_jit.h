@@ -29,6 +29,13 @@ uint64_t jit_compile_count();
 // log2_lanes: lanes of a wave that share one row (6 = the whole wave; less: several rows side by side)
 hipFunction_t jit_row_kernel(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads, int log2_lanes,
                              const JitSpec& spec, std::string* err);
+// the same with the launch's shape as compile-time constants
+struct RowShapeConst {
+    uint32_t n_inner, mask_si, core_mask, vec_plain_all, waves_per_row, rows_per_block;
+    uint64_t rows;
+};
+hipFunction_t jit_row_kernel_const(int device, int dtype, int kc, int rpw, bool wave_rows, bool ragged, int max_threads, int log2_lanes,
+                                   const JitSpec& spec, const RowShapeConst& sh, std::string* err);
 hipFunction_t jit_row_reduce_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);
 hipFunction_t jit_row_stream_kernel(int device, int dtype, bool ragged, const JitSpec& spec, std::string* err);
 hipFunction_t jit_ew_kernel(int device, int dtype, int k, bool ragged, const JitSpec& spec, std::string* err);

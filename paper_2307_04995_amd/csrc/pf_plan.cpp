@@ -355,6 +355,27 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         const int64_t rows_per_block = (int64_t)p->row.rows_per_block * p->row.rows_per_wave * (64 >> p->row_log2l);
         p->grid = dim3((uint32_t)((rows + rows_per_block - 1) / rows_per_block));
     }
+    // Tensors of half a megabyte and more: the kernel is compiled for this shape (row length and count, mask period and
+    // mode, waves per row as constants), which removes the tests and divisions in front of a wave's first load.  Not
+    // below that: a compilation per shape is only worth it where the launch is long enough to notice.
+    const int const_mode = env_int("PF_ROW_CONST", 1);
+    if (p->spec_id && !reduce_only && jit_ok && const_mode != 0 && (const_mode == 2 || rows * n * es >= (512 << 10))) {
+        pf::RowShapeConst sh;
+        sh.n_inner = (uint32_t)n;
+        sh.rows = (uint64_t)rows;
+        sh.mask_si = L.mask_si;
+        sh.core_mask = L.core_mask;
+        sh.vec_plain_all = p->args.vec_plain_all;
+        sh.waves_per_row = p->row.waves_per_row;
+        sh.rows_per_block = p->row.rows_per_block;
+        std::string err;
+        hipFunction_t fn = pf::jit_row_kernel_const(p->device, L.main_dtype, p->k, (int)p->row.rows_per_wave, best_wpr == 1, p->ragged,
+                                                   p->block.x <= 256 ? 256 : 1024, p->row_log2l, make_jit_spec(L), sh, &err);
+        if (fn) {
+            p->jit_fn = fn;
+            p->spec_id = pf::kSpecJit;
+        }
+    }
     return PF_OK;
 }
 

@@ -144,6 +144,51 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, 
     }
 }
 
+// The shape of a launch as a compile-time fact.  A row kernel's waves are short (one to four rows each), so what a
+// wave executes before its first load and the branches it takes on the way are a visible share of its life: whether
+// its rows fill the lanes, whether there is a causal mask and of what period, how the mask is applied, how many waves
+// share a row.  For large tensors the planner hands the run-time compiler a type that holds these as constants
+// (kConst = true and the members read below); RuntimeRowShape stands for "read the kernel arguments".
+struct RuntimeRowShape {
+    static constexpr bool kConst = false;
+};
+template <class RS>
+struct RowShape {
+    static PF_DEVICE uint32_t n_inner(const ChainArgs& a) {
+        if constexpr (RS::kConst) return RS::n_inner;
+        else return a.n_inner;
+    }
+    static PF_DEVICE uint64_t rows(const ChainArgs& a) {
+        if constexpr (RS::kConst) return RS::rows;
+        else return a.rows;
+    }
+    static PF_DEVICE uint32_t mask_si(const ChainArgs& a) {
+        if constexpr (RS::kConst) return RS::mask_si;
+        else return a.mask_si;
+    }
+    static PF_DEVICE uint32_t core_mask(const ChainArgs& a) {
+        if constexpr (RS::kConst) return RS::core_mask;
+        else return a.core_mask;
+    }
+    static PF_DEVICE uint32_t vec_plain_all(const ChainArgs& a) {
+        if constexpr (RS::kConst) return RS::vec_plain_all;
+        else return a.vec_plain_all;
+    }
+    static PF_DEVICE uint32_t waves_per_row(const RowGeom& g) {
+        if constexpr (RS::kConst) return RS::waves_per_row;
+        else return g.waves_per_row;
+    }
+    static PF_DEVICE uint32_t rows_per_block(const RowGeom& g) {
+        if constexpr (RS::kConst) return RS::rows_per_block;
+        else return g.rows_per_block;
+    }
+    // row mod mask_si
+    static PF_DEVICE uint32_t row_in_mask(const ChainArgs& a, uint32_t row) {
+        if constexpr (RS::kConst) return row % (RS::mask_si ? RS::mask_si : 1u);
+        else return row - fast_div(row, a.mask_div) * a.mask_si;
+    }
+};
+
 // Issue the loads of every operand of a row tile before anything is used.  `row_byte` is wave-uniform,
 // so each load is a scalar base plus a 32-bit lane offset.  Vectors that are not loaded read as `fill`.
 // The KC vectors starting at k0 belong to the row at `row_byte`.
@@ -153,7 +198,7 @@ PF_DEVICE void hook_reduce(const RowHooks<RAGGED, KC, RPW, LOG2L>& h, int code, 
 // waiting for the load).
 template <int DT, int K, int KC, class Spec, bool RAGGED = false, bool WHOLE = false>
 PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, int k0, uint64_t row_byte, uint32_t row,
-                                 uint32_t load_limit, uint32_t limit, uint32_t fill) {
+                                 uint32_t load_limit, uint32_t limit, uint32_t fill, uint32_t n_inner) {
     using S = Storage<DT>;
     static_assert(!(RAGGED && WHOLE), "a ragged row has a partial vector");
 #pragma unroll
@@ -176,7 +221,7 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                     // exists) and the fill value is selected afterwards.  A guarded load would merge with the fill
                     // value at the join, which the compiler resolves by waiting for the load: every later load of
                     // the wave would then be issued one memory round trip late.
-                    const uint32_t lim = load_limit != 0u ? load_limit : a.n_inner;
+                    const uint32_t lim = load_limit != 0u ? load_limit : n_inner;
                     const uint32_t colc = min(s.col[k], lim - (uint32_t)S::VEC);
                     const u32x4 got = load_stream(base, colc * (uint32_t)S::ESIZE);
                     const bool keep = s.col[k] < load_limit;
@@ -203,11 +248,11 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                 }
                 if (RAGGED) {
                     s.vraw[v][k] = u32x4{0u, 0u, 0u, 0u};
-                    s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], a.n_inner, elems_below<S::VEC>(s.col[k], limit));
+                    s.vraw[v][k] = load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], row, s.col[k], n_inner, elems_below<S::VEC>(s.col[k], limit));
                 } else {
                     // (as above; values of lanes past the row's end are never used)
-                    const uint32_t colc = min(s.col[k], a.n_inner - (uint32_t)S::VEC);
-                    s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, colc, a.n_inner);
+                    const uint32_t colc = min(s.col[k], n_inner - (uint32_t)S::VEC);
+                    s.vraw[v][k] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], row, colc, n_inner);
                 }
             }
         }
@@ -224,8 +269,9 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
 //   LOG2L       : (WPR1 only) a row occupies an aligned segment of 2^LOG2L lanes, so a wave holds 64 >> LOG2L
 //                 rows side by side (times RPW in registers): short rows no longer leave most lanes idle.
 //                 Row addressing is then per lane instead of per wave.
-template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false, int LOG2L = 6>
+template <int DT, int KC, int RPW, class Spec, int MAXT, bool WPR1, bool RAGGED = false, int LOG2L = 6, class RS = RuntimeRowShape>
 __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowGeom g) {
+    using Sh = RowShape<RS>;
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
     constexpr int K = KC * RPW;
@@ -236,27 +282,36 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
     constexpr uint32_t LPR = 1u << LOG2L;   // lanes per row inside a wave
     constexpr uint32_t SUB = 64u >> LOG2L;  // rows side by side in a wave
     __shared__ float red[2][16];
-    warm_chain_arguments<Spec>();
+    // (a launch of many workgroups finds the arguments in the scalar cache after the first one per compute unit)
+    if constexpr (!RS::kConst) warm_chain_arguments<Spec>();
+    else if constexpr (RS::rows * RS::n_inner <= (4u << 20)) warm_chain_arguments<Spec>();
 
     const uint32_t lane = threadIdx.x & 63u;
     // the wave index is the same for all 64 lanes: keep it, and everything derived from it, in scalar registers
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t wpr = WPR1 ? 1u : g.waves_per_row;
-    const uint32_t slot_in_block = WPR1 ? wave : (g.rows_per_block == 1u ? 0u : wave / wpr);
+    const uint32_t wpr = WPR1 ? 1u : Sh::waves_per_row(g);
+    const uint32_t rows_per_block = Sh::rows_per_block(g);
+    const uint64_t n_rows = Sh::rows(a);
+    const uint32_t mask_si = Sh::mask_si(a), core_mask = Sh::core_mask(a);
+    const uint32_t slot_in_block = WPR1 ? wave : (rows_per_block == 1u ? 0u : wave / wpr);
     const uint32_t first_wave = WPR1 ? wave : slot_in_block * wpr;  // first of the waves that share this wave's row
-    const uint64_t row0 = ((uint64_t)blockIdx.x * g.rows_per_block + slot_in_block) * (RPW * SUB);
-    if (WPR1 && row0 >= a.rows) return;  // wave-uniform; this configuration has no barrier
-    const uint32_t n = a.n_inner;
+    const uint64_t row0 = ((uint64_t)blockIdx.x * rows_per_block + slot_in_block) * (RPW * SUB);
+    // wave-uniform; this configuration has no barrier (and a row count known to be a whole number of workgroups needs no test)
+    const bool all_waves_have_rows = RS::kConst && n_rows % ((uint64_t)rows_per_block * (RPW * SUB)) == 0u;
+    if (WPR1 && !all_waves_have_rows && row0 >= n_rows) return;
+    const uint32_t n = Sh::n_inner(a);
     const uint32_t sub = LOG2L == 6 ? 0u : lane >> LOG2L;  // which of the wave's side-by-side rows this lane serves
     const uint32_t lane_in_row = WPR1 ? (lane & (LPR - 1u)) : (wave - slot_in_block * wpr) * 64u + lane;
 
     LaneState<DT, K, Spec> s;
     uint32_t limit[RPW], i_row[RPW];
     uint64_t row_byte[RPW];
-    const bool fill_inf = a.core_mask == 2u;
+    const bool fill_inf = core_mask == 2u;
     const uint32_t fill = fill_inf ? (DT == DT_F32 ? 0xff800000u : (DT == DT_F16 ? 0xfc00fc00u : 0xff80ff80u)) : 0u;
     // the usual tile: rows that fill the lanes exactly, all of them inside the tensor, no causal skipping
-    const bool whole_tile = !RAGGED && n == LPR * wpr * (uint32_t)EC && a.mask_si == 0u && a.vec_plain_all != 0u && row0 + (uint64_t)(RPW * SUB) <= a.rows;
+    // (with the shape known when the kernel is compiled, a row count that is a whole number of workgroups needs no test)
+    const bool rows_whole = all_waves_have_rows || row0 + (uint64_t)(RPW * SUB) <= n_rows;
+    const bool whole_tile = !RAGGED && n == LPR * wpr * (uint32_t)EC && mask_si == 0u && Sh::vec_plain_all(a) != 0u && rows_whole;
     if (!RAGGED && whole_tile) {
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
@@ -269,19 +324,19 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                 s.col[r * KC + c] = (lane_in_row + LPR * wpr * c) * VEC;
             }
             row_byte[r] = row64 * n * S::ESIZE;
-            load_row_operands<DT, K, KC, Spec, false, !RAGGED>(a, s, r * KC, row_byte[r], (uint32_t)row64, n, n, fill);
+            load_row_operands<DT, K, KC, Spec, false, !RAGGED>(a, s, r * KC, row_byte[r], (uint32_t)row64, n, n, fill, n);
         }
     } else
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const uint64_t row64 = row0 + (uint32_t)r * SUB + sub;
         const uint32_t row = (uint32_t)row64;
-        limit[r] = row64 < a.rows ? n : 0u;
+        limit[r] = (all_waves_have_rows || row64 < n_rows) ? n : 0u;
         uint32_t load_limit = limit[r];
         i_row[r] = 0;
-        if (a.mask_si != 0u) {
+        if (mask_si != 0u) {
             // columns beyond the diagonal are overwritten by the mask before they are used: skip their loads
-            i_row[r] = row - fast_div(row, a.mask_div) * a.mask_si;
+            i_row[r] = Sh::row_in_mask(a, row);
             const uint32_t keep_vec = (i_row[r] + VEC) / VEC * VEC;
             load_limit = load_limit < keep_vec ? load_limit : keep_vec;
         }
@@ -292,8 +347,8 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
         }
         row_byte[r] = row64 * n * S::ESIZE;
         // (loads of a row past the end of the tensor are aimed at the last row and discarded)
-        const uint64_t row_in = RAGGED ? row64 : min(row64, a.rows - 1u);
-        load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_in * n * S::ESIZE, (uint32_t)row_in, load_limit, limit[r], fill);
+        const uint64_t row_in = (RAGGED || all_waves_have_rows) ? row64 : min(row64, n_rows - 1u);
+        load_row_operands<DT, K, KC, Spec, RAGGED>(a, s, r * KC, row_in * n * S::ESIZE, (uint32_t)row_in, load_limit, limit[r], fill, n);
     }
 
     // secondary outputs (U_STORE) are supported for one row per wave only; the planner enforces it
@@ -315,7 +370,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
         auto valid_elem = [&](int c, int e) { return RAGGED ? (uint32_t)e < nvalid[c] : nvalid[c] != 0u; };
         const bool all_valid = exact && limit[r] != 0u;
         if (core == CORE_SOFTMAX) {
-            if (a.core_mask == 2u) {
+            if (core_mask == 2u) {
                 // causal mask folded into the core, nothing but the load in front of it.  Vectors wholly right
                 // of the diagonal were never loaded and already hold -inf; only the vector that contains the
                 // diagonal needs element-wise masking.  Which of its elements are masked is the same for the
@@ -329,7 +384,7 @@ __global__ void __launch_bounds__(MAXT) row_kernel(const ChainArgs a, const RowG
                     for (int e = 1; e < VEC; ++e)
                         acc[c * VEC + e] = (is_diag && (uint32_t)e > last) ? -__builtin_inff() : acc[c * VEC + e];
                 }
-            } else if (a.core_mask == 1u) {
+            } else if (core_mask == 1u) {
                 // causal mask folded into the core after other prologue steps: mask every element by position
 #pragma unroll
                 for (int c = 0; c < KC; ++c) {
@@ -459,7 +514,7 @@ __global__ void __launch_bounds__(1024) row_reduce_kernel(const ChainArgs a, con
         s.col[k] = (lane_in_row + 64u * wpr * k) * VEC;
     }
     const uint64_t row_in = RAGGED ? row64 : min(row64, a.rows - 1u);  // (a row past the end: loads aimed at the last row, discarded)
-    load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_in * n * S::ESIZE, (uint32_t)row_in, limit, limit, 0u);
+    load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_in * n * S::ESIZE, (uint32_t)row_in, limit, limit, 0u, n);
     run_program<DT, K, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
     auto valid_elem = [&](int k, int e) { return RAGGED ? s.col[k] + (uint32_t)e < limit : s.col[k] < limit; };
     float r;

@@ -167,3 +167,32 @@ def test_a_plan_that_falls_back_to_the_interpreter_says_so(tmp_path):
     with env(PF_JIT="0"):
         _, info3 = gpu_run(spec, ins)
     assert info3.spec_id == 0 and info3.interpreter_fallback == 0
+
+
+def _shape_const_cases():
+    cases = []
+    cases.append(("C1 block variant, rows not a whole workgroup count", lambda: wl.c1_bias_res_layernorm_gelu(rows=37, n=768, dtype="f32")))
+    cases.append(("C1 two waves per row", lambda: wl.c1_bias_res_layernorm_gelu(rows=21, n=1024, dtype="f16")))
+    cases.append(("C2 causal, two rows per wave", lambda: wl.c2_causal_softmax(b=2, h=3, s=512, dtype="f16")))
+    cases.append(("C2 causal, rectangular scores", lambda: wl.c2_causal_softmax(b=1, h=2, s=40, dtype="f16", s_k=256)))
+    cases.append(("C2 causal bf16, odd row count", lambda: wl.c2_causal_softmax(b=1, h=3, s=24, dtype="bf16", s_k=128)))
+    cases.append(("C3 wave per row", lambda: wl.c3_bias_res_layernorm(rows=131, n=1024, dtype="f16")))
+    cases.append(("C3 rows that do not fill the lanes", lambda: wl.c3_bias_res_layernorm(rows=50, n=640, dtype="bf16")))
+    cases.append(("C3 ragged row length", lambda: wl.c3_bias_res_layernorm(rows=33, n=197, dtype="f16")))
+    cases.append(("short rows side by side", lambda: wl.c3_bias_res_layernorm(rows=300, n=128, dtype="f16")))
+    return cases
+
+
+@pytest.mark.parametrize("idx", range(9))
+def test_row_kernels_compiled_for_their_shape(idx):
+    # the shape-constant form is planned by itself for tensors of half a megabyte and more; forced here on small ones
+    what, make = _shape_const_cases()[idx]
+    spec, ins = make()
+    with env(PF_ROW_CONST="2"):
+        outs, info, _ = check_chain(spec, ins, what=what + ", shape as constants")
+    assert info.spec_id == SPEC_JIT
+    with env(PF_ROW_CONST="0"):
+        plain, _ = gpu_run(spec, ins)
+    # (not bit for bit: with constants in place of arguments the compiler contracts other multiply-adds)
+    diff = (outs[0].double() - plain[0].double()).abs().max().item()
+    assert diff <= (4e-6 if spec.outputs[0][1] == "f32" else 8e-3), f"the shape-constant kernel and the run-time one disagree by {diff}"
