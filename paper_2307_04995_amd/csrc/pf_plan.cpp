@@ -312,6 +312,7 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
     p->k = best_k;
     p->row.waves_per_row = (uint32_t)best_wpr;
     p->row.rows_per_block = best_wpr >= 4 ? 1u : (uint32_t)(4 / best_wpr);
+    if (best_wpr == 1 && env_int("PF_ROW_WAVES", 0) > 0) p->row.rows_per_block = (uint32_t)env_int("PF_ROW_WAVES", 4);
     p->row.rows_per_wave = 1;
     // Rows per wave: a wave that owns short rows takes several at once, so that it has about 4 KB of loads
     // in flight (what it takes to cover the HBM latency at full occupancy), as long as enough waves remain
@@ -324,6 +325,10 @@ pf_status plan_row(pf_plan_s* p, int forced_variant) {
         if (forced > 0) rpw = forced;
         if (rpw > 1 && have_static(best_k, rpw, true, 256)) p->row.rows_per_wave = (uint32_t)rpw;
     }
+    // Waves that own their rows and have at most 2 KB of loads in flight each (one short row, or two whose tails a causal
+    // mask cuts off) do better two to a workgroup than four: C2 15.3 -> 14.7 us, a plain softmax of 512 columns 18.3 ->
+    // 17.9 us; with 4 KB per wave (C3) four are better (17.7 against 17.9 us), eight and sixteen worse for all.
+    if (best_wpr == 1 && env_int("PF_ROW_WAVES", 0) == 0 && (int64_t)L.n_full * best_k * p->row.rows_per_wave * 1024 <= 2048) p->row.rows_per_block = 2;
     p->block = dim3(64u * best_wpr * p->row.rows_per_block);
     p->lds_bytes = best_wpr > 1 ? 2 * 16 * 4 : 0;
     // Short rows (at most 32 vectors): several rows side by side in a wave, 8 / 16 / 32 lanes each, instead of
