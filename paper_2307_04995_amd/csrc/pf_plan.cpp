@@ -669,6 +669,7 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
         }
         }
         p->k = (g.total_vecs >= 65536u && !ragged) ? 2 : 1;
+        if (!ragged && env_int("PF_PERM_K", 0) >= 1 && env_int("PF_PERM_K", 0) <= 16) p->k = env_int("PF_PERM_K", 2);
         g.tile_a = (uint32_t)inner;  // (ragged kernels: length of the innermost run)
         p->block = dim3(256);
         p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
@@ -676,19 +677,28 @@ pf_status plan_perm(pf_plan_s* p, int forced_variant) {
     }
     // Large tensors on the rows variant: the kernel is compiled for this geometry (index arithmetic on constants).  Worth
     // a compilation per shape only where the launch is long enough to notice; smaller ones keep the run-time geometry.
-    if (p->variant == PF_VARIANT_T_ROWS && !ragged && !L.general_bcast && g.total_vecs >= (1u << 20) && jit_possible(p->device) &&
-        env_int("PF_PERM_CONST", 1) != 0) {
+    if (p->variant == PF_VARIANT_T_ROWS && !ragged && !L.general_bcast && jit_possible(p->device) && env_int("PF_PERM_CONST", 1) != 0 &&
+        (g.total_vecs >= (1u << 20) || env_int("PF_PERM_CONST", 1) == 2)) {
         uint32_t numel[PF_DEV_MAX_VEC] = {1, 1, 1, 1}, period[PF_DEV_MAX_VEC] = {1, 1, 1, 1};
         for (int v = 0; v < L.n_vec; ++v) {
             numel[v] = p->args.vec[v].numel;
             period[v] = p->args.vec[v].period_rows;
         }
+        // eight vectors per lane (the built-in kernels exist for one and two): C4 12.9 us with two, 12.4 with four, 11.9
+        // with eight, 12.0 with sixteen; six or twelve, which cut across the blocks, 13.0 - 13.6
+        const int k_const = env_int("PF_PERM_K", 0) ? p->k : 8;
         std::string err;
-        hipFunction_t fn = pf::jit_perm_rows_const(p->device, L.main_dtype, p->k, make_jit_spec(L), g, numel, period, &err);
+        hipFunction_t fn = pf::jit_perm_rows_const(p->device, L.main_dtype, k_const, make_jit_spec(L), g, numel, period, &err);
         if (fn) {
             p->jit_fn = fn;
             p->spec_id = pf::kSpecJit;
+            p->k = k_const;
+            p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
             return PF_OK;
+        }
+        if (p->k > 2) {
+            p->k = 2;
+            p->grid = dim3((g.total_vecs + 256u * p->k - 1) / (256u * p->k));
         }
     }
     if (!p->spec_id && jit_possible(p->device)) {

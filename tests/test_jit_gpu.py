@@ -196,3 +196,36 @@ def test_row_kernels_compiled_for_their_shape(idx):
     # (not bit for bit: with constants in place of arguments the compiler contracts other multiply-adds)
     diff = (outs[0].double() - plain[0].double()).abs().max().item()
     assert diff <= (4e-6 if spec.outputs[0][1] == "f32" else 8e-3), f"the shape-constant kernel and the run-time one disagree by {diff}"
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape,perm", [((3, 24, 16, 64), (0, 2, 1, 3)), ((6, 5, 32), (1, 0, 2)), ((2, 3, 4, 5, 16), (3, 0, 2, 1, 4)),
+                                        ((5, 12, 6, 64), (0, 2, 1, 3)), ((40, 24, 8), (1, 0, 2))])
+def test_permutation_kernels_compiled_for_their_geometry(shape, perm, dtype):
+    # planned by itself for tensors of 16 MB and more (full-size C4); forced here on small ones: a bias in front of the
+    # permutation, a full-shape operand and a bias behind it, every index of both layouts in play
+    import numpy as np
+    out_shape = tuple(shape[i] for i in perm)
+    x = wl.random_tensor(shape, dtype, 2101)
+    b_in = wl.random_tensor(shape[-2:], dtype, 2102, scale=0.5)
+    res = wl.random_tensor(out_shape, dtype, 2103, scale=0.5)
+    b_out = wl.random_tensor((out_shape[-1],), dtype, 2104, scale=0.5)
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, tuple(shape[-2:])), (dtype, out_shape), (dtype, (out_shape[-1],))])
+    v = s.op("scale", s.op("add", 0, 1), f=[0.125])
+    v = s.op("permute", v, i=list(perm))
+    v = s.op("add", s.op("add", v, 2), 3)
+    s.out(v, dtype)
+    with env(PF_PERM_CONST="2"):
+        outs, info, _ = check_chain(s, [x, b_in, res, b_out], what=f"permutation {perm} of {shape} {dtype}, geometry as constants")
+    assert info.spec_id == SPEC_JIT and info.vectors_per_lane == 8
+    with env(PF_PERM_CONST="0"):
+        plain, info0 = gpu_run(s, [x, b_in, res, b_out])
+    assert info0.vectors_per_lane <= 2
+    import torch
+    assert torch.equal(outs[0], plain[0])
+    # layout only: the raw bits travel
+    lay = wl.ChainSpec(inputs=[(dtype, shape)])
+    lay.out(lay.op("permute", 0, i=list(perm)), dtype)
+    with env(PF_PERM_CONST="2"):
+        (moved,), _ = gpu_run(lay, [x])
+    assert torch.equal(moved, x.permute(*perm).contiguous())
