@@ -252,10 +252,36 @@ PF_DEVICE bool merge_parts_of_block(const GroupGeom& g, const float* lds_gen, ui
 //
 // GEN != 0: groups of any width (see merge_parts_of_block; 2 and 3 are described at their use); needs 512 * parts * 12 bytes of dynamic LDS, `parts`
 // being the most groups one vector touches.
-template <int DT, int NV, class Spec, int PHASE, int GEN = 0>
-__global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g, const uint32_t tiles) {
+// GC: RuntimeGroupGeom ("read the geometry argument"), or a type generated when the plan is made that holds the
+// launch's geometry as constants: every tile is then known to be whole and every lane in use, so the loads and stores
+// of a tile carry no test, and the index arithmetic folds.
+struct RuntimeGroupGeom {
+    static constexpr bool kConst = false;
+};
+template <int DT, int NV, class Spec, int PHASE, int GEN = 0, class GC = RuntimeGroupGeom>
+__global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const GroupGeom g_arg, const uint32_t tiles_arg) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
+    GroupGeom g = g_arg;
+    uint32_t tiles = tiles_arg;
+    bool whole_tiles = false, all_active = false, one_tile = false;
+    if constexpr (GC::kConst) {
+        g.samples = GC::samples;
+        g.hw = GC::hw;
+        g.channels = GC::channels;
+        g.groups = GC::groups;
+        g.cv = GC::cv;
+        g.vpg = GC::vpg;
+        g.log2_vpg = GC::log2_vpg;
+        g.pos_per_step = GC::pos_per_step;
+        g.pos_per_block = GC::pos_per_block;
+        g.lanes_per_group = GC::lanes_per_group;
+        g.blocks_per_sample = GC::blocks_per_sample;
+        tiles = GC::tiles;
+        whole_tiles = GC::hw % GC::pos_per_block == 0u;
+        all_active = GC::cv * GC::pos_per_step == 512u;
+        one_tile = GC::grid == GC::tiles;
+    }
     // kLean: 16-bit storage and nothing but the load in front of the normalisation
     constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32 && !GEN;
     // GEN == 2: the same for the general kernels, planned when a group holds an even number of channels
@@ -264,9 +290,11 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     __shared__ float lds_stat[512 * 2];
     extern __shared__ float lds_gen[];  // GEN: [lane][part] (count, mean, M2)
     const uint32_t t = threadIdx.x;
-    const uint32_t pstep = fast_div(t, g.div_cv);
+    uint32_t pstep;
+    if constexpr (GC::kConst) pstep = t / GC::cv;
+    else pstep = fast_div(t, g.div_cv);
     const uint32_t cvi = t - pstep * g.cv;
-    const bool active = pstep < g.pos_per_step;
+    const bool active = all_active || pstep < g.pos_per_step;
     // GEN: the part (group, relative to the lane's first group) each element of the lane's vector belongs to,
     // four bits per element
     uint32_t part_code = 0, first_grp = 0;
@@ -291,8 +319,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
 
     LaneState<DT, 1, Spec> s;
     s.col[0] = cvi * VEC;
-    if (vec_per_channel) {
-        // broadcast operands that are per channel: the same vector for every position and tile
+    // broadcast operands that are per channel: the same vector for every position and tile.  The one-launch kernel
+    // asks for them behind its tile's loads (they come back in order, so in front of them they would hold up the first
+    // byte of the tile by a trip to memory; they are first needed when the tile is complete anyway).
+    auto load_channel_operands = [&]() {
 #pragma unroll
         for (int v = 0; v < Spec::NV; ++v) {
             if (v < Spec::n_vec(a)) {
@@ -302,9 +332,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                                           : load_vec_operand<DT, Spec::kVecMode>(a.vec[v], 0u, s.col[0], g.channels);
             }
         }
-    }
+    };
+    if (vec_per_channel && PHASE != 0) load_channel_operands();
 
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += (one_tile ? tiles : gridDim.x)) {
         const uint32_t sample = tile / g.blocks_per_sample;
         const uint32_t bx = tile - sample * g.blocks_per_sample;
         const uint32_t p_begin = bx * g.pos_per_block;
@@ -314,9 +345,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         // kept: the registers are for data)
         u32x4 raw[NV];
         const uint32_t rot = tile % NV;
-        const uint32_t p_count = p_end - p_begin;
+        const uint32_t p_count = whole_tiles ? g.pos_per_block : p_end - p_begin;
         auto rel_of = [&](int i) { return pstep + (((uint32_t)i + rot) % NV) * g.pos_per_step; };
-        auto valid_of = [&](int i) { return active && rel_of(i) < p_count; };
+        auto valid_of = [&](int i) { return (whole_tiles && all_active) || (active && rel_of(i) < p_count); };
         const char* in_base = static_cast<const char*>(a.full[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
@@ -329,6 +360,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 else raw[i] = load_stream(in_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
             }
         }
+
+        if (PHASE == 0) load_channel_operands();
 
         // Run the prologue on slice i (lean chains have none).
         auto prologue = [&](int i) {

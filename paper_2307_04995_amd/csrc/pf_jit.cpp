@@ -238,6 +238,24 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int gen
     return compile(device, "#include \"pf_group_kernels.hpp\"\n", name.str(), err);
 }
 
+// The one-launch group kernel with the geometry of one launch as constants.
+hipFunction_t jit_group_kernel_const(int device, int dtype, int nv, int general_parts, const JitSpec& spec, const GroupGeom& g, uint32_t tiles,
+                                     uint32_t grid, std::string* err) {
+    std::ostringstream body;
+    body << "    static constexpr bool kConst = true;\n    static constexpr unsigned samples = " << g.samples << "u, hw = " << g.hw << "u, channels = "
+         << g.channels << "u, groups = " << g.groups << "u, cv = " << g.cv << "u, vpg = " << g.vpg << "u, log2_vpg = " << g.log2_vpg
+         << "u, pos_per_step = " << g.pos_per_step << "u, pos_per_block = " << g.pos_per_block << "u, lanes_per_group = " << g.lanes_per_group
+         << "u, blocks_per_sample = " << g.blocks_per_sample << "u, tiles = " << tiles << "u, grid = " << grid << "u;\n";
+    const std::string text = body.str();
+    uint64_t h = 1469598103934665603ull;  // FNV-1a
+    for (unsigned char c : text) h = (h ^ c) * 1099511628211ull;
+    std::ostringstream type, source, name;
+    type << "PfGroupGeom_" << std::hex << h;
+    source << "#include \"pf_group_kernels.hpp\"\nstruct " << type.str() << " {\n" << text << "};\n";
+    name << "pf::group_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", 0, " << general_parts << ", " << type.str() << ">";
+    return compile(device, source.str(), name.str(), err);
+}
+
 hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
     const char* rg = ragged ? ", true>" : ", false>";

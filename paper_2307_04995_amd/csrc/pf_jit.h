@@ -49,6 +49,9 @@ hipFunction_t jit_perm_rows_const(int device, int dtype, int k, const JitSpec& s
 // group family: phase 0 fused, 1 statistics, 2 normalisation
 hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int general_parts, const JitSpec& spec, std::string* err);
 // stencil family (depthwise 3 x 3 convolution)
+// the one-launch variant (phase 0) with the launch's geometry as compile-time constants
+hipFunction_t jit_group_kernel_const(int device, int dtype, int nv, int general_parts, const JitSpec& spec, const GroupGeom& g, uint32_t tiles,
+                                     uint32_t grid, std::string* err);
 hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err);
 // workgroups of `block_threads` threads one compute unit holds at once
 hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err);
