@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         g.blocks_per_sample = GC::blocks_per_sample;
         tiles = GC::tiles;
         whole_tiles = GC::hw % GC::pos_per_block == 0u;
-        all_active = GC::cv * GC::pos_per_step == 512u;
+        all_active = GC::cv * GC::pos_per_step == GC::threads;
         one_tile = GC::grid == GC::tiles;
     }
     // kLean: 16-bit storage and nothing but the load in front of the normalisation

@@ -240,12 +240,12 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int gen
 
 // The one-launch group kernel with the geometry of one launch as constants.
 hipFunction_t jit_group_kernel_const(int device, int dtype, int nv, int general_parts, const JitSpec& spec, const GroupGeom& g, uint32_t tiles,
-                                     uint32_t grid, std::string* err) {
+                                     uint32_t grid, uint32_t threads, std::string* err) {
     std::ostringstream body;
     body << "    static constexpr bool kConst = true;\n    static constexpr unsigned samples = " << g.samples << "u, hw = " << g.hw << "u, channels = "
          << g.channels << "u, groups = " << g.groups << "u, cv = " << g.cv << "u, vpg = " << g.vpg << "u, log2_vpg = " << g.log2_vpg
          << "u, pos_per_step = " << g.pos_per_step << "u, pos_per_block = " << g.pos_per_block << "u, lanes_per_group = " << g.lanes_per_group
-         << "u, blocks_per_sample = " << g.blocks_per_sample << "u, tiles = " << tiles << "u, grid = " << grid << "u;\n";
+         << "u, blocks_per_sample = " << g.blocks_per_sample << "u, tiles = " << tiles << "u, grid = " << grid << "u, threads = " << threads << "u;\n";
     const std::string text = body.str();
     uint64_t h = 1469598103934665603ull;  // FNV-1a
     for (unsigned char c : text) h = (h ^ c) * 1099511628211ull;

@@ -51,7 +51,7 @@ hipFunction_t jit_group_kernel(int device, int dtype, int nv, int phase, int gen
 // stencil family (depthwise 3 x 3 convolution)
 // the one-launch variant (phase 0) with the launch's geometry as compile-time constants
 hipFunction_t jit_group_kernel_const(int device, int dtype, int nv, int general_parts, const JitSpec& spec, const GroupGeom& g, uint32_t tiles,
-                                     uint32_t grid, std::string* err);
+                                     uint32_t grid, uint32_t threads, std::string* err);
 hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err);
 // workgroups of `block_threads` threads one compute unit holds at once
 hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err);
