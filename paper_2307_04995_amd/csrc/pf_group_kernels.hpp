@@ -348,6 +348,12 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         const uint32_t p_count = whole_tiles ? g.pos_per_block : p_end - p_begin;
         auto rel_of = [&](int i) { return pstep + (((uint32_t)i + rot) % NV) * g.pos_per_step; };
         auto valid_of = [&](int i) { return (whole_tiles && all_active) || (active && rel_of(i) < p_count); };
+        // A vector's address = the tile's base + the step's share (the same for the whole workgroup: scalar registers)
+        // + the lane's share (the same for every step: one vector register).  Written so on purpose: one offset register
+        // per step, sixteen of them live from the loads to the stores, is what made the kernel spill.
+        const uint32_t step_bytes = g.pos_per_step * g.channels * (uint32_t)S::ESIZE;
+        const uint32_t lane_bytes = (pstep * g.channels + cvi * VEC) * (uint32_t)S::ESIZE;
+        auto step_of = [&](int i) { return ((uint32_t)i + rot) % NV; };
         const char* in_base = static_cast<const char*>(a.full[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
@@ -356,8 +362,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
                 if (ragged) raw[i] = load_elems<DT>(in_base, rel_of(i) * g.channels + cvi * VEC, cnt, 0u);
                 // (the statistics launch leaves x in the caches for the launch that re-reads it: C5 in two launches
                 // 39.2 -> 35.2 us; a one-launch tile is touched once and streams past them)
-                else if (PHASE == 1) raw[i] = load_cached(in_base, (uint64_t)(rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
-                else raw[i] = load_stream(in_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE);
+                else if (PHASE == 1) raw[i] = load_cached(in_base + (size_t)step_of(i) * step_bytes, (uint64_t)lane_bytes);
+                else raw[i] = load_stream(in_base + (size_t)step_of(i) * step_bytes, lane_bytes);
             }
         }
 
@@ -603,7 +609,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
             if (valid_of(i)) {
                 if (ragged) store_elems<DT>(out_base, rel_of(i) * g.channels + cvi * VEC, cnt, S::pack(s.acc));
-                else store_stream(out_base, (rel_of(i) * g.channels + cvi * VEC) * (uint32_t)S::ESIZE, S::pack(s.acc));
+                else store_stream(out_base + (size_t)step_of(i) * step_bytes, lane_bytes, S::pack(s.acc));
             }
         }
         __syncthreads();  // LDS staging is reused by the next tile
