@@ -860,9 +860,9 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
             p->jit_fn = fused_fn;
             p->spec_id = pf::kSpecJit;
         }
-        // tensors of 16 MB and more: the kernel compiled for this geometry (see the kernel's header)
+        // tensors of 4 MB and more: the kernel compiled for this geometry (see the kernel's header)
         const int const_mode = env_int("PF_GROUP_CONST", 1);
-        if (!general && jit_possible(p->device) && const_mode != 0 && (const_mode == 2 || samples * hw * C * es >= (16 << 20))) {
+        if (!general && jit_possible(p->device) && const_mode != 0 && (const_mode == 2 || samples * hw * C * es >= (4 << 20))) {
             std::string err;
             hipFunction_t fn = pf::jit_group_kernel_const(p->device, L.main_dtype, nv, gen_parts, jspec, g, (uint32_t)tiles, res_grid, threads, &err);
             if (fn && pf::jit_blocks_per_cu(fn, (int)threads, gen_lds) * n_cu >= (int)res_grid) {
