@@ -182,11 +182,11 @@ struct PoolGeom {
     uint32_t chunks;             // chunks (of NV position steps) a workgroup walks
     uint32_t epi_full_mask, epi_vec_mask;  // operands that belong to the epilogue (read in the result's layout)
     float inv_hw;                // 1 / positions (mean)
-    float* ws_partial;           // [samples][blocks_per_sample][channels] partial results (more than one block per sample)
-    uint32_t* ws_flags;          // [samples][blocks_per_sample] 1 = the slice's partial result is published (lowered by the merger)
+    uint32_t* ws_partial;        // [samples][blocks_per_sample][channels] partial results as words, all-ones = not published
+                                 // (more than one block per sample; the merger puts them back to all-ones)
     uint32_t* ws_error;          // set to 1 if a wait ran out
-    uint32_t spin_limit;         // polling rounds before a wait gives up
-    uint32_t pad;
+    uint32_t spin_limit;         // re-reads before a wait gives up
+    uint32_t merge_rows;         // row groups of threads the merger splits the slices over (512 / channels, at least 1)
     FastDiv div_cv;
 };
 

@@ -336,15 +336,16 @@ pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
         return fail(PF_ERR_HIP, "cannot read the error word");
     if (word != 0u) {
         // A wait gave up: the launch's outputs are invalid, and the exchange words may be in a state the next launch
-        // does not expect (slots of the wrong parity still filled, flags of late slices still raised).  Put the
+        // does not expect (slots of the wrong parity still filled, partial results of late slices still published).  Put the
         // workspace back the way the planner left it.  (The caller has synchronised: nothing of this plan is running.)
         bool ok = hipMemset(err, 0, sizeof(word)) == hipSuccess;
         if (plan->family == PF_FAMILY_GROUP && plan->group.ws_gather) {
             const pf::GroupGeom& g = plan->group;
             ok = ok && hipMemset(g.ws_gather, 0xff, (size_t)2 * g.samples * g.groups * g.blocks_per_sample * sizeof(uint64_t)) == hipSuccess;
         }
-        if (plan->family == PF_FAMILY_POOL && plan->pool.ws_flags)
-            ok = ok && hipMemset(plan->pool.ws_flags, 0, (size_t)plan->pool.samples * plan->pool.blocks_per_sample * sizeof(uint32_t)) == hipSuccess;
+        if (plan->family == PF_FAMILY_POOL && plan->pool.ws_partial)
+            ok = ok && hipMemset(plan->pool.ws_partial, 0xff,
+                                 (size_t)plan->pool.samples * plan->pool.blocks_per_sample * plan->pool.channels * sizeof(uint32_t)) == hipSuccess;
         if (!ok) return fail(PF_ERR_HIP, "cannot re-arm the workspace");
     }
     *flag = (int32_t)word;

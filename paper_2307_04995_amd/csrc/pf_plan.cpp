@@ -1244,18 +1244,18 @@ pf_status plan_pool(pf_plan_s* p) {
     p->args.rows = (uint64_t)(n * hw);
     if (g.blocks_per_sample > 1) {
         const uint64_t part_bytes = ((uint64_t)blocks * ch * sizeof(float) + 255) / 256 * 256;
-        const uint64_t flag_bytes = ((uint64_t)blocks * sizeof(uint32_t) + 255) / 256 * 256;
         if (planning_static())
             return fail(PF_ERR_UNSUPPORTED, "a pooling split over several workgroups per sample waits on the device, and a wait that gives up is reported "
                                             "through the plan: use pf_chain_plan + pf_chain_run");
         if (hipSetDevice(p->device) != hipSuccess) return fail(PF_ERR_HIP, "cannot select device %d", p->device);
-        pf_status ws_st = plan_workspace_alloc(p, part_bytes + flag_bytes + 256, "workspace allocation");
+        pf_status ws_st = plan_workspace_alloc(p, part_bytes + 256, "workspace allocation");
         if (ws_st != PF_OK) return ws_st;
-        if ((ws_st = plan_workspace_fill(p, p->workspace, 0, p->workspace_bytes, true)) != PF_OK) return ws_st;
-        g.ws_partial = reinterpret_cast<float*>(p->workspace);
-        g.ws_flags = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
-        g.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes + flag_bytes);
-        g.spin_limit = (uint32_t)env_int("PF_POOL_SPIN_LIMIT", 1 << 18);  // polling rounds before a wait gives up (tests force it small)
+        if ((ws_st = plan_workspace_fill(p, p->workspace, 0xff, part_bytes, true)) != PF_OK) return ws_st;
+        if ((ws_st = plan_workspace_fill(p, static_cast<char*>(p->workspace) + part_bytes, 0, 256, true)) != PF_OK) return ws_st;
+        g.ws_partial = reinterpret_cast<uint32_t*>(p->workspace);
+        g.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
+        g.spin_limit = (uint32_t)env_int("PF_POOL_SPIN_LIMIT", 1 << 18);  // re-reads before a wait gives up (tests force it small)
+        g.merge_rows = (uint32_t)std::max<int64_t>(1, 512 / ch);
         p->ws_error = g.ws_error;
     }
     if (jit_possible(p->device)) {

@@ -6,8 +6,8 @@
 // workgroup walks whole positions, so its HBM accesses are fully contiguous, and every lane owns one channel
 // vector, so the running reduction lives in registers and no value crosses lanes until the workgroup's slice
 // is done (one pass through LDS).  A sample's positions are spread over several workgroups: each publishes its
-// per-channel partial result and raises a flag; the sample's last workgroup waits for the flags, merges the
-// partial results, runs the epilogue and stores -- the device-scope synchronisation of section 5.1.
+// per-channel partial result; the sample's last workgroup waits for those words, merges them, runs the epilogue
+// and stores -- the device-scope synchronisation of section 5.1.
 #pragma once
 #include "pf_row_kernels.hpp"
 
@@ -23,6 +23,14 @@ template <int OP>
 PF_DEVICE float pool_combine(float acc, float x) {
     if (OP != POOL_MAX) return acc + x;
     return (x != x) ? x : ((acc != acc) ? acc : fmaxf(acc, x));
+}
+
+// A partial result as a published word: all-ones means "not written in this launch" (a NaN that arithmetic never
+// produces; a NaN result with that payload is published as the canonical one).
+constexpr uint32_t kPoolEmpty = ~0u;
+PF_DEVICE uint32_t pool_word(float x) {
+    const uint32_t w = __builtin_bit_cast(uint32_t, x);
+    return w == kPoolEmpty ? 0x7fc00000u : w;
 }
 
 template <int DT, int NV, class Spec, int OP>
@@ -100,63 +108,89 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
     }
 
     if (g.blocks_per_sample > 1u) {
-        // ---- publish the slice's partial result, then raise the slice's flag.  The sample's LAST slice (dispatched
-        // after the others) waits for all flags, merges, and lowers the flags again for the next launch.
-        // (the slice's result goes through LDS once more so that consecutive lanes store consecutive words: a wave
-        // then writes 256 contiguous bytes instead of 64 separate words)
+        // ---- a sample split over several workgroups.  Every slice but the last publishes its per-channel partial
+        // result as self-describing words (kPoolEmpty = not written in this launch); the sample's LAST slice
+        // (dispatched after the others) reads them all, re-reading the ones still empty, puts them back to empty for
+        // the next launch and merges.  The critical path is one coherent store followed by one coherent load: no
+        // flag, no wait for the stores' acknowledgement in between.
+        // (the slice's result goes through LDS so that consecutive lanes store consecutive words: a wave then writes
+        // 256 contiguous bytes instead of 64 separate words)
         __syncthreads();
         if (owner) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) lds[t * VEC + e] = acc[e];
         }
         __syncthreads();
-        float* part = g.ws_partial + (uint64_t)(sample * g.blocks_per_sample + bx) * g.channels;
-        for (uint32_t idx = t; idx < g.channels; idx += 512u) __hip_atomic_store(part + idx, lds[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The flag below must not become visible before these words.  They are device-coherent write-through stores,
-        // so nothing has to be written back; what is needed is that every wave's stores have been acknowledged before
-        // the barrier lets lane 0 raise the flag.  A workgroup-scope release does not wait for outstanding stores on
-        // this device (a workgroup never leaves its compute unit), and an agent-scope one would write back the whole
-        // L2: the wait is spelled out instead.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        uint32_t* flags = g.ws_flags + (uint64_t)sample * g.blocks_per_sample;
-        if (t == 0) __hip_atomic_store(flags + bx, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (bx + 1u != g.blocks_per_sample) return;
-        // every wait is bounded: after spin_limit rounds the error word is set and the merge goes ahead
-        for (uint32_t spins = 0;; ++spins) {
-            int pending = 0;
-            for (uint32_t b = t; b < g.blocks_per_sample; b += 512u)
-                pending |= __hip_atomic_load(flags + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u ? 1 : 0;
-            if (!__syncthreads_or(pending)) break;
-            if (spins >= g.spin_limit) {
-                if (t == 0) __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(8);
+        if (bx + 1u != g.blocks_per_sample) {
+            uint32_t* part = g.ws_partial + (uint64_t)(sample * g.blocks_per_sample + bx) * g.channels;
+            for (uint32_t idx = t; idx < g.channels; idx += 512u)
+                __hip_atomic_store(part + idx, pool_word(lds[idx]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
         }
-        for (uint32_t b = t; b < g.blocks_per_sample; b += 512u) __hip_atomic_store(flags + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // one channel per lane (consecutive lanes, consecutive words), four slices in flight at a time
-        const float* base = g.ws_partial + (uint64_t)sample * g.blocks_per_sample * g.channels;
-        __syncthreads();
-        for (uint32_t idx = t; idx < g.channels; idx += 512u) {
+        // The merger: merge_rows row groups of threads, each a channel per lane (consecutive lanes, consecutive words);
+        // row group r takes the slices r, r + merge_rows, ..., eight of them in flight at a time.  Every wait is
+        // bounded: after spin_limit re-reads the error word is set and the missing slice is left out.
+        const uint32_t others = g.blocks_per_sample - 1u;
+        const uint32_t r = t / g.channels;  // 0 for every thread when a position has 512 channels or more
+        uint32_t* base = g.ws_partial + (uint64_t)sample * g.blocks_per_sample * g.channels;
+        uint32_t spins = 0;
+        float merged[VEC];  // (channels > 512: a thread owns channels t, t + 512, ...: at most VEC of them)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uint32_t idx = t - r * g.channels + (uint32_t)k * 512u;
             float m = pool_identity<OP>();
-            for (uint32_t b0 = 0; b0 < g.blocks_per_sample; b0 += 4u) {
-                float part4[4];
+            if (r < g.merge_rows && idx < g.channels && (k == 0 || g.channels > 512u)) {
+                if (r == 0u) m = lds[idx];  // the merger's own slice
+                for (uint32_t b0 = r; b0 < others; b0 += 8u * g.merge_rows) {
+                    uint32_t w[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t b = b0 + (uint32_t)u;
-                    part4[u] = b < g.blocks_per_sample ? __hip_atomic_load(base + (uint64_t)b * g.channels + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                                       : pool_identity<OP>();
+                    for (int u = 0; u < 8; ++u) {
+                        const uint32_t b = b0 + (uint32_t)u * g.merge_rows;
+                        w[u] = b < others ? __hip_atomic_load(base + (uint64_t)b * g.channels + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                          : pool_word(pool_identity<OP>());
+                    }
+                    // words still empty are re-read together (one trip to memory per round, not one per word)
+                    for (;;) {
+                        bool waiting = false;
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) waiting = waiting || w[u] == kPoolEmpty;
+                        if (!waiting) break;
+                        if (++spins > g.spin_limit) {
+                            __hip_atomic_store(g.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(8);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const uint32_t b = b0 + (uint32_t)u * g.merge_rows;
+                            if (w[u] == kPoolEmpty) w[u] = __hip_atomic_load(base + (uint64_t)b * g.channels + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const uint32_t b = b0 + (uint32_t)u * g.merge_rows;
+                        if (b >= others || w[u] == kPoolEmpty) continue;
+                        __hip_atomic_store(base + (uint64_t)b * g.channels + idx, kPoolEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        m = pool_combine<OP>(m, __builtin_bit_cast(float, w[u]));
+                    }
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) m = pool_combine<OP>(m, part4[u]);
             }
-            lds[idx] = m;
+            merged[k] = m;
+        }
+        __syncthreads();  // (everyone has read its own slice's values)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const uint32_t idx = t - r * g.channels + (uint32_t)k * 512u;
+            if (r < g.merge_rows && idx < g.channels && (k == 0 || g.channels > 512u)) lds[r * g.channels + idx] = merged[k];
         }
         __syncthreads();
         if (owner) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = lds[t * VEC + e];
+            for (int e = 0; e < VEC; ++e) {
+                float m = lds[t * VEC + e];
+                for (uint32_t q = 1; q < g.merge_rows; ++q) m = pool_combine<OP>(m, lds[q * g.channels + t * VEC + e]);
+                acc[e] = m;
+            }
         }
     }
     if (!owner) return;
