@@ -34,8 +34,8 @@ typedef enum {
     PF_ERR_SHAPE = 2,       /* shapes do not fit the operator (broadcast, parameter length, permutation)   */
     PF_ERR_DTYPE = 3,       /* unknown dtype, or a dtype mix the kernels do not implement                  */
     PF_ERR_UNSUPPORTED = 4, /* valid chain that fits no kernel family; there is no unfused fallback        */
-    PF_ERR_ALIGNMENT = 5,   /* pointer not 16-byte aligned, or a channel count that is not a multiple of 16 bytes
-                               in the group and stencil families                                          */
+    PF_ERR_ALIGNMENT = 5,   /* pointer not 16-byte aligned, or an extent that the family needs as a whole number
+                               of 16-byte vectors (attention head dimension, tiled transposes)            */
     PF_ERR_ALIAS = 6,       /* an output overlaps an input in a family that cannot run in place            */
     PF_ERR_NOMEM = 7,       /* host or device allocation failed                                            */
     PF_ERR_HIP = 8,         /* a HIP runtime call failed; pf_last_error holds hipGetErrorString            */

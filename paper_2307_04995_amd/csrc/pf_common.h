@@ -187,6 +187,7 @@ struct PoolGeom {
     uint32_t* ws_error;          // set to 1 if a wait ran out
     uint32_t spin_limit;         // re-reads before a wait gives up
     uint32_t merge_rows;         // row groups of threads the merger splits the slices over (512 / channels, at least 1)
+    uint32_t ragged;             // the channel count is not a whole number of vectors (cv rounds up; RAGGED kernels)
     FastDiv div_cv;
 };
 

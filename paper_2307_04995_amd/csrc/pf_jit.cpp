@@ -265,9 +265,9 @@ hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, boo
     return compile(device, "#include \"pf_stencil_kernels.hpp\"\n", name.str(), err);
 }
 
-hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err) {
+hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, bool ragged, const JitSpec& spec, std::string* err) {
     std::ostringstream name;
-    name << "pf::pool_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << op << ">";
+    name << "pf::pool_kernel<" << dtype << ", " << nv << ", " << spec_text(spec) << ", " << op << (ragged ? ", true>" : ", false>");
     return compile(device, "#include \"pf_pool_kernels.hpp\"\n", name.str(), err);
 }
 

@@ -54,7 +54,7 @@ hipFunction_t jit_group_kernel_const(int device, int dtype, int nv, int general_
                                      uint32_t grid, uint32_t threads, std::string* err);
 hipFunction_t jit_stencil_kernel(int device, int dtype, int variant, int ks, bool ragged, const JitSpec& spec, std::string* err);
 // workgroups of `block_threads` threads one compute unit holds at once
-hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, const JitSpec& spec, std::string* err);
+hipFunction_t jit_pool_kernel(int device, int dtype, int nv, int op, bool ragged, const JitSpec& spec, std::string* err);
 int jit_blocks_per_cu(hipFunction_t fn, int block_threads, uint32_t lds_bytes = 0);
 // bytes of per-lane scratch memory the compiled kernel uses (register spills); 0 when it keeps everything in registers
 int jit_scratch_bytes(hipFunction_t fn);

@@ -1188,9 +1188,10 @@ pf_status plan_pool(pf_plan_s* p) {
     const Shape& xs = L.pre_shape;  // [n, spatial.., c]
     const int64_t n = xs[0], ch = xs.back();
     const int64_t hw = numel(xs) / (n * ch);
-    if ((ch * es) % 16 != 0) return fail(PF_ERR_ALIGNMENT, "channel count %lld is not a multiple of 16 bytes", (long long)ch);
-    if (p->ragged) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the pool family is not a multiple of 16 bytes");
-    const int64_t cv = ch / vec;
+    // a channel count that is not a whole number of vectors: element-aligned positions, a partial last vector
+    const bool ragged_c = (ch * es) % 16 != 0;
+    if (p->ragged && !ragged_c) return fail(PF_ERR_ALIGNMENT, "a broadcast input of the pool family is not a multiple of 16 bytes");
+    const int64_t cv = (ch + vec - 1) / vec;
     if (cv > 512) return fail(PF_ERR_UNSUPPORTED, "more than %d channels", 512 * vec);
     if (n * hw > 0xffffffffLL || n > 0x7fffffLL) return fail(PF_ERR_UNSUPPORTED, "tensor too large for the pool family");
     if (L.n_out != 1) return fail(PF_ERR_UNSUPPORTED, "secondary outputs are not implemented in the pool family");
@@ -1207,6 +1208,7 @@ pf_status plan_pool(pf_plan_s* p) {
     g.hw = (uint32_t)hw;
     g.channels = (uint32_t)ch;
     g.cv = (uint32_t)cv;
+    g.ragged = ragged_c ? 1u : 0u;
     g.div_cv = make_fastdiv(g.cv);
     g.pos_per_step = 512u / g.cv;
     g.inv_hw = 1.0f / (float)hw;
@@ -1260,7 +1262,7 @@ pf_status plan_pool(pf_plan_s* p) {
     }
     if (jit_possible(p->device)) {
         std::string err;
-        p->jit_fn = pf::jit_pool_kernel(p->device, L.main_dtype, nv, L.pool_op, make_jit_spec(L), &err);
+        p->jit_fn = pf::jit_pool_kernel(p->device, L.main_dtype, nv, L.pool_op, ragged_c, make_jit_spec(L), &err);
         if (p->jit_fn) p->spec_id = pf::kSpecJit;
         else note_interpreter_fallback(p, err);
     }

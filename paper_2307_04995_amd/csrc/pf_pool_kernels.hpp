@@ -33,7 +33,10 @@ PF_DEVICE uint32_t pool_word(float x) {
     return w == kPoolEmpty ? 0x7fc00000u : w;
 }
 
-template <int DT, int NV, class Spec, int OP>
+// RAGGED: a channel count that is not a whole number of 16-byte vectors.  A position then starts at element alignment
+// and its last vector holds `cnt` channels: elements past them are never read or stored (their accumulator slots carry
+// whatever the prologue makes of the fill value and stay in the lane).
+template <int DT, int NV, class Spec, int OP, bool RAGGED = false>
 __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const PoolGeom g) {
     using S = Storage<DT>;
     constexpr int VEC = S::VEC;
@@ -53,6 +56,10 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
 
     LaneState<DT, 1, Spec> s;
     s.col[0] = cvi * VEC;
+    const uint32_t cnt = RAGGED ? elems_below<VEC>(cvi * (uint32_t)VEC, g.channels) : (uint32_t)VEC;
+    auto load_full = [&](const void* base, uint64_t elem) {
+        return RAGGED ? load_elems<DT>(base, elem, cnt, 0u) : load_stream(base, elem * S::ESIZE);
+    };
 
     // ---- the slice in chunks of NV position steps: the primary operand of a chunk first (all its loads in flight),
     // then position by position
@@ -69,7 +76,7 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid_of(i)) raw[i] = load_stream(a.full[0], ((pos0 + rel_of(i)) * g.channels + cvi * VEC) * S::ESIZE);
+            if (valid_of(i)) raw[i] = load_full(a.full[0], (pos0 + rel_of(i)) * g.channels + cvi * VEC);
         }
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
@@ -80,13 +87,15 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
             for (int f = 1; f < Spec::NF; ++f)
                 if (f < Spec::n_full(a) && ((pro_full >> f) & 1u)) {
                     s.fraw[f][0] = u32x4{0u, 0u, 0u, 0u};
-                    if (valid_of(i)) s.fraw[f][0] = load_stream(a.full[f], ((uint64_t)pos * g.channels + cvi * VEC) * S::ESIZE);
+                    if (valid_of(i)) s.fraw[f][0] = load_full(a.full[f], (uint64_t)pos * g.channels + cvi * VEC);
                 }
 #pragma unroll
             for (int v = 0; v < Spec::NV; ++v)
                 if (v < Spec::n_vec(a) && ((pro_vec >> v) & 1u)) {
                     s.vraw[v][0] = u32x4{0u, 0u, 0u, 0u};
-                    if (valid_of(i)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.channels);
+                    if (valid_of(i))
+                        s.vraw[v][0] = RAGGED ? load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.channels, cnt)
+                                              : load_vec_operand<DT, Spec::kVecMode>(a.vec[v], pos, s.col[0], g.channels);
                 }
             run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
             if (valid_of(i)) {
@@ -202,17 +211,21 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
     }
     s.row[0] = sample;
     s.col[0] = t * VEC;
-    const uint64_t out_off = ((uint64_t)sample * g.channels + t * VEC) * S::ESIZE;
+    const uint64_t out_elem = (uint64_t)sample * g.channels + t * VEC;
+    const uint64_t out_off = out_elem * S::ESIZE;
 #pragma unroll
     for (int f = 0; f < Spec::NF; ++f)
-        if (f < Spec::n_full(a) && ((epi_full >> f) & 1u)) s.fraw[f][0] = load_cached(a.full[f], out_off);
+        if (f < Spec::n_full(a) && ((epi_full >> f) & 1u)) s.fraw[f][0] = RAGGED ? load_elems<DT>(a.full[f], out_elem, cnt, 0u) : load_cached(a.full[f], out_off);
 #pragma unroll
     for (int v = 0; v < Spec::NV; ++v)
-        if (v < Spec::n_vec(a) && ((epi_vec >> v) & 1u)) s.vraw[v][0] = load_vec_operand<DT, Spec::kVecMode>(a.vec[v], sample, s.col[0], g.channels);
+        if (v < Spec::n_vec(a) && ((epi_vec >> v) & 1u))
+            s.vraw[v][0] = RAGGED ? load_vec_operand_elems<DT, Spec::kVecMode>(a.vec[v], sample, s.col[0], g.channels, cnt)
+                                  : load_vec_operand<DT, Spec::kVecMode>(a.vec[v], sample, s.col[0], g.channels);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s.acc[e] = acc[e];
     run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
-    store_stream(a.out[0], out_off, S::pack(s.acc));
+    if (RAGGED) store_elems<DT>(a.out[0], out_elem, cnt, S::pack(s.acc));
+    else store_stream(a.out[0], out_off, S::pack(s.acc));
 }
 
 }  // namespace pf

@@ -72,7 +72,7 @@ __global__ void __launch_bounds__(kStreamThreads) row_stream_kernel(const ChainA
             s.row[k] = row;
             s.col[k] = c0 + ((uint32_t)k * kStreamThreads + threadIdx.x) * VEC;
         }
-        load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_byte, row, load_limit, n, fill);
+        load_row_operands<DT, K, K, Spec, RAGGED>(a, s, 0, row_byte, row, load_limit, n, fill, n);
     };
     // the mask folded into a softmax core, applied by position
     auto folded_mask = [&]() {

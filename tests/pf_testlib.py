@@ -115,6 +115,10 @@ def check_chain(spec, inputs, variant=None, generic=False, what=""):
     """Run the chain as planned and compare every output with the oracle at the bars above: one comparison for every
     chain, whether it runs as one kernel or as several."""
     outs, info = gpu_run(spec, inputs, variant=variant, generic=generic)
+    # a plan that should have been specialised and fell back to the interpreter (a kernel header that no longer
+    # compiles, say) would still compute the right values, several times slower: it must not pass unnoticed
+    if not generic and os.environ.get("PF_JIT", "1") != "0" and os.environ.get("PF_NO_STATIC", "0") == "0":
+        assert info.interpreter_fallback == 0, f"{what}: the plan fell back to the interpreter"
     stats = []
     wants = oracle_run(spec, inputs)
     for o, w, (_, dt) in zip(outs, wants, spec.outputs):

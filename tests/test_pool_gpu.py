@@ -40,6 +40,37 @@ def test_global_pooling(shape, dtype, op):
     assert tuple(outs[0].shape) == (shape[0],) + (1,) * (len(shape) - 2) + (shape[-1],)
 
 
+@pytest.mark.parametrize("op", ["reduce_mean", "reduce_max"])
+@pytest.mark.parametrize("shape,dtype", [((2, 7, 7, 12), "f16"), ((3, 14, 14, 100), "bf16"), ((2, 9, 9, 5), "f32"), ((2, 64, 64, 100), "f16"),
+                                         ((4, 56, 56, 61), "f32"), ((2, 40, 40, 1001), "f16"), ((1, 30, 30, 3), "bf16")])
+def test_channel_counts_that_are_not_whole_vectors(shape, dtype, op):
+    # positions at element alignment, a partial last vector per position; slices of several workgroups included
+    spec = _pool_chain(dtype, shape, op)
+    _, info, _ = check_chain(spec, [wl.random_tensor(shape, dtype, 2260 + shape[-1])], what=f"ragged pooling {shape} {dtype} {op}")
+    assert info.family == _pf().PF_FAMILY_POOL
+
+
+def test_ragged_pooling_with_operands_on_both_sides_and_interpreted():
+    # SiLU(x * s + r) -> mean -> * g + b with 100 channels: per-channel and full-shape operands gathered element by element
+    # on both sides of the reduction; once specialised when the plan is made, once on the run-time-interpreted kernels
+    shape, dtype, c = (3, 20, 20, 100), "f16", 100
+    s = wl.ChainSpec(inputs=[(dtype, shape), (dtype, (c,)), (dtype, shape), (dtype, (c,)), (dtype, (shape[0], 1, 1, c))])
+    v = s.op("mul", 0, 1)
+    v = s.op("add", v, 2)
+    v = s.op("silu", v)
+    v = s.op("reduce_mean", v, i=[1, 2])
+    v = s.op("mul", v, 3)
+    v = s.op("add", v, 4)
+    s.out(v, dtype)
+    ins = [wl.random_tensor(shape, dtype, 2271), wl.random_tensor((c,), dtype, 2272), wl.random_tensor(shape, dtype, 2273),
+           wl.random_tensor((c,), dtype, 2274), wl.random_tensor((shape[0], 1, 1, c), dtype, 2275)]
+    _, info, _ = check_chain(s, ins, what="ragged pooling with operands")
+    assert info.family == _pf().PF_FAMILY_POOL
+    with env(PF_JIT="0"):
+        _, info, _ = check_chain(s, ins, what="ragged pooling with operands, interpreted")
+    assert info.spec_id == 0
+
+
 def test_squeeze_step_of_a_squeeze_and_excite_block():
     # sigmoid(mean over H, W of SiLU(x * scale[c] + shift[c])): element-wise steps on both sides, broadcast operands
     n, h, w, c = 3, 12, 12, 96
