@@ -117,7 +117,7 @@ def check_chain(spec, inputs, variant=None, generic=False, what=""):
     outs, info = gpu_run(spec, inputs, variant=variant, generic=generic)
     # a plan that should have been specialised and fell back to the interpreter (a kernel header that no longer
     # compiles, say) would still compute the right values, several times slower: it must not pass unnoticed
-    if not generic and os.environ.get("PF_JIT", "1") != "0" and os.environ.get("PF_NO_STATIC", "0") == "0":
+    if not generic and os.environ.get("PF_JIT", "1") != "0" and os.environ.get("PF_NO_STATIC", "0") == "0" and "PF_JIT_INCLUDE" not in os.environ:
         assert info.interpreter_fallback == 0, f"{what}: the plan fell back to the interpreter"
     stats = []
     wants = oracle_run(spec, inputs)
