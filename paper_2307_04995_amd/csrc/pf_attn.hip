@@ -112,6 +112,30 @@ PF_DEVICE void finish_slice(const AttnArgs& a, uint32_t head, uint32_t split, fl
     }
 }
 
+// The 16-byte pieces of one key row and one value row, without a branch: rows below t come from the caches, row t (the
+// appended one) from the new vectors; a row past the end reads memory that exists (the new vectors, or the last cache
+// row) and is zeroed.  Behind a guard
+// every load would merge with a fill value at the join, which the compiler resolves by waiting for it: the loads of a
+// lane, all independent, would then go to memory one round trip after the other.
+template <int DT>
+PF_DEVICE void load_key_value(const AttnArgs& a, uint32_t head, uint32_t row, uint32_t in_row, uint64_t head_vec, u32x4& k, u32x4& v) {
+    using S = Storage<DT>;
+    // (a chain that does not append has no new vectors: rows past the end then read the last cache row, which exists
+    // because such a chain has t = t_total >= 1)
+    const bool from_cache = row < a.t || a.k_new == nullptr || a.v_new == nullptr;
+    const uint32_t row_c = min(row, a.t - 1u);  // (only used when from_cache, and then t >= 1)
+    const uint64_t off = (from_cache ? ((uint64_t)head * a.t + row_c) * a.d + in_row * S::VEC : head_vec) * S::ESIZE;
+    const u32x4 gk = load_stream(from_cache ? a.k_cache : a.k_new, off);
+    const u32x4 gv = load_stream(from_cache ? a.v_cache : a.v_new, off);
+    const bool keep = row < a.t_total;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t wk = gk[j], wv = gv[j];
+        k[j] = keep ? wk : 0u;
+        v[j] = keep ? wv : 0u;
+    }
+}
+
 template <int DT, int NV>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     using S = Storage<DT>;
@@ -129,7 +153,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     const uint32_t rps = 256u >> a.log2_lpr;
     const uint32_t head = blockIdx.y, split = blockIdx.x;
     const uint32_t row0 = split * (uint32_t)NV * rps;
-    const uint32_t d = a.d, t = a.t, t_total = a.t_total;
+    const uint32_t d = a.d, t_total = a.t_total;
 
     const uint64_t head_vec = (uint64_t)head * d + in_row * VEC;  // element offset inside q / k / v / o
     float qf[VEC];
@@ -139,17 +163,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     u32x4 kraw[NV], vraw[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const uint32_t row = row0 + (uint32_t)i * rps + row_in_step;
-        kraw[i] = u32x4{0u, 0u, 0u, 0u};
-        vraw[i] = u32x4{0u, 0u, 0u, 0u};
-        if (row < t) {
-            const uint64_t off = (((uint64_t)head * t + row) * d + in_row * VEC) * S::ESIZE;
-            kraw[i] = load_stream(a.k_cache, off);
-            vraw[i] = load_stream(a.v_cache, off);
-        } else if (row < t_total) {  // the appended row
-            kraw[i] = load_cached(a.k_new, head_vec * S::ESIZE);
-            vraw[i] = load_cached(a.v_new, head_vec * S::ESIZE);
-        }
+        load_key_value<DT>(a, head, row0 + (uint32_t)i * rps + row_in_step, in_row, head_vec, kraw[i], vraw[i]);
     }
     // the grown caches, if they are outputs
     if (a.k_out != nullptr || a.v_out != nullptr) {
@@ -242,7 +256,7 @@ __global__ void __launch_bounds__(256) attn_decode_stream_kernel(const AttnArgs 
     const uint32_t rps = 256u >> a.log2_lpr;
     const uint32_t head = blockIdx.y, split = blockIdx.x;
     const uint32_t chunk_rows = (uint32_t)NV * rps;
-    const uint32_t d = a.d, t = a.t, t_total = a.t_total;
+    const uint32_t d = a.d, t_total = a.t_total;
     const uint32_t row_begin = split * a.chunks * chunk_rows;
     const uint32_t row_end = min(t_total, row_begin + a.chunks * chunk_rows);
     const uint32_t n_chunks = (row_end - row_begin + chunk_rows - 1u) / chunk_rows;  // >= 1: the planner leaves no slice empty
@@ -255,17 +269,7 @@ __global__ void __launch_bounds__(256) attn_decode_stream_kernel(const AttnArgs 
     auto load_chunk = [&](uint32_t c, u32x4 (&kr)[NV], u32x4 (&vr)[NV]) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            const uint32_t row = row_begin + c * chunk_rows + (uint32_t)i * rps + row_in_step;
-            kr[i] = u32x4{0u, 0u, 0u, 0u};
-            vr[i] = u32x4{0u, 0u, 0u, 0u};
-            if (row < t) {
-                const uint64_t off = (((uint64_t)head * t + row) * d + in_row * VEC) * S::ESIZE;
-                kr[i] = load_stream(a.k_cache, off);
-                vr[i] = load_stream(a.v_cache, off);
-            } else if (row < t_total) {  // the appended row
-                kr[i] = load_cached(a.k_new, head_vec * S::ESIZE);
-                vr[i] = load_cached(a.v_new, head_vec * S::ESIZE);
-            }
+            load_key_value<DT>(a, head, row_begin + c * chunk_rows + (uint32_t)i * rps + row_in_step, in_row, head_vec, kr[i], vr[i]);
         }
     };
     float m = -__builtin_inff(), l = 0.0f, acc[VEC];

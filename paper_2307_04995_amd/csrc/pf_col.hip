@@ -9,8 +9,13 @@ static hipError_t launch_colnorm_dt(const ColArgs& a, int kc, dim3 grid, hipStre
     switch (kc) {
         case 1: hipLaunchKernelGGL((colnorm_kernel<DT, 1, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
         case 2: hipLaunchKernelGGL((colnorm_kernel<DT, 2, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((colnorm_kernel<DT, 3, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
         case 4: hipLaunchKernelGGL((colnorm_kernel<DT, 4, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
+        case 6: hipLaunchKernelGGL((colnorm_kernel<DT, 6, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((colnorm_kernel<DT, 8, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
+        case 12: hipLaunchKernelGGL((colnorm_kernel<DT, 12, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
         case 16: hipLaunchKernelGGL((colnorm_kernel<DT, 16, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
+        case 24: hipLaunchKernelGGL((colnorm_kernel<DT, 24, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
         case 32: hipLaunchKernelGGL((colnorm_kernel<DT, 32, RMS, RAGGED>), grid, dim3(256), 0, st, a); break;
         default: return hipErrorInvalidValue;
     }

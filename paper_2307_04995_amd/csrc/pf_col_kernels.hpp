@@ -63,22 +63,41 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     const uint32_t cnt = RAGGED ? elems_below<VEC>(sv * VEC, a.s) : (uint32_t)VEC;  // elements of this lane's vector inside the row
     const uint64_t base = ((uint64_t)o * a.c) * a.s + (uint64_t)sv * VEC;  // element offset of row 0 at this column
 
+    // Whole vectors are loaded without a branch: a lane whose row or column does not exist reads the last one that does
+    // (the line a neighbour reads anyway) and never uses or stores the value.  Behind a guard every load would merge
+    // with a fill value at the join, which the compiler resolves by waiting for it: the loads of a lane, all
+    // independent, would then go to memory one round trip after the other.
+    const uint64_t base_ld = RAGGED ? base : ((uint64_t)o * a.c) * a.s + (uint64_t)min(sv, a.s_vecs - 1u) * VEC;
     u32x4 raw[KC];
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
         const uint32_t c = rg + 32u * (uint32_t)k;
-        raw[k] = u32x4{0u, 0u, 0u, 0u};
-        if (col_ok && c < a.c) {
-            if (RAGGED) raw[k] = load_elems<DT>(a.x, base + (uint64_t)c * a.s, cnt, 0u);
-            else raw[k] = load_stream(a.x, (base + (uint64_t)c * a.s) * S::ESIZE);
+        if (RAGGED) {
+            raw[k] = u32x4{0u, 0u, 0u, 0u};
+            if (col_ok && c < a.c) raw[k] = load_elems<DT>(a.x, base + (uint64_t)c * a.s, cnt, 0u);
+        } else {
+            raw[k] = load_stream(a.x, (base_ld + (uint64_t)min(c, a.c - 1u) * a.s) * S::ESIZE);
         }
+    }
+    // the parameters of the lane's rows, requested behind the slab (they are needed last; fetched where they are used,
+    // every row's store would wait for a trip to the cache of its own)
+    u32x4 gam_raw[KC], bet_raw[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const uint64_t off = (uint64_t)min(rg + 32u * (uint32_t)k, a.c - 1u) * S::ESIZE;
+        gam_raw[k] = S::splat(static_cast<const char*>(a.gamma) + off);
+        // (no beta: gamma's element is read instead and dropped below -- no branch around a load, as above)
+        bet_raw[k] = S::splat(static_cast<const char*>(a.beta ? a.beta : a.gamma) + off);
     }
     // mean = piv + mean[]: kept as a pivot (row 0 of the same position) plus the mean of the differences from it, so
     // that a large common offset of the values eats the digits neither of the sum nor of x - mean
     // (every lane fetches the pivot row itself: the 32 row groups of a column read the same 16 bytes, which the cache
     // serves, and no barrier is needed to share them)
     u32x4 piv_raw = u32x4{0u, 0u, 0u, 0u};
-    if (!RMS && col_ok) piv_raw = RAGGED ? load_elems<DT>(a.x, base, cnt, 0u) : load_cached(a.x, base * S::ESIZE);
+    if (!RMS) {
+        if (!RAGGED) piv_raw = load_cached(a.x, base_ld * S::ESIZE);
+        else if (col_ok) piv_raw = load_elems<DT>(a.x, base, cnt, 0u);
+    }
     float piv[VEC], mean[VEC], acc[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) piv[j] = 0.0f, mean[j] = 0.0f, acc[j] = 0.0f;
@@ -120,15 +139,13 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     for (int k = 0; k < KC; ++k) {
         const uint32_t c = rg + 32u * (uint32_t)k;
         if (!(col_ok && c < a.c)) continue;
-        float x[VEC], gam, bet = 0.0f;
+        float x[VEC], gam, bet;
         {
             float tmp[VEC];  // one element of the parameter vectors: the same for the whole row
-            S::unpack(S::splat(static_cast<const char*>(a.gamma) + (uint64_t)c * S::ESIZE), tmp);
+            S::unpack(gam_raw[k], tmp);
             gam = tmp[0];
-            if (a.beta) {
-                S::unpack(S::splat(static_cast<const char*>(a.beta) + (uint64_t)c * S::ESIZE), tmp);
-                bet = tmp[0];
-            }
+            S::unpack(bet_raw[k], tmp);
+            bet = a.beta ? tmp[0] : 0.0f;
         }
         S::unpack(raw[k], x);
 #pragma unroll

@@ -1285,7 +1285,10 @@ pf_status plan_column(pf_plan_s* p) {
     a.tiles_per_outer = (uint32_t)tiles;
     a.inv_c = 1.0f / (float)L.col_c;
     a.eps = L.eps;
-    p->k = L.col_c <= 32 ? 1 : L.col_c <= 64 ? 2 : L.col_c <= 128 ? 4 : L.col_c <= 512 ? 16 : 32;
+    // vectors per lane: the smallest instantiated count that holds the column (32 row groups per workgroup)
+    p->k = 32;
+    for (int kc : {24, 16, 12, 8, 6, 4, 3, 2, 1})
+        if ((int64_t)kc * 32 >= L.col_c) p->k = kc;
     p->family = PF_FAMILY_COLUMN;
     p->variant = 0;
     p->spec_id = 0;
