@@ -220,7 +220,7 @@ pf_status pf_chain_run(const pf_plan* plan, const void* const* inputs, void* con
         pf::GatherArgs ga = plan->gather;
         for (int k = 0; k < plan->desc.n_inputs; ++k) ga.in[k] = inputs[k];
         for (int o = 0; o < plan->desc.n_outputs; ++o) ga.out[o] = outputs[o];
-        const hipError_t eg = pf::launch_gather(L.main_dtype, ga, plan->grid, (hipStream_t)stream);
+        const hipError_t eg = pf::launch_gather(L.main_dtype, ga, plan->k, plan->grid, (hipStream_t)stream);
         if (eg != hipSuccess) return fail(PF_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(eg));
         return PF_OK;
     }

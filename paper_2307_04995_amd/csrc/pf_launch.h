@@ -25,7 +25,7 @@ hipError_t launch_pool(int dtype, const ChainArgs& a, const PoolGeom& g, int op,
 // kc: 16-byte vectors per lane (the normalised extent is at most 32 * kc); one of 1, 2, 4, 16, 32 (eight vectors per
 // lane compile to 240 registers, twice what sixteen need, so that size is left out)
 hipError_t launch_colnorm(int dtype, const ColArgs& a, int kc, bool rms, bool ragged, dim3 grid, hipStream_t st);
-hipError_t launch_gather(int dtype, const GatherArgs& a, dim3 grid, hipStream_t st);
+hipError_t launch_gather(int dtype, const GatherArgs& a, int k, dim3 grid, hipStream_t st);
 int group_resident_blocks_per_cu(int spec_id, int dtype, int nv, int block_threads);
 // whole-tensor storage conversion, 16-bit <-> fp32 (n elements)
 hipError_t launch_cast(int src_dtype, int dst_dtype, const void* src, void* dst, uint64_t n, hipStream_t st);
