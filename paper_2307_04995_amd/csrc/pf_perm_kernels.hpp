@@ -331,22 +331,55 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Spec::
     using EpiL = typename Spec::Epi;
     const bool pro_trivial = ProL::kDynamic ? a.pro.n == 1 : ProL::n == 1;
     const bool has_epi = EpiL::kDynamic ? a.epi.n != 0 : EpiL::n != 0;
+    // Whole-vector tiles load without a branch: a lane outside the tensor (a partial tile at an edge) reads the tile's
+    // first vector instead and stores nothing.  Behind a guard every load merges with a fill value at the join, which
+    // the compiler resolves by waiting for it -- the eight rows' operands were then fetched one round trip after the
+    // other, each waiting for the whole block as well.
     uint32_t in_off[VEC];
 #pragma unroll
     for (int r = 0; r < VEC; ++r) {
         in_off[r] = in_base + (to * VEC + r) * g.t_in_stride_o + ti * VEC;
-        blk[r] = u32x4{0u, 0u, 0u, 0u};
         if (RAGGED) {
+            blk[r] = u32x4{0u, 0u, 0u, 0u};
             if (valid && (uint32_t)r < no) blk[r] = load_elems<DT>(a.full[0], in_off[r], ni, 0u);
-        } else if (valid) {
+        } else {
+            in_off[r] = valid ? in_off[r] : in_base;
             blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
         }
     }
-    if (!pro_trivial) {
+    // A specialised chain with one or two operands beside the block asks for the operands of all its rows right behind
+    // the block (they arrive together with it) and keeps them in registers; fetched row by row, in front of each row's
+    // program, every row would cost the wave a trip to the cache of its own -- and a launch of this kernel is a single
+    // round of resident waves, so a wave's latency is the kernel's.
+    constexpr bool kBatchOperands = Spec::kStatic && !RAGGED && (Spec::NF - 1) + Spec::NV <= 2;
+    if (!pro_trivial && kBatchOperands) {
+        u32x4 fop[Spec::NF][VEC], vop[Spec::NV > 0 ? Spec::NV : 1][VEC];
+        const uint32_t zero = 0u;
+        const bool row_ok = true;
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+            perm_load_operands<DT, 1, Spec, 1, RAGGED>(a, g, s, &in_off[r], &zero, &row_ok, &ni);
+#pragma unroll
+            for (int f = 1; f < Spec::NF; ++f) fop[f][r] = s.fraw[f][0];
+#pragma unroll
+            for (int v = 0; v < Spec::NV; ++v) vop[v][r] = s.vraw[v][0];
+        }
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+#pragma unroll
+            for (int f = 1; f < Spec::NF; ++f) s.fraw[f][0] = fop[f][r];
+#pragma unroll
+            for (int v = 0; v < Spec::NV; ++v) s.vraw[v][0] = vop[v][r];
+            s.fraw[0][0] = blk[r];
+            set_positions<DT, 1, Spec>(s, &in_off[r], g.div_in_inner, g.in_n_inner);
+            run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStoreT{});
+            blk[r] = S::pack(s.acc);
+        }
+    } else if (!pro_trivial) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
             const uint32_t zero = 0u;
-            const bool row_ok = valid && (!RAGGED || (uint32_t)r < no);
+            const bool row_ok = RAGGED ? valid && (uint32_t)r < no : true;
             perm_load_operands<DT, 1, Spec, 1, RAGGED>(a, g, s, &in_off[r], &zero, &row_ok, &ni);
             s.fraw[0][0] = blk[r];
             set_positions<DT, 1, Spec>(s, &in_off[r], g.div_in_inner, g.in_n_inner);
@@ -357,11 +390,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Spec::
     transpose_block<DT>(blk, outv);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
-        const uint32_t out_off = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
+        const uint32_t out_off_real = out_base + (ti * VEC + c) * g.t_out_stride_i + to * VEC;
+        const uint32_t out_off = RAGGED || valid ? out_off_real : out_base;  // (as above)
         const bool row_ok = valid && (!RAGGED || (uint32_t)c < ni);
         if (has_epi) {
             const uint32_t zero = 0u;
-            perm_load_operands<DT, 1, Spec, 2, RAGGED>(a, g, s, &zero, &out_off, &row_ok, &no);
+            const bool load_ok = RAGGED ? row_ok : true;
+            perm_load_operands<DT, 1, Spec, 2, RAGGED>(a, g, s, &zero, &out_off, &load_ok, &no);
             S::unpack(outv[c], s.acc);
             set_positions<DT, 1, Spec>(s, &out_off, g.div_out_inner, g.out_n_inner);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStoreT{});
