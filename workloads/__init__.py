@@ -646,11 +646,14 @@ def random_layout_chain(seed: int):
 
 def random_pool_chain(seed: int):
     """A random pooling chain: [element-wise] -> reduce_sum / max / mean over the positions of a channels-last tensor
-    -> [element-wise]; random sample count, 1 to 3 spatial dimensions, channel count, storage type."""
+    -> [element-wise]; random sample count, 1 to 3 spatial dimensions, channel count (whole 16-byte vectors in six
+    chains of ten, any count in the others), storage type."""
     g = np.random.default_rng(BASE_SEED * 37 + seed)
     dtype = str(g.choice(["f16", "bf16", "f32"]))
     vec = 4 if dtype == "f32" else 8
     c = vec * int(g.integers(1, 65))
+    if g.random() < 0.4:
+        c = int(g.integers(1, 400))
     n = int(g.integers(1, 6))
     spatial = [int(g.integers(1, 48)) for _ in range(int(g.integers(1, 4)))]
     shape = tuple([n] + spatial + [c])
