@@ -68,16 +68,21 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
     // with a fill value at the join, which the compiler resolves by waiting for it: the loads of a lane, all
     // independent, would then go to memory one round trip after the other.
     const uint64_t base_ld = RAGGED ? base : ((uint64_t)o * a.c) * a.s + (uint64_t)min(sv, a.s_vecs - 1u) * VEC;
+    // (RAGGED: a lane's vector is whole, partial or absent for all its rows alike, so the three cases are told apart once,
+    // outside the loop over the rows, and each runs its loads back to back)
     u32x4 raw[KC];
+    if (!RAGGED || cnt == (uint32_t)VEC) {
 #pragma unroll
-    for (int k = 0; k < KC; ++k) {
-        const uint32_t c = rg + 32u * (uint32_t)k;
-        if (RAGGED) {
-            raw[k] = u32x4{0u, 0u, 0u, 0u};
-            if (col_ok && c < a.c) raw[k] = load_elems<DT>(a.x, base + (uint64_t)c * a.s, cnt, 0u);
-        } else {
-            raw[k] = load_stream(a.x, (base_ld + (uint64_t)min(c, a.c - 1u) * a.s) * S::ESIZE);
+        for (int k = 0; k < KC; ++k) {
+            const uint64_t elem = base_ld + (uint64_t)min(rg + 32u * (uint32_t)k, a.c - 1u) * a.s;
+            raw[k] = RAGGED ? load_elems<DT>(a.x, elem, (uint32_t)VEC, 0u) : load_stream(a.x, elem * S::ESIZE);
         }
+    } else if (cnt != 0u) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k) raw[k] = load_elems<DT>(a.x, base + (uint64_t)min(rg + 32u * (uint32_t)k, a.c - 1u) * a.s, cnt, 0u);
+    } else {
+#pragma unroll
+        for (int k = 0; k < KC; ++k) raw[k] = u32x4{0u, 0u, 0u, 0u};
     }
     // the parameters of the lane's rows, requested behind the slab (they are needed last; fetched where they are used,
     // every row's store would wait for a trip to the cache of its own)

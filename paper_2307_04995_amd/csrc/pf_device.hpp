@@ -152,18 +152,25 @@ PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint
         return __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
     u32x4 r = {fill, fill, fill, fill};
+    if (count == 0u) return r;
+    // A partial vector: every slot reads an element that exists (the last one, for the slots past the end) and the
+    // fill value is selected afterwards.  No branch per element: behind one, each load would wait for the one before.
+    const uint32_t last = count - 1u;
     if (DT == DT_F32) {
         const uint32_t* p = static_cast<const uint32_t*>(base) + elem;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((uint32_t)e < count) r[e] = __builtin_nontemporal_load(p + e);
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t got = __builtin_nontemporal_load(p + min((uint32_t)e, last));
+            r[e] = (uint32_t)e < count ? got : fill;
+        }
     } else {
         const uint16_t* p = static_cast<const uint16_t*>(base) + elem;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t lo = fill & 0xffffu, hi = fill >> 16;
-            if ((uint32_t)(2 * j) < count) lo = __builtin_nontemporal_load(p + 2 * j);
-            if ((uint32_t)(2 * j + 1) < count) hi = __builtin_nontemporal_load(p + 2 * j + 1);
+            const uint32_t got_lo = __builtin_nontemporal_load(p + min((uint32_t)(2 * j), last));
+            const uint32_t got_hi = __builtin_nontemporal_load(p + min((uint32_t)(2 * j + 1), last));
+            const uint32_t lo = (uint32_t)(2 * j) < count ? got_lo : (fill & 0xffffu);
+            const uint32_t hi = (uint32_t)(2 * j + 1) < count ? got_hi : (fill >> 16);
             r[j] = lo | (hi << 16);
         }
     }
@@ -546,18 +553,24 @@ PF_DEVICE u32x4 load_vec_operand_elems(const VecArg& va, uint32_t row, uint32_t 
     if ((VM & 2) && va.numel == 1) return S::splat(va.ptr);
     if (BC && va.n_terms != 0u && va.col_bcast) return S::splat(static_cast<const char*>(va.ptr) + (uint64_t)vec_offset<BC>(va, row, col, n_inner) * S::ESIZE);
     u32x4 r = {0u, 0u, 0u, 0u};
+    if (count == 0u) return r;
+    // (slots past the end read the last element that exists and are zeroed: no branch per element, see load_elems)
+    const uint32_t last = count - 1u;
     if (DT == DT_F32) {
         const uint32_t* p = static_cast<const uint32_t*>(va.ptr);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((uint32_t)e < count) r[e] = p[vec_offset<BC>(va, row, col + e, n_inner)];
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t got = p[vec_offset<BC>(va, row, col + min((uint32_t)e, last), n_inner)];
+            r[e] = (uint32_t)e < count ? got : 0u;
+        }
     } else {
         const uint16_t* p = static_cast<const uint16_t*>(va.ptr);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t lo = 0u, hi = 0u;
-            if ((uint32_t)(2 * j) < count) lo = p[vec_offset<BC>(va, row, col + 2 * j, n_inner)];
-            if ((uint32_t)(2 * j + 1) < count) hi = p[vec_offset<BC>(va, row, col + 2 * j + 1, n_inner)];
+            const uint32_t got_lo = p[vec_offset<BC>(va, row, col + min((uint32_t)(2 * j), last), n_inner)];
+            const uint32_t got_hi = p[vec_offset<BC>(va, row, col + min((uint32_t)(2 * j + 1), last), n_inner)];
+            const uint32_t lo = (uint32_t)(2 * j) < count ? got_lo : 0u;
+            const uint32_t hi = (uint32_t)(2 * j + 1) < count ? got_hi : 0u;
             r[j] = lo | (hi << 16);
         }
     }
