@@ -79,7 +79,11 @@ __global__ void __launch_bounds__(256) colnorm_kernel(const ColArgs a) {
         }
     } else if (cnt != 0u) {
 #pragma unroll
-        for (int k = 0; k < KC; ++k) raw[k] = load_elems<DT>(a.x, base + (uint64_t)min(rg + 32u * (uint32_t)k, a.c - 1u) * a.s, cnt, 0u);
+        for (int k = 0; k < KC; ++k) {
+            // (what follows a partial vector is the next row of the tensor, unless this is its last row)
+            const uint32_t c = min(rg + 32u * (uint32_t)k, a.c - 1u);
+            raw[k] = load_elems<DT>(a.x, base + (uint64_t)c * a.s, cnt, 0u, c + 1u < a.c || blockIdx.x + a.tiles_per_outer < gridDim.x);
+        }
     } else {
 #pragma unroll
         for (int k = 0; k < KC; ++k) raw[k] = u32x4{0u, 0u, 0u, 0u};

@@ -145,14 +145,36 @@ PF_DEVICE void warm_chain_arguments() {
 // unaligned global access enabled, and the compiler emits a single dwordx4 access for this pointer type); only
 // the partial vector at the end of a row goes element by element, so nothing outside the row is touched.
 typedef u32x4 u32x4_elem_aligned __attribute__((aligned(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_elem_aligned __attribute__((aligned(2)));
+typedef uint32_t u32_elem_aligned __attribute__((aligned(2)));
 
+// `room`: the VEC elements from `elem` on all lie inside the tensor (what follows a partial vector is the start of the
+// tensor's next row, say): the partial vector is then read as one whole vector and the slots past `count` replaced by
+// the fill value -- one load instead of `count`.
 template <int DT>
-PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill) {
+PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill, bool room = false) {
     if (count == (uint32_t)Storage<DT>::VEC)
         return __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
     u32x4 r = {fill, fill, fill, fill};
     if (count == 0u) return r;
+    if (room) {
+        const u32x4 got = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = got[j];
+            if (DT == DT_F32) {
+                r[j] = (uint32_t)j < count ? w : fill;
+            } else {
+                const uint32_t lo = (uint32_t)(2 * j) < count ? (w & 0xffffu) : (fill & 0xffffu);
+                const uint32_t hi = (uint32_t)(2 * j + 1) < count ? (w & 0xffff0000u) : (fill & 0xffff0000u);
+                r[j] = lo | hi;
+            }
+        }
+        return r;
+    }
     // A partial vector: every slot reads an element that exists (the last one, for the slots past the end) and the
     // fill value is selected afterwards.  No branch per element: behind one, each load would wait for the one before.
     const uint32_t last = count - 1u;
@@ -182,19 +204,20 @@ PF_DEVICE void store_elems(void* base, uint64_t elem, uint32_t count, u32x4 v) {
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4_elem_aligned*>(static_cast<char*>(base) + elem * Storage<DT>::ESIZE));
         return;
     }
+    // A partial vector goes out in pieces of 8, 4 and 2 bytes (the binary digits of its length), at element alignment:
+    // at most three stores, not one per element.
+    const uint32_t v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
     if (DT == DT_F32) {
         uint32_t* p = static_cast<uint32_t*>(base) + elem;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((uint32_t)e < count) __builtin_nontemporal_store(v[e], p + e);
+        if (count & 2u) __builtin_nontemporal_store(u32x2{v0, v1}, reinterpret_cast<u32x2_elem_aligned*>(p));
+        if (count & 1u) __builtin_nontemporal_store((count & 2u) ? v2 : v0, p + (count & 2u));
     } else {
         uint16_t* p = static_cast<uint16_t*>(base) + elem;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t w = v[j];
-            if ((uint32_t)(2 * j) < count) __builtin_nontemporal_store((uint16_t)(w & 0xffffu), p + 2 * j);
-            if ((uint32_t)(2 * j + 1) < count) __builtin_nontemporal_store((uint16_t)(w >> 16), p + 2 * j + 1);
-        }
+        if (count & 4u) __builtin_nontemporal_store(u32x2{v0, v1}, reinterpret_cast<u32x2_elem_aligned*>(p));
+        const uint32_t mid = (count & 4u) ? v2 : v0;  // the dword behind the 8-byte piece, if there was one
+        if (count & 2u) __builtin_nontemporal_store(mid, reinterpret_cast<u32_elem_aligned*>(p + (count & 4u)));
+        const uint32_t last = (count & 4u) ? ((count & 2u) ? v3 : v2) : ((count & 2u) ? v1 : v0);
+        if (count & 1u) __builtin_nontemporal_store((uint16_t)(last & 0xffffu), p + (count & 6u));
     }
 }
 // how many elements of the vector that starts at `col` lie below `limit` (0 .. VEC)

@@ -214,7 +214,9 @@ PF_DEVICE void load_row_operands(const ChainArgs& a, LaneState<DT, K, Spec>& s, 
                 }
                 if (RAGGED) {
                     s.fraw[f][k] = u32x4{fill, fill, fill, fill};
-                    s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill);
+                    // (what follows a partial vector is the next row of the same tensor, unless this is the last row)
+                    s.fraw[f][k] = load_elems<DT>(base, s.col[k], elems_below<S::VEC>(s.col[k], load_limit), fill,
+                                                  (uint64_t)row + 1u < a.rows || s.col[k] + (uint32_t)S::VEC <= n_inner);
                 } else {
                     // No branch around the load: a lane past the limit reads the last vector inside it (the same
                     // memory line as its neighbour: no extra traffic; `row_byte` always addresses a row that
