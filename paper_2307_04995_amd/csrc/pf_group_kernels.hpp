@@ -359,7 +359,10 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         for (int i = 0; i < NV; ++i) {
             raw[i] = u32x4{0u, 0u, 0u, 0u};
             if (valid_of(i)) {
-                if (ragged) raw[i] = load_elems<DT>(in_base, rel_of(i) * g.channels + cvi * VEC, cnt, 0u);
+                // (what follows a position's partial vector is the next position, unless it is the tensor's last)
+                if (ragged)
+                    raw[i] = load_elems<DT>(in_base, rel_of(i) * g.channels + cvi * VEC, cnt, 0u,
+                                            (uint64_t)sample * g.hw + p_begin + rel_of(i) + 1u < (uint64_t)g.samples * g.hw);
                 // (the statistics launch leaves x in the caches for the launch that re-reads it: C5 in two launches
                 // 39.2 -> 35.2 us; a one-launch tile is touched once and streams past them)
                 else if (PHASE == 1) raw[i] = load_cached(in_base + (size_t)step_of(i) * step_bytes, (uint64_t)lane_bytes);

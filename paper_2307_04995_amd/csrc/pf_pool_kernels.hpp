@@ -57,8 +57,10 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
     LaneState<DT, 1, Spec> s;
     s.col[0] = cvi * VEC;
     const uint32_t cnt = RAGGED ? elems_below<VEC>(cvi * (uint32_t)VEC, g.channels) : (uint32_t)VEC;
+    // (what follows a position's partial vector is the next position, unless it is the tensor's last)
+    const uint64_t total_elems = (uint64_t)g.samples * g.hw * g.channels;
     auto load_full = [&](const void* base, uint64_t elem) {
-        return RAGGED ? load_elems<DT>(base, elem, cnt, 0u) : load_stream(base, elem * S::ESIZE);
+        return RAGGED ? load_elems<DT>(base, elem, cnt, 0u, elem + (uint64_t)VEC <= total_elems) : load_stream(base, elem * S::ESIZE);
     };
 
     // ---- the slice in chunks of NV position steps: the primary operand of a chunk first (all its loads in flight),

@@ -21,9 +21,11 @@ namespace pf {
 // aligned kernels a third of their speed): the channel count is not a whole number of vectors, so a position starts at
 // element alignment and its last vector holds `cnt` channels; the rest of that vector reads as zero (and contributes
 // zero to every tap) and is not stored.
+// total: elements of the tensor read from, when known (0 = not): a partial vector is then read as a whole one wherever
+// 16 bytes from its start still lie inside the tensor (they belong to the next position) -- see load_elems.
 template <int DT>
-PF_DEVICE u32x4 stencil_load(const void* base, uint64_t elem, bool ragged, uint32_t cnt) {
-    return ragged ? load_elems<DT>(base, elem, cnt, 0u) : load_cached(base, elem * Storage<DT>::ESIZE);
+PF_DEVICE u32x4 stencil_load(const void* base, uint64_t elem, bool ragged, uint32_t cnt, uint64_t total = 0) {
+    return ragged ? load_elems<DT>(base, elem, cnt, 0u, elem + (uint64_t)Storage<DT>::VEC <= total) : load_cached(base, elem * Storage<DT>::ESIZE);
 }
 template <int DT>
 PF_DEVICE void stencil_store(void* base, uint64_t elem, bool ragged, uint32_t cnt, u32x4 v) {
@@ -99,7 +101,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const ChainArgs a, const
 #pragma unroll
             for (int f = 0; f < Spec::NF; ++f)
                 if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
-                    pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
+                    pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt, (uint64_t)g.n * g.h * g.w * g.c);
 #pragma unroll
             for (int v = 0; v < Spec::NV; ++v)
                 if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
@@ -236,7 +238,7 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
             for (int f = 0; f < Spec::NF; ++f) {
                 pend_f[r][f] = u32x4{0u, 0u, 0u, 0u};
                 if (f < Spec::n_full(a) && ((pro_full >> f) & 1u) && ok)
-                    pend_f[r][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt);
+                    pend_f[r][f] = stencil_load<DT>(a.full[f], (uint64_t)pos * g.c + cvi * VEC, ragged, cnt, (uint64_t)g.n * g.h * g.w * g.c);
             }
         }
 #pragma unroll
@@ -415,7 +417,7 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
 #pragma unroll
                 for (int f = 0; f < Spec::NF; ++f)
                     if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
-                        pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos[dw] * g.c + cvi * VEC, ragged, cnt);
+                        pend_f[dw][f] = stencil_load<DT>(a.full[f], (uint64_t)pos[dw] * g.c + cvi * VEC, ragged, cnt, (uint64_t)g.n * g.h * g.w * g.c);
 #pragma unroll
                 for (int v = 0; v < Spec::NV; ++v)
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u))
