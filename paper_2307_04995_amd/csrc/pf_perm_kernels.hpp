@@ -341,10 +341,25 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Spec::
         in_off[r] = in_base + (to * VEC + r) * g.t_in_stride_o + ti * VEC;
         if (RAGGED) {
             blk[r] = u32x4{0u, 0u, 0u, 0u};
-            if (valid && (uint32_t)r < no) blk[r] = load_elems<DT>(a.full[0], in_off[r], ni, 0u);
         } else {
             in_off[r] = valid ? in_off[r] : in_base;
             blk[r] = load_stream(a.full[0], (uint64_t)in_off[r] * S::ESIZE);
+        }
+    }
+    if (RAGGED && valid) {
+        // The block's rows without a branch per row: a row past the block's end (r >= no) reads the last one that exists
+        // and is not stored; whether the vectors are whole (ni == VEC) is the same for all rows and told apart once.  A
+        // partial vector is read whole where the tensor continues behind it (see load_elems).
+        const uint32_t last_row = in_base + (to * VEC + (no - 1u)) * g.t_in_stride_o + ti * VEC;
+        const bool room = (uint64_t)last_row + (uint64_t)VEC <= a.rows * a.n_inner;
+        if (ni == (uint32_t)VEC) {
+#pragma unroll
+            for (int r = 0; r < VEC; ++r)
+                blk[r] = load_elems<DT>(a.full[0], in_base + (to * VEC + min((uint32_t)r, no - 1u)) * g.t_in_stride_o + ti * VEC, (uint32_t)VEC, 0u);
+        } else {
+#pragma unroll
+            for (int r = 0; r < VEC; ++r)
+                blk[r] = load_elems<DT>(a.full[0], in_base + (to * VEC + min((uint32_t)r, no - 1u)) * g.t_in_stride_o + ti * VEC, ni, 0u, room);
         }
     }
     // A specialised chain with one or two operands beside the block asks for the operands of all its rows right behind
