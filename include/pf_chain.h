@@ -380,6 +380,17 @@ pf_status pf_copy_probe(const void *src, void *dst, uint64_t bytes, int32_t vari
  */
 uint64_t pf_jit_compile_count(void);
 
+/*
+ * Diagnostic: how many of this process's plan-time kernels came from disk instead of the compiler.  With
+ * PF_JIT_CACHE=<directory> in the environment (the directory must exist and be writable; off by default) every kernel
+ * compiled at plan time is also kept there, and a later process that plans the same chain loads it instead of
+ * compiling it (a plan then takes milliseconds rather than seconds).  A file's name is a digest of everything its code
+ * depends on (generated source, template-id, compiler options and version, the contents of the kernel headers), so a
+ * new build of the library never picks up an old kernel; a file that does not load is compiled over.  For callers that
+ * start often (section 7 of the paper compiles per model as well, ahead of time).
+ */
+uint64_t pf_jit_cache_hits(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,7 +72,7 @@ class pf_partition(C.Structure):
 LIB_PATH = os.environ.get("PF_CHAIN_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpf_chain.so")
 EXPORTS = ["pf_chain_validate", "pf_chain_infer_shape", "pf_chain_plan", "pf_chain_plan_variant",
            "pf_chain_plan_get_info", "pf_chain_run", "pf_chain_plan_poll_error", "pf_chain_plan_destroy", "pf_status_str",
-           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_chain_recompose",
+           "pf_last_error", "pf_copy_probe", "pf_jit_compile_count", "pf_jit_cache_hits", "pf_chain_recompose",
            "pf_chain_partition", "pf_chain_segment_cost", "pf_chain_plan_get_partition", "pf_chain_run_static"]
 
 
@@ -104,8 +104,10 @@ def _load() -> C.CDLL:
     lib.pf_chain_segment_cost.argtypes = [C.POINTER(pf_chain_desc), C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     lib.pf_jit_compile_count.argtypes = []
     lib.pf_jit_compile_count.restype = C.c_uint64
+    lib.pf_jit_cache_hits.argtypes = []
+    lib.pf_jit_cache_hits.restype = C.c_uint64
     for name in EXPORTS:
-        if name not in ("pf_chain_plan_destroy", "pf_status_str", "pf_last_error", "pf_jit_compile_count"):
+        if name not in ("pf_chain_plan_destroy", "pf_status_str", "pf_last_error", "pf_jit_compile_count", "pf_jit_cache_hits"):
             getattr(lib, name).restype = C.c_int
     return lib
 
@@ -237,6 +239,10 @@ def pf_chain_segment_cost(desc: pf_chain_desc, first_op: int, last_op: int):
 
 def pf_jit_compile_count() -> int:
     return int(_lib.pf_jit_compile_count())
+
+
+def pf_jit_cache_hits() -> int:
+    return int(_lib.pf_jit_cache_hits())
 
 
 # ---- marshalling helpers -------------------------------------------------------------------------

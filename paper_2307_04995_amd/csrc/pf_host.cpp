@@ -379,6 +379,7 @@ const char* pf_status_str(pf_status s) {
 const char* pf_last_error(void) { return pfh::last_error(); }
 
 uint64_t pf_jit_compile_count(void) { return pf::jit_compile_count(); }
+uint64_t pf_jit_cache_hits(void) { return pf::jit_disk_hits(); }
 
 pf_status pf_copy_probe(const void* src, void* dst, uint64_t bytes, int32_t variant, void* stream) {
     if (!src || !dst) return fail(PF_ERR_INVALID_ARG, "null argument");

@@ -15,8 +15,14 @@
 #include <dlfcn.h>
 #include <hip/hiprtc.h>
 
+#include <dirent.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <map>
 #include <mutex>
 #include <sstream>
@@ -51,6 +57,69 @@ bool file_exists(const std::string& p) {
     return true;
 }
 
+// ---- kernels kept on disk between processes (opt-in: PF_JIT_CACHE=<directory>) ----------------------------------
+// A file holds one code object and the kernel's symbol in it.  Its name is a 128-bit digest of everything the code
+// depends on: the generated source, the template-id, the compiler options, the run-time compiler's version and the
+// contents of every kernel header.  A file that does not load (truncated, written by something else) is ignored and
+// compiled over; files are written under a temporary name and renamed, so a reader never sees half of one.
+struct Digest {
+    uint64_t a = 1469598103934665603ull, b = 0x9e3779b97f4a7c15ull;
+    void add(const void* data, size_t n) {
+        const unsigned char* p = static_cast<const unsigned char*>(data);
+        for (size_t i = 0; i < n; ++i) {
+            a = (a ^ p[i]) * 1099511628211ull;                 // FNV-1a
+            b = (b ^ p[i]) * 0xff51afd7ed558ccdull;            // a second, independent mix
+            b ^= b >> 29;
+        }
+    }
+    void add(const std::string& t) {
+        const uint64_t n = t.size();
+        add(&n, sizeof(n));
+        add(t.data(), t.size());
+    }
+};
+
+bool read_file(const std::string& path, std::vector<char>* out) {
+    FILE* f = fopen(path.c_str(), "rb");
+    if (!f) return false;
+    char buf[65536];
+    size_t n;
+    out->clear();
+    while ((n = fread(buf, 1, sizeof(buf), f)) > 0) out->insert(out->end(), buf, buf + n);
+    fclose(f);
+    return true;
+}
+
+// digest of the kernel headers in `inc` (and of the public header they include), computed once per directory
+std::string headers_digest(const std::string& inc) {
+    static std::map<std::string, std::string> done;  // (under g_mutex)
+    auto it = done.find(inc);
+    if (it != done.end()) return it->second;
+    std::vector<std::string> names;
+    if (DIR* d = opendir(inc.c_str())) {
+        while (dirent* e = readdir(d)) {
+            const std::string n = e->d_name;
+            const size_t dot = n.rfind('.');
+            const std::string ext = dot == std::string::npos ? "" : n.substr(dot);
+            if (ext == ".hpp" || ext == ".h" || ext == ".inc") names.push_back(n);
+        }
+        closedir(d);
+    }
+    std::sort(names.begin(), names.end());
+    Digest dg;
+    std::vector<char> data;
+    for (const std::string& n : names) {
+        dg.add(n);
+        if (read_file(inc + "/" + n, &data)) dg.add(std::string(data.begin(), data.end()));
+    }
+    if (read_file(inc + "/../../include/pf_chain.h", &data)) dg.add(std::string(data.begin(), data.end()));
+    char text[40];
+    snprintf(text, sizeof(text), "%016llx%016llx", (unsigned long long)dg.a, (unsigned long long)dg.b);
+    return done[inc] = text;
+}
+
+uint64_t g_disk_hits = 0;
+
 std::string list_text(const std::vector<uint32_t>& l) {
     std::ostringstream o;
     o << "pf::StaticList<";
@@ -84,14 +153,62 @@ hipFunction_t compile(int device, const std::string& source, const std::string& 
     const std::string inc = include_dir();
     if (inc.empty() || !file_exists(inc + "/pf_row_kernels.hpp")) return fail("kernel headers not found (looked in '" + inc + "')");
 
+    // the same code generation options as the build-time kernels
+    const std::string inc_opt = "-I" + inc;
+    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", inc_opt.c_str(), "-Wno-pass-failed",
+                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+
+    auto finish = [&](hipFunction_t fn) {
+        const char* lg = getenv("PF_LOG");
+        if (lg && atoi(lg) != 0) {  // registers and scratch of the new kernel: what decides how many waves a SIMD holds
+            int regs = 0, scratch = 0;
+            (void)hipFuncGetAttribute(&regs, HIP_FUNC_ATTRIBUTE_NUM_REGS, fn);
+            (void)hipFuncGetAttribute(&scratch, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, fn);
+            fprintf(stderr, "[pf_jit] %s: %d registers, %d bytes of scratch per lane\n", name_expr.c_str(), regs, scratch);
+        }
+        g_cache[key] = fn;  // the module stays loaded until the process ends
+        return fn;
+    };
+
+    // a kernel kept on disk by an earlier process?
+    std::string cache_file;
+    if (const char* dir = getenv("PF_JIT_CACHE")) {
+        if (*dir) {
+            int major = 0, minor = 0;
+            (void)hiprtcVersion(&major, &minor);
+            Digest dg;
+            dg.add(source);
+            dg.add(name_expr);
+            for (const char* o : opts)
+                if (o != inc_opt.c_str()) dg.add(std::string(o));
+            dg.add(headers_digest(inc));
+            dg.add(std::to_string(major) + "." + std::to_string(minor));
+            char name[64];
+            snprintf(name, sizeof(name), "/pf_%016llx%016llx.co", (unsigned long long)dg.a, (unsigned long long)dg.b);
+            cache_file = std::string(dir) + name;
+            std::vector<char> blob;
+            if (read_file(cache_file, &blob) && blob.size() > 12 && memcmp(blob.data(), "PFCO", 4) == 0) {
+                uint32_t sym_len = 0;
+                memcpy(&sym_len, blob.data() + 4, 4);
+                if (sym_len > 0 && (size_t)sym_len + 8 < blob.size()) {
+                    const std::string sym(blob.data() + 8, blob.data() + 8 + sym_len);
+                    hipModule_t mod = nullptr;
+                    hipFunction_t fn = nullptr;
+                    if (hipModuleLoadData(&mod, blob.data() + 8 + sym_len) == hipSuccess &&
+                        hipModuleGetFunction(&fn, mod, sym.c_str()) == hipSuccess) {
+                        ++g_disk_hits;
+                        return finish(fn);
+                    }
+                    (void)hipGetLastError();  // a file that does not load is compiled over below
+                }
+            }
+        }
+    }
+
     hiprtcProgram prog = nullptr;
     if (hiprtcCreateProgram(&prog, source.c_str(), "pf_jit.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
         return fail("hiprtcCreateProgram failed");
     hiprtcAddNameExpression(prog, name_expr.c_str());
-    const std::string inc_opt = "-I" + inc;
-    // the same code generation options as the build-time kernels
-    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", inc_opt.c_str(), "-Wno-pass-failed",
-                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
     const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
     if (rc != HIPRTC_SUCCESS) {
         size_t n = 0;
@@ -122,17 +239,18 @@ hipFunction_t compile(int device, const std::string& source, const std::string& 
     if (hipModuleLoadData(&mod, code.data()) != hipSuccess) return fail("hipModuleLoadData failed");
     if (hipModuleGetFunction(&fn, mod, symbol.c_str()) != hipSuccess) return fail("hipModuleGetFunction failed");
     ++g_compiles;
-    {
-        const char* lg = getenv("PF_LOG");
-        if (lg && atoi(lg) != 0) {  // registers and scratch of the new kernel: what decides how many waves a SIMD holds
-            int regs = 0, scratch = 0;
-            (void)hipFuncGetAttribute(&regs, HIP_FUNC_ATTRIBUTE_NUM_REGS, fn);
-            (void)hipFuncGetAttribute(&scratch, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, fn);
-            fprintf(stderr, "[pf_jit] %s: %d registers, %d bytes of scratch per lane\n", name_expr.c_str(), regs, scratch);
+    if (!cache_file.empty()) {
+        // keep it for later processes: written under a name of its own, then renamed into place
+        const std::string tmp = cache_file + "." + std::to_string((long)getpid()) + ".tmp";
+        if (FILE* f = fopen(tmp.c_str(), "wb")) {
+            const uint32_t sym_len = (uint32_t)symbol.size();
+            bool ok = fwrite("PFCO", 1, 4, f) == 4 && fwrite(&sym_len, 4, 1, f) == 1 && fwrite(symbol.data(), 1, sym_len, f) == sym_len &&
+                      fwrite(code.data(), 1, code.size(), f) == code.size();
+            ok = (fclose(f) == 0) && ok;
+            if (!ok || rename(tmp.c_str(), cache_file.c_str()) != 0) (void)remove(tmp.c_str());
         }
     }
-    g_cache[key] = fn;  // the module stays loaded until the process ends
-    return fn;
+    return finish(fn);
 }
 
 }  // namespace
@@ -143,6 +261,11 @@ bool jit_enabled() {
     const char* ns = getenv("PF_NO_STATIC");
     if (ns && *ns && atoi(ns) != 0) return false;
     return true;
+}
+
+uint64_t jit_disk_hits() {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return g_disk_hits;
 }
 
 uint64_t jit_compile_count() {

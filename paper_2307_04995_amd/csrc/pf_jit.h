@@ -24,6 +24,7 @@ struct JitSpec {
 bool jit_enabled();
 // kernels compiled so far in this process (cache hits do not count)
 uint64_t jit_compile_count();
+uint64_t jit_disk_hits();  // kernels taken from PF_JIT_CACHE instead of being compiled
 
 // Each returns the kernel for the current device, or nullptr (reason in *err) when it cannot be produced.
 // log2_lanes: lanes of a wave that share one row (6 = the whole wave; less: several rows side by side)

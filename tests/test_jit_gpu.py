@@ -229,3 +229,54 @@ def test_permutation_kernels_compiled_for_their_geometry(shape, perm, dtype):
     with env(PF_PERM_CONST="2"):
         (moved,), _ = gpu_run(lay, [x])
     assert torch.equal(moved, x.permute(*perm).contiguous())
+
+
+_DISK_CACHE_SCRIPT = r"""
+import hashlib, sys
+sys.path.insert(0, {root!r}); sys.path.insert(0, {root!r} + "/tests")
+import torch
+import workloads as wl
+from paper_2307_04995_amd import binding as pf
+# (a structure of its own: nothing in the catalogue, nothing another test compiles)
+spec = wl.ChainSpec(inputs=[("f16", (37, 264)), ("f16", (264,))])
+spec.out(spec.op("sigmoid", spec.op("softmax", spec.op("silu", spec.op("mul", 0, 1)))), "f16")
+ins = [wl.random_tensor((37, 264), "f16", 931).cuda(), wl.random_tensor((264,), "f16", 932).cuda()]
+out = torch.empty((37, 264), dtype=torch.float16, device="cuda")
+plan = pf.Plan(spec, 0)
+info = plan.info()
+plan.run(ins, [out])
+torch.cuda.synchronize()
+plan.close()
+digest = hashlib.sha256(out.cpu().numpy().tobytes()).hexdigest()
+print("RESULT", pf.pf_jit_compile_count(), pf.pf_jit_cache_hits(), info.spec_id, digest)
+"""
+
+
+def test_kernels_kept_on_disk_are_loaded_by_the_next_process(tmp_path):
+    """PF_JIT_CACHE: the first process compiles and keeps the kernel, the second loads it and computes the same bits; a
+    file that does not load is compiled over."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    script = _DISK_CACHE_SCRIPT.format(root=root)
+    child_env = dict(os.environ, PF_JIT_CACHE=str(tmp_path))
+
+    def run():
+        r = subprocess.run([sys.executable, "-c", script], env=child_env, capture_output=True, text=True, timeout=110)
+        assert r.returncode == 0, r.stderr[-2000:]
+        line = [l for l in r.stdout.splitlines() if l.startswith("RESULT")][-1].split()
+        return int(line[1]), int(line[2]), int(line[3]), line[4]
+
+    compiles, hits, spec_id, first = run()
+    assert compiles >= 1 and hits == 0 and spec_id == SPEC_JIT
+    files = sorted(p for p in os.listdir(tmp_path) if p.endswith(".co"))
+    assert len(files) == compiles and not [p for p in os.listdir(tmp_path) if p.endswith(".tmp")]
+    compiles2, hits2, spec_id2, second = run()
+    assert compiles2 == 0 and hits2 == compiles and spec_id2 == SPEC_JIT and second == first
+    # a damaged file is no obstacle
+    for name in files:
+        with open(os.path.join(tmp_path, name), "r+b") as fh:
+            fh.truncate(100)
+    compiles3, hits3, _, third = run()
+    assert compiles3 == compiles and hits3 == 0 and third == first
