@@ -12,14 +12,16 @@ pytestmark = pytest.mark.gpu
 
 
 def _report_ulps(name, out, want, dtype):
-    """Print the ulp histogram of a full-size result and append it to gpurun_out/ulp_histogram.jsonl."""
+    """Print the ulp histogram of a full-size result and append it to ulp_histogram.jsonl in the run's output folder
+    (PF_TEST_OUT, else a folder beside the tests that is not under version control)."""
     import json
     import os
     h = ulp_histogram(out, want, dtype)
     print(f"{name}: ulp distance to the oracle rounded to {dtype}: {h}")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(root, "gpurun_out", "ulp_histogram.jsonl"), "a") as f:
+    out_dir = os.environ.get("PF_TEST_OUT") or os.path.join(root, "gpurun_out")
+    os.makedirs(out_dir, exist_ok=True)
+    with open(os.path.join(out_dir, "ulp_histogram.jsonl"), "a") as f:
         f.write(json.dumps({"chain": name, "dtype": dtype, **h}) + "\n")
 
 
