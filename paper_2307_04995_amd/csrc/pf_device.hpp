@@ -154,12 +154,11 @@ typedef uint32_t u32_elem_aligned __attribute__((aligned(2)));
 // the fill value -- one load instead of `count`.
 template <int DT>
 PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill, bool room = false) {
-    if (count == (uint32_t)Storage<DT>::VEC)
-        return __builtin_nontemporal_load(
-            reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
     u32x4 r = {fill, fill, fill, fill};
     if (count == 0u) return r;
-    if (room) {
+    // (whole vectors and partial ones with room behind them take the same load instruction: the lanes of a wave that
+    // hold a row's whole vectors and the lane that holds its tail do not part ways)
+    if (count == (uint32_t)Storage<DT>::VEC || room) {
         const u32x4 got = __builtin_nontemporal_load(
             reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
 #pragma unroll

@@ -285,7 +285,8 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     // kLean: 16-bit storage and nothing but the load in front of the normalisation
     constexpr bool kLean = Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32 && !GEN;
     // GEN == 2: the same for the general kernels, planned when a group holds an even number of channels
-    constexpr bool kLeanGen = GEN == 2 && Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
+    // (GEN == 4: the same with a channel count that is not a whole number of vectors)
+    constexpr bool kLeanGen = (GEN == 2 || GEN == 4) && Spec::kStatic && Spec::Pro::n == 1 && DT != DT_F32;
     __shared__ float lds_part[GEN ? 1 : 512 * 3];
     __shared__ float lds_stat[512 * 2];
     extern __shared__ float lds_gen[];  // GEN: [lane][part] (count, mean, M2)
@@ -300,7 +301,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
     uint32_t part_code = 0, first_grp = 0;
     // GEN == 3: general kernels for channel counts that are not whole vectors: a position then starts at element
     // alignment and its last vector holds `cnt` channels (elements past them are never read, counted or stored)
-    constexpr bool ragged = GEN == 3;
+    constexpr bool ragged = GEN == 3 || GEN == 4;
     const uint32_t cnt = ragged ? elems_below<VEC>(cvi * (uint32_t)VEC, g.channels) : (uint32_t)VEC;
     if (GEN) {
         first_grp = fast_div(cvi * (uint32_t)VEC, g.div_cpg);
@@ -360,8 +361,9 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             raw[i] = u32x4{0u, 0u, 0u, 0u};
             if (valid_of(i)) {
                 // (what follows a position's partial vector is the next position, unless it is the tensor's last)
+                // (addressed like the whole-vector tiles: a scalar base per step plus one lane offset)
                 if (ragged)
-                    raw[i] = load_elems<DT>(in_base, rel_of(i) * g.channels + cvi * VEC, cnt, 0u,
+                    raw[i] = load_elems<DT>(in_base + (size_t)step_of(i) * step_bytes, lane_bytes / (uint32_t)S::ESIZE, cnt, 0u,
                                             (uint64_t)sample * g.hw + p_begin + rel_of(i) + 1u < (uint64_t)g.samples * g.hw);
                 // (the statistics launch leaves x in the caches for the launch that re-reads it: C5 in two launches
                 // 39.2 -> 35.2 us; a one-launch tile is touched once and streams past them)
@@ -431,7 +433,12 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             }
             const float n_pair = active ? 2.0f * npos : 0.0f;
             const float inv = n_pair > 0.0f ? 1.0f / n_pair : 0.0f;
-            auto pair_stat = [&](int j) { return Stat{n_pair, sp[j] * inv, fmaxf(ssp[j] - sp[j] * sp[j] * inv, 0.0f)}; };
+            // (a pair past the last channel of a ragged position was read as zeros and counts nothing; the channel count
+            // is even here, so a pair is whole or absent)
+            auto pair_stat = [&](int j) {
+                const bool there = !ragged || (uint32_t)(2 * j) < cnt;
+                return Stat{there ? n_pair : 0.0f, sp[j] * inv, fmaxf(ssp[j] - sp[j] * sp[j] * inv, 0.0f)};
+            };
             Stat cur = pair_stat(0);
 #pragma unroll
             for (int j = 1; j <= 4; ++j) {
@@ -611,7 +618,7 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
             for (int e = 0; e < VEC; ++e) s.acc[e] = __builtin_fmaf(kCentre ? s.acc[e] - M[e % (kCentre ? VEC : 1)] : s.acc[e], A[e], B[e]);
             run_program<DT, 1, Spec>(ProgView<typename Spec::Epi>{a.epi}, s, NoStore{});
             if (valid_of(i)) {
-                if (ragged) store_elems<DT>(out_base, rel_of(i) * g.channels + cvi * VEC, cnt, S::pack(s.acc));
+                if (ragged) store_elems<DT>(out_base + (size_t)step_of(i) * step_bytes, lane_bytes / (uint32_t)S::ESIZE, cnt, S::pack(s.acc));
                 else store_stream(out_base + (size_t)step_of(i) * step_bytes, lane_bytes, S::pack(s.acc));
             }
         }

@@ -756,8 +756,9 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     p->group_general = general;
     // 2: statistics straight from the packed 16-bit pairs (needs pairs that never straddle groups and nothing but the
     // load in front of the normalisation; the kernel checks the rest at compile time)
-    // 3: channel counts that are not whole vectors
-    const int gen_parts = !general ? 0 : ragged_c ? 3 : ((cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1) ? 2 : 1);
+    // 3: channel counts that are not whole vectors; 4: both
+    const bool packed_stats = cpg % 2 == 0 && L.main_dtype != PF_F32 && L.pro.n == 1;
+    const int gen_parts = !general ? 0 : ragged_c ? (packed_stats ? 4 : 3) : (packed_stats ? 2 : 1);
     g.spin_limit = (uint32_t)env_int("PF_GROUP_SPIN_LIMIT", 1 << 22);  // polls before a wait gives up (tests force it small)
     p->family = PF_FAMILY_GROUP;
     p->spec_id = (env_int("PF_NO_STATIC", 0) || general) ? 0 : match_spec(spec_table().group, L);
@@ -797,7 +798,7 @@ pf_status plan_group(pf_plan_s* p, int forced_variant) {
     uint32_t bps = 0;
     for (int ci = 0; ci < 3 && nv == 0; ++ci) {
         if (forced_nv && cands[ci] != forced_nv) continue;
-        if (general && !(gen_parts == 2 && jit_possible(p->device)) && cands[ci] == 16 && !forced_nv) continue;  // (16 vectors fit the general kernels' registers only with packed statistics)
+        if (general && !((gen_parts == 2 || gen_parts == 4) && jit_possible(p->device)) && cands[ci] == 16 && !forced_nv) continue;  // (16 vectors fit the general kernels' registers only with packed statistics)
         uint32_t b;
         tiling(cands[ci], &b);
         if ((uint64_t)b * samples >= min_tiles || ci == 2 || forced_nv) {
