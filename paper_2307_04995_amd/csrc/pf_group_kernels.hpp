@@ -358,18 +358,26 @@ __global__ void __launch_bounds__(512, 4) group_kernel(const ChainArgs a, const 
         const char* in_base = static_cast<const char*>(a.full[0]) + ((uint64_t)sample * g.hw + p_begin) * g.channels * S::ESIZE;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid_of(i)) {
+            if (ragged) {
+                raw[i] = u32x4{0u, 0u, 0u, 0u};
                 // (what follows a position's partial vector is the next position, unless it is the tensor's last)
                 // (addressed like the whole-vector tiles: a scalar base per step plus one lane offset)
-                if (ragged)
+                if (valid_of(i))
                     raw[i] = load_elems<DT>(in_base + (size_t)step_of(i) * step_bytes, lane_bytes / (uint32_t)S::ESIZE, cnt, 0u,
                                             (uint64_t)sample * g.hw + p_begin + rel_of(i) + 1u < (uint64_t)g.samples * g.hw);
-                // (the statistics launch leaves x in the caches for the launch that re-reads it: C5 in two launches
-                // 39.2 -> 35.2 us; a one-launch tile is touched once and streams past them)
-                else if (PHASE == 1) raw[i] = load_cached(in_base + (size_t)step_of(i) * step_bytes, (uint64_t)lane_bytes);
-                else raw[i] = load_stream(in_base + (size_t)step_of(i) * step_bytes, lane_bytes);
+                continue;
             }
+            // No branch around a load: a step wholly past the tile's end reads step 0 instead, a lane without a position
+            // at this step the step's first vector, and what they read is left out of the statistics and never stored.
+            // (Behind guards the compiler loses count of what is in flight and waits for every load of the tile before it
+            // works on the first.)
+            const bool sure = whole_tiles && all_active;
+            const uint32_t st = (sure || step_of(i) * g.pos_per_step < p_count) ? step_of(i) : 0u;
+            const uint32_t lo = (sure || valid_of(i)) ? lane_bytes : 0u;
+            // (the statistics launch leaves x in the caches for the launch that re-reads it: C5 in two launches
+            // 39.2 -> 35.2 us; a one-launch tile is touched once and streams past them)
+            if (PHASE == 1) raw[i] = load_cached(in_base + (size_t)st * step_bytes, (uint64_t)lo);
+            else raw[i] = load_stream(in_base + (size_t)st * step_bytes, lo);
         }
 
         if (PHASE == 0) load_channel_operands();

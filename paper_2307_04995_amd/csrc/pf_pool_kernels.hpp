@@ -74,11 +74,14 @@ __global__ void __launch_bounds__(512) pool_kernel(const ChainArgs a, const Pool
         if (c0 >= p_count) break;
         auto rel_of = [&](int i) { return c0 + pstep + (uint32_t)i * g.pos_per_step; };
         auto valid_of = [&](int i) { return active && rel_of(i) < p_count; };
+        // (no branch around a load: a lane without a position at step i reads the slice's first vector and leaves it out
+        // of the reduction.  Behind guards the compiler loses count of what is in flight and waits for all of the chunk's
+        // loads before the first vector is worked on.)
         u32x4 raw[NV];
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            raw[i] = u32x4{0u, 0u, 0u, 0u};
-            if (valid_of(i)) raw[i] = load_full(a.full[0], (pos0 + rel_of(i)) * g.channels + cvi * VEC);
+            const uint64_t elem = valid_of(i) ? (pos0 + rel_of(i)) * g.channels + cvi * VEC : pos0 * g.channels;
+            raw[i] = load_full(a.full[0], elem);
         }
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
