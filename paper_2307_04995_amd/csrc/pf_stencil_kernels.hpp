@@ -296,15 +296,68 @@ __global__ void __launch_bounds__(256) dwconv_staged_kernel(const ChainArgs a, c
             if (!kMix) S::unpack(wraw[k], wf[k % ((kMix || !kKeepW) ? 1 : NW)]);
         }
     }
+    // 5 x 5: the kernel vectors do not fit the registers beside the window, so the loops are turned inside out: a kernel
+    // row's five vectors are fetched together (one trip to the cache per kernel row, not one per tap and output row) and
+    // applied to every output row of the strip before the next kernel row is fetched.
+    float acc_all[kKeepW ? 1 : kOut][VEC];
+    if (!kKeepW) {
+#pragma unroll
+        for (int i = 0; i < kOut; ++i)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc_all[i % (kKeepW ? 1 : kOut)][e] = 0.0f;
+#pragma unroll
+        for (int dh = 0; dh < KS; ++dh) {
+            u32x4 wrow[KS];
+#pragma unroll
+            for (int dw = 0; dw < KS; ++dw) wrow[dw] = load_w(dh * KS + dw);
+#pragma unroll
+            for (int i = 0; i < kOut; ++i) {
+                float(&acc)[VEC] = acc_all[i % (kKeepW ? 1 : kOut)];
+#pragma unroll
+                for (int dw = 0; dw < KS; ++dw) {
+                    // (rows of the window past the image's end hold zeros or halo values; their outputs are not stored)
+                    const u32x4* src = tile + ((uint32_t)(i + dh) * tw + threadIdx.x + (uint32_t)dw * cv) * EV;
+                    const u32x4 wv = wrow[dw];
+                    if (kMix) {
+                        const u32x4 xv = src[0];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t xp = xv[j], wp = wv[j];
+                            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "+v"(acc[(2 * j) % VEC]) : "v"(xp), "v"(wp));
+                            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "+v"(acc[(2 * j + 1) % VEC]) : "v"(xp), "v"(wp));
+                        }
+                        continue;
+                    }
+                    float xf[VEC], wu[VEC];
+                    S::unpack(wv, wu);
+                    if (kPacked) {
+                        S::unpack(src[0], xf);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < EV; ++q) {
+                            const u32x4 w4 = src[q];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const uint32_t bits = w4[e];  // (a bit cast applied directly to a vector element is miscompiled)
+                                if (q * 4 + e < VEC) xf[(q * 4 + e) % VEC] = __builtin_bit_cast(float, bits);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wu[e], xf[e], acc[e]);
+                }
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < kOut; ++i) {
         const uint32_t row = h0 + (uint32_t)i;
         if (row >= g.h) break;
         float acc[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+        for (int e = 0; e < VEC; ++e) acc[e] = kKeepW ? 0.0f : acc_all[i % (kKeepW ? 1 : kOut)][e];
 #pragma unroll
-        for (int dh = 0; dh < KS; ++dh)
+        for (int dh = 0; dh < (kKeepW ? KS : 0); ++dh)
 #pragma unroll
             for (int dw = 0; dw < KS; ++dw) {
                 const u32x4* src = tile + ((uint32_t)(i + dh) * tw + threadIdx.x + (uint32_t)dw * cv) * EV;
@@ -408,12 +461,19 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
             u32x4 pend_f[KS][at_least_1(Spec::NF)], pend_v[KS][at_least_1(Spec::NV)];
             bool ok[KS];
             uint32_t pos[KS];
+            // (5 x 5: the kernel row's vectors are asked for together with its taps, not one by one where they are used)
+            u32x4 wrow[kKeepW ? 1 : KS];
+            if (!kKeepW) {
+#pragma unroll
+                for (int dw = 0; dw < KS; ++dw) wrow[dw % (kKeepW ? 1 : KS)] = load_w(dh * KS + dw);
+            }
 #pragma unroll
             for (int dw = 0; dw < KS; ++dw) {
                 const int jj = (int)(ocol * g.stride) + dw - R;
                 ok[dw] = ii >= 0 && ii < (int)g.h && jj >= 0 && jj < (int)g.w;
                 pos[dw] = ok[dw] ? (sample * g.h + (uint32_t)ii) * g.w + (uint32_t)jj : 0u;
-                if (!ok[dw]) continue;
+                // (no branch around the loads: a tap in the padding reads position 0 and is skipped below; behind a guard
+                // every tap's load would wait for the one before)
 #pragma unroll
                 for (int f = 0; f < Spec::NF; ++f)
                     if (f < Spec::n_full(a) && ((pro_full >> f) & 1u))
@@ -435,7 +495,7 @@ __global__ void __launch_bounds__(256) dwconv_strided_kernel(const ChainArgs a, 
                     if (v < Spec::n_vec(a) && v != wslot && ((pro_vec >> v) & 1u)) s.vraw[v][0] = pend_v[dw][v];
                 run_program<DT, 1, Spec>(ProgView<typename Spec::Pro>{a.pro}, s, NoStore{});
                 float wf[VEC];
-                S::unpack(kKeepW ? wraw[(dh * KS + dw) % (kKeepW ? KS * KS : 1)] : load_w(dh * KS + dw), wf);
+                S::unpack(kKeepW ? wraw[(dh * KS + dw) % (kKeepW ? KS * KS : 1)] : wrow[dw % (kKeepW ? 1 : KS)], wf);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) acc[e] = __builtin_fmaf(wf[e], s.acc[e], acc[e]);
             }
