@@ -152,15 +152,16 @@ typedef uint32_t u32_elem_aligned __attribute__((aligned(2)));
 // `room`: the VEC elements from `elem` on all lie inside the tensor (what follows a partial vector is the start of the
 // tensor's next row, say): the partial vector is then read as one whole vector and the slots past `count` replaced by
 // the fill value -- one load instead of `count`.
-template <int DT>
+// NT: streamed data (touched once) is loaded with the non-temporal hint; small operands that every row reads again are not.
+template <int DT, bool NT = true>
 PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint32_t fill, bool room = false) {
     u32x4 r = {fill, fill, fill, fill};
     if (count == 0u) return r;
     // (whole vectors and partial ones with room behind them take the same load instruction: the lanes of a wave that
     // hold a row's whole vectors and the lane that holds its tail do not part ways)
     if (count == (uint32_t)Storage<DT>::VEC || room) {
-        const u32x4 got = __builtin_nontemporal_load(
-            reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE));
+        const u32x4_elem_aligned* vp = reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(base) + elem * Storage<DT>::ESIZE);
+        const u32x4 got = NT ? __builtin_nontemporal_load(vp) : *vp;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t w = got[j];
@@ -181,15 +182,15 @@ PF_DEVICE u32x4 load_elems(const void* base, uint64_t elem, uint32_t count, uint
         const uint32_t* p = static_cast<const uint32_t*>(base) + elem;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t got = __builtin_nontemporal_load(p + min((uint32_t)e, last));
+            const uint32_t got = NT ? __builtin_nontemporal_load(p + min((uint32_t)e, last)) : p[min((uint32_t)e, last)];
             r[e] = (uint32_t)e < count ? got : fill;
         }
     } else {
         const uint16_t* p = static_cast<const uint16_t*>(base) + elem;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t got_lo = __builtin_nontemporal_load(p + min((uint32_t)(2 * j), last));
-            const uint32_t got_hi = __builtin_nontemporal_load(p + min((uint32_t)(2 * j + 1), last));
+            const uint32_t got_lo = NT ? __builtin_nontemporal_load(p + min((uint32_t)(2 * j), last)) : p[min((uint32_t)(2 * j), last)];
+            const uint32_t got_hi = NT ? __builtin_nontemporal_load(p + min((uint32_t)(2 * j + 1), last)) : p[min((uint32_t)(2 * j + 1), last)];
             const uint32_t lo = (uint32_t)(2 * j) < count ? got_lo : (fill & 0xffffu);
             const uint32_t hi = (uint32_t)(2 * j + 1) < count ? got_hi : (fill >> 16);
             r[j] = lo | (hi << 16);
@@ -576,6 +577,13 @@ PF_DEVICE u32x4 load_vec_operand_elems(const VecArg& va, uint32_t row, uint32_t 
     if (BC && va.n_terms != 0u && va.col_bcast) return S::splat(static_cast<const char*>(va.ptr) + (uint64_t)vec_offset<BC>(va, row, col, n_inner) * S::ESIZE);
     u32x4 r = {0u, 0u, 0u, 0u};
     if (count == 0u) return r;
+    // An operand whose elements for this vector lie side by side (a vector of the row's length, or one such vector per
+    // row): one 16-byte load at element alignment, as for the rows themselves, with the partial vector read whole where
+    // the operand continues behind it.
+    if (!(BC && va.n_terms != 0u) && va.numel >= n_inner) {
+        const uint32_t off = vec_offset<false>(va, row, col, n_inner);
+        return load_elems<DT, false>(va.ptr, off, count, 0u, off + (uint32_t)S::VEC <= va.numel);
+    }
     // (slots past the end read the last element that exists and are zeroed: no branch per element, see load_elems)
     const uint32_t last = count - 1u;
     if (DT == DT_F32) {
