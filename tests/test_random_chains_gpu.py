@@ -89,14 +89,23 @@ def test_random_permutation_chains_match_the_oracle(block):
     assert ran >= 9
 
 
-@pytest.mark.parametrize("block", range(5))
-def test_random_layout_chains_are_bit_exact(block):
+@pytest.mark.parametrize("block,vectors_per_lane", [(b, 0) for b in range(5)] + [(5, 2), (6, 4)])
+def test_random_layout_chains_are_bit_exact(block, vectors_per_lane):
     # joins, slices, permutations and reshapes at random: every output bit pattern must come from the right place
+    # (the last two blocks force the copy kernels that move two and four vectors per lane, which the planner itself
+    # takes for large tensors only, onto these small, ragged cases)
     import numpy as np
     import torch
     from oracle import pf_oracle as orc
     from paper_2307_04995_amd import binding as pf
-    from pf_testlib import gpu_run
+    from pf_testlib import env, gpu_run
+    ran = 0
+    with env(PF_GATHER_K=str(vectors_per_lane) if vectors_per_lane else None):
+        ran = _layout_block(block, np, torch, orc, pf, gpu_run)
+    assert ran >= 12
+
+
+def _layout_block(block, np, torch, orc, pf, gpu_run):
     ran = 0
     for seed in range(block * 16, block * 16 + 16):
         spec, desc = wl.random_layout_chain(seed)
@@ -118,7 +127,7 @@ def test_random_layout_chains_are_bit_exact(block):
             assert tuple(o.shape) == tuple(w.shape), f"{desc}: output {k} shape"
             assert np.array_equal(wl.raw_bits(o), w), f"{desc}: output {k} differs"
         ran += 1
-    assert ran >= 12
+    return ran
 
 
 @pytest.mark.parametrize("block", range(4))
