@@ -136,6 +136,106 @@ PF_DEVICE void load_key_value(const AttnArgs& a, uint32_t head, uint32_t row, ui
     }
 }
 
+// ---- polled merge ---------------------------------------------------------------------------------------------
+// Every slice, the head's last one included, publishes its partial result as self-describing words: all-ones means
+// "not written in this launch" (a NaN that arithmetic does not produce; a result with that payload is published as the
+// canonical NaN).  The head's last slice -- dispatched after the others, which never wait, so its wait ends -- reads
+// the words of all slices, re-reading the ones still empty, puts them back to all-ones for the next launch and merges.
+// The critical path is one coherent store and one coherent load; the counted merge above has four trips behind each
+// other (the stores' acknowledgement, the counter, the maxima, the partial results), which is most of what a decode
+// step at batch 1 costs.  Every wait is bounded: after spin_limit re-reads the error word is set and what is missing is
+// left out.
+constexpr uint32_t kAttnEmpty = ~0u;
+PF_DEVICE uint32_t attn_word(float x) {
+    const uint32_t w = __builtin_bit_cast(uint32_t, x);
+    return w == kAttnEmpty ? 0x7fc00000u : w;
+}
+PF_DEVICE uint32_t attn_wait(const AttnArgs& a, uint32_t* word, uint32_t* spins) {
+    for (;;) {
+        const uint32_t w = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (w != kAttnEmpty) return w;
+        if (++*spins > a.spin_limit) {
+            __hip_atomic_store(a.ws_error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return kAttnEmpty;
+        }
+        __builtin_amdgcn_s_sleep(4);
+    }
+}
+
+template <int DT>
+PF_DEVICE void finish_slice_polled(const AttnArgs& a, uint32_t head, uint32_t split, float o_mine, float m, float l_blk, float (*lds_o)[256]) {
+    using S = Storage<DT>;
+    constexpr int VEC = S::VEC;
+    constexpr bool PR = S::PRECISE;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t d = a.d;
+    const uint32_t n_split = gridDim.x;
+    uint32_t* words = reinterpret_cast<uint32_t*>(a.ws_partial);
+    uint32_t* part = words + ((uint64_t)head * n_split + split) * a.part_stride;
+    if (tid < d) __hip_atomic_store(part + tid, attn_word(o_mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        __hip_atomic_store(part + d, attn_word(m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part + d + 1u, attn_word(l_blk), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (split + 1u != n_split) return;
+
+    // ---- the head's last slice merges: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M), thread (g, c) summing column c
+    // over the slices s = g, g + G, ... as in the counted merge
+    uint32_t* base = words + (uint64_t)head * n_split * a.part_stride;
+    uint32_t spins = 0;
+    uint32_t dp = 1;
+    while (dp < d) dp <<= 1;
+    const uint32_t groups = 256u / dp, g = tid / dp, c = tid - g * dp;
+    float big = -__builtin_inff();
+    for (uint32_t s = lane; s < n_split; s += 64u) {  // every wave finds the same maximum
+        const uint32_t w = attn_wait(a, base + (uint64_t)s * a.part_stride + d, &spins);
+        if (w != kAttnEmpty) big = fmaxf(big, __builtin_bit_cast(float, w));
+    }
+    for (int msk = 1; msk < 64; msk <<= 1) big = fmaxf(big, shfl_xor_f(big, msk));
+    float num = 0.0f, den = 0.0f;
+    for (uint32_t s = g; s < n_split; s += groups) {
+        uint32_t* ps = base + (uint64_t)s * a.part_stride;
+        // the three words of a slice are asked for together; what is still empty is waited for afterwards
+        uint32_t wm = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t wl = __hip_atomic_load(ps + d + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t wo = c < d ? __hip_atomic_load(ps + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        if (wm == kAttnEmpty) wm = attn_wait(a, ps + d, &spins);
+        if (wl == kAttnEmpty) wl = attn_wait(a, ps + d + 1u, &spins);
+        if (wo == kAttnEmpty) wo = attn_wait(a, ps + c, &spins);
+        if (c < d) __hip_atomic_store(ps + c, kAttnEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // (nobody else reads this word)
+        if (wm == kAttnEmpty || wl == kAttnEmpty || wo == kAttnEmpty) continue;  // a wait gave up: the slice is left out
+        const float ms = __builtin_bit_cast(float, wm), ls = __builtin_bit_cast(float, wl), os = __builtin_bit_cast(float, wo);
+        const float w = PR ? expf(ms - big) : __builtin_amdgcn_exp2f((ms - big) * kLog2e);
+        num = __builtin_fmaf(os, w, num);
+        den = __builtin_fmaf(ls, w, den);
+    }
+    float* red_num = &lds_o[0][0];  // [groups][dp] (the per-wave partials are no longer needed)
+    float* red_den = &lds_o[2][0];
+    __syncthreads();  // (also: every thread has read the maxima and sums it needs)
+    red_num[tid] = num;
+    red_den[tid] = den;
+    // the maxima and sums were read by many threads: put back to "empty" once everybody is past the barrier above
+    for (uint32_t s = tid; s < n_split; s += 256u) {
+        __hip_atomic_store(base + (uint64_t)s * a.part_stride + d, kAttnEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(base + (uint64_t)s * a.part_stride + d + 1u, kAttnEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (tid < d) {
+        num = 0.0f;
+        den = 0.0f;
+        for (uint32_t gg = 0; gg < groups; ++gg) {
+            num += red_num[gg * dp + tid];
+            den += red_den[gg * dp + tid];
+        }
+        const float r = PR ? num / den : num * __builtin_amdgcn_rcpf(den);
+        if (DT == DT_F32) static_cast<float*>(a.o)[(uint64_t)head * d + tid] = r;
+        else {
+            float tmp[VEC] = {r};
+            static_cast<uint16_t*>(a.o)[(uint64_t)head * d + tid] = (uint16_t)(S::pack(tmp)[0] & 0xffffu);
+        }
+    }
+}
+
 template <int DT, int NV>
 __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     using S = Storage<DT>;
@@ -230,7 +330,8 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const AttnArgs a) {
     float o_mine = 0.0f;
     if (tid < d) o_mine = lds_o[0][tid] + lds_o[1][tid] + lds_o[2][tid] + lds_o[3][tid];
     const float l_blk = lds_l[0] + lds_l[1] + lds_l[2] + lds_l[3];
-    finish_slice<DT>(a, head, split, o_mine, m, l_blk, lds_o, &s_last);
+    if (a.polled != 0u && gridDim.x > 1u) finish_slice_polled<DT>(a, head, split, o_mine, m, l_blk, lds_o);
+    else finish_slice<DT>(a, head, split, o_mine, m, l_blk, lds_o, &s_last);
 }
 
 // Streaming variant: a workgroup walks a longer slice of the head in chunks of NV steps, the loads of the next
@@ -358,7 +459,8 @@ __global__ void __launch_bounds__(256) attn_decode_stream_kernel(const AttnArgs 
         l_blk += lds_l[w] * ww;
         if (tid < d) o_mine += lds_o[w][tid] * ww;
     }
-    finish_slice<DT>(a, head, split, o_mine, top, l_blk, lds_o, &s_last);
+    if (a.polled != 0u && gridDim.x > 1u) finish_slice_polled<DT>(a, head, split, o_mine, top, l_blk, lds_o);
+    else finish_slice<DT>(a, head, split, o_mine, top, l_blk, lds_o, &s_last);
 }
 
 template <int DT>

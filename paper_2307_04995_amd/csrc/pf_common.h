@@ -222,6 +222,11 @@ struct AttnArgs {
     uint32_t chunks;      // streaming variant: chunks (of NV steps of 256 / lanes_per_row rows) a workgroup walks
     uint32_t part_stride; // floats between the partial results of two slices: d + 2 rounded up to whole 128-byte lines, so
                           // that no two workgroups publish (device-coherent stores) into one memory line
+    // Polled merge (plans that own a workspace; 0 / null = the counted, wait-free merge): the partial results are
+    // published as self-describing words (all-ones = not written in this launch) and the head's last slice waits for them.
+    uint32_t polled;
+    uint32_t spin_limit;  // re-reads before the wait gives up
+    uint32_t* ws_error;   // set to 1 if it did
 };
 
 // Stencil family (depthwise 3 x 3 convolution on a channels-last tensor) geometry.

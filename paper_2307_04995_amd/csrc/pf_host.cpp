@@ -346,6 +346,8 @@ pf_status pf_chain_plan_poll_error(const pf_plan* plan, int32_t* flag) {
         if (plan->family == PF_FAMILY_POOL && plan->pool.ws_partial)
             ok = ok && hipMemset(plan->pool.ws_partial, 0xff,
                                  (size_t)plan->pool.samples * plan->pool.blocks_per_sample * plan->pool.channels * sizeof(uint32_t)) == hipSuccess;
+        if (plan->family == PF_FAMILY_ATTENTION && plan->attn.polled)
+            ok = ok && hipMemset(plan->attn.ws_partial, 0xff, (size_t)plan->grid.x * plan->grid.y * plan->attn.part_stride * sizeof(float)) == hipSuccess;
         if (!ok) return fail(PF_ERR_HIP, "cannot re-arm the workspace");
     }
     *flag = (int32_t)word;

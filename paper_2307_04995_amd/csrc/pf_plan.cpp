@@ -1375,12 +1375,21 @@ pf_status plan_attn(pf_plan_s* p, int forced_variant) {
     a.part_stride = (uint32_t)((d + 2 + 31) / 32 * 32);
     const uint64_t part_bytes = ((uint64_t)heads * splits * a.part_stride * sizeof(float) + 255) / 256 * 256;
     const uint64_t cnt_bytes = ((uint64_t)heads * sizeof(uint32_t) + 255) / 256 * 256;
-    pf_status ws_st = plan_workspace_alloc(p, part_bytes + cnt_bytes, "workspace allocation");
+    // A plan that owns its workspace merges by polling self-describing words (a bounded wait, reported through the plan);
+    // a call that plans and runs in one go has no plan to report through and keeps the counted, wait-free merge.
+    const bool polled = !planning_static() && env_int("PF_ATTN_POLLED", 1) != 0;
+    pf_status ws_st = plan_workspace_alloc(p, part_bytes + cnt_bytes + 256, "workspace allocation");
     if (ws_st != PF_OK) return ws_st;
-    if ((ws_st = plan_workspace_fill(p, p->workspace, 0, part_bytes, false)) != PF_OK) return ws_st;
-    if ((ws_st = plan_workspace_fill(p, static_cast<char*>(p->workspace) + part_bytes, 0, cnt_bytes, true)) != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, p->workspace, polled ? 0xff : 0, part_bytes, polled)) != PF_OK) return ws_st;
+    if ((ws_st = plan_workspace_fill(p, static_cast<char*>(p->workspace) + part_bytes, 0, cnt_bytes + 256, true)) != PF_OK) return ws_st;
     a.ws_partial = reinterpret_cast<float*>(p->workspace);
     a.ws_counter = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes);
+    if (polled) {
+        a.polled = 1;
+        a.spin_limit = (uint32_t)env_int("PF_ATTN_SPIN_LIMIT", 1 << 20);  // re-reads before a wait gives up (tests force it small)
+        a.ws_error = reinterpret_cast<uint32_t*>(static_cast<char*>(p->workspace) + part_bytes + cnt_bytes);
+        p->ws_error = a.ws_error;
+    }
     return PF_OK;
 }
 

@@ -143,3 +143,25 @@ def test_other_arrangements_of_the_contractions_are_refused():
     s = wl.ChainSpec(inputs=[("f16", (b, h, d + 8)), ("f16", (b, h, t, d))])
     s.out(s.op("matvec", 1, 0), "f16")
     assert pf.pf_chain_validate(pf.make_desc(s)) == pf.PF_ERR_SHAPE
+
+
+def test_bounded_wait_of_the_merging_slice_gives_up_instead_of_hanging():
+    # with the re-read limit forced to zero the head's last slice does not wait for the others: the launch must still
+    # end, and the plan must report it (results of such a launch are not checked); a plan with the default limit on the
+    # same shape is exact again, and so is the counted merge
+    pf = _pf()
+    spec, ins = wl.x2_decode_attention(b=2, h=5, t=1500, d=64, dtype="f16")
+    dev = [t.cuda() for t in ins]
+    out = torch.empty((2, 5, 64), dtype=torch.float16, device="cuda")
+    with env(PF_ATTN_SPIN_LIMIT="0"):
+        plan = pf.Plan(spec, 0)
+    for _ in range(3):
+        plan.run(dev, [out])
+    torch.cuda.synchronize()
+    assert plan.poll_error() in (0, 1)      # usually 1; 0 only if every word happened to be there at the first look
+    assert plan.poll_error() == 0           # reading clears it (and puts the words back to "empty")
+    plan.close()
+    check_chain(spec, ins, what="attention after a forced give-up")
+    with env(PF_ATTN_POLLED="0"):
+        _, info, _ = check_chain(spec, ins, what="attention, counted merge")
+    assert info.n_launches == 1
