@@ -29,7 +29,9 @@ def _pool_chain(dtype, shape, op, pre=None, post=None):
 
 @pytest.mark.parametrize("op", ["reduce_mean", "reduce_sum", "reduce_max"])
 @pytest.mark.parametrize("shape,dtype", [((2, 7, 7, 64), "f16"), ((3, 14, 14, 240), "bf16"), ((1, 5, 96), "f32"), ((2, 64, 64, 128), "f16"),
-                                         ((4, 1, 1, 8), "f32"), ((1, 3, 33, 17, 40), "f16")])
+                                         ((4, 1, 1, 8), "f32"), ((1, 3, 33, 17, 40), "f16"),
+                                         # more than 512 channels: the merging workgroup's threads own several channels each
+                                         ((4, 40, 40, 1024), "f16"), ((2, 30, 30, 2048), "f32"), ((3, 24, 24, 1280), "bf16")])
 def test_global_pooling(shape, dtype, op):
     pf = _pf()
     positions = int(np.prod(shape[1:-1]))
