@@ -457,3 +457,30 @@ def test_recompose_leaves_near_misses_alone():
     r = s.op("rsqrt", s.op("addc", s.op("reduce_mean", s.op("mul", 2, 2)), f=[1e-6]))
     s.out(s.op("mul", s.op("mul", 0, r), 1), "f32")
     assert not _recompose(s)[1]
+
+
+def test_column_family_sizes_its_slab_to_the_column():
+    """Normalisation over a strided dimension: the planner takes the fewest vectors per lane that hold the column
+    (32 row groups per workgroup), from the instantiated counts 1, 2, 3, 4, 6, 8, 12, 16, 24, 32.  Host logic only."""
+    want = {17: 1, 32: 1, 33: 2, 64: 2, 96: 3, 128: 4, 129: 6, 192: 6, 200: 8, 256: 8, 320: 12, 384: 12, 512: 16, 513: 24,
+            768: 24, 777: 32, 1024: 32}
+    for c, kc in want.items():
+        s = wl.ChainSpec(inputs=[("f16", (2, c, 8, 8)), ("f16", (c,)), ("f16", (c,))])
+        v = s.op("permute", 0, i=[0, 2, 3, 1])
+        v = s.op("layernorm", v, 1, 2, f=[1e-6])
+        s.out(s.op("permute", v, i=[0, 3, 1, 2]), "f16")
+        st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
+        assert st == pf.PF_OK and h is not None, (c, pf.pf_last_error())
+        info = pf.pf_chain_plan_get_info(h)
+        pf.pf_chain_plan_destroy(h)
+        assert info.family == pf.PF_FAMILY_COLUMN and info.vectors_per_lane == kc, (c, info.vectors_per_lane)
+    # more values per position than the registers hold: three kernels instead (a merge plan), or a refusal
+    s = wl.ChainSpec(inputs=[("f16", (2, 1025, 8, 8)), ("f16", (1025,)), ("f16", (1025,))])
+    v = s.op("permute", 0, i=[0, 2, 3, 1])
+    v = s.op("layernorm", v, 1, 2, f=[1e-6])
+    s.out(s.op("permute", v, i=[0, 3, 1, 2]), "f16")
+    st, h = pf.pf_chain_plan(pf.make_desc(s), 0)
+    if h is not None:
+        info = pf.pf_chain_plan_get_info(h)
+        pf.pf_chain_plan_destroy(h)
+        assert info.family != pf.PF_FAMILY_COLUMN or info.n_kernels > 1
