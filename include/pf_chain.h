@@ -312,16 +312,18 @@ pf_status pf_chain_plan_get_partition(const pf_plan *plan, pf_partition *out);
 pf_status pf_chain_run(const pf_plan *plan, const void *const *inputs, void *const *outputs, void *stream);
 
 /*
- * Kernels that wait for other workgroups (the fused GroupNorm variant, the merging workgroup of a pooling) bound every wait; when a wait runs
+ * Kernels that wait for other workgroups (the fused GroupNorm variant, the merging workgroup of a pooling, the merging
+ * slice of a one-token attention head) bound every wait; when a wait runs
  * out they set an error word in the plan's workspace and carry on, so a launch always terminates.  This call
  * synchronises with the device (hipMemcpy), stores the word in *flag (0 = no wait gave up since the last poll)
  * and clears it.  A non-zero flag means that the outputs of the plan's launches since the last poll are invalid;
  * the call then also puts the plan's exchange words back into their initial state, so the caller must have
  * synchronised with every stream the plan ran on.  Plans without workspace always report 0.
  * Such waits end because the workgroups waited for are running: the grids are sized to what an otherwise idle
- * device holds at once.  A plan of the one-launch GroupNorm variant or of a pooling split over several workgroups
- * should therefore not share the device with other long-running kernels (plan PF_VARIANT_GROUP_TWO_PASS where
- * streams run concurrently).
+ * device holds at once.  A plan of the one-launch GroupNorm variant should therefore not share the device with other
+ * long-running kernels (plan PF_VARIANT_GROUP_TWO_PASS where streams run concurrently).  The merging workgroups of
+ * the pool and attention families wait only for workgroups dispatched before them, which wait for nobody: those waits
+ * end whatever else runs.
  */
 pf_status pf_chain_plan_poll_error(const pf_plan *plan, int32_t *flag);
 
